@@ -1,0 +1,440 @@
+"""Pins for the fp64 oracle: every part is checked against something other than itself
+(closed forms, dense linear algebra, explicit Lanczos, exhaustive enumeration, finite
+differences, special cases).  CPU only."""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.linalg as sla
+
+from oracle import bbmm_oracle as O
+from paper_1809_11165_amd import inputs
+
+
+def _khat(w):
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)
+    return K + w.noise * np.eye(w.n)
+
+
+# ---------------------------------------------------------------- kernels ----
+def test_rbf_closed_form_values():
+    # k(0, e1) = s exp(-1 / (2 l^2)); k(x, x) = s   (Sec. 2 with the squared norm)
+    X = np.array([[0.0, 0.0], [1.0, 0.0], [1.0, 2.0]])
+    K = O.kernel_matrix(O.RBF, X, [0.5], 2.0)
+    assert K[0, 0] == pytest.approx(2.0)
+    assert K[0, 1] == pytest.approx(2.0 * np.exp(-1.0 / (2 * 0.25)))
+    assert K[0, 2] == pytest.approx(2.0 * np.exp(-5.0 / (2 * 0.25)))
+    assert np.allclose(K, K.T)
+
+
+def test_rbf_ard_is_product_of_1d_kernels():
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((7, 3))
+    ls = np.array([0.5, 1.0, 2.0])
+    K = O.kernel_matrix(O.RBF, X, ls, 1.0)
+    prod = np.ones((7, 7))
+    for q in range(3):
+        prod *= O.kernel_matrix(O.RBF, X[:, q:q + 1], [ls[q]], 1.0)
+    assert np.allclose(K, prod, rtol=1e-13)
+
+
+def test_matern52_closed_form_values():
+    # rho = 1: s (1 + sqrt5 + 5/3) exp(-sqrt5);  rho = 0: s
+    X = np.array([[0.0], [2.0]])
+    K = O.kernel_matrix(O.MATERN52, X, [2.0], 3.0)
+    assert K[0, 0] == pytest.approx(3.0)
+    assert K[0, 1] == pytest.approx(3.0 * (1 + np.sqrt(5) + 5.0 / 3.0) * np.exp(-np.sqrt(5)))
+    # ARD: distance is measured per dimension in units of l_d
+    X2 = np.array([[0.0, 0.0], [0.5, 4.0]])
+    K2 = O.kernel_matrix(O.MATERN52, X2, [0.5, 4.0], 1.0)
+    r = np.sqrt(2.0)
+    assert K2[0, 1] == pytest.approx((1 + np.sqrt(5) * r + 5 * r * r / 3) * np.exp(-np.sqrt(5) * r))
+
+
+@pytest.mark.parametrize("kernel", [O.RBF, O.MATERN52])
+@pytest.mark.parametrize("ard", [False, True])
+def test_kernel_derivative_blocks_match_finite_differences(kernel, ard):
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((6, 3))
+    ls = np.array([0.7, 1.1, 1.9]) if ard else np.array([0.8])
+    s = 1.7
+    mats = O.kernel_derivative_blocks(kernel, X, X, ls, s)
+    assert len(mats) == len(ls) + 1
+    h = 1e-6
+    for q in range(len(ls)):
+        lp, lm = ls.copy(), ls.copy()
+        lp[q] += h
+        lm[q] -= h
+        fd = (O.kernel_matrix(kernel, X, lp, s) - O.kernel_matrix(kernel, X, lm, s)) / (2 * h)
+        assert np.allclose(mats[q], fd, atol=1e-8)
+    fd = (O.kernel_matrix(kernel, X, ls, s + h) - O.kernel_matrix(kernel, X, ls, s - h)) / (2 * h)
+    assert np.allclose(mats[-1], fd, atol=1e-8)
+
+
+# ------------------------------------------------------ exact (Cholesky) -----
+def test_exact_inference_against_dense_linear_algebra():
+    w = inputs.tiny(12, 3, kernel=inputs.MATERN52, ard=True)
+    Kh = _khat(w)
+    ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise)
+    assert np.allclose(ex.u0, np.linalg.solve(Kh, w.y.astype(np.float64)), rtol=1e-10)
+    assert ex.logdet == pytest.approx(np.linalg.slogdet(Kh)[1], rel=1e-12)
+    lam = np.linalg.eigvalsh(Kh)
+    assert ex.logdet == pytest.approx(np.sum(np.log(lam)), rel=1e-10)
+    # noise derivative is the identity: Tr(K^-1) = sum 1/lambda
+    assert ex.trace[-1] == pytest.approx(np.sum(1.0 / lam), rel=1e-9)
+
+
+def test_exact_inference_1x1_closed_form():
+    X = np.array([[0.3]])
+    y = np.array([2.0])
+    ex = O.exact_inference(O.RBF, X, y, [1.0], 1.5, 0.5)
+    a = 2.0
+    assert ex.u0[0] == pytest.approx(2.0 / a)
+    assert ex.logdet == pytest.approx(np.log(a))
+    assert ex.nlml == pytest.approx(0.5 * (4.0 / a + np.log(a) + np.log(2 * np.pi)))
+    # d nlml / d s = 1/2 (1/a - y^2/a^2); same for the noise; lengthscale derivative is 0
+    g = 0.5 * (1 / a - 4.0 / a ** 2)
+    assert ex.grad == pytest.approx([0.0, g, g])
+
+
+@pytest.mark.parametrize("kernel,ard", [(O.RBF, False), (O.RBF, True), (O.MATERN52, True),
+                                         (O.MATERN52, False)])
+def test_gradient_sign_and_scale_by_finite_differences_of_cholesky_nlml(kernel, ard):
+    w = inputs.tiny(10, 3, kernel=kernel, ard=ard)
+    ls, s, nz = w.lengthscale.copy(), w.outputscale, w.noise
+    ex = O.exact_inference(kernel, w.X, w.y, ls, s, nz)
+
+    def nlml(ls_, s_, nz_):
+        return O.exact_inference(kernel, w.X, w.y, ls_, s_, nz_, with_traces=False).nlml
+
+    h = 1e-5
+    fd = []
+    for q in range(len(ls)):
+        lp, lm = ls.copy(), ls.copy()
+        lp[q] += h
+        lm[q] -= h
+        fd.append((nlml(lp, s, nz) - nlml(lm, s, nz)) / (2 * h))
+    fd.append((nlml(ls, s + h, nz) - nlml(ls, s - h, nz)) / (2 * h))
+    fd.append((nlml(ls, s, nz + h) - nlml(ls, s, nz - h)) / (2 * h))
+    assert np.allclose(ex.grad, fd, rtol=1e-6, atol=1e-7)
+
+
+# ------------------------------------------------------ pivoted Cholesky -----
+def _pc(K, k, forced=None):
+    return O.pivoted_cholesky(np.diag(K).copy(), lambda i: K[i], k, forced)
+
+
+def test_pivoted_cholesky_full_rank_reconstructs_K():
+    w = inputs.tiny(9, 2, kernel=inputs.RBF)
+    K = O.kernel_matrix(w.kernel, w.X, [0.4], w.outputscale)
+    L, piv, _ = _pc(K, 9)
+    assert sorted(piv.tolist()) == list(range(9))
+    assert np.allclose(L @ L.T, K, atol=1e-10)
+
+
+def test_pivoted_cholesky_partial_invariants():
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((14, 14))
+    K = A @ A.T + np.diag(rng.uniform(0.1, 3.0, 14))      # non-constant diagonal
+    prev_tr = np.trace(K)
+    for k in range(1, 8):
+        L, piv, dmax = _pc(K, k)
+        E = K - L @ L.T
+        # residual is PSD, its trace is the sum of the residual diagonal and decreases
+        assert np.linalg.eigvalsh(E).min() > -1e-10
+        assert np.trace(E) < prev_tr + 1e-12
+        prev_tr = np.trace(E)
+        # picked rows/columns are reproduced exactly
+        assert np.allclose(E[piv, :], 0.0, atol=1e-10)
+    # first pivot is the largest diagonal; first column is K[:, piv] / sqrt(K[piv, piv])
+    L, piv, dmax = _pc(K, 3)
+    assert piv[0] == int(np.argmax(np.diag(K)))
+    assert np.allclose(L[:, 0], K[:, piv[0]] / np.sqrt(K[piv[0], piv[0]]))
+    assert dmax[0] == pytest.approx(np.diag(K).max())
+    # second pivot maximises the Schur-complement diagonal
+    S = K - np.outer(K[:, piv[0]], K[piv[0], :]) / K[piv[0], piv[0]]
+    assert piv[1] == int(np.argmax(np.diag(S)))
+
+
+def test_pivoted_cholesky_matches_lapack_pivoted_factor():
+    # LAPACK pstrf implements the same greedy max-diagonal rule (complete pivoting).
+    rng = np.random.default_rng(11)
+    A = rng.standard_normal((10, 10))
+    K = A @ A.T + np.diag(np.arange(10) * 0.37 + 0.2)
+    L, piv, _ = _pc(K, 10)
+    c, lap_piv, rank, info = sla.lapack.dpstrf(K, lower=1)
+    assert info == 0 and rank == 10
+    lap_piv = lap_piv - 1
+    assert piv.tolist() == lap_piv.tolist()
+    Lp = np.tril(c)                       # factor of the permuted matrix
+    assert np.allclose(L[piv, :], Lp, atol=1e-9)
+
+
+def test_pivoted_cholesky_ties_pick_lowest_index_and_forced_order_replays():
+    w = inputs.tiny(8, 2, kernel=inputs.RBF)
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)   # constant diagonal
+    L, piv, _ = _pc(K, 3)
+    assert piv[0] == 0
+    forced = [5, 2, 7]
+    Lf, pf, _ = _pc(K, 3, forced)
+    assert pf.tolist() == forced
+    E = K - Lf @ Lf.T
+    assert np.allclose(E[forced, :], 0.0, atol=1e-10)
+    assert np.linalg.eigvalsh(E).min() > -1e-10
+
+
+# ------------------------------------- Woodbury, determinant lemma, probes ---
+def test_woodbury_and_determinant_lemma_against_dense():
+    rng = np.random.default_rng(2)
+    L = rng.standard_normal((11, 4))
+    noise = 0.37
+    P = O.make_preconditioner(L, noise)
+    Pd = L @ L.T + noise * np.eye(11)
+    R = rng.standard_normal((11, 3))
+    assert np.allclose(P.solve(R), np.linalg.solve(Pd, R), rtol=1e-10)
+    assert P.logdet == pytest.approx(np.linalg.slogdet(Pd)[1], rel=1e-12)
+    # rank 0: P = sigma^2 I
+    P0 = O.make_preconditioner(np.zeros((11, 0)), noise)
+    assert np.allclose(P0.solve(R), R / noise)
+    assert P0.logdet == pytest.approx(11 * np.log(noise))
+
+
+def _all_sign_vectors(m):
+    return np.array(list(itertools.product([-1.0, 1.0], repeat=m))).T      # m x 2^m
+
+
+def test_probe_covariance_is_exactly_P_by_enumeration():
+    rng = np.random.default_rng(4)
+    n, k = 6, 3
+    L = rng.standard_normal((n, k))
+    noise = 0.6
+    S = _all_sign_vectors(n + k)
+    Z = O.make_probes(L, noise, S[:k], S[k:])
+    assert np.allclose(Z.mean(axis=1), 0.0, atol=1e-12)
+    cov = Z @ Z.T / Z.shape[1]
+    assert np.allclose(cov, L @ L.T + noise * np.eye(n), atol=1e-12)
+
+
+# ----------------------------------------------------------------- mBCG ------
+def _textbook_cg(A, b, iters):
+    """Unpreconditioned CG straight from a linear-algebra textbook, single vector."""
+    x = np.zeros_like(b)
+    r = b.copy()
+    d = r.copy()
+    al, be = [], []
+    for _ in range(iters):
+        Ad = A @ d
+        a = (r @ r) / (d @ Ad)
+        x = x + a * d
+        rn = r - a * Ad
+        bt = (rn @ rn) / (r @ r)
+        d = rn + bt * d
+        r = rn
+        al.append(a)
+        be.append(bt)
+    return x, np.array(al), np.array(be)
+
+
+def _setup(w, k):
+    Kh = _khat(w)
+    K = Kh - w.noise * np.eye(w.n)
+    L, piv, _ = _pc(K, k)
+    P = O.make_preconditioner(L, w.noise)
+    return Kh, L, P
+
+
+def test_cg_with_p_equal_n_is_the_cholesky_solve():
+    w = inputs.tiny(24, 3, kernel=inputs.RBF, noise=0.3)
+    Kh, L, P = _setup(w, 4)
+    rng = np.random.default_rng(0)
+    B = rng.standard_normal((24, 5))
+    res = O.mbcg(lambda M: Kh @ M, B, P.solve, 24)
+    assert np.allclose(res.U, np.linalg.solve(Kh, B), rtol=1e-8, atol=1e-10)
+    # the recurrence residual really is b - K u
+    assert res.resid[-1].max() < 1e-9
+
+
+def test_rank0_preconditioner_reduces_to_textbook_cg_coefficients():
+    w = inputs.tiny(20, 3, kernel=inputs.MATERN52, ard=True, noise=0.5)
+    Kh, _, _ = _setup(w, 0)
+    P0 = O.make_preconditioner(np.zeros((20, 0)), w.noise)
+    rng = np.random.default_rng(1)
+    b = rng.standard_normal(20)
+    res = O.mbcg(lambda M: Kh @ M, b[:, None], P0.solve, 7)
+    x, al, be = _textbook_cg(Kh, b, 7)
+    assert np.allclose(res.U[:, 0], x, rtol=1e-10)
+    # P = sigma^2 I rescales z = r / sigma^2, hence alpha by sigma^2; beta is unchanged
+    assert np.allclose(res.alpha[:, 0], al * w.noise, rtol=1e-9)
+    assert np.allclose(res.beta[:, 0], be, rtol=1e-9)
+
+
+def test_columns_are_independent_solves():
+    w = inputs.tiny(16, 2, kernel=inputs.RBF)
+    Kh, L, P = _setup(w, 3)
+    rng = np.random.default_rng(8)
+    B = rng.standard_normal((16, 4))
+    full = O.mbcg(lambda M: Kh @ M, B, P.solve, 6)
+    for q in range(4):
+        one = O.mbcg(lambda M: Kh @ M, B[:, q:q + 1], P.solve, 6)
+        assert np.allclose(full.U[:, q], one.U[:, 0], rtol=1e-12)
+        assert np.allclose(full.alpha[:, q], one.alpha[:, 0], rtol=1e-12)
+
+
+def test_full_rank_preconditioner_converges_in_one_iteration_and_logdet_is_exact():
+    w = inputs.tiny(10, 2, kernel=inputs.RBF, noise=0.2, t=4, k=10, iters=3)
+    res = O.bbmm_inference(w.kernel, w.X, w.y, [0.5], w.outputscale, w.noise, w.E1, w.E2, 10, 3)
+    ex = O.exact_inference(w.kernel, w.X, w.y, [0.5], w.outputscale, w.noise)
+    assert res.mbcg.resid[0].max() < 1e-8
+    assert res.logdet_precond == pytest.approx(ex.logdet, rel=1e-9)
+    assert res.logdet == pytest.approx(ex.logdet, rel=1e-8)
+
+
+def test_vanishing_kernel_limit():
+    # l -> 0 with distinct points: K_hat = (s + sigma^2) I
+    w = inputs.tiny(15, 2, kernel=inputs.RBF, noise=0.4, t=3, k=0, iters=2)
+    res = O.bbmm_inference(w.kernel, w.X, w.y, [1e-4], w.outputscale, w.noise, w.E1, w.E2, 0, 2)
+    a = w.outputscale + w.noise
+    assert np.allclose(res.u0, w.y.astype(np.float64) / a, rtol=1e-12)
+    assert res.logdet == pytest.approx(15 * np.log(a), rel=1e-12)
+    assert res.mbcg.resid[0].max() < 1e-12
+
+
+def test_tolerance_stop_rule():
+    w = inputs.tiny(40, 2, kernel=inputs.RBF, noise=0.2)
+    Kh, L, P = _setup(w, 3)
+    rng = np.random.default_rng(3)
+    B = rng.standard_normal((40, 4))
+    res = O.mbcg(lambda M: Kh @ M, B, P.solve, 40, tol=1e-3)
+    assert res.iters_run < 40
+    assert res.resid[-1].max() < 1e-3
+    assert res.resid[-2].max() >= 1e-3
+    true_rel = np.linalg.norm(B - Kh @ res.U, axis=0) / np.linalg.norm(B, axis=0)
+    assert np.allclose(true_rel, res.resid[-1], rtol=1e-6)
+
+
+# ------------------------------------ Lanczos tridiagonals from CG ----------
+def _explicit_lanczos(A, q0, m):
+    """Lanczos with full re-orthogonalisation; returns (diag, off)."""
+    n = A.shape[0]
+    Q = np.zeros((n, m))
+    a = np.zeros(m)
+    b = np.zeros(m - 1)
+    q = q0 / np.linalg.norm(q0)
+    Q[:, 0] = q
+    for j in range(m):
+        v = A @ Q[:, j]
+        a[j] = Q[:, j] @ v
+        v = v - Q[:, :j + 1] @ (Q[:, :j + 1].T @ v)
+        v = v - Q[:, :j + 1] @ (Q[:, :j + 1].T @ v)
+        if j + 1 < m:
+            b[j] = np.linalg.norm(v)
+            Q[:, j + 1] = v / b[j]
+    return a, b
+
+
+def _sym_inv_sqrt(Pd):
+    lam, V = np.linalg.eigh(Pd)
+    return (V / np.sqrt(lam)) @ V.T
+
+
+@pytest.mark.parametrize("k", [0, 3])
+def test_cg_tridiagonal_equals_explicit_lanczos_of_preconditioned_matrix(k):
+    w = inputs.tiny(18, 3, kernel=inputs.RBF, noise=0.3, t=3, k=k)
+    Kh, L, P = _setup(w, k)
+    Pd = L @ L.T + w.noise * np.eye(18)
+    Pih = _sym_inv_sqrt(Pd)
+    At = Pih @ Kh @ Pih
+    Z = O.make_probes(L, w.noise, w.E1[:k], w.E2)
+    m = 9
+    res = O.mbcg(lambda M: Kh @ M, Z, P.solve, m)
+    for i in range(Z.shape[1]):
+        dg, off = O.tridiag_from_cg(res.alpha[:, i], res.beta[:, i], m)
+        a, b = _explicit_lanczos(At, Pih @ Z[:, i], m)
+        assert np.allclose(dg, a, rtol=1e-8)
+        assert np.allclose(off, b, rtol=1e-7)
+
+
+def test_slq_term_is_exact_quadratic_form_when_p_equals_n():
+    n, k = 10, 2
+    w = inputs.tiny(n, 2, kernel=inputs.MATERN52, noise=0.5, t=4, k=k)
+    Kh, L, P = _setup(w, k)
+    Pd = L @ L.T + w.noise * np.eye(n)
+    Pih = _sym_inv_sqrt(Pd)
+    At = Pih @ Kh @ Pih
+    logA = sla.logm(At).real
+    Z = O.make_probes(L, w.noise, w.E1[:k], w.E2)
+    res = O.mbcg(lambda M: Kh @ M, Z, P.solve, n)
+    for i in range(Z.shape[1]):
+        dg, off = O.tridiag_from_cg(res.alpha[:, i], res.beta[:, i], n)
+        term = res.rho0[i] * O.e1_logT_e1(dg, off)
+        v = Pih @ Z[:, i]
+        assert res.rho0[i] == pytest.approx(v @ v, rel=1e-10)
+        assert term == pytest.approx(v @ logA @ v, rel=1e-6, abs=1e-8)
+
+
+def test_e1_logT_e1_diagonal_and_2x2():
+    assert O.e1_logT_e1(np.array([3.0]), np.zeros(0)) == pytest.approx(np.log(3.0))
+    T = np.array([[2.0, 0.7], [0.7, 1.5]])
+    assert O.e1_logT_e1(np.array([2.0, 1.5]), np.array([0.7])) == pytest.approx(sla.logm(T)[0, 0])
+
+
+# ----------------------- estimators: unbiased by exhaustive enumeration ------
+def test_logdet_and_trace_estimators_average_exactly_over_all_rademacher_probes():
+    n, k = 7, 3
+    w = inputs.tiny(n, 2, kernel=inputs.RBF, ard=True, noise=0.6, t=1, k=k)
+    S = _all_sign_vectors(n + k)                    # every base-noise pattern once
+    E1, E2 = S[:k], S[k:]
+    res = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise,
+                           E1, E2, k, n)
+    ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise)
+    assert res.logdet == pytest.approx(ex.logdet, rel=1e-7)
+    assert np.allclose(res.trace, ex.trace, rtol=1e-7)
+    assert np.allclose(res.quad, ex.quad, rtol=1e-8)
+    assert np.allclose(res.u0, ex.u0, rtol=1e-8)
+    assert res.nlml == pytest.approx(ex.nlml, rel=1e-8)
+    assert np.allclose(res.grad, ex.grad, rtol=1e-6, atol=1e-9)
+
+
+def test_slq_logdet_approaches_cholesky_logdet_as_t_grows():
+    w = inputs.make(1, n=300, t=256, k=5, iters=40)
+    ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise,
+                           with_traces=False)
+    errs = []
+    for t in (4, 32, 256):
+        r = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise,
+                             w.E1[:, :t], w.E2[:, :t], 5, 40)
+        errs.append(abs(r.logdet - ex.logdet) / abs(ex.logdet))
+    assert errs[-1] < 2e-2
+    assert errs[-1] < errs[0]
+
+
+def test_preconditioner_rank_trend_univariate_rbf():
+    # Theorem 1: CG converges faster as the pivoted-Cholesky rank grows (1-D RBF).
+    rng = np.random.default_rng(0)
+    n = 200
+    X = np.sort(rng.uniform(0, 1, (n, 1)), axis=0)
+    y = np.sin(6 * X[:, 0])
+    Kh = O.kernel_matrix(O.RBF, X, [0.2], 1.0) + 0.01 * np.eye(n)
+    K = Kh - 0.01 * np.eye(n)
+    its = []
+    for k in (0, 2, 5, 9):
+        L, _, _ = _pc(K, k)
+        P = O.make_preconditioner(L, 0.01)
+        res = O.mbcg(lambda M: Kh @ M, y[:, None], P.solve, 200, tol=1e-6)
+        its.append(res.iters_run)
+    assert all(a >= b for a, b in zip(its, its[1:]))
+    assert its[-1] < its[0]
+
+
+def test_frozen_column_guard():
+    # a zero right-hand side has rho = 0: the column is frozen, others are unaffected
+    w = inputs.tiny(12, 2, kernel=inputs.RBF)
+    Kh, L, P = _setup(w, 2)
+    rng = np.random.default_rng(0)
+    B = rng.standard_normal((12, 3))
+    B[:, 1] = 0.0
+    res = O.mbcg(lambda M: Kh @ M, B, P.solve, 5)
+    assert np.all(res.U[:, 1] == 0.0)
+    assert res.m_valid[1] == 0 and res.m_valid[0] == 5
+    ref = O.mbcg(lambda M: Kh @ M, B[:, [0, 2]], P.solve, 5)
+    assert np.allclose(res.U[:, [0, 2]], ref.U)
