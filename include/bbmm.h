@@ -1,0 +1,206 @@
+/*
+ * bbmm.h -- C ABI of the MI355X (gfx950) BBMM inference hot path.
+ *
+ * One call computes, for an exact Gaussian process with kernel matrix
+ * K_hat = K_XX + sigma^2 I, the three quantities that dominate training
+ * (paper Sec. 3, "Required operations"):
+ *     K_hat^{-1} y,   log|K_hat|,   Tr(K_hat^{-1} dK_hat/dtheta),
+ * through ONE run of preconditioned modified batched conjugate gradients
+ * (mBCG, Alg. 2) on the right-hand-side block [y, z_1 .. z_t] (Eq. (3)),
+ * with the rank-k pivoted-Cholesky preconditioner of Sec. 4.1 / App. C.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the context's GPU, "host"
+ *     pointers are ordinary host memory.  All matrices are dense row-major.
+ *   - The caller owns every buffer it passes; the library neither frees nor
+ *     keeps any of them after a call returns.
+ *   - Work is queued on the context's HIP stream.  A call that returns host
+ *     values synchronises that stream once before it returns.
+ *   - Every function returns an int status (BBMM_OK == 0).  No exceptions,
+ *     no exit().  bbmm_last_error() gives a message for the last failure.
+ *   - A context is not thread-safe; use one context per stream.
+ *   - Hyperparameter order in every per-hyperparameter array:
+ *         lengthscale(s) (1 or d entries), outputscale, noise (sigma^2);
+ *     raw values, no log/softplus transform.
+ *   - Limits: 1 <= t <= 31, 0 <= k <= 32, 1 <= d <= 64, max_iters <= 256.
+ */
+#ifndef BBMM_H
+#define BBMM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bbmm_ctx bbmm_ctx;
+
+enum {
+  BBMM_OK = 0,
+  BBMM_EINVAL = 1,     /* bad shape, NULL pointer, limit exceeded, wrong call order */
+  BBMM_ENOMEM = 2,     /* device allocation failed (e.g. materialised K_hat does not fit) */
+  BBMM_ENOTPD = 3,     /* capacitance matrix not positive definite / d^T K d <= 0 everywhere */
+  BBMM_ENONFINITE = 4, /* a non-finite value reached a result */
+  BBMM_EHIP = 5        /* a HIP runtime call failed */
+};
+
+enum { BBMM_KERNEL_RBF = 0, BBMM_KERNEL_MATERN52 = 1 };
+enum { BBMM_MODE_MATERIALISED = 0, BBMM_MODE_ONTHEFLY = 1 };
+
+/*
+ * Problem statement (Sec. 2 notation).
+ *   kernel       RBF:       k = s exp(-|x-x'|^2 / (2 l^2))   (per-dimension l_d when ARD)
+ *                MATERN52:  rho^2 = sum_d (x_d-x'_d)^2 / l_d^2,
+ *                           k = s (1 + sqrt5 rho + 5 rho^2/3) exp(-sqrt5 rho)
+ *   mode         how K_hat.M products are formed inside mBCG: from an fp32 K_hat
+ *                stored in device memory (4 n^2 bytes, held by the context), or
+ *                from X tile by tile without ever storing K_hat.
+ *   n, d         number of training points and input dimension
+ *   t            number of probe vectors z_i (right-hand-side block has t+1 columns)
+ *   k            rank of the pivoted-Cholesky preconditioner (0 = P = sigma^2 I)
+ *   max_iters    mBCG iteration cap p
+ *   tol          > 0: stop when |r_j|/|b| < tol for ALL columns; <= 0: run p iterations
+ *   n_lengthscale 1 (isotropic) or d (ARD);  lengthscale: host array of that length
+ *   X            device, n x d float
+ *   y            device, n float
+ *   E1           device, k x t float, entries +-1 (may be NULL when k == 0)
+ *   E2           device, n x t float, entries +-1
+ *                probes are z_i = L_k E1[:,i] + sigma E2[:,i]  (App. C, sampling from N(0,P))
+ */
+typedef struct {
+  int32_t kernel;
+  int32_t mode;
+  int64_t n, d, t, k, max_iters;
+  double tol;
+  int64_t n_lengthscale;
+  const double* lengthscale;
+  double outputscale;
+  double noise;
+  const float* X;
+  const float* y;
+  const float* E1;
+  const float* E2;
+} bbmm_problem;
+
+/*
+ * Results.  Pointers are caller-allocated; optional ones may be NULL.
+ *   u0             device, n float: K_hat^{-1} y after the last mBCG iteration (required)
+ *   U              device, n x (t+1) float: all solves [u_0 .. u_t]           (optional)
+ *   logdet         stochastic-Lanczos-quadrature estimate of log|K_hat| (Eq. (5),(7))
+ *   logdet_precond log|P| from the matrix determinant lemma (App. C)
+ *   yKinvy         y^T u_0
+ *   nlml           1/2 (y^T u_0 + logdet + n log 2 pi)
+ *   trace[h]       (1/t) sum_i u_i^T (dK_hat/dtheta_h) P^{-1} z_i      (Eq. (8))  host, H entries
+ *   quad[h]        u_0^T (dK_hat/dtheta_h) u_0                                  host, H entries
+ *   grad_nlml[h]   1/2 (trace[h] - quad[h])                                      host, H entries
+ *                  H = n_lengthscale + 2
+ *   iters_run      mBCG iterations executed
+ *   rank           preconditioner rank actually built (< k only if the residual diagonal vanished)
+ *   alpha, beta    host, max_iters x (t+1) doubles, row j = coefficients of iteration j (optional)
+ *   resid          host, max_iters x (t+1): |r_j|/|b| per column                  (optional)
+ *   pivots         host, k entries: pivot rows in the order chosen                (optional)
+ *   slq_terms      host, t entries: (z_i^T P^{-1} z_i) e_1^T log(T_i) e_1         (optional)
+ */
+typedef struct {
+  float* u0;
+  float* U;
+  double logdet;
+  double logdet_precond;
+  double yKinvy;
+  double nlml;
+  double* trace;
+  double* quad;
+  double* grad_nlml;
+  int64_t iters_run;
+  int64_t rank;
+  double* alpha;
+  double* beta;
+  double* resid;
+  int64_t* pivots;
+  double* slq_terms;
+} bbmm_result;
+
+/* Create a context bound to GPU `device` and to `hip_stream` (a hipStream_t, NULL = default
+ * stream).  Workspaces are allocated lazily and reused across calls. */
+int bbmm_create(bbmm_ctx** out, int device, void* hip_stream);
+int bbmm_destroy(bbmm_ctx* ctx);
+const char* bbmm_last_error(const bbmm_ctx* ctx);
+
+/* Tuning knobs for experiments (all have sensible defaults):
+ *   "mat_split"  number of row chunks of K_hat a materialised product is split into
+ *   "otf_split"  number of row chunks an on-the-fly product is split into
+ *   "time_mm"    1: record HIP events on the context's stream around every K_hat.M launch of
+ *                the next mBCG runs (read back with bbmm_mm_timing); 0: off (default)
+ * value <= 0 restores the default.  Unknown key: BBMM_EINVAL. */
+int bbmm_tune(bbmm_ctx* ctx, const char* key, int64_t value);
+
+/* Duration of the K_hat.M launches of the last mBCG run, measured with HIP events on the
+ * context's stream (needs bbmm_tune("time_mm", 1) before the run).  Only launches of iterations
+ * that really executed are counted.  avg_ms, total_ms, launches: host (each optional). */
+int bbmm_mm_timing(bbmm_ctx* ctx, double* avg_ms, double* total_ms, int64_t* launches);
+
+/* The whole path (Sec. 3 + Sec. 4): preconditioner, probes, mBCG, log-det, traces. */
+int bbmm_solve_logdet_grad(bbmm_ctx* ctx, const bbmm_problem* in, bbmm_result* out);
+
+/* ------------------------------------------------------------------------
+ * Stage-level entry points (same kernels as the full call; used for parity
+ * tests and for profiling one stage in isolation).  bbmm_setup must be called
+ * first; it validates the problem, sizes the workspaces and prepares the
+ * scaled copies of X.  Stages that depend on earlier ones say so.
+ * ---------------------------------------------------------------------- */
+int bbmm_setup(bbmm_ctx* ctx, const bbmm_problem* in);
+
+/* Materialise K_hat = K_XX + sigma^2 I in fp32 in the context (Sec. 2, notation). */
+int bbmm_build_khat(bbmm_ctx* ctx);
+/* Copy the block K_hat[row0:row0+nrows, col0:col0+ncols] to `out` (device, nrows x ncols). */
+int bbmm_khat_block(bbmm_ctx* ctx, int64_t row0, int64_t nrows, int64_t col0, int64_t ncols,
+                    float* out);
+
+/* V = K_hat M, the product every mBCG iteration is built on (Sec. 3, "Runtime and space").
+ * M, V: device n x c float, 1 <= c <= 32.  mode MATERIALISED needs bbmm_build_khat first. */
+int bbmm_kernel_mm(bbmm_ctx* ctx, int32_t mode, const float* M, int64_t c, float* V);
+
+/* Rank-k pivoted Cholesky of K_XX (App. C).  L: device n x k float (optional, NULL to skip),
+ * pivots: host k (optional), rank: host (optional). */
+int bbmm_pivoted_cholesky(bbmm_ctx* ctx, float* L, int64_t* pivots, int64_t* rank);
+
+/* Capacitance matrix C = sigma^2 I + L^T L, its Cholesky factor, and log|P| (App. C).
+ * Needs bbmm_pivoted_cholesky.  logdet_precond: host. */
+int bbmm_precond_setup(bbmm_ctx* ctx, double* logdet_precond);
+
+/* Z = P^{-1} R by the Woodbury formula (App. C).  R, Z: device n x c float.
+ * Needs bbmm_precond_setup. */
+int bbmm_precond_solve(bbmm_ctx* ctx, const float* R, int64_t c, float* Z);
+
+/* B = [y, L E1 + sigma E2] (Eq. (6); App. C).  B: device n x (t+1) float.
+ * Needs bbmm_pivoted_cholesky. */
+int bbmm_make_probes(bbmm_ctx* ctx, float* B);
+
+/* mBCG (Alg. 2) on the block B (device n x c float) with the context's preconditioner.
+ * U: device n x c float.  alpha/beta/resid: host max_iters x c doubles (optional).
+ * Needs bbmm_precond_setup (and bbmm_build_khat for MATERIALISED). */
+int bbmm_mbcg(bbmm_ctx* ctx, int32_t mode, const float* B, int64_t c, float* U,
+              double* alpha, double* beta, double* resid, int64_t* iters_run);
+
+/* Eigen-decomposition of `batch` symmetric tridiagonal matrices of size m <= 256
+ * (App. B, log-det paragraph): diag is batch x m, off is batch x (m-1) (host).
+ * eigvals: host batch x m (ascending not guaranteed), first_row: host batch x m,
+ * first_row[b][i] = first component of the unit eigenvector of eigvals[b][i]. */
+int bbmm_tridiag_eig_batched(bbmm_ctx* ctx, const double* diag, const double* off, int64_t m,
+                             int64_t batch, double* eigvals, double* first_row);
+
+/* log|K_hat| estimate from the coefficients of the LAST bbmm_mbcg run, whose block must have
+ * been [y, z_1..z_t] (columns 1..t are used): log|P| + (1/t) sum_i rho0_i e_1^T log(T_i) e_1.
+ * logdet: host; slq_terms: host t (optional). */
+int bbmm_slq_logdet(bbmm_ctx* ctx, double* logdet, double* slq_terms);
+
+/* Derivative products (Eq. (8), App. B): with U = [u_0 .. u_t] (device n x (t+1)) and
+ * W = [w_1 .. w_t] (device n x t, w_i = P^{-1} z_i):
+ *   trace[h] = (1/t) sum_i u_i^T (dK_hat/dtheta_h) w_i,   quad[h] = u_0^T (dK_hat/dtheta_h) u_0.
+ * trace, quad: host, n_lengthscale + 2 entries each. */
+int bbmm_dk_traces(bbmm_ctx* ctx, const float* U, const float* W, double* trace, double* quad);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BBMM_H */

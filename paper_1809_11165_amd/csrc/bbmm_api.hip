@@ -1,0 +1,732 @@
+// Host orchestration behind the C ABI of include/bbmm.h: owns the workspaces, queues the
+// kernels of kernels_vec.hip / kernels_mm.hip on the caller's stream in the order of the
+// paper's algorithm (App. C preconditioner -> probes -> Alg. 2 -> SLQ / trace terms) and
+// copies the scalar results back with a single stream synchronisation.
+#include "bbmm.h"
+#include "bbmm_dev.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+namespace {
+
+struct Buf {
+  void* p = nullptr;
+  size_t cap = 0;
+};
+
+constexpr int kMaxVecBlocks = 256;
+constexpr int kMaxSplit = 64;
+constexpr int kDkStride = 2 * (BBMM_MAXD + 2);
+
+}  // namespace
+
+struct bbmm_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  std::string err;
+
+  // problem snapshot (valid after bbmm_setup)
+  bool is_setup = false;
+  bbmm_problem prob{};
+  std::vector<double> ls;
+  int n = 0, d = 0, t = 0, k = 0, kp = 0, np = 0, KK = 0, dp = 0, maxit = 0;
+  HypArgs hyp{};
+  bool khat_built = false, chol_done = false, pre_done = false, mbcg_done = false;
+  int last_c = 0, last_ld = 0, last_t = 0;   // shape of the last mBCG run
+
+  int64_t mat_split = 0, otf_split = 0;      // 0 = default
+  bool time_mm = false;                      // record HIP events around every product launch
+  std::vector<hipEvent_t> ev;                // 2 per iteration, created on demand
+  int ev_iters = 0;                          // iterations covered by the last timed run
+
+  Buf Xa, Xb, Xs, X4, sq, Khat, L, delta, U, R, V, Z0, D4, Vp, partial, alpha, beta, resid, st,
+      tmpA, tmpB, SA, SB, u0v, dkpartial, eig;
+  DevState* h_st = nullptr;   // pinned
+  double* h_hist = nullptr;   // pinned, 3 * MAXP * MAXC doubles
+  size_t dk_rows_cap = 0;
+};
+
+namespace {
+
+int fail(bbmm_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  return code;
+}
+
+#define HIPCHK(ctx, expr)                                                              \
+  do {                                                                                 \
+    hipError_t e_ = (expr);                                                            \
+    if (e_ != hipSuccess)                                                              \
+      return fail(ctx, BBMM_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_));  \
+  } while (0)
+
+int ensure(bbmm_ctx* c, Buf& b, size_t bytes) {
+  if (bytes <= b.cap) return BBMM_OK;
+  if (b.p) {
+    hipError_t e = hipFree(b.p);
+    b.p = nullptr;
+    b.cap = 0;
+    if (e != hipSuccess) return fail(c, BBMM_EHIP, std::string("hipFree: ") + hipGetErrorString(e));
+  }
+  void* p = nullptr;
+  hipError_t e = hipMalloc(&p, bytes);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    char msg[128];
+    snprintf(msg, sizeof msg, "device allocation of %zu bytes failed", bytes);
+    return fail(c, BBMM_ENOMEM, msg);
+  }
+  b.p = p;
+  b.cap = bytes;
+  return BBMM_OK;
+}
+
+template <typename T>
+T* ptr(const Buf& b) {
+  return reinterpret_cast<T*>(b.p);
+}
+
+int ld_for(int c) { return c <= 16 ? 16 : 32; }
+
+int vec_blocks(int n, int ld) {
+  int rpp = BBMM_VEC_THREADS / ld;
+  int nb = (n + rpp * 4 - 1) / (rpp * 4);
+  if (nb < 1) nb = 1;
+  if (nb > kMaxVecBlocks) nb = kMaxVecBlocks;
+  return nb;
+}
+
+int default_split(int np, int cols_per_wg, int want_wgs) {
+  int strips = (np + cols_per_wg - 1) / cols_per_wg;
+  int s = (want_wgs + strips - 1) / strips;
+  // multiples of 8 keep one chunk of the contraction range per XCD
+  s = ((s + 7) / 8) * 8;
+  if (s < 8) s = 8;
+  if (s > kMaxSplit) s = kMaxSplit;
+  int nblk = np / 16;
+  if (s > nblk) s = nblk;
+  return s;
+}
+
+int mat_split_of(const bbmm_ctx* c, int ld) {
+  if (c->mat_split > 0) return (int)std::min<int64_t>(c->mat_split, std::min(kMaxSplit, c->np / 16));
+  return default_split(c->np, ld == 16 ? 1024 : 512, 2048);
+}
+
+int otf_split_of(const bbmm_ctx* c) {
+  if (c->otf_split > 0) return (int)std::min<int64_t>(c->otf_split, std::min(kMaxSplit, c->np / 16));
+  return default_split(c->np, 512, 4096);
+}
+
+int check_ready(bbmm_ctx* c) {
+  if (!c) return BBMM_EINVAL;
+  if (!c->is_setup) return fail(c, BBMM_EINVAL, "bbmm_setup has not been called");
+  hipError_t e = hipSetDevice(c->device);
+  if (e != hipSuccess) return fail(c, BBMM_EHIP, std::string("hipSetDevice: ") + hipGetErrorString(e));
+  return BBMM_OK;
+}
+
+// Copies the device state to the pinned mirror and waits for the stream.
+int fetch_state(bbmm_ctx* c, bool with_hist) {
+  HIPCHK(c, hipMemcpyAsync(c->h_st, c->st.p, sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
+  if (with_hist) {
+    size_t hb = sizeof(double) * BBMM_MAXP * BBMM_MAXC;
+    HIPCHK(c, hipMemcpyAsync(c->h_hist, c->alpha.p, hb, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->h_hist + BBMM_MAXP * BBMM_MAXC, c->beta.p, hb, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->h_hist + 2 * BBMM_MAXP * BBMM_MAXC, c->resid.p, hb, hipMemcpyDeviceToHost, c->stream));
+  }
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int device_status(bbmm_ctx* c) {
+  int s = c->h_st->status;
+  if (s == BBMM_ENOTPD) return fail(c, BBMM_ENOTPD, "capacitance matrix sigma^2 I + L^T L is not positive definite");
+  if (s == BBMM_ENONFINITE) return fail(c, BBMM_ENONFINITE, "non-finite value in the log-determinant estimate");
+  if (s != 0) return fail(c, s, "device-side failure");
+  return BBMM_OK;
+}
+
+// ---- stages on internal buffers -------------------------------------------------------------
+int stage_build_khat(bbmm_ctx* c) {
+  size_t bytes = (size_t)c->np * (size_t)c->np * sizeof(float);
+  int rc = ensure(c, c->Khat, bytes);
+  if (rc) return rc;
+  if (launch_build_khat(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb),
+                        ptr<float>(c->sq), c->n, c->np, c->prob.outputscale, c->prob.noise,
+                        ptr<float>(c->Khat)))
+    return fail(c, BBMM_EINVAL, "unsupported input dimension");
+  c->khat_built = true;
+  return BBMM_OK;
+}
+
+// Vp <- partial products of K_hat with the block in D4; returns the split count and the
+// (scale, add) pair that turns the partial sums into K_hat D.
+int stage_mm(bbmm_ctx* c, int mode, int ld, int* nsplit, double* scaleV, double* addD) {
+  if (mode == BBMM_MODE_MATERIALISED) {
+    if (!c->khat_built) return fail(c, BBMM_EINVAL, "materialised product needs bbmm_build_khat first");
+    int ns = mat_split_of(c, ld);
+    if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<float>(c->D4), ptr<float>(c->Vp), c->np, ld,
+                      ns, ptr<DevState>(c->st)))
+      return fail(c, BBMM_EINVAL, "unsupported block width");
+    *nsplit = ns;
+    *scaleV = 1.0;
+    *addD = 0.0;
+  } else if (mode == BBMM_MODE_ONTHEFLY) {
+    int ns = otf_split_of(c);
+    if (launch_mm_otf(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb),
+                      ptr<float>(c->sq), ptr<float>(c->D4), ptr<float>(c->Vp), c->np, ld, ns,
+                      ptr<DevState>(c->st)))
+      return fail(c, BBMM_EINVAL, "unsupported block width or input dimension");
+    *nsplit = ns;
+    *scaleV = c->prob.outputscale;
+    *addD = c->prob.noise;
+  } else {
+    return fail(c, BBMM_EINVAL, "unknown mode");
+  }
+  return BBMM_OK;
+}
+
+int stage_pivchol(bbmm_ctx* c) {
+  hipStream_t s = c->stream;
+  int nb = vec_blocks(c->n, 16);
+  if (c->kp > 0) launch_fill_f32(s, ptr<float>(c->L), (size_t)c->np * c->kp, 0.f);
+  launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), ptr<DevState>(c->st), ptr<double>(c->partial), nb);
+  for (int m = 0; m < c->k; ++m)
+    launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<float>(c->L),
+                   ptr<DevState>(c->st), ptr<double>(c->partial), nb);
+  c->chol_done = true;
+  c->pre_done = false;
+  return BBMM_OK;
+}
+
+int stage_pre_setup(bbmm_ctx* c) {
+  if (!c->chol_done) return fail(c, BBMM_EINVAL, "bbmm_pivoted_cholesky must run first");
+  int nb = std::min(kMaxVecBlocks, std::max(1, c->n / 64));
+  launch_pre_setup(c->stream, ptr<float>(c->L), c->n, c->k, c->kp, c->prob.noise, ptr<DevState>(c->st),
+                   ptr<double>(c->partial), nb);
+  c->pre_done = true;
+  return BBMM_OK;
+}
+
+// mBCG on the block held in R (padded row-major, stride ld); U, Z0, coefficient histories and the
+// device state are left in the context.
+int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
+  if (!c->pre_done) return fail(c, BBMM_EINVAL, "bbmm_precond_setup must run first");
+  hipStream_t s = c->stream;
+  DevState* st = ptr<DevState>(c->st);
+  int nb = vec_blocks(c->n, ld);
+  size_t blk = (size_t)c->np * ld;
+  launch_fill_f32(s, ptr<float>(c->U), blk, 0.f);
+  launch_fill_f32(s, ptr<float>(c->D4), blk, 0.f);
+  launch_fill_bytes0(s, c->alpha.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
+  launch_fill_bytes0(s, c->beta.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
+  launch_fill_bytes0(s, c->resid.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
+  // done / iters_run live next to each other at the end of DevState
+  launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
+  double noise = c->prob.noise;
+  launch_ur(s, 1, c->n, ld, cc, c->kp, noise, 0.0, ptr<float>(c->D4), ptr<float>(c->V), ptr<float>(c->U),
+            ptr<float>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), nb, 0, ptr<double>(c->beta),
+            ptr<double>(c->resid));
+  launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<float>(c->R), ptr<float>(c->L), ptr<float>(c->D4),
+            ptr<float>(c->Z0), st, nb);
+  if (c->time_mm) {
+    while ((int)c->ev.size() < 2 * c->maxit) {
+      hipEvent_t e;
+      HIPCHK(c, hipEventCreate(&e));
+      c->ev.push_back(e);
+    }
+  }
+  c->ev_iters = 0;
+  for (int j = 0; j < c->maxit; ++j) {
+    int ns = 0;
+    double scaleV = 1.0, addD = 0.0;
+    if (c->time_mm) HIPCHK(c, hipEventRecord(c->ev[2 * j], s));
+    int rc = stage_mm(c, mode, ld, &ns, &scaleV, &addD);
+    if (rc) return rc;
+    if (c->time_mm) {
+      HIPCHK(c, hipEventRecord(c->ev[2 * j + 1], s));
+      c->ev_iters = j + 1;
+    }
+    launch_dv(s, ptr<float>(c->Vp), ns, c->n, c->np, ld, cc, scaleV, addD, ptr<float>(c->D4),
+              ptr<float>(c->V), st, ptr<double>(c->partial), nb, j, ptr<double>(c->alpha));
+    launch_ur(s, 0, c->n, ld, cc, c->kp, noise, c->prob.tol, ptr<float>(c->D4), ptr<float>(c->V),
+              ptr<float>(c->U), ptr<float>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), nb, j,
+              ptr<double>(c->beta), ptr<double>(c->resid));
+    launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<float>(c->R), ptr<float>(c->L), ptr<float>(c->D4),
+              ptr<float>(c->Z0), st, nb);
+  }
+  c->mbcg_done = true;
+  c->last_c = cc;
+  c->last_ld = ld;
+  c->last_t = cc - 1;
+  return BBMM_OK;
+}
+
+int stage_slq(bbmm_ctx* c) {
+  if (!c->mbcg_done || c->last_t < 1) return fail(c, BBMM_EINVAL, "bbmm_mbcg with at least one probe column must run first");
+  launch_slq(c->stream, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, c->last_ld,
+             ptr<DevState>(c->st));
+  return BBMM_OK;
+}
+
+// Derivative pass on U (padded, stride ld; columns 0..t) and Z0 (columns 1..t = W).
+int stage_dk(bbmm_ctx* c, int ld, int t) {
+  hipStream_t s = c->stream;
+  int ard = (c->prob.n_lengthscale > 1) ? 1 : 0;
+  int ncol = ard ? 2 * t : t;
+  int TS = (ncol + 3) / 4;
+  size_t opsz = (size_t)(c->np / 16) * TS * 64;
+  float* SA = ptr<float>(c->SA);
+  float* SB = ptr<float>(c->SB);
+  launch_fill_f32(s, SA, opsz, 0.f);
+  launch_fill_f32(s, SB, opsz, 0.f);
+  const float* U = ptr<float>(c->U);
+  const float* Z0 = ptr<float>(c->Z0);
+  if (!ard) {
+    launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, 0, 1.f / (float)t, SA);
+    launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, 0, 1.f, SB);
+  } else {
+    float h = 0.5f / (float)t;
+    launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, 0, h, SA);
+    launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, t, h, SA);
+    launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, 0, 1.f, SB);
+    launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, t, 1.f, SB);
+  }
+  launch_extract_col(s, U, ld, c->n, c->np, 0, ptr<float>(c->u0v));
+  int ns = otf_split_of(c);
+  if (launch_dk(s, c->prob.kernel, c->KK, ard, TS, ptr<float>(c->Xa), ptr<float>(c->Xb), ptr<float>(c->sq),
+                ptr<float>(c->Xs), ptr<float>(c->X4), SA, SB, ptr<float>(c->u0v), c->np, ns,
+                ptr<double>(c->dkpartial), kDkStride, (int)c->dk_rows_cap, ptr<DevState>(c->st)))
+    return fail(c, BBMM_EINVAL, "derivative pass: unsupported configuration");
+  int nls = ard ? c->dp : 1;
+  launch_noise_terms(s, U, Z0, c->prob.y, c->n, ld, t, nls + 1, ptr<DevState>(c->st));
+  return BBMM_OK;
+}
+
+// Turns the raw accumulators of the derivative pass into trace[h], quad[h] (host side).
+void finish_dk(const bbmm_ctx* c, double* trace, double* quad) {
+  const DevState* st = c->h_st;
+  int nl = (int)c->prob.n_lengthscale;
+  int ard = nl > 1;
+  int nls_dev = ard ? c->dp : 1;
+  double s = c->prob.outputscale;
+  // inputs were scaled by sqrt(c0)/l (RBF, c0 = log2(e)/2) or 1/l (Matern), see HypArgs::xscale
+  double c0 = (c->prob.kernel == BBMM_KERNEL_RBF) ? 0.5 * 1.4426950408889634074 : 1.0;
+  for (int h = 0; h < nl; ++h) {
+    double f = s / (c0 * c->ls[h]);
+    trace[h] = f * st->dk_out[2 * h];
+    quad[h] = f * st->dk_out[2 * h + 1];
+  }
+  trace[nl] = st->dk_out[2 * nls_dev];
+  quad[nl] = st->dk_out[2 * nls_dev + 1];
+  trace[nl + 1] = st->dk_out[2 * (nls_dev + 1)];
+  quad[nl + 1] = st->dk_out[2 * (nls_dev + 1) + 1];
+}
+
+int validate(bbmm_ctx* c, const bbmm_problem* in) {
+  if (!in) return fail(c, BBMM_EINVAL, "problem is NULL");
+  if (in->kernel != BBMM_KERNEL_RBF && in->kernel != BBMM_KERNEL_MATERN52)
+    return fail(c, BBMM_EINVAL, "unknown kernel");
+  if (in->mode != BBMM_MODE_MATERIALISED && in->mode != BBMM_MODE_ONTHEFLY)
+    return fail(c, BBMM_EINVAL, "unknown mode");
+  if (in->n < 1 || in->n > (int64_t)1 << 30) return fail(c, BBMM_EINVAL, "n out of range");
+  if (in->d < 1 || in->d > BBMM_MAXD) return fail(c, BBMM_EINVAL, "d must be in 1..64");
+  if (in->t < 1 || in->t > BBMM_MAXC - 1) return fail(c, BBMM_EINVAL, "t must be in 1..31");
+  if (in->k < 0 || in->k > BBMM_MAXK) return fail(c, BBMM_EINVAL, "k must be in 0..32");
+  if (in->k > in->n) return fail(c, BBMM_EINVAL, "k must not exceed n");
+  if (in->max_iters < 1 || in->max_iters > BBMM_MAXP) return fail(c, BBMM_EINVAL, "max_iters must be in 1..256");
+  if (in->n_lengthscale != 1 && in->n_lengthscale != in->d)
+    return fail(c, BBMM_EINVAL, "n_lengthscale must be 1 or d");
+  if (!in->lengthscale || !in->X || !in->y || !in->E2) return fail(c, BBMM_EINVAL, "NULL input pointer");
+  if (in->k > 0 && !in->E1) return fail(c, BBMM_EINVAL, "E1 is NULL but k > 0");
+  for (int64_t h = 0; h < in->n_lengthscale; ++h)
+    if (!(in->lengthscale[h] > 0.0) || !isfinite(in->lengthscale[h]))
+      return fail(c, BBMM_EINVAL, "lengthscale must be positive and finite");
+  if (!(in->outputscale > 0.0) || !isfinite(in->outputscale)) return fail(c, BBMM_EINVAL, "outputscale must be positive");
+  if (!(in->noise > 0.0) || !isfinite(in->noise)) return fail(c, BBMM_EINVAL, "noise must be positive");
+  return BBMM_OK;
+}
+
+}  // namespace
+
+// ================================================================== public ABI
+extern "C" {
+
+int bbmm_create(bbmm_ctx** out, int device, void* hip_stream) {
+  if (!out) return BBMM_EINVAL;
+  *out = nullptr;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return BBMM_EHIP;
+  if (hipSetDevice(device) != hipSuccess) return BBMM_EHIP;
+  bbmm_ctx* c = new bbmm_ctx();
+  c->device = device;
+  c->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  if (hipHostMalloc((void**)&c->h_st, sizeof(DevState), hipHostMallocDefault) != hipSuccess ||
+      hipHostMalloc((void**)&c->h_hist, sizeof(double) * 3 * BBMM_MAXP * BBMM_MAXC, hipHostMallocDefault) != hipSuccess) {
+    delete c;
+    return BBMM_ENOMEM;
+  }
+  *out = c;
+  return BBMM_OK;
+}
+
+int bbmm_destroy(bbmm_ctx* c) {
+  if (!c) return BBMM_OK;
+  (void)hipSetDevice(c->device);
+  (void)hipStreamSynchronize(c->stream);
+  Buf* bufs[] = {&c->Xa, &c->Xb, &c->Xs, &c->X4, &c->sq, &c->Khat, &c->L, &c->delta, &c->U, &c->R, &c->V,
+                 &c->Z0, &c->D4, &c->Vp, &c->partial, &c->alpha, &c->beta, &c->resid, &c->st, &c->tmpA,
+                 &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig};
+  for (Buf* b : bufs)
+    if (b->p) (void)hipFree(b->p);
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  if (c->h_st) (void)hipHostFree(c->h_st);
+  if (c->h_hist) (void)hipHostFree(c->h_hist);
+  delete c;
+  return BBMM_OK;
+}
+
+const char* bbmm_last_error(const bbmm_ctx* c) { return c ? c->err.c_str() : "context is NULL"; }
+
+int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
+  if (!c || !key) return BBMM_EINVAL;
+  if (!strcmp(key, "mat_split")) c->mat_split = value > 0 ? value : 0;
+  else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
+  else if (!strcmp(key, "time_mm")) c->time_mm = value > 0;
+  else return fail(c, BBMM_EINVAL, std::string("unknown tuning key: ") + key);
+  return BBMM_OK;
+}
+
+int bbmm_mm_timing(bbmm_ctx* c, double* avg_ms, double* total_ms, int64_t* launches) {
+  if (!c) return BBMM_EINVAL;
+  if (!c->time_mm || c->ev_iters == 0 || !c->h_st)
+    return fail(c, BBMM_EINVAL, "no timed mBCG run: set bbmm_tune(\"time_mm\", 1) and run the solver first");
+  HIPCHK(c, hipSetDevice(c->device));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  int n_it = std::min(c->ev_iters, std::max(1, c->h_st->iters_run));
+  double tot = 0.0;
+  for (int j = 0; j < n_it; ++j) {
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, c->ev[2 * j], c->ev[2 * j + 1]));
+    tot += (double)ms;
+  }
+  if (avg_ms) *avg_ms = tot / n_it;
+  if (total_ms) *total_ms = tot;
+  if (launches) *launches = n_it;
+  return BBMM_OK;
+}
+
+int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
+  if (!c) return BBMM_EINVAL;
+  c->is_setup = false;
+  int rc = validate(c, in);
+  if (rc) return rc;
+  HIPCHK(c, hipSetDevice(c->device));
+  c->prob = *in;
+  c->ls.assign(in->lengthscale, in->lengthscale + in->n_lengthscale);
+  c->prob.lengthscale = c->ls.data();
+  c->n = (int)in->n;
+  c->d = (int)in->d;
+  c->t = (int)in->t;
+  c->k = (int)in->k;
+  c->kp = ((c->k + 7) / 8) * 8;
+  c->np = ((c->n + 255) / 256) * 256;
+  c->maxit = (int)in->max_iters;
+  int KK = 1;
+  while (4 * KK < c->d) KK *= 2;
+  c->KK = KK;
+  c->dp = 4 * KK;
+  c->khat_built = c->chol_done = c->pre_done = c->mbcg_done = false;
+
+  memset(&c->hyp, 0, sizeof(HypArgs));
+  double c0 = (in->kernel == BBMM_KERNEL_RBF) ? 0.5 * 1.4426950408889634074 : 1.0;
+  for (int dim = 0; dim < c->d; ++dim) {
+    double l = (in->n_lengthscale == 1) ? c->ls[0] : c->ls[dim];
+    c->hyp.inv_ls[dim] = 1.0 / l;
+    c->hyp.xscale[dim] = (float)(sqrt(c0) / l);
+  }
+  c->hyp.outputscale = in->outputscale;
+  c->hyp.noise = in->noise;
+  c->hyp.kernel = in->kernel;
+  c->hyp.d = c->d;
+
+  size_t np = (size_t)c->np;
+  size_t blk = np * BBMM_MAXC * sizeof(float);
+  size_t opx = np * c->dp * sizeof(float);
+  struct { Buf* b; size_t bytes; } want[] = {
+      {&c->Xa, opx}, {&c->Xb, opx}, {&c->Xs, opx}, {&c->X4, opx}, {&c->sq, np * sizeof(float)},
+      {&c->L, np * std::max(c->kp, 8) * sizeof(float)}, {&c->delta, np * sizeof(double)},
+      {&c->U, blk}, {&c->R, blk}, {&c->V, blk}, {&c->Z0, blk}, {&c->D4, blk},
+      {&c->Vp, (size_t)kMaxSplit * blk},
+      {&c->partial, sizeof(double) * (size_t)kMaxVecBlocks * (BBMM_MAXK * BBMM_MAXK + (BBMM_MAXK + 1) * BBMM_MAXC)},
+      {&c->alpha, sizeof(double) * BBMM_MAXP * BBMM_MAXC}, {&c->beta, sizeof(double) * BBMM_MAXP * BBMM_MAXC},
+      {&c->resid, sizeof(double) * BBMM_MAXP * BBMM_MAXC}, {&c->st, sizeof(DevState)},
+      {&c->tmpA, blk}, {&c->tmpB, blk},
+      {&c->SA, np * 64 * sizeof(float)}, {&c->SB, np * 64 * sizeof(float)}, {&c->u0v, np * sizeof(float)},
+  };
+  for (auto& w : want) {
+    rc = ensure(c, *w.b, w.bytes);
+    if (rc) return rc;
+  }
+  // one partial row per wave of the derivative pass
+  size_t dk_rows = (size_t)((c->np / 16 + 15) / 16) * kMaxSplit * 4;
+  rc = ensure(c, c->dkpartial, dk_rows * kDkStride * sizeof(double));
+  if (rc) return rc;
+  c->dk_rows_cap = dk_rows;
+
+  hipStream_t s = c->stream;
+  launch_fill_bytes0(s, c->st.p, sizeof(DevState));
+  launch_colmean(s, in->X, c->n, c->d, ptr<DevState>(c->st));
+  launch_prep_x(s, in->X, c->n, c->d, c->np, c->KK, c->hyp, ptr<DevState>(c->st), ptr<float>(c->Xa),
+                ptr<float>(c->Xb), ptr<float>(c->Xs), ptr<float>(c->X4), ptr<float>(c->sq));
+  HIPCHK(c, hipGetLastError());
+  c->is_setup = true;
+  return BBMM_OK;
+}
+
+int bbmm_build_khat(bbmm_ctx* c) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  rc = stage_build_khat(c);
+  if (rc) return rc;
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int bbmm_khat_block(bbmm_ctx* c, int64_t row0, int64_t nrows, int64_t col0, int64_t ncols, float* out) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!c->khat_built) return fail(c, BBMM_EINVAL, "bbmm_build_khat must run first");
+  if (!out || row0 < 0 || col0 < 0 || nrows < 0 || ncols < 0 || row0 + nrows > c->n || col0 + ncols > c->n ||
+      nrows * ncols > (int64_t)1 << 31)
+    return fail(c, BBMM_EINVAL, "block out of range");
+  if (nrows * ncols == 0) return BBMM_OK;
+  launch_copy_block(c->stream, ptr<float>(c->Khat), (size_t)c->np, (int)row0, (int)nrows, (int)col0,
+                    (int)ncols, out);
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int bbmm_kernel_mm(bbmm_ctx* c, int32_t mode, const float* M, int64_t cc, float* V) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!M || !V || cc < 1 || cc > BBMM_MAXC) return fail(c, BBMM_EINVAL, "bad block");
+  int ld = ld_for((int)cc);
+  hipStream_t s = c->stream;
+  launch_fill_bytes0(s, &ptr<DevState>(c->st)->done, 2 * sizeof(int));
+  launch_pack_d4(s, M, c->n, (int)cc, c->np, ld, ptr<float>(c->D4));
+  int ns = 0;
+  double scaleV = 1.0, addD = 0.0;
+  rc = stage_mm(c, mode, ld, &ns, &scaleV, &addD);
+  if (rc) return rc;
+  launch_vreduce(s, ptr<float>(c->Vp), ns, c->n, c->np, ld, scaleV, addD, ptr<float>(c->D4), ptr<float>(c->V));
+  launch_unpack_rows(s, ptr<float>(c->V), ld, c->n, (int)cc, V);
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int bbmm_pivoted_cholesky(bbmm_ctx* c, float* L, int64_t* pivots, int64_t* rank) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  rc = stage_pivchol(c);
+  if (rc) return rc;
+  if (L && c->k > 0) launch_unpack_rows(c->stream, ptr<float>(c->L), c->kp, c->n, c->k, L);
+  rc = fetch_state(c, false);
+  if (rc) return rc;
+  if (pivots)
+    for (int m = 0; m < c->k; ++m) pivots[m] = (m < c->h_st->rank) ? c->h_st->piv[m] : -1;
+  if (rank) *rank = c->h_st->rank;
+  return BBMM_OK;
+}
+
+int bbmm_precond_setup(bbmm_ctx* c, double* logdet_precond) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  rc = stage_pre_setup(c);
+  if (rc) return rc;
+  rc = fetch_state(c, false);
+  if (rc) return rc;
+  rc = device_status(c);
+  if (rc) return rc;
+  if (logdet_precond) *logdet_precond = c->h_st->logdetP;
+  return BBMM_OK;
+}
+
+int bbmm_precond_solve(bbmm_ctx* c, const float* R, int64_t cc, float* Z) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!c->pre_done) return fail(c, BBMM_EINVAL, "bbmm_precond_setup must run first");
+  if (!R || !Z || cc < 1 || cc > BBMM_MAXC) return fail(c, BBMM_EINVAL, "bad block");
+  int ld = ld_for((int)cc);
+  hipStream_t s = c->stream;
+  DevState* st = ptr<DevState>(c->st);
+  int nb = vec_blocks(c->n, ld);
+  launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
+  launch_pack_rows(s, R, c->n, (int)cc, ld, ptr<float>(c->tmpA));
+  launch_ur(s, 1, c->n, ld, (int)cc, c->kp, c->prob.noise, 0.0, ptr<float>(c->D4), ptr<float>(c->V),
+            ptr<float>(c->U), ptr<float>(c->tmpA), ptr<float>(c->L), st, ptr<double>(c->partial), nb, 0,
+            ptr<double>(c->beta), ptr<double>(c->resid));
+  launch_psolve_apply(s, c->n, ld, c->kp, c->prob.noise, ptr<float>(c->tmpA), ptr<float>(c->L),
+                      ptr<float>(c->tmpB), st, ptr<double>(c->partial), nb);
+  launch_unpack_rows(s, ptr<float>(c->tmpB), ld, c->n, (int)cc, Z);
+  c->mbcg_done = false;
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int bbmm_make_probes(bbmm_ctx* c, float* B) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!c->chol_done) return fail(c, BBMM_EINVAL, "bbmm_pivoted_cholesky must run first");
+  if (!B) return fail(c, BBMM_EINVAL, "B is NULL");
+  int cc = c->t + 1, ld = ld_for(cc);
+  launch_probes(c->stream, c->prob.y, c->prob.E1, c->prob.E2, ptr<float>(c->L), c->n, c->t, c->kp, ld,
+                c->prob.noise, ptr<DevState>(c->st), ptr<float>(c->tmpA));
+  launch_unpack_rows(c->stream, ptr<float>(c->tmpA), ld, c->n, cc, B);
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int bbmm_mbcg(bbmm_ctx* c, int32_t mode, const float* B, int64_t cc, float* U, double* alpha, double* beta,
+              double* resid, int64_t* iters_run) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!B || !U || cc < 1 || cc > BBMM_MAXC) return fail(c, BBMM_EINVAL, "bad block");
+  int ld = ld_for((int)cc);
+  launch_pack_rows(c->stream, B, c->n, (int)cc, ld, ptr<float>(c->R));
+  rc = stage_mbcg(c, mode, (int)cc, ld);
+  if (rc) return rc;
+  launch_unpack_rows(c->stream, ptr<float>(c->U), ld, c->n, (int)cc, U);
+  rc = fetch_state(c, true);
+  if (rc) return rc;
+  int it = c->h_st->iters_run;
+  if (iters_run) *iters_run = it;
+  double* dst[3] = {alpha, beta, resid};
+  for (int a = 0; a < 3; ++a)
+    if (dst[a])
+      for (int j = 0; j < c->maxit; ++j)
+        for (int q = 0; q < cc; ++q)
+          dst[a][(size_t)j * cc + q] = c->h_hist[(size_t)a * BBMM_MAXP * BBMM_MAXC + (size_t)j * BBMM_MAXC + q];
+  return BBMM_OK;
+}
+
+int bbmm_tridiag_eig_batched(bbmm_ctx* c, const double* diag, const double* off, int64_t m, int64_t batch,
+                             double* eigvals, double* first_row) {
+  if (!c) return BBMM_EINVAL;
+  if (!diag || !eigvals || !first_row || m < 1 || m > BBMM_MAXP || batch < 1 || batch > 65535 || (m > 1 && !off))
+    return fail(c, BBMM_EINVAL, "bad tridiagonal batch");
+  HIPCHK(c, hipSetDevice(c->device));
+  size_t nd = (size_t)batch * m, no = (size_t)batch * (m > 1 ? m - 1 : 1);
+  int rc = ensure(c, c->eig, sizeof(double) * (3 * nd + no));
+  if (rc) return rc;
+  double* d_diag = ptr<double>(c->eig);
+  double* d_off = d_diag + nd;
+  double* d_val = d_off + no;
+  double* d_vec = d_val + nd;
+  HIPCHK(c, hipMemcpyAsync(d_diag, diag, sizeof(double) * nd, hipMemcpyHostToDevice, c->stream));
+  if (m > 1) HIPCHK(c, hipMemcpyAsync(d_off, off, sizeof(double) * batch * (m - 1), hipMemcpyHostToDevice, c->stream));
+  launch_tridiag_eig(c->stream, d_diag, d_off, (int)m, (int)batch, d_val, d_vec);
+  HIPCHK(c, hipMemcpyAsync(eigvals, d_val, sizeof(double) * nd, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipMemcpyAsync(first_row, d_vec, sizeof(double) * nd, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int bbmm_slq_logdet(bbmm_ctx* c, double* logdet, double* slq_terms) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  rc = stage_slq(c);
+  if (rc) return rc;
+  rc = fetch_state(c, false);
+  if (rc) return rc;
+  rc = device_status(c);
+  if (rc) return rc;
+  if (logdet) *logdet = c->h_st->logdetP + c->h_st->slq_mean;
+  if (slq_terms)
+    for (int i = 0; i < c->last_t; ++i) slq_terms[i] = c->h_st->slq_terms[i];
+  return BBMM_OK;
+}
+
+int bbmm_dk_traces(bbmm_ctx* c, const float* U, const float* W, double* trace, double* quad) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!U || !W || !trace || !quad) return fail(c, BBMM_EINVAL, "NULL pointer");
+  int cc = c->t + 1, ld = ld_for(cc);
+  hipStream_t s = c->stream;
+  launch_pack_rows(s, U, c->n, cc, ld, ptr<float>(c->U));
+  launch_fill_f32(s, ptr<float>(c->Z0), (size_t)c->np * ld, 0.f);
+  launch_pack_cols_at(s, W, c->n, c->t, ld, 1, ptr<float>(c->Z0));
+  c->mbcg_done = false;
+  rc = stage_dk(c, ld, c->t);
+  if (rc) return rc;
+  rc = fetch_state(c, false);
+  if (rc) return rc;
+  finish_dk(c, trace, quad);
+  return BBMM_OK;
+}
+
+int bbmm_solve_logdet_grad(bbmm_ctx* c, const bbmm_problem* in, bbmm_result* out) {
+  if (!c) return BBMM_EINVAL;
+  if (!out || !out->u0 || !out->trace || !out->quad || !out->grad_nlml)
+    return fail(c, BBMM_EINVAL, "result struct, u0, trace, quad and grad_nlml are required");
+  int rc = bbmm_setup(c, in);
+  if (rc) return rc;
+  hipStream_t s = c->stream;
+  int cc = c->t + 1, ld = ld_for(cc);
+  if (in->mode == BBMM_MODE_MATERIALISED) {
+    rc = stage_build_khat(c);
+    if (rc) return rc;
+  }
+  rc = stage_pivchol(c);
+  if (rc) return rc;
+  rc = stage_pre_setup(c);
+  if (rc) return rc;
+  launch_probes(s, in->y, in->E1, in->E2, ptr<float>(c->L), c->n, c->t, c->kp, ld, in->noise,
+                ptr<DevState>(c->st), ptr<float>(c->R));
+  rc = stage_mbcg(c, in->mode, cc, ld);
+  if (rc) return rc;
+  rc = stage_slq(c);
+  if (rc) return rc;
+  rc = stage_dk(c, ld, c->t);
+  if (rc) return rc;
+  launch_extract_col(s, ptr<float>(c->U), ld, c->n, c->n, 0, out->u0);
+  if (out->U) launch_unpack_rows(s, ptr<float>(c->U), ld, c->n, cc, out->U);
+  rc = fetch_state(c, true);
+  if (rc) return rc;
+  rc = device_status(c);
+  if (rc) return rc;
+
+  const DevState* st = c->h_st;
+  int nl = (int)in->n_lengthscale;
+  finish_dk(c, out->trace, out->quad);
+  for (int h = 0; h < nl + 2; ++h) out->grad_nlml[h] = 0.5 * (out->trace[h] - out->quad[h]);
+  out->logdet_precond = st->logdetP;
+  out->logdet = st->logdetP + st->slq_mean;
+  out->iters_run = st->iters_run;
+  out->rank = st->rank;
+  out->yKinvy = st->dk_out[2 * ((nl > 1 ? c->dp : 1) + 1) + 2];
+  out->nlml = 0.5 * (out->yKinvy + out->logdet + (double)c->n * log(2.0 * M_PI));
+  if (!isfinite(out->logdet) || !isfinite(out->yKinvy)) return fail(c, BBMM_ENONFINITE, "non-finite result");
+  double* dst[3] = {out->alpha, out->beta, out->resid};
+  for (int a = 0; a < 3; ++a)
+    if (dst[a])
+      for (int j = 0; j < c->maxit; ++j)
+        for (int q = 0; q < cc; ++q)
+          dst[a][(size_t)j * cc + q] = c->h_hist[(size_t)a * BBMM_MAXP * BBMM_MAXC + (size_t)j * BBMM_MAXC + q];
+  if (out->pivots)
+    for (int m = 0; m < c->k; ++m) out->pivots[m] = (m < st->rank) ? st->piv[m] : -1;
+  if (out->slq_terms)
+    for (int i = 0; i < c->t; ++i) out->slq_terms[i] = st->slq_terms[i];
+  return BBMM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Internal declarations shared by the kernel files and the host orchestrator.
+// Not part of the public ABI (see include/bbmm.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define BBMM_MAXC 32      // padded right-hand-side columns (ld of every n x c block is 16 or 32)
+#define BBMM_MAXK 32      // preconditioner rank limit
+#define BBMM_MAXD 64      // input dimension limit
+#define BBMM_MAXP 256     // mBCG iteration limit
+#define BBMM_VEC_THREADS 256
+
+// Device-resident scalar state of one call.  Everything the iteration needs between
+// kernels lives here so that the host never reads coefficients back inside the loop.
+struct DevState {
+  double rho[BBMM_MAXC];        // r^T P^{-1} r of the current residual, per column
+  double rho0[BBMM_MAXC];       // b^T P^{-1} b (first rho), per column
+  double bnorm[BBMM_MAXC];      // |b| per column
+  double alpha_cur[BBMM_MAXC];
+  double beta_cur[BBMM_MAXC];
+  double Qt[BBMM_MAXK * BBMM_MAXC];   // C^{-1} L^T R, [m][q]
+  double G[BBMM_MAXK * BBMM_MAXK];    // lower Cholesky factor of C = sigma^2 I + L^T L, [a][b]
+  double logdetP;
+  double pivdmax[BBMM_MAXK + 1];
+  double slq_terms[BBMM_MAXC];
+  double slq_mean;
+  double dk_out[2 * (BBMM_MAXD + 3)];  // raw accumulators of the derivative pass
+  double xmean[BBMM_MAXD];
+  int active[BBMM_MAXC];
+  int m_valid[BBMM_MAXC];
+  int piv[BBMM_MAXK + 1];
+  int done;         // set when the tolerance test passed; later kernels of the loop exit at once
+  int iters_run;
+  int status;       // BBMM_* code raised on the device (0 = ok)
+  int rank;         // preconditioner rank actually built
+  unsigned counter[8];   // "last block done" tickets, one per kernel family
+};
+
+struct HypArgs {
+  double inv_ls[BBMM_MAXD];   // 1 / l_d (isotropic: the same value d times)
+  float xscale[BBMM_MAXD];    // factor applied to centred x_d before the distance contraction
+  double outputscale;
+  double noise;
+  int kernel;
+  int d;
+};
+
+// ---- launchers implemented in kernels_vec.hip ---------------------------------------------
+void launch_fill_f32(hipStream_t s, float* p, size_t count, float v);
+void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes);
+void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st);
+void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, HypArgs hyp,
+                   const DevState* st, float* Xa, float* Xb, float* Xs, float* X4, float* sq);
+void launch_pack_d4(hipStream_t s, const float* M, int n, int c, int np, int ld, float* D4);
+void launch_unpack_rows(hipStream_t s, const float* src, int ld, int n, int c, float* dst);
+void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, float* dst);
+void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, float* dst);
+void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0, int nrows, int col0,
+                       int ncols, float* dst);
+void launch_vreduce(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld, double scaleV,
+                    double addD, const float* D4, float* V);
+void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* partial,
+                    int nblocks);
+void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
+                    float* L, DevState* st, double* partial, int nblocks);
+void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
+                      double* partial, int nblocks);
+void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
+                   int n, int t, int kp, int ld, double noise, const DevState* st, float* R);
+void launch_dv(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
+               double addD, const float* D4, float* V, DevState* st, double* partial, int nblocks,
+               int iter, double* alpha_hist);
+void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
+               const float* D4, const float* V, float* U, float* R, const float* L, DevState* st,
+               double* partial, int nblocks, int iter, double* beta_hist, double* resid_hist);
+void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const float* R,
+               const float* L, float* D4, float* Z0, DevState* st, int nblocks);
+void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const float* R,
+                         const float* L, float* Z, DevState* st, double* partial, int nblocks);
+void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int ld,
+                DevState* st);
+void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,
+                        double* eigvals, double* first_row);
+void launch_noise_terms(hipStream_t s, const float* U, const float* Z0, const float* y, int n, int ld,
+                        int t, int slot, DevState* st);
+
+// ---- launchers implemented in kernels_mm.hip ----------------------------------------------
+int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
+                      const float* sq, int n, int np, double outputscale, double noise, float* Khat);
+int launch_mm_mat(hipStream_t s, const float* Khat, const float* D4, float* Vp, int np, int ld,
+                  int nsplit, const DevState* st);
+int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
+                  const float* D4, float* Vp, int np, int ld, int nsplit, const DevState* st);
+// derivative pass: one partial row (pstride doubles) per wave, then a fixed-order fp64 sum into
+// st->dk_out.  Returns non-zero when the configuration is not supported.
+int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* Xa, const float* Xb,
+              const float* sq, const float* Xs, const float* X4, const float* SA, const float* SB,
+              const float* u0, int np, int nsplit, double* partial, int pstride, int max_rows,
+              DevState* st);
+void launch_swizzle_cols(hipStream_t s, const float* src, int ld, int n, int np, int col0, int ncols,
+                         int TS, int dstcol0, float scale, float* dst);
+void launch_extract_col(hipStream_t s, const float* src, int ld, int n, int np, int col, float* dst);

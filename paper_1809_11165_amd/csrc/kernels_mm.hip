@@ -1,0 +1,573 @@
+// Kernel-matrix tile kernels for gfx950 (CDNA4): the O(n^2) part of BBMM.
+//
+//   * k_mm_mat   V = K_hat D from a materialised fp32 K_hat streamed once from HBM
+//   * k_mm_otf   the same product with K_hat tiles rebuilt from X on the fly
+//   * k_build_khat  materialises K_hat
+//   * k_dk       derivative pass: sums of (dK/dtheta)_ij S_ij over all pairs
+//
+// All four work on 16 x 16 tiles held in the accumulator layout of
+// v_mfma_f32_16x16x4_f32: lane l, register r  <->  tile element (row 4*(l/16)+r, col l%16).
+// Squared distances come from the MFMA contraction  -2 x_i . x_j  plus |x_i|^2 + |x_j|^2
+// on inputs that were centred and divided by the lengthscales beforehand; the kernel
+// function is applied in registers; the tile is then used directly as the B operand
+// of a second MFMA whose A operand is the right-hand-side block stored "quad-swizzled"
+// (4 consecutive rows interleaved), so that both operands are single coalesced loads.
+// Because K_hat is symmetric, a tile computed at (rows I, cols J) is used to accumulate
+// the output rows J (contraction over I), which is what lets lanes own output columns.
+#include "bbmm_dev.h"
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr float kSqrt5 = 2.2360679774997896964f;
+constexpr float kLog2e = 1.4426950408889634074f;
+
+__device__ inline f32x4 mfma16(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// r2 tile: |xs_i - xs_j|^2 for a 16 x 16 tile, clamped at 0.
+template <int KK>
+__device__ inline f32x4 tile_r2(const float (&a)[KK], const float (&b)[KK], f32x4 sqi, float sqj) {
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) acc = mfma16(a[kk], b[kk], acc);
+  f32x4 r2;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) r2[r] = fmaxf(acc[r] + (sqi[r] + sqj), 0.f);
+  return r2;
+}
+
+// exact zero distance on the diagonal of a diagonal tile
+__device__ inline f32x4 fix_diag(f32x4 r2, int lane) {
+  int jc = lane & 15, ib = (lane >> 4) * 4;
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+    if (ib + r == jc) r2[r] = 0.f;
+  return r2;
+}
+
+// Unit-outputscale kernel value from the scaled squared distance.
+//   RBF:      inputs were scaled by sqrt(log2(e)/2)/l, so k/s = 2^(-r2)
+//   Matern52: inputs were scaled by 1/l, rho = sqrt(r2), k/s = (1 + sqrt5 rho + 5/3 rho^2) e^(-sqrt5 rho)
+template <int KIND>
+__device__ inline float unit_kernel(float r2) {
+  if (KIND == 0) {
+    return __builtin_amdgcn_exp2f(-r2);
+  } else {
+    float rho = __builtin_amdgcn_sqrtf(r2);
+    float e = __builtin_amdgcn_exp2f(-(kSqrt5 * kLog2e) * rho);
+    float poly = fmaf(rho, fmaf(rho, 5.f / 3.f, kSqrt5), 1.f);
+    return poly * e;
+  }
+}
+
+// Kernel value and the radial weight g of the lengthscale derivative
+//   dk/dl_d = s * g * (Delta_d / l_d)^2 / l_d,   g = k/s (RBF),  g = (5/3)(1 + sqrt5 rho) e^(-sqrt5 rho) (Matern52)
+template <int KIND>
+__device__ inline void unit_kernel_and_weight(float r2, float& e_out, float& g_out) {
+  if (KIND == 0) {
+    float e = __builtin_amdgcn_exp2f(-r2);
+    e_out = e;
+    g_out = e;
+  } else {
+    float rho = __builtin_amdgcn_sqrtf(r2);
+    float e = __builtin_amdgcn_exp2f(-(kSqrt5 * kLog2e) * rho);
+    e_out = fmaf(rho, fmaf(rho, 5.f / 3.f, kSqrt5), 1.f) * e;
+    g_out = (5.f / 3.f) * fmaf(rho, kSqrt5, 1.f) * e;
+  }
+}
+
+// --------------------------------------------------------- materialise K_hat --
+// One wave: column block jb (16 columns) x 4 row blocks; each tile is written at its
+// transposed position so a wave's stores cover 256 contiguous bytes per K_hat row.
+template <int KIND, int KK>
+__global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa,
+                                                     const float* __restrict__ Xb,
+                                                     const float* __restrict__ sq, int n, int np,
+                                                     float outputscale, float noise,
+                                                     float* __restrict__ Khat) {
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int jb = blockIdx.y * 4 + wave;
+  int jc = lane & 15, g = lane >> 4;
+  float b[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) b[kk] = Xb[((size_t)jb * KK + kk) * 64 + lane];
+  float sqj = sq[jb * 16 + jc];
+  int j = jb * 16 + jc;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    int ib = blockIdx.x * 4 + u;
+    float a[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
+    f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
+    f32x4 r2 = tile_r2<KK>(a, b, sqi, sqj);
+    if (ib == jb) r2 = fix_diag(r2, lane);
+    f32x4 out;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int i = ib * 16 + g * 4 + r;
+      float v = outputscale * unit_kernel<KIND>(r2[r]);
+      if (i == j) v += noise;
+      if (i >= n || j >= n) v = 0.f;
+      out[r] = v;
+    }
+    *(f32x4*)(Khat + (size_t)j * np + (size_t)(ib * 16 + g * 4)) = out;
+  }
+}
+
+// ------------------------------------------------ product from a stored K_hat --
+// Wave: 64*NC output columns, a chunk of K_hat rows.  Per 16-row step each lane loads
+// 4 rows x 4 consecutive columns per column group (row 4*(l/16)+r, columns 4*(l%16)..+3):
+// register (r, cc) of that load is the B operand of one MFMA whose A operand is the
+// quad-swizzled right-hand side.  Result partials go to Vp[split].
+template <int NQ, int NC>
+__global__ __launch_bounds__(256) void k_mm_mat(const float* __restrict__ Khat,
+                                                 const float* __restrict__ D4,
+                                                 float* __restrict__ Vp, int np, int nsplit,
+                                                 int rows_per_split,
+                                                 const DevState* __restrict__ st) {
+  if (st->done) return;
+  constexpr int LD = 16 * NQ;
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int split = blockIdx.x % nsplit;
+  int sstrip = blockIdx.x / nsplit;
+  int col0 = (sstrip * 4 + wave) * (64 * NC);
+  if (col0 >= np) return;
+  int jc = lane & 15, g = lane >> 4;
+  int j_begin = split * rows_per_split;
+  int j_end = min(np, j_begin + rows_per_split);
+  f32x4 acc[NC][4][NQ];
+#pragma unroll
+  for (int nc = 0; nc < NC; ++nc)
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const float* kbase = Khat + (size_t)(g * 4) * np + (size_t)(col0 + 4 * jc);
+  for (int j0 = j_begin; j0 < j_end; j0 += 16) {
+    f32x4 dop[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+      dop[nq] = *(const f32x4*)(D4 + ((size_t)(j0 / 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+    f32x4 kv[NC][4];
+    const float* kp = kbase + (size_t)j0 * np;
+#pragma unroll
+    for (int nc = 0; nc < NC; ++nc)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(kp + (size_t)r * np + nc * 64));
+#pragma unroll
+    for (int nc = 0; nc < NC; ++nc)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq)
+            acc[nc][cc][nq] = mfma16(dop[nq][r], kv[nc][r][cc], acc[nc][cc][nq]);
+  }
+  float* vout = Vp + (size_t)split * np * LD;
+#pragma unroll
+  for (int nc = 0; nc < NC; ++nc)
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq)
+        *(f32x4*)(vout + (size_t)(col0 + nc * 64 + 4 * jc + cc) * LD + nq * 16 + g * 4) =
+            acc[nc][cc][nq];
+}
+
+// ------------------------------------------------------- product on the fly ---
+// Wave: NJ column blocks (16*NJ output rows of V), a chunk of row blocks to contract over.
+// Writes partial sums of (K/s) D; the caller scales by s and adds sigma^2 D.
+template <int KIND, int KK, int NQ, int NJ>
+__global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
+                                                 const float* __restrict__ Xb,
+                                                 const float* __restrict__ sq,
+                                                 const float* __restrict__ D4,
+                                                 float* __restrict__ Vp, int np, int nsplit,
+                                                 int blocks_per_split,
+                                                 const DevState* __restrict__ st) {
+  if (st->done) return;
+  constexpr int LD = 16 * NQ;
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int nblk = np >> 4;
+  int split = blockIdx.x % nsplit;
+  int sstrip = blockIdx.x / nsplit;
+  int jb0 = (sstrip * 4 + wave) * NJ;
+  if (jb0 >= nblk) return;
+  int jc = lane & 15, g = lane >> 4;
+  float b[NJ][KK];
+  float sqj[NJ];
+  f32x4 acc[NJ][NQ];
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb) {
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) b[jb][kk] = Xb[((size_t)(jb0 + jb) * KK + kk) * 64 + lane];
+    sqj[jb] = sq[(jb0 + jb) * 16 + jc];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+  int ib_begin = split * blocks_per_split;
+  int ib_end = min(nblk, ib_begin + blocks_per_split);
+  for (int ib = ib_begin; ib < ib_end; ++ib) {
+    float a[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
+    f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
+    f32x4 dop[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+      dop[nq] = *(const f32x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb) {
+      f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
+      if (ib == jb0 + jb) r2 = fix_diag(r2, lane);
+      f32x4 e;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) e[r] = unit_kernel<KIND>(r2[r]);
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[jb][nq] = mfma16(dop[nq][r], e[r], acc[jb][nq]);
+    }
+  }
+  float* vout = Vp + (size_t)split * np * LD;
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb)
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+      *(f32x4*)(vout + (size_t)((jb0 + jb) * 16 + jc) * LD + nq * 16 + g * 4) = acc[jb][nq];
+}
+
+// ------------------------------------------------------------ derivative pass --
+// For every pair (i, j):  S_ij = sum_c SA[i][c] SB[j][c]  (the probe outer products, already
+// divided by t) and Q_ij = u0_i u0_j.  Accumulates
+//     sum_ij E_ij S_ij,  sum_ij E_ij Q_ij                         (outputscale)
+//   isotropic:  sum_ij g_ij r2_ij S_ij,  sum_ij g_ij r2_ij Q_ij   (lengthscale)
+//   ARD:        per dimension  sum_ij g_ij S_ij (xs_id - xs_jd)^2  (and Q), evaluated as
+//               2 sum_j xs_jd (xs_jd c_j - Y_jd),  c_j = sum_i T_ij,  Y_jd = sum_i T_ij xs_id,
+//               T = g o S with S symmetrised by the caller; Y is one more MFMA contraction.
+// Partial results: one row of `pstride` doubles per wave: [2*h] trace-type, [2*h+1] quad-type,
+// h = lengthscale slots (1 or 4*KK) then the outputscale slot.
+constexpr int DK_NJ = 4;
+constexpr int DK_TSMAX = 16;
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <int KIND, int KK, int ARD>
+__global__ __launch_bounds__(256) void k_dk(const float* __restrict__ Xa,
+                                             const float* __restrict__ Xb,
+                                             const float* __restrict__ sq,
+                                             const float* __restrict__ Xs,
+                                             const float* __restrict__ X4,
+                                             const float* __restrict__ SA,
+                                             const float* __restrict__ SB, int TS,
+                                             const float* __restrict__ u0, int np, int nsplit,
+                                             int blocks_per_split, double* __restrict__ partial,
+                                             int pstride) {
+  constexpr int DP = 4 * KK;
+  constexpr int MB = (DP + 15) / 16;
+  constexpr int NJ = DK_NJ;
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int nblk = np >> 4;
+  int split = blockIdx.x % nsplit;
+  int sstrip = blockIdx.x / nsplit;
+  int jb0 = (sstrip * 4 + wave) * NJ;
+  size_t wave_id = (size_t)blockIdx.x * 4 + wave;
+  double* pout = partial + wave_id * pstride;
+  if (jb0 >= nblk) {
+    for (int e = lane; e < pstride; e += 64) pout[e] = 0.0;
+    return;
+  }
+  int jc = lane & 15, g = lane >> 4;
+  float b[NJ][KK], sb[NJ][DK_TSMAX], sqj[NJ], u0j[NJ];
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb) {
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) b[jb][kk] = Xb[((size_t)(jb0 + jb) * KK + kk) * 64 + lane];
+#pragma unroll
+    for (int kk = 0; kk < DK_TSMAX; ++kk)
+      sb[jb][kk] = (kk < TS) ? SB[((size_t)(jb0 + jb) * TS + kk) * 64 + lane] : 0.f;
+    sqj[jb] = sq[(jb0 + jb) * 16 + jc];
+    u0j[jb] = u0[(jb0 + jb) * 16 + jc];
+  }
+  float es_tr = 0.f, es_q = 0.f, el_tr = 0.f, el_q = 0.f;
+  f32x4 ytr[NJ][MB], yq[NJ][MB];
+  float ctr[NJ], cq[NJ];
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb) {
+    ctr[jb] = 0.f;
+    cq[jb] = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      ytr[jb][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      yq[jb][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    }
+  }
+  int ib_begin = split * blocks_per_split;
+  int ib_end = min(nblk, ib_begin + blocks_per_split);
+  for (int ib = ib_begin; ib < ib_end; ++ib) {
+    float a[KK], sa[DK_TSMAX];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
+#pragma unroll
+    for (int kk = 0; kk < DK_TSMAX; ++kk)
+      sa[kk] = (kk < TS) ? SA[((size_t)ib * TS + kk) * 64 + lane] : 0.f;
+    f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
+    f32x4 u0i = *(const f32x4*)(u0 + ib * 16 + g * 4);
+    f32x4 xop[MB];
+    if (ARD) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        int dim = mb * 16 + jc;
+        xop[mb] = (dim < DP) ? *(const f32x4*)(X4 + ((size_t)(ib * 4 + g) * DP + dim) * 4)
+                             : (f32x4){0.f, 0.f, 0.f, 0.f};
+      }
+    }
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb) {
+      f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
+      if (ib == jb0 + jb) r2 = fix_diag(r2, lane);
+      f32x4 S = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kk = 0; kk < DK_TSMAX; ++kk)
+        if (kk < TS) S = mfma16(sa[kk], sb[jb][kk], S);
+      f32x4 ts, tq;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float e, gw;
+        unit_kernel_and_weight<KIND>(r2[r], e, gw);
+        float q = u0i[r] * u0j[jb];
+        es_tr = fmaf(e, S[r], es_tr);
+        es_q = fmaf(e, q, es_q);
+        if (ARD) {
+          ts[r] = gw * S[r];
+          tq[r] = gw * q;
+          ctr[jb] += ts[r];
+          cq[jb] += tq[r];
+        } else {
+          float w = gw * r2[r];
+          el_tr = fmaf(w, S[r], el_tr);
+          el_q = fmaf(w, q, el_q);
+        }
+      }
+      if (ARD) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            ytr[jb][mb] = mfma16(xop[mb][r], ts[r], ytr[jb][mb]);
+            yq[jb][mb] = mfma16(xop[mb][r], tq[r], yq[jb][mb]);
+          }
+      }
+    }
+  }
+  // ---- wave-level epilogue -----------------------------------------------------------
+  int nls = ARD ? DP : 1;
+  if (ARD) {
+    float dtr[MB][4], dq[MB][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        dtr[mb][rr] = 0.f;
+        dq[mb][rr] = 0.f;
+      }
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb) {
+      float c1 = ctr[jb], c2 = cq[jb];
+      c1 += __shfl_xor(c1, 16, 64);
+      c1 += __shfl_xor(c1, 32, 64);
+      c2 += __shfl_xor(c2, 16, 64);
+      c2 += __shfl_xor(c2, 32, 64);
+      int j = (jb0 + jb) * 16 + jc;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          int dim = mb * 16 + g * 4 + rr;
+          float xj = (dim < DP) ? Xs[(size_t)j * DP + dim] : 0.f;
+          dtr[mb][rr] += 2.f * xj * (xj * c1 - ytr[jb][mb][rr]);
+          dq[mb][rr] += 2.f * xj * (xj * c2 - yq[jb][mb][rr]);
+        }
+    }
+    // sum over the 16 columns held by lanes with the same l/16
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) {
+        float v1 = dtr[mb][rr], v2 = dq[mb][rr];
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) {
+          v1 += __shfl_xor(v1, o, 64);
+          v2 += __shfl_xor(v2, o, 64);
+        }
+        int dim = mb * 16 + g * 4 + rr;
+        if (jc == 0 && dim < DP) {
+          pout[2 * dim] = (double)v1;
+          pout[2 * dim + 1] = (double)v2;
+        }
+      }
+  } else {
+    float v1 = wave_sum(el_tr), v2 = wave_sum(el_q);
+    if (lane == 0) {
+      pout[0] = (double)v1;
+      pout[1] = (double)v2;
+    }
+  }
+  float s1 = wave_sum(es_tr), s2 = wave_sum(es_q);
+  if (lane == 0) {
+    pout[2 * nls] = (double)s1;
+    pout[2 * nls + 1] = (double)s2;
+  }
+}
+
+// dk_out[e] = sum over waves of partial[w][e], fixed order, fp64.
+__global__ __launch_bounds__(256) void k_dk_finish(const double* __restrict__ partial, int nrows,
+                                                    int pstride, int nvals, DevState* st) {
+  __shared__ double red[256];
+  for (int e = 0; e < nvals; ++e) {
+    double s = 0.0;
+    for (int w = threadIdx.x; w < nrows; w += 256) s += partial[(size_t)w * pstride + e];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) st->dk_out[e] = red[0];
+    __syncthreads();
+  }
+}
+
+// Columns [col0, col0+ncols) of a row-major block (stride ld), times `scale`, into MFMA
+// operand order at operand columns dstcol0..: dst[((i/16)*TS + c/4)*64 + (c%4)*16 + i%16].
+__global__ void k_swizzle_cols(const float* __restrict__ src, int ld, int n, int np, int col0,
+                               int ncols, int TS, int dstcol0, float scale,
+                               float* __restrict__ dst) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)np * ncols) return;
+  int i = (int)(idx / ncols), cc = (int)(idx % ncols);
+  float v = (i < n) ? src[(size_t)i * ld + col0 + cc] * scale : 0.f;
+  int c = dstcol0 + cc;
+  dst[((size_t)(i >> 4) * TS + (c >> 2)) * 64 + (size_t)((c & 3) * 16 + (i & 15))] = v;
+}
+
+__global__ void k_extract_col(const float* __restrict__ src, int ld, int n, int np, int col,
+                              float* __restrict__ dst) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= np) return;
+  dst[i] = (i < n) ? src[(size_t)i * ld + col] : 0.f;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+#define FOR_KK(MACRO)                  \
+  switch (KK) {                        \
+    case 1: MACRO(1); break;           \
+    case 2: MACRO(2); break;           \
+    case 4: MACRO(4); break;           \
+    case 8: MACRO(8); break;           \
+    case 16: MACRO(16); break;         \
+    default: return 1;                 \
+  }
+
+int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
+                      const float* sq, int n, int np, double outputscale, double noise, float* Khat) {
+  dim3 grid(np / 64, np / 64);
+#define BUILD(K)                                                                                  \
+  if (kernel == 0)                                                                                \
+    k_build_khat<0, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, (float)outputscale, (float)noise, Khat); \
+  else                                                                                            \
+    k_build_khat<1, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, (float)outputscale, (float)noise, Khat)
+  FOR_KK(BUILD)
+#undef BUILD
+  return 0;
+}
+
+int launch_mm_mat(hipStream_t s, const float* Khat, const float* D4, float* Vp, int np, int ld,
+                  int nsplit, const DevState* st) {
+  constexpr int NC = 4;
+  int nblk = np / 16;
+  int rows_per_split = 16 * ((nblk + nsplit - 1) / nsplit);
+  int sstrips = (np + 4 * 64 * NC - 1) / (4 * 64 * NC);
+  int grid = sstrips * nsplit;
+  if (ld == 16)
+    k_mm_mat<1, NC><<<grid, 256, 0, s>>>(Khat, D4, Vp, np, nsplit, rows_per_split, st);
+  else if (ld == 32)
+    k_mm_mat<2, 2><<<(np + 4 * 64 * 2 - 1) / (4 * 64 * 2) * nsplit, 256, 0, s>>>(Khat, D4, Vp, np, nsplit,
+                                                                             rows_per_split, st);
+  else
+    return 1;
+  return 0;
+}
+
+int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
+                  const float* D4, float* Vp, int np, int ld, int nsplit, const DevState* st) {
+  constexpr int NJ = 8;
+  int nblk = np / 16;
+  int blocks_per_split = (nblk + nsplit - 1) / nsplit;
+  int sstrips = (nblk + 4 * NJ - 1) / (4 * NJ);
+  int grid = sstrips * nsplit;
+#define OTF(K)                                                                                       \
+  if (kernel == 0 && ld == 16)                                                                       \
+    k_mm_otf<0, K, 1, NJ><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
+  else if (kernel == 0 && ld == 32)                                                                  \
+    k_mm_otf<0, K, 2, NJ><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
+  else if (kernel == 1 && ld == 16)                                                                  \
+    k_mm_otf<1, K, 1, NJ><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
+  else if (kernel == 1 && ld == 32)                                                                  \
+    k_mm_otf<1, K, 2, NJ><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
+  else                                                                                               \
+    return 1
+  FOR_KK(OTF)
+#undef OTF
+  return 0;
+}
+
+int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* Xa, const float* Xb,
+              const float* sq, const float* Xs, const float* X4, const float* SA, const float* SB,
+              const float* u0, int np, int nsplit, double* partial, int pstride, int max_rows,
+              DevState* st) {
+  int nblk = np / 16;
+  int blocks_per_split = (nblk + nsplit - 1) / nsplit;
+  int sstrips = (nblk + 4 * DK_NJ - 1) / (4 * DK_NJ);
+  int grid = sstrips * nsplit;
+  int nrows = grid * 4;
+  if (nrows > max_rows || TS > DK_TSMAX) return 1;
+#define DK(K)                                                                                        \
+  if (kernel == 0 && !ard)                                                                           \
+    k_dk<0, K, 0><<<grid, 256, 0, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
+  else if (kernel == 0 && ard)                                                                       \
+    k_dk<0, K, 1><<<grid, 256, 0, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
+  else if (kernel == 1 && !ard)                                                                      \
+    k_dk<1, K, 0><<<grid, 256, 0, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
+  else                                                                                               \
+    k_dk<1, K, 1><<<grid, 256, 0, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride)
+  FOR_KK(DK)
+#undef DK
+  int nls = ard ? 4 * KK : 1;
+  k_dk_finish<<<1, 256, 0, s>>>(partial, nrows, pstride, 2 * (nls + 1), st);
+  return 0;
+}
+
+void launch_swizzle_cols(hipStream_t s, const float* src, int ld, int n, int np, int col0, int ncols,
+                         int TS, int dstcol0, float scale, float* dst) {
+  size_t total = (size_t)np * ncols;
+  k_swizzle_cols<<<(int)((total + 255) / 256), 256, 0, s>>>(src, ld, n, np, col0, ncols, TS, dstcol0,
+                                                            scale, dst);
+}
+
+void launch_extract_col(hipStream_t s, const float* src, int ld, int n, int np, int col, float* dst) {
+  k_extract_col<<<(np + 255) / 256, 256, 0, s>>>(src, ld, n, np, col, dst);
+}

@@ -1,0 +1,872 @@
+// O(n t) kernels of the BBMM path: input preparation, pivoted Cholesky (App. C),
+// capacitance matrix / Woodbury solve (App. C), probe construction (App. C),
+// the fused mBCG vector updates with all alpha/beta bookkeeping on the device
+// (Alg. 2), and the batched tridiagonal eigen-solver for stochastic Lanczos
+// quadrature (App. B).
+//
+// Reductions over rows use a deterministic two-stage scheme: every block writes
+// fp64 partial sums, the block that finishes last adds them in a fixed order and
+// does the small fp64 scalar algebra (alpha, beta, k x k solves), so no value is
+// read back by the host inside the iteration.
+#include "bbmm_dev.h"
+
+#include <math.h>
+
+#define VT BBMM_VEC_THREADS
+
+namespace {
+
+__device__ inline size_t d4_index(int i, int q, int ld) {
+  return (size_t)(i >> 2) * (size_t)(4 * ld) + (size_t)q * 4 + (size_t)(i & 3);
+}
+
+// Returns true in every thread of exactly one block: the one that arrives last.
+__device__ inline bool last_block_arrives(unsigned* counter) {
+  __shared__ int is_last;
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned ticket = atomicAdd(counter, 1u);
+    is_last = (ticket == gridDim.x - 1);
+  }
+  __syncthreads();
+  if (is_last) __threadfence();
+  return is_last != 0;
+}
+
+__device__ inline bool finite_d(double x) { return x == x && fabs(x) < 1.0e300; }
+
+// ------------------------------------------------------------------ fills ----
+__global__ void k_fill_f32(float* p, size_t count, float v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) p[i] = v;
+}
+
+__global__ void k_fill_u32(unsigned* p, size_t count) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) p[i] = 0u;
+}
+
+// ------------------------------------------------------- input preparation ---
+// Column means of X (fp64), one block.
+__global__ __launch_bounds__(1024) void k_colmean(const float* __restrict__ X, int n, int d,
+                                                   DevState* st) {
+  __shared__ double red[1024];
+  for (int dim = 0; dim < d; ++dim) {
+    double s = 0.0;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) s += (double)X[(size_t)i * d + dim];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+      if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) st->xmean[dim] = red[0] / (double)n;
+    __syncthreads();
+  }
+}
+
+// Scaled, centred copies of X in the layouts the tile kernels read:
+//   Xb[(b*KK + kk)*64 + l] = xs[16 b + l%16][4 kk + l/16]          (MFMA operand order)
+//   Xa = -2 * Xb
+//   Xs[i*dp + dim]  (row-major),  X4[(i/4)*4*dp + dim*4 + i%4]  (quad-swizzled)
+//   sq[i] = sum_dim xs^2
+// with xs[i][dim] = (X[i][dim] - mean[dim]) * xscale[dim], zero for padding rows / dims.
+__global__ void k_prep_x(const float* __restrict__ X, int n, int d, int np, int KK, HypArgs hyp,
+                         const DevState* __restrict__ st, float* __restrict__ Xa,
+                         float* __restrict__ Xb, float* __restrict__ Xs, float* __restrict__ X4,
+                         float* __restrict__ sq) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= np) return;
+  int dp = 4 * KK;
+  float acc = 0.f;
+  int b = i >> 4, r16 = i & 15;
+  for (int dim = 0; dim < dp; ++dim) {
+    float v = 0.f;
+    if (i < n && dim < d) v = (float)(((double)X[(size_t)i * d + dim] - st->xmean[dim])) * hyp.xscale[dim];
+    int kk = dim >> 2, g = dim & 3;
+    size_t sw = ((size_t)b * KK + kk) * 64 + (size_t)(g * 16 + r16);
+    Xb[sw] = v;
+    Xa[sw] = -2.f * v;
+    Xs[(size_t)i * dp + dim] = v;
+    X4[(size_t)(i >> 2) * (size_t)(4 * dp) + (size_t)dim * 4 + (i & 3)] = v;
+    acc = fmaf(v, v, acc);
+  }
+  sq[i] = acc;
+}
+
+// Row-major n x c (stride c) -> quad-swizzled D4 with np rows and ld columns, zero padded.
+__global__ void k_pack_d4(const float* __restrict__ M, int n, int c, int np, int ld,
+                          float* __restrict__ D4) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t total = (size_t)np * ld;
+  if (idx >= total) return;
+  int i = (int)(idx / ld), q = (int)(idx % ld);
+  float v = (i < n && q < c) ? M[(size_t)i * c + q] : 0.f;
+  D4[d4_index(i, q, ld)] = v;
+}
+
+// padded row-major (stride ld) -> dense n x c
+__global__ void k_unpack_rows(const float* __restrict__ src, int ld, int n, int c,
+                              float* __restrict__ dst) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * c) return;
+  int i = (int)(idx / c), q = (int)(idx % c);
+  dst[idx] = src[(size_t)i * ld + q];
+}
+
+// dense n x c -> padded row-major (stride ld), padding columns zero
+__global__ void k_pack_rows(const float* __restrict__ src, int n, int c, int ld,
+                            float* __restrict__ dst) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * ld) return;
+  int i = (int)(idx / ld), q = (int)(idx % ld);
+  dst[idx] = (q < c) ? src[(size_t)i * c + q] : 0.f;
+}
+
+// dense n x c written into columns dstcol0.. of a padded row-major block (other columns untouched)
+__global__ void k_pack_cols_at(const float* __restrict__ src, int n, int c, int ld, int dstcol0,
+                               float* __restrict__ dst) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * c) return;
+  int i = (int)(idx / c), q = (int)(idx % c);
+  dst[(size_t)i * ld + dstcol0 + q] = src[idx];
+}
+
+// dst (nrows x ncols, dense) = src[row0:row0+nrows, col0:col0+ncols]
+__global__ void k_copy_block(const float* __restrict__ src, size_t ld_src, int row0, int nrows,
+                             int col0, int ncols, float* __restrict__ dst) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)nrows * ncols) return;
+  int i = (int)(idx / ncols), j = (int)(idx % ncols);
+  dst[idx] = src[(size_t)(row0 + i) * ld_src + (size_t)(col0 + j)];
+}
+
+// V = scaleV * sum_s Vp[s] + addD * D  (no dot product; used by the stand-alone product call)
+__global__ void k_vreduce(const float* __restrict__ Vp, int nsplit, int n, int np, int ld,
+                          double scaleV, double addD, const float* __restrict__ D4,
+                          float* __restrict__ V) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * ld) return;
+  int i = (int)(idx / ld), q = (int)(idx % ld);
+  double s = 0.0;
+  for (int sp = 0; sp < nsplit; ++sp) s += (double)Vp[(size_t)sp * np * ld + idx];
+  double v = scaleV * s + addD * (double)D4[d4_index(i, q, ld)];
+  V[idx] = (float)v;
+}
+
+// ------------------------------------------------------- pivoted Cholesky ----
+__device__ inline double kernel_value_f64(const float* __restrict__ X, int a, int b,
+                                          const HypArgs& hyp) {
+  double rho2 = 0.0;
+  for (int dim = 0; dim < hyp.d; ++dim) {
+    double df = ((double)X[(size_t)a * hyp.d + dim] - (double)X[(size_t)b * hyp.d + dim]) *
+                hyp.inv_ls[dim];
+    rho2 += df * df;
+  }
+  if (hyp.kernel == 0) return hyp.outputscale * exp(-0.5 * rho2);
+  double rho = sqrt(rho2);
+  const double s5 = 2.23606797749978969;
+  return hyp.outputscale * (1.0 + s5 * rho + (5.0 / 3.0) * rho2) * exp(-s5 * rho);
+}
+
+// Block-level argmax of (value, lowest index on ties); result valid in thread 0.
+__device__ inline void block_argmax(double v, int idx, double* sval, int* sidx, double* outv,
+                                    int* outi) {
+  sval[threadIdx.x] = v;
+  sidx[threadIdx.x] = idx;
+  __syncthreads();
+  for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      double v2 = sval[threadIdx.x + w];
+      int i2 = sidx[threadIdx.x + w];
+      double v1 = sval[threadIdx.x];
+      int i1 = sidx[threadIdx.x];
+      if (v2 > v1 || (v2 == v1 && i2 < i1)) {
+        sval[threadIdx.x] = v2;
+        sidx[threadIdx.x] = i2;
+      }
+    }
+    __syncthreads();
+  }
+  *outv = sval[0];
+  *outi = sidx[0];
+  __syncthreads();
+}
+
+// partial layout for the argmax: partial[2*b] = value, partial[2*b+1] = index (as double)
+__device__ inline void finish_argmax(double bv, int bi, DevState* st, double* partial, int slot,
+                                     double* sval, int* sidx) {
+  if (threadIdx.x == 0) {
+    partial[2 * blockIdx.x] = bv;
+    partial[2 * blockIdx.x + 1] = (double)bi;
+  }
+  if (!last_block_arrives(&st->counter[0])) return;
+  double v = -1.0e300;
+  int ix = 0x7fffffff;
+  for (int b = threadIdx.x; b < (int)gridDim.x; b += blockDim.x) {
+    double v2 = partial[2 * b];
+    int i2 = (int)partial[2 * b + 1];
+    if (v2 > v || (v2 == v && i2 < ix)) {
+      v = v2;
+      ix = i2;
+    }
+  }
+  double ov;
+  int oi;
+  block_argmax(v, ix, sval, sidx, &ov, &oi);
+  if (threadIdx.x == 0) {
+    st->piv[slot] = oi;
+    st->pivdmax[slot] = ov;
+    st->counter[0] = 0u;
+  }
+}
+
+// delta = diag(K_XX) = outputscale (stationary kernels); first pivot = argmax.
+__global__ __launch_bounds__(VT) void k_pc_init(int n, HypArgs hyp, double* __restrict__ delta,
+                                                 DevState* st, double* partial) {
+  __shared__ double sval[VT];
+  __shared__ int sidx[VT];
+  double bv = -1.0e300;
+  int bi = 0x7fffffff;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    double v = hyp.outputscale;
+    delta[i] = v;
+    if (v > bv || (v == bv && i < bi)) {
+      bv = v;
+      bi = i;
+    }
+  }
+  double ov;
+  int oi;
+  block_argmax(bv, bi, sval, sidx, &ov, &oi);
+  if (blockIdx.x == 0 && threadIdx.x == 0) st->rank = 0;
+  finish_argmax(ov, oi, st, partial, 0, sval, sidx);
+}
+
+// Step m of the greedy factorisation: column m of L from row piv[m] of K_XX, residual
+// diagonal update, and the argmax that selects piv[m+1].  Picked rows carry delta = -1.
+__global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int n, int m, int kp,
+                                                 HypArgs hyp, double* __restrict__ delta,
+                                                 float* __restrict__ L, DevState* st,
+                                                 double* partial, double stop_thresh) {
+  __shared__ double sval[VT];
+  __shared__ int sidx[VT];
+  __shared__ double lpiv[BBMM_MAXK];
+  if (st->rank < m) return;       // factorisation stopped early: remaining columns stay zero
+  int piv = st->piv[m];
+  double dpiv = st->pivdmax[m];
+  if (!(dpiv > stop_thresh)) return;
+  double root = sqrt(dpiv);
+  if ((int)threadIdx.x < m) lpiv[threadIdx.x] = (double)L[(size_t)piv * kp + threadIdx.x];
+  __syncthreads();
+  double bv = -1.0e300;
+  int bi = 0x7fffffff;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    double di = delta[i];
+    float lval;
+    if (i == piv) {
+      lval = (float)root;
+      di = -1.0;
+    } else if (di < 0.0) {
+      lval = 0.f;                  // already picked
+    } else {
+      double kv = kernel_value_f64(X, piv, i, hyp);
+      for (int j = 0; j < m; ++j) kv -= lpiv[j] * (double)L[(size_t)i * kp + j];
+      lval = (float)(kv / root);
+      double lf = (double)lval;
+      di = di - lf * lf;
+      if (di < 0.0) di = 0.0;
+    }
+    L[(size_t)i * kp + m] = lval;
+    delta[i] = di;
+    if (di >= 0.0 && (di > bv || (di == bv && i < bi))) {
+      bv = di;
+      bi = i;
+    }
+  }
+  double ov;
+  int oi;
+  block_argmax(bv, bi, sval, sidx, &ov, &oi);
+  if (blockIdx.x == 0 && threadIdx.x == 0) st->rank = m + 1;
+  finish_argmax(ov, oi, st, partial, m + 1, sval, sidx);
+}
+
+// ---------------------------------------------- capacitance matrix, log|P| ---
+// C = sigma^2 I + L^T L (k x k, fp64), Cholesky factor G, log|P| = log|C| + (n-k) log sigma^2.
+__global__ __launch_bounds__(VT) void k_pre_setup(const float* __restrict__ L, int n, int kp,
+                                                   double noise, DevState* st, double* partial) {
+  int k = st->rank;
+  int npairs = k * k;
+  // each thread owns pairs e = tid, tid + VT, ... (at most 4 for k <= 32)
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  int rows_per_block = (n + gridDim.x - 1) / gridDim.x;
+  int r0 = blockIdx.x * rows_per_block;
+  int r1 = min(n, r0 + rows_per_block);
+  for (int i = r0; i < r1; ++i) {
+    const float* li = L + (size_t)i * kp;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      int e = threadIdx.x + u * VT;
+      if (e < npairs) acc[u] += (double)li[e / k] * (double)li[e % k];
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    int e = threadIdx.x + u * VT;
+    if (e < npairs) partial[(size_t)blockIdx.x * (BBMM_MAXK * BBMM_MAXK) + e] = acc[u];
+  }
+  if (!last_block_arrives(&st->counter[1])) return;
+  __shared__ double C[BBMM_MAXK * BBMM_MAXK];
+  for (int e = threadIdx.x; e < npairs; e += VT) {
+    double s = 0.0;
+    for (int b = 0; b < (int)gridDim.x; ++b) s += partial[(size_t)b * (BBMM_MAXK * BBMM_MAXK) + e];
+    int a = e / k, c = e % k;
+    C[a * BBMM_MAXK + c] = s + (a == c ? noise : 0.0);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    // in-place lower Cholesky factorisation of C in LDS
+    double logdet = 0.0;
+    int bad = 0;
+    for (int a = 0; a < k; ++a) {
+      for (int c = 0; c <= a; ++c) {
+        double s = C[a * BBMM_MAXK + c];
+        for (int j = 0; j < c; ++j) s -= C[a * BBMM_MAXK + j] * C[c * BBMM_MAXK + j];
+        if (a == c) {
+          if (!(s > 0.0) || !finite_d(s)) {
+            bad = 1;
+            s = 1.0;
+          }
+          double g = sqrt(s);
+          C[a * BBMM_MAXK + a] = g;
+          logdet += 2.0 * log(g);
+        } else {
+          C[a * BBMM_MAXK + c] = s / C[c * BBMM_MAXK + c];
+        }
+      }
+    }
+    st->logdetP = logdet + (double)(n - k) * log(noise);
+    if (bad) st->status = 3;
+    st->counter[1] = 0u;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += VT) {
+    int a = e / BBMM_MAXK, c = e % BBMM_MAXK;
+    st->G[e] = (a < k && c <= a) ? C[e] : 0.0;
+  }
+}
+
+// -------------------------------------------------------------- probes -------
+// R[:,0] = y,  R[:,1+i] = L E1[:,i] + sigma E2[:,i]   (row-major, stride ld, zero padded)
+__global__ void k_probes(const float* __restrict__ y, const float* __restrict__ E1,
+                         const float* __restrict__ E2, const float* __restrict__ L, int n, int t,
+                         int kp, int ld, double sigma, const DevState* __restrict__ st,
+                         float* __restrict__ R) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * ld) return;
+  int i = (int)(idx / ld), q = (int)(idx % ld);
+  int k = st->rank;
+  float v = 0.f;
+  if (q == 0) {
+    v = y[i];
+  } else if (q <= t) {
+    double s = sigma * (double)E2[(size_t)i * t + (q - 1)];
+    for (int m = 0; m < k; ++m) s += (double)L[(size_t)i * kp + m] * (double)E1[(size_t)m * t + (q - 1)];
+    v = (float)s;
+  }
+  R[idx] = v;
+}
+
+// ------------------------------------------------ fused mBCG vector updates --
+// (1) after the product: V = scaleV * sum_s Vp[s] + addD * D,  d^T v per column,
+//     then (last block) alpha_j = rho / (d^T v) with the freeze guard.
+__global__ __launch_bounds__(VT) void k_dv(const float* __restrict__ Vp, int nsplit, int n, int np,
+                                            int ld, int c, double scaleV, double addD,
+                                            const float* __restrict__ D4, float* __restrict__ V,
+                                            DevState* st, double* partial, int iter,
+                                            double* alpha_hist) {
+  __shared__ double red[VT];
+  if (st->done) return;
+  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
+  double acc = 0.0;
+  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
+    size_t idx = (size_t)i * ld + q;
+    double s = 0.0;
+    for (int sp = 0; sp < nsplit; ++sp) s += (double)Vp[(size_t)sp * np * ld + idx];
+    double dd = (double)D4[d4_index(i, q, ld)];
+    float vf = (float)(scaleV * s + addD * dd);
+    V[idx] = vf;
+    acc += dd * (double)vf;
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  if (rl == 0) {
+    double s = 0.0;
+    for (int r = 0; r < rpp; ++r) s += red[r * ld + q];
+    partial[(size_t)blockIdx.x * ld + q] = s;
+  }
+  if (!last_block_arrives(&st->counter[2])) return;
+  if ((int)threadIdx.x < ld) {
+    int qq = threadIdx.x;
+    double s = 0.0;
+    for (int b = 0; b < (int)gridDim.x; ++b) s += partial[(size_t)b * ld + qq];
+    int ok = st->active[qq] && finite_d(s) && s > 0.0 && qq < c;
+    double alpha = ok ? st->rho[qq] / s : 0.0;
+    st->active[qq] = ok;
+    st->alpha_cur[qq] = alpha;
+    st->m_valid[qq] += ok;
+    alpha_hist[(size_t)iter * BBMM_MAXC + qq] = alpha;
+  }
+  if (threadIdx.x == 0) st->counter[2] = 0u;
+}
+
+// (2) U += alpha D, R -= alpha V, then sums |r|^2 and L^T R per column; the last block
+//     solves the k x k system, forms rho' = (|r|^2 - (L^T r)^T C^{-1} (L^T r)) / sigma^2
+//     (which equals r^T P^{-1} r by the Woodbury formula), beta_j, the residual history
+//     and the stop flag.  init != 0: no update, just the sums for R = B (gives Z_0, rho_0).
+template <int KP>
+__global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, double noise, double tol,
+                                            const float* __restrict__ D4,
+                                            const float* __restrict__ V, float* __restrict__ U,
+                                            float* __restrict__ R, const float* __restrict__ L,
+                                            DevState* st, double* partial, int iter,
+                                            double* beta_hist, double* resid_hist) {
+  __shared__ double red[VT];
+  __shared__ double tot[(BBMM_MAXK + 1) * BBMM_MAXC];
+  if (st->done) return;
+  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
+  double alpha = init ? 0.0 : st->alpha_cur[q];
+  double rr = 0.0;
+  double lr[KP > 0 ? KP : 1];
+#pragma unroll
+  for (int m = 0; m < KP; ++m) lr[m] = 0.0;
+  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
+    size_t idx = (size_t)i * ld + q;
+    float rf;
+    if (!init) {
+      double dd = (double)D4[d4_index(i, q, ld)];
+      U[idx] = (float)((double)U[idx] + alpha * dd);
+      rf = (float)((double)R[idx] - alpha * (double)V[idx]);
+      R[idx] = rf;
+    } else {
+      rf = R[idx];
+    }
+    double rd = (double)rf;
+    rr += rd * rd;
+#pragma unroll
+    for (int m = 0; m < KP; ++m) lr[m] += (double)L[(size_t)i * KP + m] * rd;
+  }
+  // block reduction over the rows handled by this block, one quantity at a time
+  size_t pstride = (size_t)(KP + 1) * ld;
+#pragma unroll
+  for (int e = 0; e <= KP; ++e) {
+    double val = (e == 0) ? rr : lr[e > 0 ? e - 1 : 0];
+    red[threadIdx.x] = val;
+    __syncthreads();
+    if (rl == 0) {
+      double s = 0.0;
+      for (int r = 0; r < rpp; ++r) s += red[r * ld + q];
+      partial[(size_t)blockIdx.x * pstride + (size_t)e * ld + q] = s;
+    }
+    __syncthreads();
+  }
+  if (!last_block_arrives(&st->counter[3])) return;
+  for (int e = threadIdx.x; e < (KP + 1) * ld; e += VT) {
+    double s = 0.0;
+    for (int b = 0; b < (int)gridDim.x; ++b) s += partial[(size_t)b * pstride + e];
+    tot[e] = s;
+  }
+  __shared__ double Gs[BBMM_MAXK * BBMM_MAXK];
+  for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += VT) Gs[e] = st->G[e];
+  __syncthreads();
+  if ((int)threadIdx.x < ld) {
+    int qq = threadIdx.x;
+    int k = st->rank;
+    double rrq = tot[qq];
+    // forward substitution G w = L^T r; quad = w^T w; back substitution G^T x = w
+    double quad = 0.0;
+    for (int a = 0; a < k; ++a) {
+      double s = tot[(size_t)(1 + a) * ld + qq];
+      for (int j = 0; j < a; ++j) s -= Gs[a * BBMM_MAXK + j] * tot[(size_t)(1 + j) * ld + qq];
+      s /= Gs[a * BBMM_MAXK + a];
+      tot[(size_t)(1 + a) * ld + qq] = s;
+      quad += s * s;
+    }
+    for (int a = k - 1; a >= 0; --a) {
+      double s = tot[(size_t)(1 + a) * ld + qq];
+      for (int j = a + 1; j < k; ++j) s -= Gs[j * BBMM_MAXK + a] * tot[(size_t)(1 + j) * ld + qq];
+      s /= Gs[a * BBMM_MAXK + a];
+      tot[(size_t)(1 + a) * ld + qq] = s;
+    }
+    for (int a = 0; a < BBMM_MAXK; ++a)
+      st->Qt[a * BBMM_MAXC + qq] = (a < k) ? tot[(size_t)(1 + a) * ld + qq] : 0.0;
+    double rho_new = (rrq - quad) / noise;
+    if (init) {
+      int ok = finite_d(rho_new) && rho_new > 0.0 && qq < c;
+      st->rho[qq] = rho_new;
+      st->rho0[qq] = rho_new;
+      st->bnorm[qq] = sqrt(rrq);
+      st->active[qq] = ok;
+      st->m_valid[qq] = 0;
+      st->beta_cur[qq] = 0.0;
+      st->alpha_cur[qq] = 0.0;
+    } else {
+      int ok2 = st->active[qq] && finite_d(rho_new) && rho_new > 0.0;
+      double beta = ok2 ? rho_new / st->rho[qq] : 0.0;
+      st->active[qq] = ok2;
+      st->beta_cur[qq] = beta;
+      if (ok2) st->rho[qq] = rho_new;
+      beta_hist[(size_t)iter * BBMM_MAXC + qq] = beta;
+      double bn = st->bnorm[qq];
+      double rel = sqrt(rrq) / (bn > 0.0 ? bn : 1.0);
+      resid_hist[(size_t)iter * BBMM_MAXC + qq] = rel;
+      red[qq] = rel;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (!init) {
+      st->iters_run = iter + 1;
+      if (tol > 0.0) {
+        int all = 1;
+        for (int qq = 0; qq < c; ++qq)
+          if (!(red[qq] < tol)) all = 0;
+        if (all) st->done = 1;
+      }
+    }
+    st->counter[3] = 0u;
+  }
+}
+
+// (3) z = P^{-1} r = (r - L Qt) / sigma^2,  d <- z + beta d  (init: d <- z and Z0 <- z).
+template <int KP>
+__global__ __launch_bounds__(VT) void k_zd(int init, int n, int ld, double noise,
+                                            const float* __restrict__ R,
+                                            const float* __restrict__ L, float* __restrict__ D4,
+                                            float* __restrict__ Z0, const DevState* __restrict__ st) {
+  if (st->done) return;
+  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
+  double beta = init ? 0.0 : st->beta_cur[q];
+  double qt[KP > 0 ? KP : 1];
+#pragma unroll
+  for (int m = 0; m < KP; ++m) qt[m] = st->Qt[m * BBMM_MAXC + q];
+  double inv_noise = 1.0 / noise;
+  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
+    size_t idx = (size_t)i * ld + q;
+    double s = (double)R[idx];
+#pragma unroll
+    for (int m = 0; m < KP; ++m) s -= (double)L[(size_t)i * KP + m] * qt[m];
+    double z = s * inv_noise;
+    size_t di = d4_index(i, q, ld);
+    if (init) {
+      Z0[idx] = (float)z;
+      D4[di] = (float)z;
+    } else {
+      D4[di] = (float)(z + beta * (double)D4[di]);
+    }
+  }
+}
+
+// Stand-alone Woodbury apply Z = P^{-1} R: sums (reuse of k_ur in init mode) then this.
+template <int KP>
+__global__ __launch_bounds__(VT) void k_psolve_apply(int n, int ld, double noise,
+                                                      const float* __restrict__ R,
+                                                      const float* __restrict__ L,
+                                                      float* __restrict__ Z,
+                                                      const DevState* __restrict__ st) {
+  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
+  double qt[KP > 0 ? KP : 1];
+#pragma unroll
+  for (int m = 0; m < KP; ++m) qt[m] = st->Qt[m * BBMM_MAXC + q];
+  double inv_noise = 1.0 / noise;
+  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
+    size_t idx = (size_t)i * ld + q;
+    double s = (double)R[idx];
+#pragma unroll
+    for (int m = 0; m < KP; ++m) s -= (double)L[(size_t)i * KP + m] * qt[m];
+    Z[idx] = (float)(s * inv_noise);
+  }
+}
+
+// ---------------------------------------- tridiagonal eigen-solver and SLQ ---
+// Eigenvalues of a symmetric tridiagonal matrix (diagonal a[0..m-1], off-diagonal
+// b[0..m-2]) together with the FIRST component of every unit eigenvector, which is all
+// that e_1^T f(T) e_1 = sum_i w_i^2 f(lambda_i) needs.  Implicit-shift QR sweeps with the
+// Wilkinson shift; each Givens rotation of a sweep is also applied to the row vector
+// w (initially e_1), so w ends up as the first row of the eigenvector matrix.
+// Serial, O(m^2); arrays live in LDS.  b needs m entries (b[m-1] is scratch).
+__device__ void tridiag_eig_first_row(double* a, double* b, double* w, int m) {
+  for (int i = 0; i < m; ++i) w[i] = (i == 0) ? 1.0 : 0.0;
+  if (m <= 1) return;
+  b[m - 1] = 0.0;
+  const double eps = 2.220446049250313e-16;
+  int hi = m - 1;
+  int budget = 60 * m;
+  while (hi > 0 && budget-- > 0) {
+    // deflate converged eigenvalues at the bottom
+    if (fabs(b[hi - 1]) <= eps * (fabs(a[hi - 1]) + fabs(a[hi]))) {
+      b[hi - 1] = 0.0;
+      --hi;
+      continue;
+    }
+    // find the top of the unreduced block ending at hi
+    int lo = hi - 1;
+    while (lo > 0 && fabs(b[lo - 1]) > eps * (fabs(a[lo - 1]) + fabs(a[lo]))) --lo;
+    if (lo > 0) b[lo - 1] = 0.0;
+    // Wilkinson shift from the trailing 2 x 2 block
+    double dlt = 0.5 * (a[hi - 1] - a[hi]);
+    double bb = b[hi - 1];
+    double denom = dlt + (dlt >= 0.0 ? 1.0 : -1.0) * sqrt(dlt * dlt + bb * bb);
+    double mu = (denom != 0.0) ? a[hi] - bb * bb / denom : a[hi];
+    // chase the bulge from lo to hi
+    double x = a[lo] - mu;
+    double z = b[lo];
+    for (int i = lo; i < hi; ++i) {
+      // rotation (c, s) that zeroes z against x:  [c s; -s c]^T applied to rows/cols i, i+1
+      double r = hypot(x, z);
+      double c = (r != 0.0) ? x / r : 1.0;
+      double s = (r != 0.0) ? z / r : 0.0;
+      if (i > lo) b[i - 1] = r;
+      double ai = a[i], aj = a[i + 1], bi = b[i];
+      a[i] = c * c * ai + 2.0 * c * s * bi + s * s * aj;
+      a[i + 1] = s * s * ai - 2.0 * c * s * bi + c * c * aj;
+      b[i] = (c * c - s * s) * bi + c * s * (aj - ai);
+      x = b[i];
+      if (i + 1 < hi) {
+        z = s * b[i + 1];
+        b[i + 1] = c * b[i + 1];
+      }
+      double wi = w[i], wj = w[i + 1];
+      w[i] = c * wi + s * wj;
+      w[i + 1] = -s * wi + c * wj;
+    }
+  }
+}
+
+// One block per probe column: T from the CG coefficients (Observation in App. A),
+// e_1^T log(T) e_1, times rho0.  Thread 0 of block 0 (last arriving) forms the mean.
+__global__ __launch_bounds__(64) void k_slq(const double* __restrict__ alpha_hist,
+                                             const double* __restrict__ beta_hist, int t,
+                                             DevState* st) {
+  __shared__ double a[BBMM_MAXP], b[BBMM_MAXP], w[BBMM_MAXP];
+  int col = blockIdx.x + 1;
+  if (threadIdx.x == 0) {
+    int m = st->m_valid[col];
+    if (m > BBMM_MAXP) m = BBMM_MAXP;
+    for (int j = 0; j < m; ++j) {
+      double al = alpha_hist[(size_t)j * BBMM_MAXC + col];
+      double dg = 1.0 / al;
+      if (j > 0) {
+        double alp = alpha_hist[(size_t)(j - 1) * BBMM_MAXC + col];
+        double bep = beta_hist[(size_t)(j - 1) * BBMM_MAXC + col];
+        dg += bep / alp;
+        b[j - 1] = sqrt(bep) / alp;
+      }
+      a[j] = dg;
+    }
+    tridiag_eig_first_row(a, b, w, m);
+    double g = 0.0;
+    int bad = 0;
+    for (int j = 0; j < m; ++j) {
+      if (!(a[j] > 0.0)) {
+        if (w[j] * w[j] > 1e-20) bad = 1;
+        continue;
+      }
+      g += w[j] * w[j] * log(a[j]);
+    }
+    double term = st->rho0[col] * g;
+    if (!finite_d(term)) bad = 1;
+    st->slq_terms[blockIdx.x] = term;
+    if (bad) st->status = 4;
+  }
+  if (!last_block_arrives(&st->counter[4])) return;
+  if (threadIdx.x == 0) {
+    double s = 0.0;
+    for (int i = 0; i < t; ++i) s += st->slq_terms[i];
+    st->slq_mean = s / (double)t;
+    st->counter[4] = 0u;
+  }
+}
+
+// Stand-alone batched eigen-solve (host arrays copied to the device by the caller).
+__global__ __launch_bounds__(64) void k_tridiag_eig(const double* __restrict__ diag,
+                                                     const double* __restrict__ off, int m,
+                                                     double* __restrict__ eigvals,
+                                                     double* __restrict__ first_row) {
+  __shared__ double a[BBMM_MAXP], b[BBMM_MAXP], w[BBMM_MAXP];
+  if (threadIdx.x != 0) return;
+  size_t bi = blockIdx.x;
+  for (int j = 0; j < m; ++j) a[j] = diag[bi * m + j];
+  for (int j = 0; j + 1 < m; ++j) b[j] = off[bi * (m - 1) + j];
+  tridiag_eig_first_row(a, b, w, m);
+  for (int j = 0; j < m; ++j) {
+    eigvals[bi * m + j] = a[j];
+    first_row[bi * m + j] = w[j];
+  }
+}
+
+// Noise-derivative terms (dK_hat/dsigma^2 = I): (1/t) sum_i u_i^T w_i and u_0^T u_0, plus y^T u_0.
+// One block; dk_out[2*slot], dk_out[2*slot+1] receive (trace, quad), dk_out[2*slot+2] = y^T u_0.
+__global__ __launch_bounds__(1024) void k_noise_terms(const float* __restrict__ U,
+                                                       const float* __restrict__ Z0,
+                                                       const float* __restrict__ y, int n, int ld,
+                                                       int t, int slot, DevState* st) {
+  __shared__ double r1[1024], r2[1024], r3[1024];
+  double tr = 0.0, qd = 0.0, yu = 0.0;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) {
+    const float* u = U + (size_t)i * ld;
+    const float* z = Z0 + (size_t)i * ld;
+    double u0 = (double)u[0];
+    qd += u0 * u0;
+    yu += u0 * (double)y[i];
+    for (int q = 1; q <= t; ++q) tr += (double)u[q] * (double)z[q];
+  }
+  r1[threadIdx.x] = tr;
+  r2[threadIdx.x] = qd;
+  r3[threadIdx.x] = yu;
+  __syncthreads();
+  for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      r1[threadIdx.x] += r1[threadIdx.x + w];
+      r2[threadIdx.x] += r2[threadIdx.x + w];
+      r3[threadIdx.x] += r3[threadIdx.x + w];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    st->dk_out[2 * slot] = r1[0] / (double)t;
+    st->dk_out[2 * slot + 1] = r2[0];
+    st->dk_out[2 * slot + 2] = r3[0];
+  }
+}
+
+inline int blocks_for(size_t count, int threads) { return (int)((count + threads - 1) / threads); }
+
+}  // namespace
+
+// ------------------------------------------------------------------ launchers
+void launch_fill_f32(hipStream_t s, float* p, size_t count, float v) {
+  if (!count) return;
+  int nb = (int)((count + 255) / 256);
+  if (nb > 4096) nb = 4096;
+  k_fill_f32<<<nb, 256, 0, s>>>(p, count, v);
+}
+
+void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes) {
+  size_t count = bytes / 4;
+  if (!count) return;
+  int nb = (int)((count + 255) / 256);
+  if (nb > 4096) nb = 4096;
+  k_fill_u32<<<nb, 256, 0, s>>>((unsigned*)p, count);
+}
+
+void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st) {
+  k_colmean<<<1, 1024, 0, s>>>(X, n, d, st);
+}
+
+void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, HypArgs hyp,
+                   const DevState* st, float* Xa, float* Xb, float* Xs, float* X4, float* sq) {
+  k_prep_x<<<blocks_for(np, 256), 256, 0, s>>>(X, n, d, np, KK, hyp, st, Xa, Xb, Xs, X4, sq);
+}
+
+void launch_pack_d4(hipStream_t s, const float* M, int n, int c, int np, int ld, float* D4) {
+  k_pack_d4<<<blocks_for((size_t)np * ld, 256), 256, 0, s>>>(M, n, c, np, ld, D4);
+}
+
+void launch_unpack_rows(hipStream_t s, const float* src, int ld, int n, int c, float* dst) {
+  k_unpack_rows<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, ld, n, c, dst);
+}
+
+void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, float* dst) {
+  k_pack_rows<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(src, n, c, ld, dst);
+}
+
+void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, float* dst) {
+  k_pack_cols_at<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, n, c, ld, dstcol0, dst);
+}
+
+void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0, int nrows, int col0,
+                       int ncols, float* dst) {
+  k_copy_block<<<blocks_for((size_t)nrows * ncols, 256), 256, 0, s>>>(src, ld_src, row0, nrows, col0,
+                                                                      ncols, dst);
+}
+
+void launch_vreduce(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld, double scaleV,
+                    double addD, const float* D4, float* V) {
+  k_vreduce<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(Vp, nsplit, n, np, ld, scaleV, addD, D4, V);
+}
+
+void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* partial,
+                    int nblocks) {
+  k_pc_init<<<nblocks, VT, 0, s>>>(n, hyp, delta, st, partial);
+}
+
+void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
+                    float* L, DevState* st, double* partial, int nblocks) {
+  double thresh = 1e-12 * hyp.outputscale;
+  k_pc_step<<<nblocks, VT, 0, s>>>(X, n, m, kp, hyp, delta, L, st, partial, thresh);
+}
+
+void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
+                      double* partial, int nblocks) {
+  (void)k;
+  k_pre_setup<<<nblocks, VT, 0, s>>>(L, n, kp, noise, st, partial);
+}
+
+void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
+                   int n, int t, int kp, int ld, double noise, const DevState* st, float* R) {
+  k_probes<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(y, E1, E2, L, n, t, kp, ld, sqrt(noise), st, R);
+}
+
+void launch_dv(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
+               double addD, const float* D4, float* V, DevState* st, double* partial, int nblocks,
+               int iter, double* alpha_hist) {
+  k_dv<<<nblocks, VT, 0, s>>>(Vp, nsplit, n, np, ld, c, scaleV, addD, D4, V, st, partial, iter,
+                              alpha_hist);
+}
+
+#define DISPATCH_KP(KERNEL, kp, grid, ...)                                  \
+  switch (kp) {                                                             \
+    case 0: KERNEL<0><<<grid, VT, 0, s>>>(__VA_ARGS__); break;              \
+    case 8: KERNEL<8><<<grid, VT, 0, s>>>(__VA_ARGS__); break;              \
+    case 16: KERNEL<16><<<grid, VT, 0, s>>>(__VA_ARGS__); break;            \
+    case 24: KERNEL<24><<<grid, VT, 0, s>>>(__VA_ARGS__); break;            \
+    default: KERNEL<32><<<grid, VT, 0, s>>>(__VA_ARGS__); break;            \
+  }
+
+void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
+               const float* D4, const float* V, float* U, float* R, const float* L, DevState* st,
+               double* partial, int nblocks, int iter, double* beta_hist, double* resid_hist) {
+  DISPATCH_KP(k_ur, kp, nblocks, init, n, ld, c, noise, tol, D4, V, U, R, L, st, partial, iter,
+              beta_hist, resid_hist);
+}
+
+void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const float* R,
+               const float* L, float* D4, float* Z0, DevState* st, int nblocks) {
+  DISPATCH_KP(k_zd, kp, nblocks, init, n, ld, noise, R, L, D4, Z0, st);
+}
+
+void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const float* R,
+                         const float* L, float* Z, DevState* st, double* partial, int nblocks) {
+  (void)partial;
+  DISPATCH_KP(k_psolve_apply, kp, nblocks, n, ld, noise, R, L, Z, st);
+}
+
+void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int ld,
+                DevState* st) {
+  (void)ld;
+  k_slq<<<t, 64, 0, s>>>(alpha_hist, beta_hist, t, st);
+}
+
+void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,
+                        double* eigvals, double* first_row) {
+  k_tridiag_eig<<<batch, 64, 0, s>>>(diag, off, m, eigvals, first_row);
+}
+
+void launch_noise_terms(hipStream_t s, const float* U, const float* Z0, const float* y, int n, int ld,
+                        int t, int slot, DevState* st) {
+  k_noise_terms<<<1, 1024, 0, s>>>(U, Z0, y, n, ld, t, slot, st);
+}

@@ -1,0 +1,391 @@
+"""GPU parity tests: every stage of the HIP path, called through the C ABI, against the fp64
+oracle on the same seeded inputs.  Sizes span several 16-row tiles, several 256-row padding
+groups and ragged tails.
+
+Tolerances (fp32 GPU vs fp64 oracle): relative 1e-3 norm-wise on each solve column, on the
+log-determinant and on each trace / quadratic term; 1e-2 on the log-determinant against the
+dense-Cholesky value.  Stage outputs that involve no iteration are held to tighter bounds
+derived from fp32 rounding (stated at each test)."""
+import numpy as np
+import pytest
+
+from oracle import bbmm_oracle as O
+from paper_1809_11165_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    from paper_1809_11165_amd import binding
+    c = binding.Context(0)
+    yield c
+    c.close()
+
+
+def _problem(w, mode):
+    from paper_1809_11165_amd import binding
+    return binding.problem_from_workload(w, mode)
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda:0")
+
+
+def _host(tn):
+    return tn.detach().cpu().numpy().astype(np.float64)
+
+
+def _colrel(a, b):
+    """max over columns of |a - b|_2 / |b|_2"""
+    a = np.atleast_2d(a.T).T
+    b = np.atleast_2d(b.T).T
+    num = np.linalg.norm(a - b, axis=0)
+    den = np.linalg.norm(b, axis=0)
+    return float(np.max(num / np.where(den > 0, den, 1.0)))
+
+
+def _khat(w):
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)
+    return K + w.noise * np.eye(w.n)
+
+
+CASES = [
+    # (kernel, ard, n, d) -- ragged n, d not a multiple of 4, d > 16
+    (inputs.RBF, False, 700, 5),
+    (inputs.MATERN52, True, 523, 16),
+    (inputs.RBF, True, 300, 3),
+    (inputs.MATERN52, False, 1030, 20),
+]
+
+
+def _case(kernel, ard, n, d, t=6, k=7, iters=12, noise=0.2, seed=0):
+    return inputs.tiny(n, d, kernel=kernel, ard=ard, t=t, k=k, iters=iters, noise=noise, seed=seed)
+
+
+# ------------------------------------------------------------- K_hat builder ---
+@pytest.mark.parametrize("kernel,ard,n,d", CASES)
+def test_build_khat_matches_oracle_kernel_matrix(ctx, kernel, ard, n, d):
+    w = _case(kernel, ard, n, d)
+    ctx.bbmm_setup(_problem(w, inputs.MATERIALISED))
+    ctx.bbmm_build_khat()
+    got = _host(ctx.bbmm_khat_block(0, n, 0, n))
+    ref = _khat(w)
+    # distance by the |x|^2+|x'|^2-2x.x' expansion in fp32: absolute error ~ 1e-6 |x|^2 in the
+    # exponent, i.e. a few 1e-6 relative to the outputscale
+    assert np.max(np.abs(got - ref)) < 2e-5 * w.outputscale
+    assert np.allclose(np.diag(got), w.outputscale + w.noise, rtol=1e-6)
+    # sub-block access
+    blk = _host(ctx.bbmm_khat_block(17, 40, n - 33, 33))
+    assert np.array_equal(blk, got[17:57, n - 33:].astype(np.float32).astype(np.float64))
+
+
+# ---------------------------------------------------------------- K_hat . M ----
+@pytest.mark.parametrize("mode", [inputs.MATERIALISED, inputs.ONTHEFLY])
+@pytest.mark.parametrize("kernel,ard,n,d", CASES)
+@pytest.mark.parametrize("c", [11, 17])
+def test_kernel_mm_matches_oracle_product(ctx, mode, kernel, ard, n, d, c):
+    w = _case(kernel, ard, n, d)
+    ctx.bbmm_setup(_problem(w, mode))
+    if mode == inputs.MATERIALISED:
+        ctx.bbmm_build_khat()
+    rng = np.random.default_rng(5)
+    M = rng.standard_normal((n, c)).astype(np.float32)
+    V = _host(ctx.bbmm_kernel_mm(mode, _dev(M)))
+    ref = _khat(w) @ M.astype(np.float64)
+    # fp32 accumulation over n terms of O(1) magnitude
+    assert _colrel(V, ref) < 1e-4
+
+
+def test_kernel_mm_split_counts_agree(ctx):
+    w = _case(inputs.RBF, False, 2100, 8)
+    rng = np.random.default_rng(6)
+    M = _dev(rng.standard_normal((w.n, 11)))
+    ref = _khat(w) @ _host(M)
+    for mode in (inputs.MATERIALISED, inputs.ONTHEFLY):
+        ctx.bbmm_setup(_problem(w, mode))
+        if mode == inputs.MATERIALISED:
+            ctx.bbmm_build_khat()
+        for split in (1, 3, 8, 64):
+            ctx.bbmm_tune("mat_split", split)
+            ctx.bbmm_tune("otf_split", split)
+            V = _host(ctx.bbmm_kernel_mm(mode, M))
+            assert _colrel(V, ref) < 1e-4, (mode, split)
+    ctx.bbmm_tune("mat_split", 0)
+    ctx.bbmm_tune("otf_split", 0)
+
+
+# ------------------------------------------------------- pivoted Cholesky ------
+def _oracle_pc(w, k, forced=None):
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)
+    return O.pivoted_cholesky(np.diag(K).copy(), lambda i: K[i], k, forced), K
+
+
+@pytest.mark.parametrize("kernel,ard,n,d", CASES)
+def test_pivoted_cholesky_matches_oracle(ctx, kernel, ard, n, d):
+    w = _case(kernel, ard, n, d, k=9)
+    ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+    L, piv, rank = ctx.bbmm_pivoted_cholesky()
+    assert rank == 9
+    assert len(set(piv.tolist())) == 9
+    assert piv[0] == 0          # constant diagonal: the tie goes to the lowest index
+    # each GPU pivot attains (within fp32 rounding of L) the oracle's maximal residual diagonal
+    (Lf, pf, dmax_forced), K = _oracle_pc(w, 9, piv)
+    delta = np.diag(K).copy()
+    for m in range(9):
+        masked = delta.copy()
+        masked[piv[:m]] = -np.inf
+        assert delta[piv[m]] >= masked.max() * (1 - 1e-4)
+        delta = delta - Lf[:, m] ** 2
+    # factor replayed with the same pivot order
+    got = _host(L)
+    assert np.max(np.abs(got - Lf)) < 5e-6 * np.sqrt(w.outputscale) * 10
+
+
+def test_pivoted_cholesky_rank_zero_and_full_small(ctx):
+    w = _case(inputs.RBF, False, 40, 2, k=0, t=2)
+    ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+    L, piv, rank = ctx.bbmm_pivoted_cholesky()
+    assert rank == 0 and len(piv) == 0
+    assert ctx.bbmm_precond_setup() == pytest.approx(40 * np.log(w.noise), rel=1e-12)
+    w = inputs.tiny(24, 2, kernel=inputs.RBF, t=2, k=24, noise=0.3)
+    w.lengthscale[:] = 0.5
+    ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+    L, piv, rank = ctx.bbmm_pivoted_cholesky()
+    assert rank == 24 and sorted(piv.tolist()) == list(range(24))
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)
+    Lh = _host(L)
+    assert np.max(np.abs(Lh @ Lh.T - K)) < 1e-4
+
+
+# --------------------------------------- Woodbury solve, log|P|, probes --------
+@pytest.mark.parametrize("kernel,ard,n,d", CASES[:2])
+def test_preconditioner_and_probes_match_oracle(ctx, kernel, ard, n, d):
+    w = _case(kernel, ard, n, d, k=8)
+    ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+    L, piv, rank = ctx.bbmm_pivoted_cholesky()
+    logdetP = ctx.bbmm_precond_setup()
+    Lh = _host(L)                                  # the fp32 factor the GPU really uses
+    P = O.make_preconditioner(Lh, w.noise)
+    assert logdetP == pytest.approx(P.logdet, rel=1e-10)
+    rng = np.random.default_rng(2)
+    R = rng.standard_normal((n, 7)).astype(np.float32)
+    Z = _host(ctx.bbmm_precond_solve(_dev(R)))
+    assert _colrel(Z, P.solve(R.astype(np.float64))) < 1e-5
+    B = _host(ctx.bbmm_make_probes())
+    ref = np.concatenate([w.y[:, None].astype(np.float64),
+                          O.make_probes(Lh, w.noise, w.E1, w.E2)], axis=1)
+    assert np.max(np.abs(B - ref)) < 1e-6 * np.max(np.abs(ref))
+
+
+# ---------------------------------------------------------------- mBCG ---------
+@pytest.mark.parametrize("mode", [inputs.MATERIALISED, inputs.ONTHEFLY])
+@pytest.mark.parametrize("kernel,ard,n,d", CASES[:3])
+def test_mbcg_matches_oracle_at_fixed_iterations(ctx, mode, kernel, ard, n, d):
+    w = _case(kernel, ard, n, d, k=6, iters=10)
+    ctx.bbmm_setup(_problem(w, mode))
+    if mode == inputs.MATERIALISED:
+        ctx.bbmm_build_khat()
+    L, piv, rank = ctx.bbmm_pivoted_cholesky()
+    ctx.bbmm_precond_setup()
+    B = ctx.bbmm_make_probes()
+    U, alpha, beta, resid, iters = ctx.bbmm_mbcg(mode, B)
+    assert iters == 10
+    Kh = _khat(w)
+    P = O.make_preconditioner(_host(L), w.noise)
+    ref = O.mbcg(lambda M: Kh @ M, _host(B), P.solve, 10)
+    assert _colrel(_host(U), ref.U) < 1e-3
+    assert np.allclose(alpha[:5], ref.alpha[:5], rtol=1e-3)
+    assert np.allclose(beta[:5], ref.beta[:5], rtol=2e-3)
+    assert np.allclose(resid, ref.resid, rtol=5e-2, atol=1e-6)
+    logdet, terms = ctx.bbmm_slq_logdet()
+    ref_terms = []
+    for i in range(w.t):
+        dg, off = O.tridiag_from_cg(ref.alpha[:, i + 1], ref.beta[:, i + 1], 10)
+        ref_terms.append(ref.rho0[i + 1] * O.e1_logT_e1(dg, off))
+    ref_logdet = P.logdet + np.mean(ref_terms)
+    assert logdet == pytest.approx(ref_logdet, rel=1e-3)
+    assert np.allclose(terms, ref_terms, rtol=1e-3, atol=1e-3 * np.max(np.abs(ref_terms)))
+
+
+def test_mbcg_tolerance_stop_and_wide_block(ctx):
+    w = _case(inputs.RBF, False, 900, 4, t=20, k=10, iters=80, noise=0.05)
+    w.tol = 0.1
+    ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+    L, piv, rank = ctx.bbmm_pivoted_cholesky()
+    ctx.bbmm_precond_setup()
+    B = ctx.bbmm_make_probes()                       # 21 columns -> 32-wide path
+    U, alpha, beta, resid, iters = ctx.bbmm_mbcg(inputs.ONTHEFLY, B)
+    assert 1 <= iters < 80
+    assert resid[iters - 1].max() < 0.1
+    if iters > 1:
+        assert resid[iters - 2].max() >= 0.1
+    assert np.all(alpha[iters:] == 0.0)
+    Kh = _khat(w)
+    P = O.make_preconditioner(_host(L), w.noise)
+    stop = O.mbcg(lambda M: Kh @ M, _host(B), P.solve, 80, tol=0.1)
+    assert abs(stop.iters_run - iters) <= 1          # the oracle's own stop rule agrees
+    ref = O.mbcg(lambda M: Kh @ M, _host(B), P.solve, iters)
+    assert _colrel(_host(U), ref.U) < 1e-3
+    true_rel = np.linalg.norm(_host(B) - Kh @ _host(U), axis=0) / np.linalg.norm(_host(B), axis=0)
+    assert true_rel.max() < 0.11
+
+
+# ------------------------------------------- tridiagonal eigen-solver, SLQ -----
+@pytest.mark.parametrize("m", [1, 2, 3, 17, 50, 100, 256])
+def test_tridiag_eig_batched_against_lapack(ctx, m):
+    import scipy.linalg as sla
+    rng = np.random.default_rng(m)
+    batch = 5
+    diag = rng.uniform(0.5, 3.0, (batch, m))
+    off = rng.uniform(-1.0, 1.0, (batch, max(m - 1, 0))) * 0.4
+    if m > 4:
+        off[1, 2] = 0.0                      # an exactly split matrix
+        diag[2, :] = 1.0                     # constant diagonal
+    vals, first = ctx.bbmm_tridiag_eig_batched(diag, off)
+    for b in range(batch):
+        if m == 1:
+            lam, vec = diag[b], np.ones((1, 1))
+        else:
+            lam, vec = sla.eigh_tridiagonal(diag[b], off[b])
+        order = np.argsort(vals[b])
+        assert np.allclose(vals[b][order], lam, rtol=1e-11, atol=1e-12)
+        assert np.sum(first[b] ** 2) == pytest.approx(1.0, rel=1e-10)
+        # compare the quadrature functional, which is what the weights are for
+        got = np.sum(first[b] ** 2 * np.log(vals[b]))
+        ref = np.sum(vec[0] ** 2 * np.log(lam))
+        assert got == pytest.approx(ref, rel=1e-9, abs=1e-11)
+
+
+# ------------------------------------------------------- derivative pass -------
+@pytest.mark.parametrize("kernel,ard,n,d", CASES)
+def test_dk_traces_match_oracle_formulas(ctx, kernel, ard, n, d):
+    w = _case(kernel, ard, n, d, t=5)
+    ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+    rng = np.random.default_rng(9)
+    U = rng.standard_normal((n, w.t + 1)).astype(np.float32)
+    W = rng.standard_normal((n, w.t)).astype(np.float32)
+    trace, quad = ctx.bbmm_dk_traces(_dev(U), _dev(W))
+    mats = O.kernel_derivative_blocks(w.kernel, w.X, w.X, w.lengthscale, w.outputscale)
+    Ud, Wd = U.astype(np.float64), W.astype(np.float64)
+    ref_tr = [np.sum(Ud[:, 1:] * (M @ Wd)) / w.t for M in mats] + [np.sum(Ud[:, 1:] * Wd) / w.t]
+    ref_q = [Ud[:, 0] @ M @ Ud[:, 0] for M in mats] + [Ud[:, 0] @ Ud[:, 0]]
+    # random-sign sums cancel heavily: scale the tolerance by the sum of absolute terms
+    scale_tr = [np.sum(np.abs(Ud[:, 1:]) * (np.abs(M) @ np.abs(Wd))) / w.t for M in mats] + [1.0]
+    scale_q = [np.abs(Ud[:, 0]) @ np.abs(M) @ np.abs(Ud[:, 0]) for M in mats] + [1.0]
+    for h in range(len(ref_tr)):
+        assert abs(trace[h] - ref_tr[h]) < 2e-5 * scale_tr[h] + 1e-3 * abs(ref_tr[h]), h
+        assert abs(quad[h] - ref_q[h]) < 2e-5 * scale_q[h] + 1e-3 * abs(ref_q[h]), h
+
+
+# ------------------------------------------------------------ whole path -------
+def _full_parity(ctx, w, mode, check_exact=True, tol_solve=1e-3):
+    res = ctx.bbmm_solve_logdet_grad(_problem(w, mode))
+    ref = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
+                           w.k, res.iters_run, forced_pivots=res.pivots)
+    assert res.rank == w.k
+    assert _colrel(_host(res.U), ref.U) < tol_solve
+    assert _colrel(_host(res.u0), ref.u0) < tol_solve
+    assert res.logdet_precond == pytest.approx(ref.logdet_precond, rel=1e-5)
+    assert res.logdet == pytest.approx(ref.logdet, rel=1e-3)
+    assert res.yKinvy == pytest.approx(ref.yKinvy, rel=1e-3)
+    assert res.nlml == pytest.approx(ref.nlml, rel=1e-3)
+    for h in range(len(ref.trace)):
+        assert res.trace[h] == pytest.approx(ref.trace[h], rel=1e-3, abs=1e-3 * np.max(np.abs(ref.trace))), h
+        assert res.quad[h] == pytest.approx(ref.quad[h], rel=1e-3, abs=1e-3 * np.max(np.abs(ref.quad))), h
+        denom = max(abs(ref.trace[h]), abs(ref.quad[h])) / 2
+        assert abs(res.grad_nlml[h] - ref.grad[h]) < 1e-3 * denom + 1e-9, h
+    if check_exact:
+        ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise,
+                               with_traces=False)
+        assert res.logdet == pytest.approx(ex.logdet, rel=1e-2)
+    return res, ref
+
+
+@pytest.mark.parametrize("mode", [inputs.MATERIALISED, inputs.ONTHEFLY])
+def test_full_path_config1(ctx, mode):
+    w = inputs.make(1)                      # n = 1000, d = 4, t = 10, k = 5, p = 20
+    res, ref = _full_parity(ctx, w, mode)
+    assert res.iters_run == 20
+
+
+@pytest.mark.parametrize("mode", [inputs.MATERIALISED, inputs.ONTHEFLY])
+def test_full_path_config2_shape_with_tolerance(ctx, mode):
+    w = inputs.make(2, n=3000)              # RBF d = 8, k = 10, tol 1e-2 or 50 iterations
+    res, ref = _full_parity(ctx, w, mode)
+    assert res.iters_run <= 50
+    assert ref.mbcg.resid[res.iters_run - 1].max() < 1.5e-2
+
+
+@pytest.mark.parametrize("mode", [inputs.MATERIALISED, inputs.ONTHEFLY])
+def test_full_path_config3_shape(ctx, mode):
+    w = inputs.make(3, n=2500)              # Matern-5/2 ARD d = 16, k = 20, p = 50
+    _full_parity(ctx, w, mode)
+
+
+def test_full_path_config4_shape(ctx):
+    w = inputs.make(4, n=3000, iters=40)    # clustered RBF d = 8, t = 16 (17 columns), k = 20
+    _full_parity(ctx, w, inputs.ONTHEFLY)
+
+
+def test_full_path_is_deterministic(ctx):
+    w = inputs.make(1, n=777)
+    a = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
+    b = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
+    assert torch.equal(a.U, b.U)
+    assert a.logdet == b.logdet and np.array_equal(a.trace, b.trace)
+    assert np.array_equal(a.alpha, b.alpha)
+
+
+# -------------------------------------------------------------- edge cases -----
+def test_edge_small_n_rank0_single_probe(ctx):
+    w = inputs.tiny(13, 2, kernel=inputs.RBF, t=1, k=0, iters=13, noise=0.3)
+    res = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
+    ref = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
+                           0, 13)
+    ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise)
+    assert _colrel(_host(res.u0), ex.u0) < 1e-3      # p = n: CG has converged
+    assert res.logdet == pytest.approx(ref.logdet, rel=2e-3)
+
+
+def test_edge_n_equals_one(ctx):
+    w = inputs.tiny(1, 1, kernel=inputs.MATERN52, t=2, k=1, iters=2, noise=0.5)
+    res = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.MATERIALISED))
+    a = w.outputscale + w.noise
+    assert float(res.u0[0]) == pytest.approx(float(w.y[0]) / a, rel=1e-5)
+    assert res.logdet == pytest.approx(np.log(a), rel=1e-5)
+
+
+def test_invalid_arguments_are_rejected(ctx):
+    from paper_1809_11165_amd import binding
+    w = inputs.tiny(50, 3, t=3, k=2)
+    p = _problem(w, inputs.ONTHEFLY)
+    for field, value in [("max_iters", 0), ("max_iters", 257), ("noise", 0.0), ("outputscale", -1.0),
+                         ("k", 33), ("kernel", 7), ("mode", 3)]:
+        q = binding.Problem(**{**{f: getattr(p, f) for f in
+                                  ("kernel", "mode", "X", "y", "lengthscale", "outputscale", "noise",
+                                   "E1", "E2", "k", "max_iters", "tol")}, field: value})
+        if field == "k":
+            q.E1 = _dev(np.ones((33, 3)))
+        with pytest.raises(binding.BbmmError) as ei:
+            ctx.bbmm_solve_logdet_grad(q)
+        assert ei.value.code == binding.EINVAL
+    q = binding.Problem(kernel=p.kernel, mode=p.mode, X=p.X, y=p.y, lengthscale=np.array([1.0, 2.0]),
+                        outputscale=1.0, noise=0.1, E1=p.E1, E2=p.E2, k=2, max_iters=5)
+    with pytest.raises(binding.BbmmError):
+        ctx.bbmm_solve_logdet_grad(q)            # 2 lengthscales for d = 3
+    # call order: the materialised product needs K_hat
+    ctx.bbmm_setup(_problem(w, inputs.MATERIALISED))
+    with pytest.raises(binding.BbmmError):
+        ctx.bbmm_kernel_mm(inputs.MATERIALISED, _dev(np.ones((50, 3))))
+
+
+def test_nan_in_targets_is_reported_not_propagated_silently(ctx):
+    from paper_1809_11165_amd import binding
+    w = inputs.tiny(64, 3, t=3, k=2, iters=4)
+    w.y[5] = np.nan
+    with pytest.raises(binding.BbmmError) as ei:
+        ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
+    assert ei.value.code == binding.ENONFINITE
