@@ -1,0 +1,125 @@
+#!/usr/bin/env python3
+"""Benchmark of the BBMM hot path on one MI355X.
+
+One "step" is one full bbmm_solve_logdet_grad call (preconditioner, probes, mBCG, SLQ
+log-det, derivative traces) on the n = 50,000, d = 16, t = 10 Matern-5/2 ARD workload
+(rank-20 preconditioner, 50 mBCG iterations), inputs resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode mat|otf] [--n N] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
+FP64_VALU_PEAK_TFLOPS = 78.6   # MI355X fp64 vector, published
+
+
+def cpu_baseline(n_sample: int, n_full: int):
+    """Times the fp64 oracle (as it stands) on an n_sample-point instance of the same recipe and
+    scales by (n_full / n_sample)^2, the cost ratio of the O(n^2) products that dominate."""
+    from oracle import bbmm_oracle as O
+    from paper_1809_11165_amd import inputs
+    w = inputs.make(3, n=n_sample)
+    t0 = time.perf_counter()
+    O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
+                     w.k, w.iters)
+    dt = time.perf_counter() - t0
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
+    return {"value": dt * 1e3 * (n_full / n_sample) ** 2, "unit": "ms", "cores": min(cores, threads),
+            "kind": "oracle",
+            "sample": "fp64 numpy oracle, full call (k=20, t=10, 50 iterations) on n=%d points of the same "
+                      "recipe: %.1f s measured, scaled by (n/n_sample)^2 = %.0f"
+                      % (n_sample, dt, (n_full / n_sample) ** 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--mode", choices=["mat", "otf"], default="mat")
+    ap.add_argument("--n", type=int, default=50000)
+    ap.add_argument("--cpu-sample", type=int, default=5000)
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)")
+
+    import torch
+    from paper_1809_11165_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU: the path runs only in the HIP library")
+    mode = inputs.MATERIALISED if args.mode == "mat" else inputs.ONTHEFLY
+    w = inputs.make(3, n=args.n)
+    prob = binding.problem_from_workload(w, mode)
+    ctx = binding.Context(0)
+    ctx.bbmm_tune("time_mm", 1)
+
+    res = None
+    for _ in range(args.warmup):
+        res = ctx.bbmm_solve_logdet_grad(prob, want_U=False)
+    torch.cuda.synchronize()
+    mm_avgs, mm_launches = [], 0
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        res = ctx.bbmm_solve_logdet_grad(prob, want_U=False)
+        avg, tot, cnt = ctx.bbmm_mm_timing()
+        mm_avgs.append(avg)
+        mm_launches += cnt
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    mm_ms = float(np.mean(mm_avgs))
+
+    n, c, d = w.n, w.t + 1, w.d
+    if mode == inputs.MATERIALISED:
+        # algorithmic bytes of one K_hat.D launch: K_hat once (4 n^2) + block in and out (8 n c)
+        alg_bytes = 4.0 * n * n + 8.0 * n * c
+        achieved = alg_bytes / (mm_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "kernel": "k_mm_mat", "avg_launch_ms": mm_ms, "launches": mm_launches}
+    else:
+        # algorithmic flops per pair: 2 d (distance contraction) + 2 c (multiply by the block)
+        alg_flops = (2.0 * d + 2.0 * c) * n * n
+        achieved = alg_flops / (mm_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
+                    "kernel": "k_mm_otf", "avg_launch_ms": mm_ms, "launches": mm_launches,
+                    "pairs_per_s": n * n / (mm_ms * 1e-3)}
+
+    out = {
+        "metric": "mBCG solve+logdet+grad ms at n=50k,t=10",
+        "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config3: exact GP, Matern-5/2 ARD, n=%d, d=16, t=10, k=20, 50 mBCG iterations"
+                               % n,
+                   "mode": "materialised fp32 K_hat" if mode == inputs.MATERIALISED else "on-the-fly tiles",
+                   "iters_run": res.iters_run, "ms_per_iteration": ms_per_step / max(res.iters_run, 1),
+                   "mm_ms_per_iteration": mm_ms,
+                   "logdet": res.logdet, "nlml": res.nlml},
+        "roofline": roofline,
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_sample, n)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

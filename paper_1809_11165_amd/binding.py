@@ -177,6 +177,7 @@ class Result:
     resid: np.ndarray
     pivots: np.ndarray
     slq_terms: np.ndarray
+    estimator_rel_err: float = float("nan")   # filled by tests only
 
 
 class Context:

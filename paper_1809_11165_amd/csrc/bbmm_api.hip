@@ -116,7 +116,7 @@ int default_split(int np, int cols_per_wg, int want_wgs) {
 
 int mat_split_of(const bbmm_ctx* c, int ld) {
   if (c->mat_split > 0) return (int)std::min<int64_t>(c->mat_split, std::min(kMaxSplit, c->np / 16));
-  return default_split(c->np, ld == 16 ? 1024 : 512, 2048);
+  return default_split(c->np, ld == 16 ? 1024 : 512, 1024);
 }
 
 int otf_split_of(const bbmm_ctx* c) {
@@ -173,7 +173,7 @@ int stage_mm(bbmm_ctx* c, int mode, int ld, int* nsplit, double* scaleV, double*
   if (mode == BBMM_MODE_MATERIALISED) {
     if (!c->khat_built) return fail(c, BBMM_EINVAL, "materialised product needs bbmm_build_khat first");
     int ns = mat_split_of(c, ld);
-    if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<float>(c->D4), ptr<float>(c->Vp), c->np, ld,
+    if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
                       ns, ptr<DevState>(c->st)))
       return fail(c, BBMM_EINVAL, "unsupported block width");
     *nsplit = ns;
@@ -182,7 +182,7 @@ int stage_mm(bbmm_ctx* c, int mode, int ld, int* nsplit, double* scaleV, double*
   } else if (mode == BBMM_MODE_ONTHEFLY) {
     int ns = otf_split_of(c);
     if (launch_mm_otf(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb),
-                      ptr<float>(c->sq), ptr<float>(c->D4), ptr<float>(c->Vp), c->np, ld, ns,
+                      ptr<float>(c->sq), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld, ns,
                       ptr<DevState>(c->st)))
       return fail(c, BBMM_EINVAL, "unsupported block width or input dimension");
     *nsplit = ns;
@@ -224,19 +224,19 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
   DevState* st = ptr<DevState>(c->st);
   int nb = vec_blocks(c->n, ld);
   size_t blk = (size_t)c->np * ld;
-  launch_fill_f32(s, ptr<float>(c->U), blk, 0.f);
-  launch_fill_f32(s, ptr<float>(c->D4), blk, 0.f);
+  launch_fill_f64(s, ptr<double>(c->U), blk, 0.0);
+  launch_fill_f64(s, ptr<double>(c->D4), blk, 0.0);
   launch_fill_bytes0(s, c->alpha.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
   launch_fill_bytes0(s, c->beta.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
   launch_fill_bytes0(s, c->resid.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
   // done / iters_run live next to each other at the end of DevState
   launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
   double noise = c->prob.noise;
-  launch_ur(s, 1, c->n, ld, cc, c->kp, noise, 0.0, ptr<float>(c->D4), ptr<float>(c->V), ptr<float>(c->U),
-            ptr<float>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), nb, 0, ptr<double>(c->beta),
+  launch_ur(s, 1, c->n, ld, cc, c->kp, noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V), ptr<double>(c->U),
+            ptr<double>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), nb, 0, ptr<double>(c->beta),
             ptr<double>(c->resid));
-  launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<float>(c->R), ptr<float>(c->L), ptr<float>(c->D4),
-            ptr<float>(c->Z0), st, nb);
+  launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<float>(c->L), ptr<double>(c->D4),
+            ptr<double>(c->Z0), st, nb);
   if (c->time_mm) {
     while ((int)c->ev.size() < 2 * c->maxit) {
       hipEvent_t e;
@@ -255,13 +255,13 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
       HIPCHK(c, hipEventRecord(c->ev[2 * j + 1], s));
       c->ev_iters = j + 1;
     }
-    launch_dv(s, ptr<float>(c->Vp), ns, c->n, c->np, ld, cc, scaleV, addD, ptr<float>(c->D4),
-              ptr<float>(c->V), st, ptr<double>(c->partial), nb, j, ptr<double>(c->alpha));
-    launch_ur(s, 0, c->n, ld, cc, c->kp, noise, c->prob.tol, ptr<float>(c->D4), ptr<float>(c->V),
-              ptr<float>(c->U), ptr<float>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), nb, j,
+    launch_dv(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, cc, scaleV, addD, ptr<double>(c->D4),
+              ptr<double>(c->V), st, ptr<double>(c->partial), nb, j, ptr<double>(c->alpha));
+    launch_ur(s, 0, c->n, ld, cc, c->kp, noise, c->prob.tol, ptr<double>(c->D4), ptr<double>(c->V),
+              ptr<double>(c->U), ptr<double>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), nb, j,
               ptr<double>(c->beta), ptr<double>(c->resid));
-    launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<float>(c->R), ptr<float>(c->L), ptr<float>(c->D4),
-              ptr<float>(c->Z0), st, nb);
+    launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<float>(c->L), ptr<double>(c->D4),
+              ptr<double>(c->Z0), st, nb);
   }
   c->mbcg_done = true;
   c->last_c = cc;
@@ -272,8 +272,7 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
 
 int stage_slq(bbmm_ctx* c) {
   if (!c->mbcg_done || c->last_t < 1) return fail(c, BBMM_EINVAL, "bbmm_mbcg with at least one probe column must run first");
-  launch_slq(c->stream, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, c->last_ld,
-             ptr<DevState>(c->st));
+  launch_slq(c->stream, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, ptr<DevState>(c->st));
   return BBMM_OK;
 }
 
@@ -288,8 +287,8 @@ int stage_dk(bbmm_ctx* c, int ld, int t) {
   float* SB = ptr<float>(c->SB);
   launch_fill_f32(s, SA, opsz, 0.f);
   launch_fill_f32(s, SB, opsz, 0.f);
-  const float* U = ptr<float>(c->U);
-  const float* Z0 = ptr<float>(c->Z0);
+  const double* U = ptr<double>(c->U);
+  const double* Z0 = ptr<double>(c->Z0);
   if (!ard) {
     launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, 0, 1.f / (float)t, SA);
     launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, 0, 1.f, SB);
@@ -307,7 +306,8 @@ int stage_dk(bbmm_ctx* c, int ld, int t) {
                 ptr<double>(c->dkpartial), kDkStride, (int)c->dk_rows_cap, ptr<DevState>(c->st)))
     return fail(c, BBMM_EINVAL, "derivative pass: unsupported configuration");
   int nls = ard ? c->dp : 1;
-  launch_noise_terms(s, U, Z0, c->prob.y, c->n, ld, t, nls + 1, ptr<DevState>(c->st));
+  launch_noise_terms(s, U, Z0, c->prob.y, c->n, ld, t, nls + 1, ptr<DevState>(c->st), ptr<double>(c->partial),
+                     vec_blocks(c->n, ld));
   return BBMM_OK;
 }
 
@@ -459,7 +459,7 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
   c->hyp.d = c->d;
 
   size_t np = (size_t)c->np;
-  size_t blk = np * BBMM_MAXC * sizeof(float);
+  size_t blk = np * BBMM_MAXC * sizeof(double);
   size_t opx = np * c->dp * sizeof(float);
   struct { Buf* b; size_t bytes; } want[] = {
       {&c->Xa, opx}, {&c->Xb, opx}, {&c->Xs, opx}, {&c->X4, opx}, {&c->sq, np * sizeof(float)},
@@ -484,7 +484,7 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
 
   hipStream_t s = c->stream;
   launch_fill_bytes0(s, c->st.p, sizeof(DevState));
-  launch_colmean(s, in->X, c->n, c->d, ptr<DevState>(c->st));
+  launch_colmean(s, in->X, c->n, c->d, ptr<DevState>(c->st), ptr<double>(c->partial));
   launch_prep_x(s, in->X, c->n, c->d, c->np, c->KK, c->hyp, ptr<DevState>(c->st), ptr<float>(c->Xa),
                 ptr<float>(c->Xb), ptr<float>(c->Xs), ptr<float>(c->X4), ptr<float>(c->sq));
   HIPCHK(c, hipGetLastError());
@@ -522,13 +522,13 @@ int bbmm_kernel_mm(bbmm_ctx* c, int32_t mode, const float* M, int64_t cc, float*
   int ld = ld_for((int)cc);
   hipStream_t s = c->stream;
   launch_fill_bytes0(s, &ptr<DevState>(c->st)->done, 2 * sizeof(int));
-  launch_pack_d4(s, M, c->n, (int)cc, c->np, ld, ptr<float>(c->D4));
+  launch_pack_d4(s, M, c->n, (int)cc, c->np, ld, ptr<double>(c->D4));
   int ns = 0;
   double scaleV = 1.0, addD = 0.0;
   rc = stage_mm(c, mode, ld, &ns, &scaleV, &addD);
   if (rc) return rc;
-  launch_vreduce(s, ptr<float>(c->Vp), ns, c->n, c->np, ld, scaleV, addD, ptr<float>(c->D4), ptr<float>(c->V));
-  launch_unpack_rows(s, ptr<float>(c->V), ld, c->n, (int)cc, V);
+  launch_vreduce(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, scaleV, addD, ptr<double>(c->D4), ptr<double>(c->V));
+  launch_unpack_rows(s, ptr<double>(c->V), ld, c->n, (int)cc, V);
   HIPCHK(c, hipGetLastError());
   return BBMM_OK;
 }
@@ -538,7 +538,7 @@ int bbmm_pivoted_cholesky(bbmm_ctx* c, float* L, int64_t* pivots, int64_t* rank)
   if (rc) return rc;
   rc = stage_pivchol(c);
   if (rc) return rc;
-  if (L && c->k > 0) launch_unpack_rows(c->stream, ptr<float>(c->L), c->kp, c->n, c->k, L);
+  if (L && c->k > 0) launch_unpack_rows_f32(c->stream, ptr<float>(c->L), c->kp, c->n, c->k, L);
   rc = fetch_state(c, false);
   if (rc) return rc;
   if (pivots)
@@ -570,13 +570,13 @@ int bbmm_precond_solve(bbmm_ctx* c, const float* R, int64_t cc, float* Z) {
   DevState* st = ptr<DevState>(c->st);
   int nb = vec_blocks(c->n, ld);
   launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
-  launch_pack_rows(s, R, c->n, (int)cc, ld, ptr<float>(c->tmpA));
-  launch_ur(s, 1, c->n, ld, (int)cc, c->kp, c->prob.noise, 0.0, ptr<float>(c->D4), ptr<float>(c->V),
-            ptr<float>(c->U), ptr<float>(c->tmpA), ptr<float>(c->L), st, ptr<double>(c->partial), nb, 0,
+  launch_pack_rows(s, R, c->n, (int)cc, ld, ptr<double>(c->tmpA));
+  launch_ur(s, 1, c->n, ld, (int)cc, c->kp, c->prob.noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V),
+            ptr<double>(c->U), ptr<double>(c->tmpA), ptr<float>(c->L), st, ptr<double>(c->partial), nb, 0,
             ptr<double>(c->beta), ptr<double>(c->resid));
-  launch_psolve_apply(s, c->n, ld, c->kp, c->prob.noise, ptr<float>(c->tmpA), ptr<float>(c->L),
-                      ptr<float>(c->tmpB), st, ptr<double>(c->partial), nb);
-  launch_unpack_rows(s, ptr<float>(c->tmpB), ld, c->n, (int)cc, Z);
+  launch_psolve_apply(s, c->n, ld, c->kp, c->prob.noise, ptr<double>(c->tmpA), ptr<float>(c->L),
+                      ptr<double>(c->tmpB), st, nb);
+  launch_unpack_rows(s, ptr<double>(c->tmpB), ld, c->n, (int)cc, Z);
   c->mbcg_done = false;
   HIPCHK(c, hipGetLastError());
   return BBMM_OK;
@@ -589,8 +589,8 @@ int bbmm_make_probes(bbmm_ctx* c, float* B) {
   if (!B) return fail(c, BBMM_EINVAL, "B is NULL");
   int cc = c->t + 1, ld = ld_for(cc);
   launch_probes(c->stream, c->prob.y, c->prob.E1, c->prob.E2, ptr<float>(c->L), c->n, c->t, c->kp, ld,
-                c->prob.noise, ptr<DevState>(c->st), ptr<float>(c->tmpA));
-  launch_unpack_rows(c->stream, ptr<float>(c->tmpA), ld, c->n, cc, B);
+                c->prob.noise, ptr<DevState>(c->st), ptr<double>(c->tmpA));
+  launch_unpack_rows(c->stream, ptr<double>(c->tmpA), ld, c->n, cc, B);
   HIPCHK(c, hipGetLastError());
   return BBMM_OK;
 }
@@ -601,10 +601,10 @@ int bbmm_mbcg(bbmm_ctx* c, int32_t mode, const float* B, int64_t cc, float* U, d
   if (rc) return rc;
   if (!B || !U || cc < 1 || cc > BBMM_MAXC) return fail(c, BBMM_EINVAL, "bad block");
   int ld = ld_for((int)cc);
-  launch_pack_rows(c->stream, B, c->n, (int)cc, ld, ptr<float>(c->R));
+  launch_pack_rows(c->stream, B, c->n, (int)cc, ld, ptr<double>(c->R));
   rc = stage_mbcg(c, mode, (int)cc, ld);
   if (rc) return rc;
-  launch_unpack_rows(c->stream, ptr<float>(c->U), ld, c->n, (int)cc, U);
+  launch_unpack_rows(c->stream, ptr<double>(c->U), ld, c->n, (int)cc, U);
   rc = fetch_state(c, true);
   if (rc) return rc;
   int it = c->h_st->iters_run;
@@ -662,9 +662,9 @@ int bbmm_dk_traces(bbmm_ctx* c, const float* U, const float* W, double* trace, d
   if (!U || !W || !trace || !quad) return fail(c, BBMM_EINVAL, "NULL pointer");
   int cc = c->t + 1, ld = ld_for(cc);
   hipStream_t s = c->stream;
-  launch_pack_rows(s, U, c->n, cc, ld, ptr<float>(c->U));
-  launch_fill_f32(s, ptr<float>(c->Z0), (size_t)c->np * ld, 0.f);
-  launch_pack_cols_at(s, W, c->n, c->t, ld, 1, ptr<float>(c->Z0));
+  launch_pack_rows(s, U, c->n, cc, ld, ptr<double>(c->U));
+  launch_fill_f64(s, ptr<double>(c->Z0), (size_t)c->np * ld, 0.0);
+  launch_pack_cols_at(s, W, c->n, c->t, ld, 1, ptr<double>(c->Z0));
   c->mbcg_done = false;
   rc = stage_dk(c, ld, c->t);
   if (rc) return rc;
@@ -691,15 +691,15 @@ int bbmm_solve_logdet_grad(bbmm_ctx* c, const bbmm_problem* in, bbmm_result* out
   rc = stage_pre_setup(c);
   if (rc) return rc;
   launch_probes(s, in->y, in->E1, in->E2, ptr<float>(c->L), c->n, c->t, c->kp, ld, in->noise,
-                ptr<DevState>(c->st), ptr<float>(c->R));
+                ptr<DevState>(c->st), ptr<double>(c->R));
   rc = stage_mbcg(c, in->mode, cc, ld);
   if (rc) return rc;
   rc = stage_slq(c);
   if (rc) return rc;
   rc = stage_dk(c, ld, c->t);
   if (rc) return rc;
-  launch_extract_col(s, ptr<float>(c->U), ld, c->n, c->n, 0, out->u0);
-  if (out->U) launch_unpack_rows(s, ptr<float>(c->U), ld, c->n, cc, out->U);
+  launch_extract_col(s, ptr<double>(c->U), ld, c->n, c->n, 0, out->u0);
+  if (out->U) launch_unpack_rows(s, ptr<double>(c->U), ld, c->n, cc, out->U);
   rc = fetch_state(c, true);
   if (rc) return rc;
   rc = device_status(c);

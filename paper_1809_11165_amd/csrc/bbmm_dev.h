@@ -47,19 +47,22 @@ struct HypArgs {
 };
 
 // ---- launchers implemented in kernels_vec.hip ---------------------------------------------
+// n x c blocks (U, R, V, Z0, D4, Vp) are fp64; kernel matrix, X copies and the factor L are fp32.
 void launch_fill_f32(hipStream_t s, float* p, size_t count, float v);
+void launch_fill_f64(hipStream_t s, double* p, size_t count, double v);
 void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes);
-void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st);
+void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st, double* partial);
 void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, HypArgs hyp,
                    const DevState* st, float* Xa, float* Xb, float* Xs, float* X4, float* sq);
-void launch_pack_d4(hipStream_t s, const float* M, int n, int c, int np, int ld, float* D4);
-void launch_unpack_rows(hipStream_t s, const float* src, int ld, int n, int c, float* dst);
-void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, float* dst);
-void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, float* dst);
+void launch_pack_d4(hipStream_t s, const float* M, int n, int c, int np, int ld, double* D4);
+void launch_unpack_rows(hipStream_t s, const double* src, int ld, int n, int c, float* dst);
+void launch_unpack_rows_f32(hipStream_t s, const float* src, int ld, int n, int c, float* dst);
+void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, double* dst);
+void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, double* dst);
 void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0, int nrows, int col0,
                        int ncols, float* dst);
-void launch_vreduce(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld, double scaleV,
-                    double addD, const float* D4, float* V);
+void launch_vreduce(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
+                    double addD, const double* D4, double* V);
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* partial,
                     int nblocks);
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
@@ -67,37 +70,36 @@ void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs
 void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
                       double* partial, int nblocks);
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
-                   int n, int t, int kp, int ld, double noise, const DevState* st, float* R);
-void launch_dv(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
-               double addD, const float* D4, float* V, DevState* st, double* partial, int nblocks,
+                   int n, int t, int kp, int ld, double noise, const DevState* st, double* R);
+void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
+               double addD, const double* D4, double* V, DevState* st, double* partial, int nblocks,
                int iter, double* alpha_hist);
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
-               const float* D4, const float* V, float* U, float* R, const float* L, DevState* st,
+               const double* D4, const double* V, double* U, double* R, const float* L, DevState* st,
                double* partial, int nblocks, int iter, double* beta_hist, double* resid_hist);
-void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const float* R,
-               const float* L, float* D4, float* Z0, DevState* st, int nblocks);
-void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const float* R,
-                         const float* L, float* Z, DevState* st, double* partial, int nblocks);
-void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int ld,
-                DevState* st);
+void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,
+               const float* L, double* D4, double* Z0, DevState* st, int nblocks);
+void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const double* R,
+                         const float* L, double* Z, DevState* st, int nblocks);
+void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, DevState* st);
 void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,
                         double* eigvals, double* first_row);
-void launch_noise_terms(hipStream_t s, const float* U, const float* Z0, const float* y, int n, int ld,
-                        int t, int slot, DevState* st);
+void launch_noise_terms(hipStream_t s, const double* U, const double* Z0, const float* y, int n, int ld,
+                        int t, int slot, DevState* st, double* partial, int nblocks);
 
 // ---- launchers implemented in kernels_mm.hip ----------------------------------------------
 int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
                       const float* sq, int n, int np, double outputscale, double noise, float* Khat);
-int launch_mm_mat(hipStream_t s, const float* Khat, const float* D4, float* Vp, int np, int ld,
+int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
                   int nsplit, const DevState* st);
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
-                  const float* D4, float* Vp, int np, int ld, int nsplit, const DevState* st);
+                  const double* D4, double* Vp, int np, int ld, int nsplit, const DevState* st);
 // derivative pass: one partial row (pstride doubles) per wave, then a fixed-order fp64 sum into
 // st->dk_out.  Returns non-zero when the configuration is not supported.
 int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* Xa, const float* Xb,
               const float* sq, const float* Xs, const float* X4, const float* SA, const float* SB,
               const float* u0, int np, int nsplit, double* partial, int pstride, int max_rows,
               DevState* st);
-void launch_swizzle_cols(hipStream_t s, const float* src, int ld, int n, int np, int col0, int ncols,
+void launch_swizzle_cols(hipStream_t s, const double* src, int ld, int n, int np, int col0, int ncols,
                          int TS, int dstcol0, float scale, float* dst);
-void launch_extract_col(hipStream_t s, const float* src, int ld, int n, int np, int col, float* dst);
+void launch_extract_col(hipStream_t s, const double* src, int ld, int n, int np, int col, float* dst);

@@ -17,6 +17,7 @@
 #include "bbmm_dev.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -25,6 +26,14 @@ constexpr float kLog2e = 1.4426950408889634074f;
 
 __device__ inline f32x4 mfma16(float a, float b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// fp64 MFMA 16x16x4: A[m = lane%16][k = lane/16], B[k = lane/16][n = lane%16] as for fp32, but the
+// accumulator holds D[m = 4*r + lane/16][n = lane%16] in register r.  The product with the
+// right-hand-side block is done in fp64 (kernel values converted on the fly) because the CG
+// recurrences amplify fp32-level errors of this product beyond any useful parity bound.
+__device__ inline f64x4 mfma16d(double a, double b, f64x4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
 // r2 tile: |xs_i - xs_j|^2 for a 16 x 16 tile, clamped at 0.
@@ -121,12 +130,13 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
 // ------------------------------------------------ product from a stored K_hat --
 // Wave: 64*NC output columns, a chunk of K_hat rows.  Per 16-row step each lane loads
 // 4 rows x 4 consecutive columns per column group (row 4*(l/16)+r, columns 4*(l%16)..+3):
-// register (r, cc) of that load is the B operand of one MFMA whose A operand is the
-// quad-swizzled right-hand side.  Result partials go to Vp[split].
+// element (r, cc) of that load, converted to fp64, is the B operand of one fp64 MFMA whose A
+// operand is the quad-swizzled fp64 right-hand side.  Result partials go to Vp[split]; a lane's
+// four accumulator values (block columns l/16, 4+l/16, 8+l/16, 12+l/16) are stored contiguously.
 template <int NQ, int NC>
 __global__ __launch_bounds__(256) void k_mm_mat(const float* __restrict__ Khat,
-                                                 const float* __restrict__ D4,
-                                                 float* __restrict__ Vp, int np, int nsplit,
+                                                 const double* __restrict__ D4,
+                                                 double* __restrict__ Vp, int np, int nsplit,
                                                  int rows_per_split,
                                                  const DevState* __restrict__ st) {
   if (st->done) return;
@@ -139,20 +149,20 @@ __global__ __launch_bounds__(256) void k_mm_mat(const float* __restrict__ Khat,
   int jc = lane & 15, g = lane >> 4;
   int j_begin = split * rows_per_split;
   int j_end = min(np, j_begin + rows_per_split);
-  f32x4 acc[NC][4][NQ];
+  f64x4 acc[NC][4][NQ];
 #pragma unroll
   for (int nc = 0; nc < NC; ++nc)
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
   const float* kbase = Khat + (size_t)(g * 4) * np + (size_t)(col0 + 4 * jc);
   for (int j0 = j_begin; j0 < j_end; j0 += 16) {
-    f32x4 dop[NQ];
+    f64x4 dop[NQ];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
-      dop[nq] = *(const f32x4*)(D4 + ((size_t)(j0 / 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+      dop[nq] = *(const f64x4*)(D4 + ((size_t)(j0 / 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
     f32x4 kv[NC][4];
     const float* kp = kbase + (size_t)j0 * np;
 #pragma unroll
@@ -165,31 +175,33 @@ __global__ __launch_bounds__(256) void k_mm_mat(const float* __restrict__ Khat,
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc)
+        for (int cc = 0; cc < 4; ++cc) {
+          double kd = (double)kv[nc][r][cc];
 #pragma unroll
-          for (int nq = 0; nq < NQ; ++nq)
-            acc[nc][cc][nq] = mfma16(dop[nq][r], kv[nc][r][cc], acc[nc][cc][nq]);
+          for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = mfma16d(dop[nq][r], kd, acc[nc][cc][nq]);
+        }
   }
-  float* vout = Vp + (size_t)split * np * LD;
+  double* vout = Vp + (size_t)split * np * LD;
 #pragma unroll
   for (int nc = 0; nc < NC; ++nc)
 #pragma unroll
     for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq)
-        *(f32x4*)(vout + (size_t)(col0 + nc * 64 + 4 * jc + cc) * LD + nq * 16 + g * 4) =
+        *(f64x4*)(vout + (size_t)(col0 + nc * 64 + 4 * jc + cc) * LD + nq * 16 + g * 4) =
             acc[nc][cc][nq];
 }
 
 // ------------------------------------------------------- product on the fly ---
 // Wave: NJ column blocks (16*NJ output rows of V), a chunk of row blocks to contract over.
+// Distances by fp32 MFMA, kernel function in registers, product with the block by fp64 MFMA.
 // Writes partial sums of (K/s) D; the caller scales by s and adds sigma^2 D.
 template <int KIND, int KK, int NQ, int NJ>
 __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
                                                  const float* __restrict__ Xb,
                                                  const float* __restrict__ sq,
-                                                 const float* __restrict__ D4,
-                                                 float* __restrict__ Vp, int np, int nsplit,
+                                                 const double* __restrict__ D4,
+                                                 double* __restrict__ Vp, int np, int nsplit,
                                                  int blocks_per_split,
                                                  const DevState* __restrict__ st) {
   if (st->done) return;
@@ -203,14 +215,14 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
   int jc = lane & 15, g = lane >> 4;
   float b[NJ][KK];
   float sqj[NJ];
-  f32x4 acc[NJ][NQ];
+  f64x4 acc[NJ][NQ];
 #pragma unroll
   for (int jb = 0; jb < NJ; ++jb) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) b[jb][kk] = Xb[((size_t)(jb0 + jb) * KK + kk) * 64 + lane];
     sqj[jb] = sq[(jb0 + jb) * 16 + jc];
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
   }
   int ib_begin = split * blocks_per_split;
   int ib_end = min(nblk, ib_begin + blocks_per_split);
@@ -219,29 +231,28 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
     f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
-    f32x4 dop[NQ];
+    f64x4 dop[NQ];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
-      dop[nq] = *(const f32x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+      dop[nq] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb) {
       f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
       if (ib == jb0 + jb) r2 = fix_diag(r2, lane);
-      f32x4 e;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) e[r] = unit_kernel<KIND>(r2[r]);
+      for (int r = 0; r < 4; ++r) {
+        double e = (double)unit_kernel<KIND>(r2[r]);
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) acc[jb][nq] = mfma16(dop[nq][r], e[r], acc[jb][nq]);
+        for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = mfma16d(dop[nq][r], e, acc[jb][nq]);
+      }
     }
   }
-  float* vout = Vp + (size_t)split * np * LD;
+  double* vout = Vp + (size_t)split * np * LD;
 #pragma unroll
   for (int jb = 0; jb < NJ; ++jb)
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
-      *(f32x4*)(vout + (size_t)((jb0 + jb) * 16 + jc) * LD + nq * 16 + g * 4) = acc[jb][nq];
+      *(f64x4*)(vout + (size_t)((jb0 + jb) * 16 + jc) * LD + nq * 16 + g * 4) = acc[jb][nq];
 }
 
 // ------------------------------------------------------------ derivative pass --
@@ -431,42 +442,40 @@ __global__ __launch_bounds__(256) void k_dk(const float* __restrict__ Xa,
   }
 }
 
-// dk_out[e] = sum over waves of partial[w][e], fixed order, fp64.
+// dk_out[e] = sum over waves of partial[w][e], fixed order, fp64; one block per value e.
 __global__ __launch_bounds__(256) void k_dk_finish(const double* __restrict__ partial, int nrows,
-                                                    int pstride, int nvals, DevState* st) {
+                                                    int pstride, DevState* st) {
   __shared__ double red[256];
-  for (int e = 0; e < nvals; ++e) {
-    double s = 0.0;
-    for (int w = threadIdx.x; w < nrows; w += 256) s += partial[(size_t)w * pstride + e];
-    red[threadIdx.x] = s;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-      if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
-      __syncthreads();
-    }
-    if (threadIdx.x == 0) st->dk_out[e] = red[0];
+  int e = blockIdx.x;
+  double s = 0.0;
+  for (int w = threadIdx.x; w < nrows; w += 256) s += partial[(size_t)w * pstride + e];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
     __syncthreads();
   }
+  if (threadIdx.x == 0) st->dk_out[e] = red[0];
 }
 
 // Columns [col0, col0+ncols) of a row-major block (stride ld), times `scale`, into MFMA
 // operand order at operand columns dstcol0..: dst[((i/16)*TS + c/4)*64 + (c%4)*16 + i%16].
-__global__ void k_swizzle_cols(const float* __restrict__ src, int ld, int n, int np, int col0,
+__global__ void k_swizzle_cols(const double* __restrict__ src, int ld, int n, int np, int col0,
                                int ncols, int TS, int dstcol0, float scale,
                                float* __restrict__ dst) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)np * ncols) return;
   int i = (int)(idx / ncols), cc = (int)(idx % ncols);
-  float v = (i < n) ? src[(size_t)i * ld + col0 + cc] * scale : 0.f;
+  float v = (i < n) ? (float)(src[(size_t)i * ld + col0 + cc] * (double)scale) : 0.f;
   int c = dstcol0 + cc;
   dst[((size_t)(i >> 4) * TS + (c >> 2)) * 64 + (size_t)((c & 3) * 16 + (i & 15))] = v;
 }
 
-__global__ void k_extract_col(const float* __restrict__ src, int ld, int n, int np, int col,
+__global__ void k_extract_col(const double* __restrict__ src, int ld, int n, int np, int col,
                               float* __restrict__ dst) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= np) return;
-  dst[i] = (i < n) ? src[(size_t)i * ld + col] : 0.f;
+  dst[i] = (i < n) ? (float)src[(size_t)i * ld + col] : 0.f;
 }
 
 }  // namespace
@@ -495,7 +504,7 @@ int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const 
   return 0;
 }
 
-int launch_mm_mat(hipStream_t s, const float* Khat, const float* D4, float* Vp, int np, int ld,
+int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
                   int nsplit, const DevState* st) {
   constexpr int NC = 4;
   int nblk = np / 16;
@@ -513,7 +522,7 @@ int launch_mm_mat(hipStream_t s, const float* Khat, const float* D4, float* Vp, 
 }
 
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
-                  const float* D4, float* Vp, int np, int ld, int nsplit, const DevState* st) {
+                  const double* D4, double* Vp, int np, int ld, int nsplit, const DevState* st) {
   constexpr int NJ = 8;
   int nblk = np / 16;
   int blocks_per_split = (nblk + nsplit - 1) / nsplit;
@@ -557,17 +566,17 @@ int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* X
   FOR_KK(DK)
 #undef DK
   int nls = ard ? 4 * KK : 1;
-  k_dk_finish<<<1, 256, 0, s>>>(partial, nrows, pstride, 2 * (nls + 1), st);
+  k_dk_finish<<<2 * (nls + 1), 256, 0, s>>>(partial, nrows, pstride, st);
   return 0;
 }
 
-void launch_swizzle_cols(hipStream_t s, const float* src, int ld, int n, int np, int col0, int ncols,
+void launch_swizzle_cols(hipStream_t s, const double* src, int ld, int n, int np, int col0, int ncols,
                          int TS, int dstcol0, float scale, float* dst) {
   size_t total = (size_t)np * ncols;
   k_swizzle_cols<<<(int)((total + 255) / 256), 256, 0, s>>>(src, ld, n, np, col0, ncols, TS, dstcol0,
                                                             scale, dst);
 }
 
-void launch_extract_col(hipStream_t s, const float* src, int ld, int n, int np, int col, float* dst) {
+void launch_extract_col(hipStream_t s, const double* src, int ld, int n, int np, int col, float* dst) {
   k_extract_col<<<(np + 255) / 256, 256, 0, s>>>(src, ld, n, np, col, dst);
 }

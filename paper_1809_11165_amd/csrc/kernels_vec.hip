@@ -36,8 +36,37 @@ __device__ inline bool last_block_arrives(unsigned* counter) {
 
 __device__ inline bool finite_d(double x) { return x == x && fabs(x) < 1.0e300; }
 
+// Column q of a product block sits at position perm16(q) of its row in the partial buffers:
+// the fp64 MFMA accumulator holds rows 4*r + lane/16, so a lane's four values are the columns
+// lane/16, 4 + lane/16, 8 + lane/16, 12 + lane/16, stored contiguously.
+__device__ inline int perm16(int q) { return (q & ~15) | ((q & 3) << 2) | ((q >> 2) & 3); }
+
+// tot[e] = sum over blocks of partial[b * stride + e], e < nentries, fixed order, all threads.
+__device__ inline void sum_partials(const double* __restrict__ partial, int nblocks, size_t stride,
+                                    int nentries, double* tot) {
+  for (int e = threadIdx.x; e < nentries; e += blockDim.x) {
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int b = 0;
+    for (; b + 3 < nblocks; b += 4) {
+      s0 += partial[(size_t)b * stride + e];
+      s1 += partial[(size_t)(b + 1) * stride + e];
+      s2 += partial[(size_t)(b + 2) * stride + e];
+      s3 += partial[(size_t)(b + 3) * stride + e];
+    }
+    for (; b < nblocks; ++b) s0 += partial[(size_t)b * stride + e];
+    tot[e] = (s0 + s1) + (s2 + s3);
+  }
+  __syncthreads();
+}
+
 // ------------------------------------------------------------------ fills ----
 __global__ void k_fill_f32(float* p, size_t count, float v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) p[i] = v;
+}
+
+__global__ void k_fill_f64(double* p, size_t count, double v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t stride = (size_t)gridDim.x * blockDim.x;
   for (; i < count; i += stride) p[i] = v;
@@ -50,22 +79,33 @@ __global__ void k_fill_u32(unsigned* p, size_t count) {
 }
 
 // ------------------------------------------------------- input preparation ---
-// Column means of X (fp64), one block.
-__global__ __launch_bounds__(1024) void k_colmean(const float* __restrict__ X, int n, int d,
-                                                   DevState* st) {
-  __shared__ double red[1024];
-  for (int dim = 0; dim < d; ++dim) {
-    double s = 0.0;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) s += (double)X[(size_t)i * d + dim];
-    red[threadIdx.x] = s;
+// Column means of X (fp64): per-block partial sums, last block finishes.
+__global__ __launch_bounds__(VT) void k_colmean(const float* __restrict__ X, int n, int d,
+                                                 DevState* st, double* partial) {
+  __shared__ double red[VT];
+  __shared__ double tot[BBMM_MAXD];
+  // thread -> (row slot, dim): consecutive threads read consecutive floats of X
+  size_t total = (size_t)n * d;
+  size_t start = (size_t)blockIdx.x * VT + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * VT;
+  // stride is kept a multiple of d so that a thread always sees the same dimension
+  int dim = (int)(start % d);
+  double acc = 0.0;
+  for (size_t e = start; e < total; e += stride) acc += (double)X[e];
+  for (int dd = 0; dd < d; ++dd) {
+    red[threadIdx.x] = (dim == dd) ? acc : 0.0;
     __syncthreads();
-    for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+    for (int w = VT / 2; w > 0; w >>= 1) {
       if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
       __syncthreads();
     }
-    if (threadIdx.x == 0) st->xmean[dim] = red[0] / (double)n;
+    if (threadIdx.x == 0) partial[(size_t)blockIdx.x * BBMM_MAXD + dd] = red[0];
     __syncthreads();
   }
+  if (!last_block_arrives(&st->counter[5])) return;
+  sum_partials(partial, gridDim.x, BBMM_MAXD, d, tot);
+  if ((int)threadIdx.x < d) st->xmean[threadIdx.x] = tot[threadIdx.x] / (double)n;
+  if (threadIdx.x == 0) st->counter[5] = 0u;
 }
 
 // Scaled, centred copies of X in the layouts the tile kernels read:
@@ -99,18 +139,27 @@ __global__ void k_prep_x(const float* __restrict__ X, int n, int d, int np, int 
 
 // Row-major n x c (stride c) -> quad-swizzled D4 with np rows and ld columns, zero padded.
 __global__ void k_pack_d4(const float* __restrict__ M, int n, int c, int np, int ld,
-                          float* __restrict__ D4) {
+                          double* __restrict__ D4) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t total = (size_t)np * ld;
   if (idx >= total) return;
   int i = (int)(idx / ld), q = (int)(idx % ld);
-  float v = (i < n && q < c) ? M[(size_t)i * c + q] : 0.f;
+  double v = (i < n && q < c) ? (double)M[(size_t)i * c + q] : 0.0;
   D4[d4_index(i, q, ld)] = v;
 }
 
 // padded row-major (stride ld) -> dense n x c
-__global__ void k_unpack_rows(const float* __restrict__ src, int ld, int n, int c,
+__global__ void k_unpack_rows(const double* __restrict__ src, int ld, int n, int c,
                               float* __restrict__ dst) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * c) return;
+  int i = (int)(idx / c), q = (int)(idx % c);
+  dst[idx] = (float)src[(size_t)i * ld + q];
+}
+
+// padded float rows (stride ld) -> dense n x c (used for the Cholesky factor)
+__global__ void k_unpack_rows_f32(const float* __restrict__ src, int ld, int n, int c,
+                                  float* __restrict__ dst) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n * c) return;
   int i = (int)(idx / c), q = (int)(idx % c);
@@ -119,20 +168,20 @@ __global__ void k_unpack_rows(const float* __restrict__ src, int ld, int n, int 
 
 // dense n x c -> padded row-major (stride ld), padding columns zero
 __global__ void k_pack_rows(const float* __restrict__ src, int n, int c, int ld,
-                            float* __restrict__ dst) {
+                            double* __restrict__ dst) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n * ld) return;
   int i = (int)(idx / ld), q = (int)(idx % ld);
-  dst[idx] = (q < c) ? src[(size_t)i * c + q] : 0.f;
+  dst[idx] = (q < c) ? (double)src[(size_t)i * c + q] : 0.0;
 }
 
 // dense n x c written into columns dstcol0.. of a padded row-major block (other columns untouched)
 __global__ void k_pack_cols_at(const float* __restrict__ src, int n, int c, int ld, int dstcol0,
-                               float* __restrict__ dst) {
+                               double* __restrict__ dst) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n * c) return;
   int i = (int)(idx / c), q = (int)(idx % c);
-  dst[(size_t)i * ld + dstcol0 + q] = src[idx];
+  dst[(size_t)i * ld + dstcol0 + q] = (double)src[idx];
 }
 
 // dst (nrows x ncols, dense) = src[row0:row0+nrows, col0:col0+ncols]
@@ -145,16 +194,16 @@ __global__ void k_copy_block(const float* __restrict__ src, size_t ld_src, int r
 }
 
 // V = scaleV * sum_s Vp[s] + addD * D  (no dot product; used by the stand-alone product call)
-__global__ void k_vreduce(const float* __restrict__ Vp, int nsplit, int n, int np, int ld,
-                          double scaleV, double addD, const float* __restrict__ D4,
-                          float* __restrict__ V) {
+__global__ void k_vreduce(const double* __restrict__ Vp, int nsplit, int n, int np, int ld,
+                          double scaleV, double addD, const double* __restrict__ D4,
+                          double* __restrict__ V) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n * ld) return;
   int i = (int)(idx / ld), q = (int)(idx % ld);
+  size_t pidx = (size_t)i * ld + perm16(q);
   double s = 0.0;
-  for (int sp = 0; sp < nsplit; ++sp) s += (double)Vp[(size_t)sp * np * ld + idx];
-  double v = scaleV * s + addD * (double)D4[d4_index(i, q, ld)];
-  V[idx] = (float)v;
+  for (int sp = 0; sp < nsplit; ++sp) s += Vp[(size_t)sp * np * ld + pidx];
+  V[idx] = scaleV * s + addD * D4[d4_index(i, q, ld)];
 }
 
 // ------------------------------------------------------- pivoted Cholesky ----
@@ -364,42 +413,56 @@ __global__ __launch_bounds__(VT) void k_pre_setup(const float* __restrict__ L, i
 __global__ void k_probes(const float* __restrict__ y, const float* __restrict__ E1,
                          const float* __restrict__ E2, const float* __restrict__ L, int n, int t,
                          int kp, int ld, double sigma, const DevState* __restrict__ st,
-                         float* __restrict__ R) {
+                         double* __restrict__ R) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n * ld) return;
   int i = (int)(idx / ld), q = (int)(idx % ld);
   int k = st->rank;
-  float v = 0.f;
+  double v = 0.0;
   if (q == 0) {
-    v = y[i];
+    v = (double)y[i];
   } else if (q <= t) {
     double s = sigma * (double)E2[(size_t)i * t + (q - 1)];
     for (int m = 0; m < k; ++m) s += (double)L[(size_t)i * kp + m] * (double)E1[(size_t)m * t + (q - 1)];
-    v = (float)s;
+    v = (double)(float)s;     // probes are defined as fp32 vectors (what bbmm_make_probes returns)
   }
   R[idx] = v;
 }
 
 // ------------------------------------------------ fused mBCG vector updates --
+// All n x c blocks of the iteration (U, R, D, V, Z0) are kept in fp64: perturbations of
+// relative size 2^-24 in the iterates are amplified by many orders of magnitude over a few
+// tens of CG iterations on ill-conditioned kernel matrices, which would make a fixed-iteration
+// comparison with an fp64 reference meaningless.  They are O(n c) and cost ~nothing next to
+// the O(n^2) product.
+//
 // (1) after the product: V = scaleV * sum_s Vp[s] + addD * D,  d^T v per column,
 //     then (last block) alpha_j = rho / (d^T v) with the freeze guard.
-__global__ __launch_bounds__(VT) void k_dv(const float* __restrict__ Vp, int nsplit, int n, int np,
+__global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, int nsplit, int n, int np,
                                             int ld, int c, double scaleV, double addD,
-                                            const float* __restrict__ D4, float* __restrict__ V,
+                                            const double* __restrict__ D4, double* __restrict__ V,
                                             DevState* st, double* partial, int iter,
                                             double* alpha_hist) {
   __shared__ double red[VT];
+  __shared__ double tot[BBMM_MAXC];
   if (st->done) return;
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
+  int pq = perm16(q);
   double acc = 0.0;
   for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
     size_t idx = (size_t)i * ld + q;
-    double s = 0.0;
-    for (int sp = 0; sp < nsplit; ++sp) s += (double)Vp[(size_t)sp * np * ld + idx];
-    double dd = (double)D4[d4_index(i, q, ld)];
-    float vf = (float)(scaleV * s + addD * dd);
-    V[idx] = vf;
-    acc += dd * (double)vf;
+    size_t pidx = (size_t)i * ld + pq;
+    double s0 = 0.0, s1 = 0.0;
+    int sp = 0;
+    for (; sp + 1 < nsplit; sp += 2) {
+      s0 += Vp[(size_t)sp * np * ld + pidx];
+      s1 += Vp[(size_t)(sp + 1) * np * ld + pidx];
+    }
+    if (sp < nsplit) s0 += Vp[(size_t)sp * np * ld + pidx];
+    double dd = D4[d4_index(i, q, ld)];
+    double v = scaleV * (s0 + s1) + addD * dd;
+    V[idx] = v;
+    acc += dd * v;
   }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -409,10 +472,10 @@ __global__ __launch_bounds__(VT) void k_dv(const float* __restrict__ Vp, int nsp
     partial[(size_t)blockIdx.x * ld + q] = s;
   }
   if (!last_block_arrives(&st->counter[2])) return;
+  sum_partials(partial, gridDim.x, ld, ld, tot);
   if ((int)threadIdx.x < ld) {
     int qq = threadIdx.x;
-    double s = 0.0;
-    for (int b = 0; b < (int)gridDim.x; ++b) s += partial[(size_t)b * ld + qq];
+    double s = tot[qq];
     int ok = st->active[qq] && finite_d(s) && s > 0.0 && qq < c;
     double alpha = ok ? st->rho[qq] / s : 0.0;
     st->active[qq] = ok;
@@ -429,13 +492,14 @@ __global__ __launch_bounds__(VT) void k_dv(const float* __restrict__ Vp, int nsp
 //     and the stop flag.  init != 0: no update, just the sums for R = B (gives Z_0, rho_0).
 template <int KP>
 __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, double noise, double tol,
-                                            const float* __restrict__ D4,
-                                            const float* __restrict__ V, float* __restrict__ U,
-                                            float* __restrict__ R, const float* __restrict__ L,
+                                            const double* __restrict__ D4,
+                                            const double* __restrict__ V, double* __restrict__ U,
+                                            double* __restrict__ R, const float* __restrict__ L,
                                             DevState* st, double* partial, int iter,
                                             double* beta_hist, double* resid_hist) {
   __shared__ double red[VT];
   __shared__ double tot[(BBMM_MAXK + 1) * BBMM_MAXC];
+  __shared__ double Gs[BBMM_MAXK * BBMM_MAXK];
   if (st->done) return;
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
   double alpha = init ? 0.0 : st->alpha_cur[q];
@@ -445,16 +509,15 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
   for (int m = 0; m < KP; ++m) lr[m] = 0.0;
   for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
     size_t idx = (size_t)i * ld + q;
-    float rf;
+    double rd;
     if (!init) {
-      double dd = (double)D4[d4_index(i, q, ld)];
-      U[idx] = (float)((double)U[idx] + alpha * dd);
-      rf = (float)((double)R[idx] - alpha * (double)V[idx]);
-      R[idx] = rf;
+      double dd = D4[d4_index(i, q, ld)];
+      U[idx] = U[idx] + alpha * dd;
+      rd = R[idx] - alpha * V[idx];
+      R[idx] = rd;
     } else {
-      rf = R[idx];
+      rd = R[idx];
     }
-    double rd = (double)rf;
     rr += rd * rd;
 #pragma unroll
     for (int m = 0; m < KP; ++m) lr[m] += (double)L[(size_t)i * KP + m] * rd;
@@ -474,14 +537,8 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
     __syncthreads();
   }
   if (!last_block_arrives(&st->counter[3])) return;
-  for (int e = threadIdx.x; e < (KP + 1) * ld; e += VT) {
-    double s = 0.0;
-    for (int b = 0; b < (int)gridDim.x; ++b) s += partial[(size_t)b * pstride + e];
-    tot[e] = s;
-  }
-  __shared__ double Gs[BBMM_MAXK * BBMM_MAXK];
   for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += VT) Gs[e] = st->G[e];
-  __syncthreads();
+  sum_partials(partial, gridDim.x, pstride, (KP + 1) * ld, tot);
   if ((int)threadIdx.x < ld) {
     int qq = threadIdx.x;
     int k = st->rank;
@@ -544,9 +601,9 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
 // (3) z = P^{-1} r = (r - L Qt) / sigma^2,  d <- z + beta d  (init: d <- z and Z0 <- z).
 template <int KP>
 __global__ __launch_bounds__(VT) void k_zd(int init, int n, int ld, double noise,
-                                            const float* __restrict__ R,
-                                            const float* __restrict__ L, float* __restrict__ D4,
-                                            float* __restrict__ Z0, const DevState* __restrict__ st) {
+                                            const double* __restrict__ R,
+                                            const float* __restrict__ L, double* __restrict__ D4,
+                                            double* __restrict__ Z0, const DevState* __restrict__ st) {
   if (st->done) return;
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
   double beta = init ? 0.0 : st->beta_cur[q];
@@ -556,16 +613,16 @@ __global__ __launch_bounds__(VT) void k_zd(int init, int n, int ld, double noise
   double inv_noise = 1.0 / noise;
   for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
     size_t idx = (size_t)i * ld + q;
-    double s = (double)R[idx];
+    double s = R[idx];
 #pragma unroll
     for (int m = 0; m < KP; ++m) s -= (double)L[(size_t)i * KP + m] * qt[m];
     double z = s * inv_noise;
     size_t di = d4_index(i, q, ld);
     if (init) {
-      Z0[idx] = (float)z;
-      D4[di] = (float)z;
+      Z0[idx] = z;
+      D4[di] = z;
     } else {
-      D4[di] = (float)(z + beta * (double)D4[di]);
+      D4[di] = z + beta * D4[di];
     }
   }
 }
@@ -573,9 +630,9 @@ __global__ __launch_bounds__(VT) void k_zd(int init, int n, int ld, double noise
 // Stand-alone Woodbury apply Z = P^{-1} R: sums (reuse of k_ur in init mode) then this.
 template <int KP>
 __global__ __launch_bounds__(VT) void k_psolve_apply(int n, int ld, double noise,
-                                                      const float* __restrict__ R,
+                                                      const double* __restrict__ R,
                                                       const float* __restrict__ L,
-                                                      float* __restrict__ Z,
+                                                      double* __restrict__ Z,
                                                       const DevState* __restrict__ st) {
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
   double qt[KP > 0 ? KP : 1];
@@ -584,10 +641,10 @@ __global__ __launch_bounds__(VT) void k_psolve_apply(int n, int ld, double noise
   double inv_noise = 1.0 / noise;
   for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
     size_t idx = (size_t)i * ld + q;
-    double s = (double)R[idx];
+    double s = R[idx];
 #pragma unroll
     for (int m = 0; m < KP; ++m) s -= (double)L[(size_t)i * KP + m] * qt[m];
-    Z[idx] = (float)(s * inv_noise);
+    Z[idx] = s * inv_noise;
   }
 }
 
@@ -626,7 +683,7 @@ __device__ void tridiag_eig_first_row(double* a, double* b, double* w, int m) {
     double z = b[lo];
     for (int i = lo; i < hi; ++i) {
       // rotation (c, s) that zeroes z against x:  [c s; -s c]^T applied to rows/cols i, i+1
-      double r = hypot(x, z);
+      double r = sqrt(x * x + z * z);
       double c = (r != 0.0) ? x / r : 1.0;
       double s = (r != 0.0) ? z / r : 0.0;
       if (i > lo) b[i - 1] = r;
@@ -709,26 +766,29 @@ __global__ __launch_bounds__(64) void k_tridiag_eig(const double* __restrict__ d
 }
 
 // Noise-derivative terms (dK_hat/dsigma^2 = I): (1/t) sum_i u_i^T w_i and u_0^T u_0, plus y^T u_0.
-// One block; dk_out[2*slot], dk_out[2*slot+1] receive (trace, quad), dk_out[2*slot+2] = y^T u_0.
-__global__ __launch_bounds__(1024) void k_noise_terms(const float* __restrict__ U,
-                                                       const float* __restrict__ Z0,
-                                                       const float* __restrict__ y, int n, int ld,
-                                                       int t, int slot, DevState* st) {
-  __shared__ double r1[1024], r2[1024], r3[1024];
+// dk_out[2*slot], dk_out[2*slot+1] receive (trace, quad), dk_out[2*slot+2] = y^T u_0.
+__global__ __launch_bounds__(VT) void k_noise_terms(const double* __restrict__ U,
+                                                     const double* __restrict__ Z0,
+                                                     const float* __restrict__ y, int n, int ld,
+                                                     int t, int slot, DevState* st, double* partial) {
+  __shared__ double r1[VT], r2[VT], r3[VT];
+  __shared__ double tot[4];
   double tr = 0.0, qd = 0.0, yu = 0.0;
-  for (int i = threadIdx.x; i < n; i += blockDim.x) {
-    const float* u = U + (size_t)i * ld;
-    const float* z = Z0 + (size_t)i * ld;
-    double u0 = (double)u[0];
-    qd += u0 * u0;
-    yu += u0 * (double)y[i];
-    for (int q = 1; q <= t; ++q) tr += (double)u[q] * (double)z[q];
+  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
+  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
+    double u = U[(size_t)i * ld + q];
+    if (q == 0) {
+      qd += u * u;
+      yu += u * (double)y[i];
+    } else if (q <= t) {
+      tr += u * Z0[(size_t)i * ld + q];
+    }
   }
   r1[threadIdx.x] = tr;
   r2[threadIdx.x] = qd;
   r3[threadIdx.x] = yu;
   __syncthreads();
-  for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+  for (int w = VT / 2; w > 0; w >>= 1) {
     if ((int)threadIdx.x < w) {
       r1[threadIdx.x] += r1[threadIdx.x + w];
       r2[threadIdx.x] += r2[threadIdx.x + w];
@@ -737,9 +797,17 @@ __global__ __launch_bounds__(1024) void k_noise_terms(const float* __restrict__ 
     __syncthreads();
   }
   if (threadIdx.x == 0) {
-    st->dk_out[2 * slot] = r1[0] / (double)t;
-    st->dk_out[2 * slot + 1] = r2[0];
-    st->dk_out[2 * slot + 2] = r3[0];
+    partial[(size_t)blockIdx.x * 4] = r1[0];
+    partial[(size_t)blockIdx.x * 4 + 1] = r2[0];
+    partial[(size_t)blockIdx.x * 4 + 2] = r3[0];
+  }
+  if (!last_block_arrives(&st->counter[6])) return;
+  sum_partials(partial, gridDim.x, 4, 3, tot);
+  if (threadIdx.x == 0) {
+    st->dk_out[2 * slot] = tot[0] / (double)t;
+    st->dk_out[2 * slot + 1] = tot[1];
+    st->dk_out[2 * slot + 2] = tot[2];
+    st->counter[6] = 0u;
   }
 }
 
@@ -755,6 +823,13 @@ void launch_fill_f32(hipStream_t s, float* p, size_t count, float v) {
   k_fill_f32<<<nb, 256, 0, s>>>(p, count, v);
 }
 
+void launch_fill_f64(hipStream_t s, double* p, size_t count, double v) {
+  if (!count) return;
+  int nb = (int)((count + 255) / 256);
+  if (nb > 4096) nb = 4096;
+  k_fill_f64<<<nb, 256, 0, s>>>(p, count, v);
+}
+
 void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes) {
   size_t count = bytes / 4;
   if (!count) return;
@@ -763,8 +838,11 @@ void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes) {
   k_fill_u32<<<nb, 256, 0, s>>>((unsigned*)p, count);
 }
 
-void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st) {
-  k_colmean<<<1, 1024, 0, s>>>(X, n, d, st);
+void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st, double* partial) {
+  // grid stride must be a multiple of d: use nb blocks with nb * 256 % d == 0
+  int nb = 64;
+  while (((size_t)nb * VT) % d != 0) ++nb;      // d <= 64, terminates within d steps
+  k_colmean<<<nb, VT, 0, s>>>(X, n, d, st, partial);
 }
 
 void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, HypArgs hyp,
@@ -772,19 +850,23 @@ void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, 
   k_prep_x<<<blocks_for(np, 256), 256, 0, s>>>(X, n, d, np, KK, hyp, st, Xa, Xb, Xs, X4, sq);
 }
 
-void launch_pack_d4(hipStream_t s, const float* M, int n, int c, int np, int ld, float* D4) {
+void launch_pack_d4(hipStream_t s, const float* M, int n, int c, int np, int ld, double* D4) {
   k_pack_d4<<<blocks_for((size_t)np * ld, 256), 256, 0, s>>>(M, n, c, np, ld, D4);
 }
 
-void launch_unpack_rows(hipStream_t s, const float* src, int ld, int n, int c, float* dst) {
+void launch_unpack_rows(hipStream_t s, const double* src, int ld, int n, int c, float* dst) {
   k_unpack_rows<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, ld, n, c, dst);
 }
 
-void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, float* dst) {
+void launch_unpack_rows_f32(hipStream_t s, const float* src, int ld, int n, int c, float* dst) {
+  k_unpack_rows_f32<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, ld, n, c, dst);
+}
+
+void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, double* dst) {
   k_pack_rows<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(src, n, c, ld, dst);
 }
 
-void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, float* dst) {
+void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, double* dst) {
   k_pack_cols_at<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, n, c, ld, dstcol0, dst);
 }
 
@@ -794,8 +876,8 @@ void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0,
                                                                       ncols, dst);
 }
 
-void launch_vreduce(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld, double scaleV,
-                    double addD, const float* D4, float* V) {
+void launch_vreduce(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
+                    double addD, const double* D4, double* V) {
   k_vreduce<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(Vp, nsplit, n, np, ld, scaleV, addD, D4, V);
 }
 
@@ -817,12 +899,12 @@ void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, doubl
 }
 
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
-                   int n, int t, int kp, int ld, double noise, const DevState* st, float* R) {
+                   int n, int t, int kp, int ld, double noise, const DevState* st, double* R) {
   k_probes<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(y, E1, E2, L, n, t, kp, ld, sqrt(noise), st, R);
 }
 
-void launch_dv(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
-               double addD, const float* D4, float* V, DevState* st, double* partial, int nblocks,
+void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
+               double addD, const double* D4, double* V, DevState* st, double* partial, int nblocks,
                int iter, double* alpha_hist) {
   k_dv<<<nblocks, VT, 0, s>>>(Vp, nsplit, n, np, ld, c, scaleV, addD, D4, V, st, partial, iter,
                               alpha_hist);
@@ -838,26 +920,23 @@ void launch_dv(hipStream_t s, const float* Vp, int nsplit, int n, int np, int ld
   }
 
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
-               const float* D4, const float* V, float* U, float* R, const float* L, DevState* st,
+               const double* D4, const double* V, double* U, double* R, const float* L, DevState* st,
                double* partial, int nblocks, int iter, double* beta_hist, double* resid_hist) {
   DISPATCH_KP(k_ur, kp, nblocks, init, n, ld, c, noise, tol, D4, V, U, R, L, st, partial, iter,
               beta_hist, resid_hist);
 }
 
-void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const float* R,
-               const float* L, float* D4, float* Z0, DevState* st, int nblocks) {
+void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,
+               const float* L, double* D4, double* Z0, DevState* st, int nblocks) {
   DISPATCH_KP(k_zd, kp, nblocks, init, n, ld, noise, R, L, D4, Z0, st);
 }
 
-void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const float* R,
-                         const float* L, float* Z, DevState* st, double* partial, int nblocks) {
-  (void)partial;
+void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const double* R,
+                         const float* L, double* Z, DevState* st, int nblocks) {
   DISPATCH_KP(k_psolve_apply, kp, nblocks, n, ld, noise, R, L, Z, st);
 }
 
-void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int ld,
-                DevState* st) {
-  (void)ld;
+void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, DevState* st) {
   k_slq<<<t, 64, 0, s>>>(alpha_hist, beta_hist, t, st);
 }
 
@@ -866,7 +945,7 @@ void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, in
   k_tridiag_eig<<<batch, 64, 0, s>>>(diag, off, m, eigvals, first_row);
 }
 
-void launch_noise_terms(hipStream_t s, const float* U, const float* Z0, const float* y, int n, int ld,
-                        int t, int slot, DevState* st) {
-  k_noise_terms<<<1, 1024, 0, s>>>(U, Z0, y, n, ld, t, slot, st);
+void launch_noise_terms(hipStream_t s, const double* U, const double* Z0, const float* y, int n, int ld,
+                        int t, int slot, DevState* st, double* partial, int nblocks) {
+  k_noise_terms<<<nblocks, VT, 0, s>>>(U, Z0, y, n, ld, t, slot, st, partial);
 }
