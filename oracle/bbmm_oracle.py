@@ -361,7 +361,7 @@ class BbmmResult:
 
 def bbmm_inference(kernel: int, X, y, ls, s: float, noise: float, E1, E2, k: int, p: int,
                    tol: float = 0.0, forced_pivots: Optional[Sequence[int]] = None,
-                   Khat: Optional[np.ndarray] = None) -> BbmmResult:
+                   Khat: Optional[np.ndarray] = None, trace_row_chunk: int = 2048) -> BbmmResult:
     """One BBMM call: K_hat^{-1} y, log|K_hat| estimate, trace estimates, NLML and gradient."""
     X = np.asarray(X, dtype=np.float64)
     y = np.asarray(y, dtype=np.float64)
@@ -395,13 +395,21 @@ def bbmm_inference(kernel: int, X, y, ls, s: float, noise: float, E1, E2, k: int
         terms[i] = res.rho0[col] * e1_logT_e1(dg, off)
     logdet = P.logdet + float(np.mean(terms))
 
-    # trace estimates with preconditioned probes: (1/t) sum_i u_i^T M_h w_i
+    # trace estimates with preconditioned probes: (1/t) sum_i u_i^T M_h w_i, and u_0^T M_h u_0.
+    # The derivative matrices are formed a block of rows at a time (memory only; each row
+    # block contributes its rows of M_h W and M_h u_0 exactly as the full matrix would).
     U = res.U
     u0 = U[:, 0]
     W = res.Z0[:, 1:]
-    mats = kernel_derivative_blocks(kernel, X, X, ls, s)
-    trace = [float(np.sum(U[:, 1:] * (M @ W)) / t) for M in mats]
-    quad = [float(u0 @ (M @ u0)) for M in mats]
+    H = ls.shape[0] + 1
+    trace = [0.0] * H
+    quad = [0.0] * H
+    for a in range(0, n, trace_row_chunk):
+        b = min(n, a + trace_row_chunk)
+        mats = kernel_derivative_blocks(kernel, X[a:b], X, ls, s)
+        for h, M in enumerate(mats):
+            trace[h] += float(np.sum(U[a:b, 1:] * (M @ W)) / t)
+            quad[h] += float(u0[a:b] @ (M @ u0))
     trace.append(float(np.sum(U[:, 1:] * W) / t))     # dK_hat/dsigma^2 = I
     quad.append(float(u0 @ u0))
     trace = np.array(trace)

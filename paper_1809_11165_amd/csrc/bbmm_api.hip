@@ -20,7 +20,7 @@ struct Buf {
   size_t cap = 0;
 };
 
-constexpr int kMaxVecBlocks = 256;
+constexpr int kMaxVecBlocks = 512;   // at most 32 reduction groups of 16 blocks
 constexpr int kMaxSplit = 64;
 constexpr int kDkStride = 2 * (BBMM_MAXD + 2);
 
@@ -45,7 +45,7 @@ struct bbmm_ctx {
   std::vector<hipEvent_t> ev;                // 2 per iteration, created on demand
   int ev_iters = 0;                          // iterations covered by the last timed run
 
-  Buf Xa, Xb, Xs, X4, sq, Khat, L, delta, U, R, V, Z0, D4, Vp, partial, alpha, beta, resid, st,
+  Buf Xa, Xb, Xs, X4, sq, Khat, L, delta, U, R, V, Z0, D4, Vp, partial, gpartial, alpha, beta, resid, st,
       tmpA, tmpB, SA, SB, u0v, dkpartial, eig;
   DevState* h_st = nullptr;   // pinned
   double* h_hist = nullptr;   // pinned, 3 * MAXP * MAXC doubles
@@ -211,7 +211,7 @@ int stage_pre_setup(bbmm_ctx* c) {
   if (!c->chol_done) return fail(c, BBMM_EINVAL, "bbmm_pivoted_cholesky must run first");
   int nb = std::min(kMaxVecBlocks, std::max(1, c->n / 64));
   launch_pre_setup(c->stream, ptr<float>(c->L), c->n, c->k, c->kp, c->prob.noise, ptr<DevState>(c->st),
-                   ptr<double>(c->partial), nb);
+                   ptr<double>(c->partial), ptr<double>(c->gpartial), nb);
   c->pre_done = true;
   return BBMM_OK;
 }
@@ -233,7 +233,7 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
   launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
   double noise = c->prob.noise;
   launch_ur(s, 1, c->n, ld, cc, c->kp, noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V), ptr<double>(c->U),
-            ptr<double>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), nb, 0, ptr<double>(c->beta),
+            ptr<double>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), ptr<double>(c->gpartial), nb, 0, ptr<double>(c->beta),
             ptr<double>(c->resid));
   launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<float>(c->L), ptr<double>(c->D4),
             ptr<double>(c->Z0), st, nb);
@@ -256,9 +256,9 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
       c->ev_iters = j + 1;
     }
     launch_dv(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, cc, scaleV, addD, ptr<double>(c->D4),
-              ptr<double>(c->V), st, ptr<double>(c->partial), nb, j, ptr<double>(c->alpha));
+              ptr<double>(c->V), st, ptr<double>(c->partial), ptr<double>(c->gpartial), nb, j, ptr<double>(c->alpha));
     launch_ur(s, 0, c->n, ld, cc, c->kp, noise, c->prob.tol, ptr<double>(c->D4), ptr<double>(c->V),
-              ptr<double>(c->U), ptr<double>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), nb, j,
+              ptr<double>(c->U), ptr<double>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), ptr<double>(c->gpartial), nb, j,
               ptr<double>(c->beta), ptr<double>(c->resid));
     launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<float>(c->L), ptr<double>(c->D4),
               ptr<double>(c->Z0), st, nb);
@@ -307,7 +307,7 @@ int stage_dk(bbmm_ctx* c, int ld, int t) {
     return fail(c, BBMM_EINVAL, "derivative pass: unsupported configuration");
   int nls = ard ? c->dp : 1;
   launch_noise_terms(s, U, Z0, c->prob.y, c->n, ld, t, nls + 1, ptr<DevState>(c->st), ptr<double>(c->partial),
-                     vec_blocks(c->n, ld));
+                     ptr<double>(c->gpartial), vec_blocks(c->n, ld));
   return BBMM_OK;
 }
 
@@ -383,7 +383,7 @@ int bbmm_destroy(bbmm_ctx* c) {
   (void)hipSetDevice(c->device);
   (void)hipStreamSynchronize(c->stream);
   Buf* bufs[] = {&c->Xa, &c->Xb, &c->Xs, &c->X4, &c->sq, &c->Khat, &c->L, &c->delta, &c->U, &c->R, &c->V,
-                 &c->Z0, &c->D4, &c->Vp, &c->partial, &c->alpha, &c->beta, &c->resid, &c->st, &c->tmpA,
+                 &c->Z0, &c->D4, &c->Vp, &c->partial, &c->gpartial, &c->alpha, &c->beta, &c->resid, &c->st, &c->tmpA,
                  &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig};
   for (Buf* b : bufs)
     if (b->p) (void)hipFree(b->p);
@@ -467,6 +467,7 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
       {&c->U, blk}, {&c->R, blk}, {&c->V, blk}, {&c->Z0, blk}, {&c->D4, blk},
       {&c->Vp, (size_t)kMaxSplit * blk},
       {&c->partial, sizeof(double) * (size_t)kMaxVecBlocks * (BBMM_MAXK * BBMM_MAXK + (BBMM_MAXK + 1) * BBMM_MAXC)},
+      {&c->gpartial, sizeof(double) * 40 * (BBMM_MAXK * BBMM_MAXK + (BBMM_MAXK + 1) * BBMM_MAXC)},
       {&c->alpha, sizeof(double) * BBMM_MAXP * BBMM_MAXC}, {&c->beta, sizeof(double) * BBMM_MAXP * BBMM_MAXC},
       {&c->resid, sizeof(double) * BBMM_MAXP * BBMM_MAXC}, {&c->st, sizeof(DevState)},
       {&c->tmpA, blk}, {&c->tmpB, blk},
@@ -484,7 +485,7 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
 
   hipStream_t s = c->stream;
   launch_fill_bytes0(s, c->st.p, sizeof(DevState));
-  launch_colmean(s, in->X, c->n, c->d, ptr<DevState>(c->st), ptr<double>(c->partial));
+  launch_colmean(s, in->X, c->n, c->d, ptr<DevState>(c->st), ptr<double>(c->partial), ptr<double>(c->gpartial));
   launch_prep_x(s, in->X, c->n, c->d, c->np, c->KK, c->hyp, ptr<DevState>(c->st), ptr<float>(c->Xa),
                 ptr<float>(c->Xb), ptr<float>(c->Xs), ptr<float>(c->X4), ptr<float>(c->sq));
   HIPCHK(c, hipGetLastError());
@@ -572,7 +573,7 @@ int bbmm_precond_solve(bbmm_ctx* c, const float* R, int64_t cc, float* Z) {
   launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
   launch_pack_rows(s, R, c->n, (int)cc, ld, ptr<double>(c->tmpA));
   launch_ur(s, 1, c->n, ld, (int)cc, c->kp, c->prob.noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V),
-            ptr<double>(c->U), ptr<double>(c->tmpA), ptr<float>(c->L), st, ptr<double>(c->partial), nb, 0,
+            ptr<double>(c->U), ptr<double>(c->tmpA), ptr<float>(c->L), st, ptr<double>(c->partial), ptr<double>(c->gpartial), nb, 0,
             ptr<double>(c->beta), ptr<double>(c->resid));
   launch_psolve_apply(s, c->n, ld, c->kp, c->prob.noise, ptr<double>(c->tmpA), ptr<float>(c->L),
                       ptr<double>(c->tmpB), st, nb);

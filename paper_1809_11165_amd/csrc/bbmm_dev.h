@@ -34,7 +34,7 @@ struct DevState {
   int iters_run;
   int status;       // BBMM_* code raised on the device (0 = ok)
   int rank;         // preconditioner rank actually built
-  unsigned counter[8];   // "last block done" tickets, one per kernel family
+  unsigned counter[8][40];   // arrival tickets per kernel family: [0] final, [1 + g] group g
 };
 
 struct HypArgs {
@@ -51,7 +51,8 @@ struct HypArgs {
 void launch_fill_f32(hipStream_t s, float* p, size_t count, float v);
 void launch_fill_f64(hipStream_t s, double* p, size_t count, double v);
 void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes);
-void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st, double* partial);
+void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st, double* partial,
+                    double* gpartial);
 void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, HypArgs hyp,
                    const DevState* st, float* Xa, float* Xb, float* Xs, float* X4, float* sq);
 void launch_pack_d4(hipStream_t s, const float* M, int n, int c, int np, int ld, double* D4);
@@ -68,15 +69,16 @@ void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* 
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
                     float* L, DevState* st, double* partial, int nblocks);
 void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
-                      double* partial, int nblocks);
+                      double* partial, double* gpartial, int nblocks);
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
                    int n, int t, int kp, int ld, double noise, const DevState* st, double* R);
 void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
-               double addD, const double* D4, double* V, DevState* st, double* partial, int nblocks,
-               int iter, double* alpha_hist);
+               double addD, const double* D4, double* V, DevState* st, double* partial,
+               double* gpartial, int nblocks, int iter, double* alpha_hist);
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
                const double* D4, const double* V, double* U, double* R, const float* L, DevState* st,
-               double* partial, int nblocks, int iter, double* beta_hist, double* resid_hist);
+               double* partial, double* gpartial, int nblocks, int iter, double* beta_hist,
+               double* resid_hist);
 void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,
                const float* L, double* D4, double* Z0, DevState* st, int nblocks);
 void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const double* R,
@@ -85,7 +87,7 @@ void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist
 void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,
                         double* eigvals, double* first_row);
 void launch_noise_terms(hipStream_t s, const double* U, const double* Z0, const float* y, int n, int ld,
-                        int t, int slot, DevState* st, double* partial, int nblocks);
+                        int t, int slot, DevState* st, double* partial, double* gpartial, int nblocks);
 
 // ---- launchers implemented in kernels_mm.hip ----------------------------------------------
 int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,

@@ -41,22 +41,56 @@ __device__ inline bool finite_d(double x) { return x == x && fabs(x) < 1.0e300; 
 // lane/16, 4 + lane/16, 8 + lane/16, 12 + lane/16, stored contiguously.
 __device__ inline int perm16(int q) { return (q & ~15) | ((q & 3) << 2) | ((q >> 2) & 3); }
 
-// tot[e] = sum over blocks of partial[b * stride + e], e < nentries, fixed order, all threads.
-__device__ inline void sum_partials(const double* __restrict__ partial, int nblocks, size_t stride,
-                                    int nentries, double* tot) {
-  for (int e = threadIdx.x; e < nentries; e += blockDim.x) {
+// Deterministic two-level sum of per-block partial vectors (the latency of a single block adding
+// hundreds of partial rows one after the other would dominate these small kernels).
+// Every block has written partial[blockIdx.x * stride + e], e < E.  Blocks are grouped by
+// RGROUP: the last block of a group to arrive adds its group's rows into gpartial[group], the
+// last group to finish adds the group rows into tot (LDS).  Returns true, in every thread, only
+// in that final block.  counters: 1 + number of groups tickets, all zero on entry, reset on exit.
+constexpr int RGROUP = 16;
+__device__ inline bool reduce_blocks(const double* __restrict__ partial, double* __restrict__ gpartial,
+                                     size_t stride, int E, unsigned* counters, double* tot) {
+  __shared__ int flag;
+  int nb = gridDim.x, ng = (nb + RGROUP - 1) / RGROUP;
+  int grp = blockIdx.x / RGROUP;
+  int gsize = min(RGROUP, nb - grp * RGROUP);
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) flag = (atomicAdd(&counters[1 + grp], 1u) == (unsigned)(gsize - 1));
+  __syncthreads();
+  if (!flag) return false;
+  __threadfence();
+  const double* base = partial + (size_t)grp * RGROUP * stride;
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    double v[RGROUP];
+#pragma unroll
+    for (int b = 0; b < RGROUP; ++b) v[b] = (b < gsize) ? base[(size_t)b * stride + e] : 0.0;
+    double s = 0.0;
+#pragma unroll
+    for (int b = 0; b < RGROUP; ++b) s += v[b];
+    gpartial[(size_t)grp * stride + e] = s;
+  }
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) flag = (atomicAdd(&counters[0], 1u) == (unsigned)(ng - 1));
+  __syncthreads();
+  if (!flag) return false;
+  __threadfence();
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
     double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    int b = 0;
-    for (; b + 3 < nblocks; b += 4) {
-      s0 += partial[(size_t)b * stride + e];
-      s1 += partial[(size_t)(b + 1) * stride + e];
-      s2 += partial[(size_t)(b + 2) * stride + e];
-      s3 += partial[(size_t)(b + 3) * stride + e];
+    int g = 0;
+    for (; g + 3 < ng; g += 4) {
+      s0 += gpartial[(size_t)g * stride + e];
+      s1 += gpartial[(size_t)(g + 1) * stride + e];
+      s2 += gpartial[(size_t)(g + 2) * stride + e];
+      s3 += gpartial[(size_t)(g + 3) * stride + e];
     }
-    for (; b < nblocks; ++b) s0 += partial[(size_t)b * stride + e];
+    for (; g < ng; ++g) s0 += gpartial[(size_t)g * stride + e];
     tot[e] = (s0 + s1) + (s2 + s3);
   }
   __syncthreads();
+  if ((int)threadIdx.x <= ng) counters[threadIdx.x] = 0u;
+  return true;
 }
 
 // ------------------------------------------------------------------ fills ----
@@ -81,7 +115,7 @@ __global__ void k_fill_u32(unsigned* p, size_t count) {
 // ------------------------------------------------------- input preparation ---
 // Column means of X (fp64): per-block partial sums, last block finishes.
 __global__ __launch_bounds__(VT) void k_colmean(const float* __restrict__ X, int n, int d,
-                                                 DevState* st, double* partial) {
+                                                 DevState* st, double* partial, double* gpartial) {
   __shared__ double red[VT];
   __shared__ double tot[BBMM_MAXD];
   // thread -> (row slot, dim): consecutive threads read consecutive floats of X
@@ -102,10 +136,8 @@ __global__ __launch_bounds__(VT) void k_colmean(const float* __restrict__ X, int
     if (threadIdx.x == 0) partial[(size_t)blockIdx.x * BBMM_MAXD + dd] = red[0];
     __syncthreads();
   }
-  if (!last_block_arrives(&st->counter[5])) return;
-  sum_partials(partial, gridDim.x, BBMM_MAXD, d, tot);
+  if (!reduce_blocks(partial, gpartial, BBMM_MAXD, d, st->counter[5], tot)) return;
   if ((int)threadIdx.x < d) st->xmean[threadIdx.x] = tot[threadIdx.x] / (double)n;
-  if (threadIdx.x == 0) st->counter[5] = 0u;
 }
 
 // Scaled, centred copies of X in the layouts the tile kernels read:
@@ -252,7 +284,7 @@ __device__ inline void finish_argmax(double bv, int bi, DevState* st, double* pa
     partial[2 * blockIdx.x] = bv;
     partial[2 * blockIdx.x + 1] = (double)bi;
   }
-  if (!last_block_arrives(&st->counter[0])) return;
+  if (!last_block_arrives(&st->counter[0][0])) return;
   double v = -1.0e300;
   int ix = 0x7fffffff;
   for (int b = threadIdx.x; b < (int)gridDim.x; b += blockDim.x) {
@@ -269,7 +301,7 @@ __device__ inline void finish_argmax(double bv, int bi, DevState* st, double* pa
   if (threadIdx.x == 0) {
     st->piv[slot] = oi;
     st->pivdmax[slot] = ov;
-    st->counter[0] = 0u;
+    st->counter[0][0] = 0u;
   }
 }
 
@@ -346,7 +378,8 @@ __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int
 // ---------------------------------------------- capacitance matrix, log|P| ---
 // C = sigma^2 I + L^T L (k x k, fp64), Cholesky factor G, log|P| = log|C| + (n-k) log sigma^2.
 __global__ __launch_bounds__(VT) void k_pre_setup(const float* __restrict__ L, int n, int kp,
-                                                   double noise, DevState* st, double* partial) {
+                                                   double noise, DevState* st, double* partial,
+                                                   double* gpartial) {
   int k = st->rank;
   int npairs = k * k;
   // each thread owns pairs e = tid, tid + VT, ... (at most 4 for k <= 32)
@@ -367,13 +400,12 @@ __global__ __launch_bounds__(VT) void k_pre_setup(const float* __restrict__ L, i
     int e = threadIdx.x + u * VT;
     if (e < npairs) partial[(size_t)blockIdx.x * (BBMM_MAXK * BBMM_MAXK) + e] = acc[u];
   }
-  if (!last_block_arrives(&st->counter[1])) return;
   __shared__ double C[BBMM_MAXK * BBMM_MAXK];
+  __shared__ double tot[BBMM_MAXK * BBMM_MAXK];
+  if (!reduce_blocks(partial, gpartial, BBMM_MAXK * BBMM_MAXK, npairs, st->counter[1], tot)) return;
   for (int e = threadIdx.x; e < npairs; e += VT) {
-    double s = 0.0;
-    for (int b = 0; b < (int)gridDim.x; ++b) s += partial[(size_t)b * (BBMM_MAXK * BBMM_MAXK) + e];
     int a = e / k, c = e % k;
-    C[a * BBMM_MAXK + c] = s + (a == c ? noise : 0.0);
+    C[a * BBMM_MAXK + c] = tot[e] + (a == c ? noise : 0.0);
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -399,7 +431,6 @@ __global__ __launch_bounds__(VT) void k_pre_setup(const float* __restrict__ L, i
     }
     st->logdetP = logdet + (double)(n - k) * log(noise);
     if (bad) st->status = 3;
-    st->counter[1] = 0u;
   }
   __syncthreads();
   for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += VT) {
@@ -441,8 +472,8 @@ __global__ void k_probes(const float* __restrict__ y, const float* __restrict__ 
 __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, int nsplit, int n, int np,
                                             int ld, int c, double scaleV, double addD,
                                             const double* __restrict__ D4, double* __restrict__ V,
-                                            DevState* st, double* partial, int iter,
-                                            double* alpha_hist) {
+                                            DevState* st, double* partial, double* gpartial,
+                                            int iter, double* alpha_hist) {
   __shared__ double red[VT];
   __shared__ double tot[BBMM_MAXC];
   if (st->done) return;
@@ -471,8 +502,7 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, int ns
     for (int r = 0; r < rpp; ++r) s += red[r * ld + q];
     partial[(size_t)blockIdx.x * ld + q] = s;
   }
-  if (!last_block_arrives(&st->counter[2])) return;
-  sum_partials(partial, gridDim.x, ld, ld, tot);
+  if (!reduce_blocks(partial, gpartial, ld, ld, st->counter[2], tot)) return;
   if ((int)threadIdx.x < ld) {
     int qq = threadIdx.x;
     double s = tot[qq];
@@ -483,7 +513,6 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, int ns
     st->m_valid[qq] += ok;
     alpha_hist[(size_t)iter * BBMM_MAXC + qq] = alpha;
   }
-  if (threadIdx.x == 0) st->counter[2] = 0u;
 }
 
 // (2) U += alpha D, R -= alpha V, then sums |r|^2 and L^T R per column; the last block
@@ -495,8 +524,8 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
                                             const double* __restrict__ D4,
                                             const double* __restrict__ V, double* __restrict__ U,
                                             double* __restrict__ R, const float* __restrict__ L,
-                                            DevState* st, double* partial, int iter,
-                                            double* beta_hist, double* resid_hist) {
+                                            DevState* st, double* partial, double* gpartial,
+                                            int iter, double* beta_hist, double* resid_hist) {
   __shared__ double red[VT];
   __shared__ double tot[(BBMM_MAXK + 1) * BBMM_MAXC];
   __shared__ double Gs[BBMM_MAXK * BBMM_MAXK];
@@ -536,9 +565,9 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
     }
     __syncthreads();
   }
-  if (!last_block_arrives(&st->counter[3])) return;
+  if (!reduce_blocks(partial, gpartial, pstride, (KP + 1) * ld, st->counter[3], tot)) return;
   for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += VT) Gs[e] = st->G[e];
-  sum_partials(partial, gridDim.x, pstride, (KP + 1) * ld, tot);
+  __syncthreads();
   if ((int)threadIdx.x < ld) {
     int qq = threadIdx.x;
     int k = st->rank;
@@ -594,7 +623,6 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
         if (all) st->done = 1;
       }
     }
-    st->counter[3] = 0u;
   }
 }
 
@@ -739,12 +767,12 @@ __global__ __launch_bounds__(64) void k_slq(const double* __restrict__ alpha_his
     st->slq_terms[blockIdx.x] = term;
     if (bad) st->status = 4;
   }
-  if (!last_block_arrives(&st->counter[4])) return;
+  if (!last_block_arrives(&st->counter[4][0])) return;
   if (threadIdx.x == 0) {
     double s = 0.0;
     for (int i = 0; i < t; ++i) s += st->slq_terms[i];
     st->slq_mean = s / (double)t;
-    st->counter[4] = 0u;
+    st->counter[4][0] = 0u;
   }
 }
 
@@ -770,7 +798,8 @@ __global__ __launch_bounds__(64) void k_tridiag_eig(const double* __restrict__ d
 __global__ __launch_bounds__(VT) void k_noise_terms(const double* __restrict__ U,
                                                      const double* __restrict__ Z0,
                                                      const float* __restrict__ y, int n, int ld,
-                                                     int t, int slot, DevState* st, double* partial) {
+                                                     int t, int slot, DevState* st, double* partial,
+                                                     double* gpartial) {
   __shared__ double r1[VT], r2[VT], r3[VT];
   __shared__ double tot[4];
   double tr = 0.0, qd = 0.0, yu = 0.0;
@@ -801,13 +830,11 @@ __global__ __launch_bounds__(VT) void k_noise_terms(const double* __restrict__ U
     partial[(size_t)blockIdx.x * 4 + 1] = r2[0];
     partial[(size_t)blockIdx.x * 4 + 2] = r3[0];
   }
-  if (!last_block_arrives(&st->counter[6])) return;
-  sum_partials(partial, gridDim.x, 4, 3, tot);
+  if (!reduce_blocks(partial, gpartial, 4, 3, st->counter[6], tot)) return;
   if (threadIdx.x == 0) {
     st->dk_out[2 * slot] = tot[0] / (double)t;
     st->dk_out[2 * slot + 1] = tot[1];
     st->dk_out[2 * slot + 2] = tot[2];
-    st->counter[6] = 0u;
   }
 }
 
@@ -838,11 +865,12 @@ void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes) {
   k_fill_u32<<<nb, 256, 0, s>>>((unsigned*)p, count);
 }
 
-void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st, double* partial) {
+void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st, double* partial,
+                    double* gpartial) {
   // grid stride must be a multiple of d: use nb blocks with nb * 256 % d == 0
   int nb = 64;
   while (((size_t)nb * VT) % d != 0) ++nb;      // d <= 64, terminates within d steps
-  k_colmean<<<nb, VT, 0, s>>>(X, n, d, st, partial);
+  k_colmean<<<nb, VT, 0, s>>>(X, n, d, st, partial, gpartial);
 }
 
 void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, HypArgs hyp,
@@ -893,9 +921,9 @@ void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs
 }
 
 void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
-                      double* partial, int nblocks) {
+                      double* partial, double* gpartial, int nblocks) {
   (void)k;
-  k_pre_setup<<<nblocks, VT, 0, s>>>(L, n, kp, noise, st, partial);
+  k_pre_setup<<<nblocks, VT, 0, s>>>(L, n, kp, noise, st, partial, gpartial);
 }
 
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
@@ -904,10 +932,10 @@ void launch_probes(hipStream_t s, const float* y, const float* E1, const float* 
 }
 
 void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
-               double addD, const double* D4, double* V, DevState* st, double* partial, int nblocks,
-               int iter, double* alpha_hist) {
-  k_dv<<<nblocks, VT, 0, s>>>(Vp, nsplit, n, np, ld, c, scaleV, addD, D4, V, st, partial, iter,
-                              alpha_hist);
+               double addD, const double* D4, double* V, DevState* st, double* partial,
+               double* gpartial, int nblocks, int iter, double* alpha_hist) {
+  k_dv<<<nblocks, VT, 0, s>>>(Vp, nsplit, n, np, ld, c, scaleV, addD, D4, V, st, partial, gpartial,
+                              iter, alpha_hist);
 }
 
 #define DISPATCH_KP(KERNEL, kp, grid, ...)                                  \
@@ -921,9 +949,10 @@ void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int l
 
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
                const double* D4, const double* V, double* U, double* R, const float* L, DevState* st,
-               double* partial, int nblocks, int iter, double* beta_hist, double* resid_hist) {
-  DISPATCH_KP(k_ur, kp, nblocks, init, n, ld, c, noise, tol, D4, V, U, R, L, st, partial, iter,
-              beta_hist, resid_hist);
+               double* partial, double* gpartial, int nblocks, int iter, double* beta_hist,
+               double* resid_hist) {
+  DISPATCH_KP(k_ur, kp, nblocks, init, n, ld, c, noise, tol, D4, V, U, R, L, st, partial, gpartial,
+              iter, beta_hist, resid_hist);
 }
 
 void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,
@@ -946,6 +975,6 @@ void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, in
 }
 
 void launch_noise_terms(hipStream_t s, const double* U, const double* Z0, const float* y, int n, int ld,
-                        int t, int slot, DevState* st, double* partial, int nblocks) {
-  k_noise_terms<<<nblocks, VT, 0, s>>>(U, Z0, y, n, ld, t, slot, st, partial);
+                        int t, int slot, DevState* st, double* partial, double* gpartial, int nblocks) {
+  k_noise_terms<<<nblocks, VT, 0, s>>>(U, Z0, y, n, ld, t, slot, st, partial, gpartial);
 }

@@ -1,0 +1,68 @@
+"""Writes the stored oracle results used by the full-size GPU parity tests.
+
+Calls ONLY the fp64 oracle and the seeded input generators (never the HIP path):
+    python tests/golden/make_golden.py [case ...]
+Each case is one of the benchmark configurations at a size where running the oracle inside the
+GPU test session would take minutes.  Output: tests/golden/<case>.json (text).
+"""
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
+sys.path.insert(0, ROOT)
+
+from oracle import bbmm_oracle as O                      # noqa: E402
+from paper_1809_11165_amd import inputs                  # noqa: E402
+
+N_SAMPLE = 512
+
+CASES = {
+    # name: (config, n, overrides)
+    "cfg2_n10000": (2, 10000, {}),
+    "cfg3_n50000": (3, 50000, {}),
+    "cfg4_sub_n20000": (4, 20000, {}),
+}
+
+
+def sample_rows(n: int, cfg: int) -> np.ndarray:
+    rng = np.random.Generator(np.random.Philox(inputs.BASE_SEED + 1000 + cfg))
+    return np.sort(rng.choice(n, size=min(N_SAMPLE, n), replace=False))
+
+
+def run(name: str):
+    cfg, n, kw = CASES[name]
+    w = inputs.make(cfg, n=n, **kw)
+    t0 = time.time()
+    res = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
+                           w.k, w.iters, tol=w.tol)
+    rows = sample_rows(n, cfg)
+    out = {
+        "source": "oracle/bbmm_oracle.py bbmm_inference on paper_1809_11165_amd.inputs.make(%d, n=%d)" % (cfg, n),
+        "config": cfg, "n": n, "d": w.d, "t": w.t, "k": w.k, "iters_cap": w.iters, "tol": w.tol,
+        "iters_run": int(res.mbcg.iters_run),
+        "pivots": res.pivots.tolist(), "pivot_dmax": res.pivot_dmax.tolist(),
+        "logdet": res.logdet, "logdet_precond": res.logdet_precond, "yKinvy": res.yKinvy,
+        "nlml": res.nlml, "trace": res.trace.tolist(), "quad": res.quad.tolist(),
+        "grad": res.grad.tolist(), "slq_terms": res.slq_terms.tolist(),
+        "alpha": res.mbcg.alpha.tolist(), "beta": res.mbcg.beta.tolist(),
+        "resid": res.mbcg.resid.tolist(), "rho0": res.mbcg.rho0.tolist(),
+        "sample_rows": rows.tolist(),
+        "U_sample": res.U[rows].tolist(),
+        "U_colnorm": np.linalg.norm(res.U, axis=0).tolist(),
+        "B_sample": res.B[rows].tolist(),
+        "seconds": time.time() - t0,
+    }
+    path = os.path.join(HERE, name + ".json")
+    with open(path, "w") as f:
+        json.dump(out, f)
+    print("wrote", path, "in %.0f s" % out["seconds"], flush=True)
+
+
+if __name__ == "__main__":
+    for nm in (sys.argv[1:] or list(CASES)):
+        run(nm)
