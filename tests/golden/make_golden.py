@@ -19,7 +19,7 @@ sys.path.insert(0, ROOT)
 from oracle import bbmm_oracle as O                      # noqa: E402
 from paper_1809_11165_amd import inputs                  # noqa: E402
 
-N_SAMPLE = 512
+N_SAMPLE = 128
 
 CASES = {
     # name: (config, n, overrides)
@@ -54,7 +54,6 @@ def run(name: str):
         "sample_rows": rows.tolist(),
         "U_sample": res.U[rows].tolist(),
         "U_colnorm": np.linalg.norm(res.U, axis=0).tolist(),
-        "B_sample": res.B[rows].tolist(),
         "seconds": time.time() - t0,
     }
     path = os.path.join(HERE, name + ".json")
