@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
 FP64_VALU_PEAK_TFLOPS = 78.6   # MI355X fp64 vector, published
+# HBM bytes per k_mm_mat launch at n = 50000 from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by a
+# 1 GiB copy (profiles/k_mm_mat_cfg3_n50000_hbm_counters.txt); only valid for that workload.
+MEASURED_TRAFFIC_MAT_N50000 = 10.244e9
 
 
 def cpu_baseline(n_sample: int, n_full: int):
@@ -55,6 +58,8 @@ def main():
     ap.add_argument("--n", type=int, default=50000)
     ap.add_argument("--cpu-sample", type=int, default=5000)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)")
@@ -86,13 +91,20 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     mm_ms = float(np.mean(mm_avgs))
 
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     n, c, d = w.n, w.t + 1, w.d
     if mode == inputs.MATERIALISED:
         # algorithmic bytes of one K_hat.D launch: K_hat once (4 n^2) + block in and out (8 n c)
         alg_bytes = 4.0 * n * n + 8.0 * n * c
         achieved = alg_bytes / (mm_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": MEASURED_TRAFFIC_MAT_N50000 if n == 50000 else None,
                     "kernel": "k_mm_mat", "avg_launch_ms": mm_ms, "launches": mm_launches}
     else:
         # algorithmic flops per pair: 2 d (distance contraction) + 2 c (multiply by the block)

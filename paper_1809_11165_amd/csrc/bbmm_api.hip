@@ -102,6 +102,13 @@ int vec_blocks(int n, int ld) {
   return nb;
 }
 
+// blocks of the 1024-thread update kernel: at least ~4 rows per thread, at most 128 partial rows
+int ur_blocks(int n, int ld) {
+  int rpp = 1024 / ld;
+  int nb = (n + rpp * 4 - 1) / (rpp * 4);
+  return std::max(1, std::min(nb, 128));
+}
+
 int default_split(int np, int cols_per_wg, int want_wgs) {
   int strips = (np + cols_per_wg - 1) / cols_per_wg;
   int s = (want_wgs + strips - 1) / strips;
@@ -198,10 +205,12 @@ int stage_pivchol(bbmm_ctx* c) {
   hipStream_t s = c->stream;
   int nb = vec_blocks(c->n, 16);
   if (c->kp > 0) launch_fill_f32(s, ptr<float>(c->L), (size_t)c->np * c->kp, 0.f);
-  launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), ptr<DevState>(c->st), ptr<double>(c->partial), nb);
+  // pivot candidates alternate between two buffers (a step reads one and writes the other)
+  double* arg[2] = {ptr<double>(c->partial), ptr<double>(c->partial) + 2 * kMaxVecBlocks};
+  launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), ptr<DevState>(c->st), arg[0], nb);
   for (int m = 0; m < c->k; ++m)
     launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<float>(c->L),
-                   ptr<DevState>(c->st), ptr<double>(c->partial), nb);
+                   ptr<DevState>(c->st), arg[m & 1], arg[(m + 1) & 1], nb);
   c->chol_done = true;
   c->pre_done = false;
   return BBMM_OK;
@@ -232,9 +241,12 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
   // done / iters_run live next to each other at the end of DevState
   launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
   double noise = c->prob.noise;
+  int nb_ur = ur_blocks(c->n, ld);
+  double* pdv = ptr<double>(c->gpartial);
+  double* pur = ptr<double>(c->partial);
   launch_ur(s, 1, c->n, ld, cc, c->kp, noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V), ptr<double>(c->U),
-            ptr<double>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), ptr<double>(c->gpartial), nb, 0, ptr<double>(c->beta),
-            ptr<double>(c->resid));
+            ptr<double>(c->R), ptr<float>(c->L), st, pdv, nb, pur, nb_ur, 0, ptr<double>(c->alpha),
+            ptr<double>(c->beta), ptr<double>(c->resid));
   launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<float>(c->L), ptr<double>(c->D4),
             ptr<double>(c->Z0), st, nb);
   if (c->time_mm) {
@@ -255,11 +267,11 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
       HIPCHK(c, hipEventRecord(c->ev[2 * j + 1], s));
       c->ev_iters = j + 1;
     }
-    launch_dv(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, cc, scaleV, addD, ptr<double>(c->D4),
-              ptr<double>(c->V), st, ptr<double>(c->partial), ptr<double>(c->gpartial), nb, j, ptr<double>(c->alpha));
+    launch_dv(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, scaleV, addD, ptr<double>(c->D4),
+              ptr<double>(c->V), st, pdv, nb);
     launch_ur(s, 0, c->n, ld, cc, c->kp, noise, c->prob.tol, ptr<double>(c->D4), ptr<double>(c->V),
-              ptr<double>(c->U), ptr<double>(c->R), ptr<float>(c->L), st, ptr<double>(c->partial), ptr<double>(c->gpartial), nb, j,
-              ptr<double>(c->beta), ptr<double>(c->resid));
+              ptr<double>(c->U), ptr<double>(c->R), ptr<float>(c->L), st, pdv, nb, pur, nb_ur, j,
+              ptr<double>(c->alpha), ptr<double>(c->beta), ptr<double>(c->resid));
     launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<float>(c->L), ptr<double>(c->D4),
               ptr<double>(c->Z0), st, nb);
   }
@@ -573,8 +585,9 @@ int bbmm_precond_solve(bbmm_ctx* c, const float* R, int64_t cc, float* Z) {
   launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
   launch_pack_rows(s, R, c->n, (int)cc, ld, ptr<double>(c->tmpA));
   launch_ur(s, 1, c->n, ld, (int)cc, c->kp, c->prob.noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V),
-            ptr<double>(c->U), ptr<double>(c->tmpA), ptr<float>(c->L), st, ptr<double>(c->partial), ptr<double>(c->gpartial), nb, 0,
-            ptr<double>(c->beta), ptr<double>(c->resid));
+            ptr<double>(c->U), ptr<double>(c->tmpA), ptr<float>(c->L), st, ptr<double>(c->gpartial), nb,
+            ptr<double>(c->partial), ur_blocks(c->n, ld), 0, ptr<double>(c->alpha), ptr<double>(c->beta),
+            ptr<double>(c->resid));
   launch_psolve_apply(s, c->n, ld, c->kp, c->prob.noise, ptr<double>(c->tmpA), ptr<float>(c->L),
                       ptr<double>(c->tmpB), st, nb);
   launch_unpack_rows(s, ptr<double>(c->tmpB), ld, c->n, (int)cc, Z);

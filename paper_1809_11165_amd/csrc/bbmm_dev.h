@@ -19,6 +19,7 @@ struct DevState {
   double bnorm[BBMM_MAXC];      // |b| per column
   double alpha_cur[BBMM_MAXC];
   double beta_cur[BBMM_MAXC];
+  double dvtot[BBMM_MAXC];      // d^T K_hat d of the current iteration, per column
   double Qt[BBMM_MAXK * BBMM_MAXC];   // C^{-1} L^T R, [m][q]
   double G[BBMM_MAXK * BBMM_MAXK];    // lower Cholesky factor of C = sigma^2 I + L^T L, [a][b]
   double logdetP;
@@ -64,21 +65,21 @@ void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0,
                        int ncols, float* dst);
 void launch_vreduce(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
                     double addD, const double* D4, double* V);
-void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* partial,
+void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
                     int nblocks);
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
-                    float* L, DevState* st, double* partial, int nblocks);
+                    float* L, DevState* st, const double* arg_in, double* arg_out, int nblocks);
 void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
                       double* partial, double* gpartial, int nblocks);
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
                    int n, int t, int kp, int ld, double noise, const DevState* st, double* R);
-void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
-               double addD, const double* D4, double* V, DevState* st, double* partial,
-               double* gpartial, int nblocks, int iter, double* alpha_hist);
+void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
+               double addD, const double* D4, double* V, const DevState* st, double* partial_dv,
+               int nblocks);
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
                const double* D4, const double* V, double* U, double* R, const float* L, DevState* st,
-               double* partial, double* gpartial, int nblocks, int iter, double* beta_hist,
-               double* resid_hist);
+               const double* partial_dv, int nb_dv, double* partial, int nb_ur, int iter,
+               double* alpha_hist, double* beta_hist, double* resid_hist);
 void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,
                const float* L, double* D4, double* Z0, DevState* st, int nblocks);
 void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const double* R,

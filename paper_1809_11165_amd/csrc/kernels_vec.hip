@@ -277,37 +277,28 @@ __device__ inline void block_argmax(double v, int idx, double* sval, int* sidx, 
   __syncthreads();
 }
 
-// partial layout for the argmax: partial[2*b] = value, partial[2*b+1] = index (as double)
-__device__ inline void finish_argmax(double bv, int bi, DevState* st, double* partial, int slot,
-                                     double* sval, int* sidx) {
-  if (threadIdx.x == 0) {
-    partial[2 * blockIdx.x] = bv;
-    partial[2 * blockIdx.x + 1] = (double)bi;
-  }
-  if (!last_block_arrives(&st->counter[0][0])) return;
+// Argmax across blocks without in-kernel communication (a device-wide fence costs tens of
+// microseconds on a multi-die GPU): every block writes (value, index) to arg[2*b], arg[2*b+1];
+// the NEXT kernel starts with every block reducing those pairs, which is cheap and gives all
+// blocks the same pivot.  Two buffers alternate so that a step never overwrites what it reads.
+__device__ inline void reduce_argmax(const double* __restrict__ arg, int npart, double* sval,
+                                     int* sidx, double* outv, int* outi) {
   double v = -1.0e300;
   int ix = 0x7fffffff;
-  for (int b = threadIdx.x; b < (int)gridDim.x; b += blockDim.x) {
-    double v2 = partial[2 * b];
-    int i2 = (int)partial[2 * b + 1];
+  for (int b = threadIdx.x; b < npart; b += blockDim.x) {
+    double v2 = arg[2 * b];
+    int i2 = (int)arg[2 * b + 1];
     if (v2 > v || (v2 == v && i2 < ix)) {
       v = v2;
       ix = i2;
     }
   }
-  double ov;
-  int oi;
-  block_argmax(v, ix, sval, sidx, &ov, &oi);
-  if (threadIdx.x == 0) {
-    st->piv[slot] = oi;
-    st->pivdmax[slot] = ov;
-    st->counter[0][0] = 0u;
-  }
+  block_argmax(v, ix, sval, sidx, outv, outi);
 }
 
-// delta = diag(K_XX) = outputscale (stationary kernels); first pivot = argmax.
+// delta = diag(K_XX) = outputscale (stationary kernels); block argmax candidates for pivot 0.
 __global__ __launch_bounds__(VT) void k_pc_init(int n, HypArgs hyp, double* __restrict__ delta,
-                                                 DevState* st, double* partial) {
+                                                 DevState* st, double* __restrict__ arg_out) {
   __shared__ double sval[VT];
   __shared__ int sidx[VT];
   double bv = -1.0e300;
@@ -323,23 +314,41 @@ __global__ __launch_bounds__(VT) void k_pc_init(int n, HypArgs hyp, double* __re
   double ov;
   int oi;
   block_argmax(bv, bi, sval, sidx, &ov, &oi);
-  if (blockIdx.x == 0 && threadIdx.x == 0) st->rank = 0;
-  finish_argmax(ov, oi, st, partial, 0, sval, sidx);
+  if (threadIdx.x == 0) {
+    arg_out[2 * blockIdx.x] = ov;
+    arg_out[2 * blockIdx.x + 1] = (double)oi;
+    if (blockIdx.x == 0) st->rank = 0;
+  }
 }
 
-// Step m of the greedy factorisation: column m of L from row piv[m] of K_XX, residual
-// diagonal update, and the argmax that selects piv[m+1].  Picked rows carry delta = -1.
+// Step m of the greedy factorisation: pivot m = argmax of the candidates left by the previous
+// kernel, column m of L from row piv of K_XX, residual diagonal update, and the candidates for
+// pivot m+1.  Picked rows carry delta = -1.  If the largest residual diagonal has vanished the
+// step (and every later one, which sees the same candidates) does nothing.
 __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int n, int m, int kp,
                                                  HypArgs hyp, double* __restrict__ delta,
                                                  float* __restrict__ L, DevState* st,
-                                                 double* partial, double stop_thresh) {
+                                                 const double* __restrict__ arg_in,
+                                                 double* __restrict__ arg_out, double stop_thresh) {
   __shared__ double sval[VT];
   __shared__ int sidx[VT];
   __shared__ double lpiv[BBMM_MAXK];
-  if (st->rank < m) return;       // factorisation stopped early: remaining columns stay zero
-  int piv = st->piv[m];
-  double dpiv = st->pivdmax[m];
-  if (!(dpiv > stop_thresh)) return;
+  double dpiv;
+  int piv;
+  reduce_argmax(arg_in, gridDim.x, sval, sidx, &dpiv, &piv);
+  if (!(dpiv > stop_thresh)) {
+    // keep the candidates alive for the remaining steps
+    if (threadIdx.x == 0) {
+      arg_out[2 * blockIdx.x] = arg_in[2 * blockIdx.x];
+      arg_out[2 * blockIdx.x + 1] = arg_in[2 * blockIdx.x + 1];
+    }
+    return;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    st->piv[m] = piv;
+    st->pivdmax[m] = dpiv;
+    st->rank = m + 1;
+  }
   double root = sqrt(dpiv);
   if ((int)threadIdx.x < m) lpiv[threadIdx.x] = (double)L[(size_t)piv * kp + threadIdx.x];
   __syncthreads();
@@ -371,8 +380,10 @@ __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int
   double ov;
   int oi;
   block_argmax(bv, bi, sval, sidx, &ov, &oi);
-  if (blockIdx.x == 0 && threadIdx.x == 0) st->rank = m + 1;
-  finish_argmax(ov, oi, st, partial, m + 1, sval, sidx);
+  if (threadIdx.x == 0) {
+    arg_out[2 * blockIdx.x] = ov;
+    arg_out[2 * blockIdx.x + 1] = (double)oi;
+  }
 }
 
 // ---------------------------------------------- capacitance matrix, log|P| ---
@@ -467,15 +478,18 @@ __global__ void k_probes(const float* __restrict__ y, const float* __restrict__ 
 // comparison with an fp64 reference meaningless.  They are O(n c) and cost ~nothing next to
 // the O(n^2) product.
 //
-// (1) after the product: V = scaleV * sum_s Vp[s] + addD * D,  d^T v per column,
-//     then (last block) alpha_j = rho / (d^T v) with the freeze guard.
+// Reductions over rows are split over kernels instead of being finished inside one kernel:
+// a kernel writes per-block fp64 partial sums, the NEXT kernel (or a one-block finishing kernel)
+// adds them in a fixed order.  Kernel boundaries give the needed ordering for free, whereas a
+// device-wide fence inside a kernel was measured at ~60 us here.
+//
+// (1) after the product: V = scaleV * sum_s Vp[s] + addD * D, and per-block partial d^T v.
 __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, int nsplit, int n, int np,
-                                            int ld, int c, double scaleV, double addD,
+                                            int ld, double scaleV, double addD,
                                             const double* __restrict__ D4, double* __restrict__ V,
-                                            DevState* st, double* partial, double* gpartial,
-                                            int iter, double* alpha_hist) {
+                                            const DevState* __restrict__ st,
+                                            double* __restrict__ partial_dv) {
   __shared__ double red[VT];
-  __shared__ double tot[BBMM_MAXC];
   if (st->done) return;
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
   int pq = perm16(q);
@@ -500,38 +514,53 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, int ns
   if (rl == 0) {
     double s = 0.0;
     for (int r = 0; r < rpp; ++r) s += red[r * ld + q];
-    partial[(size_t)blockIdx.x * ld + q] = s;
-  }
-  if (!reduce_blocks(partial, gpartial, ld, ld, st->counter[2], tot)) return;
-  if ((int)threadIdx.x < ld) {
-    int qq = threadIdx.x;
-    double s = tot[qq];
-    int ok = st->active[qq] && finite_d(s) && s > 0.0 && qq < c;
-    double alpha = ok ? st->rho[qq] / s : 0.0;
-    st->active[qq] = ok;
-    st->alpha_cur[qq] = alpha;
-    st->m_valid[qq] += ok;
-    alpha_hist[(size_t)iter * BBMM_MAXC + qq] = alpha;
+    partial_dv[(size_t)blockIdx.x * ld + q] = s;
   }
 }
 
-// (2) U += alpha D, R -= alpha V, then sums |r|^2 and L^T R per column; the last block
-//     solves the k x k system, forms rho' = (|r|^2 - (L^T r)^T C^{-1} (L^T r)) / sigma^2
-//     (which equals r^T P^{-1} r by the Woodbury formula), beta_j, the residual history
-//     and the stop flag.  init != 0: no update, just the sums for R = B (gives Z_0, rho_0).
+constexpr int UT = 1024;      // threads of the update kernel
+constexpr int URB = 5;        // quantities reduced per barrier pair
+
+// alpha_j for column q from the d^T v total, with the freeze guard (same expression in
+// k_ur_main, which needs the value, and in k_ur_fin, which records it).
+__device__ inline double alpha_of(const DevState* st, int q, int c, double dv, int* ok_out) {
+  int ok = st->active[q] && finite_d(dv) && dv > 0.0 && q < c;
+  *ok_out = ok;
+  return ok ? st->rho[q] / dv : 0.0;
+}
+
+// (2a) every block first adds the d^T v partials of k_dv (same order in every block), forms
+//      alpha_j, then U += alpha D, R -= alpha V and its partial sums of |r|^2 and L^T R.
+//      init != 0: no update, just the sums for R = B (gives Z_0, rho_0).
 template <int KP>
-__global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, double noise, double tol,
-                                            const double* __restrict__ D4,
-                                            const double* __restrict__ V, double* __restrict__ U,
-                                            double* __restrict__ R, const float* __restrict__ L,
-                                            DevState* st, double* partial, double* gpartial,
-                                            int iter, double* beta_hist, double* resid_hist) {
-  __shared__ double red[VT];
-  __shared__ double tot[(BBMM_MAXK + 1) * BBMM_MAXC];
-  __shared__ double Gs[BBMM_MAXK * BBMM_MAXK];
+__global__ __launch_bounds__(UT) void k_ur_main(int init, int n, int ld, int c,
+                                                 const double* __restrict__ D4,
+                                                 const double* __restrict__ V,
+                                                 double* __restrict__ U, double* __restrict__ R,
+                                                 const float* __restrict__ L, DevState* st,
+                                                 const double* __restrict__ partial_dv, int nb_dv,
+                                                 double* __restrict__ partial) {
+  __shared__ double red[UT];
+  __shared__ double dvtot[BBMM_MAXC];
+  __shared__ double stage[URB][UT / 64][BBMM_MAXC];
   if (st->done) return;
-  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
-  double alpha = init ? 0.0 : st->alpha_cur[q];
+  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = UT / ld;
+  double alpha = 0.0;
+  if (!init) {
+    double s = 0.0;
+    for (int b = rl; b < nb_dv; b += rpp) s += partial_dv[(size_t)b * ld + q];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (rl == 0) {
+      double t = 0.0;
+      for (int r = 0; r < rpp; ++r) t += red[r * ld + q];
+      dvtot[q] = t;
+      if (blockIdx.x == 0) st->dvtot[q] = t;
+    }
+    __syncthreads();
+    int ok;
+    alpha = alpha_of(st, q, c, dvtot[q], &ok);
+  }
   double rr = 0.0;
   double lr[KP > 0 ? KP : 1];
 #pragma unroll
@@ -551,45 +580,92 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
 #pragma unroll
     for (int m = 0; m < KP; ++m) lr[m] += (double)L[(size_t)i * KP + m] * rd;
   }
-  // block reduction over the rows handled by this block, one quantity at a time
+  // in-block reduction: rows held by one wave through shuffles, waves through LDS
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   size_t pstride = (size_t)(KP + 1) * ld;
 #pragma unroll
-  for (int e = 0; e <= KP; ++e) {
-    double val = (e == 0) ? rr : lr[e > 0 ? e - 1 : 0];
-    red[threadIdx.x] = val;
+  for (int e0 = 0; e0 <= KP; e0 += URB) {
+#pragma unroll
+    for (int eb = 0; eb < URB; ++eb) {
+      int e = e0 + eb;
+      if (e <= KP) {
+        double v = (e == 0) ? rr : lr[e > 0 ? e - 1 : 0];
+        v += __shfl_xor(v, 32, 64);
+        if (ld == 16) v += __shfl_xor(v, 16, 64);
+        if (lane < ld) stage[eb][wave][lane] = v;
+      }
+    }
     __syncthreads();
-    if (rl == 0) {
-      double s = 0.0;
-      for (int r = 0; r < rpp; ++r) s += red[r * ld + q];
-      partial[(size_t)blockIdx.x * pstride + (size_t)e * ld + q] = s;
+    if ((int)threadIdx.x < URB * ld) {
+      int eb = threadIdx.x / ld, qq = threadIdx.x % ld;
+      int e = e0 + eb;
+      if (e <= KP) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < UT / 64; ++w) s += stage[eb][w][qq];
+        partial[(size_t)blockIdx.x * pstride + (size_t)e * ld + qq] = s;
+      }
     }
     __syncthreads();
   }
-  if (!reduce_blocks(partial, gpartial, pstride, (KP + 1) * ld, st->counter[3], tot)) return;
-  for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += VT) Gs[e] = st->G[e];
+}
+
+// (2b) one block: totals of |r|^2 and L^T R, the k x k solves (one wave per column, lanes =
+//      rows of the triangular systems), rho' = (|r|^2 - (L^T r)^T C^{-1} (L^T r)) / sigma^2
+//      (= r^T P^{-1} r by the Woodbury formula), alpha/beta bookkeeping, residual history, stop flag.
+template <int KP>
+__global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double noise, double tol,
+                                                DevState* st, const double* __restrict__ partial,
+                                                int nb, int iter, double* alpha_hist,
+                                                double* beta_hist, double* resid_hist) {
+  __shared__ double tot[(BBMM_MAXK + 1) * BBMM_MAXC];
+  __shared__ double Gs[BBMM_MAXK * BBMM_MAXK];
+  __shared__ double quad_s[BBMM_MAXC];
+  __shared__ double rel_s[BBMM_MAXC];
+  if (st->done) return;
+  size_t pstride = (size_t)(KP + 1) * ld;
+  int E = (KP + 1) * ld;
+  for (int e = threadIdx.x; e < E; e += UT) {
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int b = 0;
+    for (; b + 3 < nb; b += 4) {
+      s0 += partial[(size_t)b * pstride + e];
+      s1 += partial[(size_t)(b + 1) * pstride + e];
+      s2 += partial[(size_t)(b + 2) * pstride + e];
+      s3 += partial[(size_t)(b + 3) * pstride + e];
+    }
+    for (; b < nb; ++b) s0 += partial[(size_t)b * pstride + e];
+    tot[e] = (s0 + s1) + (s2 + s3);
+  }
+  for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += UT) Gs[e] = st->G[e];
+  __syncthreads();
+  int k = st->rank;
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int qq = wave; qq < ld; qq += UT / 64) {
+    // lane a holds component a of L^T r; forward substitution G w = y, quad = w^T w,
+    // back substitution G^T x = w
+    double y = (lane < k) ? tot[(size_t)(1 + lane) * ld + qq] : 0.0;
+    for (int a = 0; a < k; ++a) {
+      double wa = __shfl(y, a, 64) / Gs[a * BBMM_MAXK + a];
+      if (lane == a) y = wa;
+      else if (lane > a && lane < k) y -= Gs[lane * BBMM_MAXK + a] * wa;
+    }
+    double sq = (lane < k) ? y * y : 0.0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
+    for (int a = k - 1; a >= 0; --a) {
+      double xa = __shfl(y, a, 64) / Gs[a * BBMM_MAXK + a];
+      if (lane == a) y = xa;
+      else if (lane < a) y -= Gs[a * BBMM_MAXK + lane] * xa;
+    }
+    if (lane < BBMM_MAXK) st->Qt[lane * BBMM_MAXC + qq] = (lane < k) ? y : 0.0;
+    if (lane == 0) quad_s[qq] = sq;
+  }
   __syncthreads();
   if ((int)threadIdx.x < ld) {
     int qq = threadIdx.x;
-    int k = st->rank;
     double rrq = tot[qq];
-    // forward substitution G w = L^T r; quad = w^T w; back substitution G^T x = w
-    double quad = 0.0;
-    for (int a = 0; a < k; ++a) {
-      double s = tot[(size_t)(1 + a) * ld + qq];
-      for (int j = 0; j < a; ++j) s -= Gs[a * BBMM_MAXK + j] * tot[(size_t)(1 + j) * ld + qq];
-      s /= Gs[a * BBMM_MAXK + a];
-      tot[(size_t)(1 + a) * ld + qq] = s;
-      quad += s * s;
-    }
-    for (int a = k - 1; a >= 0; --a) {
-      double s = tot[(size_t)(1 + a) * ld + qq];
-      for (int j = a + 1; j < k; ++j) s -= Gs[j * BBMM_MAXK + a] * tot[(size_t)(1 + j) * ld + qq];
-      s /= Gs[a * BBMM_MAXK + a];
-      tot[(size_t)(1 + a) * ld + qq] = s;
-    }
-    for (int a = 0; a < BBMM_MAXK; ++a)
-      st->Qt[a * BBMM_MAXC + qq] = (a < k) ? tot[(size_t)(1 + a) * ld + qq] : 0.0;
-    double rho_new = (rrq - quad) / noise;
+    double rho_new = (rrq - quad_s[qq]) / noise;
     if (init) {
       int ok = finite_d(rho_new) && rho_new > 0.0 && qq < c;
       st->rho[qq] = rho_new;
@@ -600,7 +676,12 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
       st->beta_cur[qq] = 0.0;
       st->alpha_cur[qq] = 0.0;
     } else {
-      int ok2 = st->active[qq] && finite_d(rho_new) && rho_new > 0.0;
+      int ok;
+      double alpha = alpha_of(st, qq, c, st->dvtot[qq], &ok);
+      st->alpha_cur[qq] = alpha;
+      st->m_valid[qq] += ok;
+      alpha_hist[(size_t)iter * BBMM_MAXC + qq] = alpha;
+      int ok2 = ok && finite_d(rho_new) && rho_new > 0.0;
       double beta = ok2 ? rho_new / st->rho[qq] : 0.0;
       st->active[qq] = ok2;
       st->beta_cur[qq] = beta;
@@ -609,19 +690,17 @@ __global__ __launch_bounds__(VT) void k_ur(int init, int n, int ld, int c, doubl
       double bn = st->bnorm[qq];
       double rel = sqrt(rrq) / (bn > 0.0 ? bn : 1.0);
       resid_hist[(size_t)iter * BBMM_MAXC + qq] = rel;
-      red[qq] = rel;
+      rel_s[qq] = rel;
     }
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    if (!init) {
-      st->iters_run = iter + 1;
-      if (tol > 0.0) {
-        int all = 1;
-        for (int qq = 0; qq < c; ++qq)
-          if (!(red[qq] < tol)) all = 0;
-        if (all) st->done = 1;
-      }
+  if (threadIdx.x == 0 && !init) {
+    st->iters_run = iter + 1;
+    if (tol > 0.0) {
+      int all = 1;
+      for (int qq = 0; qq < c; ++qq)
+        if (!(rel_s[qq] < tol)) all = 0;
+      if (all) st->done = 1;
     }
   }
 }
@@ -909,15 +988,15 @@ void launch_vreduce(hipStream_t s, const double* Vp, int nsplit, int n, int np, 
   k_vreduce<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(Vp, nsplit, n, np, ld, scaleV, addD, D4, V);
 }
 
-void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* partial,
+void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
                     int nblocks) {
-  k_pc_init<<<nblocks, VT, 0, s>>>(n, hyp, delta, st, partial);
+  k_pc_init<<<nblocks, VT, 0, s>>>(n, hyp, delta, st, arg_out);
 }
 
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
-                    float* L, DevState* st, double* partial, int nblocks) {
+                    float* L, DevState* st, const double* arg_in, double* arg_out, int nblocks) {
   double thresh = 1e-12 * hyp.outputscale;
-  k_pc_step<<<nblocks, VT, 0, s>>>(X, n, m, kp, hyp, delta, L, st, partial, thresh);
+  k_pc_step<<<nblocks, VT, 0, s>>>(X, n, m, kp, hyp, delta, L, st, arg_in, arg_out, thresh);
 }
 
 void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
@@ -931,28 +1010,30 @@ void launch_probes(hipStream_t s, const float* y, const float* E1, const float* 
   k_probes<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(y, E1, E2, L, n, t, kp, ld, sqrt(noise), st, R);
 }
 
-void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, int c, double scaleV,
-               double addD, const double* D4, double* V, DevState* st, double* partial,
-               double* gpartial, int nblocks, int iter, double* alpha_hist) {
-  k_dv<<<nblocks, VT, 0, s>>>(Vp, nsplit, n, np, ld, c, scaleV, addD, D4, V, st, partial, gpartial,
-                              iter, alpha_hist);
+void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
+               double addD, const double* D4, double* V, const DevState* st, double* partial_dv,
+               int nblocks) {
+  k_dv<<<nblocks, VT, 0, s>>>(Vp, nsplit, n, np, ld, scaleV, addD, D4, V, st, partial_dv);
 }
 
-#define DISPATCH_KP(KERNEL, kp, grid, ...)                                  \
+#define DISPATCH_KP_T(KERNEL, kp, grid, threads, ...)                        \
   switch (kp) {                                                             \
-    case 0: KERNEL<0><<<grid, VT, 0, s>>>(__VA_ARGS__); break;              \
-    case 8: KERNEL<8><<<grid, VT, 0, s>>>(__VA_ARGS__); break;              \
-    case 16: KERNEL<16><<<grid, VT, 0, s>>>(__VA_ARGS__); break;            \
-    case 24: KERNEL<24><<<grid, VT, 0, s>>>(__VA_ARGS__); break;            \
-    default: KERNEL<32><<<grid, VT, 0, s>>>(__VA_ARGS__); break;            \
+    case 0: KERNEL<0><<<grid, threads, 0, s>>>(__VA_ARGS__); break;         \
+    case 8: KERNEL<8><<<grid, threads, 0, s>>>(__VA_ARGS__); break;         \
+    case 16: KERNEL<16><<<grid, threads, 0, s>>>(__VA_ARGS__); break;       \
+    case 24: KERNEL<24><<<grid, threads, 0, s>>>(__VA_ARGS__); break;       \
+    default: KERNEL<32><<<grid, threads, 0, s>>>(__VA_ARGS__); break;       \
   }
+#define DISPATCH_KP(KERNEL, kp, grid, ...) DISPATCH_KP_T(KERNEL, kp, grid, VT, __VA_ARGS__)
 
+// U, R update + partial sums (nb_ur blocks of 1024 threads), then the one-block finish.
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
                const double* D4, const double* V, double* U, double* R, const float* L, DevState* st,
-               double* partial, double* gpartial, int nblocks, int iter, double* beta_hist,
-               double* resid_hist) {
-  DISPATCH_KP(k_ur, kp, nblocks, init, n, ld, c, noise, tol, D4, V, U, R, L, st, partial, gpartial,
-              iter, beta_hist, resid_hist);
+               const double* partial_dv, int nb_dv, double* partial, int nb_ur, int iter,
+               double* alpha_hist, double* beta_hist, double* resid_hist) {
+  DISPATCH_KP_T(k_ur_main, kp, nb_ur, UT, init, n, ld, c, D4, V, U, R, L, st, partial_dv, nb_dv, partial);
+  DISPATCH_KP_T(k_ur_fin, kp, 1, UT, init, ld, c, noise, tol, st, partial, nb_ur, iter, alpha_hist,
+                beta_hist, resid_hist);
 }
 
 void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,

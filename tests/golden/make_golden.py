@@ -24,6 +24,8 @@ N_SAMPLE = 128
 CASES = {
     # name: (config, n, overrides)
     "cfg2_n10000": (2, 10000, {}),
+    # same problem with the iteration cap raised so that the 1e-2 tolerance is actually reached
+    "cfg2_n10000_cap128": (2, 10000, {"iters": 128}),
     "cfg3_n50000": (3, 50000, {}),
     "cfg4_sub_n20000": (4, 20000, {}),
 }

@@ -211,17 +211,17 @@ def test_mbcg_matches_oracle_at_fixed_iterations(ctx, mode, kernel, ard, n, d):
 
 
 def test_mbcg_tolerance_stop_and_wide_block(ctx):
-    w = _case(inputs.RBF, False, 900, 4, t=20, k=10, iters=80, noise=0.05)
-    w.tol = 0.1
+    w = _case(inputs.RBF, False, 900, 4, t=20, k=10, iters=80, noise=0.3)
+    w.tol = 0.01
     ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
     L, piv, rank = ctx.bbmm_pivoted_cholesky()
     ctx.bbmm_precond_setup()
     B = ctx.bbmm_make_probes()                       # 21 columns -> 32-wide path
     U, alpha, beta, resid, iters = ctx.bbmm_mbcg(inputs.ONTHEFLY, B)
     assert 1 <= iters < 80
-    assert resid[iters - 1].max() < 0.1
+    assert resid[iters - 1].max() < 0.01
     if iters > 1:
-        assert resid[iters - 2].max() >= 0.1
+        assert resid[iters - 2].max() >= 0.01
     assert np.all(alpha[iters:] == 0.0)
     Kh = _khat(w)
     P = O.make_preconditioner(_host(L), w.noise)
@@ -229,10 +229,10 @@ def test_mbcg_tolerance_stop_and_wide_block(ctx):
     # the residual hovers near the threshold for several iterations, so the exact stopping
     # iteration is not unique across precisions: the oracle, run for the same number of
     # iterations, must itself be at the threshold (within a factor 2)
-    assert ref.resid[-1].max() < 0.2
+    assert ref.resid[-1].max() < 0.02
     assert _colrel(_host(U), ref.U) < 1e-3
     true_rel = np.linalg.norm(_host(B) - Kh @ _host(U), axis=0) / np.linalg.norm(_host(B), axis=0)
-    assert true_rel.max() < 0.11
+    assert true_rel.max() < 0.011
 
 
 # ------------------------------------------- tridiagonal eigen-solver, SLQ -----
