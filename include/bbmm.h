@@ -160,9 +160,10 @@ int bbmm_khat_block(bbmm_ctx* ctx, int64_t row0, int64_t nrows, int64_t col0, in
  * M, V: device n x c float, 1 <= c <= 32.  mode MATERIALISED needs bbmm_build_khat first. */
 int bbmm_kernel_mm(bbmm_ctx* ctx, int32_t mode, const float* M, int64_t c, float* V);
 
-/* Rank-k pivoted Cholesky of K_XX (App. C).  L: device n x k float (optional, NULL to skip),
+/* Rank-k pivoted Cholesky of K_XX (App. C).  L: device n x k double, row-major (optional, NULL to
+ * skip) -- the factor is built and kept in fp64, and this is that factor unrounded;
  * pivots: host k (optional), rank: host (optional). */
-int bbmm_pivoted_cholesky(bbmm_ctx* ctx, float* L, int64_t* pivots, int64_t* rank);
+int bbmm_pivoted_cholesky(bbmm_ctx* ctx, double* L, int64_t* pivots, int64_t* rank);
 
 /* Capacitance matrix C = sigma^2 I + L^T L, its Cholesky factor, and log|P| (App. C).
  * Needs bbmm_pivoted_cholesky.  logdet_precond: host. */

@@ -361,8 +361,13 @@ class BbmmResult:
 
 def bbmm_inference(kernel: int, X, y, ls, s: float, noise: float, E1, E2, k: int, p: int,
                    tol: float = 0.0, forced_pivots: Optional[Sequence[int]] = None,
-                   Khat: Optional[np.ndarray] = None, trace_row_chunk: int = 2048) -> BbmmResult:
-    """One BBMM call: K_hat^{-1} y, log|K_hat| estimate, trace estimates, NLML and gradient."""
+                   Khat: Optional[np.ndarray] = None, trace_row_chunk: int = 2048,
+                   progress: Optional[Callable[[str], None]] = None) -> BbmmResult:
+    """One BBMM call: K_hat^{-1} y, log|K_hat| estimate, trace estimates, NLML and gradient.
+
+    `progress`, if given, is called with a short text at stage boundaries (long runs only).
+    """
+    say = progress if progress is not None else (lambda msg: None)
     X = np.asarray(X, dtype=np.float64)
     y = np.asarray(y, dtype=np.float64)
     ls = np.atleast_1d(np.asarray(ls, dtype=np.float64))
@@ -384,7 +389,9 @@ def bbmm_inference(kernel: int, X, y, ls, s: float, noise: float, E1, E2, k: int
     Zp = make_probes(L, noise, np.asarray(E1)[:L.shape[1]], E2)
     B = np.concatenate([y[:, None], Zp], axis=1)
 
+    say("preconditioner and probes ready")
     res = mbcg(lambda M: Khat @ M, B, P.solve, p, tol)
+    say("mBCG done: %d iterations" % res.iters_run)
 
     # stochastic Lanczos quadrature, probe columns only
     terms = np.zeros(t)
@@ -410,6 +417,7 @@ def bbmm_inference(kernel: int, X, y, ls, s: float, noise: float, E1, E2, k: int
         for h, M in enumerate(mats):
             trace[h] += float(np.sum(U[a:b, 1:] * (M @ W)) / t)
             quad[h] += float(u0[a:b] @ (M @ u0))
+        say("derivative rows %d / %d" % (b, n))
     trace.append(float(np.sum(U[:, 1:] * W) / t))     # dK_hat/dsigma^2 = I
     quad.append(float(u0 @ u0))
     trace = np.array(trace)

@@ -273,7 +273,7 @@ class Context:
 
     def bbmm_pivoted_cholesky(self):
         n, _, _, k, _, _ = self._shape
-        L = self._empty(n, max(k, 1))
+        L = self.torch.empty(n, max(k, 1), dtype=self.torch.float64, device=self.device)
         piv = np.full(max(k, 1), -1, dtype=np.int64)
         rank = C.c_int64(0)
         self._ck(self.lib.bbmm_pivoted_cholesky(self.h, _dptr(L) if k > 0 else None,

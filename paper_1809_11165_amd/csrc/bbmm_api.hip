@@ -204,12 +204,12 @@ int stage_mm(bbmm_ctx* c, int mode, int ld, int* nsplit, double* scaleV, double*
 int stage_pivchol(bbmm_ctx* c) {
   hipStream_t s = c->stream;
   int nb = vec_blocks(c->n, 16);
-  if (c->kp > 0) launch_fill_f32(s, ptr<float>(c->L), (size_t)c->np * c->kp, 0.f);
+  if (c->kp > 0) launch_fill_f64(s, ptr<double>(c->L), (size_t)c->np * c->kp, 0.0);
   // pivot candidates alternate between two buffers (a step reads one and writes the other)
   double* arg[2] = {ptr<double>(c->partial), ptr<double>(c->partial) + 2 * kMaxVecBlocks};
   launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), ptr<DevState>(c->st), arg[0], nb);
   for (int m = 0; m < c->k; ++m)
-    launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<float>(c->L),
+    launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<double>(c->L),
                    ptr<DevState>(c->st), arg[m & 1], arg[(m + 1) & 1], nb);
   c->chol_done = true;
   c->pre_done = false;
@@ -219,7 +219,7 @@ int stage_pivchol(bbmm_ctx* c) {
 int stage_pre_setup(bbmm_ctx* c) {
   if (!c->chol_done) return fail(c, BBMM_EINVAL, "bbmm_pivoted_cholesky must run first");
   int nb = std::min(kMaxVecBlocks, std::max(1, c->n / 64));
-  launch_pre_setup(c->stream, ptr<float>(c->L), c->n, c->k, c->kp, c->prob.noise, ptr<DevState>(c->st),
+  launch_pre_setup(c->stream, ptr<double>(c->L), c->n, c->k, c->kp, c->prob.noise, ptr<DevState>(c->st),
                    ptr<double>(c->partial), ptr<double>(c->gpartial), nb);
   c->pre_done = true;
   return BBMM_OK;
@@ -245,9 +245,9 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
   double* pdv = ptr<double>(c->gpartial);
   double* pur = ptr<double>(c->partial);
   launch_ur(s, 1, c->n, ld, cc, c->kp, noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V), ptr<double>(c->U),
-            ptr<double>(c->R), ptr<float>(c->L), st, pdv, nb, pur, nb_ur, 0, ptr<double>(c->alpha),
+            ptr<double>(c->R), ptr<double>(c->L), st, pdv, nb, pur, nb_ur, 0, ptr<double>(c->alpha),
             ptr<double>(c->beta), ptr<double>(c->resid));
-  launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<float>(c->L), ptr<double>(c->D4),
+  launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<double>(c->L), ptr<double>(c->D4),
             ptr<double>(c->Z0), st, nb);
   if (c->time_mm) {
     while ((int)c->ev.size() < 2 * c->maxit) {
@@ -270,9 +270,9 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
     launch_dv(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, scaleV, addD, ptr<double>(c->D4),
               ptr<double>(c->V), st, pdv, nb);
     launch_ur(s, 0, c->n, ld, cc, c->kp, noise, c->prob.tol, ptr<double>(c->D4), ptr<double>(c->V),
-              ptr<double>(c->U), ptr<double>(c->R), ptr<float>(c->L), st, pdv, nb, pur, nb_ur, j,
+              ptr<double>(c->U), ptr<double>(c->R), ptr<double>(c->L), st, pdv, nb, pur, nb_ur, j,
               ptr<double>(c->alpha), ptr<double>(c->beta), ptr<double>(c->resid));
-    launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<float>(c->L), ptr<double>(c->D4),
+    launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<double>(c->L), ptr<double>(c->D4),
               ptr<double>(c->Z0), st, nb);
   }
   c->mbcg_done = true;
@@ -463,7 +463,7 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
   for (int dim = 0; dim < c->d; ++dim) {
     double l = (in->n_lengthscale == 1) ? c->ls[0] : c->ls[dim];
     c->hyp.inv_ls[dim] = 1.0 / l;
-    c->hyp.xscale[dim] = (float)(sqrt(c0) / l);
+    c->hyp.xscale[dim] = sqrt(c0) / l;
   }
   c->hyp.outputscale = in->outputscale;
   c->hyp.noise = in->noise;
@@ -475,7 +475,7 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
   size_t opx = np * c->dp * sizeof(float);
   struct { Buf* b; size_t bytes; } want[] = {
       {&c->Xa, opx}, {&c->Xb, opx}, {&c->Xs, opx}, {&c->X4, opx}, {&c->sq, np * sizeof(float)},
-      {&c->L, np * std::max(c->kp, 8) * sizeof(float)}, {&c->delta, np * sizeof(double)},
+      {&c->L, np * std::max(c->kp, 8) * sizeof(double)}, {&c->delta, np * sizeof(double)},
       {&c->U, blk}, {&c->R, blk}, {&c->V, blk}, {&c->Z0, blk}, {&c->D4, blk},
       {&c->Vp, (size_t)kMaxSplit * blk},
       {&c->partial, sizeof(double) * (size_t)kMaxVecBlocks * (BBMM_MAXK * BBMM_MAXK + (BBMM_MAXK + 1) * BBMM_MAXC)},
@@ -546,12 +546,12 @@ int bbmm_kernel_mm(bbmm_ctx* c, int32_t mode, const float* M, int64_t cc, float*
   return BBMM_OK;
 }
 
-int bbmm_pivoted_cholesky(bbmm_ctx* c, float* L, int64_t* pivots, int64_t* rank) {
+int bbmm_pivoted_cholesky(bbmm_ctx* c, double* L, int64_t* pivots, int64_t* rank) {
   int rc = check_ready(c);
   if (rc) return rc;
   rc = stage_pivchol(c);
   if (rc) return rc;
-  if (L && c->k > 0) launch_unpack_rows_f32(c->stream, ptr<float>(c->L), c->kp, c->n, c->k, L);
+  if (L && c->k > 0) launch_unpack_rows_f64(c->stream, ptr<double>(c->L), c->kp, c->n, c->k, L);
   rc = fetch_state(c, false);
   if (rc) return rc;
   if (pivots)
@@ -585,10 +585,10 @@ int bbmm_precond_solve(bbmm_ctx* c, const float* R, int64_t cc, float* Z) {
   launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
   launch_pack_rows(s, R, c->n, (int)cc, ld, ptr<double>(c->tmpA));
   launch_ur(s, 1, c->n, ld, (int)cc, c->kp, c->prob.noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V),
-            ptr<double>(c->U), ptr<double>(c->tmpA), ptr<float>(c->L), st, ptr<double>(c->gpartial), nb,
+            ptr<double>(c->U), ptr<double>(c->tmpA), ptr<double>(c->L), st, ptr<double>(c->gpartial), nb,
             ptr<double>(c->partial), ur_blocks(c->n, ld), 0, ptr<double>(c->alpha), ptr<double>(c->beta),
             ptr<double>(c->resid));
-  launch_psolve_apply(s, c->n, ld, c->kp, c->prob.noise, ptr<double>(c->tmpA), ptr<float>(c->L),
+  launch_psolve_apply(s, c->n, ld, c->kp, c->prob.noise, ptr<double>(c->tmpA), ptr<double>(c->L),
                       ptr<double>(c->tmpB), st, nb);
   launch_unpack_rows(s, ptr<double>(c->tmpB), ld, c->n, (int)cc, Z);
   c->mbcg_done = false;
@@ -602,7 +602,7 @@ int bbmm_make_probes(bbmm_ctx* c, float* B) {
   if (!c->chol_done) return fail(c, BBMM_EINVAL, "bbmm_pivoted_cholesky must run first");
   if (!B) return fail(c, BBMM_EINVAL, "B is NULL");
   int cc = c->t + 1, ld = ld_for(cc);
-  launch_probes(c->stream, c->prob.y, c->prob.E1, c->prob.E2, ptr<float>(c->L), c->n, c->t, c->kp, ld,
+  launch_probes(c->stream, c->prob.y, c->prob.E1, c->prob.E2, ptr<double>(c->L), c->n, c->t, c->kp, ld,
                 c->prob.noise, ptr<DevState>(c->st), ptr<double>(c->tmpA));
   launch_unpack_rows(c->stream, ptr<double>(c->tmpA), ld, c->n, cc, B);
   HIPCHK(c, hipGetLastError());
@@ -704,7 +704,7 @@ int bbmm_solve_logdet_grad(bbmm_ctx* c, const bbmm_problem* in, bbmm_result* out
   if (rc) return rc;
   rc = stage_pre_setup(c);
   if (rc) return rc;
-  launch_probes(s, in->y, in->E1, in->E2, ptr<float>(c->L), c->n, c->t, c->kp, ld, in->noise,
+  launch_probes(s, in->y, in->E1, in->E2, ptr<double>(c->L), c->n, c->t, c->kp, ld, in->noise,
                 ptr<DevState>(c->st), ptr<double>(c->R));
   rc = stage_mbcg(c, in->mode, cc, ld);
   if (rc) return rc;

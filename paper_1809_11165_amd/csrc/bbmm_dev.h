@@ -40,7 +40,7 @@ struct DevState {
 
 struct HypArgs {
   double inv_ls[BBMM_MAXD];   // 1 / l_d (isotropic: the same value d times)
-  float xscale[BBMM_MAXD];    // factor applied to centred x_d before the distance contraction
+  double xscale[BBMM_MAXD];   // factor applied to centred x_d in fp64; the product is rounded to fp32 once
   double outputscale;
   double noise;
   int kernel;
@@ -48,7 +48,7 @@ struct HypArgs {
 };
 
 // ---- launchers implemented in kernels_vec.hip ---------------------------------------------
-// n x c blocks (U, R, V, Z0, D4, Vp) are fp64; kernel matrix, X copies and the factor L are fp32.
+// n x c blocks (U, R, V, Z0, D4, Vp) and the factor L are fp64; kernel matrix and X copies are fp32.
 void launch_fill_f32(hipStream_t s, float* p, size_t count, float v);
 void launch_fill_f64(hipStream_t s, double* p, size_t count, double v);
 void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes);
@@ -58,7 +58,7 @@ void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, 
                    const DevState* st, float* Xa, float* Xb, float* Xs, float* X4, float* sq);
 void launch_pack_d4(hipStream_t s, const float* M, int n, int c, int np, int ld, double* D4);
 void launch_unpack_rows(hipStream_t s, const double* src, int ld, int n, int c, float* dst);
-void launch_unpack_rows_f32(hipStream_t s, const float* src, int ld, int n, int c, float* dst);
+void launch_unpack_rows_f64(hipStream_t s, const double* src, int ld, int n, int c, double* dst);
 void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, double* dst);
 void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, double* dst);
 void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0, int nrows, int col0,
@@ -68,22 +68,22 @@ void launch_vreduce(hipStream_t s, const double* Vp, int nsplit, int n, int np, 
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
                     int nblocks);
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
-                    float* L, DevState* st, const double* arg_in, double* arg_out, int nblocks);
-void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
+                    double* L, DevState* st, const double* arg_in, double* arg_out, int nblocks);
+void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, double noise, DevState* st,
                       double* partial, double* gpartial, int nblocks);
-void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
+void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const double* L,
                    int n, int t, int kp, int ld, double noise, const DevState* st, double* R);
 void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
                double addD, const double* D4, double* V, const DevState* st, double* partial_dv,
                int nblocks);
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
-               const double* D4, const double* V, double* U, double* R, const float* L, DevState* st,
+               const double* D4, const double* V, double* U, double* R, const double* L, DevState* st,
                const double* partial_dv, int nb_dv, double* partial, int nb_ur, int iter,
                double* alpha_hist, double* beta_hist, double* resid_hist);
 void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,
-               const float* L, double* D4, double* Z0, DevState* st, int nblocks);
+               const double* L, double* D4, double* Z0, DevState* st, int nblocks);
 void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const double* R,
-                         const float* L, double* Z, DevState* st, int nblocks);
+                         const double* L, double* Z, DevState* st, int nblocks);
 void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, DevState* st);
 void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,
                         double* eigvals, double* first_row);

@@ -23,6 +23,11 @@ namespace {
 
 constexpr float kSqrt5 = 2.2360679774997896964f;
 constexpr float kLog2e = 1.4426950408889634074f;
+// sqrt(5) * log2(e) as the nearest float, and ln(2) times what that rounding drops: the exponent
+// is evaluated with the float, the dropped part re-enters as the factor (1 - kMatExpFix * rho),
+// so the value carries no bias that grows with rho.
+constexpr float kMatExpC = 3.225964069366455f;
+constexpr float kMatExpFix = 7.8230743523e-8f;
 
 __device__ inline f32x4 mfma16(float a, float b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -66,9 +71,10 @@ __device__ inline float unit_kernel(float r2) {
     return __builtin_amdgcn_exp2f(-r2);
   } else {
     float rho = __builtin_amdgcn_sqrtf(r2);
-    float e = __builtin_amdgcn_exp2f(-(kSqrt5 * kLog2e) * rho);
+    float e = __builtin_amdgcn_exp2f(-kMatExpC * rho);
     float poly = fmaf(rho, fmaf(rho, 5.f / 3.f, kSqrt5), 1.f);
-    return poly * e;
+    float v = poly * e;
+    return fmaf(-kMatExpFix * rho, v, v);
   }
 }
 
@@ -82,7 +88,8 @@ __device__ inline void unit_kernel_and_weight(float r2, float& e_out, float& g_o
     g_out = e;
   } else {
     float rho = __builtin_amdgcn_sqrtf(r2);
-    float e = __builtin_amdgcn_exp2f(-(kSqrt5 * kLog2e) * rho);
+    float e = __builtin_amdgcn_exp2f(-kMatExpC * rho);
+    e = fmaf(-kMatExpFix * rho, e, e);
     e_out = fmaf(rho, fmaf(rho, 5.f / 3.f, kSqrt5), 1.f) * e;
     g_out = (5.f / 3.f) * fmaf(rho, kSqrt5, 1.f) * e;
   }

@@ -157,7 +157,7 @@ __global__ void k_prep_x(const float* __restrict__ X, int n, int d, int np, int 
   int b = i >> 4, r16 = i & 15;
   for (int dim = 0; dim < dp; ++dim) {
     float v = 0.f;
-    if (i < n && dim < d) v = (float)(((double)X[(size_t)i * d + dim] - st->xmean[dim])) * hyp.xscale[dim];
+    if (i < n && dim < d) v = (float)(((double)X[(size_t)i * d + dim] - st->xmean[dim]) * hyp.xscale[dim]);
     int kk = dim >> 2, g = dim & 3;
     size_t sw = ((size_t)b * KK + kk) * 64 + (size_t)(g * 16 + r16);
     Xb[sw] = v;
@@ -189,9 +189,9 @@ __global__ void k_unpack_rows(const double* __restrict__ src, int ld, int n, int
   dst[idx] = (float)src[(size_t)i * ld + q];
 }
 
-// padded float rows (stride ld) -> dense n x c (used for the Cholesky factor)
-__global__ void k_unpack_rows_f32(const float* __restrict__ src, int ld, int n, int c,
-                                  float* __restrict__ dst) {
+// padded fp64 rows (stride ld) -> dense n x c fp64 (used for the Cholesky factor)
+__global__ void k_unpack_rows_f64(const double* __restrict__ src, int ld, int n, int c,
+                                  double* __restrict__ dst) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n * c) return;
   int i = (int)(idx / c), q = (int)(idx % c);
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(VT) void k_pc_init(int n, HypArgs hyp, double* __re
 // step (and every later one, which sees the same candidates) does nothing.
 __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int n, int m, int kp,
                                                  HypArgs hyp, double* __restrict__ delta,
-                                                 float* __restrict__ L, DevState* st,
+                                                 double* __restrict__ L, DevState* st,
                                                  const double* __restrict__ arg_in,
                                                  double* __restrict__ arg_out, double stop_thresh) {
   __shared__ double sval[VT];
@@ -356,18 +356,17 @@ __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int
   int bi = 0x7fffffff;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
     double di = delta[i];
-    float lval;
+    double lval;
     if (i == piv) {
-      lval = (float)root;
+      lval = root;
       di = -1.0;
     } else if (di < 0.0) {
-      lval = 0.f;                  // already picked
+      lval = 0.0;                  // already picked
     } else {
       double kv = kernel_value_f64(X, piv, i, hyp);
       for (int j = 0; j < m; ++j) kv -= lpiv[j] * (double)L[(size_t)i * kp + j];
-      lval = (float)(kv / root);
-      double lf = (double)lval;
-      di = di - lf * lf;
+      lval = kv / root;
+      di = di - lval * lval;
       if (di < 0.0) di = 0.0;
     }
     L[(size_t)i * kp + m] = lval;
@@ -388,7 +387,7 @@ __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int
 
 // ---------------------------------------------- capacitance matrix, log|P| ---
 // C = sigma^2 I + L^T L (k x k, fp64), Cholesky factor G, log|P| = log|C| + (n-k) log sigma^2.
-__global__ __launch_bounds__(VT) void k_pre_setup(const float* __restrict__ L, int n, int kp,
+__global__ __launch_bounds__(VT) void k_pre_setup(const double* __restrict__ L, int n, int kp,
                                                    double noise, DevState* st, double* partial,
                                                    double* gpartial) {
   int k = st->rank;
@@ -399,7 +398,7 @@ __global__ __launch_bounds__(VT) void k_pre_setup(const float* __restrict__ L, i
   int r0 = blockIdx.x * rows_per_block;
   int r1 = min(n, r0 + rows_per_block);
   for (int i = r0; i < r1; ++i) {
-    const float* li = L + (size_t)i * kp;
+    const double* li = L + (size_t)i * kp;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       int e = threadIdx.x + u * VT;
@@ -453,7 +452,7 @@ __global__ __launch_bounds__(VT) void k_pre_setup(const float* __restrict__ L, i
 // -------------------------------------------------------------- probes -------
 // R[:,0] = y,  R[:,1+i] = L E1[:,i] + sigma E2[:,i]   (row-major, stride ld, zero padded)
 __global__ void k_probes(const float* __restrict__ y, const float* __restrict__ E1,
-                         const float* __restrict__ E2, const float* __restrict__ L, int n, int t,
+                         const float* __restrict__ E2, const double* __restrict__ L, int n, int t,
                          int kp, int ld, double sigma, const DevState* __restrict__ st,
                          double* __restrict__ R) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -466,7 +465,7 @@ __global__ void k_probes(const float* __restrict__ y, const float* __restrict__ 
   } else if (q <= t) {
     double s = sigma * (double)E2[(size_t)i * t + (q - 1)];
     for (int m = 0; m < k; ++m) s += (double)L[(size_t)i * kp + m] * (double)E1[(size_t)m * t + (q - 1)];
-    v = (double)(float)s;     // probes are defined as fp32 vectors (what bbmm_make_probes returns)
+    v = s;
   }
   R[idx] = v;
 }
@@ -537,7 +536,7 @@ __global__ __launch_bounds__(UT) void k_ur_main(int init, int n, int ld, int c,
                                                  const double* __restrict__ D4,
                                                  const double* __restrict__ V,
                                                  double* __restrict__ U, double* __restrict__ R,
-                                                 const float* __restrict__ L, DevState* st,
+                                                 const double* __restrict__ L, DevState* st,
                                                  const double* __restrict__ partial_dv, int nb_dv,
                                                  double* __restrict__ partial) {
   __shared__ double red[UT];
@@ -709,7 +708,7 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
 template <int KP>
 __global__ __launch_bounds__(VT) void k_zd(int init, int n, int ld, double noise,
                                             const double* __restrict__ R,
-                                            const float* __restrict__ L, double* __restrict__ D4,
+                                            const double* __restrict__ L, double* __restrict__ D4,
                                             double* __restrict__ Z0, const DevState* __restrict__ st) {
   if (st->done) return;
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
@@ -738,7 +737,7 @@ __global__ __launch_bounds__(VT) void k_zd(int init, int n, int ld, double noise
 template <int KP>
 __global__ __launch_bounds__(VT) void k_psolve_apply(int n, int ld, double noise,
                                                       const double* __restrict__ R,
-                                                      const float* __restrict__ L,
+                                                      const double* __restrict__ L,
                                                       double* __restrict__ Z,
                                                       const DevState* __restrict__ st) {
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
@@ -965,8 +964,8 @@ void launch_unpack_rows(hipStream_t s, const double* src, int ld, int n, int c, 
   k_unpack_rows<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, ld, n, c, dst);
 }
 
-void launch_unpack_rows_f32(hipStream_t s, const float* src, int ld, int n, int c, float* dst) {
-  k_unpack_rows_f32<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, ld, n, c, dst);
+void launch_unpack_rows_f64(hipStream_t s, const double* src, int ld, int n, int c, double* dst) {
+  k_unpack_rows_f64<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, ld, n, c, dst);
 }
 
 void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, double* dst) {
@@ -994,18 +993,18 @@ void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* 
 }
 
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
-                    float* L, DevState* st, const double* arg_in, double* arg_out, int nblocks) {
+                    double* L, DevState* st, const double* arg_in, double* arg_out, int nblocks) {
   double thresh = 1e-12 * hyp.outputscale;
   k_pc_step<<<nblocks, VT, 0, s>>>(X, n, m, kp, hyp, delta, L, st, arg_in, arg_out, thresh);
 }
 
-void launch_pre_setup(hipStream_t s, const float* L, int n, int k, int kp, double noise, DevState* st,
+void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, double noise, DevState* st,
                       double* partial, double* gpartial, int nblocks) {
   (void)k;
   k_pre_setup<<<nblocks, VT, 0, s>>>(L, n, kp, noise, st, partial, gpartial);
 }
 
-void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const float* L,
+void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const double* L,
                    int n, int t, int kp, int ld, double noise, const DevState* st, double* R) {
   k_probes<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(y, E1, E2, L, n, t, kp, ld, sqrt(noise), st, R);
 }
@@ -1028,7 +1027,7 @@ void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int l
 
 // U, R update + partial sums (nb_ur blocks of 1024 threads), then the one-block finish.
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
-               const double* D4, const double* V, double* U, double* R, const float* L, DevState* st,
+               const double* D4, const double* V, double* U, double* R, const double* L, DevState* st,
                const double* partial_dv, int nb_dv, double* partial, int nb_ur, int iter,
                double* alpha_hist, double* beta_hist, double* resid_hist) {
   DISPATCH_KP_T(k_ur_main, kp, nb_ur, UT, init, n, ld, c, D4, V, U, R, L, st, partial_dv, nb_dv, partial);
@@ -1037,12 +1036,12 @@ void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noi
 }
 
 void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,
-               const float* L, double* D4, double* Z0, DevState* st, int nblocks) {
+               const double* L, double* D4, double* Z0, DevState* st, int nblocks) {
   DISPATCH_KP(k_zd, kp, nblocks, init, n, ld, noise, R, L, D4, Z0, st);
 }
 
 void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const double* R,
-                         const float* L, double* Z, DevState* st, int nblocks) {
+                         const double* L, double* Z, DevState* st, int nblocks) {
   DISPATCH_KP(k_psolve_apply, kp, nblocks, n, ld, noise, R, L, Z, st);
 }
 

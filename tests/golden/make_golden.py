@@ -40,9 +40,49 @@ def run(name: str):
     cfg, n, kw = CASES[name]
     w = inputs.make(cfg, n=n, **kw)
     t0 = time.time()
+
+    def say(msg):
+        print("[%s %.0fs] %s" % (name, time.time() - t0, msg), flush=True)
+
+    # K_hat row block by row block (what O.kernel_matrix does), reporting progress
+    X64 = w.X.astype(np.float64)
+    Khat = np.empty((n, n))
+    for a in range(0, n, 2048):
+        Khat[a:a + 2048] = O.kernel_block(w.kernel, X64[a:a + 2048], X64, w.lengthscale, w.outputscale)
+        if (a // 2048) % 4 == 0:
+            say("kernel rows %d / %d" % (min(a + 2048, n), n))
+    Khat[np.diag_indices(n)] += w.noise
     res = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
-                           w.k, w.iters, tol=w.tol)
+                           w.k, w.iters, tol=w.tol, Khat=Khat, progress=say)
     rows = sample_rows(n, cfg)
+    # How well the iterate at this iteration count is defined at all.  Once the leading Ritz values
+    # have converged the CG recurrences amplify rounding differences until two runs that are both
+    # correct to fp64 sit a fraction of an iteration apart in their convergence history.  Two
+    # measures of that, from the oracle alone: the size of the last update U_p - U_(p-1), and the
+    # distance between the oracle's run and a second run whose K_hat.M products are summed in 20
+    # column panels (mathematically the same operator, another fp64 rounding order).
+    it = int(res.mbcg.iters_run)
+    P = O.make_preconditioner(res.L, w.noise)
+    norm = lambda A: np.linalg.norm(A, axis=0)
+    say("rerun to iteration %d" % (it - 1))
+    if it > 1:
+        prev = O.mbcg(lambda M: Khat @ M, res.B, P.solve, it - 1)
+        last_step = norm(res.U - prev.U) / norm(res.U)
+        del prev
+    else:
+        last_step = np.ones(res.U.shape[1])
+
+    def panel_mm(M, panels=20):
+        width = (n + panels - 1) // panels
+        acc = np.zeros_like(M)
+        for a in range(0, n, width):
+            acc += Khat[:, a:a + width] @ M[a:a + width]
+        return acc
+
+    say("rerun with panel-ordered products")
+    other = O.mbcg(panel_mm, res.B, P.solve, it)
+    reorder_dev = norm(res.U - other.U) / norm(res.U)
+    del other
     out = {
         "source": "oracle/bbmm_oracle.py bbmm_inference on paper_1809_11165_amd.inputs.make(%d, n=%d)" % (cfg, n),
         "config": cfg, "n": n, "d": w.d, "t": w.t, "k": w.k, "iters_cap": w.iters, "tol": w.tol,
@@ -56,14 +96,24 @@ def run(name: str):
         "sample_rows": rows.tolist(),
         "U_sample": res.U[rows].tolist(),
         "U_colnorm": np.linalg.norm(res.U, axis=0).tolist(),
+        "U_last_step": last_step.tolist(),
+        "U_reorder_dev": reorder_dev.tolist(),
         "seconds": time.time() - t0,
     }
-    path = os.path.join(HERE, name + ".json")
+    path = os.path.join(OUT_DIR, name + ".json")
     with open(path, "w") as f:
         json.dump(out, f)
     print("wrote", path, "in %.0f s" % out["seconds"], flush=True)
 
 
+OUT_DIR = HERE
+
 if __name__ == "__main__":
-    for nm in (sys.argv[1:] or list(CASES)):
+    args = sys.argv[1:]
+    if "--out" in args:                       # e.g. a scratch directory on another machine
+        i = args.index("--out")
+        OUT_DIR = args[i + 1]
+        os.makedirs(OUT_DIR, exist_ok=True)
+        del args[i:i + 2]
+    for nm in (args or list(CASES)):
         run(nm)

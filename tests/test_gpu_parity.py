@@ -167,7 +167,7 @@ def test_preconditioner_and_probes_match_oracle(ctx, kernel, ard, n, d):
     ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
     L, piv, rank = ctx.bbmm_pivoted_cholesky()
     logdetP = ctx.bbmm_precond_setup()
-    Lh = _host(L)                                  # the fp32 factor the GPU really uses
+    Lh = _host(L)                                  # the fp64 factor the GPU really uses
     P = O.make_preconditioner(Lh, w.noise)
     assert logdetP == pytest.approx(P.logdet, rel=1e-10)
     rng = np.random.default_rng(2)
