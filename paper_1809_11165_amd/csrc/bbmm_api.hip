@@ -28,6 +28,7 @@ constexpr int kDkStride = 2 * (BBMM_MAXD + 2);
 
 struct bbmm_ctx {
   int device = 0;
+  int num_cus = 256;          // compute units of the device (hipDeviceProp_t::multiProcessorCount)
   hipStream_t stream = nullptr;
   std::string err;
 
@@ -121,9 +122,28 @@ int default_split(int np, int cols_per_wg, int want_wgs) {
   return s;
 }
 
+// Row chunks of the materialised product.  The kernel keeps its own loads in flight, so one
+// workgroup per compute unit already saturates that unit's share of HBM; what costs time is a
+// last round in which only some units have work.  Take the smallest number of chunks for which
+// strips * chunks fills whole rounds of num_cus workgroups to 95 % (else the best filling).
 int mat_split_of(const bbmm_ctx* c, int ld) {
-  if (c->mat_split > 0) return (int)std::min<int64_t>(c->mat_split, std::min(kMaxSplit, c->np / 16));
-  return default_split(c->np, ld == 16 ? 1024 : 512, 1024);
+  int cap = std::min(kMaxSplit, c->np / 16);
+  if (c->mat_split > 0) return (int)std::min<int64_t>(c->mat_split, cap);
+  int cols_per_wg = (ld == 16) ? 1024 : 512;
+  int strips = (c->np + cols_per_wg - 1) / cols_per_wg;
+  int best = 1;
+  double best_fill = 0.0;
+  for (int s = 1; s <= cap; ++s) {
+    int wgs = strips * s;
+    int rounds = (wgs + c->num_cus - 1) / c->num_cus;
+    double fill = (double)wgs / ((double)rounds * c->num_cus);
+    if (fill > best_fill + 1e-12) {
+      best_fill = fill;
+      best = s;
+    }
+    if (fill >= 0.95) break;
+  }
+  return best;
 }
 
 int otf_split_of(const bbmm_ctx* c) {
@@ -380,6 +400,9 @@ int bbmm_create(bbmm_ctx** out, int device, void* hip_stream) {
   if (hipSetDevice(device) != hipSuccess) return BBMM_EHIP;
   bbmm_ctx* c = new bbmm_ctx();
   c->device = device;
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
+    c->num_cus = cus;
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
   if (hipHostMalloc((void**)&c->h_st, sizeof(DevState), hipHostMallocDefault) != hipSuccess ||
       hipHostMalloc((void**)&c->h_hist, sizeof(double) * 3 * BBMM_MAXP * BBMM_MAXC, hipHostMallocDefault) != hipSuccess) {

@@ -140,8 +140,51 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
 // element (r, cc) of that load, converted to fp64, is the B operand of one fp64 MFMA whose A
 // operand is the quad-swizzled fp64 right-hand side.  Result partials go to Vp[split]; a lane's
 // four accumulator values (block columns l/16, 4+l/16, 8+l/16, 12+l/16) are stored contiguously.
+//
+// The loads run one 16-row step ahead of the arithmetic: as soon as the MFMAs of one load's
+// registers are issued, the same registers receive the load for the next step, so every wave
+// keeps 16*NC KB in flight while its MFMAs run.
+template <int NQ>
+__device__ __forceinline__ void mm_mat_load_d(const double* __restrict__ D4, int j0, int jc, int g,
+                                              f64x4 (&dop)[NQ]) {
+  constexpr int LD = 16 * NQ;
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq)
+    dop[nq] = *(const f64x4*)(D4 + ((size_t)(j0 / 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+}
+
+// One 16-row step.  kv / dop hold this step's operands on entry and the next step's on exit
+// (MORE); the right-hand-side operand of the next step is requested first because memory
+// results return in issue order.
+template <int NQ, int NC, bool MORE>
+__device__ __forceinline__ void mm_mat_step(const float* __restrict__ knext,
+                                            const double* __restrict__ D4, int jnext, int np, int jc,
+                                            int g, f32x4 (&kv)[NC][4], f64x4 (&dop)[NQ],
+                                            f64x4 (&acc)[NC][4][NQ]) {
+  f64x4 dcur[NQ];
+#pragma unroll
+  for (int nq = 0; nq < NQ; ++nq) dcur[nq] = dop[nq];
+  if (MORE) mm_mat_load_d<NQ>(D4, jnext, jc, g, dop);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int nc = 0; nc < NC; ++nc) {
+      double kd[4];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) kd[cc] = (double)kv[nc][r][cc];
+      // the registers are free once converted: refill them before the MFMAs are issued
+      if (MORE) kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(knext + (size_t)r * np + nc * 64));
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = mfma16d(dcur[nq][r], kd[cc], acc[nc][cc][nq]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <int NQ, int NC>
-__global__ __launch_bounds__(256) void k_mm_mat(const float* __restrict__ Khat,
+__global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Khat,
                                                  const double* __restrict__ D4,
                                                  double* __restrict__ Vp, int np, int nsplit,
                                                  int rows_per_split,
@@ -164,29 +207,22 @@ __global__ __launch_bounds__(256) void k_mm_mat(const float* __restrict__ Khat,
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
-  const float* kbase = Khat + (size_t)(g * 4) * np + (size_t)(col0 + 4 * jc);
-  for (int j0 = j_begin; j0 < j_end; j0 += 16) {
-    f64x4 dop[NQ];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
-      dop[nq] = *(const f64x4*)(D4 + ((size_t)(j0 / 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+  if (j_begin < j_end) {
+    const float* kp = Khat + (size_t)(j_begin + g * 4) * np + (size_t)(col0 + 4 * jc);
     f32x4 kv[NC][4];
-    const float* kp = kbase + (size_t)j0 * np;
+    f64x4 dop[NQ];
+    mm_mat_load_d<NQ>(D4, j_begin, jc, g, dop);
 #pragma unroll
-    for (int nc = 0; nc < NC; ++nc)
+    for (int r = 0; r < 4; ++r)
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
+      for (int nc = 0; nc < NC; ++nc)
         kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(kp + (size_t)r * np + nc * 64));
-#pragma unroll
-    for (int nc = 0; nc < NC; ++nc)
-#pragma unroll
-      for (int r = 0; r < 4; ++r)
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-          double kd = (double)kv[nc][r][cc];
-#pragma unroll
-          for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = mfma16d(dop[nq][r], kd, acc[nc][cc][nq]);
-        }
+    int j0 = j_begin;
+    for (; j0 + 16 < j_end; j0 += 16) {
+      kp += (size_t)16 * np;
+      mm_mat_step<NQ, NC, true>(kp, D4, j0 + 16, np, jc, g, kv, dop, acc);
+    }
+    mm_mat_step<NQ, NC, false>(kp, D4, j0, np, jc, g, kv, dop, acc);
   }
   double* vout = Vp + (size_t)split * np * LD;
 #pragma unroll
