@@ -312,7 +312,9 @@ int stage_slq(bbmm_ctx* c) {
 int stage_dk(bbmm_ctx* c, int ld, int t) {
   hipStream_t s = c->stream;
   int ard = (c->prob.n_lengthscale > 1) ? 1 : 0;
-  int ncol = ard ? 2 * t : t;
+  // S = (U W^T + W U^T) / (2t): operands [U, W] / (2t) and [W, U], so that S is symmetric and the
+  // pass needs only the tiles on and above the diagonal
+  int ncol = 2 * t;
   int TS = (ncol + 3) / 4;
   size_t opsz = (size_t)(c->np / 16) * TS * 64;
   float* SA = ptr<float>(c->SA);
@@ -321,16 +323,11 @@ int stage_dk(bbmm_ctx* c, int ld, int t) {
   launch_fill_f32(s, SB, opsz, 0.f);
   const double* U = ptr<double>(c->U);
   const double* Z0 = ptr<double>(c->Z0);
-  if (!ard) {
-    launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, 0, 1.f / (float)t, SA);
-    launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, 0, 1.f, SB);
-  } else {
-    float h = 0.5f / (float)t;
-    launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, 0, h, SA);
-    launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, t, h, SA);
-    launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, 0, 1.f, SB);
-    launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, t, 1.f, SB);
-  }
+  float h = 0.5f / (float)t;
+  launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, 0, h, SA);
+  launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, t, h, SA);
+  launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, 0, 1.f, SB);
+  launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, t, 1.f, SB);
   launch_extract_col(s, U, ld, c->n, c->np, 0, ptr<float>(c->u0v));
   int ns = otf_split_of(c);
   if (launch_dk(s, c->prob.kernel, c->KK, ard, TS, ptr<float>(c->Xa), ptr<float>(c->Xb), ptr<float>(c->sq),

@@ -299,13 +299,15 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
 }
 
 // ------------------------------------------------------------ derivative pass --
-// For every pair (i, j):  S_ij = sum_c SA[i][c] SB[j][c]  (the probe outer products, already
-// divided by t) and Q_ij = u0_i u0_j.  Accumulates
+// For every pair (i, j):  S_ij = sum_c SA[i][c] SB[j][c]  (the probe outer products, divided by t
+// and symmetrised by the caller) and Q_ij = u0_i u0_j.  Accumulates
 //     sum_ij E_ij S_ij,  sum_ij E_ij Q_ij                         (outputscale)
 //   isotropic:  sum_ij g_ij r2_ij S_ij,  sum_ij g_ij r2_ij Q_ij   (lengthscale)
-//   ARD:        per dimension  sum_ij g_ij S_ij (xs_id - xs_jd)^2  (and Q), evaluated as
-//               2 sum_j xs_jd (xs_jd c_j - Y_jd),  c_j = sum_i T_ij,  Y_jd = sum_i T_ij xs_id,
-//               T = g o S with S symmetrised by the caller; Y is one more MFMA contraction.
+//   ARD:        per dimension  sum_ij T_ij (xs_id - xs_jd)^2,  T = g o S (and g o Q), evaluated per
+//               tile as  sum_j [ xs_jd^2 c_j + Y2_jd - 2 xs_jd Y_jd ],  c_j = sum_i T_ij,
+//               Y_jd = sum_i T_ij xs_id,  Y2_jd = sum_i T_ij xs_id^2  (two MFMA contractions).
+// Every summand is symmetric in (i, j), so only tiles with row block <= column block are
+// evaluated: weight 1 above the diagonal, 1/2 on it, and the total is doubled at the end.
 // Partial results: one row of `pstride` doubles per wave: [2*h] trace-type, [2*h+1] quad-type,
 // h = lengthscale slots (1 or 4*KK) then the outputscale slot.
 constexpr int DK_NJ = 4;
@@ -315,6 +317,101 @@ __device__ inline float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
+}
+
+template <int KK, int ARD>
+struct DkAcc {
+  static constexpr int MB = (4 * KK + 15) / 16;
+  float es_tr = 0.f, es_q = 0.f, el_tr = 0.f, el_q = 0.f;
+  f32x4 ytr[DK_NJ][ARD ? MB : 1], yq[DK_NJ][ARD ? MB : 1], y2tr[DK_NJ][ARD ? MB : 1],
+      y2q[DK_NJ][ARD ? MB : 1];
+  float ctr[DK_NJ], cq[DK_NJ];
+};
+
+// One row block ib against the wave's DK_NJ column blocks.  NEAR: the row block lies inside the
+// wave's own column range, so the tile weights (1, 1/2, 0) differ per column block.
+template <int KIND, int KK, int ARD, bool NEAR>
+__device__ __forceinline__ void dk_step(int ib, int jb0, int lane, int TS, const float* __restrict__ Xa,
+                                        const float* __restrict__ sq, const float* __restrict__ X4,
+                                        const float* __restrict__ SA, const float* __restrict__ u0,
+                                        const float* __restrict__ sb_lds, const float (&b)[DK_NJ][KK],
+                                        const float (&sqj)[DK_NJ], const float (&u0j)[DK_NJ],
+                                        DkAcc<KK, ARD>& A) {
+  constexpr int DP = 4 * KK;
+  constexpr int MB = (DP + 15) / 16;
+  constexpr int NJ = DK_NJ;
+  int jc = lane & 15, g = lane >> 4;
+  float a[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
+  f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
+  f32x4 u0i = *(const f32x4*)(u0 + ib * 16 + g * 4);
+  f32x4 xop[ARD ? MB : 1], xop2[ARD ? MB : 1];
+  if (ARD) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      int dim = mb * 16 + jc;
+      xop[mb] = (dim < DP) ? *(const f32x4*)(X4 + ((size_t)(ib * 4 + g) * DP + dim) * 4)
+                           : (f32x4){0.f, 0.f, 0.f, 0.f};
+      xop2[mb] = xop[mb] * xop[mb];
+    }
+  }
+  // S tiles for all column blocks: contraction over the probe index, TS chunks of 4
+  f32x4 S[NJ];
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb) S[jb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  const float* sap = SA + (size_t)ib * TS * 64 + lane;
+  float sa_next = sap[0];
+  for (int kk = 0; kk < TS; ++kk) {
+    float sa = sa_next;
+    if (kk + 1 < TS) sa_next = sap[(kk + 1) * 64];
+#pragma unroll
+    for (int jb = 0; jb < NJ; ++jb) S[jb] = mfma16(sa, sb_lds[(jb * TS + kk) * 64 + lane], S[jb]);
+  }
+#pragma unroll
+  for (int jb = 0; jb < NJ; ++jb) {
+    float wt = 1.f;
+    if (NEAR) {
+      int jbg = jb0 + jb;
+      wt = (ib < jbg) ? 1.f : ((ib == jbg) ? 0.5f : 0.f);
+    }
+    f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
+    if (NEAR && ib == jb0 + jb) r2 = fix_diag(r2, lane);
+    f32x4 ts, tq;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float e, gw;
+      unit_kernel_and_weight<KIND>(r2[r], e, gw);
+      if (NEAR) {
+        e *= wt;
+        gw *= wt;
+      }
+      float q = u0i[r] * u0j[jb];
+      A.es_tr = fmaf(e, S[jb][r], A.es_tr);
+      A.es_q = fmaf(e, q, A.es_q);
+      if (ARD) {
+        ts[r] = gw * S[jb][r];
+        tq[r] = gw * q;
+        A.ctr[jb] += ts[r];
+        A.cq[jb] += tq[r];
+      } else {
+        float w = gw * r2[r];
+        A.el_tr = fmaf(w, S[jb][r], A.el_tr);
+        A.el_q = fmaf(w, q, A.el_q);
+      }
+    }
+    if (ARD) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          A.ytr[jb][mb] = mfma16(xop[mb][r], ts[r], A.ytr[jb][mb]);
+          A.yq[jb][mb] = mfma16(xop[mb][r], tq[r], A.yq[jb][mb]);
+          A.y2tr[jb][mb] = mfma16(xop2[mb][r], ts[r], A.y2tr[jb][mb]);
+          A.y2q[jb][mb] = mfma16(xop2[mb][r], tq[r], A.y2q[jb][mb]);
+        }
+    }
+  }
 }
 
 template <int KIND, int KK, int ARD>
@@ -328,6 +425,7 @@ __global__ __launch_bounds__(256) void k_dk(const float* __restrict__ Xa,
                                              const float* __restrict__ u0, int np, int nsplit,
                                              int blocks_per_split, double* __restrict__ partial,
                                              int pstride) {
+  extern __shared__ float dk_lds[];   // [wave][NJ][TS][64]: the wave's SB operands
   constexpr int DP = 4 * KK;
   constexpr int MB = (DP + 15) / 16;
   constexpr int NJ = DK_NJ;
@@ -338,94 +436,46 @@ __global__ __launch_bounds__(256) void k_dk(const float* __restrict__ Xa,
   int jb0 = (sstrip * 4 + wave) * NJ;
   size_t wave_id = (size_t)blockIdx.x * 4 + wave;
   double* pout = partial + wave_id * pstride;
-  if (jb0 >= nblk) {
+  // row blocks of this chunk that lie on or above the diagonal of the wave's column blocks
+  int ib_begin = split * blocks_per_split;
+  int ib_end = min(min(nblk, ib_begin + blocks_per_split), jb0 + NJ);
+  if (jb0 >= nblk || ib_begin >= ib_end) {
     for (int e = lane; e < pstride; e += 64) pout[e] = 0.0;
     return;
   }
   int jc = lane & 15, g = lane >> 4;
-  float b[NJ][KK], sb[NJ][DK_TSMAX], sqj[NJ], u0j[NJ];
+  float* sb_lds = dk_lds + (size_t)wave * NJ * TS * 64;
+  float b[NJ][KK], sqj[NJ], u0j[NJ];
 #pragma unroll
   for (int jb = 0; jb < NJ; ++jb) {
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) b[jb][kk] = Xb[((size_t)(jb0 + jb) * KK + kk) * 64 + lane];
-#pragma unroll
-    for (int kk = 0; kk < DK_TSMAX; ++kk)
-      sb[jb][kk] = (kk < TS) ? SB[((size_t)(jb0 + jb) * TS + kk) * 64 + lane] : 0.f;
+    for (int kk = 0; kk < TS; ++kk)
+      sb_lds[(jb * TS + kk) * 64 + lane] = SB[((size_t)(jb0 + jb) * TS + kk) * 64 + lane];
     sqj[jb] = sq[(jb0 + jb) * 16 + jc];
     u0j[jb] = u0[(jb0 + jb) * 16 + jc];
   }
-  float es_tr = 0.f, es_q = 0.f, el_tr = 0.f, el_q = 0.f;
-  f32x4 ytr[NJ][MB], yq[NJ][MB];
-  float ctr[NJ], cq[NJ];
+  DkAcc<KK, ARD> A;
 #pragma unroll
   for (int jb = 0; jb < NJ; ++jb) {
-    ctr[jb] = 0.f;
-    cq[jb] = 0.f;
+    A.ctr[jb] = 0.f;
+    A.cq[jb] = 0.f;
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      ytr[jb][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      yq[jb][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int mb = 0; mb < (ARD ? MB : 1); ++mb) {
+      A.ytr[jb][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      A.yq[jb][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      A.y2tr[jb][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      A.y2q[jb][mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
     }
   }
-  int ib_begin = split * blocks_per_split;
-  int ib_end = min(nblk, ib_begin + blocks_per_split);
-  for (int ib = ib_begin; ib < ib_end; ++ib) {
-    float a[KK], sa[DK_TSMAX];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
-#pragma unroll
-    for (int kk = 0; kk < DK_TSMAX; ++kk)
-      sa[kk] = (kk < TS) ? SA[((size_t)ib * TS + kk) * 64 + lane] : 0.f;
-    f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
-    f32x4 u0i = *(const f32x4*)(u0 + ib * 16 + g * 4);
-    f32x4 xop[MB];
-    if (ARD) {
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-        int dim = mb * 16 + jc;
-        xop[mb] = (dim < DP) ? *(const f32x4*)(X4 + ((size_t)(ib * 4 + g) * DP + dim) * 4)
-                             : (f32x4){0.f, 0.f, 0.f, 0.f};
-      }
-    }
-#pragma unroll
-    for (int jb = 0; jb < NJ; ++jb) {
-      f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
-      if (ib == jb0 + jb) r2 = fix_diag(r2, lane);
-      f32x4 S = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kk = 0; kk < DK_TSMAX; ++kk)
-        if (kk < TS) S = mfma16(sa[kk], sb[jb][kk], S);
-      f32x4 ts, tq;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float e, gw;
-        unit_kernel_and_weight<KIND>(r2[r], e, gw);
-        float q = u0i[r] * u0j[jb];
-        es_tr = fmaf(e, S[r], es_tr);
-        es_q = fmaf(e, q, es_q);
-        if (ARD) {
-          ts[r] = gw * S[r];
-          tq[r] = gw * q;
-          ctr[jb] += ts[r];
-          cq[jb] += tq[r];
-        } else {
-          float w = gw * r2[r];
-          el_tr = fmaf(w, S[r], el_tr);
-          el_q = fmaf(w, q, el_q);
-        }
-      }
-      if (ARD) {
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            ytr[jb][mb] = mfma16(xop[mb][r], ts[r], ytr[jb][mb]);
-            yq[jb][mb] = mfma16(xop[mb][r], tq[r], yq[jb][mb]);
-          }
-      }
-    }
-  }
-  // ---- wave-level epilogue -----------------------------------------------------------
+  int ib = ib_begin;
+  int far_end = min(ib_end, jb0);
+  for (; ib < far_end; ++ib)
+    dk_step<KIND, KK, ARD, false>(ib, jb0, lane, TS, Xa, sq, X4, SA, u0, sb_lds, b, sqj, u0j, A);
+  for (; ib < ib_end; ++ib)
+    dk_step<KIND, KK, ARD, true>(ib, jb0, lane, TS, Xa, sq, X4, SA, u0, sb_lds, b, sqj, u0j, A);
+
+  // ---- wave-level epilogue (the factor 2 restores the tiles below the diagonal) -------
   int nls = ARD ? DP : 1;
   if (ARD) {
     float dtr[MB][4], dq[MB][4];
@@ -438,7 +488,7 @@ __global__ __launch_bounds__(256) void k_dk(const float* __restrict__ Xa,
       }
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb) {
-      float c1 = ctr[jb], c2 = cq[jb];
+      float c1 = A.ctr[jb], c2 = A.cq[jb];
       c1 += __shfl_xor(c1, 16, 64);
       c1 += __shfl_xor(c1, 32, 64);
       c2 += __shfl_xor(c2, 16, 64);
@@ -450,8 +500,8 @@ __global__ __launch_bounds__(256) void k_dk(const float* __restrict__ Xa,
         for (int rr = 0; rr < 4; ++rr) {
           int dim = mb * 16 + g * 4 + rr;
           float xj = (dim < DP) ? Xs[(size_t)j * DP + dim] : 0.f;
-          dtr[mb][rr] += 2.f * xj * (xj * c1 - ytr[jb][mb][rr]);
-          dq[mb][rr] += 2.f * xj * (xj * c2 - yq[jb][mb][rr]);
+          dtr[mb][rr] += A.y2tr[jb][mb][rr] + xj * (xj * c1 - 2.f * A.ytr[jb][mb][rr]);
+          dq[mb][rr] += A.y2q[jb][mb][rr] + xj * (xj * c2 - 2.f * A.yq[jb][mb][rr]);
         }
     }
     // sum over the 16 columns held by lanes with the same l/16
@@ -467,21 +517,21 @@ __global__ __launch_bounds__(256) void k_dk(const float* __restrict__ Xa,
         }
         int dim = mb * 16 + g * 4 + rr;
         if (jc == 0 && dim < DP) {
-          pout[2 * dim] = (double)v1;
-          pout[2 * dim + 1] = (double)v2;
+          pout[2 * dim] = 2.0 * (double)v1;
+          pout[2 * dim + 1] = 2.0 * (double)v2;
         }
       }
   } else {
-    float v1 = wave_sum(el_tr), v2 = wave_sum(el_q);
+    float v1 = wave_sum(A.el_tr), v2 = wave_sum(A.el_q);
     if (lane == 0) {
-      pout[0] = (double)v1;
-      pout[1] = (double)v2;
+      pout[0] = 2.0 * (double)v1;
+      pout[1] = 2.0 * (double)v2;
     }
   }
-  float s1 = wave_sum(es_tr), s2 = wave_sum(es_q);
+  float s1 = wave_sum(A.es_tr), s2 = wave_sum(A.es_q);
   if (lane == 0) {
-    pout[2 * nls] = (double)s1;
-    pout[2 * nls + 1] = (double)s2;
+    pout[2 * nls] = 2.0 * (double)s1;
+    pout[2 * nls + 1] = 2.0 * (double)s2;
   }
 }
 
@@ -596,16 +646,17 @@ int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* X
   int sstrips = (nblk + 4 * DK_NJ - 1) / (4 * DK_NJ);
   int grid = sstrips * nsplit;
   int nrows = grid * 4;
-  if (nrows > max_rows || TS > DK_TSMAX) return 1;
+  if (nrows > max_rows || TS < 1 || TS > DK_TSMAX) return 1;
+  size_t lds = (size_t)4 * DK_NJ * TS * 64 * sizeof(float);
 #define DK(K)                                                                                        \
   if (kernel == 0 && !ard)                                                                           \
-    k_dk<0, K, 0><<<grid, 256, 0, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
+    k_dk<0, K, 0><<<grid, 256, lds, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
   else if (kernel == 0 && ard)                                                                       \
-    k_dk<0, K, 1><<<grid, 256, 0, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
+    k_dk<0, K, 1><<<grid, 256, lds, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
   else if (kernel == 1 && !ard)                                                                      \
-    k_dk<1, K, 0><<<grid, 256, 0, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
+    k_dk<1, K, 0><<<grid, 256, lds, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride); \
   else                                                                                               \
-    k_dk<1, K, 1><<<grid, 256, 0, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride)
+    k_dk<1, K, 1><<<grid, 256, lds, s>>>(Xa, Xb, sq, Xs, X4, SA, SB, TS, u0, np, nsplit, blocks_per_split, partial, pstride)
   FOR_KK(DK)
 #undef DK
   int nls = ard ? 4 * KK : 1;
