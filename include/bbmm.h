@@ -127,7 +127,8 @@ int bbmm_destroy(bbmm_ctx* ctx);
 const char* bbmm_last_error(const bbmm_ctx* ctx);
 
 /* Tuning knobs for experiments (all have sensible defaults):
- *   "mat_split"  number of row chunks of K_hat a materialised product is split into
+ *   "mat_wgs"    number of workgroups a materialised product is dealt out to (default: one per
+ *                compute unit; clamped to [strips, 60 * strips], strips = column strips of K_hat)
  *   "otf_split"  number of row chunks an on-the-fly product is split into
  *   "time_mm"    1: record HIP events on the context's stream around every K_hat.M launch of
  *                the next mBCG runs (read back with bbmm_mm_timing); 0: off (default)

@@ -30,6 +30,8 @@ struct bbmm_ctx {
   int device = 0;
   int num_cus = 256;          // compute units of the device (hipDeviceProp_t::multiProcessorCount)
   hipStream_t stream = nullptr;
+  hipStream_t side = nullptr;            // second stream (default priority) for the SLQ eigensolves
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   std::string err;
 
   // problem snapshot (valid after bbmm_setup)
@@ -41,13 +43,16 @@ struct bbmm_ctx {
   bool khat_built = false, chol_done = false, pre_done = false, mbcg_done = false;
   int last_c = 0, last_ld = 0, last_t = 0;   // shape of the last mBCG run
 
-  int64_t mat_split = 0, otf_split = 0;      // 0 = default
+  int64_t mat_wgs = 0, otf_split = 0;        // 0 = default
+  // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
+  int plan_np = 0, plan_wgs[2] = {0, 0};
+  int64_t plan_tune = -1;
   bool time_mm = false;                      // record HIP events around every product launch
   std::vector<hipEvent_t> ev;                // 2 per iteration, created on demand
   int ev_iters = 0;                          // iterations covered by the last timed run
 
   Buf Xa, Xb, Xs, X4, sq, Khat, L, delta, U, R, V, Z0, D4, Vp, partial, gpartial, alpha, beta, resid, st,
-      tmpA, tmpB, SA, SB, u0v, dkpartial, eig;
+      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[2], nseg[2];
   DevState* h_st = nullptr;   // pinned
   double* h_hist = nullptr;   // pinned, 3 * MAXP * MAXC doubles
   size_t dk_rows_cap = 0;
@@ -122,28 +127,65 @@ int default_split(int np, int cols_per_wg, int want_wgs) {
   return s;
 }
 
-// Row chunks of the materialised product.  The kernel keeps its own loads in flight, so one
-// workgroup per compute unit already saturates that unit's share of HBM; what costs time is a
-// last round in which only some units have work.  Take the smallest number of chunks for which
-// strips * chunks fills whole rounds of num_cus workgroups to 95 % (else the best filling).
-int mat_split_of(const bbmm_ctx* c, int ld) {
-  int cap = std::min(kMaxSplit, c->np / 16);
-  if (c->mat_split > 0) return (int)std::min<int64_t>(c->mat_split, cap);
+// Workgroups of the materialised product.  The kernel keeps its own loads in flight, so one
+// workgroup per compute unit already saturates that unit's share of HBM; the plan deals the
+// (strip, row step) units out evenly, so whole rounds of num_cus workgroups leave no tail.
+// Bounds: at least one workgroup per strip (a run then spans at most two strips), at most
+// kMaxSplit partial slots per strip (checked when the plan is laid out), at most one workgroup per unit.
+int mat_wgs_of(const bbmm_ctx* c, int ld) {
   int cols_per_wg = (ld == 16) ? 1024 : 512;
   int strips = (c->np + cols_per_wg - 1) / cols_per_wg;
-  int best = 1;
-  double best_fill = 0.0;
-  for (int s = 1; s <= cap; ++s) {
-    int wgs = strips * s;
-    int rounds = (wgs + c->num_cus - 1) / c->num_cus;
-    double fill = (double)wgs / ((double)rounds * c->num_cus);
-    if (fill > best_fill + 1e-12) {
-      best_fill = fill;
-      best = s;
+  long long units = (long long)strips * (c->np / 16);
+  long long w = (c->mat_wgs > 0) ? c->mat_wgs
+                                 : (long long)c->num_cus * ((strips + c->num_cus - 1) / c->num_cus);
+  w = std::min<long long>(w, (long long)(kMaxSplit - 4) * strips);
+  w = std::min<long long>(w, units);
+  w = std::max<long long>(w, strips);
+  return (int)w;
+}
+
+// Lays out the plans on the host and uploads them: units (strip, 16-row step) in strip-major order
+// are dealt to the workgroups in equal contiguous runs; a run that crosses a strip boundary becomes
+// two pieces.  Everything the kernel relies on (rows inside K_hat, slot inside Vp, at most two
+// pieces) is checked here.
+int ensure_mat_plans(bbmm_ctx* c) {
+  if (c->plan_np == c->np && c->plan_tune == c->mat_wgs) return BBMM_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));   // earlier launches may still read the old plans
+  for (int v = 0; v < 2; ++v) {
+    int ld = v ? 32 : 16, cols_per_wg = v ? 512 : 1024;
+    int strips = (c->np + cols_per_wg - 1) / cols_per_wg;
+    int steps = c->np / 16;
+    int wgs = mat_wgs_of(c, ld);
+    long long units = (long long)strips * steps;
+    std::vector<MmPlan> plan((size_t)wgs);
+    std::vector<int> nseg((size_t)strips, 0);
+    for (int w = 0; w < wgs; ++w) {
+      long long b = units * w / wgs, e = units * (w + 1) / wgs;
+      for (int pc = 0; pc < 2; ++pc) {
+        MmPiece P = {0, 0, 0, 0};
+        if (b < e) {
+          int strip = (int)(b / steps), jb = (int)(b % steps);
+          int je = (int)std::min<long long>(steps, jb + (e - b));
+          P = MmPiece{strip, jb * 16, je * 16, nseg[strip]++};
+          b += je - jb;
+          if (strip >= strips || P.row_end > c->np || P.slot >= kMaxSplit)
+            return fail(c, BBMM_EINVAL, "internal: product plan out of range");
+        }
+        plan[w].piece[pc] = P;
+      }
+      if (b < e) return fail(c, BBMM_EINVAL, "internal: product plan needs more than two pieces");
     }
-    if (fill >= 0.95) break;
+    int rc = ensure(c, c->plan[v], sizeof(MmPlan) * (size_t)wgs);
+    if (rc) return rc;
+    rc = ensure(c, c->nseg[v], sizeof(int) * (size_t)strips);
+    if (rc) return rc;
+    HIPCHK(c, hipMemcpy(c->plan[v].p, plan.data(), sizeof(MmPlan) * (size_t)wgs, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(c->nseg[v].p, nseg.data(), sizeof(int) * (size_t)strips, hipMemcpyHostToDevice));
+    c->plan_wgs[v] = wgs;
   }
-  return best;
+  c->plan_np = c->np;
+  c->plan_tune = c->mat_wgs;
+  return BBMM_OK;
 }
 
 int otf_split_of(const bbmm_ctx* c) {
@@ -196,14 +238,17 @@ int stage_build_khat(bbmm_ctx* c) {
 
 // Vp <- partial products of K_hat with the block in D4; returns the split count and the
 // (scale, add) pair that turns the partial sums into K_hat D.
-int stage_mm(bbmm_ctx* c, int mode, int ld, int* nsplit, double* scaleV, double* addD) {
+int stage_mm(bbmm_ctx* c, int mode, int ld, VpShape* shape, double* scaleV, double* addD) {
   if (mode == BBMM_MODE_MATERIALISED) {
     if (!c->khat_built) return fail(c, BBMM_EINVAL, "materialised product needs bbmm_build_khat first");
-    int ns = mat_split_of(c, ld);
+    if (ld != 16 && ld != 32) return fail(c, BBMM_EINVAL, "unsupported block width");
+    int rc = ensure_mat_plans(c);
+    if (rc) return rc;
+    int v = (ld == 32) ? 1 : 0;
     if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
-                      ns, ptr<DevState>(c->st)))
+                      ptr<MmPlan>(c->plan[v]), c->plan_wgs[v], ptr<DevState>(c->st)))
       return fail(c, BBMM_EINVAL, "unsupported block width");
-    *nsplit = ns;
+    *shape = VpShape{0, ptr<int>(c->nseg[v]), v ? 512 : 1024};
     *scaleV = 1.0;
     *addD = 0.0;
   } else if (mode == BBMM_MODE_ONTHEFLY) {
@@ -212,7 +257,7 @@ int stage_mm(bbmm_ctx* c, int mode, int ld, int* nsplit, double* scaleV, double*
                       ptr<float>(c->sq), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld, ns,
                       ptr<DevState>(c->st)))
       return fail(c, BBMM_EINVAL, "unsupported block width or input dimension");
-    *nsplit = ns;
+    *shape = VpShape{ns, nullptr, 1};
     *scaleV = c->prob.outputscale;
     *addD = c->prob.noise;
   } else {
@@ -278,7 +323,7 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
   }
   c->ev_iters = 0;
   for (int j = 0; j < c->maxit; ++j) {
-    int ns = 0;
+    VpShape ns{0, nullptr, 1};
     double scaleV = 1.0, addD = 0.0;
     if (c->time_mm) HIPCHK(c, hipEventRecord(c->ev[2 * j], s));
     int rc = stage_mm(c, mode, ld, &ns, &scaleV, &addD);
@@ -302,9 +347,9 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
   return BBMM_OK;
 }
 
-int stage_slq(bbmm_ctx* c) {
+int stage_slq(bbmm_ctx* c, hipStream_t s) {
   if (!c->mbcg_done || c->last_t < 1) return fail(c, BBMM_EINVAL, "bbmm_mbcg with at least one probe column must run first");
-  launch_slq(c->stream, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, ptr<DevState>(c->st));
+  launch_slq(s, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, ptr<DevState>(c->st));
   return BBMM_OK;
 }
 
@@ -406,6 +451,12 @@ int bbmm_create(bbmm_ctx** out, int device, void* hip_stream) {
     delete c;
     return BBMM_ENOMEM;
   }
+  if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+    bbmm_destroy(c);
+    return BBMM_EHIP;
+  }
   *out = c;
   return BBMM_OK;
 }
@@ -414,9 +465,16 @@ int bbmm_destroy(bbmm_ctx* c) {
   if (!c) return BBMM_OK;
   (void)hipSetDevice(c->device);
   (void)hipStreamSynchronize(c->stream);
+  if (c->side) {
+    (void)hipStreamSynchronize(c->side);
+    (void)hipStreamDestroy(c->side);
+  }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   Buf* bufs[] = {&c->Xa, &c->Xb, &c->Xs, &c->X4, &c->sq, &c->Khat, &c->L, &c->delta, &c->U, &c->R, &c->V,
                  &c->Z0, &c->D4, &c->Vp, &c->partial, &c->gpartial, &c->alpha, &c->beta, &c->resid, &c->st, &c->tmpA,
-                 &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig};
+                 &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig, &c->plan[0], &c->plan[1], &c->nseg[0],
+                 &c->nseg[1]};
   for (Buf* b : bufs)
     if (b->p) (void)hipFree(b->p);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -430,7 +488,7 @@ const char* bbmm_last_error(const bbmm_ctx* c) { return c ? c->err.c_str() : "co
 
 int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   if (!c || !key) return BBMM_EINVAL;
-  if (!strcmp(key, "mat_split")) c->mat_split = value > 0 ? value : 0;
+  if (!strcmp(key, "mat_wgs")) c->mat_wgs = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
   else if (!strcmp(key, "time_mm")) c->time_mm = value > 0;
   else return fail(c, BBMM_EINVAL, std::string("unknown tuning key: ") + key);
@@ -556,7 +614,7 @@ int bbmm_kernel_mm(bbmm_ctx* c, int32_t mode, const float* M, int64_t cc, float*
   hipStream_t s = c->stream;
   launch_fill_bytes0(s, &ptr<DevState>(c->st)->done, 2 * sizeof(int));
   launch_pack_d4(s, M, c->n, (int)cc, c->np, ld, ptr<double>(c->D4));
-  int ns = 0;
+  VpShape ns{0, nullptr, 1};
   double scaleV = 1.0, addD = 0.0;
   rc = stage_mm(c, mode, ld, &ns, &scaleV, &addD);
   if (rc) return rc;
@@ -678,7 +736,7 @@ int bbmm_tridiag_eig_batched(bbmm_ctx* c, const double* diag, const double* off,
 int bbmm_slq_logdet(bbmm_ctx* c, double* logdet, double* slq_terms) {
   int rc = check_ready(c);
   if (rc) return rc;
-  rc = stage_slq(c);
+  rc = stage_slq(c, c->stream);
   if (rc) return rc;
   rc = fetch_state(c, false);
   if (rc) return rc;
@@ -728,12 +786,18 @@ int bbmm_solve_logdet_grad(bbmm_ctx* c, const bbmm_problem* in, bbmm_result* out
                 ptr<DevState>(c->st), ptr<double>(c->R));
   rc = stage_mbcg(c, in->mode, cc, ld);
   if (rc) return rc;
-  rc = stage_slq(c);
+  // The eigensolves need only the coefficient histories and the derivative pass only the solves:
+  // they run side by side, the SLQ kernel on the context's second stream.
+  HIPCHK(c, hipEventRecord(c->ev_fork, s));
+  HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+  rc = stage_slq(c, c->side);
   if (rc) return rc;
+  HIPCHK(c, hipEventRecord(c->ev_join, c->side));
   rc = stage_dk(c, ld, c->t);
   if (rc) return rc;
   launch_extract_col(s, ptr<double>(c->U), ld, c->n, c->n, 0, out->u0);
   if (out->U) launch_unpack_rows(s, ptr<double>(c->U), ld, c->n, cc, out->U);
+  HIPCHK(c, hipStreamWaitEvent(s, c->ev_join, 0));
   rc = fetch_state(c, true);
   if (rc) return rc;
   rc = device_status(c);

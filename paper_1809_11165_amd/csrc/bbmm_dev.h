@@ -47,6 +47,24 @@ struct HypArgs {
   int d;
 };
 
+// Work of one workgroup of the materialised product: up to two pieces, each a run of K_hat rows
+// [row_begin, row_end) (multiples of 16) inside one strip of output columns, whose partial result
+// goes to slot `slot` of that strip.  An unused piece has row_begin == row_end.
+struct MmPiece {
+  int strip, row_begin, row_end, slot;
+};
+struct MmPlan {
+  MmPiece piece[2];
+};
+
+// How the partial products in Vp are to be summed: `nsplit` slots for every row, or, when nseg is
+// set, nseg[row / seg_cols] slots.
+struct VpShape {
+  int nsplit;
+  const int* nseg;
+  int seg_cols;
+};
+
 // ---- launchers implemented in kernels_vec.hip ---------------------------------------------
 // n x c blocks (U, R, V, Z0, D4, Vp) and the factor L are fp64; kernel matrix and X copies are fp32.
 void launch_fill_f32(hipStream_t s, float* p, size_t count, float v);
@@ -63,7 +81,7 @@ void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, dou
 void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, double* dst);
 void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0, int nrows, int col0,
                        int ncols, float* dst);
-void launch_vreduce(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
+void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                     double addD, const double* D4, double* V);
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
                     int nblocks);
@@ -73,7 +91,7 @@ void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, doub
                       double* partial, double* gpartial, int nblocks);
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const double* L,
                    int n, int t, int kp, int ld, double noise, const DevState* st, double* R);
-void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
+void launch_dv(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                double addD, const double* D4, double* V, const DevState* st, double* partial_dv,
                int nblocks);
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
@@ -93,8 +111,9 @@ void launch_noise_terms(hipStream_t s, const double* U, const double* Z0, const 
 // ---- launchers implemented in kernels_mm.hip ----------------------------------------------
 int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
                       const float* sq, int n, int np, double outputscale, double noise, float* Khat);
+// plan: one entry per workgroup, laid out by the host (see ensure_mat_plans).
 int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
-                  int nsplit, const DevState* st);
+                  const MmPlan* plan, int wgs, const DevState* st);
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
                   const double* D4, double* Vp, int np, int ld, int nsplit, const DevState* st);
 // derivative pass: one partial row (pstride doubles) per wave, then a fixed-order fp64 sum into

@@ -183,31 +183,33 @@ __device__ __forceinline__ void mm_mat_step(const float* __restrict__ knext,
     }
 }
 
+// Workgroup = 4 waves on 256*NC adjacent columns (one strip); it runs the pieces of its plan
+// entry one after the other.  All workgroups get the same number of 16-row steps (+-1), so the
+// launch ends without a tail however strips and compute units divide.
 template <int NQ, int NC>
 __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Khat,
-                                                 const double* __restrict__ D4,
-                                                 double* __restrict__ Vp, int np, int nsplit,
-                                                 int rows_per_split,
-                                                 const DevState* __restrict__ st) {
+                                                    const double* __restrict__ D4,
+                                                    double* __restrict__ Vp, int np,
+                                                    const MmPlan* __restrict__ plan,
+                                                    const DevState* __restrict__ st) {
   if (st->done) return;
   constexpr int LD = 16 * NQ;
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  int split = blockIdx.x % nsplit;
-  int sstrip = blockIdx.x / nsplit;
-  int col0 = (sstrip * 4 + wave) * (64 * NC);
-  if (col0 >= np) return;
   int jc = lane & 15, g = lane >> 4;
-  int j_begin = split * rows_per_split;
-  int j_end = min(np, j_begin + rows_per_split);
-  f64x4 acc[NC][4][NQ];
+#pragma unroll 1
+  for (int pc = 0; pc < 2; ++pc) {
+    MmPiece P = plan[blockIdx.x].piece[pc];
+    int j_begin = P.row_begin, j_end = P.row_end;
+    int col0 = (P.strip * 4 + wave) * (64 * NC);
+    if (j_begin >= j_end || col0 >= np) continue;
+    f64x4 acc[NC][4][NQ];
 #pragma unroll
-  for (int nc = 0; nc < NC; ++nc)
+    for (int nc = 0; nc < NC; ++nc)
 #pragma unroll
-    for (int cc = 0; cc < 4; ++cc)
+      for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
+        for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
-  if (j_begin < j_end) {
     const float* kp = Khat + (size_t)(j_begin + g * 4) * np + (size_t)(col0 + 4 * jc);
     f32x4 kv[NC][4];
     f64x4 dop[NQ];
@@ -223,16 +225,17 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
       mm_mat_step<NQ, NC, true>(kp, D4, j0 + 16, np, jc, g, kv, dop, acc);
     }
     mm_mat_step<NQ, NC, false>(kp, D4, j0, np, jc, g, kv, dop, acc);
+
+    double* vout = Vp + (size_t)P.slot * np * LD;
+#pragma unroll
+    for (int nc = 0; nc < NC; ++nc)
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+          *(f64x4*)(vout + (size_t)(col0 + nc * 64 + 4 * jc + cc) * LD + nq * 16 + g * 4) =
+              acc[nc][cc][nq];
   }
-  double* vout = Vp + (size_t)split * np * LD;
-#pragma unroll
-  for (int nc = 0; nc < NC; ++nc)
-#pragma unroll
-    for (int cc = 0; cc < 4; ++cc)
-#pragma unroll
-      for (int nq = 0; nq < NQ; ++nq)
-        *(f64x4*)(vout + (size_t)(col0 + nc * 64 + 4 * jc + cc) * LD + nq * 16 + g * 4) =
-            acc[nc][cc][nq];
 }
 
 // ------------------------------------------------------- product on the fly ---
@@ -598,17 +601,11 @@ int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const 
 }
 
 int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
-                  int nsplit, const DevState* st) {
-  constexpr int NC = 4;
-  int nblk = np / 16;
-  int rows_per_split = 16 * ((nblk + nsplit - 1) / nsplit);
-  int sstrips = (np + 4 * 64 * NC - 1) / (4 * 64 * NC);
-  int grid = sstrips * nsplit;
+                  const MmPlan* plan, int wgs, const DevState* st) {
   if (ld == 16)
-    k_mm_mat<1, NC><<<grid, 256, 0, s>>>(Khat, D4, Vp, np, nsplit, rows_per_split, st);
+    k_mm_mat<1, 4><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, plan, st);
   else if (ld == 32)
-    k_mm_mat<2, 2><<<(np + 4 * 64 * 2 - 1) / (4 * 64 * 2) * nsplit, 256, 0, s>>>(Khat, D4, Vp, np, nsplit,
-                                                                             rows_per_split, st);
+    k_mm_mat<2, 2><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, plan, st);
   else
     return 1;
   return 0;

@@ -226,13 +226,14 @@ __global__ void k_copy_block(const float* __restrict__ src, size_t ld_src, int r
 }
 
 // V = scaleV * sum_s Vp[s] + addD * D  (no dot product; used by the stand-alone product call)
-__global__ void k_vreduce(const double* __restrict__ Vp, int nsplit, int n, int np, int ld,
+__global__ void k_vreduce(const double* __restrict__ Vp, VpShape shape, int n, int np, int ld,
                           double scaleV, double addD, const double* __restrict__ D4,
                           double* __restrict__ V) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)n * ld) return;
   int i = (int)(idx / ld), q = (int)(idx % ld);
   size_t pidx = (size_t)i * ld + perm16(q);
+  int nsplit = shape.nseg ? shape.nseg[i / shape.seg_cols] : shape.nsplit;
   double s = 0.0;
   for (int sp = 0; sp < nsplit; ++sp) s += Vp[(size_t)sp * np * ld + pidx];
   V[idx] = scaleV * s + addD * D4[d4_index(i, q, ld)];
@@ -483,7 +484,7 @@ __global__ void k_probes(const float* __restrict__ y, const float* __restrict__ 
 // device-wide fence inside a kernel was measured at ~60 us here.
 //
 // (1) after the product: V = scaleV * sum_s Vp[s] + addD * D, and per-block partial d^T v.
-__global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, int nsplit, int n, int np,
+__global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShape shape, int n, int np,
                                             int ld, double scaleV, double addD,
                                             const double* __restrict__ D4, double* __restrict__ V,
                                             const DevState* __restrict__ st,
@@ -496,6 +497,7 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, int ns
   for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
     size_t idx = (size_t)i * ld + q;
     size_t pidx = (size_t)i * ld + pq;
+    int nsplit = shape.nseg ? shape.nseg[i / shape.seg_cols] : shape.nsplit;
     double s0 = 0.0, s1 = 0.0;
     int sp = 0;
     for (; sp + 1 < nsplit; sp += 2) {
@@ -982,9 +984,9 @@ void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0,
                                                                       ncols, dst);
 }
 
-void launch_vreduce(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
+void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                     double addD, const double* D4, double* V) {
-  k_vreduce<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(Vp, nsplit, n, np, ld, scaleV, addD, D4, V);
+  k_vreduce<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(Vp, shape, n, np, ld, scaleV, addD, D4, V);
 }
 
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
@@ -1009,10 +1011,10 @@ void launch_probes(hipStream_t s, const float* y, const float* E1, const float* 
   k_probes<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(y, E1, E2, L, n, t, kp, ld, sqrt(noise), st, R);
 }
 
-void launch_dv(hipStream_t s, const double* Vp, int nsplit, int n, int np, int ld, double scaleV,
+void launch_dv(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                double addD, const double* D4, double* V, const DevState* st, double* partial_dv,
                int nblocks) {
-  k_dv<<<nblocks, VT, 0, s>>>(Vp, nsplit, n, np, ld, scaleV, addD, D4, V, st, partial_dv);
+  k_dv<<<nblocks, VT, 0, s>>>(Vp, shape, n, np, ld, scaleV, addD, D4, V, st, partial_dv);
 }
 
 #define DISPATCH_KP_T(KERNEL, kp, grid, threads, ...)                        \

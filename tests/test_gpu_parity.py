@@ -99,21 +99,24 @@ def test_kernel_mm_matches_oracle_product(ctx, mode, kernel, ard, n, d, c):
     assert _colrel(V, ref) < 1e-4
 
 
-def test_kernel_mm_split_counts_agree(ctx):
+@pytest.mark.parametrize("c", [11, 20])
+def test_kernel_mm_work_decompositions_agree(ctx, c):
+    # the way the product is dealt out to workgroups (and the number of partial results summed
+    # per row) must not change the result beyond rounding order
     w = _case(inputs.RBF, False, 2100, 8)
     rng = np.random.default_rng(6)
-    M = _dev(rng.standard_normal((w.n, 11)))
+    M = _dev(rng.standard_normal((w.n, c)))
     ref = _khat(w) @ _host(M)
     for mode in (inputs.MATERIALISED, inputs.ONTHEFLY):
         ctx.bbmm_setup(_problem(w, mode))
         if mode == inputs.MATERIALISED:
             ctx.bbmm_build_khat()
-        for split in (1, 3, 8, 64):
-            ctx.bbmm_tune("mat_split", split)
+        for split in (1, 3, 8, 64, 177):
+            ctx.bbmm_tune("mat_wgs", split)
             ctx.bbmm_tune("otf_split", split)
             V = _host(ctx.bbmm_kernel_mm(mode, M))
             assert _colrel(V, ref) < 1e-4, (mode, split)
-    ctx.bbmm_tune("mat_split", 0)
+    ctx.bbmm_tune("mat_wgs", 0)
     ctx.bbmm_tune("otf_split", 0)
 
 
