@@ -130,6 +130,7 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *   "mat_wgs"    number of workgroups a materialised product is dealt out to (default: one per
  *                compute unit; clamped to [strips, 60 * strips], strips = column strips of K_hat)
  *   "otf_split"  number of row chunks an on-the-fly product is split into
+ *   "ur_blocks"  upper limit of the workgroups of the fused U/R update (default 128, at most 512)
  *   "time_mm"    1: record HIP events on the context's stream around every K_hat.M launch of
  *                the next mBCG runs (read back with bbmm_mm_timing); 0: off (default)
  * value <= 0 restores the default.  Unknown key: BBMM_EINVAL. */

@@ -44,6 +44,7 @@ struct bbmm_ctx {
   int last_c = 0, last_ld = 0, last_t = 0;   // shape of the last mBCG run
 
   int64_t mat_wgs = 0, otf_split = 0;        // 0 = default
+  int64_t ur_blocks_cap = 0;
   // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
   int plan_np = 0, plan_wgs[2] = {0, 0};
   int64_t plan_tune = -1;
@@ -108,11 +109,13 @@ int vec_blocks(int n, int ld) {
   return nb;
 }
 
-// blocks of the 1024-thread update kernel: at least ~4 rows per thread, at most 128 partial rows
-int ur_blocks(int n, int ld) {
-  int rpp = 1024 / ld;
-  int nb = (n + rpp * 4 - 1) / (rpp * 4);
-  return std::max(1, std::min(nb, 128));
+// blocks of the 1024-thread update kernel: at least two 4-row steps per wave, at most 128 partial rows
+int ur_blocks(const bbmm_ctx* c, int n, int ld) {
+  (void)ld;
+  int rows_per_step = 16 * 4;               // 16 waves, 4 rows each
+  int nb = (n + rows_per_step * 2 - 1) / (rows_per_step * 2);
+  int cap = c->ur_blocks_cap > 0 ? (int)std::min<int64_t>(c->ur_blocks_cap, kMaxVecBlocks) : 128;
+  return std::max(1, std::min(nb, cap));
 }
 
 int default_split(int np, int cols_per_wg, int want_wgs) {
@@ -306,7 +309,7 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
   // done / iters_run live next to each other at the end of DevState
   launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
   double noise = c->prob.noise;
-  int nb_ur = ur_blocks(c->n, ld);
+  int nb_ur = ur_blocks(c, c->n, ld);
   double* pdv = ptr<double>(c->gpartial);
   double* pur = ptr<double>(c->partial);
   launch_ur(s, 1, c->n, ld, cc, c->kp, noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V), ptr<double>(c->U),
@@ -490,6 +493,7 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   if (!c || !key) return BBMM_EINVAL;
   if (!strcmp(key, "mat_wgs")) c->mat_wgs = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
+  else if (!strcmp(key, "ur_blocks")) c->ur_blocks_cap = value > 0 ? value : 0;
   else if (!strcmp(key, "time_mm")) c->time_mm = value > 0;
   else return fail(c, BBMM_EINVAL, std::string("unknown tuning key: ") + key);
   return BBMM_OK;
@@ -664,7 +668,7 @@ int bbmm_precond_solve(bbmm_ctx* c, const float* R, int64_t cc, float* Z) {
   launch_pack_rows(s, R, c->n, (int)cc, ld, ptr<double>(c->tmpA));
   launch_ur(s, 1, c->n, ld, (int)cc, c->kp, c->prob.noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V),
             ptr<double>(c->U), ptr<double>(c->tmpA), ptr<double>(c->L), st, ptr<double>(c->gpartial), nb,
-            ptr<double>(c->partial), ur_blocks(c->n, ld), 0, ptr<double>(c->alpha), ptr<double>(c->beta),
+            ptr<double>(c->partial), ur_blocks(c, c->n, ld), 0, ptr<double>(c->alpha), ptr<double>(c->beta),
             ptr<double>(c->resid));
   launch_psolve_apply(s, c->n, ld, c->kp, c->prob.noise, ptr<double>(c->tmpA), ptr<double>(c->L),
                       ptr<double>(c->tmpB), st, nb);

@@ -16,6 +16,14 @@
 
 namespace {
 
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// fp64 MFMA 16x16x4: A[m = lane%16][k = lane/16], B[k = lane/16][n = lane%16]; register r of the
+// result holds D[m = 4*r + lane/16][n = lane%16].
+__device__ inline f64x4 mfma16d(double a, double b, f64x4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
 __device__ inline size_t d4_index(int i, int q, int ld) {
   return (size_t)(i >> 2) * (size_t)(4 * ld) + (size_t)q * 4 + (size_t)(i & 3);
 }
@@ -519,96 +527,164 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShap
   }
 }
 
+// value of lane `src` (the same for the whole wave) in every lane
+__device__ inline double bcast_lane(double v, int src) {
+  int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+  int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+  return __hiloint2double(hi, lo);
+}
+
 constexpr int UT = 1024;      // threads of the update kernel
+static_assert(BBMM_MAXK * BBMM_MAXK == UT, "k_ur_fin loads one entry of G per thread");
 constexpr int URB = 5;        // quantities reduced per barrier pair
 
-// alpha_j for column q from the d^T v total, with the freeze guard (same expression in
-// k_ur_main, which needs the value, and in k_ur_fin, which records it).
-__device__ inline double alpha_of(const DevState* st, int q, int c, double dv, int* ok_out) {
-  int ok = st->active[q] && finite_d(dv) && dv > 0.0 && q < c;
+// alpha_j for column q from the d^T v total, with the freeze guard (k_ur_main needs the value,
+// k_ur_fin records it; both evaluate this on the state they read at their start).
+__device__ inline double alpha_from(int active, double rho, double dv, int q, int c, int* ok_out) {
+  int ok = active && finite_d(dv) && dv > 0.0 && q < c;
   *ok_out = ok;
-  return ok ? st->rho[q] / dv : 0.0;
+  return ok ? rho / dv : 0.0;
 }
 
 // (2a) every block first adds the d^T v partials of k_dv (same order in every block), forms
 //      alpha_j, then U += alpha D, R -= alpha V and its partial sums of |r|^2 and L^T R.
 //      init != 0: no update, just the sums for R = B (gives Z_0, rho_0).
-template <int KP>
-__global__ __launch_bounds__(UT) void k_ur_main(int init, int n, int ld, int c,
+//      A wave takes 4 rows per step: lane l holds element (row l/16, column l%16 [+16]) of the
+//      blocks, which is exactly the B operand of an fp64 MFMA whose A operand is the same four
+//      rows of L, so L^T R costs one load of L per 16 columns of L instead of one per entry.
+template <int KP, int NQ>
+__global__ __launch_bounds__(UT) void k_ur_main(int init, int n, int c,
                                                  const double* __restrict__ D4,
                                                  const double* __restrict__ V,
                                                  double* __restrict__ U, double* __restrict__ R,
                                                  const double* __restrict__ L, DevState* st,
                                                  const double* __restrict__ partial_dv, int nb_dv,
                                                  double* __restrict__ partial) {
-  __shared__ double red[UT];
+  constexpr int LD = 16 * NQ;
+  constexpr int MB = (KP + 15) / 16;
+  constexpr int NW = UT / 64;
+  __shared__ double stage[NW][256];
   __shared__ double dvtot[BBMM_MAXC];
-  __shared__ double stage[URB][UT / 64][BBMM_MAXC];
-  if (st->done) return;
-  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = UT / ld;
-  double alpha = 0.0;
-  if (!init) {
-    double s = 0.0;
-    for (int b = rl; b < nb_dv; b += rpp) s += partial_dv[(size_t)b * ld + q];
-    red[threadIdx.x] = s;
-    __syncthreads();
-    if (rl == 0) {
-      double t = 0.0;
-      for (int r = 0; r < rpp; ++r) t += red[r * ld + q];
-      dvtot[q] = t;
-      if (blockIdx.x == 0) st->dvtot[q] = t;
-    }
-    __syncthreads();
-    int ok;
-    alpha = alpha_of(st, q, c, dvtot[q], &ok);
-  }
-  double rr = 0.0;
-  double lr[KP > 0 ? KP : 1];
-#pragma unroll
-  for (int m = 0; m < KP; ++m) lr[m] = 0.0;
-  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
-    size_t idx = (size_t)i * ld + q;
-    double rd;
-    if (!init) {
-      double dd = D4[d4_index(i, q, ld)];
-      U[idx] = U[idx] + alpha * dd;
-      rd = R[idx] - alpha * V[idx];
-      R[idx] = rd;
-    } else {
-      rd = R[idx];
-    }
-    rr += rd * rd;
-#pragma unroll
-    for (int m = 0; m < KP; ++m) lr[m] += (double)L[(size_t)i * KP + m] * rd;
-  }
-  // in-block reduction: rows held by one wave through shuffles, waves through LDS
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  size_t pstride = (size_t)(KP + 1) * ld;
+  int q = lane & 15, g = lane >> 4;
+  // state reads are requested together with the first partial sums (one memory round trip)
+  int done = st->done;
+  double alpha[NQ], s_rho[NQ];
+  int s_active[NQ];
 #pragma unroll
-  for (int e0 = 0; e0 <= KP; e0 += URB) {
-#pragma unroll
-    for (int eb = 0; eb < URB; ++eb) {
-      int e = e0 + eb;
-      if (e <= KP) {
-        double v = (e == 0) ? rr : lr[e > 0 ? e - 1 : 0];
-        v += __shfl_xor(v, 32, 64);
-        if (ld == 16) v += __shfl_xor(v, 16, 64);
-        if (lane < ld) stage[eb][wave][lane] = v;
-      }
-    }
-    __syncthreads();
-    if ((int)threadIdx.x < URB * ld) {
-      int eb = threadIdx.x / ld, qq = threadIdx.x % ld;
-      int e = e0 + eb;
-      if (e <= KP) {
-        double s = 0.0;
-#pragma unroll
-        for (int w = 0; w < UT / 64; ++w) s += stage[eb][w][qq];
-        partial[(size_t)blockIdx.x * pstride + (size_t)e * ld + qq] = s;
-      }
-    }
-    __syncthreads();
+  for (int qb = 0; qb < NQ; ++qb) {
+    alpha[qb] = 0.0;
+    s_rho[qb] = st->rho[qb * 16 + q];
+    s_active[qb] = st->active[qb * 16 + q];
   }
+  if (!init) {
+    // thread (row group rl, column cq): rows rl, rl + rpp, ... of the partials
+    int cq = threadIdx.x % LD, rl = threadIdx.x / LD;
+    constexpr int rpp = UT / LD;
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int b = rl;
+    for (; b + 3 * rpp < nb_dv; b += 4 * rpp) {
+      s0 += partial_dv[(size_t)b * LD + cq];
+      s1 += partial_dv[(size_t)(b + rpp) * LD + cq];
+      s2 += partial_dv[(size_t)(b + 2 * rpp) * LD + cq];
+      s3 += partial_dv[(size_t)(b + 3 * rpp) * LD + cq];
+    }
+    for (; b < nb_dv; b += rpp) s0 += partial_dv[(size_t)b * LD + cq];
+    double sv = (s0 + s1) + (s2 + s3);
+    // a wave holds 64 / LD row groups of the same columns
+    sv += __shfl_xor(sv, 32, 64);
+    if (LD == 16) sv += __shfl_xor(sv, 16, 64);
+    if (lane < LD) stage[wave][lane] = sv;
+    __syncthreads();
+    if ((int)threadIdx.x < LD) {
+      double t = 0.0;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) t += stage[w][threadIdx.x];
+      dvtot[threadIdx.x] = t;
+      if (blockIdx.x == 0) st->dvtot[threadIdx.x] = t;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+      int ok;
+      alpha[qb] = alpha_from(s_active[qb], s_rho[qb], dvtot[qb * 16 + q], qb * 16 + q, c, &ok);
+    }
+  }
+  if (done) return;                                   // block-uniform
+  double rr[NQ];
+  f64x4 acc[MB > 0 ? MB : 1][NQ];
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) {
+    rr[qb] = 0.0;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb][qb] = (f64x4){0.0, 0.0, 0.0, 0.0};
+  }
+  int gw = blockIdx.x * NW + wave, nw = gridDim.x * NW;
+  for (int i0 = 4 * gw; i0 < n; i0 += 4 * nw) {     // wave-uniform bounds: MFMA needs all lanes
+    int i = i0 + g;
+    bool ok = i < n;
+    double rd[NQ];
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+      int col = qb * 16 + q;
+      size_t idx = (size_t)i * LD + col;
+      double v = 0.0;
+      if (ok) {
+        if (!init) {
+          double dd = D4[d4_index(i, col, LD)];
+          U[idx] = U[idx] + alpha[qb] * dd;
+          v = R[idx] - alpha[qb] * V[idx];
+          R[idx] = v;
+        } else {
+          v = R[idx];
+        }
+      }
+      rd[qb] = v;
+      rr[qb] += v * v;
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      int m = mb * 16 + q;
+      double la = (ok && m < KP) ? L[(size_t)i * KP + m] : 0.0;
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) acc[mb][qb] = mfma16d(la, rd[qb], acc[mb][qb]);
+    }
+  }
+  // ---- block reduction over the waves, 256 values (16 rows of L^T R x 16 columns) per round ----
+  size_t pstride = (size_t)(KP + 1) * LD;
+  double* pout = partial + (size_t)blockIdx.x * pstride;
+#pragma unroll
+  for (int qb = 0; qb < NQ; ++qb) {
+    double v = rr[qb];
+    v += __shfl_xor(v, 16, 64);
+    v += __shfl_xor(v, 32, 64);
+    if (g == 0) stage[wave][qb * 16 + q] = v;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < LD) {
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) t += stage[w][threadIdx.x];
+    pout[threadIdx.x] = t;
+  }
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int qb = 0; qb < NQ; ++qb) {
+      __syncthreads();
+#pragma unroll
+      for (int r = 0; r < 4; ++r) stage[wave][(4 * r + g) * 16 + q] = acc[mb][qb][r];
+      __syncthreads();
+      if ((int)threadIdx.x < 256) {
+        int m = mb * 16 + (int)threadIdx.x / 16, qq = qb * 16 + (int)threadIdx.x % 16;
+        if (m < KP) {
+          double t = 0.0;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) t += stage[w][threadIdx.x];
+          pout[(size_t)(1 + m) * LD + qq] = t;
+        }
+      }
+    }
 }
 
 // (2b) one block: totals of |r|^2 and L^T R, the k x k solves (one wave per column, lanes =
@@ -620,49 +696,93 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
                                                 int nb, int iter, double* alpha_hist,
                                                 double* beta_hist, double* resid_hist) {
   __shared__ double tot[(BBMM_MAXK + 1) * BBMM_MAXC];
+  __shared__ double psum[(BBMM_MAXK + 1) * BBMM_MAXC];   // parts x E, parts * E <= this size
   __shared__ double Gs[BBMM_MAXK * BBMM_MAXK];
   __shared__ double quad_s[BBMM_MAXC];
   __shared__ double rel_s[BBMM_MAXC];
-  if (st->done) return;
+  __shared__ double ginv[BBMM_MAXK];
+  // Everything this block needs from the state is requested first, together with the partial
+  // sums, so that the kernel pays one memory round trip instead of one per dependent read.
+#ifdef BBMM_PROBE
+  unsigned long long tp0 = wall_clock64(), tp1 = 0, tp2 = 0, tp3 = 0, tp4 = 0;
+#endif
+  int done = st->done;
+  int k = st->rank;
+  int tq = (int)threadIdx.x < ld ? (int)threadIdx.x : 0;
+  double s_rho = st->rho[tq], s_bnorm = st->bnorm[tq], s_dv = st->dvtot[tq];
+  int s_active = st->active[tq], s_mvalid = st->m_valid[tq];
+  double g_mine = st->G[threadIdx.x];   // BBMM_MAXK * BBMM_MAXK == UT entries
+  double g_diag = st->G[(threadIdx.x % BBMM_MAXK) * (BBMM_MAXK + 1)];
   size_t pstride = (size_t)(KP + 1) * ld;
   int E = (KP + 1) * ld;
-  for (int e = threadIdx.x; e < E; e += UT) {
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    int b = 0;
-    for (; b + 3 < nb; b += 4) {
-      s0 += partial[(size_t)b * pstride + e];
-      s1 += partial[(size_t)(b + 1) * pstride + e];
-      s2 += partial[(size_t)(b + 2) * pstride + e];
-      s3 += partial[(size_t)(b + 3) * pstride + e];
+  // totals over the nb partial rows: `parts` thread groups take every parts-th row
+  int parts = (E <= UT / 4) ? 4 : ((E <= UT / 2) ? 2 : 1);
+  int per = UT / parts;
+  int part = threadIdx.x / per, te = threadIdx.x % per;
+  for (int e = te; e < E; e += per) {
+    // 16 loads are issued before the first is consumed: the sum is latency-, not bandwidth-bound
+    double tsum = 0.0;
+    int b = part;
+    for (; b + 15 * parts < nb; b += 16 * parts) {
+      double v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = partial[(size_t)(b + u * parts) * pstride + e];
+#pragma unroll
+      for (int w = 8; w > 0; w >>= 1)
+#pragma unroll
+        for (int u = 0; u < w; ++u) v[u] += v[u + w];
+      tsum += v[0];
     }
-    for (; b < nb; ++b) s0 += partial[(size_t)b * pstride + e];
-    tot[e] = (s0 + s1) + (s2 + s3);
+    for (; b < nb; b += parts) tsum += partial[(size_t)b * pstride + e];
+    psum[part * E + e] = tsum;
   }
-  for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += UT) Gs[e] = st->G[e];
   __syncthreads();
-  int k = st->rank;
+  for (int e = threadIdx.x; e < E; e += UT) {
+    double t = psum[e];
+    for (int pp = 1; pp < parts; ++pp) t += psum[pp * E + e];
+    tot[e] = t;
+  }
+#ifdef BBMM_PROBE
+  tp1 = wall_clock64();
+#endif
+  if (done) return;                     // block-uniform
+  Gs[threadIdx.x] = g_mine;
+  if ((int)threadIdx.x < BBMM_MAXK) ginv[threadIdx.x] = ((int)threadIdx.x < k) ? 1.0 / g_diag : 0.0;
+  __syncthreads();
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   for (int qq = wave; qq < ld; qq += UT / 64) {
     // lane a holds component a of L^T r; forward substitution G w = y, quad = w^T w,
-    // back substitution G^T x = w
+    // back substitution G^T x = w.  Loops are unrolled over the compiled rank limit and the
+    // pivots enter as reciprocals, so that only a broadcast, a multiply and an FMA sit in the
+    // dependent chain of each step.
     double y = (lane < k) ? tot[(size_t)(1 + lane) * ld + qq] : 0.0;
-    for (int a = 0; a < k; ++a) {
-      double wa = __shfl(y, a, 64) / Gs[a * BBMM_MAXK + a];
-      if (lane == a) y = wa;
-      else if (lane > a && lane < k) y -= Gs[lane * BBMM_MAXK + a] * wa;
+    int lrow = lane < BBMM_MAXK ? lane : 0;
+#pragma unroll
+    for (int a = 0; a < KP; ++a) {
+      if (a < k) {
+        double wa = bcast_lane(y, a) * ginv[a];
+        if (lane == a) y = wa;
+        else if (lane > a && lane < k) y -= Gs[lrow * BBMM_MAXK + a] * wa;
+      }
     }
     double sq = (lane < k) ? y * y : 0.0;
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
-    for (int a = k - 1; a >= 0; --a) {
-      double xa = __shfl(y, a, 64) / Gs[a * BBMM_MAXK + a];
-      if (lane == a) y = xa;
-      else if (lane < a) y -= Gs[a * BBMM_MAXK + lane] * xa;
+#pragma unroll
+    for (int a = KP - 1; a >= 0; --a) {
+      if (a < k) {
+        double xa = bcast_lane(y, a) * ginv[a];
+        if (lane == a) y = xa;
+        else if (lane < a) y -= Gs[a * BBMM_MAXK + lrow] * xa;
+      }
     }
     if (lane < BBMM_MAXK) st->Qt[lane * BBMM_MAXC + qq] = (lane < k) ? y : 0.0;
     if (lane == 0) quad_s[qq] = sq;
   }
   __syncthreads();
+#ifdef BBMM_PROBE
+  tp3 = wall_clock64();
+#endif
   if ((int)threadIdx.x < ld) {
     int qq = threadIdx.x;
     double rrq = tot[qq];
@@ -678,23 +798,29 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
       st->alpha_cur[qq] = 0.0;
     } else {
       int ok;
-      double alpha = alpha_of(st, qq, c, st->dvtot[qq], &ok);
+      double alpha = alpha_from(s_active, s_rho, s_dv, qq, c, &ok);
       st->alpha_cur[qq] = alpha;
-      st->m_valid[qq] += ok;
+      st->m_valid[qq] = s_mvalid + ok;
       alpha_hist[(size_t)iter * BBMM_MAXC + qq] = alpha;
       int ok2 = ok && finite_d(rho_new) && rho_new > 0.0;
-      double beta = ok2 ? rho_new / st->rho[qq] : 0.0;
+      double beta = ok2 ? rho_new / s_rho : 0.0;
       st->active[qq] = ok2;
       st->beta_cur[qq] = beta;
       if (ok2) st->rho[qq] = rho_new;
       beta_hist[(size_t)iter * BBMM_MAXC + qq] = beta;
-      double bn = st->bnorm[qq];
+      double bn = s_bnorm;
       double rel = sqrt(rrq) / (bn > 0.0 ? bn : 1.0);
       resid_hist[(size_t)iter * BBMM_MAXC + qq] = rel;
       rel_s[qq] = rel;
     }
   }
   __syncthreads();
+#ifdef BBMM_PROBE
+  tp4 = wall_clock64();
+  if (threadIdx.x == 0 && iter == 7)
+    printf("k_ur_fin probe (10 ns ticks): reduce %llu  solves %llu  bookkeeping %llu\n", tp1 - tp0, tp3 - tp1, tp4 - tp3);
+  (void)tp2;
+#endif
   if (threadIdx.x == 0 && !init) {
     st->iters_run = iter + 1;
     if (tol > 0.0) {
@@ -706,53 +832,66 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
   }
 }
 
-// (3) z = P^{-1} r = (r - L Qt) / sigma^2,  d <- z + beta d  (init: d <- z and Z0 <- z).
-template <int KP>
-__global__ __launch_bounds__(VT) void k_zd(int init, int n, int ld, double noise,
-                                            const double* __restrict__ R,
+// (3) z = P^{-1} r by the Woodbury formula, z = (r - L (C^{-1} L^T r)) / sigma^2 with C^{-1} L^T r
+//     left in st->Qt by k_ur_fin, then D <- z + beta D (MODE 0), or Z0 = D = z at the start
+//     (MODE 1), or just Z = z for the stand-alone preconditioner solve (MODE 2).
+//     A wave takes 16 rows per step: L Qt is KP / 4 fp64 MFMAs whose result register r holds
+//     row 4 r + lane / 16, column lane % 16 -- rows in which R and the quad-swizzled D are
+//     contiguous across the wave.
+template <int KP, int NQ, int MODE>
+__global__ __launch_bounds__(VT) void k_zd(int n, double noise, const double* __restrict__ R,
                                             const double* __restrict__ L, double* __restrict__ D4,
-                                            double* __restrict__ Z0, const DevState* __restrict__ st) {
-  if (st->done) return;
-  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
-  double beta = init ? 0.0 : st->beta_cur[q];
-  double qt[KP > 0 ? KP : 1];
+                                            double* __restrict__ Z, const DevState* __restrict__ st) {
+  constexpr int LD = 16 * NQ;
+  constexpr int KS = KP / 4;
+  if (MODE != 2 && st->done) return;
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int q = lane & 15, g = lane >> 4;
+  double beta[NQ];
+  double qtb[KS > 0 ? KS : 1][NQ];
 #pragma unroll
-  for (int m = 0; m < KP; ++m) qt[m] = st->Qt[m * BBMM_MAXC + q];
-  double inv_noise = 1.0 / noise;
-  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
-    size_t idx = (size_t)i * ld + q;
-    double s = R[idx];
+  for (int qb = 0; qb < NQ; ++qb) {
+    beta[qb] = (MODE == 0) ? st->beta_cur[qb * 16 + q] : 0.0;
 #pragma unroll
-    for (int m = 0; m < KP; ++m) s -= (double)L[(size_t)i * KP + m] * qt[m];
-    double z = s * inv_noise;
-    size_t di = d4_index(i, q, ld);
-    if (init) {
-      Z0[idx] = z;
-      D4[di] = z;
-    } else {
-      D4[di] = z + beta * D4[di];
-    }
+    for (int kk = 0; kk < KS; ++kk) qtb[kk][qb] = st->Qt[(4 * kk + g) * BBMM_MAXC + qb * 16 + q];
   }
-}
-
-// Stand-alone Woodbury apply Z = P^{-1} R: sums (reuse of k_ur in init mode) then this.
-template <int KP>
-__global__ __launch_bounds__(VT) void k_psolve_apply(int n, int ld, double noise,
-                                                      const double* __restrict__ R,
-                                                      const double* __restrict__ L,
-                                                      double* __restrict__ Z,
-                                                      const DevState* __restrict__ st) {
-  int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
-  double qt[KP > 0 ? KP : 1];
-#pragma unroll
-  for (int m = 0; m < KP; ++m) qt[m] = st->Qt[m * BBMM_MAXC + q];
   double inv_noise = 1.0 / noise;
-  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
-    size_t idx = (size_t)i * ld + q;
-    double s = R[idx];
+  constexpr int NW = VT / 64;
+  int gw = blockIdx.x * NW + wave, nw = gridDim.x * NW;
+  for (int i0 = 16 * gw; i0 < n; i0 += 16 * nw) {   // wave-uniform bounds: MFMA needs all lanes
+    f64x4 acc[NQ];
 #pragma unroll
-    for (int m = 0; m < KP; ++m) s -= (double)L[(size_t)i * KP + m] * qt[m];
-    Z[idx] = s * inv_noise;
+    for (int qb = 0; qb < NQ; ++qb) acc[qb] = (f64x4){0.0, 0.0, 0.0, 0.0};
+    int arow = i0 + q;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      double la = (arow < n) ? L[(size_t)arow * KP + 4 * kk + g] : 0.0;
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) acc[qb] = mfma16d(la, qtb[kk][qb], acc[qb]);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int i = i0 + 4 * r + g;
+      if (i < n) {
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) {
+          int col = qb * 16 + q;
+          size_t idx = (size_t)i * LD + col;
+          double z = (R[idx] - acc[qb][r]) * inv_noise;
+          if (MODE == 2) {
+            Z[idx] = z;
+          } else {
+            size_t di = d4_index(i, col, LD);
+            if (MODE == 1) {
+              Z[idx] = z;
+              D4[di] = z;
+            } else {
+              D4[di] = z + beta[qb] * D4[di];
+            }
+          }
+        }
+      }
+    }
   }
 }
 
@@ -1025,26 +1164,64 @@ void launch_dv(hipStream_t s, const double* Vp, VpShape shape, int n, int np, in
     case 24: KERNEL<24><<<grid, threads, 0, s>>>(__VA_ARGS__); break;       \
     default: KERNEL<32><<<grid, threads, 0, s>>>(__VA_ARGS__); break;       \
   }
-#define DISPATCH_KP(KERNEL, kp, grid, ...) DISPATCH_KP_T(KERNEL, kp, grid, VT, __VA_ARGS__)
+// kernels templated on the rank limit and on the block width in units of 16 columns
+#define DISPATCH_KP_NQ(KERNEL, kp, nq, grid, threads, ...)                        \
+  switch (kp) {                                                                  \
+    case 0:                                                                      \
+      if (nq == 1) KERNEL(0, 1)<<<grid, threads, 0, s>>>(__VA_ARGS__);           \
+      else KERNEL(0, 2)<<<grid, threads, 0, s>>>(__VA_ARGS__);                   \
+      break;                                                                     \
+    case 8:                                                                      \
+      if (nq == 1) KERNEL(8, 1)<<<grid, threads, 0, s>>>(__VA_ARGS__);           \
+      else KERNEL(8, 2)<<<grid, threads, 0, s>>>(__VA_ARGS__);                   \
+      break;                                                                     \
+    case 16:                                                                     \
+      if (nq == 1) KERNEL(16, 1)<<<grid, threads, 0, s>>>(__VA_ARGS__);          \
+      else KERNEL(16, 2)<<<grid, threads, 0, s>>>(__VA_ARGS__);                  \
+      break;                                                                     \
+    case 24:                                                                     \
+      if (nq == 1) KERNEL(24, 1)<<<grid, threads, 0, s>>>(__VA_ARGS__);          \
+      else KERNEL(24, 2)<<<grid, threads, 0, s>>>(__VA_ARGS__);                  \
+      break;                                                                     \
+    default:                                                                     \
+      if (nq == 1) KERNEL(32, 1)<<<grid, threads, 0, s>>>(__VA_ARGS__);          \
+      else KERNEL(32, 2)<<<grid, threads, 0, s>>>(__VA_ARGS__);                  \
+      break;                                                                     \
+  }
 
 // U, R update + partial sums (nb_ur blocks of 1024 threads), then the one-block finish.
 void launch_ur(hipStream_t s, int init, int n, int ld, int c, int kp, double noise, double tol,
                const double* D4, const double* V, double* U, double* R, const double* L, DevState* st,
                const double* partial_dv, int nb_dv, double* partial, int nb_ur, int iter,
                double* alpha_hist, double* beta_hist, double* resid_hist) {
-  DISPATCH_KP_T(k_ur_main, kp, nb_ur, UT, init, n, ld, c, D4, V, U, R, L, st, partial_dv, nb_dv, partial);
+  int nq = ld / 16;
+#define UR_MAIN(KP, NQ) k_ur_main<KP, NQ>
+  DISPATCH_KP_NQ(UR_MAIN, kp, nq, nb_ur, UT, init, n, c, D4, V, U, R, L, st, partial_dv, nb_dv, partial);
+#undef UR_MAIN
   DISPATCH_KP_T(k_ur_fin, kp, 1, UT, init, ld, c, noise, tol, st, partial, nb_ur, iter, alpha_hist,
                 beta_hist, resid_hist);
 }
 
 void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, const double* R,
                const double* L, double* D4, double* Z0, DevState* st, int nblocks) {
-  DISPATCH_KP(k_zd, kp, nblocks, init, n, ld, noise, R, L, D4, Z0, st);
+  int nq = ld / 16;
+  if (init) {
+#define ZD_INIT(KP, NQ) k_zd<KP, NQ, 1>
+    DISPATCH_KP_NQ(ZD_INIT, kp, nq, nblocks, VT, n, noise, R, L, D4, Z0, st);
+#undef ZD_INIT
+  } else {
+#define ZD_ITER(KP, NQ) k_zd<KP, NQ, 0>
+    DISPATCH_KP_NQ(ZD_ITER, kp, nq, nblocks, VT, n, noise, R, L, D4, Z0, st);
+#undef ZD_ITER
+  }
 }
 
 void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const double* R,
                          const double* L, double* Z, DevState* st, int nblocks) {
-  DISPATCH_KP(k_psolve_apply, kp, nblocks, n, ld, noise, R, L, Z, st);
+  int nq = ld / 16;
+#define ZD_APPLY(KP, NQ) k_zd<KP, NQ, 2>
+  DISPATCH_KP_NQ(ZD_APPLY, kp, nq, nblocks, VT, n, noise, R, L, (double*)nullptr, Z, st);
+#undef ZD_APPLY
 }
 
 void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, DevState* st) {
