@@ -22,6 +22,7 @@ struct DevState {
   double dvtot[BBMM_MAXC];      // d^T K_hat d of the current iteration, per column
   double Qt[BBMM_MAXK * BBMM_MAXC];   // C^{-1} L^T R, [m][q]
   double G[BBMM_MAXK * BBMM_MAXK];    // lower Cholesky factor of C = sigma^2 I + L^T L, [a][b]
+  double Ginv[BBMM_MAXK * BBMM_MAXK]; // G^{-1} (lower triangular, zero padded), [a][b]
   double logdetP;
   double pivdmax[BBMM_MAXK + 1];
   double slq_terms[BBMM_MAXC];

@@ -452,9 +452,26 @@ __global__ __launch_bounds__(VT) void k_pre_setup(const double* __restrict__ L, 
     if (bad) st->status = 3;
   }
   __syncthreads();
+  // G^{-1}, one column per thread by forward substitution on the unit vectors; the iteration
+  // applies C^{-1} = G^{-T} G^{-1} as two small dense products instead of serial substitutions
+  // (cond(G) = sqrt(cond(C)) <= sqrt(1 + |L|^2 / sigma^2): harmless in fp64).
+  for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += VT) tot[e] = 0.0;
+  __syncthreads();
+  if ((int)threadIdx.x < k) {
+    int j = threadIdx.x;
+    tot[j * BBMM_MAXK + j] = 1.0 / C[j * BBMM_MAXK + j];
+    for (int i = j + 1; i < k; ++i) {
+      double sacc = 0.0;
+      for (int a = j; a < i; ++a) sacc += C[i * BBMM_MAXK + a] * tot[a * BBMM_MAXK + j];
+      tot[i * BBMM_MAXK + j] = -sacc / C[i * BBMM_MAXK + i];
+    }
+  }
+  __syncthreads();
   for (int e = threadIdx.x; e < BBMM_MAXK * BBMM_MAXK; e += VT) {
     int a = e / BBMM_MAXK, c = e % BBMM_MAXK;
-    st->G[e] = (a < k && c <= a) ? C[e] : 0.0;
+    bool low = a < k && c <= a;
+    st->G[e] = low ? C[e] : 0.0;
+    st->Ginv[e] = low ? tot[e] : 0.0;
   }
 }
 
@@ -502,21 +519,38 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShap
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
   int pq = perm16(q);
   double acc = 0.0;
-  for (int i = blockIdx.x * rpp + rl; i < n; i += gridDim.x * rpp) {
-    size_t idx = (size_t)i * ld + q;
-    size_t pidx = (size_t)i * ld + pq;
-    int nsplit = shape.nseg ? shape.nseg[i / shape.seg_cols] : shape.nsplit;
-    double s0 = 0.0, s1 = 0.0;
-    int sp = 0;
-    for (; sp + 1 < nsplit; sp += 2) {
-      s0 += Vp[(size_t)sp * np * ld + pidx];
-      s1 += Vp[(size_t)(sp + 1) * np * ld + pidx];
+  // RU rows per loop trip; the first 8 partial slots of each and its D entry are requested before
+  // anything is added, so a trip costs one memory round trip
+  constexpr int RU = 3;
+  int stride = gridDim.x * rpp;
+  size_t slot_stride = (size_t)np * ld;
+  for (int ib = blockIdx.x * rpp + rl; ib < n; ib += RU * stride) {
+    double pv[RU][8], dd[RU];
+    int ns[RU];
+#pragma unroll
+    for (int u = 0; u < RU; ++u) {
+      int i = ib + u * stride;
+      bool ok = i < n;
+      int ic = ok ? i : ib;
+      ns[u] = ok ? (shape.nseg ? shape.nseg[ic / shape.seg_cols] : shape.nsplit) : 0;
+      size_t pidx = (size_t)ic * ld + pq;
+#pragma unroll
+      for (int sp = 0; sp < 8; ++sp) pv[u][sp] = (sp < ns[u]) ? Vp[(size_t)sp * slot_stride + pidx] : 0.0;
+      dd[u] = ok ? D4[d4_index(ic, q, ld)] : 0.0;
     }
-    if (sp < nsplit) s0 += Vp[(size_t)sp * np * ld + pidx];
-    double dd = D4[d4_index(i, q, ld)];
-    double v = scaleV * (s0 + s1) + addD * dd;
-    V[idx] = v;
-    acc += dd * v;
+#pragma unroll
+    for (int u = 0; u < RU; ++u) {
+      int i = ib + u * stride;
+      if (i < n) {
+        double sv = ((pv[u][0] + pv[u][1]) + (pv[u][2] + pv[u][3])) +
+                    ((pv[u][4] + pv[u][5]) + (pv[u][6] + pv[u][7]));
+        size_t pidx = (size_t)i * ld + pq;
+        for (int sp = 8; sp < ns[u]; ++sp) sv += Vp[(size_t)sp * slot_stride + pidx];
+        double v = scaleV * sv + addD * dd[u];
+        V[(size_t)i * ld + q] = v;
+        acc += dd[u] * v;
+      }
+    }
   }
   red[threadIdx.x] = acc;
   __syncthreads();
@@ -581,16 +615,17 @@ __global__ __launch_bounds__(UT) void k_ur_main(int init, int n, int c,
     // thread (row group rl, column cq): rows rl, rl + rpp, ... of the partials
     int cq = threadIdx.x % LD, rl = threadIdx.x / LD;
     constexpr int rpp = UT / LD;
-    double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    int b = rl;
-    for (; b + 3 * rpp < nb_dv; b += 4 * rpp) {
-      s0 += partial_dv[(size_t)b * LD + cq];
-      s1 += partial_dv[(size_t)(b + rpp) * LD + cq];
-      s2 += partial_dv[(size_t)(b + 2 * rpp) * LD + cq];
-      s3 += partial_dv[(size_t)(b + 3 * rpp) * LD + cq];
+    // all rows of a thread are requested before the first is added (one memory round trip)
+    double sv = 0.0;
+    for (int b0 = rl; b0 < nb_dv; b0 += 8 * rpp) {
+      double v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        int b = b0 + u * rpp;
+        v[u] = (b < nb_dv) ? partial_dv[(size_t)b * LD + cq] : 0.0;
+      }
+      sv += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
     }
-    for (; b < nb_dv; b += rpp) s0 += partial_dv[(size_t)b * LD + cq];
-    double sv = (s0 + s1) + (s2 + s3);
     // a wave holds 64 / LD row groups of the same columns
     sv += __shfl_xor(sv, 32, 64);
     if (LD == 16) sv += __shfl_xor(sv, 16, 64);
@@ -619,35 +654,56 @@ __global__ __launch_bounds__(UT) void k_ur_main(int init, int n, int c,
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) acc[mb][qb] = (f64x4){0.0, 0.0, 0.0, 0.0};
   }
+  // RU row quads per loop trip, all their loads requested before the first use
+  constexpr int RU = (NQ == 1) ? 4 : 2;
   int gw = blockIdx.x * NW + wave, nw = gridDim.x * NW;
-  for (int i0 = 4 * gw; i0 < n; i0 += 4 * nw) {     // wave-uniform bounds: MFMA needs all lanes
-    int i = i0 + g;
-    bool ok = i < n;
-    double rd[NQ];
+  for (int ib = 4 * gw; ib < n; ib += 4 * nw * RU) {   // wave-uniform bounds: MFMA needs all lanes
+    double dd[RU][NQ], uu[RU][NQ], vv[RU][NQ], rv[RU][NQ], la[RU][MB > 0 ? MB : 1];
+    bool ok[RU];
 #pragma unroll
-    for (int qb = 0; qb < NQ; ++qb) {
-      int col = qb * 16 + q;
-      size_t idx = (size_t)i * LD + col;
-      double v = 0.0;
-      if (ok) {
-        if (!init) {
-          double dd = D4[d4_index(i, col, LD)];
-          U[idx] = U[idx] + alpha[qb] * dd;
-          v = R[idx] - alpha[qb] * V[idx];
-          R[idx] = v;
-        } else {
-          v = R[idx];
+    for (int u = 0; u < RU; ++u) {
+      int i = ib + u * 4 * nw + g;
+      ok[u] = i < n;
+#pragma unroll
+      for (int qb = 0; qb < NQ; ++qb) {
+        int col = qb * 16 + q;
+        size_t idx = (size_t)i * LD + col;
+        dd[u][qb] = uu[u][qb] = vv[u][qb] = rv[u][qb] = 0.0;
+        if (ok[u]) {
+          rv[u][qb] = R[idx];
+          if (!init) {
+            dd[u][qb] = D4[d4_index(i, col, LD)];
+            uu[u][qb] = U[idx];
+            vv[u][qb] = V[idx];
+          }
         }
       }
-      rd[qb] = v;
-      rr[qb] += v * v;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        int m = mb * 16 + q;
+        la[u][mb] = (ok[u] && m < KP) ? L[(size_t)i * KP + m] : 0.0;
+      }
     }
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-      int m = mb * 16 + q;
-      double la = (ok && m < KP) ? L[(size_t)i * KP + m] : 0.0;
+    for (int u = 0; u < RU; ++u) {
+      int i = ib + u * 4 * nw + g;
+      double rd[NQ];
 #pragma unroll
-      for (int qb = 0; qb < NQ; ++qb) acc[mb][qb] = mfma16d(la, rd[qb], acc[mb][qb]);
+      for (int qb = 0; qb < NQ; ++qb) {
+        size_t idx = (size_t)i * LD + qb * 16 + q;
+        double v = rv[u][qb];
+        if (!init && ok[u]) {
+          U[idx] = uu[u][qb] + alpha[qb] * dd[u][qb];
+          v = v - alpha[qb] * vv[u][qb];
+          R[idx] = v;
+        }
+        rd[qb] = v;
+        rr[qb] += v * v;
+      }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int qb = 0; qb < NQ; ++qb) acc[mb][qb] = mfma16d(la[u][mb], rd[qb], acc[mb][qb]);
     }
   }
   // ---- block reduction over the waves, 256 values (16 rows of L^T R x 16 columns) per round ----
@@ -700,19 +756,13 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
   __shared__ double Gs[BBMM_MAXK * BBMM_MAXK];
   __shared__ double quad_s[BBMM_MAXC];
   __shared__ double rel_s[BBMM_MAXC];
-  __shared__ double ginv[BBMM_MAXK];
   // Everything this block needs from the state is requested first, together with the partial
   // sums, so that the kernel pays one memory round trip instead of one per dependent read.
-#ifdef BBMM_PROBE
-  unsigned long long tp0 = wall_clock64(), tp1 = 0, tp2 = 0, tp3 = 0, tp4 = 0;
-#endif
   int done = st->done;
-  int k = st->rank;
   int tq = (int)threadIdx.x < ld ? (int)threadIdx.x : 0;
   double s_rho = st->rho[tq], s_bnorm = st->bnorm[tq], s_dv = st->dvtot[tq];
   int s_active = st->active[tq], s_mvalid = st->m_valid[tq];
-  double g_mine = st->G[threadIdx.x];   // BBMM_MAXK * BBMM_MAXK == UT entries
-  double g_diag = st->G[(threadIdx.x % BBMM_MAXK) * (BBMM_MAXK + 1)];
+  double g_mine = st->Ginv[threadIdx.x];   // BBMM_MAXK * BBMM_MAXK == UT entries
   size_t pstride = (size_t)(KP + 1) * ld;
   int E = (KP + 1) * ld;
   // totals over the nb partial rows: `parts` thread groups take every parts-th row
@@ -720,15 +770,16 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
   int per = UT / parts;
   int part = threadIdx.x / per, te = threadIdx.x % per;
   for (int e = te; e < E; e += per) {
-    // 16 loads are issued before the first is consumed: the sum is latency-, not bandwidth-bound
+    // 32 loads are issued before the first is consumed: the sum is latency-, not bandwidth-bound
+    // (a round trip to memory written by other compute units costs ~2.4 us here)
     double tsum = 0.0;
     int b = part;
-    for (; b + 15 * parts < nb; b += 16 * parts) {
-      double v[16];
+    for (; b + 31 * parts < nb; b += 32 * parts) {
+      double v[32];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) v[u] = partial[(size_t)(b + u * parts) * pstride + e];
+      for (int u = 0; u < 32; ++u) v[u] = partial[(size_t)(b + u * parts) * pstride + e];
 #pragma unroll
-      for (int w = 8; w > 0; w >>= 1)
+      for (int w = 16; w > 0; w >>= 1)
 #pragma unroll
         for (int u = 0; u < w; ++u) v[u] += v[u + w];
       tsum += v[0];
@@ -742,47 +793,37 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
     for (int pp = 1; pp < parts; ++pp) t += psum[pp * E + e];
     tot[e] = t;
   }
-#ifdef BBMM_PROBE
-  tp1 = wall_clock64();
-#endif
   if (done) return;                     // block-uniform
-  Gs[threadIdx.x] = g_mine;
-  if ((int)threadIdx.x < BBMM_MAXK) ginv[threadIdx.x] = ((int)threadIdx.x < k) ? 1.0 / g_diag : 0.0;
+  Gs[threadIdx.x] = g_mine;             // G^{-1}, zero outside the leading k x k lower triangle
   __syncthreads();
-  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int qq = wave; qq < ld; qq += UT / 64) {
-    // lane a holds component a of L^T r; forward substitution G w = y, quad = w^T w,
-    // back substitution G^T x = w.  Loops are unrolled over the compiled rank limit and the
-    // pivots enter as reciprocals, so that only a broadcast, a multiply and an FMA sit in the
-    // dependent chain of each step.
-    double y = (lane < k) ? tot[(size_t)(1 + lane) * ld + qq] : 0.0;
-    int lrow = lane < BBMM_MAXK ? lane : 0;
+  // C^{-1} (L^T r) for all columns at once: w = G^{-1} y, quad = w^T w, x = G^{-T} w; thread
+  // (m, qq) owns one entry; sums run over the compiled rank limit (padding is zero)
+  {
+    int m = threadIdx.x / ld, qq = threadIdx.x % ld;
+    double wv = 0.0;
+    if (m < KP) {
 #pragma unroll
-    for (int a = 0; a < KP; ++a) {
-      if (a < k) {
-        double wa = bcast_lane(y, a) * ginv[a];
-        if (lane == a) y = wa;
-        else if (lane > a && lane < k) y -= Gs[lrow * BBMM_MAXK + a] * wa;
-      }
+      for (int a = 0; a < KP; ++a) wv += Gs[m * BBMM_MAXK + a] * tot[(size_t)(1 + a) * ld + qq];
+      psum[m * ld + qq] = wv;
     }
-    double sq = (lane < k) ? y * y : 0.0;
+    __syncthreads();
+    if (m < KP) {
+      double xv = 0.0;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) sq += __shfl_xor(sq, o, 64);
-#pragma unroll
-    for (int a = KP - 1; a >= 0; --a) {
-      if (a < k) {
-        double xa = bcast_lane(y, a) * ginv[a];
-        if (lane == a) y = xa;
-        else if (lane < a) y -= Gs[a * BBMM_MAXK + lrow] * xa;
-      }
+      for (int a = 0; a < KP; ++a) xv += Gs[a * BBMM_MAXK + m] * psum[a * ld + qq];
+      st->Qt[m * BBMM_MAXC + qq] = xv;
     }
-    if (lane < BBMM_MAXK) st->Qt[lane * BBMM_MAXC + qq] = (lane < k) ? y : 0.0;
-    if (lane == 0) quad_s[qq] = sq;
+    if ((int)threadIdx.x < ld) {
+      double sq = 0.0;
+#pragma unroll
+      for (int a = 0; a < KP; ++a) {
+        double wa = psum[a * ld + threadIdx.x];
+        sq += wa * wa;
+      }
+      quad_s[threadIdx.x] = sq;
+    }
   }
   __syncthreads();
-#ifdef BBMM_PROBE
-  tp3 = wall_clock64();
-#endif
   if ((int)threadIdx.x < ld) {
     int qq = threadIdx.x;
     double rrq = tot[qq];
@@ -815,12 +856,6 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
     }
   }
   __syncthreads();
-#ifdef BBMM_PROBE
-  tp4 = wall_clock64();
-  if (threadIdx.x == 0 && iter == 7)
-    printf("k_ur_fin probe (10 ns ticks): reduce %llu  solves %llu  bookkeeping %llu\n", tp1 - tp0, tp3 - tp1, tp4 - tp3);
-  (void)tp2;
-#endif
   if (threadIdx.x == 0 && !init) {
     st->iters_run = iter + 1;
     if (tol > 0.0) {
