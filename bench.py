@@ -24,7 +24,7 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
 FP64_VALU_PEAK_TFLOPS = 78.6   # MI355X fp64 vector, published
 # HBM bytes per k_mm_mat launch at n = 50000 from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by a
 # 1 GiB copy (profiles/k_mm_mat_cfg3_n50000_hbm_counters.txt); only valid for that workload.
-MEASURED_TRAFFIC_MAT_N50000 = 10.244e9
+MEASURED_TRAFFIC_MAT_N50000 = 10.425e9
 
 
 def cpu_baseline(n_sample: int, n_full: int):
@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--mode", choices=["mat", "otf"], default="mat")
     ap.add_argument("--n", type=int, default=50000)
-    ap.add_argument("--cpu-sample", type=int, default=5000)
+    ap.add_argument("--cpu-sample", type=int, default=10000)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for HBM byte counters)")

@@ -118,16 +118,27 @@ int ur_blocks(const bbmm_ctx* c, int n, int ld) {
   return std::max(1, std::min(nb, cap));
 }
 
-int default_split(int np, int cols_per_wg, int want_wgs) {
-  int strips = (np + cols_per_wg - 1) / cols_per_wg;
-  int s = (want_wgs + strips - 1) / strips;
-  // multiples of 8 keep one chunk of the contraction range per XCD
-  s = ((s + 7) / 8) * 8;
-  if (s < 8) s = 8;
-  if (s > kMaxSplit) s = kMaxSplit;
-  int nblk = np / 16;
-  if (s > nblk) s = nblk;
-  return s;
+// Row chunks of a kernel whose workgroups each take one strip of columns and one chunk of rows:
+// the smallest count from `want_wgs` workgroups up for which strips * chunks fills whole rounds of
+// num_cus workgroups to `min_fill` (else the best filling seen).  Fewer chunks mean fewer partial
+// results to add afterwards; a last round in which only some compute units have work is what
+// costs time.
+int split_by_fill(const bbmm_ctx* c, int strips, int want_wgs, double min_fill) {
+  int cap = std::min(kMaxSplit, c->np / 16);
+  int s0 = std::max(1, std::min(cap, (want_wgs + strips - 1) / strips));
+  int best = s0;
+  double best_fill = 0.0;
+  for (int s = s0; s <= cap; ++s) {
+    int wgs = strips * s;
+    int rounds = (wgs + c->num_cus - 1) / c->num_cus;
+    double fill = (double)wgs / ((double)rounds * c->num_cus);
+    if (fill > best_fill + 1e-12) {
+      best_fill = fill;
+      best = s;
+    }
+    if (fill >= min_fill) break;
+  }
+  return best;
 }
 
 // Workgroups of the materialised product.  The kernel keeps its own loads in flight, so one
@@ -193,7 +204,16 @@ int ensure_mat_plans(bbmm_ctx* c) {
 
 int otf_split_of(const bbmm_ctx* c) {
   if (c->otf_split > 0) return (int)std::min<int64_t>(c->otf_split, std::min(kMaxSplit, c->np / 16));
-  return default_split(c->np, 512, 4096);
+  int strips = (c->np / 16 + 31) / 32;          // 4 waves x 8 column blocks per workgroup
+  return split_by_fill(c, strips, 4 * c->num_cus, 0.97);
+}
+
+// the derivative pass skips the tiles below the diagonal, so its workgroups differ in length:
+// many small ones even that out
+int dk_split_of(const bbmm_ctx* c) {
+  int strips = (c->np / 16 + 15) / 16;          // 4 waves x 4 column blocks per workgroup
+  int s = (16 * c->num_cus + strips - 1) / strips;
+  return std::max(1, std::min(s, std::min(kMaxSplit, c->np / 16)));
 }
 
 int check_ready(bbmm_ctx* c) {
@@ -377,7 +397,7 @@ int stage_dk(bbmm_ctx* c, int ld, int t) {
   launch_swizzle_cols(s, Z0, ld, c->n, c->np, 1, t, TS, 0, 1.f, SB);
   launch_swizzle_cols(s, U, ld, c->n, c->np, 1, t, TS, t, 1.f, SB);
   launch_extract_col(s, U, ld, c->n, c->np, 0, ptr<float>(c->u0v));
-  int ns = otf_split_of(c);
+  int ns = dk_split_of(c);
   if (launch_dk(s, c->prob.kernel, c->KK, ard, TS, ptr<float>(c->Xa), ptr<float>(c->Xb), ptr<float>(c->sq),
                 ptr<float>(c->Xs), ptr<float>(c->X4), SA, SB, ptr<float>(c->u0v), c->np, ns,
                 ptr<double>(c->dkpartial), kDkStride, (int)c->dk_rows_cap, ptr<DevState>(c->st)))
