@@ -14,8 +14,12 @@
  *     pointers are ordinary host memory.  All matrices are dense row-major.
  *   - The caller owns every buffer it passes; the library neither frees nor
  *     keeps any of them after a call returns.
- *   - Work is queued on the context's HIP stream.  A call that returns host
- *     values synchronises that stream once before it returns.
+ *   - Work is queued on the context's HIP stream (bbmm_solve_logdet_grad also
+ *     uses a second stream of its own, joined back before it returns).  A call
+ *     that returns host values synchronises the stream once before it returns.
+ *   - Precision: K_hat entries are fp32; inside the library every n x c block of
+ *     the iteration, the pivoted-Cholesky factor and all sums are fp64.  float
+ *     block arguments are converted on entry and rounded once on exit.
  *   - Every function returns an int status (BBMM_OK == 0).  No exceptions,
  *     no exit().  bbmm_last_error() gives a message for the last failure.
  *   - A context is not thread-safe; use one context per stream.
