@@ -6,6 +6,7 @@ Each case is one of the benchmark configurations at a size where running the ora
 GPU test session would take minutes.  Output: tests/golden/<case>.json (text).
 """
 import json
+import multiprocessing
 import os
 import sys
 import time
@@ -36,7 +37,83 @@ def sample_rows(n: int, cfg: int) -> np.ndarray:
     return np.sort(rng.choice(n, size=min(N_SAMPLE, n), replace=False))
 
 
+_MF = None
+
+
+def _mf_rows(a):
+    kernel, X64, ls, s, M = _MF
+    n = X64.shape[0]
+    b = min(n, a + 1024)
+    acc = np.zeros((b - a, M.shape[1]))
+    for r in range(a, b, 128):
+        for c in range(0, n, 2048):
+            acc[r - a:r - a + 128] += O.kernel_block(kernel, X64[r:r + 128], X64[c:c + 2048], ls, s) @ M[c:c + 2048]
+    return a, acc
+
+
+def run_matrix_free(name: str, cfg: int, n: int, iters: int):
+    """A few mBCG iterations at a size where K_hat cannot be stored (n = 200,000: 320 GB in fp64):
+    the oracle's stages are called one by one with products formed from row blocks of the kernel
+    matrix that are built, used and dropped.  Early iterations are sharply defined (no Ritz value
+    has converged), so coefficients and iterates are stored for a tight comparison."""
+    w = inputs.make(cfg, n=n)
+    t0 = time.time()
+
+    def say(msg):
+        print("[%s %.0fs] %s" % (name, time.time() - t0, msg), flush=True)
+
+    X64 = w.X.astype(np.float64)
+    ls, s, noise = w.lengthscale, w.outputscale, w.noise
+    get_row = lambda i: O.kernel_block(w.kernel, X64[i:i + 1], X64, ls, s)[0]
+    L, pivots, dmax = O.pivoted_cholesky(np.full(n, float(s)), get_row, w.k)
+    P = O.make_preconditioner(L, noise)
+    B = np.concatenate([w.y.astype(np.float64)[:, None], O.make_probes(L, noise, w.E1[:L.shape[1]], w.E2)],
+                       axis=1)
+    say("preconditioner and probes ready")
+    calls = [0]
+    workers = min(16, os.cpu_count() or 1)
+
+    def matmul(M):
+        # rows are dealt to worker processes (forked, so X64 and M are shared); each forms its rows
+        # of K M from tiles of the oracle's kernel_block small enough to stay in cache
+        global _MF
+        _MF = (w.kernel, X64, ls, s, M)
+        tasks = list(range(0, n, 1024))
+        out = np.empty_like(M)
+        with multiprocessing.get_context("fork").Pool(workers) as pool:
+            for done, (a, blk) in enumerate(pool.imap_unordered(_mf_rows, tasks)):
+                out[a:a + blk.shape[0]] = blk
+                if done % 32 == 0:
+                    say("product %d: %d / %d row groups" % (calls[0], done + 1, len(tasks)))
+        calls[0] += 1
+        return out + noise * M
+
+    res = O.mbcg(matmul, B, P.solve, iters)
+    rows = sample_rows(n, cfg)
+    out = {
+        "source": "oracle/bbmm_oracle.py stages (pivoted_cholesky, make_probes, mbcg) with row-block products "
+                  "on paper_1809_11165_amd.inputs.make(%d, n=%d)" % (cfg, n),
+        "config": cfg, "n": n, "d": w.d, "t": w.t, "k": w.k, "iters_run": int(res.iters_run),
+        "pivots": pivots.tolist(), "pivot_dmax": dmax.tolist(), "logdet_precond": P.logdet,
+        "alpha": res.alpha.tolist(), "beta": res.beta.tolist(), "resid": res.resid.tolist(),
+        "rho0": res.rho0.tolist(), "sample_rows": rows.tolist(), "U_sample": res.U[rows].tolist(),
+        "U_colnorm": np.linalg.norm(res.U, axis=0).tolist(), "seconds": time.time() - t0,
+    }
+    path = os.path.join(OUT_DIR, name + ".json")
+    with open(path, "w") as f:
+        json.dump(out, f)
+    print("wrote", path, "in %.0f s" % out["seconds"], flush=True)
+
+
+MATRIX_FREE_CASES = {
+    # name: (config, n, iterations)
+    "cfg4_n200000_p3": (4, 200000, 3),
+}
+
+
 def run(name: str):
+    if name in MATRIX_FREE_CASES:
+        return run_matrix_free(name, *MATRIX_FREE_CASES[name])
     cfg, n, kw = CASES[name]
     w = inputs.make(cfg, n=n, **kw)
     t0 = time.time()
@@ -115,5 +192,5 @@ if __name__ == "__main__":
         OUT_DIR = args[i + 1]
         os.makedirs(OUT_DIR, exist_ok=True)
         del args[i:i + 2]
-    for nm in (args or list(CASES)):
+    for nm in (args or list(CASES) + list(MATRIX_FREE_CASES)):
         run(nm)
