@@ -150,6 +150,58 @@ def nlml_from_terms(yKinvy: float, logdet: float, n: int) -> float:
     return 0.5 * (yKinvy + logdet + n * np.log(2.0 * np.pi))
 
 
+def exact_solve_logdet(Khat: np.ndarray, y: np.ndarray, overwrite: bool = False):
+    """K_hat^{-1} y and log|K_hat| = 2 sum_i log G_ii from the dense Cholesky factor K_hat = G G^T
+    (Sec. 3, "Required operations").  Returns (u0, logdet, factor) with `factor` in the form
+    scipy.linalg.cho_solve takes.
+
+    overwrite=True factorises in the memory of Khat (for matrices that fit only once): the
+    transposed view of the symmetric row-major array is column-major, and its upper factor G^T
+    lands where K_hat was."""
+    if overwrite:
+        factor = (sla.cholesky(Khat.T, lower=False, overwrite_a=True, check_finite=False), False)
+    else:
+        factor = (sla.cholesky(Khat, lower=True), True)
+    u0 = sla.cho_solve(factor, y)
+    logdet = 2.0 * np.sum(np.log(np.diag(factor[0])))
+    return u0, float(logdet), factor
+
+
+def exact_solve_logdet_blocked(Khat: np.ndarray, y: np.ndarray, block: int = 4096):
+    """The same two quantities for matrices with more than 2^31 entries, which the LAPACK build
+    behind scipy does not factorise in one call: textbook right-looking blocked Cholesky in the
+    lower triangle of Khat (overwritten), then blocked forward and back substitution.
+    Returns (u0, logdet)."""
+    n = Khat.shape[0]
+    for j0 in range(0, n, block):
+        j1 = min(n, j0 + block)
+        G11 = sla.cholesky(Khat[j0:j1, j0:j1], lower=True)
+        Khat[j0:j1, j0:j1] = G11
+        if j1 < n:
+            # G21 = A21 G11^{-T}
+            G21 = sla.solve_triangular(G11, Khat[j1:, j0:j1].T, lower=True, check_finite=False).T
+            Khat[j1:, j0:j1] = G21
+            # trailing matrix, lower part: A22 -= G21 G21^T
+            for i0 in range(j1, n, block):
+                i1 = min(n, i0 + block)
+                Khat[i0:i1, j1:i1] -= G21[i0 - j1:i1 - j1] @ G21[:i1 - j1].T
+    logdet = 2.0 * float(np.sum(np.log(np.diag(Khat))))
+    w = np.array(y, dtype=np.float64)
+    for j0 in range(0, n, block):                       # G w = y
+        j1 = min(n, j0 + block)
+        w[j0:j1] = sla.solve_triangular(Khat[j0:j1, j0:j1], w[j0:j1], lower=True, check_finite=False)
+        if j1 < n:
+            w[j1:] -= Khat[j1:, j0:j1] @ w[j0:j1]
+    starts = list(range(0, n, block))
+    for j0 in reversed(starts):                         # G^T u = w
+        j1 = min(n, j0 + block)
+        if j1 < n:
+            w[j0:j1] -= Khat[j1:, j0:j1].T @ w[j1:]
+        w[j0:j1] = sla.solve_triangular(Khat[j0:j1, j0:j1], w[j0:j1], lower=True, trans='T',
+                                        check_finite=False)
+    return w, logdet
+
+
 def exact_inference(kernel: int, X, y, ls, s: float, noise: float,
                     with_traces: bool = True) -> ExactResult:
     X = np.asarray(X, dtype=np.float64)
@@ -157,9 +209,8 @@ def exact_inference(kernel: int, X, y, ls, s: float, noise: float,
     n = X.shape[0]
     Khat = kernel_matrix(kernel, X, ls, s)
     Khat[np.diag_indices(n)] += noise
-    G = sla.cholesky(Khat, lower=True)
-    u0 = sla.cho_solve((G, True), y)
-    logdet = 2.0 * np.sum(np.log(np.diag(G)))
+    u0, logdet, factor = exact_solve_logdet(Khat, y)
+    G = factor[0]
     yKinvy = float(y @ u0)
     if with_traces:
         Kinv = sla.cho_solve((G, True), np.eye(n))

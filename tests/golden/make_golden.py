@@ -160,6 +160,14 @@ def run(name: str):
     other = O.mbcg(panel_mm, res.B, P.solve, it)
     reorder_dev = norm(res.U - other.U) / norm(res.U)
     del other
+    # the plain definition, last because it factorises K_hat in place
+    say("dense Cholesky")
+    if n * n < 2 ** 31:
+        u_exact, logdet_exact, _ = O.exact_solve_logdet(Khat, w.y.astype(np.float64), overwrite=True)
+    else:
+        u_exact, logdet_exact = O.exact_solve_logdet_blocked(Khat, w.y.astype(np.float64))
+    yKinvy_exact = float(w.y.astype(np.float64) @ u_exact)
+    u0_err = float(np.linalg.norm(res.U[:, 0] - u_exact) / np.linalg.norm(u_exact))
     out = {
         "source": "oracle/bbmm_oracle.py bbmm_inference on paper_1809_11165_amd.inputs.make(%d, n=%d)" % (cfg, n),
         "config": cfg, "n": n, "d": w.d, "t": w.t, "k": w.k, "iters_cap": w.iters, "tol": w.tol,
@@ -173,6 +181,8 @@ def run(name: str):
         "sample_rows": rows.tolist(),
         "U_sample": res.U[rows].tolist(),
         "U_colnorm": np.linalg.norm(res.U, axis=0).tolist(),
+        "exact_logdet": logdet_exact, "exact_yKinvy": yKinvy_exact,
+        "u0_sample_exact": u_exact[rows].tolist(), "u0_rel_err_vs_exact": u0_err,
         "U_last_step": last_step.tolist(),
         "U_reorder_dev": reorder_dev.tolist(),
         "seconds": time.time() - t0,

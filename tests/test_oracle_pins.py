@@ -438,3 +438,35 @@ def test_frozen_column_guard():
     assert res.m_valid[1] == 0 and res.m_valid[0] == 5
     ref = O.mbcg(lambda M: Kh @ M, B[:, [0, 2]], P.solve, 5)
     assert np.allclose(res.U[:, [0, 2]], ref.U)
+
+
+def test_exact_solve_logdet_matches_lapack_free_definitions():
+    # log-det against numpy's LU-based slogdet and the eigenvalue sum, solve against the LU solve;
+    # the in-place variant must give the same numbers and really use the caller's memory
+    rng = np.random.default_rng(11)
+    A = rng.standard_normal((40, 40))
+    K = A @ A.T + 0.5 * np.eye(40)
+    y = rng.standard_normal(40)
+    u0, logdet, _ = O.exact_solve_logdet(K, y)
+    assert logdet == pytest.approx(np.linalg.slogdet(K)[1], rel=1e-12)
+    assert logdet == pytest.approx(np.sum(np.log(np.linalg.eigvalsh(K))), rel=1e-12)
+    assert np.allclose(u0, np.linalg.solve(K, y), rtol=1e-10)
+    K2 = K.copy()
+    u1, logdet1, fac = O.exact_solve_logdet(K2, y, overwrite=True)
+    assert logdet1 == pytest.approx(logdet, rel=1e-13)
+    assert np.allclose(u1, u0, rtol=1e-12)
+    assert not np.allclose(K2, K)                 # factorised in place
+    assert np.shares_memory(fac[0], K2)
+
+
+def test_blocked_cholesky_equals_the_single_call():
+    rng = np.random.default_rng(12)
+    A = rng.standard_normal((300, 300))
+    K = A @ A.T + 2.0 * np.eye(300)
+    y = rng.standard_normal(300)
+    u0, logdet, _ = O.exact_solve_logdet(K, y)
+    for block in (64, 100, 300, 512):              # ragged last block, one block, block > n
+        u1, logdet1 = O.exact_solve_logdet_blocked(K.copy(), y, block=block)
+        assert logdet1 == pytest.approx(logdet, rel=1e-13)
+        assert np.allclose(u1, u0, rtol=1e-10, atol=1e-14)
+    assert logdet == pytest.approx(np.linalg.slogdet(K)[1], rel=1e-12)
