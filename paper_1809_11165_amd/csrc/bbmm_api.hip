@@ -261,7 +261,7 @@ int stage_build_khat(bbmm_ctx* c) {
 
 // Vp <- partial products of K_hat with the block in D4; returns the split count and the
 // (scale, add) pair that turns the partial sums into K_hat D.
-int stage_mm(bbmm_ctx* c, int mode, int ld, VpShape* shape, double* scaleV, double* addD) {
+int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scaleV, double* addD) {
   if (mode == BBMM_MODE_MATERIALISED) {
     if (!c->khat_built) return fail(c, BBMM_EINVAL, "materialised product needs bbmm_build_khat first");
     if (ld != 16 && ld != 32) return fail(c, BBMM_EINVAL, "unsupported block width");
@@ -277,7 +277,7 @@ int stage_mm(bbmm_ctx* c, int mode, int ld, VpShape* shape, double* scaleV, doub
   } else if (mode == BBMM_MODE_ONTHEFLY) {
     int ns = otf_split_of(c);
     if (launch_mm_otf(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb),
-                      ptr<float>(c->sq), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld, ns,
+                      ptr<float>(c->sq), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld, cc, ns,
                       ptr<DevState>(c->st)))
       return fail(c, BBMM_EINVAL, "unsupported block width or input dimension");
     *shape = VpShape{ns, nullptr, 1};
@@ -349,7 +349,7 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
     VpShape ns{0, nullptr, 1};
     double scaleV = 1.0, addD = 0.0;
     if (c->time_mm) HIPCHK(c, hipEventRecord(c->ev[2 * j], s));
-    int rc = stage_mm(c, mode, ld, &ns, &scaleV, &addD);
+    int rc = stage_mm(c, mode, cc, ld, &ns, &scaleV, &addD);
     if (rc) return rc;
     if (c->time_mm) {
       HIPCHK(c, hipEventRecord(c->ev[2 * j + 1], s));
@@ -640,7 +640,7 @@ int bbmm_kernel_mm(bbmm_ctx* c, int32_t mode, const float* M, int64_t cc, float*
   launch_pack_d4(s, M, c->n, (int)cc, c->np, ld, ptr<double>(c->D4));
   VpShape ns{0, nullptr, 1};
   double scaleV = 1.0, addD = 0.0;
-  rc = stage_mm(c, mode, ld, &ns, &scaleV, &addD);
+  rc = stage_mm(c, mode, (int)cc, ld, &ns, &scaleV, &addD);
   if (rc) return rc;
   launch_vreduce(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, scaleV, addD, ptr<double>(c->D4), ptr<double>(c->V));
   launch_unpack_rows(s, ptr<double>(c->V), ld, c->n, (int)cc, V);

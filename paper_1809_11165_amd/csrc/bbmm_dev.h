@@ -115,8 +115,9 @@ int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const 
 // plan: one entry per workgroup, laid out by the host (see ensure_mat_plans).
 int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
                   const MmPlan* plan, int wgs, const DevState* st);
+// c: number of columns really used (<= ld); lets 17..20 columns run one MFMA group plus vector FMAs
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
-                  const double* D4, double* Vp, int np, int ld, int nsplit, const DevState* st);
+                  const double* D4, double* Vp, int np, int ld, int c, int nsplit, const DevState* st);
 // derivative pass: one partial row (pstride doubles) per wave, then a fixed-order fp64 sum into
 // st->dk_out.  Returns non-zero when the configuration is not supported.
 int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* Xa, const float* Xb,

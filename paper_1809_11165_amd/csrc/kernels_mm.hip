@@ -242,7 +242,14 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
 // Wave: NJ column blocks (16*NJ output rows of V), a chunk of row blocks to contract over.
 // Distances by fp32 MFMA, kernel function in registers, product with the block by fp64 MFMA.
 // Writes partial sums of (K/s) D; the caller scales by s and adds sigma^2 D.
-template <int KIND, int KK, int NQ, int NJ>
+//
+// NQ groups of 16 right-hand-side columns go through the fp64 MFMA.  NX further columns
+// (16*NQ .. 16*NQ+NX-1) are accumulated with plain fp64 FMAs instead: on this chip an fp64 MFMA
+// runs at the rate of the fp64 vector unit, so a 17th column costs 4 FMAs per tile and lane this
+// way against a whole second MFMA group (4 x 64 cycles) of which 15/16 would be padding.  A lane
+// then holds the sum over its own 4 rows of each tile; the four lane groups are added at the end
+// and stored where the MFMA path would have put them.
+template <int KIND, int KK, int NQ, int NJ, int NX>
 __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
                                                  const float* __restrict__ Xb,
                                                  const float* __restrict__ sq,
@@ -251,7 +258,8 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
                                                  int blocks_per_split,
                                                  const DevState* __restrict__ st) {
   if (st->done) return;
-  constexpr int LD = 16 * NQ;
+  static_assert(NX >= 0 && NX <= 4, "at most 4 columns on the vector unit");
+  constexpr int LD = 16 * (NQ + (NX > 0 ? 1 : 0));
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int nblk = np >> 4;
   int split = blockIdx.x % nsplit;
@@ -262,6 +270,7 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
   float b[NJ][KK];
   float sqj[NJ];
   f64x4 acc[NJ][NQ];
+  double accx[NJ][NX > 0 ? NX : 1];
 #pragma unroll
   for (int jb = 0; jb < NJ; ++jb) {
 #pragma unroll
@@ -269,6 +278,8 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
     sqj[jb] = sq[(jb0 + jb) * 16 + jc];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int x = 0; x < NX; ++x) accx[jb][x] = 0.0;
   }
   int ib_begin = split * blocks_per_split;
   int ib_end = min(nblk, ib_begin + blocks_per_split);
@@ -278,9 +289,13 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
     for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
     f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
     f64x4 dop[NQ];
+    f64x4 dx[NX > 0 ? NX : 1];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
       dop[nq] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+#pragma unroll
+    for (int x = 0; x < NX; ++x)   // rows 4g..4g+3 of column 16 NQ + x (the same for all jc)
+      dx[x] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(NQ * 16 + x)) * 4);
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb) {
       f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
@@ -290,15 +305,32 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
         double e = (double)unit_kernel<KIND>(r2[r]);
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = mfma16d(dop[nq][r], e, acc[jb][nq]);
+#pragma unroll
+        for (int x = 0; x < NX; ++x) accx[jb][x] = fma(e, dx[x][r], accx[jb][x]);
       }
     }
   }
   double* vout = Vp + (size_t)split * np * LD;
 #pragma unroll
-  for (int jb = 0; jb < NJ; ++jb)
+  for (int jb = 0; jb < NJ; ++jb) {
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
       *(f64x4*)(vout + (size_t)((jb0 + jb) * 16 + jc) * LD + nq * 16 + g * 4) = acc[jb][nq];
+    if (NX > 0) {
+      // column 16 NQ + x belongs at position 4 x of the last group (the order the MFMA path
+      // stores its columns in): lane group g writes positions 4g..4g+3, i.e. column g and zeros
+      double mine = 0.0;
+#pragma unroll
+      for (int x = 0; x < NX; ++x) {
+        double v = accx[jb][x];
+        v += __shfl_xor(v, 16, 64);
+        v += __shfl_xor(v, 32, 64);
+        if (g == x) mine = v;
+      }
+      *(f64x4*)(vout + (size_t)((jb0 + jb) * 16 + jc) * LD + NQ * 16 + g * 4) =
+          (f64x4){mine, 0.0, 0.0, 0.0};
+    }
+  }
 }
 
 // ------------------------------------------------------------ derivative pass --
@@ -612,25 +644,37 @@ int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp
 }
 
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
-                  const double* D4, double* Vp, int np, int ld, int nsplit, const DevState* st) {
+                  const double* D4, double* Vp, int np, int ld, int c, int nsplit, const DevState* st) {
   constexpr int NJ = 8;
   int nblk = np / 16;
   int blocks_per_split = (nblk + nsplit - 1) / nsplit;
   int sstrips = (nblk + 4 * NJ - 1) / (4 * NJ);
   int grid = sstrips * nsplit;
-#define OTF(K)                                                                                       \
-  if (kernel == 0 && ld == 16)                                                                       \
-    k_mm_otf<0, K, 1, NJ><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
-  else if (kernel == 0 && ld == 32)                                                                  \
-    k_mm_otf<0, K, 2, NJ><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
-  else if (kernel == 1 && ld == 16)                                                                  \
-    k_mm_otf<1, K, 1, NJ><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
-  else if (kernel == 1 && ld == 32)                                                                  \
-    k_mm_otf<1, K, 2, NJ><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
-  else                                                                                               \
-    return 1
+  // MFMA column groups and columns left to the vector unit: 17..20 columns = one group + 1, 2 or 4
+  int nq = ld / 16, nx = 0;
+  if (ld == 32 && c > 16 && c <= 20) {
+    nq = 1;
+    nx = (c == 17) ? 1 : ((c == 18) ? 2 : 4);
+  }
+  if (ld != 16 && ld != 32) return 1;
+#define OTF_LAUNCH(KIND, K, Q, X) \
+  k_mm_otf<KIND, K, Q, NJ, X><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st)
+#define OTF_KIND(KIND, K)                             \
+  if (nq == 2) OTF_LAUNCH(KIND, K, 2, 0);             \
+  else if (nx == 0) OTF_LAUNCH(KIND, K, 1, 0);        \
+  else if (nx == 1) OTF_LAUNCH(KIND, K, 1, 1);        \
+  else if (nx == 2) OTF_LAUNCH(KIND, K, 1, 2);        \
+  else OTF_LAUNCH(KIND, K, 1, 4)
+#define OTF(K)                  \
+  if (kernel == 0) {            \
+    OTF_KIND(0, K);             \
+  } else {                      \
+    OTF_KIND(1, K);             \
+  }
   FOR_KK(OTF)
 #undef OTF
+#undef OTF_KIND
+#undef OTF_LAUNCH
   return 0;
 }
 

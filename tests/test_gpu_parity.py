@@ -95,8 +95,25 @@ def test_kernel_mm_matches_oracle_product(ctx, mode, kernel, ard, n, d, c):
     M = rng.standard_normal((n, c)).astype(np.float32)
     V = _host(ctx.bbmm_kernel_mm(mode, _dev(M)))
     ref = _khat(w) @ M.astype(np.float64)
-    # fp32 accumulation over n terms of O(1) magnitude
+    # fp32 kernel entries, fp64 sums
     assert _colrel(V, ref) < 1e-4
+
+
+@pytest.mark.parametrize("c", [1, 16, 18, 19, 20, 21, 32])
+def test_kernel_mm_block_widths(ctx, c):
+    # every width class of the right-hand side: one MFMA group, one group plus 1/2/4 columns on
+    # the vector unit (17..20), two groups; each column must come out in its own place
+    w = _case(inputs.MATERN52, True, 777, 5)
+    rng = np.random.default_rng(50 + c)
+    M = rng.standard_normal((w.n, c)).astype(np.float32)
+    ref = _khat(w) @ M.astype(np.float64)
+    for mode in (inputs.MATERIALISED, inputs.ONTHEFLY):
+        ctx.bbmm_setup(_problem(w, mode))
+        if mode == inputs.MATERIALISED:
+            ctx.bbmm_build_khat()
+        V = _host(ctx.bbmm_kernel_mm(mode, _dev(M)))
+        assert V.shape == ref.shape
+        assert _colrel(V, ref) < 1e-4, mode
 
 
 @pytest.mark.parametrize("c", [11, 20])
