@@ -478,3 +478,42 @@ def bbmm_inference(kernel: int, X, y, ls, s: float, noise: float, E1, E2, k: int
                       yKinvy=yKinvy, trace=trace, quad=quad,
                       nlml=nlml_from_terms(yKinvy, logdet, n), grad=0.5 * (trace - quad),
                       L=L, pivots=pivots, pivot_dmax=dmax, mbcg=res, B=B)
+
+
+# ----------------------------------------------------------------------------
+# Predictive distribution at test inputs (Sec. 2, Eq. (1), zero prior mean):
+#   mean(x*)       = k_{X x*}^T K_hat^{-1} y
+#   cov(x*, x*')   = k(x*, x*') - k_{X x*}^T K_hat^{-1} k_{X x*'}      (latent f; add sigma^2 for y)
+# ----------------------------------------------------------------------------
+def exact_predict(kernel: int, X, y, ls, s: float, noise: float, Xs):
+    """The plain definition through the dense Cholesky factor.  Returns (mean, cov), cov ns x ns."""
+    X = np.asarray(X, dtype=np.float64)
+    Xs = np.asarray(Xs, dtype=np.float64)
+    y = np.asarray(y, dtype=np.float64)
+    n = X.shape[0]
+    Khat = kernel_matrix(kernel, X, ls, s)
+    Khat[np.diag_indices(n)] += noise
+    KXs = kernel_block(kernel, X, Xs, ls, s)                  # n x ns, columns k_{X x*}
+    u0, _, factor = exact_solve_logdet(Khat, y)
+    mean = KXs.T @ u0
+    cov = kernel_block(kernel, Xs, Xs, ls, s) - KXs.T @ sla.cho_solve(factor, KXs)
+    return mean, cov
+
+
+def bbmm_predict(kernel: int, X, ls, s: float, noise: float, Xs, u0: np.ndarray,
+                 P: "Preconditioner", p: int, tol: float = 0.0, Khat: Optional[np.ndarray] = None):
+    """The same two quantities the way the method obtains them: the mean from a solve u0 that is
+    already there, the variances from one more preconditioned mBCG run (Alg. 2) whose right-hand
+    sides are the columns k_{X x*}.  Returns (mean, var, MbcgResult)."""
+    X = np.asarray(X, dtype=np.float64)
+    Xs = np.asarray(Xs, dtype=np.float64)
+    n = X.shape[0]
+    if Khat is None:
+        Khat = kernel_matrix(kernel, X, ls, s)
+        Khat[np.diag_indices(n)] += noise
+    KXs = kernel_block(kernel, X, Xs, ls, s)
+    mean = KXs.T @ np.asarray(u0, dtype=np.float64)
+    res = mbcg(lambda M: Khat @ M, KXs, P.solve, p, tol)
+    prior = np.array([kernel_block(kernel, Xs[a:a + 1], Xs[a:a + 1], ls, s)[0, 0] for a in range(Xs.shape[0])])
+    var = prior - np.sum(KXs * res.U, axis=0)
+    return mean, var, res

@@ -470,3 +470,70 @@ def test_blocked_cholesky_equals_the_single_call():
         assert logdet1 == pytest.approx(logdet, rel=1e-13)
         assert np.allclose(u1, u0, rtol=1e-10, atol=1e-14)
     assert logdet == pytest.approx(np.linalg.slogdet(K)[1], rel=1e-12)
+
+
+# ---------------------------------------------------------------- predictions (Eq. (1)) ---
+def test_predictive_one_training_point_closed_form():
+    # n = 1: mean = k(x*, x) y / (s + sigma^2), var = s - k(x*, x)^2 / (s + sigma^2)
+    X = np.array([[0.3, -0.2]])
+    y = np.array([1.7])
+    Xs = np.array([[0.5, 0.1], [0.3, -0.2], [40.0, 40.0]])
+    ls, s, noise = np.array([0.7, 1.3]), 1.9, 0.05
+    for kernel in (O.RBF, O.MATERN52):
+        mean, cov = O.exact_predict(kernel, X, y, ls, s, noise, Xs)
+        k = O.kernel_block(kernel, Xs, X, ls, s)[:, 0]
+        assert np.allclose(mean, k * y[0] / (s + noise), rtol=1e-13)
+        assert np.allclose(np.diag(cov), s - k * k / (s + noise), rtol=1e-12)
+        assert np.allclose(cov[0, 1], O.kernel_block(kernel, Xs[:1], Xs[1:2], ls, s)[0, 0] - k[0] * k[1] / (s + noise),
+                           rtol=1e-12)
+    assert k[1] == pytest.approx(s)                      # test point on the training point
+    assert abs(mean[2]) < 1e-6 and cov[2, 2] == pytest.approx(s, rel=1e-6)   # far away: the prior
+
+
+def test_predictive_interpolates_and_is_a_valid_covariance():
+    w = inputs.tiny(40, 2, kernel=inputs.RBF, t=3, k=4, noise=1e-2, seed=4)
+    mean, cov = O.exact_predict(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.X[:7])
+    # at training inputs K K_hat^{-1} = I - sigma^2 K_hat^{-1}: mean = y - sigma^2 u0 and
+    # cov = sigma^2 (I - sigma^2 K_hat^{-1}); both shrink to interpolation as sigma^2 -> 0
+    Khat = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale) + w.noise * np.eye(w.n)
+    Kinv = np.linalg.inv(Khat)
+    assert np.allclose(mean, (w.y - w.noise * (Kinv @ w.y))[:7], rtol=1e-9, atol=1e-12)
+    assert np.allclose(cov, w.noise * (np.eye(w.n) - w.noise * Kinv)[:7, :7], rtol=1e-7, atol=1e-11)
+    assert np.all(np.diag(cov) < w.noise) and np.all(np.diag(cov) > 0)
+    rng = np.random.default_rng(3)
+    Xs = rng.uniform(-1, 2, size=(9, 2))
+    w.noise = 0.1
+    mean, cov = O.exact_predict(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, Xs)
+    ev = np.linalg.eigvalsh(cov)
+    assert ev.min() > -1e-10 and np.all(np.diag(cov) <= w.outputscale + 1e-12)
+    # independent route: joint Gaussian of (y, f*) conditioned by the Schur complement of the
+    # (n + ns) x (n + ns) covariance, via an explicit inverse
+    K = O.kernel_matrix(w.kernel, np.vstack([w.X.astype(np.float64), Xs]), w.lengthscale, w.outputscale)
+    n = w.n
+    Kyy = K[:n, :n] + w.noise * np.eye(n)
+    A = np.linalg.inv(Kyy)
+    assert np.allclose(mean, K[n:, :n] @ A @ w.y, rtol=1e-8, atol=1e-10)
+    assert np.allclose(cov, K[n:, n:] - K[n:, :n] @ A @ K[:n, n:], rtol=1e-8, atol=1e-10)
+
+
+def test_bbmm_predict_reaches_the_definition():
+    w = inputs.tiny(60, 3, kernel=inputs.MATERN52, ard=True, t=3, k=6, noise=0.2, seed=9)
+    rng = np.random.default_rng(5)
+    Xs = rng.standard_normal((5, 3))
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)
+    L, piv, _ = O.pivoted_cholesky(np.diag(K).copy(), lambda i: K[i], w.k)
+    P = O.make_preconditioner(L, w.noise)
+    ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, with_traces=False)
+    mean_e, cov_e = O.exact_predict(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, Xs)
+    mean, var, res = O.bbmm_predict(w.kernel, w.X, w.lengthscale, w.outputscale, w.noise, Xs, ex.u0, P, 60)
+    assert np.allclose(mean, mean_e, rtol=1e-10)
+    assert np.allclose(var, np.diag(cov_e), rtol=1e-8)           # CG run to p = n
+    # a few iterations only: variance estimates from CG iterates decrease towards the exact value
+    # (u_a^T b_a = b^T K^-1 b - |error|^2_K grows monotonically)
+    v_prev = None
+    for p in (1, 3, 6, 12):
+        _, v, _ = O.bbmm_predict(w.kernel, w.X, w.lengthscale, w.outputscale, w.noise, Xs, ex.u0, P, p)
+        assert np.all(v >= np.diag(cov_e) - 1e-10)
+        if v_prev is not None:
+            assert np.all(v <= v_prev + 1e-12)
+        v_prev = v
