@@ -207,6 +207,26 @@ int bbmm_slq_logdet(bbmm_ctx* ctx, double* logdet, double* slq_terms);
  * trace, quad: host, n_lengthscale + 2 entries each. */
 int bbmm_dk_traces(bbmm_ctx* ctx, const float* U, const float* W, double* trace, double* quad);
 
+/* ------------------------------------------------------------------------
+ * Predictive distribution at test inputs (Sec. 2, Eq. (1), zero prior mean).
+ * Both need bbmm_setup (or a completed bbmm_solve_logdet_grad) for the same
+ * training data and hyperparameters; Xstar is device memory, ns x d float,
+ * in the coordinates of X.
+ * ---------------------------------------------------------------------- */
+
+/* mean[a] = k_{X x*_a}^T u0 with u0 = K_hat^{-1} y (device, n float; e.g. the u0 of
+ * bbmm_solve_logdet_grad).  mean: device, ns float.  Kernel values in fp64 from X. */
+int bbmm_predict_mean(bbmm_ctx* ctx, const float* Xstar, int64_t ns, const float* u0, float* mean);
+
+/* var[a] = k(x*_a, x*_a) - k_{X x*_a}^T K_hat^{-1} k_{X x*_a} (latent function; add sigma^2 for
+ * observations): one preconditioned mBCG run (Alg. 2) whose right-hand sides are the columns
+ * k_{X x*_a}, with the context's preconditioner, iteration cap and tolerance.  1 <= ns <= 32 per
+ * call.  var: device, ns float.  iters_run, max_resid (largest relative residual over the columns
+ * at the last iteration): host, optional.  Needs bbmm_precond_setup (and bbmm_build_khat for
+ * MATERIALISED); overwrites the solves and coefficient histories held in the context. */
+int bbmm_predict_var(bbmm_ctx* ctx, int32_t mode, const float* Xstar, int64_t ns, float* var,
+                     int64_t* iters_run, double* max_resid);
+
 #ifdef __cplusplus
 }
 #endif

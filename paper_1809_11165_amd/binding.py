@@ -28,6 +28,7 @@ EXPORTS = [
     "bbmm_setup", "bbmm_build_khat", "bbmm_khat_block", "bbmm_kernel_mm", "bbmm_pivoted_cholesky",
     "bbmm_precond_setup", "bbmm_precond_solve", "bbmm_make_probes", "bbmm_mbcg",
     "bbmm_tridiag_eig_batched", "bbmm_slq_logdet", "bbmm_dk_traces",
+    "bbmm_predict_mean", "bbmm_predict_var",
 ]
 
 
@@ -98,6 +99,9 @@ def load_library() -> C.CDLL:
     lib.bbmm_slq_logdet.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.bbmm_dk_traces.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double),
                                    C.POINTER(C.c_double)]
+    lib.bbmm_predict_mean.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    lib.bbmm_predict_var.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
+                                     C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     _lib = lib
     return lib
 
@@ -245,6 +249,7 @@ class Context:
         r.slq_terms = _dbl(slq)
         self._ck(self.lib.bbmm_solve_logdet_grad(self.h, C.byref(p), C.byref(r)))
         self._prob = prob
+        self._shape = (int(p.n), int(p.d), int(p.t), int(p.k), int(p.max_iters), int(p.n_lengthscale))
         return Result(u0=u0, U=U, logdet=r.logdet, logdet_precond=r.logdet_precond, yKinvy=r.yKinvy,
                       nlml=r.nlml, trace=trace, quad=quad, grad_nlml=grad, iters_run=int(r.iters_run),
                       rank=int(r.rank), alpha=alpha, beta=beta, resid=resid, pivots=pivots[:k],
@@ -334,6 +339,25 @@ class Context:
         trace, quad = np.zeros(nl + 2), np.zeros(nl + 2)
         self._ck(self.lib.bbmm_dk_traces(self.h, _dptr(U), _dptr(W), _dbl(trace), _dbl(quad)))
         return trace, quad
+
+    def bbmm_predict_mean(self, Xstar, u0):
+        n, d = self._shape[0], self._shape[1]
+        ns = Xstar.shape[0]
+        _check_dev(Xstar, (ns, d), "Xstar")
+        _check_dev(u0, (n,), "u0")
+        mean = self._empty(ns)
+        self._ck(self.lib.bbmm_predict_mean(self.h, _dptr(Xstar), ns, _dptr(u0), _dptr(mean)))
+        return mean
+
+    def bbmm_predict_var(self, mode: int, Xstar):
+        d = self._shape[1]
+        ns = Xstar.shape[0]
+        _check_dev(Xstar, (ns, d), "Xstar")
+        var = self._empty(ns)
+        iters, resid = C.c_int64(0), C.c_double(0.0)
+        self._ck(self.lib.bbmm_predict_var(self.h, mode, _dptr(Xstar), ns, _dptr(var), C.byref(iters),
+                                           C.byref(resid)))
+        return var, int(iters.value), float(resid.value)
 
 
 def problem_from_workload(w, mode: int, device="cuda:0") -> Problem:

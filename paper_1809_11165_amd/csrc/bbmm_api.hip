@@ -734,6 +734,47 @@ int bbmm_mbcg(bbmm_ctx* c, int32_t mode, const float* B, int64_t cc, float* U, d
   return BBMM_OK;
 }
 
+int bbmm_predict_mean(bbmm_ctx* c, const float* Xstar, int64_t ns, const float* u0, float* mean) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!Xstar || !u0 || !mean || ns < 1 || ns > (1 << 30)) return fail(c, BBMM_EINVAL, "bad test block");
+  hipStream_t s = c->stream;
+  launch_pack_rows(s, u0, c->n, 1, 16, ptr<double>(c->tmpB));
+  launch_cross_dot(s, c->prob.X, Xstar, c->n, (int)ns, c->hyp, ptr<double>(c->tmpB), 16, 0, 0.0, 1.0, mean);
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int bbmm_predict_var(bbmm_ctx* c, int32_t mode, const float* Xstar, int64_t ns, float* var,
+                     int64_t* iters_run, double* max_resid) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!Xstar || !var || ns < 1 || ns > BBMM_MAXC)
+    return fail(c, BBMM_EINVAL, "bad test block (1 <= ns <= 32 per call)");
+  if (!c->pre_done) return fail(c, BBMM_EINVAL, "bbmm_precond_setup must run first");
+  hipStream_t s = c->stream;
+  int ld = ld_for((int)ns);
+  launch_cross_block(s, c->prob.X, Xstar, c->n, (int)ns, ld, c->hyp, ptr<double>(c->R));
+  rc = stage_mbcg(c, mode, (int)ns, ld);
+  if (rc) return rc;
+  launch_cross_dot(s, c->prob.X, Xstar, c->n, (int)ns, c->hyp, ptr<double>(c->U), ld, 1,
+                   c->prob.outputscale, -1.0, var);
+  rc = fetch_state(c, true);
+  if (rc) return rc;
+  rc = device_status(c);
+  if (rc) return rc;
+  int it = c->h_st->iters_run;
+  if (iters_run) *iters_run = it;
+  if (max_resid) {
+    double m = 0.0;
+    if (it > 0)
+      for (int q = 0; q < (int)ns; ++q)
+        m = std::max(m, c->h_hist[(size_t)2 * BBMM_MAXP * BBMM_MAXC + (size_t)(it - 1) * BBMM_MAXC + q]);
+    *max_resid = m;
+  }
+  return BBMM_OK;
+}
+
 int bbmm_tridiag_eig_batched(bbmm_ctx* c, const double* diag, const double* off, int64_t m, int64_t batch,
                              double* eigvals, double* first_row) {
   if (!c) return BBMM_EINVAL;

@@ -103,6 +103,10 @@ void launch_zd(hipStream_t s, int init, int n, int ld, int kp, double noise, con
                const double* L, double* D4, double* Z0, DevState* st, int nblocks);
 void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, const double* R,
                          const double* L, double* Z, DevState* st, int nblocks);
+void launch_cross_block(hipStream_t s, const float* X, const float* Xs, int n, int ns, int ld, HypArgs hyp,
+                        double* B);
+void launch_cross_dot(hipStream_t s, const float* X, const float* Xs, int n, int ns, HypArgs hyp,
+                      const double* V, int ldv, int percol, double prior, double sign, float* out);
 void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, DevState* st);
 void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,
                         double* eigvals, double* first_row);

@@ -394,6 +394,54 @@ __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int
   }
 }
 
+// --------------------------------------------- predictions at test inputs ----
+// k(x_j, x*_a) in fp64 from the raw inputs (Sec. 2, Eq. (1) needs the columns k_{X x*}).
+__device__ inline double cross_value_f64(const float* __restrict__ X, int j,
+                                         const float* __restrict__ Xs, int a, const HypArgs& hyp) {
+  double rho2 = 0.0;
+  for (int dim = 0; dim < hyp.d; ++dim) {
+    double df = ((double)X[(size_t)j * hyp.d + dim] - (double)Xs[(size_t)a * hyp.d + dim]) *
+                hyp.inv_ls[dim];
+    rho2 += df * df;
+  }
+  if (hyp.kernel == 0) return hyp.outputscale * exp(-0.5 * rho2);
+  double rho = sqrt(rho2);
+  const double s5 = 2.23606797749978969;
+  return hyp.outputscale * (1.0 + s5 * rho + (5.0 / 3.0) * rho2) * exp(-s5 * rho);
+}
+
+// B[j][a] = k(x_j, x*_a): the right-hand-side block of the variance solves (stride ld, zero padded)
+__global__ void k_cross_block(const float* __restrict__ X, const float* __restrict__ Xs, int n,
+                              int ns, int ld, HypArgs hyp, double* __restrict__ B) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)n * ld) return;
+  int j = (int)(idx / ld), a = (int)(idx % ld);
+  B[idx] = (a < ns) ? cross_value_f64(X, j, Xs, a, hyp) : 0.0;
+}
+
+// out[a] = prior + sign * sum_j k(x*_a, x_j) V[j][percol ? a : 0], one block per test point,
+// fixed-order fp64 block sum.  Mean: V = K_hat^{-1} y, prior 0, sign +1.  Variance: V = the
+// solves of the block above, prior k(x*, x*) = s (both kernels are stationary), sign -1.
+__global__ __launch_bounds__(VT) void k_cross_dot(const float* __restrict__ X,
+                                                   const float* __restrict__ Xs, int n,
+                                                   HypArgs hyp, const double* __restrict__ V,
+                                                   int ldv, int percol, double prior, double sign,
+                                                   float* __restrict__ out) {
+  __shared__ double red[VT];
+  int a = blockIdx.x;
+  int col = percol ? a : 0;
+  double acc = 0.0;
+  for (int j = threadIdx.x; j < n; j += VT)
+    acc += cross_value_f64(X, j, Xs, a, hyp) * V[(size_t)j * ldv + col];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = VT / 2; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[a] = (float)(prior + sign * red[0]);
+}
+
 // ---------------------------------------------- capacitance matrix, log|P| ---
 // C = sigma^2 I + L^T L (k x k, fp64), Cholesky factor G, log|P| = log|C| + (n-k) log sigma^2.
 __global__ __launch_bounds__(VT) void k_pre_setup(const double* __restrict__ L, int n, int kp,
@@ -1257,6 +1305,16 @@ void launch_psolve_apply(hipStream_t s, int n, int ld, int kp, double noise, con
 #define ZD_APPLY(KP, NQ) k_zd<KP, NQ, 2>
   DISPATCH_KP_NQ(ZD_APPLY, kp, nq, nblocks, VT, n, noise, R, L, (double*)nullptr, Z, st);
 #undef ZD_APPLY
+}
+
+void launch_cross_block(hipStream_t s, const float* X, const float* Xs, int n, int ns, int ld, HypArgs hyp,
+                        double* B) {
+  k_cross_block<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(X, Xs, n, ns, ld, hyp, B);
+}
+
+void launch_cross_dot(hipStream_t s, const float* X, const float* Xs, int n, int ns, HypArgs hyp,
+                      const double* V, int ldv, int percol, double prior, double sign, float* out) {
+  k_cross_dot<<<ns, VT, 0, s>>>(X, Xs, n, hyp, V, ldv, percol, prior, sign, out);
 }
 
 void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, DevState* st) {
