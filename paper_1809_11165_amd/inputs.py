@@ -25,6 +25,7 @@ MATERN52 = 1
 
 MATERIALISED = 0
 ONTHEFLY = 1
+SGPR = 2                        # subset-of-regressors covariance K_XU K_UU^-1 K_UX + sigma^2 I
 
 
 @dataclass
@@ -46,6 +47,8 @@ class Workload:
     E2: np.ndarray              # (n, t) float32, entries +-1
     modes: tuple = (MATERIALISED, ONTHEFLY)
     meta: dict = field(default_factory=dict)
+    Uind: Optional[np.ndarray] = None   # (m, d) float32 inducing inputs (SGPR workloads only)
+    jitter_rel: float = 0.0             # K_UU gets jitter_rel * outputscale on its diagonal
 
     @property
     def n(self) -> int:
@@ -131,9 +134,32 @@ def config4(n: int = 200000, t: int = 16, k: int = 20, iters: int = 100, salt: i
                    re2, re1, modes=(ONTHEFLY,))
 
 
+def with_inducing(w: Workload, m: int, rng: np.random.Generator, jitter_rel: float = 1e-6) -> Workload:
+    """Turns `w` into an SGPR workload: m inducing inputs = rows of X chosen by a seeded permutation."""
+    rows = np.sort(rng.permutation(w.n)[:m])
+    w.Uind = np.ascontiguousarray(w.X[rows])
+    w.jitter_rel = float(jitter_rel)
+    w.modes = (SGPR,)
+    w.meta["inducing_rows"] = rows
+    return w
+
+
+def config5(n: int = 500000, m: int = 1024, t: int = 10, k: int = 10, iters: int = 50,
+            salt: int = 0) -> Workload:
+    """SGPR, RBF, d = 8, X ~ U[-1,1]^d, y = prod_j cos(x_j) + 0.1 N(0,1); l = 1, s = 1, sigma^2 = 0.01;
+    m inducing inputs drawn from X; K_UU jitter 1e-6 s."""
+    rx, rw, rn, re2, re1 = _streams(5, salt)
+    d = 8
+    X = rx.uniform(-1.0, 1.0, size=(n, d))
+    y = np.prod(np.cos(X), axis=1) + 0.1 * rn.standard_normal(n)
+    w = _finish("cfg5_sgpr_rbf_n%d_m%d_d8" % (n, m), RBF, X, y, [1.0], 1.0, 0.01, t, k, iters, 0.0,
+                re2, re1)
+    return with_inducing(w, m, rw)
+
+
 def make(cfg: int, n: Optional[int] = None, **kw) -> Workload:
-    """Workload `cfg` (1..4); `n` overrides the number of points, keeping the recipe."""
-    fn = {1: config1, 2: config2, 3: config3, 4: config4}[cfg]
+    """Workload `cfg` (1..5); `n` overrides the number of points, keeping the recipe."""
+    fn = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}[cfg]
     if n is not None:
         kw["n"] = n
     return fn(**kw)
@@ -147,3 +173,11 @@ def tiny(n: int, d: int, kernel: int = RBF, ard: bool = False, t: int = 3, k: in
     y = np.sin(X.sum(axis=1)) + 0.1 * rn.standard_normal(n)
     ls = rw.uniform(0.6, 1.6, size=d) if ard else np.array([0.9])
     return _finish("tiny_n%d_d%d" % (n, d), kernel, X, y, ls, 1.3, noise, t, k, iters, 0.0, re2, re1)
+
+
+def tiny_sgpr(n: int, d: int, m: int, kernel: int = RBF, ard: bool = False, t: int = 3, k: int = 2,
+              iters: int = 5, noise: float = 0.1, seed: int = 0, jitter_rel: float = 1e-6) -> Workload:
+    """Small SGPR instance: `tiny` plus m inducing inputs drawn from its X."""
+    w = tiny(n, d, kernel=kernel, ard=ard, t=t, k=k, iters=iters, noise=noise, seed=seed)
+    rng = np.random.Generator(np.random.Philox(np.random.SeedSequence([BASE_SEED + 95, seed, n, m])))
+    return with_inducing(w, m, rng, jitter_rel)

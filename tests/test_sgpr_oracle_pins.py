@@ -1,0 +1,179 @@
+"""Pins for the SGPR (subset-of-regressors) half of the fp64 oracle: every function is checked
+against something other than itself -- the exact-GP limit U = X, Nystrom identities, dense linear
+algebra, finite differences, the finite-termination property of CG on a rank-m-plus-identity
+matrix, exhaustive probe enumeration.  CPU only."""
+import itertools
+
+import numpy as np
+import pytest
+import scipy.linalg as sla
+
+from oracle import bbmm_oracle as O
+from oracle import sgpr_oracle as S
+from paper_1809_11165_amd import inputs
+
+
+def _parts(w, jitter=None):
+    j = w.jitter_rel if jitter is None else jitter
+    return S.sor_parts(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.noise, j)
+
+
+def test_inducing_set_equal_to_X_recovers_the_exact_gp():
+    # U = X and jitter -> 0:  Q = K (K + jI)^{-1} K = K - jI + O(j^2)
+    w = inputs.tiny(24, 3, kernel=O.MATERN52, ard=True)
+    w.Uind = w.X.copy()
+    j = 1e-9
+    parts = S.sor_parts(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.noise, j)
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)
+    assert np.allclose(S.sor_dense_q(parts), K, atol=1e-6)
+    ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, with_traces=False)
+    sx = S.sor_exact_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise, j,
+                               with_traces=False)
+    assert np.allclose(sx.u0, ex.u0, rtol=1e-5, atol=1e-7)
+    assert sx.logdet == pytest.approx(ex.logdet, rel=1e-6)
+
+
+def test_nystrom_identities():
+    w = inputs.tiny_sgpr(40, 3, 9, kernel=O.RBF, seed=2)
+    parts = _parts(w)
+    Q = S.sor_dense_q(parts)
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)
+    rows = w.meta["inducing_rows"]
+    # exact on the inducing rows up to the jitter: Q_UU = K_UU (K_UU + jI)^{-1} K_UU
+    assert np.allclose(Q[np.ix_(rows, rows)], K[np.ix_(rows, rows)], atol=10 * w.jitter_rel * w.outputscale)
+    # symmetric PSD of rank m, and never above the full kernel matrix (K - Q is PSD)
+    assert np.allclose(Q, Q.T, atol=1e-12)
+    ev = np.linalg.eigvalsh(Q)
+    assert ev[-9] > 1e-6 and abs(ev[:-9]).max() < 1e-9
+    assert np.linalg.eigvalsh(K - Q).min() > -1e-8
+    # diagonal and rows as the matrix-free accessors give them
+    assert np.allclose(parts.q_diag(), np.diag(Q), rtol=1e-10)
+    for i in (0, 7, 39):
+        assert np.allclose(parts.q_row(i), Q[i], rtol=1e-9, atol=1e-12)
+    M = np.random.default_rng(0).standard_normal((40, 4))
+    assert np.allclose(parts.khat_matmul(M), Q @ M + w.noise * M, rtol=1e-10)
+
+
+def test_one_inducing_point_closed_form():
+    # m = 1: Q_ij = k(x_i,u) k(x_j,u) / (k(u,u) + j s)
+    X = np.array([[0.0], [1.0], [3.0]])
+    U = np.array([[1.0]])
+    s, l, j = 2.0, 1.5, 1e-3
+    parts = S.sor_parts(O.RBF, X, U, [l], s, 0.1, j)
+    kv = s * np.exp(-0.5 * (X[:, 0] - 1.0) ** 2 / l ** 2)
+    assert np.allclose(S.sor_dense_q(parts), np.outer(kv, kv) / (s + j * s), rtol=1e-13)
+
+
+def test_woodbury_solve_and_logdet_against_dense_cholesky():
+    w = inputs.tiny_sgpr(60, 4, 11, kernel=O.MATERN52, ard=True, seed=1)
+    parts = _parts(w)
+    Khat = S.sor_dense_q(parts) + w.noise * np.eye(w.n)
+    u_ref = np.linalg.solve(Khat, w.y.astype(np.float64))
+    ld_ref = np.linalg.slogdet(Khat)[1]
+    u0, ld = S.sor_woodbury(parts, w.y)
+    assert np.allclose(u0, u_ref, rtol=1e-9, atol=1e-12)
+    assert ld == pytest.approx(ld_ref, rel=1e-11)
+    ex = S.sor_exact_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise,
+                               w.jitter_rel, with_traces=False)
+    assert np.allclose(ex.u0, u_ref, rtol=1e-9, atol=1e-12)
+    assert ex.logdet == pytest.approx(ld_ref, rel=1e-11)
+
+
+@pytest.mark.parametrize("kernel,ard", [(O.RBF, False), (O.RBF, True), (O.MATERN52, False), (O.MATERN52, True)])
+def test_sor_gradient_by_finite_differences_of_the_dense_nlml(kernel, ard):
+    w = inputs.tiny_sgpr(30, 3, 7, kernel=kernel, ard=ard, seed=4, jitter_rel=1e-4)
+    theta = np.concatenate([w.lengthscale, [w.outputscale, w.noise]])
+    nl = w.lengthscale.shape[0]
+
+    def nlml(th):
+        parts = S.sor_parts(kernel, w.X, w.Uind, th[:nl], th[nl], th[nl + 1], w.jitter_rel)
+        Khat = S.sor_dense_q(parts) + th[nl + 1] * np.eye(w.n)
+        G = sla.cholesky(0.5 * (Khat + Khat.T), lower=True)
+        a = sla.cho_solve((G, True), w.y.astype(np.float64))
+        return 0.5 * (w.y @ a + 2 * np.sum(np.log(np.diag(G))) + w.n * np.log(2 * np.pi))
+
+    ex = S.sor_exact_inference(kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise, w.jitter_rel)
+    for h in range(theta.shape[0]):
+        e = np.zeros_like(theta)
+        e[h] = 1e-5 * max(1.0, abs(theta[h]))
+        fd = (nlml(theta + e) - nlml(theta - e)) / (2 * e[h])
+        assert ex.grad[h] == pytest.approx(fd, rel=2e-5, abs=1e-6), h
+
+
+def test_dq_ds_is_q_over_s_and_matrix_free_products_match_dense():
+    w = inputs.tiny_sgpr(35, 3, 8, kernel=O.RBF, ard=True, seed=5)
+    parts = _parts(w)
+    mats = S.sor_khat_derivatives(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel)
+    nl = w.lengthscale.shape[0]
+    assert np.allclose(mats[nl], S.sor_dense_q(parts) / w.outputscale, rtol=1e-9, atol=1e-12)
+    assert np.allclose(mats[nl + 1], np.eye(w.n))
+    rng = np.random.default_rng(1)
+    A = rng.standard_normal((w.n, 4))
+    B = rng.standard_normal((w.n, 4))
+    got = S.sor_derivative_products(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel,
+                                    parts, A, B, row_chunk=16)
+    for h in range(nl + 1):
+        assert got[h] == pytest.approx(np.sum(A * (mats[h] @ B)), rel=1e-9, abs=1e-11)
+
+
+def test_cg_on_rank_m_plus_identity_terminates_in_m_plus_1_iterations():
+    # K_hat = Q + sigma^2 I has at most m + 1 distinct eigenvalues, so unpreconditioned CG is exact
+    # after m + 1 iterations; this pins operator, mBCG signs and indices together
+    w = inputs.tiny_sgpr(50, 3, 5, kernel=O.RBF, seed=6, noise=0.3)
+    parts = _parts(w)
+    P0 = O.make_preconditioner(np.zeros((w.n, 0)), w.noise)
+    B = np.stack([w.y.astype(np.float64), np.cos(np.arange(w.n))], axis=1)
+    u_ref, _ = S.sor_woodbury(parts, B[:, 0])
+    res = O.mbcg(parts.khat_matmul, B, P0.solve, 6)
+    assert np.allclose(res.U[:, 0], u_ref, rtol=1e-7, atol=1e-9)
+    assert res.resid[-1].max() < 1e-7
+    assert res.resid[3].min() > 1e-5      # and not earlier
+
+
+def test_rank_m_pivoted_cholesky_reconstructs_q_and_full_preconditioner_is_exact():
+    w = inputs.tiny_sgpr(40, 3, 6, kernel=O.MATERN52, seed=7, k=6, t=4, iters=3)
+    parts = _parts(w)
+    Q = S.sor_dense_q(parts)
+    L, piv, dmax = O.pivoted_cholesky(parts.q_diag(), parts.q_row, 6)
+    assert len(set(piv.tolist())) == 6
+    assert np.allclose(L @ L.T, Q, atol=1e-8)
+    assert np.all(np.diff(dmax) <= 1e-12)
+    # k = m: P = K_hat, one iteration, log-det equals log|P| equals the Woodbury value
+    r = S.sor_bbmm_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise,
+                             w.jitter_rel, w.E1, w.E2, 6, 3)
+    u_ref, ld_ref = S.sor_woodbury(parts, w.y)
+    assert np.allclose(r.u0, u_ref, rtol=1e-6, atol=1e-9)
+    assert r.logdet_precond == pytest.approx(ld_ref, rel=1e-8)
+    assert r.logdet == pytest.approx(ld_ref, rel=1e-6)
+
+
+def test_sor_bbmm_estimators_average_exactly_over_all_probes():
+    # all 2^(n+k) sign patterns of (e1, e2): the mean of the SLQ terms is log|K_hat| - log|P| and
+    # the mean of the trace terms is Tr(K_hat^{-1} dK_hat/dtheta), when every run is exact (p = n)
+    n, m, k = 7, 3, 2
+    w = inputs.tiny_sgpr(n, 2, m, kernel=O.RBF, seed=8, k=k, noise=0.4, jitter_rel=1e-3)
+    ex = S.sor_exact_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise, w.jitter_rel)
+    signs = np.array(list(itertools.product([-1.0, 1.0], repeat=n + k)))
+    E1 = signs[:, :k].T
+    E2 = signs[:, k:].T
+    r = S.sor_bbmm_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise,
+                             w.jitter_rel, E1, E2, k, n)
+    assert r.logdet == pytest.approx(ex.logdet, rel=1e-8)
+    assert np.allclose(r.trace, ex.trace, rtol=1e-7)
+    assert np.allclose(r.quad, ex.quad, rtol=1e-7)
+    assert np.allclose(r.u0, ex.u0, rtol=1e-8)
+
+
+def test_sor_bbmm_against_exact_on_a_moderate_problem():
+    w = inputs.tiny_sgpr(600, 4, 48, kernel=O.RBF, seed=9, k=8, t=10, iters=40, noise=0.05)
+    parts = _parts(w)
+    r = S.sor_bbmm_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise,
+                             w.jitter_rel, w.E1, w.E2, w.k, w.iters)
+    u_ref, ld_ref = S.sor_woodbury(parts, w.y)
+    assert np.linalg.norm(r.u0 - u_ref) / np.linalg.norm(u_ref) < 1e-6
+    assert r.logdet == pytest.approx(ld_ref, rel=2e-2)
+    ex = S.sor_exact_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise, w.jitter_rel)
+    assert np.allclose(r.quad, ex.quad, rtol=1e-5)
+    # Hutchinson with t = 10: the outputscale and noise traces are sums of positive terms; the
+    # lengthscale trace is a small difference of large ones and only unbiased (enumeration test)
+    assert np.allclose(r.trace[1:], ex.trace[1:], rtol=0.2)
