@@ -5,7 +5,11 @@ One "step" is one full bbmm_solve_logdet_grad call (preconditioner, probes, mBCG
 log-det, derivative traces) on the n = 50,000, d = 16, t = 10 Matern-5/2 ARD workload
 (rank-20 preconditioner, 50 mBCG iterations), inputs resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode mat|otf] [--n N] [--no-cpu]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode mat|otf|sgpr] [--n N] [--no-cpu]
+
+--mode sgpr measures the widened path instead (config 5: subset-of-regressors covariance,
+n = 500,000, m = 1024 inducing inputs, d = 8, t = 10, rank-10 preconditioner, 50 iterations);
+the default line is the exact-GP workload above.
 """
 import argparse
 import json
@@ -49,13 +53,36 @@ def cpu_baseline(n_sample: int, n_full: int):
                       % (n_sample, dt, (n_full / n_sample) ** 2)}
 
 
+def cpu_baseline_sgpr(n_sample: int, n_full: int, m: int):
+    """The SGPR oracle on n_sample points of config 5 (same m), scaled by n_full / n_sample: every
+    O(n) term of the SoR path (products n m c, root n m^2, derivative pairs n m) is linear in n."""
+    from oracle import sgpr_oracle as S
+    from paper_1809_11165_amd import inputs
+    w = inputs.make(5, n=n_sample, m=m)
+    t0 = time.perf_counter()
+    S.sor_bbmm_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise, w.jitter_rel,
+                         w.E1, w.E2, w.k, w.iters)
+    dt = time.perf_counter() - t0
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
+    return {"value": dt * 1e3 * (n_full / n_sample), "unit": "ms", "cores": min(cores, threads),
+            "kind": "oracle",
+            "sample": "fp64 numpy SGPR oracle, full call (m=%d, k=10, t=10, 50 iterations) on n=%d points of "
+                      "the same recipe: %.1f s measured, scaled by n/n_sample = %.0f"
+                      % (m, n_sample, dt, n_full / n_sample)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--mode", choices=["mat", "otf"], default="mat")
-    ap.add_argument("--n", type=int, default=50000)
+    ap.add_argument("--mode", choices=["mat", "otf", "sgpr"], default="mat")
+    ap.add_argument("--n", type=int, default=None, help="points (default 50000; 500000 for --mode sgpr)")
+    ap.add_argument("--m", type=int, default=1024, help="inducing inputs (--mode sgpr)")
     ap.add_argument("--cpu-sample", type=int, default=10000)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
@@ -69,8 +96,10 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU: the path runs only in the HIP library")
-    mode = inputs.MATERIALISED if args.mode == "mat" else inputs.ONTHEFLY
-    w = inputs.make(3, n=args.n)
+    mode = {"mat": inputs.MATERIALISED, "otf": inputs.ONTHEFLY, "sgpr": inputs.SGPR}[args.mode]
+    if args.n is None:
+        args.n = 500000 if mode == inputs.SGPR else 50000
+    w = inputs.make(5, n=args.n, m=args.m) if mode == inputs.SGPR else inputs.make(3, n=args.n)
     prob = binding.problem_from_workload(w, mode)
     ctx = binding.Context(0)
     ctx.bbmm_tune("time_mm", 1)
@@ -98,7 +127,24 @@ def main():
         torch.cuda.synchronize()
 
     n, c, d = w.n, w.t + 1, w.d
-    if mode == inputs.MATERIALISED:
+    workload = "config3: exact GP, Matern-5/2 ARD, n=%d, d=16, t=10, k=20, 50 mBCG iterations" % n
+    metric = "mBCG solve+logdet+grad ms at n=50k,t=10"
+    mode_name = "materialised fp32 K_hat" if mode == inputs.MATERIALISED else "on-the-fly tiles"
+    if mode == inputs.SGPR:
+        # one product = the root A (n x m fp32) streamed once in each layout, the block in and out,
+        # the m x c middle result out and in: 8 n m + 16 n c + 16 m c bytes
+        m = args.m
+        alg_bytes = 8.0 * n * m + 16.0 * n * c + 16.0 * m * c
+        achieved = alg_bytes / (mm_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "kernel": "k_mm_mat (two launches per product: A^T D, then A T)",
+                    "avg_launch_ms": mm_ms / 2.0, "avg_product_ms": mm_ms, "launches": 2 * mm_launches}
+        workload = ("config5: SGPR (subset of regressors), RBF, n=%d, m=%d, d=8, t=10, k=10, 50 mBCG "
+                    "iterations" % (n, m))
+        metric = "mBCG solve+logdet+grad ms at n=500k,m=1024,t=10 (SGPR)"
+        mode_name = "fp32 root A = K_XU G^-T in both layouts"
+    elif mode == inputs.MATERIALISED:
         # algorithmic bytes of one K_hat.D launch: K_hat once (4 n^2) + block in and out (8 n c)
         alg_bytes = 4.0 * n * n + 8.0 * n * c
         achieved = alg_bytes / (mm_ms * 1e-3) / 1e9
@@ -116,20 +162,20 @@ def main():
                     "pairs_per_s": n * n / (mm_ms * 1e-3)}
 
     out = {
-        "metric": "mBCG solve+logdet+grad ms at n=50k,t=10",
+        "metric": metric,
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config3: exact GP, Matern-5/2 ARD, n=%d, d=16, t=10, k=20, 50 mBCG iterations"
-                               % n,
-                   "mode": "materialised fp32 K_hat" if mode == inputs.MATERIALISED else "on-the-fly tiles",
+        "config": {"workload": workload,
+                   "mode": mode_name,
                    "iters_run": res.iters_run, "ms_per_iteration": ms_per_step / max(res.iters_run, 1),
                    "mm_ms_per_iteration": mm_ms,
                    "logdet": res.logdet, "nlml": res.nlml},
         "roofline": roofline,
     }
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(args.cpu_sample, n)
+        out["cpu_baseline"] = (cpu_baseline_sgpr(min(n, 5 * args.cpu_sample), n, args.m)
+                               if mode == inputs.SGPR else cpu_baseline(args.cpu_sample, n))
     print(json.dumps(out))
 
 

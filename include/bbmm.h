@@ -49,7 +49,7 @@ enum {
 };
 
 enum { BBMM_KERNEL_RBF = 0, BBMM_KERNEL_MATERN52 = 1 };
-enum { BBMM_MODE_MATERIALISED = 0, BBMM_MODE_ONTHEFLY = 1 };
+enum { BBMM_MODE_MATERIALISED = 0, BBMM_MODE_ONTHEFLY = 1, BBMM_MODE_SGPR = 2 };
 
 /*
  * Problem statement (Sec. 2 notation).
@@ -59,6 +59,16 @@ enum { BBMM_MODE_MATERIALISED = 0, BBMM_MODE_ONTHEFLY = 1 };
  *   mode         how K_hat.M products are formed inside mBCG: from an fp32 K_hat
  *                stored in device memory (4 n^2 bytes, held by the context), or
  *                from X tile by tile without ever storing K_hat.
+ *                BBMM_MODE_SGPR replaces the covariance itself by the subset-of-regressors
+ *                form of Sec. 5 (sparse GP regression paragraph),
+ *                    K_hat = K_XU K_UU^{-1} K_UX + sigma^2 I,
+ *                with m inducing inputs Uind; K_UU gets jitter_rel * outputscale on its
+ *                diagonal before it is factorised.  The library keeps the n x m root
+ *                A = K_XU G^{-T} (K_UU = G G^T) in fp32 in both layouts (8 n m bytes) and
+ *                forms products as A (A^T M).  Preconditioner, probes, mBCG, log-det and
+ *                traces are those of the SoR matrix; the inducing inputs are fixed, not
+ *                hyperparameters.  SGPR supports one shared lengthscale (n_lengthscale 1)
+ *                or one per dimension, 1 <= m <= min(n, 4096), d <= 32.
  *   n, d         number of training points and input dimension
  *   t            number of probe vectors z_i (right-hand-side block has t+1 columns)
  *   k            rank of the pivoted-Cholesky preconditioner (0 = P = sigma^2 I)
@@ -70,6 +80,8 @@ enum { BBMM_MODE_MATERIALISED = 0, BBMM_MODE_ONTHEFLY = 1 };
  *   E1           device, k x t float, entries +-1 (may be NULL when k == 0)
  *   E2           device, n x t float, entries +-1
  *                probes are z_i = L_k E1[:,i] + sigma E2[:,i]  (App. C, sampling from N(0,P))
+ *   m, Uind, jitter_rel   BBMM_MODE_SGPR only (ignored otherwise): number of inducing inputs,
+ *                device m x d float (coordinates of X), relative jitter >= 0
  */
 typedef struct {
   int32_t kernel;
@@ -84,6 +96,9 @@ typedef struct {
   const float* y;
   const float* E1;
   const float* E2;
+  int64_t m;
+  const float* Uind;
+  double jitter_rel;
 } bbmm_problem;
 
 /*
@@ -162,11 +177,19 @@ int bbmm_build_khat(bbmm_ctx* ctx);
 int bbmm_khat_block(bbmm_ctx* ctx, int64_t row0, int64_t nrows, int64_t col0, int64_t ncols,
                     float* out);
 
+/* BBMM_MODE_SGPR: form the root A = K_XU G^{-T} of the subset-of-regressors matrix (Sec. 5) in
+ * the context: K_UU and its Cholesky factor in fp64, A rounded once to fp32.  Must run before any
+ * other SGPR stage. */
+int bbmm_sgpr_build(bbmm_ctx* ctx);
+/* Copy rows [row0, row0 + nrows) of the root A (n x m) to `out` (device, nrows x m float). */
+int bbmm_sgpr_root_rows(bbmm_ctx* ctx, int64_t row0, int64_t nrows, float* out);
+
 /* V = K_hat M, the product every mBCG iteration is built on (Sec. 3, "Runtime and space").
- * M, V: device n x c float, 1 <= c <= 32.  mode MATERIALISED needs bbmm_build_khat first. */
+ * M, V: device n x c float, 1 <= c <= 32.  mode MATERIALISED needs bbmm_build_khat first, mode
+ * SGPR bbmm_sgpr_build; an SGPR problem takes mode SGPR only, and no other problem does. */
 int bbmm_kernel_mm(bbmm_ctx* ctx, int32_t mode, const float* M, int64_t c, float* V);
 
-/* Rank-k pivoted Cholesky of K_XX (App. C).  L: device n x k double, row-major (optional, NULL to
+/* Rank-k pivoted Cholesky of K_XX (App. C; of the SoR matrix for an SGPR problem).  L: device n x k double, row-major (optional, NULL to
  * skip) -- the factor is built and kept in fp64, and this is that factor unrounded;
  * pivots: host k (optional), rank: host (optional). */
 int bbmm_pivoted_cholesky(bbmm_ctx* ctx, double* L, int64_t* pivots, int64_t* rank);
@@ -212,6 +235,7 @@ int bbmm_dk_traces(bbmm_ctx* ctx, const float* U, const float* W, double* trace,
  * Both need bbmm_setup (or a completed bbmm_solve_logdet_grad) for the same
  * training data and hyperparameters; Xstar is device memory, ns x d float,
  * in the coordinates of X.
+ * Not available for SGPR problems (BBMM_EINVAL).
  * ---------------------------------------------------------------------- */
 
 /* mean[a] = k_{X x*_a}^T u0 with u0 = K_hat^{-1} y (device, n float; e.g. the u0 of

@@ -163,9 +163,15 @@ def sor_derivative_products(kernel: int, X, Uind, ls, s: float, jitter_rel: floa
 def sor_bbmm_inference(kernel: int, X, Uind, y, ls, s: float, noise: float, jitter_rel: float,
                        E1, E2, k: int, p: int, tol: float = 0.0,
                        forced_pivots: Optional[Sequence[int]] = None,
-                       progress: Optional[Callable[[str], None]] = None) -> O.BbmmResult:
+                       progress: Optional[Callable[[str], None]] = None,
+                       via_root: bool = False) -> O.BbmmResult:
     """One BBMM call on the SoR covariance: the steps of bbmm_oracle.bbmm_inference with the
-    operator, diagonal, rows and derivative products of Q."""
+    operator, diagonal, rows and derivative products of Q.
+
+    via_root=True forms the products of the iteration as A (A^T M) with A = K_XU G^{-T},
+    K_UU = G G^T -- the same operator in another fp64 rounding order.  Tests use the distance
+    between the two runs as the measure of how sharply a quantity is defined at an unconverged
+    iteration count."""
     say = progress if progress is not None else (lambda msg: None)
     X = np.asarray(X, dtype=np.float64)
     y = np.asarray(y, dtype=np.float64)
@@ -181,7 +187,11 @@ def sor_bbmm_inference(kernel: int, X, Uind, y, ls, s: float, noise: float, jitt
     B = np.concatenate([y[:, None], Zp], axis=1)
     say("preconditioner and probes ready")
 
-    res = O.mbcg(parts.khat_matmul, B, P.solve, p, tol)
+    matmul = parts.khat_matmul
+    if via_root:
+        A = sla.solve_triangular(parts.chol_UU, parts.KXU.T, lower=True).T
+        matmul = lambda M: A @ (A.T @ M) + noise * M
+    res = O.mbcg(matmul, B, P.solve, p, tol)
     say("mBCG done: %d iterations" % res.iters_run)
 
     terms = np.zeros(t)

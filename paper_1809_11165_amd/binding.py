@@ -18,14 +18,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbbmm.so")
 
 KERNEL_RBF, KERNEL_MATERN52 = 0, 1
-MODE_MATERIALISED, MODE_ONTHEFLY = 0, 1
+MODE_MATERIALISED, MODE_ONTHEFLY, MODE_SGPR = 0, 1, 2
 OK, EINVAL, ENOMEM, ENOTPD, ENONFINITE, EHIP = 0, 1, 2, 3, 4, 5
 MAX_ITERS = 256
 
 EXPORTS = [
     "bbmm_create", "bbmm_destroy", "bbmm_last_error", "bbmm_tune", "bbmm_mm_timing",
     "bbmm_solve_logdet_grad",
-    "bbmm_setup", "bbmm_build_khat", "bbmm_khat_block", "bbmm_kernel_mm", "bbmm_pivoted_cholesky",
+    "bbmm_setup", "bbmm_build_khat", "bbmm_khat_block", "bbmm_sgpr_build", "bbmm_sgpr_root_rows",
+    "bbmm_kernel_mm", "bbmm_pivoted_cholesky",
     "bbmm_precond_setup", "bbmm_precond_solve", "bbmm_make_probes", "bbmm_mbcg",
     "bbmm_tridiag_eig_batched", "bbmm_slq_logdet", "bbmm_dk_traces",
     "bbmm_predict_mean", "bbmm_predict_var",
@@ -44,7 +45,8 @@ class _Problem(C.Structure):
                 ("max_iters", C.c_int64), ("tol", C.c_double),
                 ("n_lengthscale", C.c_int64), ("lengthscale", C.POINTER(C.c_double)),
                 ("outputscale", C.c_double), ("noise", C.c_double),
-                ("X", C.c_void_p), ("y", C.c_void_p), ("E1", C.c_void_p), ("E2", C.c_void_p)]
+                ("X", C.c_void_p), ("y", C.c_void_p), ("E1", C.c_void_p), ("E2", C.c_void_p),
+                ("m", C.c_int64), ("Uind", C.c_void_p), ("jitter_rel", C.c_double)]
 
 
 class _Result(C.Structure):
@@ -84,6 +86,8 @@ def load_library() -> C.CDLL:
     lib.bbmm_setup.argtypes = [C.c_void_p, C.POINTER(_Problem)]
     lib.bbmm_build_khat.argtypes = [C.c_void_p]
     lib.bbmm_khat_block.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_void_p]
+    lib.bbmm_sgpr_build.argtypes = [C.c_void_p]
+    lib.bbmm_sgpr_root_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p]
     lib.bbmm_kernel_mm.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
     lib.bbmm_pivoted_cholesky.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64),
                                           C.POINTER(C.c_int64)]
@@ -138,6 +142,8 @@ class Problem:
     k: int
     max_iters: int
     tol: float = 0.0
+    Uind: "object" = None           # SGPR only: m x d device tensor of inducing inputs
+    jitter_rel: float = 0.0         # SGPR only
     _keep: list = field(default_factory=list, repr=False)
 
     def to_c(self) -> _Problem:
@@ -160,6 +166,12 @@ class Problem:
         p.X, p.y = self.X.data_ptr(), self.y.data_ptr()
         p.E1 = self.E1.data_ptr() if self.k > 0 else None
         p.E2 = self.E2.data_ptr()
+        p.m, p.Uind, p.jitter_rel = 0, None, 0.0
+        if self.mode == MODE_SGPR:
+            if self.Uind is None:
+                raise ValueError("an SGPR problem needs Uind")
+            _check_dev(self.Uind, (self.Uind.shape[0], d), "Uind")
+            p.m, p.Uind, p.jitter_rel = int(self.Uind.shape[0]), self.Uind.data_ptr(), float(self.jitter_rel)
         return p
 
 
@@ -269,6 +281,15 @@ class Context:
         self._ck(self.lib.bbmm_khat_block(self.h, row0, nrows, col0, ncols, _dptr(out)))
         return out
 
+    def bbmm_sgpr_build(self):
+        self._ck(self.lib.bbmm_sgpr_build(self.h))
+
+    def bbmm_sgpr_root_rows(self, row0: int, nrows: int):
+        m = int(self._prob.Uind.shape[0])
+        out = self._empty(nrows, m)
+        self._ck(self.lib.bbmm_sgpr_root_rows(self.h, row0, nrows, _dptr(out)))
+        return out
+
     def bbmm_kernel_mm(self, mode: int, M):
         n = self._shape[0]
         _check_dev(M, (n, M.shape[1]), "M")
@@ -369,6 +390,7 @@ def problem_from_workload(w, mode: int, device="cuda:0") -> Problem:
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
 
     E1 = up(w.E1) if w.k > 0 else None
+    Uind = up(w.Uind) if mode == MODE_SGPR else None
     return Problem(kernel=w.kernel, mode=mode, X=up(w.X), y=up(w.y), lengthscale=w.lengthscale,
                    outputscale=w.outputscale, noise=w.noise, E1=E1, E2=up(w.E2), k=w.k,
-                   max_iters=w.iters, tol=w.tol)
+                   max_iters=w.iters, tol=w.tol, Uind=Uind, jitter_rel=w.jitter_rel)

@@ -39,8 +39,10 @@ struct bbmm_ctx {
   bbmm_problem prob{};
   std::vector<double> ls;
   int n = 0, d = 0, t = 0, k = 0, kp = 0, np = 0, KK = 0, dp = 0, maxit = 0;
+  int m = 0, mp = 0;                        // inducing inputs (SGPR), padded to 256
   HypArgs hyp{};
   bool khat_built = false, chol_done = false, pre_done = false, mbcg_done = false;
+  bool sgpr = false, sgpr_built = false;
   int last_c = 0, last_ld = 0, last_t = 0;   // shape of the last mBCG run
 
   int64_t mat_wgs = 0, otf_split = 0;        // 0 = default
@@ -48,12 +50,17 @@ struct bbmm_ctx {
   // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
   int plan_np = 0, plan_wgs[2] = {0, 0};
   int64_t plan_tune = -1;
+  // SGPR: plans of the two streaming products per block width: [v] = A (rows np, columns mp),
+  // [2 + v] = A^T (rows mp, columns np)
+  int sg_np = 0, sg_mp = 0, sg_wgs[4] = {0, 0, 0, 0}, sg_slots[4] = {0, 0, 0, 0};
   bool time_mm = false;                      // record HIP events around every product launch
   std::vector<hipEvent_t> ev;                // 2 per iteration, created on demand
   int ev_iters = 0;                          // iterations covered by the last timed run
 
   Buf Xa, Xb, Xs, X4, sq, Khat, L, delta, U, R, V, Z0, D4, Vp, partial, gpartial, alpha, beta, resid, st,
-      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[2], nseg[2];
+      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[2], nseg[2],
+      KUU, Gm, Ginv, Kux, AT, A, qdiag, Tp, T4, sgplan[4], sgnseg[4],
+      Ua, Ub, Us, U4, usq, TU, TW, BU, BW, dkops;
   DevState* h_st = nullptr;   // pinned
   double* h_hist = nullptr;   // pinned, 3 * MAXP * MAXC doubles
   size_t dk_rows_cap = 0;
@@ -158,47 +165,94 @@ int mat_wgs_of(const bbmm_ctx* c, int ld) {
   return (int)w;
 }
 
-// Lays out the plans on the host and uploads them: units (strip, 16-row step) in strip-major order
-// are dealt to the workgroups in equal contiguous runs; a run that crosses a strip boundary becomes
-// two pieces.  Everything the kernel relies on (rows inside K_hat, slot inside Vp, at most two
-// pieces) is checked here.
+// Lays out one plan on the host and uploads it: the units (strip of output columns, 16-row step)
+// of a rows_p x cols_p matrix, in strip-major order, are dealt to `wgs` workgroups in equal
+// contiguous runs; a run that crosses strip boundaries becomes several pieces, each with its own
+// partial slot in its strip.  Everything the kernel relies on (rows inside the matrix, slot below
+// slot_cap, at most BBMM_MM_PIECES pieces) is checked here.
+int make_plan(bbmm_ctx* c, int rows_p, int cols_p, int ld, int wgs, int slot_cap, Buf& plan_buf,
+              Buf& nseg_buf, int* max_slots) {
+  int cols_per_wg = (ld == 32) ? 512 : 1024;
+  int strips = (cols_p + cols_per_wg - 1) / cols_per_wg;
+  int steps = rows_p / 16;
+  long long units = (long long)strips * steps;
+  std::vector<MmPlan> plan((size_t)wgs);
+  std::vector<int> nseg((size_t)strips, 0);
+  for (int w = 0; w < wgs; ++w) {
+    long long b = units * w / wgs, e = units * (w + 1) / wgs;
+    for (int pc = 0; pc < BBMM_MM_PIECES; ++pc) {
+      MmPiece P = {0, 0, 0, 0};
+      if (b < e) {
+        int strip = (int)(b / steps), jb = (int)(b % steps);
+        int je = (int)std::min<long long>(steps, jb + (e - b));
+        P = MmPiece{strip, jb * 16, je * 16, nseg[strip]++};
+        b += je - jb;
+        if (strip >= strips || P.row_end > rows_p || P.slot >= slot_cap)
+          return fail(c, BBMM_EINVAL, "internal: product plan out of range");
+      }
+      plan[w].piece[pc] = P;
+    }
+    if (b < e) return fail(c, BBMM_EINVAL, "internal: product plan needs too many pieces");
+  }
+  int rc = ensure(c, plan_buf, sizeof(MmPlan) * (size_t)wgs);
+  if (rc) return rc;
+  rc = ensure(c, nseg_buf, sizeof(int) * (size_t)strips);
+  if (rc) return rc;
+  HIPCHK(c, hipMemcpy(plan_buf.p, plan.data(), sizeof(MmPlan) * (size_t)wgs, hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(nseg_buf.p, nseg.data(), sizeof(int) * (size_t)strips, hipMemcpyHostToDevice));
+  if (max_slots) *max_slots = *std::max_element(nseg.begin(), nseg.end());
+  return BBMM_OK;
+}
+
 int ensure_mat_plans(bbmm_ctx* c) {
   if (c->plan_np == c->np && c->plan_tune == c->mat_wgs) return BBMM_OK;
   HIPCHK(c, hipStreamSynchronize(c->stream));   // earlier launches may still read the old plans
   for (int v = 0; v < 2; ++v) {
-    int ld = v ? 32 : 16, cols_per_wg = v ? 512 : 1024;
-    int strips = (c->np + cols_per_wg - 1) / cols_per_wg;
-    int steps = c->np / 16;
+    int ld = v ? 32 : 16;
     int wgs = mat_wgs_of(c, ld);
-    long long units = (long long)strips * steps;
-    std::vector<MmPlan> plan((size_t)wgs);
-    std::vector<int> nseg((size_t)strips, 0);
-    for (int w = 0; w < wgs; ++w) {
-      long long b = units * w / wgs, e = units * (w + 1) / wgs;
-      for (int pc = 0; pc < 2; ++pc) {
-        MmPiece P = {0, 0, 0, 0};
-        if (b < e) {
-          int strip = (int)(b / steps), jb = (int)(b % steps);
-          int je = (int)std::min<long long>(steps, jb + (e - b));
-          P = MmPiece{strip, jb * 16, je * 16, nseg[strip]++};
-          b += je - jb;
-          if (strip >= strips || P.row_end > c->np || P.slot >= kMaxSplit)
-            return fail(c, BBMM_EINVAL, "internal: product plan out of range");
-        }
-        plan[w].piece[pc] = P;
-      }
-      if (b < e) return fail(c, BBMM_EINVAL, "internal: product plan needs more than two pieces");
-    }
-    int rc = ensure(c, c->plan[v], sizeof(MmPlan) * (size_t)wgs);
+    int rc = make_plan(c, c->np, c->np, ld, wgs, kMaxSplit, c->plan[v], c->nseg[v], nullptr);
     if (rc) return rc;
-    rc = ensure(c, c->nseg[v], sizeof(int) * (size_t)strips);
-    if (rc) return rc;
-    HIPCHK(c, hipMemcpy(c->plan[v].p, plan.data(), sizeof(MmPlan) * (size_t)wgs, hipMemcpyHostToDevice));
-    HIPCHK(c, hipMemcpy(c->nseg[v].p, nseg.data(), sizeof(int) * (size_t)strips, hipMemcpyHostToDevice));
     c->plan_wgs[v] = wgs;
   }
   c->plan_np = c->np;
   c->plan_tune = c->mat_wgs;
+  return BBMM_OK;
+}
+
+// Workgroups for streaming a rows_p x cols_p matrix: whole rounds of num_cus, enough of them that
+// a run is at most two strips long (so at most three pieces), never more than there are units.
+int rect_wgs_of(const bbmm_ctx* c, int rows_p, int cols_p, int ld, int slot_cap) {
+  int cols_per_wg = (ld == 32) ? 512 : 1024;
+  int strips = (cols_p + cols_per_wg - 1) / cols_per_wg;
+  long long units = (long long)strips * (rows_p / 16);
+  long long w = (long long)c->num_cus * std::max(1, (strips + 2 * c->num_cus - 1) / (2 * c->num_cus));
+  w = std::min<long long>(w, (long long)(slot_cap - 4) * strips);
+  w = std::min<long long>(w, units);
+  w = std::max<long long>(w, std::min<long long>(units, (strips + 1) / 2));
+  return (int)std::max<long long>(w, 1);
+}
+
+constexpr int kSgprSlotCap = 1024;   // partial results of A^T D: one per workgroup when m <= 1024
+
+int ensure_sgpr_plans(bbmm_ctx* c) {
+  if (c->sg_np == c->np && c->sg_mp == c->mp) return BBMM_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (int v = 0; v < 2; ++v) {
+    int ld = v ? 32 : 16;
+    int w1 = rect_wgs_of(c, c->np, c->mp, ld, kSgprSlotCap);
+    int rc = make_plan(c, c->np, c->mp, ld, w1, kSgprSlotCap, c->sgplan[v], c->sgnseg[v], &c->sg_slots[v]);
+    if (rc) return rc;
+    c->sg_wgs[v] = w1;
+    int w2 = rect_wgs_of(c, c->mp, c->np, ld, kMaxSplit);
+    rc = make_plan(c, c->mp, c->np, ld, w2, kMaxSplit, c->sgplan[2 + v], c->sgnseg[2 + v], &c->sg_slots[2 + v]);
+    if (rc) return rc;
+    c->sg_wgs[2 + v] = w2;
+  }
+  size_t slots = (size_t)std::max(c->sg_slots[0], c->sg_slots[1]);
+  int rc = ensure(c, c->Tp, slots * (size_t)c->mp * BBMM_MAXC * sizeof(double));
+  if (rc) return rc;
+  c->sg_np = c->np;
+  c->sg_mp = c->mp;
   return BBMM_OK;
 }
 
@@ -240,7 +294,8 @@ int fetch_state(bbmm_ctx* c, bool with_hist) {
 
 int device_status(bbmm_ctx* c) {
   int s = c->h_st->status;
-  if (s == BBMM_ENOTPD) return fail(c, BBMM_ENOTPD, "capacitance matrix sigma^2 I + L^T L is not positive definite");
+  if (s == BBMM_ENOTPD)
+    return fail(c, BBMM_ENOTPD, "capacitance matrix sigma^2 I + L^T L (or K_UU + jitter I) is not positive definite");
   if (s == BBMM_ENONFINITE) return fail(c, BBMM_ENONFINITE, "non-finite value in the log-determinant estimate");
   if (s != 0) return fail(c, s, "device-side failure");
   return BBMM_OK;
@@ -259,10 +314,89 @@ int stage_build_khat(bbmm_ctx* c) {
   return BBMM_OK;
 }
 
+// SGPR: K_UU (fp64) -> Cholesky factor G -> G^{-1}; K_UX (fp64); A^T = G^{-1} K_UX rounded to fp32,
+// A by transposition, and the diagonal of Q = A A^T.
+int stage_sgpr_build(bbmm_ctx* c) {
+  if (!c->sgpr) return fail(c, BBMM_EINVAL, "the problem is not an SGPR problem");
+  hipStream_t s = c->stream;
+  size_t mp = (size_t)c->mp, np = (size_t)c->np;
+  struct { Buf* b; size_t bytes; } want[] = {
+      {&c->KUU, mp * mp * sizeof(double)}, {&c->Gm, mp * mp * sizeof(double)},
+      {&c->Ginv, mp * mp * sizeof(double)}, {&c->Kux, mp * np * sizeof(double)},
+      {&c->AT, mp * np * sizeof(float)}, {&c->A, mp * np * sizeof(float)},
+      {&c->qdiag, np * sizeof(double)}, {&c->T4, mp * BBMM_MAXC * sizeof(double)},
+      {&c->Ua, mp * c->dp * sizeof(float)}, {&c->Ub, mp * c->dp * sizeof(float)},
+      {&c->Us, mp * c->dp * sizeof(float)}, {&c->U4, mp * c->dp * sizeof(float)},
+      {&c->usq, mp * sizeof(float)},
+      {&c->TU, mp * BBMM_MAXC * sizeof(double)}, {&c->TW, mp * BBMM_MAXC * sizeof(double)},
+      {&c->BU, mp * BBMM_MAXC * sizeof(double)}, {&c->BW, mp * BBMM_MAXC * sizeof(double)},
+      {&c->dkops, mp * (3 * 64 + 2) * sizeof(float)},
+  };
+  for (auto& w : want) {
+    int rc = ensure(c, *w.b, w.bytes);
+    if (rc) return rc;
+  }
+  int rc = ensure_sgpr_plans(c);
+  if (rc) return rc;
+  DevState* st = ptr<DevState>(c->st);
+  launch_fill_f64(s, ptr<double>(c->Gm), mp * mp, 0.0);
+  launch_fill_f64(s, ptr<double>(c->Ginv), mp * mp, 0.0);
+  launch_sgpr_kuu(s, c->prob.Uind, c->m, c->mp, c->hyp, c->prob.jitter_rel * c->prob.outputscale,
+                  ptr<double>(c->KUU));
+  launch_sgpr_chol(s, ptr<double>(c->KUU), ptr<double>(c->Gm), c->mp, 1e-13 * c->prob.outputscale, st);
+  launch_sgpr_trinv(s, ptr<double>(c->Gm), ptr<double>(c->Ginv), c->mp);
+  if (c->mp > c->m)
+    launch_fill_f64(s, ptr<double>(c->Kux) + (size_t)c->m * np, (mp - (size_t)c->m) * np, 0.0);
+  if (launch_sgpr_kux(s, c->prob.X, c->prob.Uind, c->n, c->np, c->m, c->dp, c->hyp, ptr<double>(c->Kux)))
+    return fail(c, BBMM_EINVAL, "unsupported input dimension");
+  launch_sgpr_root(s, ptr<double>(c->Ginv), ptr<double>(c->Kux), c->mp, c->np, ptr<float>(c->AT));
+  launch_transpose_f32(s, ptr<float>(c->AT), c->mp, c->np, ptr<float>(c->A));
+  launch_sgpr_qdiag(s, ptr<float>(c->A), c->n, c->mp, ptr<double>(c->qdiag));
+  // inducing inputs in the centred, scaled coordinates of X (for the derivative pair sums)
+  launch_prep_x(s, c->prob.Uind, c->m, c->d, c->mp, c->KK, c->hyp, st, ptr<float>(c->Ua), ptr<float>(c->Ub),
+                ptr<float>(c->Us), ptr<float>(c->U4), ptr<float>(c->usq));
+  c->sgpr_built = true;
+  c->chol_done = c->pre_done = c->mbcg_done = false;
+  return BBMM_OK;
+}
+
+// SGPR product, second half: Vp <- partial sums of A T with T (quad-swizzled, mp rows) in T4.
+int sgpr_second_pass(bbmm_ctx* c, int ld, VpShape* shape) {
+  int v = (ld == 32) ? 1 : 0;
+  if (launch_mm_mat(c->stream, ptr<float>(c->AT), ptr<double>(c->T4), ptr<double>(c->Vp), c->np, ld,
+                    ptr<MmPlan>(c->sgplan[2 + v]), c->sg_wgs[2 + v], ptr<DevState>(c->st)))
+    return fail(c, BBMM_EINVAL, "unsupported block width");
+  *shape = VpShape{0, ptr<int>(c->sgnseg[2 + v]), v ? 512 : 1024};
+  return BBMM_OK;
+}
+
+// SGPR product, first half: Tp <- partial sums of A^T D with D (quad-swizzled, np rows) in `D4`.
+int sgpr_first_pass(bbmm_ctx* c, int ld, const double* D4, VpShape* shape) {
+  int v = (ld == 32) ? 1 : 0;
+  if (launch_mm_mat(c->stream, ptr<float>(c->A), D4, ptr<double>(c->Tp), c->mp, ld,
+                    ptr<MmPlan>(c->sgplan[v]), c->sg_wgs[v], ptr<DevState>(c->st)))
+    return fail(c, BBMM_EINVAL, "unsupported block width");
+  *shape = VpShape{0, ptr<int>(c->sgnseg[v]), v ? 512 : 1024};
+  return BBMM_OK;
+}
+
 // Vp <- partial products of K_hat with the block in D4; returns the split count and the
 // (scale, add) pair that turns the partial sums into K_hat D.
 int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scaleV, double* addD) {
-  if (mode == BBMM_MODE_MATERIALISED) {
+  if ((mode == BBMM_MODE_SGPR) != c->sgpr)
+    return fail(c, BBMM_EINVAL, "an SGPR problem takes mode SGPR, and only an SGPR problem does");
+  if (mode == BBMM_MODE_SGPR) {
+    if (!c->sgpr_built) return fail(c, BBMM_EINVAL, "SGPR product needs bbmm_sgpr_build first");
+    if (ld != 16 && ld != 32) return fail(c, BBMM_EINVAL, "unsupported block width");
+    VpShape sh1{0, nullptr, 1};
+    int rc = sgpr_first_pass(c, ld, ptr<double>(c->D4), &sh1);
+    if (rc) return rc;
+    launch_sgpr_mid(c->stream, ptr<double>(c->Tp), sh1, c->mp, ld, ptr<DevState>(c->st), ptr<double>(c->T4));
+    rc = sgpr_second_pass(c, ld, shape);
+    if (rc) return rc;
+    *scaleV = 1.0;
+    *addD = c->prob.noise;
+  } else if (mode == BBMM_MODE_MATERIALISED) {
     if (!c->khat_built) return fail(c, BBMM_EINVAL, "materialised product needs bbmm_build_khat first");
     if (ld != 16 && ld != 32) return fail(c, BBMM_EINVAL, "unsupported block width");
     int rc = ensure_mat_plans(c);
@@ -295,10 +429,31 @@ int stage_pivchol(bbmm_ctx* c) {
   if (c->kp > 0) launch_fill_f64(s, ptr<double>(c->L), (size_t)c->np * c->kp, 0.0);
   // pivot candidates alternate between two buffers (a step reads one and writes the other)
   double* arg[2] = {ptr<double>(c->partial), ptr<double>(c->partial) + 2 * kMaxVecBlocks};
-  launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), ptr<DevState>(c->st), arg[0], nb);
+  if (c->sgpr) {
+    // App. C, SoR case: the diagonal of Q is not constant and a row of Q costs one pass over the
+    // root: row piv = A (A^T e_piv), the second streaming product applied to row piv of A.
+    if (!c->sgpr_built) return fail(c, BBMM_EINVAL, "bbmm_sgpr_build must run first");
+    DevState* st = ptr<DevState>(c->st);
+    launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
+    launch_fill_f64(s, ptr<double>(c->D4), (size_t)c->np * 16, 0.0);
+    launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), st, arg[0], nb, ptr<double>(c->qdiag));
+    for (int m = 0; m < c->k; ++m) {
+      launch_sgpr_pick(s, ptr<float>(c->A), c->mp, arg[m & 1], nb, ptr<double>(c->T4));
+      VpShape sh{0, nullptr, 1};
+      int rc = sgpr_second_pass(c, 16, &sh);
+      if (rc) return rc;
+      launch_vreduce(s, ptr<double>(c->Vp), sh, c->n, c->np, 16, 1.0, 0.0, ptr<double>(c->D4), ptr<double>(c->V));
+      launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<double>(c->L), st,
+                     arg[m & 1], arg[(m + 1) & 1], nb, ptr<double>(c->V), 16);
+    }
+    c->chol_done = true;
+    c->pre_done = false;
+    return BBMM_OK;
+  }
+  launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), ptr<DevState>(c->st), arg[0], nb, nullptr);
   for (int m = 0; m < c->k; ++m)
     launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<double>(c->L),
-                   ptr<DevState>(c->st), arg[m & 1], arg[(m + 1) & 1], nb);
+                   ptr<DevState>(c->st), arg[m & 1], arg[(m + 1) & 1], nb, nullptr, 0);
   c->chol_done = true;
   c->pre_done = false;
   return BBMM_OK;
@@ -376,8 +531,11 @@ int stage_slq(bbmm_ctx* c, hipStream_t s) {
   return BBMM_OK;
 }
 
+int stage_dk_sgpr(bbmm_ctx* c, int ld, int t);
+
 // Derivative pass on U (padded, stride ld; columns 0..t) and Z0 (columns 1..t = W).
 int stage_dk(bbmm_ctx* c, int ld, int t) {
+  if (c->sgpr) return stage_dk_sgpr(c, ld, t);
   hipStream_t s = c->stream;
   int ard = (c->prob.n_lengthscale > 1) ? 1 : 0;
   // S = (U W^T + W U^T) / (2t): operands [U, W] / (2t) and [W, U], so that S is symmetric and the
@@ -408,6 +566,57 @@ int stage_dk(bbmm_ctx* c, int ld, int t) {
   return BBMM_OK;
 }
 
+// Derivative terms of the SoR matrix on U (padded, stride ld; columns 0..t) and Z0 (columns 1..t = W).
+int stage_dk_sgpr(bbmm_ctx* c, int ld, int t) {
+  if (!c->sgpr_built) return fail(c, BBMM_EINVAL, "bbmm_sgpr_build must run first");
+  hipStream_t s = c->stream;
+  DevState* st = ptr<DevState>(c->st);
+  int ard = (c->prob.n_lengthscale > 1) ? 1 : 0;
+  int NT = (2 * t <= 32) ? 32 : 64;
+  const double* U = ptr<double>(c->U);
+  const double* Z0 = ptr<double>(c->Z0);
+  // the streaming product skips its work when the stop flag is set; iters_run (next to it) stays
+  launch_fill_bytes0(s, &st->done, sizeof(int));
+  // T_U = A^T U, T_W = A^T Z0 (m x ld), then b = G^{-T} T = K_UU^{-1} K_UX (.)
+  const double* blocks[2] = {U, Z0};
+  double* tout[2] = {ptr<double>(c->TU), ptr<double>(c->TW)};
+  double* bout[2] = {ptr<double>(c->BU), ptr<double>(c->BW)};
+  for (int h = 0; h < 2; ++h) {
+    launch_rows_to_d4(s, blocks[h], c->n, c->np, ld, ptr<double>(c->tmpA));
+    VpShape sh{0, nullptr, 1};
+    int rc = sgpr_first_pass(c, ld, ptr<double>(c->tmpA), &sh);
+    if (rc) return rc;
+    launch_sgpr_mid_rows(s, ptr<double>(c->Tp), sh, c->mp, ld, tout[h]);
+    launch_sgpr_bsolve(s, ptr<double>(c->Ginv), tout[h], c->mp, ld, bout[h]);
+  }
+  float* PR = ptr<float>(c->SA);           // np x NT
+  float* qr = ptr<float>(c->u0v);          // np
+  size_t mp = (size_t)c->mp;
+  float* PCx = ptr<float>(c->dkops);
+  float* PRu = PCx + mp * 64;
+  float* PCu = PRu + mp * 64;
+  float* qcx = PCu + mp * 64;
+  float* qru = qcx + mp;
+  launch_sgpr_dk_ops(s, U, Z0, bout[0], bout[1], c->n, c->np, c->m, c->mp, ld, t, NT, PR, qr, PCx, qcx, PRu,
+                     qru, PCu);
+  double* partial = ptr<double>(c->dkpartial);
+  // one partial row per block of each pair sum; the (U, U) rows follow the (X, U) rows
+  int col_chunks = (c->m + 127) / 128;
+  int nb1 = (c->np / 256) * col_chunks, nb2 = (c->mp / 256) * col_chunks;
+  if ((size_t)(nb1 + nb2) > c->dk_rows_cap) return fail(c, BBMM_EINVAL, "internal: derivative partial rows");
+  if (launch_dk_rect(s, c->prob.kernel, c->dp, NT, ard, ptr<float>(c->Xs), ptr<float>(c->Us), PR, qr, PCx, qcx,
+                     c->np, c->m, partial, kDkStride) != nb1 ||
+      launch_dk_rect(s, c->prob.kernel, c->dp, NT, ard, ptr<float>(c->Us), ptr<float>(c->Us), PRu, qru, PCu, qcx,
+                     c->mp, c->m, partial + (size_t)nb1 * kDkStride, kDkStride) != nb2)
+    return fail(c, BBMM_EINVAL, "SGPR derivative terms: unsupported configuration");
+  int nls = ard ? c->dp : 1;
+  launch_dk_finish(s, partial, nb1 + nb2, kDkStride, 2 * nls, st);
+  launch_sgpr_sterm(s, tout[0], tout[1], c->mp, ld, t, c->prob.outputscale, nls, st);
+  launch_noise_terms(s, U, Z0, c->prob.y, c->n, ld, t, nls + 1, st, ptr<double>(c->partial),
+                     ptr<double>(c->gpartial), vec_blocks(c->n, ld));
+  return BBMM_OK;
+}
+
 // Turns the raw accumulators of the derivative pass into trace[h], quad[h] (host side).
 void finish_dk(const bbmm_ctx* c, double* trace, double* quad) {
   const DevState* st = c->h_st;
@@ -432,8 +641,14 @@ int validate(bbmm_ctx* c, const bbmm_problem* in) {
   if (!in) return fail(c, BBMM_EINVAL, "problem is NULL");
   if (in->kernel != BBMM_KERNEL_RBF && in->kernel != BBMM_KERNEL_MATERN52)
     return fail(c, BBMM_EINVAL, "unknown kernel");
-  if (in->mode != BBMM_MODE_MATERIALISED && in->mode != BBMM_MODE_ONTHEFLY)
+  if (in->mode != BBMM_MODE_MATERIALISED && in->mode != BBMM_MODE_ONTHEFLY && in->mode != BBMM_MODE_SGPR)
     return fail(c, BBMM_EINVAL, "unknown mode");
+  if (in->mode == BBMM_MODE_SGPR) {
+    if (in->m < 1 || in->m > 4096 || in->m > in->n) return fail(c, BBMM_EINVAL, "m must be in 1..min(n, 4096)");
+    if (!in->Uind) return fail(c, BBMM_EINVAL, "Uind is NULL");
+    if (in->d > 32) return fail(c, BBMM_EINVAL, "SGPR needs d <= 32");
+    if (!(in->jitter_rel >= 0.0) || !isfinite(in->jitter_rel)) return fail(c, BBMM_EINVAL, "jitter_rel must be >= 0");
+  }
   if (in->n < 1 || in->n > (int64_t)1 << 30) return fail(c, BBMM_EINVAL, "n out of range");
   if (in->d < 1 || in->d > BBMM_MAXD) return fail(c, BBMM_EINVAL, "d must be in 1..64");
   if (in->t < 1 || in->t > BBMM_MAXC - 1) return fail(c, BBMM_EINVAL, "t must be in 1..31");
@@ -497,7 +712,10 @@ int bbmm_destroy(bbmm_ctx* c) {
   Buf* bufs[] = {&c->Xa, &c->Xb, &c->Xs, &c->X4, &c->sq, &c->Khat, &c->L, &c->delta, &c->U, &c->R, &c->V,
                  &c->Z0, &c->D4, &c->Vp, &c->partial, &c->gpartial, &c->alpha, &c->beta, &c->resid, &c->st, &c->tmpA,
                  &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig, &c->plan[0], &c->plan[1], &c->nseg[0],
-                 &c->nseg[1]};
+                 &c->nseg[1], &c->KUU, &c->Gm, &c->Ginv, &c->Kux, &c->AT, &c->A, &c->qdiag, &c->Tp, &c->T4,
+                 &c->sgplan[0], &c->sgplan[1], &c->sgplan[2], &c->sgplan[3], &c->sgnseg[0], &c->sgnseg[1],
+                 &c->sgnseg[2], &c->sgnseg[3], &c->Ua, &c->Ub, &c->Us, &c->U4, &c->usq, &c->TU, &c->TW, &c->BU,
+                 &c->BW, &c->dkops};
   for (Buf* b : bufs)
     if (b->p) (void)hipFree(b->p);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
@@ -559,6 +777,10 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
   c->KK = KK;
   c->dp = 4 * KK;
   c->khat_built = c->chol_done = c->pre_done = c->mbcg_done = false;
+  c->sgpr = (in->mode == BBMM_MODE_SGPR);
+  c->sgpr_built = false;
+  c->m = c->sgpr ? (int)in->m : 0;
+  c->mp = ((c->m + 255) / 256) * 256;
 
   memset(&c->hyp, 0, sizeof(HypArgs));
   double c0 = (in->kernel == BBMM_KERNEL_RBF) ? 0.5 * 1.4426950408889634074 : 1.0;
@@ -612,6 +834,29 @@ int bbmm_build_khat(bbmm_ctx* c) {
   if (rc) return rc;
   rc = stage_build_khat(c);
   if (rc) return rc;
+  HIPCHK(c, hipGetLastError());
+  return BBMM_OK;
+}
+
+int bbmm_sgpr_build(bbmm_ctx* c) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  rc = stage_sgpr_build(c);
+  if (rc) return rc;
+  rc = fetch_state(c, false);
+  if (rc) return rc;
+  if (c->h_st->status == BBMM_ENOTPD) return fail(c, BBMM_ENOTPD, "K_UU + jitter I is not positive definite");
+  return device_status(c);
+}
+
+int bbmm_sgpr_root_rows(bbmm_ctx* c, int64_t row0, int64_t nrows, float* out) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!c->sgpr_built) return fail(c, BBMM_EINVAL, "bbmm_sgpr_build must run first");
+  if (!out || row0 < 0 || nrows < 0 || row0 + nrows > c->n || nrows * (int64_t)c->m > (int64_t)1 << 31)
+    return fail(c, BBMM_EINVAL, "rows out of range");
+  if (nrows == 0) return BBMM_OK;
+  launch_copy_block(c->stream, ptr<float>(c->A), (size_t)c->mp, (int)row0, (int)nrows, 0, c->m, out);
   HIPCHK(c, hipGetLastError());
   return BBMM_OK;
 }
@@ -737,6 +982,7 @@ int bbmm_mbcg(bbmm_ctx* c, int32_t mode, const float* B, int64_t cc, float* U, d
 int bbmm_predict_mean(bbmm_ctx* c, const float* Xstar, int64_t ns, const float* u0, float* mean) {
   int rc = check_ready(c);
   if (rc) return rc;
+  if (c->sgpr) return fail(c, BBMM_EINVAL, "predictions are not available for SGPR problems");
   if (!Xstar || !u0 || !mean || ns < 1 || ns > (1 << 30)) return fail(c, BBMM_EINVAL, "bad test block");
   hipStream_t s = c->stream;
   launch_pack_rows(s, u0, c->n, 1, 16, ptr<double>(c->tmpB));
@@ -749,6 +995,7 @@ int bbmm_predict_var(bbmm_ctx* c, int32_t mode, const float* Xstar, int64_t ns, 
                      int64_t* iters_run, double* max_resid) {
   int rc = check_ready(c);
   if (rc) return rc;
+  if (c->sgpr) return fail(c, BBMM_EINVAL, "predictions are not available for SGPR problems");
   if (!Xstar || !var || ns < 1 || ns > BBMM_MAXC)
     return fail(c, BBMM_EINVAL, "bad test block (1 <= ns <= 32 per call)");
   if (!c->pre_done) return fail(c, BBMM_EINVAL, "bbmm_precond_setup must run first");
@@ -841,6 +1088,9 @@ int bbmm_solve_logdet_grad(bbmm_ctx* c, const bbmm_problem* in, bbmm_result* out
   int cc = c->t + 1, ld = ld_for(cc);
   if (in->mode == BBMM_MODE_MATERIALISED) {
     rc = stage_build_khat(c);
+    if (rc) return rc;
+  } else if (in->mode == BBMM_MODE_SGPR) {
+    rc = stage_sgpr_build(c);
     if (rc) return rc;
   }
   rc = stage_pivchol(c);

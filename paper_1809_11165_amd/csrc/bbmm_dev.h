@@ -48,14 +48,15 @@ struct HypArgs {
   int d;
 };
 
-// Work of one workgroup of the materialised product: up to two pieces, each a run of K_hat rows
-// [row_begin, row_end) (multiples of 16) inside one strip of output columns, whose partial result
-// goes to slot `slot` of that strip.  An unused piece has row_begin == row_end.
+// Work of one workgroup of the materialised product: up to BBMM_MM_PIECES pieces, each a run of
+// matrix rows [row_begin, row_end) (multiples of 16) inside one strip of output columns, whose
+// partial result goes to slot `slot` of that strip.  An unused piece has row_begin == row_end.
+#define BBMM_MM_PIECES 4
 struct MmPiece {
   int strip, row_begin, row_end, slot;
 };
 struct MmPlan {
-  MmPiece piece[2];
+  MmPiece piece[BBMM_MM_PIECES];
 };
 
 // How the partial products in Vp are to be summed: `nsplit` slots for every row, or, when nseg is
@@ -84,10 +85,13 @@ void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0,
                        int ncols, float* dst);
 void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                     double addD, const double* D4, double* V);
+// diag_in / row_in: NULL for a plain kernel matrix of X (constant diagonal, rows evaluated from X);
+// otherwise the matrix diagonal (n) and, per step, the pivot's row at row_in[i * row_ld].
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
-                    int nblocks);
+                    int nblocks, const double* diag_in);
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
-                    double* L, DevState* st, const double* arg_in, double* arg_out, int nblocks);
+                    double* L, DevState* st, const double* arg_in, double* arg_out, int nblocks,
+                    const double* row_in, int row_ld);
 void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, double noise, DevState* st,
                       double* partial, double* gpartial, int nblocks);
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const double* L,
@@ -113,10 +117,40 @@ void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, in
 void launch_noise_terms(hipStream_t s, const double* U, const double* Z0, const float* y, int n, int ld,
                         int t, int slot, DevState* st, double* partial, double* gpartial, int nblocks);
 
+// ---- launchers implemented in kernels_sgpr.hip (subset-of-regressors covariance) ----------
+void launch_sgpr_kuu(hipStream_t s, const float* Uind, int m, int mp, HypArgs hyp, double jitter,
+                     double* KUU);
+void launch_sgpr_chol(hipStream_t s, double* KUU, double* G, int mp, double tiny, DevState* st);
+void launch_sgpr_trinv(hipStream_t s, const double* G, double* Ginv, int mp);
+int launch_sgpr_kux(hipStream_t s, const float* X, const float* Uind, int n, int np, int m, int dp,
+                    HypArgs hyp, double* Kux);
+void launch_sgpr_root(hipStream_t s, const double* Ginv, const double* Kux, int mp, int np, float* AT);
+void launch_transpose_f32(hipStream_t s, const float* src, int rows, int cols, float* dst);
+void launch_sgpr_qdiag(hipStream_t s, const float* A, int n, int mp, double* qdiag);
+void launch_sgpr_mid(hipStream_t s, const double* Tp, VpShape shape, int mp, int ld, const DevState* st,
+                     double* T4);
+void launch_sgpr_mid_rows(hipStream_t s, const double* Tp, VpShape shape, int mp, int ld, double* T);
+void launch_sgpr_pick(hipStream_t s, const float* A, int mp, const double* arg_in, int npart,
+                      double* T4);
+
+void launch_rows_to_d4(hipStream_t s, const double* src, int n, int np, int ld, double* D4);
+void launch_sgpr_bsolve(hipStream_t s, const double* Ginv, const double* T, int mp, int ld, double* B);
+void launch_sgpr_sterm(hipStream_t s, const double* TU, const double* TW, int mp, int ld, int t,
+                       double outputscale, int slot, DevState* st);
+void launch_sgpr_dk_ops(hipStream_t s, const double* U, const double* Z0, const double* BU,
+                        const double* BW, int n, int np, int m, int mp, int ld, int t, int NT, float* PR,
+                        float* qr, float* PCx, float* qcx, float* PRu, float* qru, float* PCu);
+int launch_dk_rect(hipStream_t s, int kernel, int dp, int NT, int ard, const float* Xr, const float* Xc,
+                   const float* PR, const float* qr, const float* PC, const float* qc, int nrows_p,
+                   int ncols, double* partial, int pstride);
+
 // ---- launchers implemented in kernels_mm.hip ----------------------------------------------
 int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
                       const float* sq, int n, int np, double outputscale, double noise, float* Khat);
-// plan: one entry per workgroup, laid out by the host (see ensure_mat_plans).
+// Streams the row-major fp32 matrix M (row stride = column count `np`, a multiple of 256) once and
+// leaves partial sums of M^T D in Vp, D4 indexed by the rows of M.  For the symmetric K_hat that is
+// K_hat D; the SGPR root uses it on both of its layouts.  plan: one entry per workgroup, laid out
+// by the host (see make_plan).
 int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
                   const MmPlan* plan, int wgs, const DevState* st);
 // c: number of columns really used (<= ld); lets 17..20 columns run one MFMA group plus vector FMAs
@@ -128,6 +162,9 @@ int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* X
               const float* sq, const float* Xs, const float* X4, const float* SA, const float* SB,
               const float* u0, int np, int nsplit, double* partial, int pstride, int max_rows,
               DevState* st);
+// dk_out[e] = fixed-order fp64 sum over the first `nrows` partial rows, e < nvalues
+void launch_dk_finish(hipStream_t s, const double* partial, int nrows, int pstride, int nvalues,
+                      DevState* st);
 void launch_swizzle_cols(hipStream_t s, const double* src, int ld, int n, int np, int col0, int ncols,
                          int TS, int dstcol0, float scale, float* dst);
 void launch_extract_col(hipStream_t s, const double* src, int ld, int n, int np, int col, float* dst);

@@ -15,19 +15,12 @@
 // Because K_hat is symmetric, a tile computed at (rows I, cols J) is used to accumulate
 // the output rows J (contraction over I), which is what lets lanes own output columns.
 #include "bbmm_dev.h"
+#include "bbmm_kfun.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
 namespace {
-
-constexpr float kSqrt5 = 2.2360679774997896964f;
-constexpr float kLog2e = 1.4426950408889634074f;
-// sqrt(5) * log2(e) as the nearest float, and ln(2) times what that rounding drops: the exponent
-// is evaluated with the float, the dropped part re-enters as the factor (1 - kMatExpFix * rho),
-// so the value carries no bias that grows with rho.
-constexpr float kMatExpC = 3.225964069366455f;
-constexpr float kMatExpFix = 7.8230743523e-8f;
 
 __device__ inline f32x4 mfma16(float a, float b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -60,39 +53,6 @@ __device__ inline f32x4 fix_diag(f32x4 r2, int lane) {
   for (int r = 0; r < 4; ++r)
     if (ib + r == jc) r2[r] = 0.f;
   return r2;
-}
-
-// Unit-outputscale kernel value from the scaled squared distance.
-//   RBF:      inputs were scaled by sqrt(log2(e)/2)/l, so k/s = 2^(-r2)
-//   Matern52: inputs were scaled by 1/l, rho = sqrt(r2), k/s = (1 + sqrt5 rho + 5/3 rho^2) e^(-sqrt5 rho)
-template <int KIND>
-__device__ inline float unit_kernel(float r2) {
-  if (KIND == 0) {
-    return __builtin_amdgcn_exp2f(-r2);
-  } else {
-    float rho = __builtin_amdgcn_sqrtf(r2);
-    float e = __builtin_amdgcn_exp2f(-kMatExpC * rho);
-    float poly = fmaf(rho, fmaf(rho, 5.f / 3.f, kSqrt5), 1.f);
-    float v = poly * e;
-    return fmaf(-kMatExpFix * rho, v, v);
-  }
-}
-
-// Kernel value and the radial weight g of the lengthscale derivative
-//   dk/dl_d = s * g * (Delta_d / l_d)^2 / l_d,   g = k/s (RBF),  g = (5/3)(1 + sqrt5 rho) e^(-sqrt5 rho) (Matern52)
-template <int KIND>
-__device__ inline void unit_kernel_and_weight(float r2, float& e_out, float& g_out) {
-  if (KIND == 0) {
-    float e = __builtin_amdgcn_exp2f(-r2);
-    e_out = e;
-    g_out = e;
-  } else {
-    float rho = __builtin_amdgcn_sqrtf(r2);
-    float e = __builtin_amdgcn_exp2f(-kMatExpC * rho);
-    e = fmaf(-kMatExpFix * rho, e, e);
-    e_out = fmaf(rho, fmaf(rho, 5.f / 3.f, kSqrt5), 1.f) * e;
-    g_out = (5.f / 3.f) * fmaf(rho, kSqrt5, 1.f) * e;
-  }
 }
 
 // --------------------------------------------------------- materialise K_hat --
@@ -197,7 +157,7 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int jc = lane & 15, g = lane >> 4;
 #pragma unroll 1
-  for (int pc = 0; pc < 2; ++pc) {
+  for (int pc = 0; pc < BBMM_MM_PIECES; ++pc) {
     MmPiece P = plan[blockIdx.x].piece[pc];
     int j_begin = P.row_begin, j_end = P.row_end;
     int col0 = (P.strip * 4 + wave) * (64 * NC);
@@ -703,6 +663,11 @@ int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* X
   int nls = ard ? 4 * KK : 1;
   k_dk_finish<<<2 * (nls + 1), 256, 0, s>>>(partial, nrows, pstride, st);
   return 0;
+}
+
+void launch_dk_finish(hipStream_t s, const double* partial, int nrows, int pstride, int nvalues,
+                      DevState* st) {
+  k_dk_finish<<<nvalues, 256, 0, s>>>(partial, nrows, pstride, st);
 }
 
 void launch_swizzle_cols(hipStream_t s, const double* src, int ld, int n, int np, int col0, int ncols,

@@ -305,15 +305,17 @@ __device__ inline void reduce_argmax(const double* __restrict__ arg, int npart, 
   block_argmax(v, ix, sval, sidx, outv, outi);
 }
 
-// delta = diag(K_XX) = outputscale (stationary kernels); block argmax candidates for pivot 0.
+// delta = diag(K_XX) = outputscale (stationary kernels), or the diagonal handed in (a covariance
+// whose diagonal is not constant); block argmax candidates for pivot 0.
 __global__ __launch_bounds__(VT) void k_pc_init(int n, HypArgs hyp, double* __restrict__ delta,
-                                                 DevState* st, double* __restrict__ arg_out) {
+                                                 DevState* st, double* __restrict__ arg_out,
+                                                 const double* __restrict__ diag_in) {
   __shared__ double sval[VT];
   __shared__ int sidx[VT];
   double bv = -1.0e300;
   int bi = 0x7fffffff;
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
-    double v = hyp.outputscale;
+    double v = diag_in ? diag_in[i] : hyp.outputscale;
     delta[i] = v;
     if (v > bv || (v == bv && i < bi)) {
       bv = v;
@@ -334,11 +336,14 @@ __global__ __launch_bounds__(VT) void k_pc_init(int n, HypArgs hyp, double* __re
 // kernel, column m of L from row piv of K_XX, residual diagonal update, and the candidates for
 // pivot m+1.  Picked rows carry delta = -1.  If the largest residual diagonal has vanished the
 // step (and every later one, which sees the same candidates) does nothing.
+// The pivot's row of the matrix is evaluated in fp64 from X, or read from row_in[i * row_ld]
+// when the caller has formed it (a covariance that is not a plain kernel matrix of X).
 __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int n, int m, int kp,
                                                  HypArgs hyp, double* __restrict__ delta,
                                                  double* __restrict__ L, DevState* st,
                                                  const double* __restrict__ arg_in,
-                                                 double* __restrict__ arg_out, double stop_thresh) {
+                                                 double* __restrict__ arg_out, double stop_thresh,
+                                                 const double* __restrict__ row_in, int row_ld) {
   __shared__ double sval[VT];
   __shared__ int sidx[VT];
   __shared__ double lpiv[BBMM_MAXK];
@@ -372,7 +377,7 @@ __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int
     } else if (di < 0.0) {
       lval = 0.0;                  // already picked
     } else {
-      double kv = kernel_value_f64(X, piv, i, hyp);
+      double kv = row_in ? row_in[(size_t)i * row_ld] : kernel_value_f64(X, piv, i, hyp);
       for (int j = 0; j < m; ++j) kv -= lpiv[j] * (double)L[(size_t)i * kp + j];
       lval = kv / root;
       di = di - lval * lval;
@@ -1212,14 +1217,15 @@ void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int n
 }
 
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
-                    int nblocks) {
-  k_pc_init<<<nblocks, VT, 0, s>>>(n, hyp, delta, st, arg_out);
+                    int nblocks, const double* diag_in) {
+  k_pc_init<<<nblocks, VT, 0, s>>>(n, hyp, delta, st, arg_out, diag_in);
 }
 
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
-                    double* L, DevState* st, const double* arg_in, double* arg_out, int nblocks) {
+                    double* L, DevState* st, const double* arg_in, double* arg_out, int nblocks,
+                    const double* row_in, int row_ld) {
   double thresh = 1e-12 * hyp.outputscale;
-  k_pc_step<<<nblocks, VT, 0, s>>>(X, n, m, kp, hyp, delta, L, st, arg_in, arg_out, thresh);
+  k_pc_step<<<nblocks, VT, 0, s>>>(X, n, m, kp, hyp, delta, L, st, arg_in, arg_out, thresh, row_in, row_ld);
 }
 
 void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, double noise, DevState* st,

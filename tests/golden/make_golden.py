@@ -18,6 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(HERE))
 sys.path.insert(0, ROOT)
 
 from oracle import bbmm_oracle as O                      # noqa: E402
+from oracle import sgpr_oracle as S                      # noqa: E402
 from paper_1809_11165_amd import inputs                  # noqa: E402
 
 N_SAMPLE = 128
@@ -111,9 +112,83 @@ MATRIX_FREE_CASES = {
 }
 
 
+SGPR_CASES = {
+    # name: (config, n, m): subset-of-regressors covariance, oracle/sgpr_oracle.py
+    "cfg5_n500000": (5, 500000, 1024),
+    "cfg5_sub_n50000": (5, 50000, 1024),
+}
+
+
+def run_sgpr(name: str, cfg: int, n: int, m: int):
+    """Configuration 5 (SGPR): the oracle's BBMM call on the SoR covariance, the size of its last
+    update, a second fp64 run with the products grouped through the root A = K_XU G^-T (another
+    rounding order of the same operator), and the plain definition by the Woodbury identity."""
+    import scipy.linalg as sla
+    w = inputs.make(cfg, n=n, m=m)
+    t0 = time.time()
+
+    def say(msg):
+        print("[%s %.0fs] %s" % (name, time.time() - t0, msg), flush=True)
+
+    args = (w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise, w.jitter_rel, w.E1, w.E2)
+    res = S.sor_bbmm_inference(*args, w.k, w.iters, tol=w.tol, progress=say)
+    it = int(res.mbcg.iters_run)
+    parts = S.sor_parts(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.noise, w.jitter_rel)
+    P = O.make_preconditioner(res.L, w.noise)
+    norm = lambda A: np.linalg.norm(A, axis=0)
+    say("rerun to iteration %d" % (it - 1))
+    prev = O.mbcg(parts.khat_matmul, res.B, P.solve, it - 1)
+    last_step = norm(res.U - prev.U) / norm(res.U)
+    del prev
+    say("rerun with products grouped through the root")
+    A = sla.solve_triangular(parts.chol_UU, parts.KXU.T, lower=True).T
+    other = O.mbcg(lambda M: A @ (A.T @ M) + w.noise * M, res.B, P.solve, it)
+    reorder_dev = norm(res.U - other.U) / norm(res.U)
+    del A
+    # the derivative terms of that second run: u^T dQ w is a small difference of large terms, so at
+    # an unconverged iteration count its value moves with the rounding order far more than U does
+    say("derivative terms of the second run")
+    dargs = (w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel, parts)
+    trace_alt = list(S.sor_derivative_products(*dargs, other.U[:, 1:], other.Z0[:, 1:]) / w.t)
+    quad_alt = list(S.sor_derivative_products(*dargs, other.U[:, :1], other.U[:, :1]))
+    trace_alt.append(float(np.sum(other.U[:, 1:] * other.Z0[:, 1:]) / w.t))
+    quad_alt.append(float(other.U[:, 0] @ other.U[:, 0]))
+    del other
+    say("Woodbury solve and log-determinant")
+    u_exact, logdet_exact = S.sor_woodbury(parts, w.y)
+    yKinvy_exact = float(w.y.astype(np.float64) @ u_exact)
+    rows = sample_rows(n, cfg)
+    out = {
+        "source": "oracle/sgpr_oracle.py sor_bbmm_inference on paper_1809_11165_amd.inputs.make(%d, n=%d, m=%d)"
+                  % (cfg, n, m),
+        "config": cfg, "n": n, "m": m, "d": w.d, "t": w.t, "k": w.k, "iters_cap": w.iters, "tol": w.tol,
+        "iters_run": it, "pivots": res.pivots.tolist(), "pivot_dmax": res.pivot_dmax.tolist(),
+        "logdet": res.logdet, "logdet_precond": res.logdet_precond, "yKinvy": res.yKinvy,
+        "nlml": res.nlml, "trace": res.trace.tolist(), "quad": res.quad.tolist(),
+        "grad": res.grad.tolist(), "slq_terms": res.slq_terms.tolist(),
+        "alpha": res.mbcg.alpha.tolist(), "beta": res.mbcg.beta.tolist(),
+        "resid": res.mbcg.resid.tolist(), "rho0": res.mbcg.rho0.tolist(),
+        "sample_rows": rows.tolist(), "U_sample": res.U[rows].tolist(),
+        "U_colnorm": norm(res.U).tolist(),
+        "exact_logdet": logdet_exact, "exact_yKinvy": yKinvy_exact,
+        "u0_sample_exact": u_exact[rows].tolist(),
+        "u0_rel_err_vs_exact": float(np.linalg.norm(res.U[:, 0] - u_exact) / np.linalg.norm(u_exact)),
+        "U_last_step": last_step.tolist(), "U_reorder_dev": reorder_dev.tolist(),
+        "trace_alt": [float(v) for v in trace_alt], "quad_alt": [float(v) for v in quad_alt],
+        "L_sample": res.L[rows].tolist(),
+        "seconds": time.time() - t0,
+    }
+    path = os.path.join(OUT_DIR, name + ".json")
+    with open(path, "w") as f:
+        json.dump(out, f)
+    print("wrote", path, "in %.0f s" % out["seconds"], flush=True)
+
+
 def run(name: str):
     if name in MATRIX_FREE_CASES:
         return run_matrix_free(name, *MATRIX_FREE_CASES[name])
+    if name in SGPR_CASES:
+        return run_sgpr(name, *SGPR_CASES[name])
     cfg, n, kw = CASES[name]
     w = inputs.make(cfg, n=n, **kw)
     t0 = time.time()
@@ -202,5 +277,5 @@ if __name__ == "__main__":
         OUT_DIR = args[i + 1]
         os.makedirs(OUT_DIR, exist_ok=True)
         del args[i:i + 2]
-    for nm in (args or list(CASES) + list(MATRIX_FREE_CASES)):
+    for nm in (args or list(CASES) + list(MATRIX_FREE_CASES) + list(SGPR_CASES)):
         run(nm)
