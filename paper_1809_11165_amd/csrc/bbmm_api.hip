@@ -345,11 +345,12 @@ int stage_sgpr_build(bbmm_ctx* c) {
                   ptr<double>(c->KUU));
   launch_sgpr_chol(s, ptr<double>(c->KUU), ptr<double>(c->Gm), c->mp, 1e-13 * c->prob.outputscale, st);
   launch_sgpr_trinv(s, ptr<double>(c->Gm), ptr<double>(c->Ginv), c->mp);
-  if (c->mp > c->m)
-    launch_fill_f64(s, ptr<double>(c->Kux) + (size_t)c->m * np, (mp - (size_t)c->m) * np, 0.0);
-  if (launch_sgpr_kux(s, c->prob.X, c->prob.Uind, c->n, c->np, c->m, c->dp, c->hyp, ptr<double>(c->Kux)))
+  if (c->mp > c->m) launch_fill_f64(s, ptr<double>(c->Kux), mp * np, 0.0);   // padding rows of every panel
+  if (launch_sgpr_kux(s, c->prob.X, c->prob.Uind, c->n, c->np, c->m, c->mp, c->dp, c->hyp, ptr<double>(c->Kux)))
     return fail(c, BBMM_EINVAL, "unsupported input dimension");
-  launch_sgpr_root(s, ptr<double>(c->Ginv), ptr<double>(c->Kux), c->mp, c->np, ptr<float>(c->AT));
+  // the Cholesky work matrix is free again: it receives G^{-1} in MFMA operand order
+  launch_sgpr_root(s, ptr<double>(c->Ginv), ptr<double>(c->KUU), ptr<double>(c->Kux), c->mp, c->np,
+                   ptr<float>(c->AT));
   launch_transpose_f32(s, ptr<float>(c->AT), c->mp, c->np, ptr<float>(c->A));
   launch_sgpr_qdiag(s, ptr<float>(c->A), c->n, c->mp, ptr<double>(c->qdiag));
   // inducing inputs in the centred, scaled coordinates of X (for the derivative pair sums)

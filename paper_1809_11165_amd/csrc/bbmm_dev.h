@@ -122,9 +122,10 @@ void launch_sgpr_kuu(hipStream_t s, const float* Uind, int m, int mp, HypArgs hy
                      double* KUU);
 void launch_sgpr_chol(hipStream_t s, double* KUU, double* G, int mp, double tiny, DevState* st);
 void launch_sgpr_trinv(hipStream_t s, const double* G, double* Ginv, int mp);
-int launch_sgpr_kux(hipStream_t s, const float* X, const float* Uind, int n, int np, int m, int dp,
+int launch_sgpr_kux(hipStream_t s, const float* X, const float* Uind, int n, int np, int m, int mp, int dp,
                     HypArgs hyp, double* Kux);
-void launch_sgpr_root(hipStream_t s, const double* Ginv, const double* Kux, int mp, int np, float* AT);
+void launch_sgpr_root(hipStream_t s, const double* Ginv, double* GinvP, const double* Kux, int mp, int np,
+                      float* AT);
 void launch_transpose_f32(hipStream_t s, const float* src, int rows, int cols, float* dst);
 void launch_sgpr_qdiag(hipStream_t s, const float* A, int n, int mp, double* qdiag);
 void launch_sgpr_mid(hipStream_t s, const double* Tp, VpShape shape, int mp, int ld, const DevState* st,

@@ -6,7 +6,7 @@
 //   * k_kuu_f64, k_chol_panel / k_chol_update, k_trinv_diag / k_trinv_off: K_UU, its Cholesky
 //     factor and G^{-1}, all fp64 (m x m is small);
 //   * k_kux_f64: K_UX in fp64 from the raw inputs;
-//   * k_sgpr_root: A^T = G^{-1} K_UX by fp64 MFMA, rounded ONCE to fp32 (rows of A have norm
+//   * k_sgpr_root: A^T = G^{-1} K_UX by fp64 MFMA (LDS-staged), rounded ONCE to fp32 (rows of A have norm
 //     sqrt(Q_ii) <= sqrt(s), so the rounding perturbs Q by ~1e-7 s, like an fp32 kernel matrix);
 //   * k_transpose_f32: A from A^T (both layouts are streamed once per iteration).
 // Derivative terms (Eq. (4),(8) with the derivative of the SoR matrix): dQ = dK_XU Kinv K_UX +
@@ -216,16 +216,32 @@ __global__ __launch_bounds__(256) void k_trinv_off(const double* __restrict__ G,
   }
 }
 
+// G^{-1} in the order the root kernel feeds its MFMAs: GinvP[row / 16][col / 4][(col % 4) * 16 + row % 16]
+__global__ void k_pack_ginv(const double* __restrict__ Ginv, int mp, double* __restrict__ GinvP) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)mp * mp) return;
+  int lane = (int)(idx & 63);
+  size_t blk = idx >> 6;
+  int ks = (int)(blk % (mp / 4)), rt = (int)(blk / (mp / 4));
+  int row = rt * 16 + (lane & 15), col = ks * 4 + (lane >> 4);
+  GinvP[idx] = Ginv[(size_t)row * mp + col];
+}
+
 // ---------------------------------------------------------- K_UX, fp64 -------
-// Kux[b][i] = k(u_b, x_i), b < m, i < n; zero for padding points.  Thread = one point, a run of
-// KUX_RUN inducing inputs (their coordinates are uniform across the wave).
+// K_UX in fp64: k(u_b, x_i), b < m, i < n; zero for padding points.  Stored in panels of 128
+// points, and inside a panel in the order the root kernel feeds its MFMAs,
+//   Kux[panel][b / 4][(i % 128) / 16][(b % 4) * 16 + i % 16],
+// so that 16 consecutive b's of a panel are 16 KB of contiguous memory that the root kernel
+// copies to LDS as it is.  Thread = one point, a run of KUX_RUN inducing inputs (their
+// coordinates are uniform across the wave).
 constexpr int KUX_RUN = 16;
 
 template <int DP>
 __global__ __launch_bounds__(256) void k_kux_f64(const float* __restrict__ X,
-                                                  const float* __restrict__ Uind, int n, int np,
+                                                  const float* __restrict__ Uind, int n, int mp,
                                                   int m, HypArgs hyp, double* __restrict__ Kux) {
   int i = blockIdx.x * 256 + threadIdx.x;
+  double* panel = Kux + (size_t)(i >> 7) * mp * 128 + ((i & 127) >> 4) * 64 + (i & 15);
   int b0 = blockIdx.y * KUX_RUN;
   double xi[DP];
 #pragma unroll
@@ -247,55 +263,113 @@ __global__ __launch_bounds__(256) void k_kux_f64(const float* __restrict__ X,
       double rho = sqrt(rho2);
       v = hyp.outputscale * (1.0 + s5 * rho + (5.0 / 3.0) * rho2) * exp(-s5 * rho);
     }
-    Kux[(size_t)b * np + i] = (i < n) ? v : 0.0;
+    panel[(size_t)(b >> 2) * 512 + (b & 3) * 16] = (i < n) ? v : 0.0;
   }
 }
 
 // ------------------------------------------------- root: A^T = G^{-1} K_UX ---
 // Workgroup: 128 rows of A^T (inducing index a) x 128 points; wave w: rows 32 w .. 32 w + 31
-// (2 row tiles) x 8 point tiles.  G^{-1} is lower triangular, so the contraction index b stops
-// at the end of the row block.  Operands come straight from global memory (G^{-1} is 8 MB and
-// stays in cache; the four waves read the same K_UX operands); the operands of the next step
-// are requested before the MFMAs of the current one.
-constexpr int RT_ROWS = 128, RT_PTS = 128;
+// (2 row tiles) x 8 point tiles = 16 fp64 MFMA accumulators.  G^{-1} is lower triangular, so the
+// contraction index b stops at the end of the row block.  Chunks of 16 b's are staged through
+// LDS in MFMA operand order ([tile][lane], so every operand read is 512 contiguous bytes); both
+// operands already lie in that order in global memory (k_pack_ginv, k_kux_f64), so the staging
+// is a plain copy, 16 bytes per lane, requested one chunk ahead of the arithmetic.  (Operands
+// read straight from global memory, 16 cache lines per G^{-1} operand, kept the kernel at 21 %
+// of the fp64 matrix rate: the address units were the limit, not the MFMAs.)
+//
+// Work differs 8 : 1 between the last and the first row block, and the hardware deals
+// consecutive workgroups round-robin to the 8 XCDs.  With (row block, panel) = (id % 8, id / 8)
+// one XCD would get all the longest workgroups and the launch would take 64/36 of the balanced
+// time (measured: the compute units were busy 55 % of the launch).  So the flat id is decoded as
+// XCD x = id % 8, sequence j = id / 8 on that XCD: panel = (j / nrb) * 8 + x, row block =
+// nrb - 1 - j % nrb -- every XCD walks whole panels, longest row block first, and re-reads the
+// K_UX panel from its own L2.
+constexpr int RT_ROWS = 128, RT_PTS = 128, RT_BK = 16;
 
-__global__ __launch_bounds__(256) void k_sgpr_root(const double* __restrict__ Ginv,
-                                                    const double* __restrict__ Kux, int mp, int np,
-                                                    float* __restrict__ AT) {
-  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+__global__ __launch_bounds__(256, 2) void k_sgpr_root(const double* __restrict__ GinvP,
+                                                       const double* __restrict__ Kux, int mp, int np,
+                                                       float* __restrict__ AT) {
+  __shared__ double sA[2][8 * 4][64];   // [buffer][row tile * 4 + k step][lane]
+  __shared__ double sB[2][4 * 8][64];   // [buffer][k step * 8 + point tile][lane]
+  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int g = lane >> 4, jc = lane & 15;
-  int a0 = blockIdx.x * RT_ROWS + wave * 32;
-  int i0 = blockIdx.y * RT_PTS;
-  int b_end = min(mp, (int)(blockIdx.x + 1) * RT_ROWS);
+  int nrb = mp / RT_ROWS;
+  int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+  int panel = (seq / nrb) * 8 + xcd;
+  if (panel >= np / RT_PTS) return;
+  int a_blk = (nrb - 1 - seq % nrb) * RT_ROWS;
+  int i0 = panel * RT_PTS;
+  int nchunks = min(mp, a_blk + RT_ROWS) / RT_BK;
   f64x4 acc[2][8];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
     for (int ct = 0; ct < 8; ++ct) acc[rt][ct] = (f64x4){0.0, 0.0, 0.0, 0.0};
-  const double* ga = Ginv + (size_t)(a0 + jc) * mp + g;            // + rt*16*mp + b
-  const double* kb = Kux + (size_t)g * np + (size_t)(i0 + jc);     // + b*np + ct*16
-  double an[2], bn[8];
+
+  // staging: both operands lie in global memory in LDS order, so a chunk is 8 pieces of 2 KB of
+  // G^{-1} (one per row tile) and 16 KB of the K_UX panel, copied 16 bytes per thread and item
+  typedef double f64x2 __attribute__((ext_vector_type(2)));
+  f64x2 ra[4], rb[4];
+  const double* gA[4];
+  const double* gB[4];
+  int ia[4], ib[4];
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) an[rt] = ga[(size_t)rt * 16 * mp];
+  for (int u = 0; u < 4; ++u) {
+    int e = tid + 256 * u;
+    int rt = e >> 7, w2 = 2 * (e & 127);
+    gA[u] = GinvP + ((size_t)(a_blk / 16 + rt) * (mp / 4)) * 64 + w2;
+    ia[u] = rt * 256 + w2;
+    gB[u] = Kux + (size_t)panel * mp * RT_PTS + 2 * e;
+    ib[u] = 2 * e;
+  }
 #pragma unroll
-  for (int ct = 0; ct < 8; ++ct) bn[ct] = kb[ct * 16];
-  for (int b = 0; b < b_end; b += 4) {
-    double ac[2], bc[8];
+  for (int u = 0; u < 4; ++u) {
+    ra[u] = *(const f64x2*)(gA[u]);
+    rb[u] = *(const f64x2*)(gB[u]);
+  }
+  double* fa = &sA[0][0][0];
+  double* fb = &sB[0][0][0];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) ac[rt] = an[rt];
+  for (int u = 0; u < 4; ++u) {
+    *(f64x2*)(fa + ia[u]) = ra[u];
+    *(f64x2*)(fb + ib[u]) = rb[u];
+  }
+  __syncthreads();
+  for (int c = 0; c < nchunks; ++c) {
+    int buf = c & 1;
+    bool more = c + 1 < nchunks;
+    if (more) {
+      int b0 = (c + 1) * RT_BK;
 #pragma unroll
-    for (int ct = 0; ct < 8; ++ct) bc[ct] = bn[ct];
-    if (b + 4 < b_end) {
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) an[rt] = ga[(size_t)rt * 16 * mp + (b + 4)];
-#pragma unroll
-      for (int ct = 0; ct < 8; ++ct) bn[ct] = kb[(size_t)(b + 4) * np + ct * 16];
+      for (int u = 0; u < 4; ++u) {
+        ra[u] = *(const f64x2*)(gA[u] + (size_t)b0 * 16);          // (b0 / 4) k steps of 64 doubles
+        rb[u] = *(const f64x2*)(gB[u] + (size_t)b0 * RT_PTS);
+      }
     }
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
+    for (int kk = 0; kk < 4; ++kk) {
+      double av[2], bv[8];
 #pragma unroll
-      for (int ct = 0; ct < 8; ++ct) acc[rt][ct] = mfma16d(ac[rt], bc[ct], acc[rt][ct]);
+      for (int rt = 0; rt < 2; ++rt) av[rt] = sA[buf][(wave * 2 + rt) * 4 + kk][lane];
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) bv[ct] = sB[buf][kk * 8 + ct][lane];
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) acc[rt][ct] = mfma16d(av[rt], bv[ct], acc[rt][ct]);
+    }
+    if (more) {
+      double* na = &sA[buf ^ 1][0][0];
+      double* nb = &sB[buf ^ 1][0][0];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        *(f64x2*)(na + ia[u]) = ra[u];
+        *(f64x2*)(nb + ib[u]) = rb[u];
+      }
+    }
+    __syncthreads();
   }
+  int a0 = a_blk + wave * 32;
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
@@ -636,24 +710,31 @@ void launch_sgpr_trinv(hipStream_t s, const double* G, double* Ginv, int mp) {
   if (nblk > 1) k_trinv_off<<<nblk - 1, 256, 0, s>>>(G, Ginv, mp);
 }
 
-// Kux: mp x np doubles; rows m..mp-1 must be zero (the caller zero-fills them).
-int launch_sgpr_kux(hipStream_t s, const float* X, const float* Uind, int n, int np, int m, int dp,
+// Kux: (np / 128) panels of mp x 128 doubles; rows m..mp-1 of every panel must be zero (the
+// caller zero-fills the buffer when mp > m).
+int launch_sgpr_kux(hipStream_t s, const float* X, const float* Uind, int n, int np, int m, int mp, int dp,
                     HypArgs hyp, double* Kux) {
   dim3 grid(np / 256, (m + KUX_RUN - 1) / KUX_RUN);
   switch (dp) {
-    case 4: k_kux_f64<4><<<grid, 256, 0, s>>>(X, Uind, n, np, m, hyp, Kux); break;
-    case 8: k_kux_f64<8><<<grid, 256, 0, s>>>(X, Uind, n, np, m, hyp, Kux); break;
-    case 16: k_kux_f64<16><<<grid, 256, 0, s>>>(X, Uind, n, np, m, hyp, Kux); break;
-    case 32: k_kux_f64<32><<<grid, 256, 0, s>>>(X, Uind, n, np, m, hyp, Kux); break;
-    case 64: k_kux_f64<64><<<grid, 256, 0, s>>>(X, Uind, n, np, m, hyp, Kux); break;
+    case 4: k_kux_f64<4><<<grid, 256, 0, s>>>(X, Uind, n, mp, m, hyp, Kux); break;
+    case 8: k_kux_f64<8><<<grid, 256, 0, s>>>(X, Uind, n, mp, m, hyp, Kux); break;
+    case 16: k_kux_f64<16><<<grid, 256, 0, s>>>(X, Uind, n, mp, m, hyp, Kux); break;
+    case 32: k_kux_f64<32><<<grid, 256, 0, s>>>(X, Uind, n, mp, m, hyp, Kux); break;
+    case 64: k_kux_f64<64><<<grid, 256, 0, s>>>(X, Uind, n, mp, m, hyp, Kux); break;
     default: return 1;
   }
   return 0;
 }
 
-// AT (mp x np) = Ginv Kux in fp32; mp and np are multiples of 256.
-void launch_sgpr_root(hipStream_t s, const double* Ginv, const double* Kux, int mp, int np, float* AT) {
-  k_sgpr_root<<<dim3(mp / RT_ROWS, np / RT_PTS), 256, 0, s>>>(Ginv, Kux, mp, np, AT);
+// AT (mp x np) = Ginv Kux in fp32; mp and np are multiples of 256.  GinvP: scratch of mp x mp
+// doubles that receives G^{-1} in MFMA operand order.
+void launch_sgpr_root(hipStream_t s, const double* Ginv, double* GinvP, const double* Kux, int mp, int np,
+                      float* AT) {
+  size_t total = (size_t)mp * mp;
+  k_pack_ginv<<<(int)((total + 255) / 256), 256, 0, s>>>(Ginv, mp, GinvP);
+  int panels = np / RT_PTS, nrb = mp / RT_ROWS;
+  int grid = ((panels + 7) / 8) * nrb * 8;
+  k_sgpr_root<<<grid, 256, 0, s>>>(GinvP, Kux, mp, np, AT);
 }
 
 void launch_transpose_f32(hipStream_t s, const float* src, int rows, int cols, float* dst) {
