@@ -82,6 +82,12 @@ enum { BBMM_MODE_MATERIALISED = 0, BBMM_MODE_ONTHEFLY = 1, BBMM_MODE_SGPR = 2 };
  *                probes are z_i = L_k E1[:,i] + sigma E2[:,i]  (App. C, sampling from N(0,P))
  *   m, Uind, jitter_rel   BBMM_MODE_SGPR only (ignored otherwise): number of inducing inputs,
  *                device m x d float (coordinates of X), relative jitter >= 0
+ *   pivots_in    host, k distinct row indices, or NULL.  NULL: the greedy rule of App. C (largest
+ *                residual diagonal, lowest index on ties).  Otherwise the pivoted Cholesky takes
+ *                these rows in this order.  The greedy order is not unique under rounding when
+ *                residual diagonals tie (a stationary kernel's diagonal is constant; the inducing
+ *                rows of an SoR matrix agree to ~1e-10), so a caller who needs the same
+ *                preconditioner as another run or implementation passes that run's pivots.
  */
 typedef struct {
   int32_t kernel;
@@ -99,6 +105,7 @@ typedef struct {
   int64_t m;
   const float* Uind;
   double jitter_rel;
+  const int64_t* pivots_in;
 } bbmm_problem;
 
 /*
@@ -150,6 +157,8 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *                compute unit; clamped to [strips, 60 * strips], strips = column strips of K_hat)
  *   "otf_split"  number of row chunks an on-the-fly product is split into
  *   "ur_blocks"  upper limit of the workgroups of the fused U/R update (default 128, at most 512)
+ *   "sgpr_wgs1", "sgpr_wgs2"  workgroups of the two streaming products of an SGPR product
+ *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build
  *   "time_mm"    1: record HIP events on the context's stream around every K_hat.M launch of
  *                the next mBCG runs (read back with bbmm_mm_timing); 0: off (default)
  * value <= 0 restores the default.  Unknown key: BBMM_EINVAL. */

@@ -133,31 +133,61 @@ def sor_woodbury(parts: SorParts, y: np.ndarray):
     return u0, float(logdet)
 
 
-def sor_derivative_products(kernel: int, X, Uind, ls, s: float, jitter_rel: float, parts: SorParts,
-                            Ucols: np.ndarray, Wcols: np.ndarray, row_chunk: int = 16384):
-    """sum_c Ucols[:, c]^T (dQ/dtheta_h) Wcols[:, c] for every kernel hyperparameter
-    (lengthscale(s), outputscale), matrix-free: the three terms of dQ applied to the columns with
-    the n x m derivative blocks formed a block of rows at a time."""
+def sor_derivative_matvec(kernel: int, X, Uind, ls, s: float, jitter_rel: float, parts: SorParts,
+                          W: np.ndarray, row_chunk: int = 16384) -> list:
+    """[(dQ/dtheta_h) W for every kernel hyperparameter h] (lengthscale(s), outputscale), each
+    n x c, matrix-free: the three terms of dQ applied right to left, with the n x m derivative
+    blocks formed a block of rows at a time."""
     X = np.asarray(X, dtype=np.float64)
     Uind = np.asarray(Uind, dtype=np.float64)
     ls = np.atleast_1d(np.asarray(ls, dtype=np.float64))
+    W = np.asarray(W, dtype=np.float64)
     m = Uind.shape[0]
     n = X.shape[0]
-    AU = parts.kuu_solve(parts.KXU.T @ Ucols)      # K_UU^{-1} K_UX u, m x c
-    AW = parts.kuu_solve(parts.KXU.T @ Wcols)
     H = ls.shape[0] + 1
-    out = np.zeros(H)
+    AW = parts.kuu_solve(parts.KXU.T @ W)              # K_UU^{-1} K_UX W, m x c
+    out = [np.empty((n, W.shape[1])) for _ in range(H)]
+    dKW = [np.zeros((m, W.shape[1])) for _ in range(H)]      # dK_UX W, summed over the row blocks
     for a in range(0, n, row_chunk):
         b = min(n, a + row_chunk)
         dXU = O.kernel_derivative_blocks(kernel, X[a:b], Uind, ls, s)
         for h in range(H):
-            # u^T dK_XU (Kinv K_UX w)  +  (Kinv K_UX u)^T dK_UX w
-            out[h] += np.sum(Ucols[a:b] * (dXU[h] @ AW)) + np.sum(Wcols[a:b] * (dXU[h] @ AU))
+            out[h][a:b] = dXU[h] @ AW                        # dK_XU (Kinv K_UX W)
+            dKW[h] += dXU[h].T @ W[a:b]
     dUU = O.kernel_derivative_blocks(kernel, Uind, Uind, ls, s)
     dUU[-1] = dUU[-1] + jitter_rel * np.eye(m)
     for h in range(H):
-        out[h] -= np.sum(AU * (dUU[h] @ AW))
+        # + K_XU Kinv (dK_UX W) - K_XU Kinv dK_UU (Kinv K_UX W)
+        out[h] += parts.KXU @ parts.kuu_solve(dKW[h] - dUU[h] @ AW)
     return out
+
+
+def sor_derivative_products(kernel: int, X, Uind, ls, s: float, jitter_rel: float, parts: SorParts,
+                            Ucols: np.ndarray, Wcols: np.ndarray, row_chunk: int = 16384):
+    """sum_c Ucols[:, c]^T (dQ/dtheta_h) Wcols[:, c] for every kernel hyperparameter
+    (lengthscale(s), outputscale)."""
+    MW = sor_derivative_matvec(kernel, X, Uind, ls, s, jitter_rel, parts, Wcols, row_chunk)
+    return np.array([np.sum(np.asarray(Ucols, dtype=np.float64) * M) for M in MW])
+
+
+def sor_term_sensitivity(kernel: int, X, Uind, ls, s: float, jitter_rel: float, parts: SorParts,
+                         U: np.ndarray, W: np.ndarray):
+    """First-order bounds on how far the trace and quadratic terms can move when the solves move:
+    if every column u_i changes by at most eps |u_i| (W = P^{-1} Z is fixed), then
+        |delta trace_h| <= eps * (1/t) sum_i |u_i| |M_h w_i|,
+        |delta quad_h|  <= eps * 2 |u_0| |M_h u_0|          (plus O(eps^2)),
+    by Cauchy-Schwarz.  U: n x (t+1) (column 0 = u_0), W: n x t.  Returns (trace_sens, quad_sens),
+    one entry per hyperparameter, noise (M = I) last.  Test infrastructure: the parity tests use it
+    to turn the bound on the iterate into a bound on terms that cancel heavily."""
+    U = np.asarray(U, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    t = W.shape[1]
+    norm = lambda A: np.linalg.norm(A, axis=0)
+    MW = sor_derivative_matvec(kernel, X, Uind, ls, s, jitter_rel, parts, W) + [W]
+    Mu = sor_derivative_matvec(kernel, X, Uind, ls, s, jitter_rel, parts, U[:, :1]) + [U[:, :1]]
+    tr = np.array([np.sum(norm(U[:, 1:]) * norm(M)) / t for M in MW])
+    qd = np.array([2.0 * norm(U[:, :1])[0] * norm(M)[0] for M in Mu])
+    return tr, qd
 
 
 def sor_bbmm_inference(kernel: int, X, Uind, y, ls, s: float, noise: float, jitter_rel: float,

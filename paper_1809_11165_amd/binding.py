@@ -46,7 +46,8 @@ class _Problem(C.Structure):
                 ("n_lengthscale", C.c_int64), ("lengthscale", C.POINTER(C.c_double)),
                 ("outputscale", C.c_double), ("noise", C.c_double),
                 ("X", C.c_void_p), ("y", C.c_void_p), ("E1", C.c_void_p), ("E2", C.c_void_p),
-                ("m", C.c_int64), ("Uind", C.c_void_p), ("jitter_rel", C.c_double)]
+                ("m", C.c_int64), ("Uind", C.c_void_p), ("jitter_rel", C.c_double),
+                ("pivots_in", C.POINTER(C.c_int64))]
 
 
 class _Result(C.Structure):
@@ -144,6 +145,7 @@ class Problem:
     tol: float = 0.0
     Uind: "object" = None           # SGPR only: m x d device tensor of inducing inputs
     jitter_rel: float = 0.0         # SGPR only
+    pivots_in: Optional[np.ndarray] = None   # replay this pivot order instead of the greedy rule
     _keep: list = field(default_factory=list, repr=False)
 
     def to_c(self) -> _Problem:
@@ -167,6 +169,13 @@ class Problem:
         p.E1 = self.E1.data_ptr() if self.k > 0 else None
         p.E2 = self.E2.data_ptr()
         p.m, p.Uind, p.jitter_rel = 0, None, 0.0
+        p.pivots_in = None
+        if self.pivots_in is not None:
+            piv = np.ascontiguousarray(self.pivots_in, dtype=np.int64)
+            if piv.shape != (int(self.k),):
+                raise ValueError("pivots_in must have k entries")
+            self._keep.append(piv)
+            p.pivots_in = piv.ctypes.data_as(C.POINTER(C.c_int64))
         if self.mode == MODE_SGPR:
             if self.Uind is None:
                 raise ValueError("an SGPR problem needs Uind")

@@ -38,6 +38,7 @@ struct bbmm_ctx {
   bool is_setup = false;
   bbmm_problem prob{};
   std::vector<double> ls;
+  std::vector<int> forced;                  // replayed pivot order (empty = greedy rule)
   int n = 0, d = 0, t = 0, k = 0, kp = 0, np = 0, KK = 0, dp = 0, maxit = 0;
   int m = 0, mp = 0;                        // inducing inputs (SGPR), padded to 256
   HypArgs hyp{};
@@ -46,6 +47,7 @@ struct bbmm_ctx {
   int last_c = 0, last_ld = 0, last_t = 0;   // shape of the last mBCG run
 
   int64_t mat_wgs = 0, otf_split = 0;        // 0 = default
+  int64_t sgpr_wgs[2] = {0, 0};              // workgroups of the two SGPR streaming products (0 = default)
   int64_t ur_blocks_cap = 0;
   // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
   int plan_np = 0, plan_wgs[2] = {0, 0};
@@ -53,6 +55,7 @@ struct bbmm_ctx {
   // SGPR: plans of the two streaming products per block width: [v] = A (rows np, columns mp),
   // [2 + v] = A^T (rows mp, columns np)
   int sg_np = 0, sg_mp = 0, sg_wgs[4] = {0, 0, 0, 0}, sg_slots[4] = {0, 0, 0, 0};
+  int64_t sg_tune[2] = {-1, -1};
   bool time_mm = false;                      // record HIP events around every product launch
   std::vector<hipEvent_t> ev;                // 2 per iteration, created on demand
   int ev_iters = 0;                          // iterations covered by the last timed run
@@ -219,13 +222,17 @@ int ensure_mat_plans(bbmm_ctx* c) {
   return BBMM_OK;
 }
 
-// Workgroups for streaming a rows_p x cols_p matrix: whole rounds of num_cus, enough of them that
-// a run is at most two strips long (so at most three pieces), never more than there are units.
-int rect_wgs_of(const bbmm_ctx* c, int rows_p, int cols_p, int ld, int slot_cap) {
+// Workgroups for streaming a rows_p x cols_p matrix.  With at least one column strip per compute
+// unit every workgroup takes one whole strip: a piece that ends inside a strip costs a pipeline
+// drain, a partial result to store and one more to add later (measured at 1024 x 500,224: 373 us
+// with 256 balanced runs of ~3 pieces, 320 us with 489 whole strips).  Otherwise whole rounds of
+// num_cus balanced runs, never more than there are units.
+int rect_wgs_of(const bbmm_ctx* c, int rows_p, int cols_p, int ld, int slot_cap, int64_t tuned) {
   int cols_per_wg = (ld == 32) ? 512 : 1024;
   int strips = (cols_p + cols_per_wg - 1) / cols_per_wg;
   long long units = (long long)strips * (rows_p / 16);
-  long long w = (long long)c->num_cus * std::max(1, (strips + 2 * c->num_cus - 1) / (2 * c->num_cus));
+  long long w = (strips >= c->num_cus) ? strips : c->num_cus;
+  if (tuned > 0) w = tuned;
   w = std::min<long long>(w, (long long)(slot_cap - 4) * strips);
   w = std::min<long long>(w, units);
   w = std::max<long long>(w, std::min<long long>(units, (strips + 1) / 2));
@@ -235,15 +242,16 @@ int rect_wgs_of(const bbmm_ctx* c, int rows_p, int cols_p, int ld, int slot_cap)
 constexpr int kSgprSlotCap = 1024;   // partial results of A^T D: one per workgroup when m <= 1024
 
 int ensure_sgpr_plans(bbmm_ctx* c) {
-  if (c->sg_np == c->np && c->sg_mp == c->mp) return BBMM_OK;
+  if (c->sg_np == c->np && c->sg_mp == c->mp && c->sg_tune[0] == c->sgpr_wgs[0] && c->sg_tune[1] == c->sgpr_wgs[1])
+    return BBMM_OK;
   HIPCHK(c, hipStreamSynchronize(c->stream));
   for (int v = 0; v < 2; ++v) {
     int ld = v ? 32 : 16;
-    int w1 = rect_wgs_of(c, c->np, c->mp, ld, kSgprSlotCap);
+    int w1 = rect_wgs_of(c, c->np, c->mp, ld, kSgprSlotCap, c->sgpr_wgs[0]);
     int rc = make_plan(c, c->np, c->mp, ld, w1, kSgprSlotCap, c->sgplan[v], c->sgnseg[v], &c->sg_slots[v]);
     if (rc) return rc;
     c->sg_wgs[v] = w1;
-    int w2 = rect_wgs_of(c, c->mp, c->np, ld, kMaxSplit);
+    int w2 = rect_wgs_of(c, c->mp, c->np, ld, kMaxSplit, c->sgpr_wgs[1]);
     rc = make_plan(c, c->mp, c->np, ld, w2, kMaxSplit, c->sgplan[2 + v], c->sgnseg[2 + v], &c->sg_slots[2 + v]);
     if (rc) return rc;
     c->sg_wgs[2 + v] = w2;
@@ -253,6 +261,8 @@ int ensure_sgpr_plans(bbmm_ctx* c) {
   if (rc) return rc;
   c->sg_np = c->np;
   c->sg_mp = c->mp;
+  c->sg_tune[0] = c->sgpr_wgs[0];
+  c->sg_tune[1] = c->sgpr_wgs[1];
   return BBMM_OK;
 }
 
@@ -323,7 +333,8 @@ int stage_sgpr_build(bbmm_ctx* c) {
   struct { Buf* b; size_t bytes; } want[] = {
       {&c->KUU, mp * mp * sizeof(double)}, {&c->Gm, mp * mp * sizeof(double)},
       {&c->Ginv, mp * mp * sizeof(double)}, {&c->Kux, mp * np * sizeof(double)},
-      {&c->AT, mp * np * sizeof(float)}, {&c->A, mp * np * sizeof(float)},
+      {&c->AT, mp * ((np + BBMM_SGPR_PANEL - 1) / BBMM_SGPR_PANEL) * BBMM_SGPR_PANEL * sizeof(float)},
+      {&c->A, mp * np * sizeof(float)},
       {&c->qdiag, np * sizeof(double)}, {&c->T4, mp * BBMM_MAXC * sizeof(double)},
       {&c->Ua, mp * c->dp * sizeof(float)}, {&c->Ub, mp * c->dp * sizeof(float)},
       {&c->Us, mp * c->dp * sizeof(float)}, {&c->U4, mp * c->dp * sizeof(float)},
@@ -351,7 +362,7 @@ int stage_sgpr_build(bbmm_ctx* c) {
   // the Cholesky work matrix is free again: it receives G^{-1} in MFMA operand order
   launch_sgpr_root(s, ptr<double>(c->Ginv), ptr<double>(c->KUU), ptr<double>(c->Kux), c->mp, c->np,
                    ptr<float>(c->AT));
-  launch_transpose_f32(s, ptr<float>(c->AT), c->mp, c->np, ptr<float>(c->A));
+  launch_root_transpose(s, ptr<float>(c->AT), c->mp, c->np, ptr<float>(c->A));
   launch_sgpr_qdiag(s, ptr<float>(c->A), c->n, c->mp, ptr<double>(c->qdiag));
   // inducing inputs in the centred, scaled coordinates of X (for the derivative pair sums)
   launch_prep_x(s, c->prob.Uind, c->m, c->d, c->mp, c->KK, c->hyp, st, ptr<float>(c->Ua), ptr<float>(c->Ub),
@@ -365,7 +376,8 @@ int stage_sgpr_build(bbmm_ctx* c) {
 int sgpr_second_pass(bbmm_ctx* c, int ld, VpShape* shape) {
   int v = (ld == 32) ? 1 : 0;
   if (launch_mm_mat(c->stream, ptr<float>(c->AT), ptr<double>(c->T4), ptr<double>(c->Vp), c->np, ld,
-                    ptr<MmPlan>(c->sgplan[2 + v]), c->sg_wgs[2 + v], ptr<DevState>(c->st)))
+                    ptr<MmPlan>(c->sgplan[2 + v]), c->sg_wgs[2 + v], ptr<DevState>(c->st), BBMM_SGPR_PANEL,
+                    c->mp))
     return fail(c, BBMM_EINVAL, "unsupported block width");
   *shape = VpShape{0, ptr<int>(c->sgnseg[2 + v]), v ? 512 : 1024};
   return BBMM_OK;
@@ -375,7 +387,7 @@ int sgpr_second_pass(bbmm_ctx* c, int ld, VpShape* shape) {
 int sgpr_first_pass(bbmm_ctx* c, int ld, const double* D4, VpShape* shape) {
   int v = (ld == 32) ? 1 : 0;
   if (launch_mm_mat(c->stream, ptr<float>(c->A), D4, ptr<double>(c->Tp), c->mp, ld,
-                    ptr<MmPlan>(c->sgplan[v]), c->sg_wgs[v], ptr<DevState>(c->st)))
+                    ptr<MmPlan>(c->sgplan[v]), c->sg_wgs[v], ptr<DevState>(c->st), 0, 0))
     return fail(c, BBMM_EINVAL, "unsupported block width");
   *shape = VpShape{0, ptr<int>(c->sgnseg[v]), v ? 512 : 1024};
   return BBMM_OK;
@@ -404,7 +416,7 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     if (rc) return rc;
     int v = (ld == 32) ? 1 : 0;
     if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
-                      ptr<MmPlan>(c->plan[v]), c->plan_wgs[v], ptr<DevState>(c->st)))
+                      ptr<MmPlan>(c->plan[v]), c->plan_wgs[v], ptr<DevState>(c->st), 0, 0))
       return fail(c, BBMM_EINVAL, "unsupported block width");
     *shape = VpShape{0, ptr<int>(c->nseg[v]), v ? 512 : 1024};
     *scaleV = 1.0;
@@ -430,6 +442,7 @@ int stage_pivchol(bbmm_ctx* c) {
   if (c->kp > 0) launch_fill_f64(s, ptr<double>(c->L), (size_t)c->np * c->kp, 0.0);
   // pivot candidates alternate between two buffers (a step reads one and writes the other)
   double* arg[2] = {ptr<double>(c->partial), ptr<double>(c->partial) + 2 * kMaxVecBlocks};
+  auto fpiv = [c](int m) { return (m < (int)c->forced.size()) ? c->forced[m] : -1; };
   if (c->sgpr) {
     // App. C, SoR case: the diagonal of Q is not constant and a row of Q costs one pass over the
     // root: row piv = A (A^T e_piv), the second streaming product applied to row piv of A.
@@ -437,24 +450,24 @@ int stage_pivchol(bbmm_ctx* c) {
     DevState* st = ptr<DevState>(c->st);
     launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
     launch_fill_f64(s, ptr<double>(c->D4), (size_t)c->np * 16, 0.0);
-    launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), st, arg[0], nb, ptr<double>(c->qdiag));
+    launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), st, arg[0], nb, ptr<double>(c->qdiag), fpiv(0));
     for (int m = 0; m < c->k; ++m) {
-      launch_sgpr_pick(s, ptr<float>(c->A), c->mp, arg[m & 1], nb, ptr<double>(c->T4));
+      launch_sgpr_pick(s, ptr<float>(c->A), c->mp, arg[m & 1], nb, ptr<double>(c->T4), fpiv(m));
       VpShape sh{0, nullptr, 1};
       int rc = sgpr_second_pass(c, 16, &sh);
       if (rc) return rc;
       launch_vreduce(s, ptr<double>(c->Vp), sh, c->n, c->np, 16, 1.0, 0.0, ptr<double>(c->D4), ptr<double>(c->V));
       launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<double>(c->L), st,
-                     arg[m & 1], arg[(m + 1) & 1], nb, ptr<double>(c->V), 16);
+                     arg[m & 1], arg[(m + 1) & 1], nb, ptr<double>(c->V), 16, fpiv(m), fpiv(m + 1));
     }
     c->chol_done = true;
     c->pre_done = false;
     return BBMM_OK;
   }
-  launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), ptr<DevState>(c->st), arg[0], nb, nullptr);
+  launch_pc_init(s, c->n, c->hyp, ptr<double>(c->delta), ptr<DevState>(c->st), arg[0], nb, nullptr, fpiv(0));
   for (int m = 0; m < c->k; ++m)
     launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<double>(c->L),
-                   ptr<DevState>(c->st), arg[m & 1], arg[(m + 1) & 1], nb, nullptr, 0);
+                   ptr<DevState>(c->st), arg[m & 1], arg[(m + 1) & 1], nb, nullptr, 0, fpiv(m), fpiv(m + 1));
   c->chol_done = true;
   c->pre_done = false;
   return BBMM_OK;
@@ -660,6 +673,12 @@ int validate(bbmm_ctx* c, const bbmm_problem* in) {
     return fail(c, BBMM_EINVAL, "n_lengthscale must be 1 or d");
   if (!in->lengthscale || !in->X || !in->y || !in->E2) return fail(c, BBMM_EINVAL, "NULL input pointer");
   if (in->k > 0 && !in->E1) return fail(c, BBMM_EINVAL, "E1 is NULL but k > 0");
+  if (in->pivots_in)
+    for (int64_t a = 0; a < in->k; ++a) {
+      if (in->pivots_in[a] < 0 || in->pivots_in[a] >= in->n) return fail(c, BBMM_EINVAL, "pivots_in entry out of range");
+      for (int64_t b = 0; b < a; ++b)
+        if (in->pivots_in[a] == in->pivots_in[b]) return fail(c, BBMM_EINVAL, "pivots_in entries must be distinct");
+    }
   for (int64_t h = 0; h < in->n_lengthscale; ++h)
     if (!(in->lengthscale[h] > 0.0) || !isfinite(in->lengthscale[h]))
       return fail(c, BBMM_EINVAL, "lengthscale must be positive and finite");
@@ -733,6 +752,8 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   if (!strcmp(key, "mat_wgs")) c->mat_wgs = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
   else if (!strcmp(key, "ur_blocks")) c->ur_blocks_cap = value > 0 ? value : 0;
+  else if (!strcmp(key, "sgpr_wgs1")) c->sgpr_wgs[0] = value > 0 ? value : 0;
+  else if (!strcmp(key, "sgpr_wgs2")) c->sgpr_wgs[1] = value > 0 ? value : 0;
   else if (!strcmp(key, "time_mm")) c->time_mm = value > 0;
   else return fail(c, BBMM_EINVAL, std::string("unknown tuning key: ") + key);
   return BBMM_OK;
@@ -766,6 +787,9 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
   c->prob = *in;
   c->ls.assign(in->lengthscale, in->lengthscale + in->n_lengthscale);
   c->prob.lengthscale = c->ls.data();
+  c->forced.clear();
+  if (in->pivots_in) c->forced.assign(in->pivots_in, in->pivots_in + in->k);
+  c->prob.pivots_in = nullptr;              // the caller's array is not kept
   c->n = (int)in->n;
   c->d = (int)in->d;
   c->t = (int)in->t;

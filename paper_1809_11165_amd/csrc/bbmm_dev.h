@@ -87,11 +87,13 @@ void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int n
                     double addD, const double* D4, double* V);
 // diag_in / row_in: NULL for a plain kernel matrix of X (constant diagonal, rows evaluated from X);
 // otherwise the matrix diagonal (n) and, per step, the pivot's row at row_in[i * row_ld].
+// forced / next_forced: -1 for the greedy rule; otherwise the pivot this step must take and the
+// one the following step will take (a replayed pivot order).
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
-                    int nblocks, const double* diag_in);
+                    int nblocks, const double* diag_in, int next_forced);
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
                     double* L, DevState* st, const double* arg_in, double* arg_out, int nblocks,
-                    const double* row_in, int row_ld);
+                    const double* row_in, int row_ld, int forced, int next_forced);
 void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, double noise, DevState* st,
                       double* partial, double* gpartial, int nblocks);
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const double* L,
@@ -126,13 +128,13 @@ int launch_sgpr_kux(hipStream_t s, const float* X, const float* Uind, int n, int
                     HypArgs hyp, double* Kux);
 void launch_sgpr_root(hipStream_t s, const double* Ginv, double* GinvP, const double* Kux, int mp, int np,
                       float* AT);
-void launch_transpose_f32(hipStream_t s, const float* src, int rows, int cols, float* dst);
+void launch_root_transpose(hipStream_t s, const float* ATp, int mp, int np, float* A);
 void launch_sgpr_qdiag(hipStream_t s, const float* A, int n, int mp, double* qdiag);
 void launch_sgpr_mid(hipStream_t s, const double* Tp, VpShape shape, int mp, int ld, const DevState* st,
                      double* T4);
 void launch_sgpr_mid_rows(hipStream_t s, const double* Tp, VpShape shape, int mp, int ld, double* T);
 void launch_sgpr_pick(hipStream_t s, const float* A, int mp, const double* arg_in, int npart,
-                      double* T4);
+                      double* T4, int forced);
 
 void launch_rows_to_d4(hipStream_t s, const double* src, int n, int np, int ld, double* D4);
 void launch_sgpr_bsolve(hipStream_t s, const double* Ginv, const double* T, int mp, int ld, double* B);
@@ -151,9 +153,11 @@ int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const 
 // Streams the row-major fp32 matrix M (row stride = column count `np`, a multiple of 256) once and
 // leaves partial sums of M^T D in Vp, D4 indexed by the rows of M.  For the symmetric K_hat that is
 // K_hat D; the SGPR root uses it on both of its layouts.  plan: one entry per workgroup, laid out
-// by the host (see make_plan).
+// by the host (see make_plan).  panel_width > 0: M is stored in column panels of that width
+// (a multiple of 256), each panel row-major with panel_rows rows; 0: plain row-major.
 int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
-                  const MmPlan* plan, int wgs, const DevState* st);
+                  const MmPlan* plan, int wgs, const DevState* st, int panel_width, int panel_rows);
+#define BBMM_SGPR_PANEL 512   // column-panel width of the transposed SGPR root
 // c: number of columns really used (<= ld); lets 17..20 columns run one MFMA group plus vector FMAs
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
                   const double* D4, double* Vp, int np, int ld, int c, int nsplit, const DevState* st);

@@ -118,7 +118,7 @@ __device__ __forceinline__ void mm_mat_load_d(const double* __restrict__ D4, int
 // results return in issue order.
 template <int NQ, int NC, bool MORE>
 __device__ __forceinline__ void mm_mat_step(const float* __restrict__ knext,
-                                            const double* __restrict__ D4, int jnext, int np, int jc,
+                                            const double* __restrict__ D4, int jnext, int ldk, int jc,
                                             int g, f32x4 (&kv)[NC][4], f64x4 (&dop)[NQ],
                                             f64x4 (&acc)[NC][4][NQ]) {
   f64x4 dcur[NQ];
@@ -134,7 +134,7 @@ __device__ __forceinline__ void mm_mat_step(const float* __restrict__ knext,
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) kd[cc] = (double)kv[nc][r][cc];
       // the registers are free once converted: refill them before the MFMAs are issued
-      if (MORE) kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(knext + (size_t)r * np + nc * 64));
+      if (MORE) kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(knext + (size_t)r * ldk + nc * 64));
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc)
 #pragma unroll
@@ -146,10 +146,17 @@ __device__ __forceinline__ void mm_mat_step(const float* __restrict__ knext,
 // Workgroup = 4 waves on 256*NC adjacent columns (one strip); it runs the pieces of its plan
 // entry one after the other.  All workgroups get the same number of 16-row steps (+-1), so the
 // launch ends without a tail however strips and compute units divide.
+//
+// Matrix layout: element (row, col) lies at  (col / pw) * panel_stride + row * ldk + col % pw.
+// Plain row-major: pw >= np, ldk = np.  Column panels of width pw (a multiple of 256), each
+// panel row-major with ldk = pw: a matrix with few, very long rows (the transposed SGPR root:
+// 1024 x 500,000) then keeps the 16 rows of a step within 16 * pw * 4 bytes instead of one
+// memory page per row.
 template <int NQ, int NC>
 __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Khat,
                                                     const double* __restrict__ D4,
-                                                    double* __restrict__ Vp, int np,
+                                                    double* __restrict__ Vp, int np, int pw,
+                                                    size_t panel_stride, int ldk,
                                                     const MmPlan* __restrict__ plan,
                                                     const DevState* __restrict__ st) {
   if (st->done) return;
@@ -170,7 +177,8 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
 
-    const float* kp = Khat + (size_t)(j_begin + g * 4) * np + (size_t)(col0 + 4 * jc);
+    const float* kp = Khat + (size_t)(col0 / pw) * panel_stride + (size_t)(j_begin + g * 4) * ldk +
+                      (size_t)(col0 % pw + 4 * jc);
     f32x4 kv[NC][4];
     f64x4 dop[NQ];
     mm_mat_load_d<NQ>(D4, j_begin, jc, g, dop);
@@ -178,13 +186,13 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
     for (int r = 0; r < 4; ++r)
 #pragma unroll
       for (int nc = 0; nc < NC; ++nc)
-        kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(kp + (size_t)r * np + nc * 64));
+        kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(kp + (size_t)r * ldk + nc * 64));
     int j0 = j_begin;
     for (; j0 + 16 < j_end; j0 += 16) {
-      kp += (size_t)16 * np;
-      mm_mat_step<NQ, NC, true>(kp, D4, j0 + 16, np, jc, g, kv, dop, acc);
+      kp += (size_t)16 * ldk;
+      mm_mat_step<NQ, NC, true>(kp, D4, j0 + 16, ldk, jc, g, kv, dop, acc);
     }
-    mm_mat_step<NQ, NC, false>(kp, D4, j0, np, jc, g, kv, dop, acc);
+    mm_mat_step<NQ, NC, false>(kp, D4, j0, ldk, jc, g, kv, dop, acc);
 
     double* vout = Vp + (size_t)P.slot * np * LD;
 #pragma unroll
@@ -593,11 +601,16 @@ int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const 
 }
 
 int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
-                  const MmPlan* plan, int wgs, const DevState* st) {
+                  const MmPlan* plan, int wgs, const DevState* st, int panel_width, int panel_rows) {
+  // panel_width 0: plain row-major with row stride np
+  int pw = panel_width > 0 ? panel_width : np;
+  int ldk = panel_width > 0 ? panel_width : np;
+  size_t panel_stride = panel_width > 0 ? (size_t)panel_rows * panel_width : 0;
+  if (pw % 256 != 0) return 1;
   if (ld == 16)
-    k_mm_mat<1, 4><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, plan, st);
+    k_mm_mat<1, 4><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, pw, panel_stride, ldk, plan, st);
   else if (ld == 32)
-    k_mm_mat<2, 2><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, plan, st);
+    k_mm_mat<2, 2><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, pw, panel_stride, ldk, plan, st);
   else
     return 1;
   return 0;

@@ -8,7 +8,8 @@
 //   * k_kux_f64: K_UX in fp64 from the raw inputs;
 //   * k_sgpr_root: A^T = G^{-1} K_UX by fp64 MFMA (LDS-staged), rounded ONCE to fp32 (rows of A have norm
 //     sqrt(Q_ii) <= sqrt(s), so the rounding perturbs Q by ~1e-7 s, like an fp32 kernel matrix);
-//   * k_transpose_f32: A from A^T (both layouts are streamed once per iteration).
+//   * k_root_transpose: A from A^T (both layouts are streamed once per iteration; A^T is kept in
+//     column panels of 512 points so that its 1024 long rows do not cost a memory page each).
 // Derivative terms (Eq. (4),(8) with the derivative of the SoR matrix): dQ = dK_XU Kinv K_UX +
 // (its transpose) - K_XU Kinv dK_UU Kinv K_UX, so u^T dQ w needs b_u = Kinv K_UX u = G^{-T} A^T u
 // and b_w likewise (m-vectors, k_sgpr_bsolve) and then two sums over pairs, (X, U) and (U, U),
@@ -376,18 +377,21 @@ __global__ __launch_bounds__(256, 2) void k_sgpr_root(const double* __restrict__
     for (int ct = 0; ct < 8; ++ct)
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        AT[(size_t)(a0 + rt * 16 + 4 * r + g) * np + (size_t)(i0 + ct * 16 + jc)] = (float)acc[rt][ct][r];
+        // column panels of BBMM_SGPR_PANEL points (the layout the streaming product reads)
+        AT[((size_t)(i0 / BBMM_SGPR_PANEL) * mp + (size_t)(a0 + rt * 16 + 4 * r + g)) * BBMM_SGPR_PANEL +
+           (size_t)(i0 % BBMM_SGPR_PANEL + ct * 16 + jc)] = (float)acc[rt][ct][r];
 }
 
-// dst (cols x rows, row-major) = src^T, src rows x cols row-major; both multiples of 64.
-__global__ __launch_bounds__(256) void k_transpose_f32(const float* __restrict__ src, int rows,
-                                                        int cols, float* __restrict__ dst) {
+// A (np x mp, row-major) from A^T stored in column panels of BBMM_SGPR_PANEL points.
+__global__ __launch_bounds__(256) void k_root_transpose(const float* __restrict__ ATp, int mp, int np,
+                                                         float* __restrict__ A) {
   __shared__ float tile[64][65];
-  int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  int a0 = blockIdx.y * 64, i0 = blockIdx.x * 64;
   int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int r = ty; r < 64; r += 4) tile[r][tx] = src[(size_t)(r0 + r) * cols + c0 + tx];
+  const float* src = ATp + (size_t)(i0 / BBMM_SGPR_PANEL) * mp * BBMM_SGPR_PANEL + i0 % BBMM_SGPR_PANEL;
+  for (int r = ty; r < 64; r += 4) tile[r][tx] = src[(size_t)(a0 + r) * BBMM_SGPR_PANEL + tx];
   __syncthreads();
-  for (int c = ty; c < 64; c += 4) dst[(size_t)(c0 + c) * rows + r0 + tx] = tile[tx][c];
+  for (int c = ty; c < 64; c += 4) A[(size_t)(i0 + c) * mp + a0 + tx] = tile[tx][c];
 }
 
 // qdiag[i] = sum_a A[i][a]^2 in fp64 (the diagonal of Q = A A^T as the iteration sees it);
@@ -450,7 +454,7 @@ __global__ void k_sgpr_mid_rows(const double* __restrict__ Tp, VpShape shape, in
 // kernel (lowest index on ties), found again here by every block.
 __global__ __launch_bounds__(256) void k_sgpr_pick(const float* __restrict__ A, int mp,
                                                     const double* __restrict__ arg_in, int npart,
-                                                    double* __restrict__ T4) {
+                                                    double* __restrict__ T4, int forced) {
   __shared__ double sval[256];
   __shared__ int sidx[256];
   double v = -1.0e300;
@@ -477,7 +481,7 @@ __global__ __launch_bounds__(256) void k_sgpr_pick(const float* __restrict__ A, 
     }
     __syncthreads();
   }
-  int piv = sidx[0];
+  int piv = (forced >= 0) ? forced : sidx[0];
   int a = blockIdx.x * 256 + threadIdx.x;
   if (a >= mp) return;
   // an empty candidate list (every diagonal entry already picked) leaves no valid pivot
@@ -726,7 +730,8 @@ int launch_sgpr_kux(hipStream_t s, const float* X, const float* Uind, int n, int
   return 0;
 }
 
-// AT (mp x np) = Ginv Kux in fp32; mp and np are multiples of 256.  GinvP: scratch of mp x mp
+// AT (mp x np, in column panels of BBMM_SGPR_PANEL points: ceil(np / panel) * mp * panel floats)
+// = Ginv Kux in fp32; mp and np are multiples of 256.  GinvP: scratch of mp x mp
 // doubles that receives G^{-1} in MFMA operand order.
 void launch_sgpr_root(hipStream_t s, const double* Ginv, double* GinvP, const double* Kux, int mp, int np,
                       float* AT) {
@@ -737,8 +742,8 @@ void launch_sgpr_root(hipStream_t s, const double* Ginv, double* GinvP, const do
   k_sgpr_root<<<grid, 256, 0, s>>>(GinvP, Kux, mp, np, AT);
 }
 
-void launch_transpose_f32(hipStream_t s, const float* src, int rows, int cols, float* dst) {
-  k_transpose_f32<<<dim3(cols / 64, rows / 64), 256, 0, s>>>(src, rows, cols, dst);
+void launch_root_transpose(hipStream_t s, const float* ATp, int mp, int np, float* A) {
+  k_root_transpose<<<dim3(np / 64, mp / 64), 256, 0, s>>>(ATp, mp, np, A);
 }
 
 void launch_sgpr_qdiag(hipStream_t s, const float* A, int n, int mp, double* qdiag) {
@@ -757,8 +762,8 @@ void launch_sgpr_mid_rows(hipStream_t s, const double* Tp, VpShape shape, int mp
 }
 
 void launch_sgpr_pick(hipStream_t s, const float* A, int mp, const double* arg_in, int npart,
-                      double* T4) {
-  k_sgpr_pick<<<(mp + 255) / 256, 256, 0, s>>>(A, mp, arg_in, npart, T4);
+                      double* T4, int forced) {
+  k_sgpr_pick<<<(mp + 255) / 256, 256, 0, s>>>(A, mp, arg_in, npart, T4, forced);
 }
 
 void launch_rows_to_d4(hipStream_t s, const double* src, int n, int np, int ld, double* D4) {

@@ -307,9 +307,12 @@ __device__ inline void reduce_argmax(const double* __restrict__ arg, int npart, 
 
 // delta = diag(K_XX) = outputscale (stationary kernels), or the diagonal handed in (a covariance
 // whose diagonal is not constant); block argmax candidates for pivot 0.
+// next_forced >= 0: the caller replays a given pivot order; the thread that owns that row leaves
+// its residual diagonal in st->pivdmax[0] for the first step (a step cannot read delta[] of a
+// row that another block of the same launch is about to overwrite).
 __global__ __launch_bounds__(VT) void k_pc_init(int n, HypArgs hyp, double* __restrict__ delta,
                                                  DevState* st, double* __restrict__ arg_out,
-                                                 const double* __restrict__ diag_in) {
+                                                 const double* __restrict__ diag_in, int next_forced) {
   __shared__ double sval[VT];
   __shared__ int sidx[VT];
   double bv = -1.0e300;
@@ -317,6 +320,7 @@ __global__ __launch_bounds__(VT) void k_pc_init(int n, HypArgs hyp, double* __re
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
     double v = diag_in ? diag_in[i] : hyp.outputscale;
     delta[i] = v;
+    if (i == next_forced) st->pivdmax[0] = v;
     if (v > bv || (v == bv && i < bi)) {
       bv = v;
       bi = i;
@@ -343,13 +347,18 @@ __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int
                                                  double* __restrict__ L, DevState* st,
                                                  const double* __restrict__ arg_in,
                                                  double* __restrict__ arg_out, double stop_thresh,
-                                                 const double* __restrict__ row_in, int row_ld) {
+                                                 const double* __restrict__ row_in, int row_ld,
+                                                 int forced, int next_forced) {
   __shared__ double sval[VT];
   __shared__ int sidx[VT];
   __shared__ double lpiv[BBMM_MAXK];
   double dpiv;
   int piv;
   reduce_argmax(arg_in, gridDim.x, sval, sidx, &dpiv, &piv);
+  if (forced >= 0) {          // replayed pivot order: its residual diagonal was left by the previous kernel
+    piv = forced;
+    dpiv = st->pivdmax[m];
+  }
   if (!(dpiv > stop_thresh)) {
     // keep the candidates alive for the remaining steps
     if (threadIdx.x == 0) {
@@ -385,6 +394,7 @@ __global__ __launch_bounds__(VT) void k_pc_step(const float* __restrict__ X, int
     }
     L[(size_t)i * kp + m] = lval;
     delta[i] = di;
+    if (i == next_forced) st->pivdmax[m + 1] = di;
     if (di >= 0.0 && (di > bv || (di == bv && i < bi))) {
       bv = di;
       bi = i;
@@ -1217,15 +1227,16 @@ void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int n
 }
 
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,
-                    int nblocks, const double* diag_in) {
-  k_pc_init<<<nblocks, VT, 0, s>>>(n, hyp, delta, st, arg_out, diag_in);
+                    int nblocks, const double* diag_in, int next_forced) {
+  k_pc_init<<<nblocks, VT, 0, s>>>(n, hyp, delta, st, arg_out, diag_in, next_forced);
 }
 
 void launch_pc_step(hipStream_t s, const float* X, int n, int m, int kp, HypArgs hyp, double* delta,
                     double* L, DevState* st, const double* arg_in, double* arg_out, int nblocks,
-                    const double* row_in, int row_ld) {
+                    const double* row_in, int row_ld, int forced, int next_forced) {
   double thresh = 1e-12 * hyp.outputscale;
-  k_pc_step<<<nblocks, VT, 0, s>>>(X, n, m, kp, hyp, delta, L, st, arg_in, arg_out, thresh, row_in, row_ld);
+  k_pc_step<<<nblocks, VT, 0, s>>>(X, n, m, kp, hyp, delta, L, st, arg_in, arg_out, thresh, row_in, row_ld,
+                                   forced, next_forced);
 }
 
 void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, double noise, DevState* st,

@@ -154,6 +154,9 @@ def run_sgpr(name: str, cfg: int, n: int, m: int):
     trace_alt.append(float(np.sum(other.U[:, 1:] * other.Z0[:, 1:]) / w.t))
     quad_alt.append(float(other.U[:, 0] @ other.U[:, 0]))
     del other
+    say("first-order sensitivity of the trace and quadratic terms to the iterate")
+    trace_sens, quad_sens = S.sor_term_sensitivity(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale,
+                                                   w.jitter_rel, parts, res.U, res.W)
     say("Woodbury solve and log-determinant")
     u_exact, logdet_exact = S.sor_woodbury(parts, w.y)
     yKinvy_exact = float(w.y.astype(np.float64) @ u_exact)
@@ -175,6 +178,7 @@ def run_sgpr(name: str, cfg: int, n: int, m: int):
         "u0_rel_err_vs_exact": float(np.linalg.norm(res.U[:, 0] - u_exact) / np.linalg.norm(u_exact)),
         "U_last_step": last_step.tolist(), "U_reorder_dev": reorder_dev.tolist(),
         "trace_alt": [float(v) for v in trace_alt], "quad_alt": [float(v) for v in quad_alt],
+        "trace_sens": trace_sens.tolist(), "quad_sens": quad_sens.tolist(),
         "L_sample": res.L[rows].tolist(),
         "seconds": time.time() - t0,
     }

@@ -164,6 +164,33 @@ def test_pivoted_cholesky_matches_oracle(ctx, kernel, ard, n, d):
     assert np.max(np.abs(got - Lf)) < 5e-6 * np.sqrt(w.outputscale) * 10
 
 
+def test_pivoted_cholesky_replays_a_given_pivot_order(ctx):
+    # pivots_in: the factor of App. C along a caller-given order (here not the greedy one)
+    w = _case(inputs.MATERN52, True, 523, 16, k=6)
+    order = np.array([400, 3, 77, 522, 250, 9], dtype=np.int64)
+    prob = _problem(w, inputs.ONTHEFLY)
+    prob.pivots_in = order
+    ctx.bbmm_setup(prob)
+    L, piv, rank = ctx.bbmm_pivoted_cholesky()
+    assert rank == 6 and piv.tolist() == order.tolist()
+    (Lf, pf, dmax), K = _oracle_pc(w, 6, order)
+    assert np.max(np.abs(_host(L) - Lf)) < 5e-6 * np.sqrt(w.outputscale) * 10
+    # and the whole call runs on that preconditioner
+    res = ctx.bbmm_solve_logdet_grad(prob)
+    assert res.pivots.tolist() == order.tolist()
+    ref = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
+                           6, res.iters_run, forced_pivots=order)
+    assert res.logdet_precond == pytest.approx(ref.logdet_precond, rel=1e-6)
+    assert _colrel(_host(res.u0), ref.u0) < 1e-3
+    # invalid orders are rejected
+    from paper_1809_11165_amd import binding
+    for bad in ([1, 1, 2, 3, 4, 5], [0, 1, 2, 3, 4, 523]):
+        prob.pivots_in = np.array(bad, dtype=np.int64)
+        with pytest.raises(binding.BbmmError) as ei:
+            ctx.bbmm_setup(prob)
+        assert ei.value.code == binding.EINVAL
+
+
 def test_pivoted_cholesky_rank_zero_and_full_small(ctx):
     w = _case(inputs.RBF, False, 40, 2, k=0, t=2)
     ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))

@@ -116,6 +116,40 @@ def test_dq_ds_is_q_over_s_and_matrix_free_products_match_dense():
         assert got[h] == pytest.approx(np.sum(A * (mats[h] @ B)), rel=1e-9, abs=1e-11)
 
 
+def test_derivative_matvec_against_dense_and_sensitivity_bound_holds():
+    w = inputs.tiny_sgpr(45, 3, 9, kernel=O.MATERN52, ard=True, seed=11)
+    parts = _parts(w)
+    mats = S.sor_khat_derivatives(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel)
+    rng = np.random.default_rng(2)
+    t = 4
+    U = rng.standard_normal((w.n, t + 1))
+    W = rng.standard_normal((w.n, t))
+    MW = S.sor_derivative_matvec(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel,
+                                 parts, W, row_chunk=16)
+    for h, M in enumerate(MW):
+        assert np.allclose(M, mats[h] @ W, rtol=1e-9, atol=1e-11)
+    # Cauchy-Schwarz: moving every column of U by eps |u_i| moves the terms by at most eps * sens
+    tr_s, qd_s = S.sor_term_sensitivity(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale,
+                                        w.jitter_rel, parts, U, W)
+    assert len(tr_s) == len(mats) and len(qd_s) == len(mats)
+    eps = 1e-3
+    for trial in range(5):
+        dU = rng.standard_normal(U.shape)
+        dU *= eps * np.linalg.norm(U, axis=0) / np.linalg.norm(dU, axis=0)
+        U2 = U + dU
+        for h, M in enumerate(mats):
+            d_tr = abs(np.sum(U2[:, 1:] * (M @ W)) - np.sum(U[:, 1:] * (M @ W))) / t
+            d_q = abs(U2[:, 0] @ M @ U2[:, 0] - U[:, 0] @ M @ U[:, 0])
+            assert d_tr <= eps * tr_s[h] * (1 + 1e-12)
+            assert d_q <= eps * qd_s[h] * (1 + 10 * eps)
+    # the bound is attained in the worst direction (so it is not slack by construction)
+    h = 0
+    worst = mats[h] @ W
+    worst = worst / np.linalg.norm(worst, axis=0) * np.linalg.norm(U[:, 1:], axis=0) * eps
+    d_tr = abs(np.sum(worst * (mats[h] @ W))) / t
+    assert d_tr == pytest.approx(eps * tr_s[h], rel=1e-9)
+
+
 def test_cg_on_rank_m_plus_identity_terminates_in_m_plus_1_iterations():
     # K_hat = Q + sigma^2 I has at most m + 1 distinct eigenvalues, so unpreconditioned CG is exact
     # after m + 1 iterations; this pins operator, mBCG signs and indices together
