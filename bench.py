@@ -29,6 +29,9 @@ FP64_VALU_PEAK_TFLOPS = 78.6   # MI355X fp64 vector, published
 # HBM bytes per k_mm_mat launch at n = 50000 from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by a
 # 1 GiB copy (profiles/k_mm_mat_cfg3_n50000_hbm_counters.txt); only valid for that workload.
 MEASURED_TRAFFIC_MAT_N50000 = 10.425e9
+# HBM bytes per SGPR product (both k_mm_mat launches) at n = 500000, m = 1024, measured the same way
+# (profiles/k_mm_mat_cfg5_n500000_sgpr_hbm_counters.txt); only valid for that workload.
+MEASURED_TRAFFIC_SGPR_N500000_M1024 = 4.261e9
 
 
 def cpu_baseline(n_sample: int, n_full: int):
@@ -137,7 +140,8 @@ def main():
         alg_bytes = 8.0 * n * m + 16.0 * n * c + 16.0 * m * c
         achieved = alg_bytes / (mm_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": MEASURED_TRAFFIC_SGPR_N500000_M1024 if (n, m) == (500000, 1024) else None,
                     "kernel": "k_mm_mat (two launches per product: A^T D, then A T)",
                     "avg_launch_ms": mm_ms / 2.0, "avg_product_ms": mm_ms, "launches": 2 * mm_launches}
         workload = ("config5: SGPR (subset of regressors), RBF, n=%d, m=%d, d=8, t=10, k=10, 50 mBCG "
