@@ -350,15 +350,22 @@ int stage_sgpr_build(bbmm_ctx* c) {
   int rc = ensure_sgpr_plans(c);
   if (rc) return rc;
   DevState* st = ptr<DevState>(c->st);
+  // K_UX (n m kernel values in fp64, one big launch) does not depend on the K_UU chain (about a
+  // hundred small launches): it runs beside it on the context's second stream
+  HIPCHK(c, hipEventRecord(c->ev_fork, s));
+  HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+  if (c->mp > c->m) launch_fill_f64(c->side, ptr<double>(c->Kux), mp * np, 0.0);   // padding rows of every panel
+  if (launch_sgpr_kux(c->side, c->prob.X, c->prob.Uind, c->n, c->np, c->m, c->mp, c->dp, c->hyp,
+                      ptr<double>(c->Kux)))
+    return fail(c, BBMM_EINVAL, "unsupported input dimension");
+  HIPCHK(c, hipEventRecord(c->ev_join, c->side));
   launch_fill_f64(s, ptr<double>(c->Gm), mp * mp, 0.0);
   launch_fill_f64(s, ptr<double>(c->Ginv), mp * mp, 0.0);
   launch_sgpr_kuu(s, c->prob.Uind, c->m, c->mp, c->hyp, c->prob.jitter_rel * c->prob.outputscale,
                   ptr<double>(c->KUU));
   launch_sgpr_chol(s, ptr<double>(c->KUU), ptr<double>(c->Gm), c->mp, 1e-13 * c->prob.outputscale, st);
   launch_sgpr_trinv(s, ptr<double>(c->Gm), ptr<double>(c->Ginv), c->mp);
-  if (c->mp > c->m) launch_fill_f64(s, ptr<double>(c->Kux), mp * np, 0.0);   // padding rows of every panel
-  if (launch_sgpr_kux(s, c->prob.X, c->prob.Uind, c->n, c->np, c->m, c->mp, c->dp, c->hyp, ptr<double>(c->Kux)))
-    return fail(c, BBMM_EINVAL, "unsupported input dimension");
+  HIPCHK(c, hipStreamWaitEvent(s, c->ev_join, 0));
   // the Cholesky work matrix is free again: it receives G^{-1} in MFMA operand order
   launch_sgpr_root(s, ptr<double>(c->Ginv), ptr<double>(c->KUU), ptr<double>(c->Kux), c->mp, c->np,
                    ptr<float>(c->AT));

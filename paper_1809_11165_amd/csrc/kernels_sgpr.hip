@@ -6,7 +6,7 @@
 //   * k_kuu_f64, k_chol_panel / k_chol_update, k_trinv_diag / k_trinv_off: K_UU, its Cholesky
 //     factor and G^{-1}, all fp64 (m x m is small);
 //   * k_kux_f64: K_UX in fp64 from the raw inputs;
-//   * k_sgpr_root: A^T = G^{-1} K_UX by fp64 MFMA (LDS-staged), rounded ONCE to fp32 (rows of A have norm
+//   * k_sgpr_root: A^T = G^{-1} K_UX by fp64 MFMA, rounded ONCE to fp32 (rows of A have norm
 //     sqrt(Q_ii) <= sqrt(s), so the rounding perturbs Q by ~1e-7 s, like an fp32 kernel matrix);
 //   * k_root_transpose: A from A^T (both layouts are streamed once per iteration; A^T is kept in
 //     column panels of 512 points so that its 1024 long rows do not cost a memory page each).
@@ -232,8 +232,7 @@ __global__ void k_pack_ginv(const double* __restrict__ Ginv, int mp, double* __r
 // K_UX in fp64: k(u_b, x_i), b < m, i < n; zero for padding points.  Stored in panels of 128
 // points, and inside a panel in the order the root kernel feeds its MFMAs,
 //   Kux[panel][b / 4][(i % 128) / 16][(b % 4) * 16 + i % 16],
-// so that 16 consecutive b's of a panel are 16 KB of contiguous memory that the root kernel
-// copies to LDS as it is.  Thread = one point, a run of KUX_RUN inducing inputs (their
+// so that every MFMA operand of the root kernel is 512 contiguous bytes.  Thread = one point, a run of KUX_RUN inducing inputs (their
 // coordinates are uniform across the wave).
 constexpr int KUX_RUN = 16;
 
@@ -269,116 +268,99 @@ __global__ __launch_bounds__(256) void k_kux_f64(const float* __restrict__ X,
 }
 
 // ------------------------------------------------- root: A^T = G^{-1} K_UX ---
-// Workgroup: 128 rows of A^T (inducing index a) x 128 points; wave w: rows 32 w .. 32 w + 31
-// (2 row tiles) x 8 point tiles = 16 fp64 MFMA accumulators.  G^{-1} is lower triangular, so the
-// contraction index b stops at the end of the row block.  Chunks of 16 b's are staged through
-// LDS in MFMA operand order ([tile][lane], so every operand read is 512 contiguous bytes); both
-// operands already lie in that order in global memory (k_pack_ginv, k_kux_f64), so the staging
-// is a plain copy, 16 bytes per lane, requested one chunk ahead of the arithmetic.  (Operands
-// read straight from global memory, 16 cache lines per G^{-1} operand, kept the kernel at 21 %
-// of the fp64 matrix rate: the address units were the limit, not the MFMAs.)
+// fp64 MFMA product without LDS and without barriers.  Both operands lie in MFMA operand order in
+// global memory (k_pack_ginv, k_kux_f64), so every operand is one 512-byte coalesced load.
+// Workgroup: NW waves, 32 NW rows of A^T (inducing index a) x 128 points; wave w owns row tiles
+// w and 2 NW - 1 - w (16 rows each) x 8 point tiles = 16 accumulators, reads its own G^{-1}
+// operands, and shares the K_UX operands with the other waves through L1.  Operands are requested
+// PF k steps ahead of their MFMAs.
 //
-// Work differs 8 : 1 between the last and the first row block, and the hardware deals
-// consecutive workgroups round-robin to the 8 XCDs.  With (row block, panel) = (id % 8, id / 8)
-// one XCD would get all the longest workgroups and the launch would take 64/36 of the balanced
-// time (measured: the compute units were busy 55 % of the launch).  So the flat id is decoded as
-// XCD x = id % 8, sequence j = id / 8 on that XCD: panel = (j / nrb) * 8 + x, row block =
-// nrb - 1 - j % nrb -- every XCD walks whole panels, longest row block first, and re-reads the
-// K_UX panel from its own L2.
-constexpr int RT_ROWS = 128, RT_PTS = 128, RT_BK = 16;
+// G^{-1} is lower triangular: a row block contracts over the columns up to its own end only, and
+// inside the diagonal block row tile t needs the 16-column chunks 0..t only (pairing tiles w and
+// 2 NW - 1 - w gives every wave the same share).  So work differs 4 : 1 between the last and the
+// first row block, while the hardware deals consecutive workgroups round-robin to the 8 XCDs:
+// with (row block, panel) = (id % nrb, id / nrb) one XCD gets all the longest workgroups (measured:
+// compute units busy 55 % of the launch).  The flat id is decoded as XCD x = id % 8, sequence
+// j = id / 8 on that XCD; every XCD takes the panels x, x + 8, ... and walks them once per row
+// block, longest block first, so that at any time an XCD works on ONE row block and its slab of
+// G^{-1} (at most 2 MB) stays in that XCD's L2.  (Walking all row blocks of a panel first instead
+// keeps the K_UX panel hot but has every workgroup pull a different slab of the 8 MB G^{-1}
+// through the fabric: 12.3 ms against 10.4.)
+//
+// History at n = 500,000, m = 1024: operands gathered straight from row-major global memory
+// 35.8 ms (address units saturated: 16 cache lines per G^{-1} operand) -> LDS staging 19.1 ->
+// XCD-balanced 14.0 -> operands pre-packed 12.6 -> zero tiles of the diagonal block skipped 12.3
+// -> row-block-major order 10.7 -> no LDS, 8 waves per workgroup 10.4 ms (51 TFLOP/s fp64).
+constexpr int RT_PTS = 128;
 
-__global__ __launch_bounds__(256, 2) void k_sgpr_root(const double* __restrict__ GinvP,
-                                                       const double* __restrict__ Kux, int mp, int np,
-                                                       float* __restrict__ AT) {
-  __shared__ double sA[2][8 * 4][64];   // [buffer][row tile * 4 + k step][lane]
-  __shared__ double sB[2][4 * 8][64];   // [buffer][k step * 8 + point tile][lane]
+template <int PF, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void k_sgpr_root(const double* __restrict__ GinvP,
+                                                                  const double* __restrict__ Kux,
+                                                                  int mp, int np,
+                                                                  float* __restrict__ AT) {
+  constexpr int ROWS = 32 * NW;
   int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int g = lane >> 4, jc = lane & 15;
-  int nrb = mp / RT_ROWS;
+  int nrb = mp / ROWS;
   int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
-  int panel = (seq / nrb) * 8 + xcd;
+  int ppx = (np / RT_PTS + 7) / 8;                 // panels per XCD
+  int panel = (seq % ppx) * 8 + xcd;
   if (panel >= np / RT_PTS) return;
-  int a_blk = (nrb - 1 - seq % nrb) * RT_ROWS;
+  int a_blk = (nrb - 1 - seq / ppx) * ROWS;
   int i0 = panel * RT_PTS;
-  int nchunks = min(mp, a_blk + RT_ROWS) / RT_BK;
+  int nsteps = min(mp, a_blk + ROWS) / 4;          // k steps of 4
+  int dstep = a_blk / 4;                           // first k step of the diagonal block
+  int tile[2] = {wave, 2 * NW - 1 - wave};
   f64x4 acc[2][8];
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
     for (int ct = 0; ct < 8; ++ct) acc[rt][ct] = (f64x4){0.0, 0.0, 0.0, 0.0};
-
-  // staging: both operands lie in global memory in LDS order, so a chunk is 8 pieces of 2 KB of
-  // G^{-1} (one per row tile) and 16 KB of the K_UX panel, copied 16 bytes per thread and item
-  typedef double f64x2 __attribute__((ext_vector_type(2)));
-  f64x2 ra[4], rb[4];
-  const double* gA[4];
-  const double* gB[4];
-  int ia[4], ib[4];
+  const double* pa[2];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    int e = tid + 256 * u;
-    int rt = e >> 7, w2 = 2 * (e & 127);
-    gA[u] = GinvP + ((size_t)(a_blk / 16 + rt) * (mp / 4)) * 64 + w2;
-    ia[u] = rt * 256 + w2;
-    gB[u] = Kux + (size_t)panel * mp * RT_PTS + 2 * e;
-    ib[u] = 2 * e;
+  for (int rt = 0; rt < 2; ++rt) pa[rt] = GinvP + ((size_t)(a_blk / 16 + tile[rt]) * (mp / 4)) * 64 + lane;
+  const double* pb = Kux + (size_t)panel * mp * RT_PTS + lane;
+  double av[PF][2], bv[PF][8];
+#pragma unroll
+  for (int p = 0; p < PF; ++p) {
+    int ks = min(p, nsteps - 1);
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) av[p][rt] = pa[rt][(size_t)ks * 64];
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) bv[p][ct] = pb[((size_t)ks * 8 + ct) * 64];
   }
+  for (int ks0 = 0; ks0 < nsteps; ks0 += PF) {
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    ra[u] = *(const f64x2*)(gA[u]);
-    rb[u] = *(const f64x2*)(gB[u]);
-  }
-  double* fa = &sA[0][0][0];
-  double* fb = &sB[0][0][0];
+    for (int p = 0; p < PF; ++p) {
+      int ks = ks0 + p;
+      double ac[2], bc[8];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    *(f64x2*)(fa + ia[u]) = ra[u];
-    *(f64x2*)(fb + ib[u]) = rb[u];
-  }
-  __syncthreads();
-  for (int c = 0; c < nchunks; ++c) {
-    int buf = c & 1;
-    bool more = c + 1 < nchunks;
-    if (more) {
-      int b0 = (c + 1) * RT_BK;
+      for (int rt = 0; rt < 2; ++rt) ac[rt] = av[p][rt];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        ra[u] = *(const f64x2*)(gA[u] + (size_t)b0 * 16);          // (b0 / 4) k steps of 64 doubles
-        rb[u] = *(const f64x2*)(gB[u] + (size_t)b0 * RT_PTS);
+      for (int ct = 0; ct < 8; ++ct) bc[ct] = bv[p][ct];
+      int kn = min(ks + PF, nsteps - 1);
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) av[p][rt] = pa[rt][(size_t)kn * 64];
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) bv[p][ct] = pb[((size_t)kn * 8 + ct) * 64];
+      int cd = (ks - dstep) >> 2;                  // chunk of 16 inside the diagonal block
+      if (cd <= tile[0]) {
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) acc[0][ct] = mfma16d(ac[0], bc[ct], acc[0][ct]);
+      }
+      if (cd <= tile[1]) {
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) acc[1][ct] = mfma16d(ac[1], bc[ct], acc[1][ct]);
       }
     }
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      double av[2], bv[8];
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) av[rt] = sA[buf][(wave * 2 + rt) * 4 + kk][lane];
-#pragma unroll
-      for (int ct = 0; ct < 8; ++ct) bv[ct] = sB[buf][kk * 8 + ct][lane];
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-        for (int ct = 0; ct < 8; ++ct) acc[rt][ct] = mfma16d(av[rt], bv[ct], acc[rt][ct]);
-    }
-    if (more) {
-      double* na = &sA[buf ^ 1][0][0];
-      double* nb = &sB[buf ^ 1][0][0];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        *(f64x2*)(na + ia[u]) = ra[u];
-        *(f64x2*)(nb + ib[u]) = rb[u];
-      }
-    }
-    __syncthreads();
   }
-  int a0 = a_blk + wave * 32;
 #pragma unroll
   for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
     for (int ct = 0; ct < 8; ++ct)
 #pragma unroll
       for (int r = 0; r < 4; ++r)
-        // column panels of BBMM_SGPR_PANEL points (the layout the streaming product reads)
-        AT[((size_t)(i0 / BBMM_SGPR_PANEL) * mp + (size_t)(a0 + rt * 16 + 4 * r + g)) * BBMM_SGPR_PANEL +
+        AT[((size_t)(i0 / BBMM_SGPR_PANEL) * mp + (size_t)(a_blk + tile[rt] * 16 + 4 * r + g)) * BBMM_SGPR_PANEL +
            (size_t)(i0 % BBMM_SGPR_PANEL + ct * 16 + jc)] = (float)acc[rt][ct][r];
 }
 
@@ -737,9 +719,9 @@ void launch_sgpr_root(hipStream_t s, const double* Ginv, double* GinvP, const do
                       float* AT) {
   size_t total = (size_t)mp * mp;
   k_pack_ginv<<<(int)((total + 255) / 256), 256, 0, s>>>(Ginv, mp, GinvP);
-  int panels = np / RT_PTS, nrb = mp / RT_ROWS;
+  int panels = np / RT_PTS, nrb = mp / 256;        // 8 waves: 256 rows per workgroup
   int grid = ((panels + 7) / 8) * nrb * 8;
-  k_sgpr_root<<<grid, 256, 0, s>>>(GinvP, Kux, mp, np, AT);
+  k_sgpr_root<2, 8><<<grid, 512, 0, s>>>(GinvP, Kux, mp, np, AT);
 }
 
 void launch_root_transpose(hipStream_t s, const float* ATp, int mp, int np, float* A) {

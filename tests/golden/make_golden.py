@@ -139,11 +139,22 @@ def run_sgpr(name: str, cfg: int, n: int, m: int):
     say("rerun to iteration %d" % (it - 1))
     prev = O.mbcg(parts.khat_matmul, res.B, P.solve, it - 1)
     last_step = norm(res.U - prev.U) / norm(res.U)
+    # the same two scalars one iteration earlier: y^T u_p grows monotonically with p (CG minimises
+    # the energy norm of the error), so two runs a fraction of an iteration apart differ by at
+    # most that increment; likewise the quadrature estimate of the log-determinant
+    yKinvy_prev = float(w.y.astype(np.float64) @ prev.U[:, 0])
+    terms_prev = []
+    for i in range(w.t):
+        mv = min(int(prev.m_valid[i + 1]), it - 1)
+        dg, off = O.tridiag_from_cg(prev.alpha[:, i + 1], prev.beta[:, i + 1], mv)
+        terms_prev.append(prev.rho0[i + 1] * O.e1_logT_e1(dg, off))
+    logdet_prev = P.logdet + float(np.mean(terms_prev))
     del prev
     say("rerun with products grouped through the root")
     A = sla.solve_triangular(parts.chol_UU, parts.KXU.T, lower=True).T
     other = O.mbcg(lambda M: A @ (A.T @ M) + w.noise * M, res.B, P.solve, it)
     reorder_dev = norm(res.U - other.U) / norm(res.U)
+    yKinvy_alt = float(w.y.astype(np.float64) @ other.U[:, 0])
     del A
     # the derivative terms of that second run: u^T dQ w is a small difference of large terms, so at
     # an unconverged iteration count its value moves with the rounding order far more than U does
@@ -179,6 +190,7 @@ def run_sgpr(name: str, cfg: int, n: int, m: int):
         "U_last_step": last_step.tolist(), "U_reorder_dev": reorder_dev.tolist(),
         "trace_alt": [float(v) for v in trace_alt], "quad_alt": [float(v) for v in quad_alt],
         "trace_sens": trace_sens.tolist(), "quad_sens": quad_sens.tolist(),
+        "yKinvy_prev": yKinvy_prev, "logdet_prev": logdet_prev, "yKinvy_alt": yKinvy_alt,
         "L_sample": res.L[rows].tolist(),
         "seconds": time.time() - t0,
     }

@@ -233,9 +233,16 @@ def _run_sgpr_case(ctx, name):
     assert err.max() < tol_u, (err, tol_u)
     coln = torch.linalg.vector_norm(res.U.double(), dim=0).cpu().numpy()
     assert np.allclose(coln, g["U_colnorm"], rtol=tol_u)
-    assert res.logdet == pytest.approx(g["logdet"], rel=TOL)
-    assert res.yKinvy == pytest.approx(g["yKinvy"], rel=TOL)
-    assert res.nlml == pytest.approx(g["nlml"], rel=TOL)
+    # y^T u_p grows monotonically with p (CG minimises the energy norm of the error), so two runs
+    # a fraction of an iteration apart differ by at most the last increment, which the oracle
+    # stores ("yKinvy_prev"); the same for the quadrature estimate of the log-determinant.  Both
+    # increments vanish when the run has converged, leaving the plain 1e-3.
+    b_ld = TOL * abs(g["logdet"]) + abs(g["logdet"] - g["logdet_prev"])
+    b_yk = TOL * abs(g["yKinvy"]) + abs(g["yKinvy"] - g["yKinvy_prev"])
+    assert abs(res.logdet - g["logdet"]) <= b_ld
+    assert abs(res.yKinvy - g["yKinvy"]) <= b_yk, (res.yKinvy, g["yKinvy"], g["yKinvy_prev"], g["yKinvy_alt"])
+    assert abs(res.nlml - g["nlml"]) <= (b_ld + b_yk) / 2
+    assert abs(g["yKinvy_alt"] - g["yKinvy"]) <= b_yk          # the second fp64 run is inside the bound
     tr, qd = np.array(g["trace"]), np.array(g["quad"])
     nl = len(w.lengthscale)
     # Derivative terms.  u^T dQ w is a small difference of terms as large as |u| |dQ w| (e.g.
