@@ -88,6 +88,13 @@ enum { BBMM_MODE_MATERIALISED = 0, BBMM_MODE_ONTHEFLY = 1, BBMM_MODE_SGPR = 2 };
  *                residual diagonals tie (a stationary kernel's diagonal is constant; the inducing
  *                rows of an SoR matrix agree to ~1e-10), so a caller who needs the same
  *                preconditioner as another run or implementation passes that run's pivots.
+ *   u0_init      device, n float, or NULL.  Alg. 1/2 take the current solution as input and start
+ *                from r_0 = b - K_hat u_0; with u0_init the y column (column 0 of the block) starts
+ *                from it, at the cost of one more product (e.g. the solve of the previous
+ *                optimiser step).  The probe columns always start from zero: their Lanczos
+ *                tridiagonals need r_0 = z_i.  Residuals stay relative to |b|.  Used by
+ *                bbmm_solve_logdet_grad and bbmm_mbcg; the pointer must stay valid while the
+ *                problem set by bbmm_setup is in use.
  */
 typedef struct {
   int32_t kernel;
@@ -106,6 +113,7 @@ typedef struct {
   const float* Uind;
   double jitter_rel;
   const int64_t* pivots_in;
+  const float* u0_init;
 } bbmm_problem;
 
 /*

@@ -315,16 +315,23 @@ class MbcgResult:
 
 
 def mbcg(matmul: Callable[[np.ndarray], np.ndarray], B: np.ndarray,
-         psolve: Callable[[np.ndarray], np.ndarray], p: int, tol: float = 0.0) -> MbcgResult:
+         psolve: Callable[[np.ndarray], np.ndarray], p: int, tol: float = 0.0,
+         U0: Optional[np.ndarray] = None) -> MbcgResult:
     """Modified batched preconditioned CG (Alg. 2) on the n x c block B.
 
     Every column runs its own PCG recurrence with its own alpha_j, beta_j; the
     coefficients are kept so that the Lanczos tridiagonals can be rebuilt.
+    U0: the current solutions the algorithm takes as input (first line of Alg. 1/2:
+    r_0 = b - A u_0); None = zero.  Residuals stay relative to |b|.
     """
     B = np.asarray(B, dtype=np.float64)
     n, c = B.shape
-    U = np.zeros((n, c))
-    R = B.copy()
+    if U0 is None:
+        U = np.zeros((n, c))
+        R = B.copy()
+    else:
+        U = np.array(U0, dtype=np.float64)
+        R = B - matmul(U)
     Z = psolve(R)
     D = Z.copy()
     rho = np.sum(R * Z, axis=0)
@@ -413,10 +420,13 @@ class BbmmResult:
 def bbmm_inference(kernel: int, X, y, ls, s: float, noise: float, E1, E2, k: int, p: int,
                    tol: float = 0.0, forced_pivots: Optional[Sequence[int]] = None,
                    Khat: Optional[np.ndarray] = None, trace_row_chunk: int = 2048,
-                   progress: Optional[Callable[[str], None]] = None) -> BbmmResult:
+                   progress: Optional[Callable[[str], None]] = None,
+                   u0_init: Optional[np.ndarray] = None) -> BbmmResult:
     """One BBMM call: K_hat^{-1} y, log|K_hat| estimate, trace estimates, NLML and gradient.
 
     `progress`, if given, is called with a short text at stage boundaries (long runs only).
+    `u0_init` warm-starts the y column (Alg. 2's input U_0); the probe columns start from zero,
+    because their tridiagonals are those of the Lanczos process started at z_i.
     """
     say = progress if progress is not None else (lambda msg: None)
     X = np.asarray(X, dtype=np.float64)
@@ -441,7 +451,11 @@ def bbmm_inference(kernel: int, X, y, ls, s: float, noise: float, E1, E2, k: int
     B = np.concatenate([y[:, None], Zp], axis=1)
 
     say("preconditioner and probes ready")
-    res = mbcg(lambda M: Khat @ M, B, P.solve, p, tol)
+    U0 = None
+    if u0_init is not None:
+        U0 = np.zeros_like(B)
+        U0[:, 0] = np.asarray(u0_init, dtype=np.float64)
+    res = mbcg(lambda M: Khat @ M, B, P.solve, p, tol, U0=U0)
     say("mBCG done: %d iterations" % res.iters_run)
 
     # stochastic Lanczos quadrature, probe columns only

@@ -47,7 +47,7 @@ class _Problem(C.Structure):
                 ("outputscale", C.c_double), ("noise", C.c_double),
                 ("X", C.c_void_p), ("y", C.c_void_p), ("E1", C.c_void_p), ("E2", C.c_void_p),
                 ("m", C.c_int64), ("Uind", C.c_void_p), ("jitter_rel", C.c_double),
-                ("pivots_in", C.POINTER(C.c_int64))]
+                ("pivots_in", C.POINTER(C.c_int64)), ("u0_init", C.c_void_p)]
 
 
 class _Result(C.Structure):
@@ -146,6 +146,7 @@ class Problem:
     Uind: "object" = None           # SGPR only: m x d device tensor of inducing inputs
     jitter_rel: float = 0.0         # SGPR only
     pivots_in: Optional[np.ndarray] = None   # replay this pivot order instead of the greedy rule
+    u0_init: "object" = None                 # n device floats: warm start of the y column
     _keep: list = field(default_factory=list, repr=False)
 
     def to_c(self) -> _Problem:
@@ -169,6 +170,10 @@ class Problem:
         p.E1 = self.E1.data_ptr() if self.k > 0 else None
         p.E2 = self.E2.data_ptr()
         p.m, p.Uind, p.jitter_rel = 0, None, 0.0
+        p.u0_init = None
+        if self.u0_init is not None:
+            _check_dev(self.u0_init, (n,), "u0_init")
+            p.u0_init = self.u0_init.data_ptr()
         p.pivots_in = None
         if self.pivots_in is not None:
             piv = np.ascontiguousarray(self.pivots_in, dtype=np.int64)

@@ -491,7 +491,8 @@ int stage_pre_setup(bbmm_ctx* c) {
 
 // mBCG on the block held in R (padded row-major, stride ld); U, Z0, coefficient histories and the
 // device state are left in the context.
-int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
+// warm != NULL: column 0 starts from that solution (device, n floats) instead of zero.
+int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld, const float* warm = nullptr) {
   if (!c->pre_done) return fail(c, BBMM_EINVAL, "bbmm_precond_setup must run first");
   hipStream_t s = c->stream;
   DevState* st = ptr<DevState>(c->st);
@@ -511,6 +512,22 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld) {
   launch_ur(s, 1, c->n, ld, cc, c->kp, noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V), ptr<double>(c->U),
             ptr<double>(c->R), ptr<double>(c->L), st, pdv, nb, pur, nb_ur, 0, ptr<double>(c->alpha),
             ptr<double>(c->beta), ptr<double>(c->resid));
+  if (warm) {
+    // Alg. 1/2: r_0 = b - K_hat u_0 for the current solution u_0 -- one more product, of the block
+    // [u_init, 0, ..]; the pass above has left |b| (the residuals stay relative to it), the second
+    // pass redoes rho_0 for the new residual
+    launch_warm_rhs(s, warm, c->n, ld, ptr<double>(c->D4));
+    VpShape ns{0, nullptr, 1};
+    double scaleV = 1.0, addD = 0.0;
+    int rc = stage_mm(c, mode, cc, ld, &ns, &scaleV, &addD);
+    if (rc) return rc;
+    launch_vreduce(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, scaleV, addD, ptr<double>(c->D4), ptr<double>(c->V));
+    launch_warm_apply(s, warm, ptr<double>(c->V), c->n, ld, ptr<double>(c->U), ptr<double>(c->R));
+    launch_fill_f64(s, ptr<double>(c->D4), blk, 0.0);
+    launch_ur(s, 2, c->n, ld, cc, c->kp, noise, 0.0, ptr<double>(c->D4), ptr<double>(c->V), ptr<double>(c->U),
+              ptr<double>(c->R), ptr<double>(c->L), st, pdv, nb, pur, nb_ur, 0, ptr<double>(c->alpha),
+              ptr<double>(c->beta), ptr<double>(c->resid));
+  }
   launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<double>(c->L), ptr<double>(c->D4),
             ptr<double>(c->Z0), st, nb);
   if (c->time_mm) {
@@ -995,7 +1012,7 @@ int bbmm_mbcg(bbmm_ctx* c, int32_t mode, const float* B, int64_t cc, float* U, d
   if (!B || !U || cc < 1 || cc > BBMM_MAXC) return fail(c, BBMM_EINVAL, "bad block");
   int ld = ld_for((int)cc);
   launch_pack_rows(c->stream, B, c->n, (int)cc, ld, ptr<double>(c->R));
-  rc = stage_mbcg(c, mode, (int)cc, ld);
+  rc = stage_mbcg(c, mode, (int)cc, ld, c->prob.u0_init);
   if (rc) return rc;
   launch_unpack_rows(c->stream, ptr<double>(c->U), ld, c->n, (int)cc, U);
   rc = fetch_state(c, true);
@@ -1131,7 +1148,7 @@ int bbmm_solve_logdet_grad(bbmm_ctx* c, const bbmm_problem* in, bbmm_result* out
   if (rc) return rc;
   launch_probes(s, in->y, in->E1, in->E2, ptr<double>(c->L), c->n, c->t, c->kp, ld, in->noise,
                 ptr<DevState>(c->st), ptr<double>(c->R));
-  rc = stage_mbcg(c, in->mode, cc, ld);
+  rc = stage_mbcg(c, in->mode, cc, ld, in->u0_init);
   if (rc) return rc;
   // The eigensolves need only the coefficient histories and the derivative pass only the solves:
   // they run side by side, the SLQ kernel on the context's second stream.

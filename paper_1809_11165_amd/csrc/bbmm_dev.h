@@ -83,6 +83,9 @@ void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, dou
 void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, double* dst);
 void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0, int nrows, int col0,
                        int ncols, float* dst);
+void launch_warm_rhs(hipStream_t s, const float* u_init, int n, int ld, double* D4);
+void launch_warm_apply(hipStream_t s, const float* u_init, const double* V, int n, int ld, double* U,
+                       double* R);
 void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                     double addD, const double* D4, double* V);
 // diag_in / row_in: NULL for a plain kernel matrix of X (constant diagonal, rows evaluated from X);

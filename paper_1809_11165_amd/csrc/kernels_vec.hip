@@ -247,6 +247,22 @@ __global__ void k_vreduce(const double* __restrict__ Vp, VpShape shape, int n, i
   V[idx] = scaleV * s + addD * D4[d4_index(i, q, ld)];
 }
 
+// Warm start of column 0 (Alg. 1/2 take the current solution as input): the quad-swizzled
+// right-hand side gets u_init in column 0 (the rest of the block was zero-filled) ...
+__global__ void k_warm_rhs(const float* __restrict__ u_init, int n, int ld, double* __restrict__ D4) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) D4[d4_index(i, 0, ld)] = (double)u_init[i];
+}
+
+// ... and with V = K_hat [u_init, 0, ..] the iteration starts from U[:,0] = u_init, R[:,0] = b - V[:,0].
+__global__ void k_warm_apply(const float* __restrict__ u_init, const double* __restrict__ V, int n,
+                             int ld, double* __restrict__ U, double* __restrict__ R) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  U[(size_t)i * ld] = (double)u_init[i];
+  R[(size_t)i * ld] -= V[(size_t)i * ld];
+}
+
 // ------------------------------------------------------- pivoted Cholesky ----
 __device__ inline double kernel_value_f64(const float* __restrict__ X, int a, int b,
                                           const HypArgs& hyp) {
@@ -645,7 +661,8 @@ __device__ inline double alpha_from(int active, double rho, double dv, int q, in
 
 // (2a) every block first adds the d^T v partials of k_dv (same order in every block), forms
 //      alpha_j, then U += alpha D, R -= alpha V and its partial sums of |r|^2 and L^T R.
-//      init != 0: no update, just the sums for R = B (gives Z_0, rho_0).
+//      init != 0: no update, just the sums for R = B (gives Z_0, rho_0).  init == 2: the same
+//      after a warm start, R = B - K_hat U_0: the norms |b| of the first pass are kept.
 //      A wave takes 4 rows per step: lane l holds element (row l/16, column l%16 [+16]) of the
 //      blocks, which is exactly the B operand of an fp64 MFMA whose A operand is the same four
 //      rows of L, so L^T R costs one load of L per 16 columns of L instead of one per entry.
@@ -895,7 +912,7 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
       int ok = finite_d(rho_new) && rho_new > 0.0 && qq < c;
       st->rho[qq] = rho_new;
       st->rho0[qq] = rho_new;
-      st->bnorm[qq] = sqrt(rrq);
+      if (init != 2) st->bnorm[qq] = sqrt(rrq);   // init == 2: warm start, |b| is already there
       st->active[qq] = ok;
       st->m_valid[qq] = 0;
       st->beta_cur[qq] = 0.0;
@@ -1224,6 +1241,15 @@ void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0,
 void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                     double addD, const double* D4, double* V) {
   k_vreduce<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(Vp, shape, n, np, ld, scaleV, addD, D4, V);
+}
+
+void launch_warm_rhs(hipStream_t s, const float* u_init, int n, int ld, double* D4) {
+  k_warm_rhs<<<(n + 255) / 256, 256, 0, s>>>(u_init, n, ld, D4);
+}
+
+void launch_warm_apply(hipStream_t s, const float* u_init, const double* V, int n, int ld, double* U,
+                       double* R) {
+  k_warm_apply<<<(n + 255) / 256, 256, 0, s>>>(u_init, V, n, ld, U, R);
 }
 
 void launch_pc_init(hipStream_t s, int n, HypArgs hyp, double* delta, DevState* st, double* arg_out,

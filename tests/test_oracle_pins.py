@@ -268,6 +268,41 @@ def test_rank0_preconditioner_reduces_to_textbook_cg_coefficients():
     assert np.allclose(res.beta[:, 0], be, rtol=1e-9)
 
 
+def test_warm_start_of_cg():
+    # Alg. 1/2 take the current solution as input: r_0 = b - A u_0
+    w = inputs.tiny(30, 3, kernel=O.RBF, t=3, k=3, noise=0.2)
+    Kh, L, P = _setup(w, 3)
+    B = np.concatenate([w.y[:, None].astype(np.float64), O.make_probes(L, w.noise, w.E1, w.E2)], axis=1)
+    exact = np.linalg.solve(Kh, B)
+    mm = lambda M: Kh @ M
+    cold = O.mbcg(mm, B, P.solve, 6)
+    # a zero start is the cold start, bit for bit
+    zero = O.mbcg(mm, B, P.solve, 6, U0=np.zeros_like(B))
+    assert np.array_equal(zero.U, cold.U) and np.array_equal(zero.alpha, cold.alpha)
+    # started at the exact solution nothing moves and the residual is at rounding level
+    at = O.mbcg(mm, B, P.solve, 3, U0=exact)
+    assert np.allclose(at.U, exact, rtol=1e-10, atol=1e-12)
+    assert at.resid.max() < 1e-10
+    # any start reaches the Cholesky solve at p = n, and a start near the solution is ahead of
+    # the cold start at every iteration (residuals relative to |b| in both)
+    rng = np.random.default_rng(0)
+    near = exact + 1e-3 * rng.standard_normal(exact.shape) * np.abs(exact).max()
+    full = O.mbcg(mm, B, P.solve, 30, U0=rng.standard_normal(B.shape))
+    assert np.allclose(full.U, exact, rtol=1e-7, atol=1e-9)
+    warm = O.mbcg(mm, B, P.solve, 6, U0=near)
+    assert np.all(warm.resid[:4] < cold.resid[:4])
+    # the error of a warm-started column is that of a cold CG on the shifted right-hand side
+    shifted = O.mbcg(mm, B - Kh @ near, P.solve, 6)
+    assert np.allclose(warm.U, near + shifted.U, rtol=1e-12, atol=1e-14)
+    # whole call: only the y column is warm-started
+    r_cold = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2, 3, 6)
+    r_warm = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2, 3, 6,
+                              u0_init=np.linalg.solve(Kh, w.y.astype(np.float64)))
+    assert np.array_equal(r_warm.mbcg.alpha[:, 1:], r_cold.mbcg.alpha[:, 1:])
+    assert r_warm.logdet == r_cold.logdet
+    assert np.allclose(r_warm.u0, np.linalg.solve(Kh, w.y.astype(np.float64)), rtol=1e-10)
+
+
 def test_columns_are_independent_solves():
     w = inputs.tiny(16, 2, kernel=inputs.RBF)
     Kh, L, P = _setup(w, 3)
