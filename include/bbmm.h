@@ -165,6 +165,7 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *                compute unit; clamped to [strips, 60 * strips], strips = column strips of K_hat)
  *   "otf_split"  number of row chunks an on-the-fly product is split into
  *   "ur_blocks"  upper limit of the workgroups of the fused U/R update (default 128, at most 512)
+ *   "zd_blocks"  workgroups per compute unit of the direction update (default 16, at most 64)
  *   "sgpr_wgs1", "sgpr_wgs2"  workgroups of the two streaming products of an SGPR product
  *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build
  *   "time_mm"    1: record HIP events on the context's stream around every K_hat.M launch of
@@ -252,7 +253,9 @@ int bbmm_dk_traces(bbmm_ctx* ctx, const float* U, const float* W, double* trace,
  * Both need bbmm_setup (or a completed bbmm_solve_logdet_grad) for the same
  * training data and hyperparameters; Xstar is device memory, ns x d float,
  * in the coordinates of X.
- * Not available for SGPR problems (BBMM_EINVAL).
+ * For an SGPR problem every covariance is the subset-of-regressors one,
+ * q(a, b) = k_{aU} K_UU^{-1} k_{Ub} (bbmm_sgpr_build must have run): mean = q_{x* X} u0,
+ * var = q(x*, x*) - q_{x* X} K_hat^{-1} q_{X x*}.
  * ---------------------------------------------------------------------- */
 
 /* mean[a] = k_{X x*_a}^T u0 with u0 = K_hat^{-1} y (device, n float; e.g. the u0 of

@@ -246,3 +246,46 @@ def sor_bbmm_inference(kernel: int, X, Uind, y, ls, s: float, noise: float, jitt
                         yKinvy=yKinvy, trace=trace, quad=quad,
                         nlml=O.nlml_from_terms(yKinvy, logdet, n), grad=0.5 * (trace - quad),
                         L=L, pivots=pivots, pivot_dmax=dmax, mbcg=res, B=B)
+
+
+# ----------------------------------------------------------------------------
+# Predictive distribution at test inputs under the SoR prior (Sec. 2, Eq. (1), with every
+# covariance replaced by its subset-of-regressors form q(a, b) = k_{aU} K_UU^{-1} k_{Ub}):
+#   mean(x*)     = q_{x* X} K_hat^{-1} y
+#   var(x*)      = q(x*, x*) - q_{x* X} K_hat^{-1} q_{X x*}          (latent f; add sigma^2 for y)
+# ----------------------------------------------------------------------------
+def sor_cross(kernel: int, Xs, Uind, ls, s: float, parts: SorParts):
+    """(Q_{X x*} as an n x ns matrix, q(x*, x*) as ns values)."""
+    Xs = np.asarray(Xs, dtype=np.float64)
+    Uind = np.asarray(Uind, dtype=np.float64)
+    KUs = O.kernel_block(kernel, Uind, Xs, ls, s)                   # m x ns
+    W = parts.kuu_solve(KUs)
+    return parts.KXU @ W, np.sum(KUs * W, axis=0)
+
+
+def sor_exact_predict(kernel: int, X, Uind, y, ls, s: float, noise: float, jitter_rel: float, Xs):
+    """The plain definition through the dense Cholesky factor of K_hat = Q + sigma^2 I (small n).
+    Returns (mean, var)."""
+    y = np.asarray(y, dtype=np.float64)
+    parts = sor_parts(kernel, X, Uind, ls, s, noise, jitter_rel)
+    n = y.shape[0]
+    Khat = sor_dense_q(parts) + noise * np.eye(n)
+    Khat = 0.5 * (Khat + Khat.T)
+    QXs, qss = sor_cross(kernel, Xs, Uind, ls, s, parts)
+    u0, _, factor = O.exact_solve_logdet(Khat, y)
+    mean = QXs.T @ u0
+    var = qss - np.sum(QXs * sla.cho_solve(factor, QXs), axis=0)
+    return mean, var
+
+
+def sor_bbmm_predict(kernel: int, X, Uind, ls, s: float, noise: float, jitter_rel: float, Xs,
+                     u0: np.ndarray, P: "O.Preconditioner", p: int, tol: float = 0.0):
+    """The same two quantities the way the method obtains them: the mean from a solve u0 that is
+    already there, the variances from one more preconditioned mBCG run (Alg. 2) whose right-hand
+    sides are the columns Q_{X x*}.  Returns (mean, var, MbcgResult)."""
+    parts = sor_parts(kernel, X, Uind, ls, s, noise, jitter_rel)
+    QXs, qss = sor_cross(kernel, Xs, Uind, ls, s, parts)
+    mean = QXs.T @ np.asarray(u0, dtype=np.float64)
+    res = O.mbcg(parts.khat_matmul, QXs, P.solve, p, tol)
+    var = qss - np.sum(QXs * res.U, axis=0)
+    return mean, var, res

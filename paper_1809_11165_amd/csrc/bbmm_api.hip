@@ -49,6 +49,7 @@ struct bbmm_ctx {
   int64_t mat_wgs = 0, otf_split = 0;        // 0 = default
   int64_t sgpr_wgs[2] = {0, 0};              // workgroups of the two SGPR streaming products (0 = default)
   int64_t ur_blocks_cap = 0;
+  int64_t zd_blocks = 0;                     // workgroups per compute unit of the D update (0 = default)
   // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
   int plan_np = 0, plan_wgs[2] = {0, 0};
   int64_t plan_tune = -1;
@@ -497,6 +498,9 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld, const float* warm = nullpt
   hipStream_t s = c->stream;
   DevState* st = ptr<DevState>(c->st);
   int nb = vec_blocks(c->n, ld);
+  // k_zd has no reduction, so its grid is not tied to the partial-sum layout: one 16-row trip per
+  // wave where n allows it (a trip costs a memory round trip; more waves overlap more of them)
+  int nb_zd = std::max(nb, std::min((c->n / 16 + 3) / 4, (c->zd_blocks > 0 ? (int)c->zd_blocks : 16) * c->num_cus));
   size_t blk = (size_t)c->np * ld;
   launch_fill_f64(s, ptr<double>(c->U), blk, 0.0);
   launch_fill_f64(s, ptr<double>(c->D4), blk, 0.0);
@@ -554,7 +558,7 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld, const float* warm = nullpt
               ptr<double>(c->U), ptr<double>(c->R), ptr<double>(c->L), st, pdv, nb, pur, nb_ur, j,
               ptr<double>(c->alpha), ptr<double>(c->beta), ptr<double>(c->resid));
     launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<double>(c->L), ptr<double>(c->D4),
-              ptr<double>(c->Z0), st, nb);
+              ptr<double>(c->Z0), st, nb_zd);
   }
   c->mbcg_done = true;
   c->last_c = cc;
@@ -776,6 +780,7 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   if (!strcmp(key, "mat_wgs")) c->mat_wgs = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
   else if (!strcmp(key, "ur_blocks")) c->ur_blocks_cap = value > 0 ? value : 0;
+  else if (!strcmp(key, "zd_blocks")) c->zd_blocks = value > 0 ? std::min<int64_t>(value, 64) : 0;
   else if (!strcmp(key, "sgpr_wgs1")) c->sgpr_wgs[0] = value > 0 ? value : 0;
   else if (!strcmp(key, "sgpr_wgs2")) c->sgpr_wgs[1] = value > 0 ? value : 0;
   else if (!strcmp(key, "time_mm")) c->time_mm = value > 0;
@@ -1031,9 +1036,23 @@ int bbmm_mbcg(bbmm_ctx* c, int32_t mode, const float* B, int64_t cc, float* U, d
 int bbmm_predict_mean(bbmm_ctx* c, const float* Xstar, int64_t ns, const float* u0, float* mean) {
   int rc = check_ready(c);
   if (rc) return rc;
-  if (c->sgpr) return fail(c, BBMM_EINVAL, "predictions are not available for SGPR problems");
   if (!Xstar || !u0 || !mean || ns < 1 || ns > (1 << 30)) return fail(c, BBMM_EINVAL, "bad test block");
   hipStream_t s = c->stream;
+  if (c->sgpr) {
+    // SoR prior: mean = k_{*U} K_UU^{-1} K_UX u0 = k_{*U} b0 with b0 = G^{-T} (A^T u0)
+    if (!c->sgpr_built) return fail(c, BBMM_EINVAL, "bbmm_sgpr_build must run first");
+    launch_fill_bytes0(s, &ptr<DevState>(c->st)->done, sizeof(int));
+    launch_fill_f64(s, ptr<double>(c->tmpA), (size_t)c->np * 16, 0.0);
+    launch_warm_rhs(s, u0, c->n, 16, ptr<double>(c->tmpA));
+    VpShape sh{0, nullptr, 1};
+    rc = sgpr_first_pass(c, 16, ptr<double>(c->tmpA), &sh);
+    if (rc) return rc;
+    launch_sgpr_mid_rows(s, ptr<double>(c->Tp), sh, c->mp, 16, ptr<double>(c->TU));
+    launch_sgpr_bsolve(s, ptr<double>(c->Ginv), ptr<double>(c->TU), c->mp, 16, ptr<double>(c->BU));
+    launch_cross_dot(s, c->prob.Uind, Xstar, c->m, (int)ns, c->hyp, ptr<double>(c->BU), 16, 0, 0.0, 1.0, mean);
+    HIPCHK(c, hipGetLastError());
+    return BBMM_OK;
+  }
   launch_pack_rows(s, u0, c->n, 1, 16, ptr<double>(c->tmpB));
   launch_cross_dot(s, c->prob.X, Xstar, c->n, (int)ns, c->hyp, ptr<double>(c->tmpB), 16, 0, 0.0, 1.0, mean);
   HIPCHK(c, hipGetLastError());
@@ -1044,17 +1063,37 @@ int bbmm_predict_var(bbmm_ctx* c, int32_t mode, const float* Xstar, int64_t ns, 
                      int64_t* iters_run, double* max_resid) {
   int rc = check_ready(c);
   if (rc) return rc;
-  if (c->sgpr) return fail(c, BBMM_EINVAL, "predictions are not available for SGPR problems");
   if (!Xstar || !var || ns < 1 || ns > BBMM_MAXC)
     return fail(c, BBMM_EINVAL, "bad test block (1 <= ns <= 32 per call)");
   if (!c->pre_done) return fail(c, BBMM_EINVAL, "bbmm_precond_setup must run first");
   hipStream_t s = c->stream;
   int ld = ld_for((int)ns);
-  launch_cross_block(s, c->prob.X, Xstar, c->n, (int)ns, ld, c->hyp, ptr<double>(c->R));
-  rc = stage_mbcg(c, mode, (int)ns, ld);
-  if (rc) return rc;
-  launch_cross_dot(s, c->prob.X, Xstar, c->n, (int)ns, c->hyp, ptr<double>(c->U), ld, 1,
-                   c->prob.outputscale, -1.0, var);
+  if (c->sgpr) {
+    // SoR prior: q(x*, x*) = |v|^2 and the right-hand sides Q_{X x*} = A v with v = G^{-1} k_{U x*}
+    if (mode != BBMM_MODE_SGPR) return fail(c, BBMM_EINVAL, "an SGPR problem takes mode SGPR");
+    size_t mb = (size_t)c->mp * ld;
+    launch_fill_bytes0(s, &ptr<DevState>(c->st)->done, sizeof(int));
+    launch_fill_f64(s, ptr<double>(c->TU), mb, 0.0);
+    launch_cross_block(s, c->prob.Uind, Xstar, c->m, (int)ns, ld, c->hyp, ptr<double>(c->TU));
+    launch_sgpr_fsolve(s, ptr<double>(c->Ginv), ptr<double>(c->TU), c->mp, ld, ptr<double>(c->BU));
+    launch_colnorm2(s, ptr<double>(c->BU), c->mp, ld, ptr<double>(c->TW));
+    launch_rows_to_d4(s, ptr<double>(c->BU), c->mp, c->mp, ld, ptr<double>(c->T4));
+    VpShape sh{0, nullptr, 1};
+    rc = sgpr_second_pass(c, ld, &sh);
+    if (rc) return rc;
+    launch_fill_f64(s, ptr<double>(c->D4), (size_t)c->np * ld, 0.0);
+    launch_vreduce(s, ptr<double>(c->Vp), sh, c->n, c->np, ld, 1.0, 0.0, ptr<double>(c->D4), ptr<double>(c->R));
+    HIPCHK(c, hipMemcpyAsync(c->tmpB.p, c->R.p, sizeof(double) * (size_t)c->np * ld, hipMemcpyDeviceToDevice, s));
+    rc = stage_mbcg(c, mode, (int)ns, ld);
+    if (rc) return rc;
+    launch_coldot_var(s, ptr<double>(c->tmpB), ptr<double>(c->U), c->n, ld, (int)ns, ptr<double>(c->TW), var);
+  } else {
+    launch_cross_block(s, c->prob.X, Xstar, c->n, (int)ns, ld, c->hyp, ptr<double>(c->R));
+    rc = stage_mbcg(c, mode, (int)ns, ld);
+    if (rc) return rc;
+    launch_cross_dot(s, c->prob.X, Xstar, c->n, (int)ns, c->hyp, ptr<double>(c->U), ld, 1,
+                     c->prob.outputscale, -1.0, var);
+  }
   rc = fetch_state(c, true);
   if (rc) return rc;
   rc = device_status(c);

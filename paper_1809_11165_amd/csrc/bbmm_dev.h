@@ -141,6 +141,10 @@ void launch_sgpr_pick(hipStream_t s, const float* A, int mp, const double* arg_i
 
 void launch_rows_to_d4(hipStream_t s, const double* src, int n, int np, int ld, double* D4);
 void launch_sgpr_bsolve(hipStream_t s, const double* Ginv, const double* T, int mp, int ld, double* B);
+void launch_sgpr_fsolve(hipStream_t s, const double* Ginv, const double* T, int mp, int ld, double* B);
+void launch_colnorm2(hipStream_t s, const double* V, int mp, int ld, double* out);
+void launch_coldot_var(hipStream_t s, const double* B, const double* U, int n, int ld, int ns,
+                       const double* prior, float* var);
 void launch_sgpr_sterm(hipStream_t s, const double* TU, const double* TW, int mp, int ld, int t,
                        double outputscale, int slot, DevState* st);
 void launch_sgpr_dk_ops(hipStream_t s, const double* U, const double* Z0, const double* BU,

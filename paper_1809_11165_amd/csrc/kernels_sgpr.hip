@@ -482,6 +482,59 @@ __global__ void k_rows_to_d4(const double* __restrict__ src, int n, int np, int 
   D4[d4_index(i, q, ld)] = (i < n) ? src[idx] : 0.0;
 }
 
+// forward: B = G^{-1} T,  B[a][q] = sum_{b <= a} Ginv[a][b] T[b][q]   (mp x ld, row-major)
+__global__ void k_sgpr_fsolve(const double* __restrict__ Ginv, const double* __restrict__ T, int mp,
+                              int ld, double* __restrict__ B) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)mp * ld) return;
+  int q = (int)(idx % ld), a = (int)(idx / ld);
+  double s0 = 0.0, s1 = 0.0;
+  int b = 0;
+  for (; b + 1 <= a; b += 2) {
+    s0 += Ginv[(size_t)a * mp + b] * T[(size_t)b * ld + q];
+    s1 += Ginv[(size_t)a * mp + b + 1] * T[(size_t)(b + 1) * ld + q];
+  }
+  if (b <= a) s0 += Ginv[(size_t)a * mp + b] * T[(size_t)b * ld + q];
+  B[idx] = s0 + s1;
+}
+
+// out[q] = sum_a V[a][q]^2, q < ld (one block; V is mp x ld)
+__global__ __launch_bounds__(256) void k_colnorm2(const double* __restrict__ V, int mp, int ld,
+                                                   double* __restrict__ out) {
+  __shared__ double red[256];
+  int q = threadIdx.x % ld, part = threadIdx.x / ld, parts = 256 / ld;
+  double acc = 0.0;
+  for (int a = part; a < mp; a += parts) {
+    double v = V[(size_t)a * ld + q];
+    acc += v * v;
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  if (part == 0) {
+    double s = 0.0;
+    for (int pp = 0; pp < parts; ++pp) s += red[pp * ld + q];
+    out[q] = s;
+  }
+}
+
+// var[a] = prior[a] - sum_i B[i][a] U[i][a]  (one block per column a, fixed-order fp64 block sum)
+__global__ __launch_bounds__(256) void k_coldot_var(const double* __restrict__ B,
+                                                     const double* __restrict__ U, int n, int ld,
+                                                     const double* __restrict__ prior,
+                                                     float* __restrict__ var) {
+  __shared__ double red[256];
+  int a = blockIdx.x;
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) acc += B[(size_t)i * ld + a] * U[(size_t)i * ld + a];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) var[a] = (float)(prior[a] - red[0]);
+}
+
 // B = G^{-T} T:  B[a][q] = sum_{b >= a} Ginv[b][a] T[b][q]   (mp x ld, row-major)
 __global__ void k_sgpr_bsolve(const double* __restrict__ Ginv, const double* __restrict__ T, int mp,
                               int ld, double* __restrict__ B) {
@@ -756,6 +809,20 @@ void launch_rows_to_d4(hipStream_t s, const double* src, int n, int np, int ld, 
 void launch_sgpr_bsolve(hipStream_t s, const double* Ginv, const double* T, int mp, int ld, double* B) {
   size_t total = (size_t)mp * ld;
   k_sgpr_bsolve<<<(int)((total + 255) / 256), 256, 0, s>>>(Ginv, T, mp, ld, B);
+}
+
+void launch_sgpr_fsolve(hipStream_t s, const double* Ginv, const double* T, int mp, int ld, double* B) {
+  size_t total = (size_t)mp * ld;
+  k_sgpr_fsolve<<<(int)((total + 255) / 256), 256, 0, s>>>(Ginv, T, mp, ld, B);
+}
+
+void launch_colnorm2(hipStream_t s, const double* V, int mp, int ld, double* out) {
+  k_colnorm2<<<1, 256, 0, s>>>(V, mp, ld, out);
+}
+
+void launch_coldot_var(hipStream_t s, const double* B, const double* U, int n, int ld, int ns,
+                       const double* prior, float* var) {
+  k_coldot_var<<<ns, 256, 0, s>>>(B, U, n, ld, prior, var);
 }
 
 void launch_sgpr_sterm(hipStream_t s, const double* TU, const double* TW, int mp, int ld, int t,

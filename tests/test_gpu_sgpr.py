@@ -287,6 +287,39 @@ def test_sgpr_is_deterministic(ctx):
     assert a.logdet == b.logdet and np.array_equal(a.trace, b.trace)
 
 
+# ------------------------------------------------------------- predictions -----
+@pytest.mark.parametrize("kernel,ard,n,d,m,ns", [(inputs.RBF, False, 700, 5, 37, 1),
+                                                  (inputs.MATERN52, True, 523, 16, 64, 17),
+                                                  (inputs.RBF, True, 1300, 3, 300, 32)])
+def test_sgpr_predictions_match_oracle(ctx, kernel, ard, n, d, m, ns):
+    # Eq. (1) under the SoR prior: mean = q_{x* X} u0, var = q(x*, x*) - q_{x* X} K_hat^{-1} q_{X x*}
+    w = _case(kernel, ard, n, d, m, t=4, k=6, iters=60, noise=0.2)
+    rng = np.random.default_rng(21)
+    Xs = np.concatenate([rng.standard_normal((ns - ns // 2, d)), w.X[:ns // 2]]).astype(np.float32)
+    res = ctx.bbmm_solve_logdet_grad(_problem(w))
+    parts = _parts(w)
+    QXs, qss = S.sor_cross(w.kernel, Xs, w.Uind, w.lengthscale, w.outputscale, parts)
+    mean = _host(ctx.bbmm_predict_mean(_dev(Xs), res.u0))
+    # the mean is a plain product with the solve it is given
+    ref_mean = QXs.T @ _host(res.u0)
+    assert np.max(np.abs(mean - ref_mean)) < 2e-6 * np.max(np.abs(ref_mean)) + 1e-6 * np.linalg.norm(_host(res.u0))
+    var, iters, resid = ctx.bbmm_predict_var(SGPR, _dev(Xs))
+    var = _host(var)
+    L = np.zeros((n, w.k))
+    # the oracle's run on the same right-hand sides, pivots and iteration count
+    Lf, pf, dmax = O.pivoted_cholesky(parts.q_diag(), parts.q_row, w.k, res.pivots)
+    P = O.make_preconditioner(Lf, w.noise)
+    m2, v2, ref = S.sor_bbmm_predict(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.noise,
+                                     w.jitter_rel, Xs, _host(res.u0), P, iters)
+    assert np.max(np.abs(var - v2)) < 1e-3 * w.outputscale
+    # and the definition (dense Cholesky of the SoR K_hat): 60 iterations have converged here
+    me, ve = S.sor_exact_predict(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise,
+                                 w.jitter_rel, Xs)
+    assert np.max(np.abs(var - ve)) < 1e-3 * w.outputscale + 2 * np.max(np.abs(v2 - ve))
+    assert np.max(np.abs(mean - me)) < 1e-3 * np.max(np.abs(me)) + 2 * np.max(np.abs(m2 - me))
+    assert np.all(var > -1e-5) and np.all(var <= qss + 1e-5)
+
+
 # -------------------------------------------------------------- edge cases -----
 def test_sgpr_edge_one_inducing_point_and_m_equals_n(ctx):
     w = _case(inputs.RBF, False, 40, 2, 1, t=2, k=1, iters=4)
@@ -312,7 +345,7 @@ def test_sgpr_invalid_arguments_and_call_order(ctx):
     with pytest.raises(binding.BbmmError):
         ctx.bbmm_kernel_mm(inputs.ONTHEFLY, _dev(np.ones((60, 3))))
     with pytest.raises(binding.BbmmError):
-        ctx.bbmm_predict_mean(_dev(np.ones((2, 3))), _dev(np.ones(60)))
+        ctx.bbmm_predict_var(inputs.ONTHEFLY, _dev(np.ones((2, 3))))
     # m > n, negative jitter
     q = _problem(w)
     q.Uind = _dev(np.ones((61, 3)))

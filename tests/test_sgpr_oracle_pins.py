@@ -211,3 +211,40 @@ def test_sor_bbmm_against_exact_on_a_moderate_problem():
     # Hutchinson with t = 10: the outputscale and noise traces are sums of positive terms; the
     # lengthscale trace is a small difference of large ones and only unbiased (enumeration test)
     assert np.allclose(r.trace[1:], ex.trace[1:], rtol=0.2)
+
+
+def test_sor_predictions_against_definitions():
+    w = inputs.tiny_sgpr(50, 3, 8, kernel=O.MATERN52, ard=True, seed=12, noise=0.15)
+    rng = np.random.default_rng(3)
+    Xs = np.concatenate([rng.standard_normal((5, 3)), w.X[:3].astype(np.float64), w.Uind[:2].astype(np.float64)])
+    mean, var = S.sor_exact_predict(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise,
+                                    w.jitter_rel, Xs)
+    # (1) weight-space view of SoR (a Bayesian linear model in the m features k_{U x}): with
+    #     Sigma = (K_UU + K_UX K_XU / sigma^2)^{-1}, mean = k_{*U} Sigma K_UX y / sigma^2 and
+    #     var = k_{*U} Sigma k_{U*}  -- an independent closed form of the same posterior
+    parts = _parts(w)
+    KUs = O.kernel_block(w.kernel, w.Uind, Xs, w.lengthscale, w.outputscale)
+    Sigma = np.linalg.inv(parts.KUU + parts.KXU.T @ parts.KXU / w.noise)
+    mean_ws = KUs.T @ Sigma @ (parts.KXU.T @ w.y.astype(np.float64)) / w.noise
+    var_ws = np.sum(KUs * (Sigma @ KUs), axis=0)
+    assert np.allclose(mean, mean_ws, rtol=1e-7, atol=1e-10)
+    assert np.allclose(var, var_ws, rtol=1e-6, atol=1e-10)
+    # (2) valid variances: 0 <= var <= q(x*, x*) <= k(x*, x*)
+    QXs, qss = S.sor_cross(w.kernel, Xs, w.Uind, w.lengthscale, w.outputscale, parts)
+    assert np.all(var > -1e-12) and np.all(var <= qss + 1e-12) and np.all(qss <= w.outputscale * (1 + 1e-9))
+    # (3) U = X, jitter -> 0: the exact-GP predictions
+    mean_x, cov_x = O.exact_predict(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, Xs)
+    mean_u, var_u = S.sor_exact_predict(w.kernel, w.X, w.X, w.y, w.lengthscale, w.outputscale, w.noise,
+                                        1e-10, w.X[:6])
+    mean_e, cov_e = O.exact_predict(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.X[:6])
+    assert np.allclose(mean_u, mean_e, rtol=1e-5, atol=1e-7)
+    assert np.allclose(var_u, np.diag(cov_e), rtol=1e-4, atol=1e-7)
+    # (4) the method's route (mBCG on the columns Q_{X x*}) reaches the definition when run to p = n
+    ex = S.sor_exact_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise,
+                               w.jitter_rel, with_traces=False)
+    L, piv, _ = O.pivoted_cholesky(parts.q_diag(), parts.q_row, 3)
+    P = O.make_preconditioner(L, w.noise)
+    m2, v2, res = S.sor_bbmm_predict(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.noise,
+                                     w.jitter_rel, Xs, ex.u0, P, 50)
+    assert np.allclose(m2, mean, rtol=1e-8, atol=1e-10)
+    assert np.allclose(v2, var, rtol=1e-6, atol=1e-9)
