@@ -149,6 +149,12 @@ def run_sgpr(name: str, cfg: int, n: int, m: int):
         dg, off = O.tridiag_from_cg(prev.alpha[:, i + 1], prev.beta[:, i + 1], mv)
         terms_prev.append(prev.rho0[i + 1] * O.e1_logT_e1(dg, off))
     logdet_prev = P.logdet + float(np.mean(terms_prev))
+    say("derivative terms one iteration earlier")
+    dargs0 = (w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel, parts)
+    trace_prev = list(S.sor_derivative_products(*dargs0, prev.U[:, 1:], prev.Z0[:, 1:]) / w.t)
+    quad_prev = list(S.sor_derivative_products(*dargs0, prev.U[:, :1], prev.U[:, :1]))
+    trace_prev.append(float(np.sum(prev.U[:, 1:] * prev.Z0[:, 1:]) / w.t))
+    quad_prev.append(float(prev.U[:, 0] @ prev.U[:, 0]))
     del prev
     say("rerun with products grouped through the root")
     A = sla.solve_triangular(parts.chol_UU, parts.KXU.T, lower=True).T
@@ -191,6 +197,7 @@ def run_sgpr(name: str, cfg: int, n: int, m: int):
         "trace_alt": [float(v) for v in trace_alt], "quad_alt": [float(v) for v in quad_alt],
         "trace_sens": trace_sens.tolist(), "quad_sens": quad_sens.tolist(),
         "yKinvy_prev": yKinvy_prev, "logdet_prev": logdet_prev, "yKinvy_alt": yKinvy_alt,
+        "trace_prev": [float(v) for v in trace_prev], "quad_prev": [float(v) for v in quad_prev],
         "L_sample": res.L[rows].tolist(),
         "seconds": time.time() - t0,
     }
