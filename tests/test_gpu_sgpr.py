@@ -262,6 +262,25 @@ def test_sgpr_full_path_small(ctx, kernel, ard, n, d, m):
     assert abs(res.logdet - ld_ref) <= max(1e-2 * abs(ld_ref), est_err + 1e-3 * abs(ld_ref))
 
 
+def test_sgpr_full_path_wide_block_and_warm_start(ctx):
+    # t = 20: 21 columns -> 32-wide blocks, 512-column strips, 64-entry derivative operands
+    w = _case(inputs.MATERN52, True, 1500, 6, 130, t=20, k=8, iters=40, noise=0.3)
+    res, ref = _full_parity(ctx, w)
+    # warm start of the y column from a perturbed solve: same probe columns, y column ahead
+    from paper_1809_11165_amd import binding
+    u_ref, _ = S.sor_woodbury(_parts(w), w.y)
+    rng = np.random.default_rng(8)
+    u_init = (u_ref + 0.05 * np.abs(u_ref).max() * rng.standard_normal(w.n)).astype(np.float32)
+    prob = _problem(w)
+    prob.u0_init = _dev(u_init)
+    prob.pivots_in = res.pivots
+    warm = ctx.bbmm_solve_logdet_grad(prob)
+    assert warm.pivots.tolist() == res.pivots.tolist()
+    assert np.array_equal(warm.alpha[:, 1:], res.alpha[:, 1:]) and warm.logdet == res.logdet
+    assert np.all(warm.resid[:5, 0] < res.resid[:5, 0])
+    assert _colrel(_host(warm.u0), u_ref) < 1e-3 + _colrel(ref.u0, u_ref)
+
+
 def test_sgpr_full_path_config5_shape(ctx):
     w = inputs.make(5, n=20000, m=512)       # the recipe of config 5 at reduced n and m
     res, ref = _full_parity(ctx, w)
