@@ -365,7 +365,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_sgpr_root(const double* __restri
 }
 
 // A (np x mp, row-major) from A^T stored in column panels of BBMM_SGPR_PANEL points.
-__global__ __launch_bounds__(256) void k_root_transpose(const float* __restrict__ ATp, int mp, int np,
+__global__ __launch_bounds__(256) void k_root_transpose(const float* __restrict__ ATp, int mp,
                                                          float* __restrict__ A) {
   __shared__ float tile[64][65];
   int a0 = blockIdx.y * 64, i0 = blockIdx.x * 64;
@@ -778,7 +778,7 @@ void launch_sgpr_root(hipStream_t s, const double* Ginv, double* GinvP, const do
 }
 
 void launch_root_transpose(hipStream_t s, const float* ATp, int mp, int np, float* A) {
-  k_root_transpose<<<dim3(np / 64, mp / 64), 256, 0, s>>>(ATp, mp, np, A);
+  k_root_transpose<<<dim3(np / 64, mp / 64), 256, 0, s>>>(ATp, mp, A);
 }
 
 void launch_sgpr_qdiag(hipStream_t s, const float* A, int n, int mp, double* qdiag) {

@@ -640,16 +640,8 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShap
   }
 }
 
-// value of lane `src` (the same for the whole wave) in every lane
-__device__ inline double bcast_lane(double v, int src) {
-  int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
-  int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
-  return __hiloint2double(hi, lo);
-}
-
 constexpr int UT = 1024;      // threads of the update kernel
 static_assert(BBMM_MAXK * BBMM_MAXK == UT, "k_ur_fin loads one entry of G per thread");
-constexpr int URB = 5;        // quantities reduced per barrier pair
 
 // alpha_j for column q from the d^T v total, with the freeze guard (k_ur_main needs the value,
 // k_ur_fin records it; both evaluate this on the state they read at their start).
