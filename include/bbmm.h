@@ -12,10 +12,14 @@
  * Conventions
  *   - "device" pointers are HIP device memory on the context's GPU, "host"
  *     pointers are ordinary host memory.  All matrices are dense row-major.
- *   - The caller owns every buffer it passes; the library neither frees nor
- *     keeps any of them after a call returns.
- *   - Work is queued on the context's HIP stream (bbmm_solve_logdet_grad also
- *     uses a second stream of its own, joined back before it returns).  A call
+ *   - The caller owns every buffer it passes; the library never frees them.
+ *     bbmm_solve_logdet_grad uses them only until it returns; the stage-level
+ *     entry points read the problem's device buffers (X, y, E1, E2, Uind,
+ *     u0_init) again, so these must stay valid while the problem set by
+ *     bbmm_setup is in use.
+ *   - Work is queued on the context's HIP stream (bbmm_solve_logdet_grad and
+ *     bbmm_sgpr_build also use a second stream of the context, joined back
+ *     before they return).  A call
  *     that returns host values synchronises the stream once before it returns.
  *   - Precision: K_hat entries are fp32; inside the library every n x c block of
  *     the iteration, the pivoted-Cholesky factor and all sums are fp64.  float
@@ -26,7 +30,8 @@
  *   - Hyperparameter order in every per-hyperparameter array:
  *         lengthscale(s) (1 or d entries), outputscale, noise (sigma^2);
  *     raw values, no log/softplus transform.
- *   - Limits: 1 <= t <= 31, 0 <= k <= 32, 1 <= d <= 64, max_iters <= 256.
+ *   - Limits: 1 <= t <= 31, 0 <= k <= 32, 1 <= d <= 64, max_iters <= 256;
+ *     BBMM_MODE_SGPR: 1 <= m <= min(n, 4096), d <= 32.
  */
 #ifndef BBMM_H
 #define BBMM_H
@@ -43,7 +48,7 @@ enum {
   BBMM_OK = 0,
   BBMM_EINVAL = 1,     /* bad shape, NULL pointer, limit exceeded, wrong call order */
   BBMM_ENOMEM = 2,     /* device allocation failed (e.g. materialised K_hat does not fit) */
-  BBMM_ENOTPD = 3,     /* capacitance matrix not positive definite / d^T K d <= 0 everywhere */
+  BBMM_ENOTPD = 3,     /* capacitance matrix (or K_UU + jitter I) not positive definite */
   BBMM_ENONFINITE = 4, /* a non-finite value reached a result */
   BBMM_EHIP = 5        /* a HIP runtime call failed */
 };
