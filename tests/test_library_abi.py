@@ -72,6 +72,28 @@ def test_struct_layouts_match_the_header_field_order():
     assert fields("bbmm_result") == [f[0] for f in binding._Result._fields_]
 
 
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 on its own, and a C translation unit
+    # that takes the address of every declared function must link against the library
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    _ensure_built()
+    names = _declared_functions()
+    src = tmp_path / "abi.c"
+    src.write_text('#include "bbmm.h"\n#include <stdio.h>\ntypedef void (*fn)(void);\nint main(void) {\n'
+                   '  fn f[] = {%s};\n  bbmm_problem p; bbmm_result r; (void)p; (void)r;\n'
+                   '  printf("%%d\\n", (int)(sizeof f / sizeof f[0]));\n  return bbmm_destroy(0);\n}\n'
+                   % ", ".join("(fn)%s" % n for n in names))
+    exe = tmp_path / "abi"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.dirname(HEADER), str(src),
+                    "-o", str(exe), LIB, "-Wl,-rpath," + os.path.dirname(LIB)], check=True)
+    out = subprocess.run([str(exe)], check=True, stdout=subprocess.PIPE, text=True).stdout
+    assert int(out) == len(names)
+
+
 def test_context_refuses_to_run_without_a_gpu():
     import torch
     if torch.cuda.is_available():
