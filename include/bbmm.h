@@ -170,6 +170,9 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *                compute unit; clamped to [strips, 60 * strips], strips = column strips of K_hat)
  *   "otf_split"  number of row chunks an on-the-fly product is split into
  *   "ur_blocks"  upper limit of the workgroups of the fused U/R update (default 128, at most 512)
+ *   "khat_panel" layout of the materialised K_hat: column panels of that width (a multiple of
+ *                256; default 1024), each panel row-major; 1 = plain row-major.  Takes effect at
+ *                the next bbmm_build_khat
  *   "zd_blocks"  workgroups per compute unit of the direction update (default 16, at most 64)
  *   "sgpr_wgs1", "sgpr_wgs2"  workgroups of the two streaming products of an SGPR product
  *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build

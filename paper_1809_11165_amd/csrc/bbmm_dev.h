@@ -81,8 +81,8 @@ void launch_unpack_rows(hipStream_t s, const double* src, int ld, int n, int c, 
 void launch_unpack_rows_f64(hipStream_t s, const double* src, int ld, int n, int c, double* dst);
 void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, double* dst);
 void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, double* dst);
-void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0, int nrows, int col0,
-                       int ncols, float* dst);
+void launch_copy_block(hipStream_t s, const float* src, size_t pw, size_t rows_p, int row0, int nrows,
+                       int col0, int ncols, float* dst);
 void launch_warm_rhs(hipStream_t s, const float* u_init, int n, int ld, double* D4);
 void launch_warm_apply(hipStream_t s, const float* u_init, const double* V, int n, int ld, double* U,
                        double* R);
@@ -155,8 +155,10 @@ int launch_dk_rect(hipStream_t s, int kernel, int dp, int NT, int ard, const flo
                    int ncols, double* partial, int pstride);
 
 // ---- launchers implemented in kernels_mm.hip ----------------------------------------------
+// panel_width > 0: K_hat is written in column panels of that width (see launch_mm_mat); 0: row-major
 int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
-                      const float* sq, int n, int np, double outputscale, double noise, float* Khat);
+                      const float* sq, int n, int np, int panel_width, double outputscale, double noise,
+                      float* Khat);
 // Streams the row-major fp32 matrix M (row stride = column count `np`, a multiple of 256) once and
 // leaves partial sums of M^T D in Vp, D4 indexed by the rows of M.  For the symmetric K_hat that is
 // K_hat D; the SGPR root uses it on both of its layouts.  plan: one entry per workgroup, laid out

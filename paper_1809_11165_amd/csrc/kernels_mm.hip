@@ -62,7 +62,7 @@ template <int KIND, int KK>
 __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa,
                                                      const float* __restrict__ Xb,
                                                      const float* __restrict__ sq, int n, int np,
-                                                     float outputscale, float noise,
+                                                     int pw, float outputscale, float noise,
                                                      float* __restrict__ Khat) {
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int jb = blockIdx.y * 4 + wave;
@@ -90,7 +90,9 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
       if (i >= n || j >= n) v = 0.f;
       out[r] = v;
     }
-    *(f32x4*)(Khat + (size_t)j * np + (size_t)(ib * 16 + g * 4)) = out;
+    // column panels of width pw, each row-major (pw == np: plain row-major)
+    int col = ib * 16 + g * 4;
+    *(f32x4*)(Khat + (size_t)(col / pw) * np * pw + (size_t)j * pw + (size_t)(col % pw)) = out;
   }
 }
 
@@ -588,13 +590,15 @@ __global__ void k_extract_col(const double* __restrict__ src, int ld, int n, int
   }
 
 int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
-                      const float* sq, int n, int np, double outputscale, double noise, float* Khat) {
+                      const float* sq, int n, int np, int panel_width, double outputscale, double noise,
+                      float* Khat) {
+  int pw = panel_width > 0 ? panel_width : np;
   dim3 grid(np / 64, np / 64);
 #define BUILD(K)                                                                                  \
   if (kernel == 0)                                                                                \
-    k_build_khat<0, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, (float)outputscale, (float)noise, Khat); \
+    k_build_khat<0, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, pw, (float)outputscale, (float)noise, Khat); \
   else                                                                                            \
-    k_build_khat<1, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, (float)outputscale, (float)noise, Khat)
+    k_build_khat<1, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, pw, (float)outputscale, (float)noise, Khat)
   FOR_KK(BUILD)
 #undef BUILD
   return 0;

@@ -224,13 +224,15 @@ __global__ void k_pack_cols_at(const float* __restrict__ src, int n, int c, int 
   dst[(size_t)i * ld + dstcol0 + q] = (double)src[idx];
 }
 
-// dst (nrows x ncols, dense) = src[row0:row0+nrows, col0:col0+ncols]
-__global__ void k_copy_block(const float* __restrict__ src, size_t ld_src, int row0, int nrows,
-                             int col0, int ncols, float* __restrict__ dst) {
+// dst (nrows x ncols, dense) = src[row0:row0+nrows, col0:col0+ncols]; src is stored in column
+// panels of width pw, each row-major with rows_p rows (pw = row length: plain row-major)
+__global__ void k_copy_block(const float* __restrict__ src, size_t pw, size_t rows_p, int row0,
+                             int nrows, int col0, int ncols, float* __restrict__ dst) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)nrows * ncols) return;
   int i = (int)(idx / ncols), j = (int)(idx % ncols);
-  dst[idx] = src[(size_t)(row0 + i) * ld_src + (size_t)(col0 + j)];
+  size_t col = (size_t)(col0 + j);
+  dst[idx] = src[(col / pw) * rows_p * pw + (size_t)(row0 + i) * pw + col % pw];
 }
 
 // V = scaleV * sum_s Vp[s] + addD * D  (no dot product; used by the stand-alone product call)
@@ -1224,9 +1226,9 @@ void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, 
   k_pack_cols_at<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, n, c, ld, dstcol0, dst);
 }
 
-void launch_copy_block(hipStream_t s, const float* src, size_t ld_src, int row0, int nrows, int col0,
-                       int ncols, float* dst) {
-  k_copy_block<<<blocks_for((size_t)nrows * ncols, 256), 256, 0, s>>>(src, ld_src, row0, nrows, col0,
+void launch_copy_block(hipStream_t s, const float* src, size_t pw, size_t rows_p, int row0, int nrows,
+                       int col0, int ncols, float* dst) {
+  k_copy_block<<<blocks_for((size_t)nrows * ncols, 256), 256, 0, s>>>(src, pw, rows_p, row0, nrows, col0,
                                                                       ncols, dst);
 }
 
