@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
+MFMA_F64_PEAK_TFLOPS = 78.6    # MI355X dense fp64 matrix, published
 FP64_VALU_PEAK_TFLOPS = 78.6   # MI355X fp64 vector, published
 # HBM bytes per k_mm_mat launch at n = 50000 from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by a
 # 1 GiB copy (profiles/k_mm_mat_cfg3_n50000_hbm_counters.txt); only valid for that workload.
@@ -32,6 +33,7 @@ MEASURED_TRAFFIC_MAT_N50000 = 10.425e9
 # HBM bytes per SGPR product (both k_mm_mat launches) at n = 500000, m = 1024, measured the same way
 # (profiles/k_mm_mat_cfg5_n500000_sgpr_hbm_counters.txt); only valid for that workload.
 MEASURED_TRAFFIC_SGPR_N500000_M1024 = 4.261e9
+MEASURED_TRAFFIC_SYM_N50000 = None      # not measured yet
 
 
 def cpu_baseline(n_sample: int, n_full: int):
@@ -83,7 +85,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--mode", choices=["mat", "otf", "sgpr"], default="mat")
+    ap.add_argument("--mode", choices=["mat", "sym", "otf", "sgpr"], default="mat")
     ap.add_argument("--n", type=int, default=None, help="points (default 50000; 500000 for --mode sgpr)")
     ap.add_argument("--m", type=int, default=1024, help="inducing inputs (--mode sgpr)")
     ap.add_argument("--cpu-sample", type=int, default=10000)
@@ -99,13 +101,16 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU: the path runs only in the HIP library")
-    mode = {"mat": inputs.MATERIALISED, "otf": inputs.ONTHEFLY, "sgpr": inputs.SGPR}[args.mode]
+    mode = {"mat": inputs.MATERIALISED, "sym": inputs.MATERIALISED, "otf": inputs.ONTHEFLY,
+            "sgpr": inputs.SGPR}[args.mode]
     if args.n is None:
         args.n = 500000 if mode == inputs.SGPR else 50000
     w = inputs.make(5, n=args.n, m=args.m) if mode == inputs.SGPR else inputs.make(3, n=args.n)
     prob = binding.problem_from_workload(w, mode)
     ctx = binding.Context(0)
     ctx.bbmm_tune("time_mm", 1)
+    if args.mode == "sym":
+        ctx.bbmm_tune("khat_sym", 1)        # keep the upper triangle of K_hat only
 
     res = None
     for _ in range(args.warmup):
@@ -148,6 +153,19 @@ def main():
                     "iterations" % (n, m))
         metric = "mBCG solve+logdet+grad ms at n=500k,m=1024,t=10 (SGPR)"
         mode_name = "fp32 root A = K_XU G^-T in both layouts"
+    elif args.mode == "sym":
+        # the triangle is read once (2 n^2 + 4 n W bytes, W = 1024: the diagonal blocks are whole), but
+        # every 16 x 16 tile still takes its 2 x 4 fp64 MFMAs per 16 columns of the block: the
+        # product is bound by the fp64 matrix rate, 2 n^2 * 16 flop per launch
+        alg_flops = 2.0 * n * n * 16 * ((c + 15) // 16)
+        achieved = alg_flops / (mm_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F64_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / MFMA_F64_PEAK_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_SYM_N50000 if n == 50000 else None,
+                    "kernel": "k_mm_sym<true> (+ k_mm_sym<false> on the diagonal blocks)",
+                    "avg_launch_ms": mm_ms, "launches": mm_launches,
+                    "effective_GBps_of_full_matrix": (4.0 * n * n + 8.0 * n * c) / (mm_ms * 1e-3) / 1e9}
+        mode_name = "materialised fp32 K_hat, upper triangle only (khat_sym)"
     elif mode == inputs.MATERIALISED:
         # algorithmic bytes of one K_hat.D launch: K_hat once (4 n^2) + block in and out (8 n c)
         alg_bytes = 4.0 * n * n + 8.0 * n * c

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libbbmm.so")
-SOURCES = ["kernels_vec.hip", "kernels_mm.hip", "kernels_sgpr.hip", "bbmm_api.hip"]
+SOURCES = ["kernels_vec.hip", "kernels_mm.hip", "kernels_sym.hip", "kernels_sgpr.hip", "bbmm_api.hip"]
 # packed fp32 VALU ops are switched off for all device code
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

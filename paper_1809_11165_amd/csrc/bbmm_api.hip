@@ -51,7 +51,12 @@ struct bbmm_ctx {
   int64_t ur_blocks_cap = 0;
   int64_t zd_blocks = 0;
   int64_t khat_panel = 0;                    // column-panel width of the stored K_hat (0 = row-major)
-  int khat_pw = 0;                           // layout of the K_hat currently in memory                     // workgroups per compute unit of the D update (0 = default)
+  int khat_pw = 0;                           // layout of the K_hat currently in memory
+  int64_t khat_sym = 0;                      // 1: keep only the upper triangle of K_hat (packed panels)
+  bool khat_tri = false;                     // the K_hat currently in memory is such a triangle
+  // work list of the product from the triangle
+  int sym_np = 0, sym_wgs[2] = {0, 0};
+  int64_t sym_tune = -1;
   // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
   int plan_np = 0, plan_wgs[2] = {0, 0};
   int64_t plan_tune = -1;
@@ -64,7 +69,7 @@ struct bbmm_ctx {
   int ev_iters = 0;                          // iterations covered by the last timed run
 
   Buf Xa, Xb, Xs, X4, sq, Khat, L, delta, U, R, V, Z0, D4, Vp, partial, gpartial, alpha, beta, resid, st,
-      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[2], nseg[2],
+      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[2], nseg[2], sym_pieces, sym_first, sym_first1, sym_base, sym_tot,
       KUU, Gm, Ginv, Kux, AT, A, qdiag, Tp, T4, sgplan[4], sgnseg[4],
       Ua, Ub, Us, U4, usq, TU, TW, BU, BW, dkops;
   DevState* h_st = nullptr;   // pinned
@@ -225,6 +230,85 @@ int ensure_mat_plans(bbmm_ctx* c) {
   return BBMM_OK;
 }
 
+// Work lists of the product from the upper triangle (launch_mm_sym).  Panel P offers P * W / 16
+// steps above its diagonal block, in which every tile is used twice, and up to W / 16 steps inside
+// it, used once; each kind is cut into runs of equal length for its own launch.  Output panel s
+// then has cnt[s] column-side partial results (one per piece of panel s) followed by one row-side
+// partial result from every panel right of it.
+int ensure_sym_plan(bbmm_ctx* c) {
+  if (c->sym_np == c->np && c->sym_tune == c->mat_wgs) return BBMM_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));   // earlier launches may still read the old lists
+  const int W = BBMM_SYM_PANEL;
+  const int S = (c->np + W - 1) / W;
+  struct Seg {
+    int strip, row_begin, steps;
+  };
+  std::vector<MmPiece> pieces;
+  std::vector<int> cnt((size_t)S, 0), first[2];
+  int wgs[2] = {0, 0};
+  for (int kind = 0; kind < 2; ++kind) {   // 0: above the diagonal blocks, 1: inside them
+    std::vector<Seg> segs;
+    long long total = 0;
+    for (int P = 0; P < S; ++P) {
+      Seg g = kind == 0 ? Seg{P, 0, P * W / 16} : Seg{P, P * W, (std::min(c->np, (P + 1) * W) - P * W) / 16};
+      if (g.steps > 0) segs.push_back(g);
+      total += g.steps;
+    }
+    int nw = (int)std::min<long long>(c->mat_wgs > 0 ? c->mat_wgs : c->num_cus, total);
+    wgs[kind] = nw;
+    first[kind].assign((size_t)nw + 1, (int)pieces.size());
+    size_t si = 0;
+    int off = 0;
+    long long done = 0;
+    for (int w = 0; w < nw; ++w) {
+      first[kind][(size_t)w] = (int)pieces.size();
+      long long target = total * (w + 1) / nw;
+      while (si < segs.size() && done < target) {
+        const Seg& g = segs[si];
+        int take = (int)std::min<long long>(g.steps - off, target - done);
+        pieces.push_back(MmPiece{g.strip, g.row_begin + off * 16, g.row_begin + (off + take) * 16,
+                                 cnt[(size_t)g.strip]++});
+        done += take;
+        off += take;
+        if (off == g.steps) {
+          ++si;
+          off = 0;
+        }
+      }
+    }
+    first[kind][(size_t)nw] = (int)pieces.size();
+    if (si != segs.size() || done != total) return fail(c, BBMM_EINVAL, "internal: triangle work list incomplete");
+  }
+  std::vector<int> tot((size_t)S);
+  int max_slots = 0;
+  for (int s = 0; s < S; ++s) {
+    tot[(size_t)s] = cnt[(size_t)s] + (S - 1 - s);
+    max_slots = std::max(max_slots, tot[(size_t)s]);
+  }
+  // partial-result slots are whole n x 32 blocks; more of them than the other modes ever use
+  int rc = ensure(c, c->Vp, (size_t)max_slots * c->np * BBMM_MAXC * sizeof(double));
+  if (rc) return rc;
+  struct Up {
+    Buf* b;
+    const void* src;
+    size_t bytes;
+  } ups[] = {{&c->sym_pieces, pieces.data(), sizeof(MmPiece) * pieces.size()},
+             {&c->sym_first, first[0].data(), sizeof(int) * first[0].size()},
+             {&c->sym_first1, first[1].data(), sizeof(int) * first[1].size()},
+             {&c->sym_base, cnt.data(), sizeof(int) * cnt.size()},
+             {&c->sym_tot, tot.data(), sizeof(int) * tot.size()}};
+  for (const Up& u : ups) {
+    rc = ensure(c, *u.b, u.bytes);
+    if (rc) return rc;
+    HIPCHK(c, hipMemcpy(u.b->p, u.src, u.bytes, hipMemcpyHostToDevice));
+  }
+  c->sym_wgs[0] = wgs[0];
+  c->sym_wgs[1] = wgs[1];
+  c->sym_np = c->np;
+  c->sym_tune = c->mat_wgs;
+  return BBMM_OK;
+}
+
 // Workgroups for streaming a rows_p x cols_p matrix.  With at least one column strip per compute
 // unit every workgroup takes one whole strip: a piece that ends inside a strip costs a pipeline
 // drain, a partial result to store and one more to add later (measured at 1024 x 500,224: 373 us
@@ -319,13 +403,21 @@ int stage_build_khat(bbmm_ctx* c) {
   // column panels of 1024 (one 16-row step of a workgroup is then 64 KB of contiguous memory:
   // 1.515 -> 1.498 ms per product at n = 50,000); "khat_panel" = 1 keeps plain row-major
   int pw = c->khat_panel == 0 ? 1024 : (c->khat_panel == 1 ? 0 : (int)c->khat_panel);
+  bool tri = c->khat_sym != 0;
   size_t cols_alloc = pw > 0 ? (size_t)((c->np + pw - 1) / pw) * pw : (size_t)c->np;
   size_t bytes = (size_t)c->np * cols_alloc * sizeof(float);
+  if (tri) {
+    // "khat_sym": the upper triangle in packed panels, all panels but the last being full height
+    pw = BBMM_SYM_PANEL;
+    size_t S = (size_t)((c->np + pw - 1) / pw);
+    bytes = ((size_t)pw * pw * (S * (S - 1) / 2) + (size_t)c->np * pw) * sizeof(float);
+  }
   int rc = ensure(c, c->Khat, bytes);
   if (rc) return rc;
   c->khat_pw = pw;
+  c->khat_tri = tri;
   if (launch_build_khat(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb),
-                        ptr<float>(c->sq), c->n, c->np, pw, c->prob.outputscale, c->prob.noise,
+                        ptr<float>(c->sq), c->n, c->np, pw, tri ? 1 : 0, c->prob.outputscale, c->prob.noise,
                         ptr<float>(c->Khat)))
     return fail(c, BBMM_EINVAL, "unsupported input dimension");
   c->khat_built = true;
@@ -427,6 +519,18 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
   } else if (mode == BBMM_MODE_MATERIALISED) {
     if (!c->khat_built) return fail(c, BBMM_EINVAL, "materialised product needs bbmm_build_khat first");
     if (ld != 16 && ld != 32) return fail(c, BBMM_EINVAL, "unsupported block width");
+    if (c->khat_tri) {
+      int rc = ensure_sym_plan(c);
+      if (rc) return rc;
+      if (launch_mm_sym(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
+                        ptr<MmPiece>(c->sym_pieces), ptr<int>(c->sym_first), c->sym_wgs[0],
+                        ptr<int>(c->sym_first1), c->sym_wgs[1], ptr<int>(c->sym_base), ptr<DevState>(c->st)))
+        return fail(c, BBMM_EINVAL, "unsupported block width");
+      *shape = VpShape{0, ptr<int>(c->sym_tot), BBMM_SYM_PANEL};
+      *scaleV = 1.0;
+      *addD = 0.0;
+      return BBMM_OK;
+    }
     int rc = ensure_mat_plans(c);
     if (rc) return rc;
     int v = (ld == 32) ? 1 : 0;
@@ -765,7 +869,7 @@ int bbmm_destroy(bbmm_ctx* c) {
   if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
   if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   Buf* bufs[] = {&c->Xa, &c->Xb, &c->Xs, &c->X4, &c->sq, &c->Khat, &c->L, &c->delta, &c->U, &c->R, &c->V,
-                 &c->Z0, &c->D4, &c->Vp, &c->partial, &c->gpartial, &c->alpha, &c->beta, &c->resid, &c->st, &c->tmpA,
+                 &c->Z0, &c->D4, &c->Vp, &c->partial, &c->gpartial, &c->alpha, &c->beta, &c->resid, &c->st, &c->sym_pieces, &c->sym_first, &c->sym_first1, &c->sym_base, &c->sym_tot, &c->tmpA,
                  &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig, &c->plan[0], &c->plan[1], &c->nseg[0],
                  &c->nseg[1], &c->KUU, &c->Gm, &c->Ginv, &c->Kux, &c->AT, &c->A, &c->qdiag, &c->Tp, &c->T4,
                  &c->sgplan[0], &c->sgplan[1], &c->sgplan[2], &c->sgplan[3], &c->sgnseg[0], &c->sgnseg[1],
@@ -787,7 +891,11 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   if (!strcmp(key, "mat_wgs")) c->mat_wgs = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
   else if (!strcmp(key, "ur_blocks")) c->ur_blocks_cap = value > 0 ? value : 0;
-  else if (!strcmp(key, "khat_panel")) {
+  else if (!strcmp(key, "khat_sym")) {
+    if (value != 0 && value != 1) return fail(c, BBMM_EINVAL, "khat_sym must be 0 or 1");
+    if (c->khat_sym != value) c->khat_built = false;   // the stored matrix has the other layout
+    c->khat_sym = value;
+  } else if (!strcmp(key, "khat_panel")) {
     if (value > 1 && value % 256 != 0) return fail(c, BBMM_EINVAL, "khat_panel must be 1 or a multiple of 256");
     c->khat_panel = value > 0 ? value : 0;
     c->khat_built = false;
@@ -921,7 +1029,7 @@ int bbmm_sgpr_root_rows(bbmm_ctx* c, int64_t row0, int64_t nrows, float* out) {
   if (!out || row0 < 0 || nrows < 0 || row0 + nrows > c->n || nrows * (int64_t)c->m > (int64_t)1 << 31)
     return fail(c, BBMM_EINVAL, "rows out of range");
   if (nrows == 0) return BBMM_OK;
-  launch_copy_block(c->stream, ptr<float>(c->A), (size_t)c->mp, (size_t)c->np, (int)row0, (int)nrows, 0, c->m, out);
+  launch_copy_block(c->stream, ptr<float>(c->A), (size_t)c->mp, (size_t)c->np, 0, (int)row0, (int)nrows, 0, c->m, out);
   HIPCHK(c, hipGetLastError());
   return BBMM_OK;
 }
@@ -935,7 +1043,7 @@ int bbmm_khat_block(bbmm_ctx* c, int64_t row0, int64_t nrows, int64_t col0, int6
     return fail(c, BBMM_EINVAL, "block out of range");
   if (nrows * ncols == 0) return BBMM_OK;
   launch_copy_block(c->stream, ptr<float>(c->Khat), (size_t)(c->khat_pw > 0 ? c->khat_pw : c->np), (size_t)c->np,
-                    (int)row0, (int)nrows, (int)col0, (int)ncols, out);
+                    c->khat_tri ? 1 : 0, (int)row0, (int)nrows, (int)col0, (int)ncols, out);
   HIPCHK(c, hipGetLastError());
   return BBMM_OK;
 }

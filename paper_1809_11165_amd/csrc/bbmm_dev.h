@@ -81,8 +81,9 @@ void launch_unpack_rows(hipStream_t s, const double* src, int ld, int n, int c, 
 void launch_unpack_rows_f64(hipStream_t s, const double* src, int ld, int n, int c, double* dst);
 void launch_pack_rows(hipStream_t s, const float* src, int n, int c, int ld, double* dst);
 void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, int dstcol0, double* dst);
-void launch_copy_block(hipStream_t s, const float* src, size_t pw, size_t rows_p, int row0, int nrows,
-                       int col0, int ncols, float* dst);
+// tri: src is the packed upper triangle of a symmetric matrix (see launch_mm_sym)
+void launch_copy_block(hipStream_t s, const float* src, size_t pw, size_t rows_p, int tri, int row0,
+                       int nrows, int col0, int ncols, float* dst);
 void launch_warm_rhs(hipStream_t s, const float* u_init, int n, int ld, double* D4);
 void launch_warm_apply(hipStream_t s, const float* u_init, const double* V, int n, int ld, double* U,
                        double* R);
@@ -155,10 +156,21 @@ int launch_dk_rect(hipStream_t s, int kernel, int dp, int NT, int ard, const flo
                    int ncols, double* partial, int pstride);
 
 // ---- launchers implemented in kernels_mm.hip ----------------------------------------------
-// panel_width > 0: K_hat is written in column panels of that width (see launch_mm_mat); 0: row-major
+// panel_width > 0: K_hat is written in column panels of that width (see launch_mm_mat); 0: row-major.
+// tri: panel P keeps rows [0, (P+1) * panel_width) only and the panels are packed (see launch_mm_sym).
 int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
-                      const float* sq, int n, int np, int panel_width, double outputscale, double noise,
-                      float* Khat);
+                      const float* sq, int n, int np, int panel_width, int tri, double outputscale,
+                      double noise, float* Khat);
+// ---- launcher implemented in kernels_sym.hip ------------------------------------------------
+// K_hat D from the upper triangle of K_hat stored in packed column panels of BBMM_SYM_PANEL columns
+// (panel P: rows [0, min(np, (P+1) * BBMM_SYM_PANEL)), row-major, at float offset
+// BBMM_SYM_PANEL^2 * P (P+1) / 2).  pieces: flat work list; first_dual / first_single: per workgroup
+// of the launch over the rows above the diagonal blocks / inside them, the range of the list to run
+// (wgs + 1 entries each).  slot_base[s]: first slot of output panel s that takes row-side sums.
+#define BBMM_SYM_PANEL 1024
+int launch_mm_sym(hipStream_t s, const float* Ktri, const double* D4, double* Vp, int np, int ld,
+                  const MmPiece* pieces, const int* first_dual, int wgs_dual, const int* first_single,
+                  int wgs_single, const int* slot_base, const DevState* st);
 // Streams the row-major fp32 matrix M (row stride = column count `np`, a multiple of 256) once and
 // leaves partial sums of M^T D in Vp, D4 indexed by the rows of M.  For the symmetric K_hat that is
 // K_hat D; the SGPR root uses it on both of its layouts.  plan: one entry per workgroup, laid out

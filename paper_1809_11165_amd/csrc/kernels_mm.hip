@@ -62,8 +62,8 @@ template <int KIND, int KK>
 __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa,
                                                      const float* __restrict__ Xb,
                                                      const float* __restrict__ sq, int n, int np,
-                                                     int pw, float outputscale, float noise,
-                                                     float* __restrict__ Khat) {
+                                                     int pw, int tri, float outputscale,
+                                                     float noise, float* __restrict__ Khat) {
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int jb = blockIdx.y * 4 + wave;
   int jc = lane & 15, g = lane >> 4;
@@ -75,6 +75,8 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     int ib = blockIdx.x * 4 + u;
+    // triangular storage: panel P keeps rows [0, (P+1) pw) only
+    if (tri && jb * 16 >= (ib * 16 / pw + 1) * pw) continue;
     float a[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
@@ -90,9 +92,12 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
       if (i >= n || j >= n) v = 0.f;
       out[r] = v;
     }
-    // column panels of width pw, each row-major (pw == np: plain row-major)
+    // column panels of width pw, each row-major (pw == np: plain row-major); the panels of the
+    // triangular storage follow each other without the rows they leave out
     int col = ib * 16 + g * 4;
-    *(f32x4*)(Khat + (size_t)(col / pw) * np * pw + (size_t)j * pw + (size_t)(col % pw)) = out;
+    size_t P = (size_t)(col / pw);
+    size_t poff = tri ? (size_t)pw * pw * (P * (P + 1) / 2) : P * np * pw;
+    *(f32x4*)(Khat + poff + (size_t)j * pw + (size_t)(col % pw)) = out;
   }
 }
 
@@ -590,15 +595,16 @@ __global__ void k_extract_col(const double* __restrict__ src, int ld, int n, int
   }
 
 int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb,
-                      const float* sq, int n, int np, int panel_width, double outputscale, double noise,
-                      float* Khat) {
+                      const float* sq, int n, int np, int panel_width, int tri, double outputscale,
+                      double noise, float* Khat) {
   int pw = panel_width > 0 ? panel_width : np;
+  if (tri && (panel_width <= 0 || panel_width % 64 != 0)) return 1;
   dim3 grid(np / 64, np / 64);
 #define BUILD(K)                                                                                  \
   if (kernel == 0)                                                                                \
-    k_build_khat<0, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, pw, (float)outputscale, (float)noise, Khat); \
+    k_build_khat<0, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, pw, tri, (float)outputscale, (float)noise, Khat); \
   else                                                                                            \
-    k_build_khat<1, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, pw, (float)outputscale, (float)noise, Khat)
+    k_build_khat<1, K><<<grid, 256, 0, s>>>(Xa, Xb, sq, n, np, pw, tri, (float)outputscale, (float)noise, Khat)
   FOR_KK(BUILD)
 #undef BUILD
   return 0;

@@ -1,0 +1,254 @@
+// Product V = K_hat D from ONE triangle of the materialised fp32 K_hat (gfx950 / CDNA4).
+//
+// K_hat is symmetric, so its upper triangle holds everything: stored in column panels of
+// BBMM_SYM_PANEL columns, panel P keeping rows [0, (P+1) * BBMM_SYM_PANEL) (the square block on the
+// diagonal is stored whole), the product streams half the bytes of the full matrix.  A tile T at
+// (rows I, columns J) above the diagonal blocks is then used twice,
+//     out[J] += T^T D[I]      (contraction over the tile's rows, as in k_mm_mat)
+//     out[I] += T   D[J]      (contraction over its columns),
+// both with v_mfma_f64_16x16x4_f64.  The second use needs the tile in the transposed lane layout;
+// every wave passes its 16 x 64 tile through a private LDS area for that (no barrier: a wave's LDS
+// operations execute in order).  The first kind of partial sum stays in registers for a whole piece
+// of work; the second kind is finished after every 16-row step, staged in LDS per wave, and every
+// SYM_GROUP steps the four waves' parts are added in a fixed order and written to a partial-result
+// slot (two barriers per group).  The number of fp64 MFMAs is that of the full-matrix product, which
+// is what bounds this kernel: HBM traffic is halved, arithmetic is not.
+#include "bbmm_dev.h"
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef double f64x4s __attribute__((ext_vector_type(4), aligned(16)));   // as laid out in LDS
+
+namespace {
+
+// A[m = lane%16][k = lane/16], B[k = lane/16][n = lane%16]; register r of the result holds
+// C[m = 4*r + lane/16][n = lane%16].
+__device__ inline f64x4 mfma16d(double a, double b, f64x4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+constexpr int SYM_NC = 4;                    // 64-column groups per wave
+constexpr int SYM_W = BBMM_SYM_PANEL;        // columns per workgroup = panel width of the storage
+constexpr int SYM_TLD = 68;                  // floats per row of a wave's transposition area (64 + 4:
+                                             // the transposed 16-byte reads then hit all banks once)
+constexpr int SYM_GROUP = 8;                 // 16-row steps between two flushes of the row-side sums
+constexpr int SYM_PLD = 18;                  // doubles per staged row (16 + 2: conflict-free stores)
+static_assert(SYM_W == 256 * SYM_NC, "a workgroup of four waves covers one panel");
+
+__device__ __forceinline__ size_t sym_panel_offset(int P) {
+  return (size_t)SYM_W * SYM_W * ((size_t)P * (size_t)(P + 1) / 2);
+}
+
+// One 16-row step that uses every tile twice.  kv / dI hold this step's operands on entry and the
+// next step's on exit (knext / jnext point at the same step again after the last one, so the loads
+// need no branch).  Lane (jc = lane%16, g = lane/16):
+//   kv[nc][r]   rows 4g+r, columns 64 nc + 4 jc .. +3 of the wave's 16 x 256 slab
+//   dI[r]       D[row 4g+r of the step][rhs jc]                       (A operand of the first use)
+//   dJ[nc][s]   D[column 64 nc + 16 s + 4 g + cc of the wave][rhs jc]  (A operand of the second use)
+//   kt[s][cc]   K[row jc of the step][column 64 nc + 16 s + 4 g + cc]  (from LDS, B operand)
+// out2: lane holds out[row jc of the step][rhs 4 i + g], i = 0..3, summed over the wave's columns.
+__device__ __forceinline__ void sym_step_dual(const float* __restrict__ knext, const double* __restrict__ Dq,
+                                              int jnext, int LD, int jc, int g, float* __restrict__ Tw,
+                                              f32x4 (&kv)[SYM_NC][4], f64x4& dI,
+                                              const f64x4 (&dJ)[SYM_NC][4], f64x4 (&acc1)[SYM_NC][4],
+                                              f64x4& out2) {
+  f64x4 dcur = dI;
+  dI = *(const f64x4*)(Dq + ((size_t)(jnext / 4 + g) * LD + (size_t)jc) * 4);
+  f64x4 acc2[4];
+#pragma unroll
+  for (int cc = 0; cc < 4; ++cc) acc2[cc] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int nc = 0; nc < SYM_NC; ++nc) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) *(f32x4*)(Tw + (4 * g + r) * SYM_TLD + 4 * jc) = kv[nc][r];
+    __builtin_amdgcn_wave_barrier();
+    f32x4 kt[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) kt[s] = *(const f32x4*)(Tw + jc * SYM_TLD + 16 * s + 4 * g);
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      double kd[4];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) kd[cc] = (double)kv[nc][r][cc];
+      kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(knext + (size_t)r * SYM_W + nc * 64));
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) acc1[nc][cc] = mfma16d(dcur[r], kd[cc], acc1[nc][cc]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      double kd[4];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) kd[cc] = (double)kt[s][cc];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) acc2[cc] = mfma16d(dJ[nc][s][cc], kd[cc], acc2[cc]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  out2 = (acc2[0] + acc2[1]) + (acc2[2] + acc2[3]);
+}
+
+// One 16-row step inside a diagonal block: the first use only.
+__device__ __forceinline__ void sym_step_single(const float* __restrict__ knext, const double* __restrict__ Dq,
+                                                int jnext, int LD, int jc, int g, f32x4 (&kv)[SYM_NC][4],
+                                                f64x4& dI, f64x4 (&acc1)[SYM_NC][4]) {
+  f64x4 dcur = dI;
+  dI = *(const f64x4*)(Dq + ((size_t)(jnext / 4 + g) * LD + (size_t)jc) * 4);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int nc = 0; nc < SYM_NC; ++nc) {
+      double kd[4];
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) kd[cc] = (double)kv[nc][r][cc];
+      kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(knext + (size_t)r * SYM_W + nc * 64));
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) acc1[nc][cc] = mfma16d(dcur[r], kd[cc], acc1[nc][cc]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Workgroup = 4 waves on the 1024 columns of one panel; it runs pieces first[b] .. first[b+1]-1 of
+// the work list, each a run of rows of one panel.  DUAL: the rows lie above the panel's diagonal
+// block and every tile is used twice; otherwise they lie inside it and only the column-side use is
+// made (the block is stored whole).  The two kinds run as separate launches because the second
+// needs less than half the registers of the first.  Partial results: the column-side sum of a
+// piece goes to slot `piece.slot` of its panel's rows of the output; the row-side sums of panel P
+// for output rows of panel s < P go to slot slot_base[s] + P - s - 1.
+//
+// Dq / Vq point at the 16-column group of the right-hand side / output that this launch handles;
+// LD (16 or 32) is the padded width of both.
+template <bool DUAL>
+__global__ __launch_bounds__(256) void k_mm_sym(const float* __restrict__ Kt, const double* __restrict__ Dq,
+                                                double* __restrict__ Vq, int np, int LD,
+                                                const MmPiece* __restrict__ pieces,
+                                                const int* __restrict__ first,
+                                                const int* __restrict__ slot_base,
+                                                const DevState* __restrict__ st) {
+  if (st->done) return;
+  __shared__ __align__(16) float T[DUAL ? 4 : 1][DUAL ? 16 * SYM_TLD : 4];
+  __shared__ __align__(16) double S[DUAL ? 4 : 1][DUAL ? 16 * SYM_GROUP * SYM_PLD : 2];
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int jc = lane & 15, g = lane >> 4;
+  float* Tw = T[DUAL ? wave : 0];
+  double* Sw = S[DUAL ? wave : 0];
+
+  int pb = first[blockIdx.x], pe = first[blockIdx.x + 1];
+#pragma unroll 1
+  for (int pc = pb; pc < pe; ++pc) {
+    MmPiece P = pieces[pc];
+    int colw = P.strip * SYM_W + wave * (64 * SYM_NC);
+    bool active = colw < np;
+    int nsteps = (P.row_end - P.row_begin) >> 4;
+    if (nsteps <= 0) continue;
+    const float* kp = Kt + sym_panel_offset(P.strip) + (size_t)(P.row_begin + g * 4) * SYM_W +
+                      (size_t)(wave * (64 * SYM_NC) + 4 * jc);
+    f64x4 acc1[SYM_NC][4];
+#pragma unroll
+    for (int nc = 0; nc < SYM_NC; ++nc)
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) acc1[nc][cc] = (f64x4){0.0, 0.0, 0.0, 0.0};
+    f32x4 kv[SYM_NC][4];
+    f64x4 dI = (f64x4){0.0, 0.0, 0.0, 0.0};
+    if (active) {
+      dI = *(const f64x4*)(Dq + ((size_t)(P.row_begin / 4 + g) * LD + (size_t)jc) * 4);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int nc = 0; nc < SYM_NC; ++nc)
+          kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(kp + (size_t)r * SYM_W + nc * 64));
+    }
+    int j0 = P.row_begin;
+    if (!DUAL) {
+      if (active) {
+#pragma unroll 1
+        for (int q = 0; q < nsteps; ++q, j0 += 16) {
+          bool more = q + 1 < nsteps;
+          if (more) kp += (size_t)16 * SYM_W;
+          sym_step_single(kp, Dq, more ? j0 + 16 : j0, LD, jc, g, kv, dI, acc1);
+        }
+      }
+    } else {
+      f64x4 dJ[SYM_NC][4];
+      if (!active) {
+        // a wave whose columns lie beyond the matrix (last, narrower panel) stages nothing in this
+        // piece: its area must read as zero in the flushes (the barrier that ended the previous
+        // flush has passed, so nobody reads the old content any more)
+        for (int i = lane; i < 16 * SYM_GROUP * SYM_PLD; i += 64) Sw[i] = 0.0;
+      }
+      if (active) {
+#pragma unroll
+        for (int nc = 0; nc < SYM_NC; ++nc)
+#pragma unroll
+          for (int s = 0; s < 4; ++s)
+            dJ[nc][s] = *(const f64x4*)(Dq + ((size_t)((colw + nc * 64) / 4 + 4 * s + g) * LD + (size_t)jc) * 4);
+      }
+#pragma unroll 1
+      for (int q0 = 0; q0 < nsteps; q0 += SYM_GROUP) {
+        int ng = min(SYM_GROUP, nsteps - q0);
+        int jg = j0;
+        if (active) {
+#pragma unroll 1
+          for (int q = 0; q < ng; ++q, j0 += 16) {
+            bool more = q0 + q + 1 < nsteps;
+            if (more) kp += (size_t)16 * SYM_W;
+            f64x4 out2;
+            sym_step_dual(kp, Dq, more ? j0 + 16 : j0, LD, jc, g, Tw, kv, dI, dJ, acc1, out2);
+            *(f64x4s*)(Sw + (q * 16 + jc) * SYM_PLD + 4 * g) = out2;
+          }
+        } else {
+          j0 += 16 * ng;
+        }
+        __syncthreads();
+        {
+          int rl = threadIdx.x >> 1, half = threadIdx.x & 1;
+          if (rl < ng * 16) {
+            int row = jg + rl;
+            const double* sp = &S[0][0] + rl * SYM_PLD + 8 * half;
+            f64x4 lo = *(const f64x4s*)sp, hi = *(const f64x4s*)(sp + 4);
+#pragma unroll
+            for (int w = 1; w < 4; ++w) {
+              lo += *(const f64x4s*)(sp + w * (16 * SYM_GROUP * SYM_PLD));
+              hi += *(const f64x4s*)(sp + w * (16 * SYM_GROUP * SYM_PLD) + 4);
+            }
+            int so = row / SYM_W;
+            int slot = slot_base[so] + (P.strip - so - 1);
+            double* dst = Vq + ((size_t)slot * np + (size_t)row) * LD + 8 * half;
+            *(f64x4*)dst = lo;
+            *(f64x4*)(dst + 4) = hi;
+          }
+        }
+        __syncthreads();
+      }
+    }
+    if (active) {
+      double* vout = Vq + (size_t)P.slot * np * LD;
+#pragma unroll
+      for (int nc = 0; nc < SYM_NC; ++nc)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+          *(f64x4*)(vout + (size_t)(colw + nc * 64 + 4 * jc + cc) * LD + g * 4) = acc1[nc][cc];
+    }
+  }
+}
+
+}  // namespace
+
+// K_hat D from the triangular storage: per group of 16 right-hand-side columns one launch over
+// the pieces above the diagonal blocks and one over the pieces inside them.
+int launch_mm_sym(hipStream_t s, const float* Ktri, const double* D4, double* Vp, int np, int ld,
+                  const MmPiece* pieces, const int* first_dual, int wgs_dual, const int* first_single,
+                  int wgs_single, const int* slot_base, const DevState* st) {
+  if (ld != 16 && ld != 32) return 1;
+  for (int nq = 0; nq < ld / 16; ++nq) {
+    if (wgs_dual > 0)
+      k_mm_sym<true><<<wgs_dual, 256, 0, s>>>(Ktri, D4 + 64 * nq, Vp + 16 * nq, np, ld, pieces, first_dual,
+                                              slot_base, st);
+    k_mm_sym<false><<<wgs_single, 256, 0, s>>>(Ktri, D4 + 64 * nq, Vp + 16 * nq, np, ld, pieces, first_single,
+                                               slot_base, st);
+  }
+  return 0;
+}

@@ -225,14 +225,26 @@ __global__ void k_pack_cols_at(const float* __restrict__ src, int n, int c, int 
 }
 
 // dst (nrows x ncols, dense) = src[row0:row0+nrows, col0:col0+ncols]; src is stored in column
-// panels of width pw, each row-major with rows_p rows (pw = row length: plain row-major)
-__global__ void k_copy_block(const float* __restrict__ src, size_t pw, size_t rows_p, int row0,
+// panels of width pw, each row-major with rows_p rows (pw = row length: plain row-major).
+// tri: packed upper triangle of a symmetric matrix, panel P keeping rows [0, (P+1) pw) only; an
+// element below that is read at its mirror position.
+__global__ void k_copy_block(const float* __restrict__ src, size_t pw, size_t rows_p, int tri, int row0,
                              int nrows, int col0, int ncols, float* __restrict__ dst) {
   size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (size_t)nrows * ncols) return;
   int i = (int)(idx / ncols), j = (int)(idx % ncols);
-  size_t col = (size_t)(col0 + j);
-  dst[idx] = src[(col / pw) * rows_p * pw + (size_t)(row0 + i) * pw + col % pw];
+  size_t row = (size_t)(row0 + i), col = (size_t)(col0 + j);
+  if (tri) {
+    if (row >= (col / pw + 1) * pw) {
+      size_t t = row;
+      row = col;
+      col = t;
+    }
+    size_t P = col / pw;
+    dst[idx] = src[pw * pw * (P * (P + 1) / 2) + row * pw + col % pw];
+  } else {
+    dst[idx] = src[(col / pw) * rows_p * pw + row * pw + col % pw];
+  }
 }
 
 // V = scaleV * sum_s Vp[s] + addD * D  (no dot product; used by the stand-alone product call)
@@ -1226,10 +1238,10 @@ void launch_pack_cols_at(hipStream_t s, const float* src, int n, int c, int ld, 
   k_pack_cols_at<<<blocks_for((size_t)n * c, 256), 256, 0, s>>>(src, n, c, ld, dstcol0, dst);
 }
 
-void launch_copy_block(hipStream_t s, const float* src, size_t pw, size_t rows_p, int row0, int nrows,
-                       int col0, int ncols, float* dst) {
-  k_copy_block<<<blocks_for((size_t)nrows * ncols, 256), 256, 0, s>>>(src, pw, rows_p, row0, nrows, col0,
-                                                                      ncols, dst);
+void launch_copy_block(hipStream_t s, const float* src, size_t pw, size_t rows_p, int tri, int row0,
+                       int nrows, int col0, int ncols, float* dst) {
+  k_copy_block<<<blocks_for((size_t)nrows * ncols, 256), 256, 0, s>>>(src, pw, rows_p, tri, row0, nrows,
+                                                                      col0, ncols, dst);
 }
 
 void launch_vreduce(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,

@@ -1,0 +1,169 @@
+"""GPU parity of the reduced-traffic materialised mode ("khat_sym"): only the upper triangle of the
+symmetric K_hat is kept (packed column panels of 1024) and every tile above the diagonal blocks is
+used for both of its contributions to K_hat D.
+
+The stored entries must be the very fp32 values of the full matrix, the product must agree with
+the full-matrix product up to the order of the fp64 sums, and the whole call must meet the same
+bounds against the fp64 oracle as the other modes (1e-3 on solves, log-det and traces).  Sizes
+run from one panel to six, with last panels of 256, 512 and 1024 columns."""
+import numpy as np
+import pytest
+
+from oracle import bbmm_oracle as O
+from paper_1809_11165_amd import inputs
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture()
+def ctx():
+    from paper_1809_11165_amd import binding
+    c = binding.Context(0)
+    yield c
+    c.close()
+
+
+def _problem(w, mode=inputs.MATERIALISED):
+    from paper_1809_11165_amd import binding
+    return binding.problem_from_workload(w, mode)
+
+
+def _host(tn):
+    return tn.detach().cpu().numpy().astype(np.float64)
+
+
+def _colrel(a, b):
+    num = np.linalg.norm(a - b, axis=0)
+    den = np.linalg.norm(b, axis=0)
+    return float(np.max(num / np.where(den > 0, den, 1.0)))
+
+
+def _khat(w):
+    K = O.kernel_matrix(w.kernel, w.X, w.lengthscale, w.outputscale)
+    return K + w.noise * np.eye(w.n)
+
+
+# n -> padded size, panels: 523 -> 768 (one panel of 768), 1000 -> 1024 (1), 2100 -> 2304 (2 + 256),
+# 3500 -> 3584 (3 + 512), 5000 -> 5120 (5), 5300 -> 5376 (5 + 256)
+SIZES = [523, 1000, 2100, 3500, 5000, 5300]
+
+
+@pytest.mark.parametrize("n", SIZES)
+def test_triangle_holds_the_entries_of_the_full_matrix(ctx, n):
+    w = inputs.tiny(n, 5, kernel=inputs.MATERN52, ard=True, t=6, k=7, iters=12, noise=0.2)
+    ctx.bbmm_setup(_problem(w))
+    ctx.bbmm_build_khat()
+    full = ctx.bbmm_khat_block(0, n, 0, n).cpu().numpy()
+    ctx.bbmm_tune("khat_sym", 1)
+    ctx.bbmm_build_khat()
+    tri = ctx.bbmm_khat_block(0, n, 0, n).cpu().numpy()
+    assert np.array_equal(full, full.T)          # the builder itself is symmetric bit for bit
+    assert np.array_equal(tri, full)
+    # a block that straddles a panel boundary and the diagonal
+    r0, c0 = max(0, min(n, 1024) - 40), max(0, min(n, 1024) - 25)
+    nr, ncol = min(70, n - r0), min(60, n - c0)
+    blk = ctx.bbmm_khat_block(r0, nr, c0, ncol).cpu().numpy()
+    assert np.array_equal(blk, full[r0:r0 + nr, c0:c0 + ncol])
+
+
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("c", [11, 17, 32])
+def test_product_from_the_triangle(ctx, n, c):
+    w = inputs.tiny(n, 8, kernel=inputs.RBF, ard=False, t=6, k=7, iters=12, noise=0.2)
+    rng = np.random.default_rng(100 + c)
+    M = torch.from_numpy(rng.standard_normal((n, c)).astype(np.float32)).cuda()
+    ctx.bbmm_setup(_problem(w))
+    ctx.bbmm_build_khat()
+    V_full = _host(ctx.bbmm_kernel_mm(inputs.MATERIALISED, M))
+    Kg = _host(ctx.bbmm_khat_block(0, n, 0, n))
+    ctx.bbmm_tune("khat_sym", 1)
+    ctx.bbmm_build_khat()
+    V = _host(ctx.bbmm_kernel_mm(inputs.MATERIALISED, M))
+    # same fp32 entries, fp64 products and sums in another order; the result is rounded to fp32
+    ref_same_entries = Kg @ _host(M)
+    assert _colrel(V, ref_same_entries) < 2e-7
+    assert _colrel(V, V_full) < 2e-7
+    assert _colrel(V, _khat(w) @ _host(M)) < 1e-4
+
+
+def test_work_decompositions_agree(ctx):
+    # however the rows of the panels are dealt out to workgroups, every output row must receive
+    # each of its partial sums exactly once
+    n = 4200                                      # 4 full panels + 256
+    w = inputs.tiny(n, 6, kernel=inputs.RBF, ard=True, t=6, k=7, iters=12, noise=0.2)
+    rng = np.random.default_rng(7)
+    M = torch.from_numpy(rng.standard_normal((n, 13)).astype(np.float32)).cuda()
+    ctx.bbmm_tune("khat_sym", 1)
+    ctx.bbmm_setup(_problem(w))
+    ctx.bbmm_build_khat()
+    ref = _host(ctx.bbmm_khat_block(0, n, 0, n)) @ _host(M)
+    for wgs in (1, 2, 3, 7, 64, 177, 256, 1000, 100000):
+        ctx.bbmm_tune("mat_wgs", wgs)
+        V = _host(ctx.bbmm_kernel_mm(inputs.MATERIALISED, M))
+        assert _colrel(V, ref) < 2e-7, wgs
+
+
+def test_product_is_deterministic(ctx):
+    n = 3000
+    w = inputs.tiny(n, 4, kernel=inputs.MATERN52, ard=False, t=6, k=7, iters=12, noise=0.2)
+    M = torch.randn(n, 11, device="cuda:0", generator=torch.Generator("cuda:0").manual_seed(1))
+    ctx.bbmm_tune("khat_sym", 1)
+    ctx.bbmm_setup(_problem(w))
+    ctx.bbmm_build_khat()
+    a = ctx.bbmm_kernel_mm(inputs.MATERIALISED, M)
+    b = ctx.bbmm_kernel_mm(inputs.MATERIALISED, M)
+    assert torch.equal(a, b)
+
+
+def _full_parity(ctx, w, tol_solve=1e-3):
+    ctx.bbmm_tune("khat_sym", 1)
+    res = ctx.bbmm_solve_logdet_grad(_problem(w))
+    ref = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
+                           w.k, res.iters_run, forced_pivots=res.pivots)
+    assert res.rank == w.k
+    assert _colrel(_host(res.U), ref.U) < tol_solve
+    assert res.logdet == pytest.approx(ref.logdet, rel=1e-3)
+    assert res.yKinvy == pytest.approx(ref.yKinvy, rel=1e-3)
+    assert res.nlml == pytest.approx(ref.nlml, rel=1e-3)
+    for h in range(len(ref.trace)):
+        assert res.trace[h] == pytest.approx(ref.trace[h], rel=1e-3, abs=1e-3 * np.max(np.abs(ref.trace))), h
+        assert res.quad[h] == pytest.approx(ref.quad[h], rel=1e-3, abs=1e-3 * np.max(np.abs(ref.quad))), h
+        denom = max(abs(ref.trace[h]), abs(ref.quad[h])) / 2
+        assert abs(res.grad_nlml[h] - ref.grad[h]) < 1e-3 * denom + 1e-9, h
+    return res, ref
+
+
+def test_full_path_config1(ctx):
+    res, ref = _full_parity(ctx, inputs.make(1))             # n = 1000: a single panel
+    assert res.iters_run == 20
+
+
+def test_full_path_config2_shape_with_tolerance(ctx):
+    res, ref = _full_parity(ctx, inputs.make(2, n=3000))     # 3 panels, tol 1e-2 or 50 iterations
+    assert res.iters_run <= 50
+
+
+def test_full_path_config3_shape(ctx):
+    w = inputs.make(3, n=2500)                               # Matern-5/2 ARD d = 16, k = 20, p = 50
+    res, ref = _full_parity(ctx, w)
+    ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, with_traces=False)
+    assert res.logdet == pytest.approx(ex.logdet, rel=1e-2)
+    assert _colrel(_host(res.u0)[:, None], ex.u0[:, None]) < 1e-3
+
+
+def test_full_path_wide_block(ctx):
+    # t = 16 probes: 17 columns, i.e. two groups of 16 through the product
+    _full_parity(ctx, inputs.make(4, n=3000, iters=40))
+
+
+def test_same_call_in_both_storages_agrees(ctx):
+    # the two storages differ only in the order of fp64 sums inside the product
+    w = inputs.make(3, n=2300)
+    full = ctx.bbmm_solve_logdet_grad(_problem(w))
+    ctx.bbmm_tune("khat_sym", 1)
+    tri = ctx.bbmm_solve_logdet_grad(_problem(w))
+    assert tri.pivots.tolist() == full.pivots.tolist()
+    assert _colrel(_host(tri.U), _host(full.U)) < 1e-5
+    assert tri.logdet == pytest.approx(full.logdet, rel=1e-8)
+    assert np.allclose(tri.trace, full.trace, rtol=1e-6)
