@@ -8,7 +8,7 @@
 //     out[I] += T   D[J]      (contraction over its columns),
 // both with v_mfma_f64_16x16x4_f64.  The second use needs the tile in the transposed lane layout;
 // every wave passes its 16 x 64 tile through a private LDS area for that (no barrier: a wave's LDS
-// operations execute in order).  The first kind of partial sum stays in registers for a whole piece
+// operations execute in order), one tile ahead of its use.  The first kind of partial sum stays in registers for a whole piece
 // of work; the second kind is finished after every 16-row step, staged in LDS per wave, and every
 // SYM_GROUP steps the four waves' parts are added in a fixed order and written to a partial-result
 // slot (two barriers per group).  The number of fp64 MFMAs is that of the full-matrix product, which
@@ -39,17 +39,37 @@ __device__ __forceinline__ size_t sym_panel_offset(int P) {
   return (size_t)SYM_W * SYM_W * ((size_t)P * (size_t)(P + 1) / 2);
 }
 
-// One 16-row step that uses every tile twice.  kv / dI hold this step's operands on entry and the
-// next step's on exit (knext / jnext point at the same step again after the last one, so the loads
-// need no branch).  Lane (jc = lane%16, g = lane/16):
+// Passes one 16 x 64 tile through the wave's LDS area: written as loaded (rows 4g+r, columns 4jc..),
+// read back transposed for the row-side use.  Split in four parts so that a step can place one part
+// after each group of MFMAs.  On this chip LDS reads and memory loads issue for free beside the
+// fp64 MFMAs, VALU instructions do not (each adds its ~5 cycles), and an LDS *write* holds the matrix
+// pipe up for ~11 cycles per dword (measured: 45 cycles per ds_write_b128 per wave, wherever it is
+// placed), which makes the transposition the largest cost of this kernel after the MFMAs.
+__device__ __forceinline__ void sym_lds_part(int part, float* __restrict__ Tw, int jc, int g,
+                                             const f32x4 (&kvt)[4], f32x4 (&kt)[4]) {
+  if (part < 2) {
+#pragma unroll
+    for (int r = 2 * part; r < 2 * part + 2; ++r) *(f32x4*)(Tw + (4 * g + r) * SYM_TLD + 4 * jc) = kvt[r];
+    if (part == 1) __builtin_amdgcn_wave_barrier();
+  } else {
+#pragma unroll
+    for (int s = 2 * part - 4; s < 2 * part - 2; ++s) kt[s] = *(const f32x4*)(Tw + jc * SYM_TLD + 16 * s + 4 * g);
+    if (part == 3) __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// One 16-row step that uses every tile twice.  kv / dI / kt hold this step's operands on entry and
+// the next step's on exit (knext / jnext point at the same step again after the last one, so the
+// loads need no branch).  Lane (jc = lane%16, g = lane/16):
 //   kv[nc][r]   rows 4g+r, columns 64 nc + 4 jc .. +3 of the wave's 16 x 256 slab
 //   dI[r]       D[row 4g+r of the step][rhs jc]                       (A operand of the first use)
 //   dJ[nc][s]   D[column 64 nc + 16 s + 4 g + cc of the wave][rhs jc]  (A operand of the second use)
-//   kt[s][cc]   K[row jc of the step][column 64 nc + 16 s + 4 g + cc]  (from LDS, B operand)
+//   kt[s][cc]   K[row jc of the step][column 64 nc + 16 s + 4 g + cc]  (from LDS, B operand); on
+//               entry that of tile 0, requested for tile nc+1 during the second use of tile nc
 // out2: lane holds out[row jc of the step][rhs 4 i + g], i = 0..3, summed over the wave's columns.
 __device__ __forceinline__ void sym_step_dual(const float* __restrict__ knext, const double* __restrict__ Dq,
                                               int jnext, int LD, int jc, int g, float* __restrict__ Tw,
-                                              f32x4 (&kv)[SYM_NC][4], f64x4& dI,
+                                              f32x4 (&kv)[SYM_NC][4], f64x4& dI, f32x4 (&kt)[4],
                                               const f64x4 (&dJ)[SYM_NC][4], f64x4 (&acc1)[SYM_NC][4],
                                               f64x4& out2) {
   f64x4 dcur = dI;
@@ -57,16 +77,9 @@ __device__ __forceinline__ void sym_step_dual(const float* __restrict__ knext, c
   f64x4 acc2[4];
 #pragma unroll
   for (int cc = 0; cc < 4; ++cc) acc2[cc] = (f64x4){0.0, 0.0, 0.0, 0.0};
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int nc = 0; nc < SYM_NC; ++nc) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) *(f32x4*)(Tw + (4 * g + r) * SYM_TLD + 4 * jc) = kv[nc][r];
-    __builtin_amdgcn_wave_barrier();
-    f32x4 kt[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) kt[s] = *(const f32x4*)(Tw + jc * SYM_TLD + 16 * s + 4 * g);
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       double kd[4];
@@ -77,6 +90,8 @@ __device__ __forceinline__ void sym_step_dual(const float* __restrict__ knext, c
       for (int cc = 0; cc < 4; ++cc) acc1[nc][cc] = mfma16d(dcur[r], kd[cc], acc1[nc][cc]);
       __builtin_amdgcn_sched_barrier(0);
     }
+    // the tile that follows: nc + 1 of this step, or tile 0 of the next (already reloaded above)
+    f32x4 ktn[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       double kd[4];
@@ -84,8 +99,11 @@ __device__ __forceinline__ void sym_step_dual(const float* __restrict__ knext, c
       for (int cc = 0; cc < 4; ++cc) kd[cc] = (double)kt[s][cc];
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) acc2[cc] = mfma16d(dJ[nc][s][cc], kd[cc], acc2[cc]);
+      sym_lds_part(s, Tw, jc, g, kv[(nc + 1) % SYM_NC], ktn);
       __builtin_amdgcn_sched_barrier(0);
     }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) kt[s] = ktn[s];
   }
   out2 = (acc2[0] + acc2[1]) + (acc2[2] + acc2[3]);
 }
@@ -122,7 +140,7 @@ __device__ __forceinline__ void sym_step_single(const float* __restrict__ knext,
 // Dq / Vq point at the 16-column group of the right-hand side / output that this launch handles;
 // LD (16 or 32) is the padded width of both.
 template <bool DUAL>
-__global__ __launch_bounds__(256) void k_mm_sym(const float* __restrict__ Kt, const double* __restrict__ Dq,
+__global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __restrict__ Kt, const double* __restrict__ Dq,
                                                 double* __restrict__ Vq, int np, int LD,
                                                 const MmPiece* __restrict__ pieces,
                                                 const int* __restrict__ first,
@@ -173,6 +191,11 @@ __global__ __launch_bounds__(256) void k_mm_sym(const float* __restrict__ Kt, co
       }
     } else {
       f64x4 dJ[SYM_NC][4];
+      f32x4 kt[4];
+      if (active) {
+#pragma unroll
+        for (int part = 0; part < 4; ++part) sym_lds_part(part, Tw, jc, g, kv[0], kt);
+      }
       if (!active) {
         // a wave whose columns lie beyond the matrix (last, narrower panel) stages nothing in this
         // piece: its area must read as zero in the flushes (the barrier that ended the previous
@@ -196,7 +219,7 @@ __global__ __launch_bounds__(256) void k_mm_sym(const float* __restrict__ Kt, co
             bool more = q0 + q + 1 < nsteps;
             if (more) kp += (size_t)16 * SYM_W;
             f64x4 out2;
-            sym_step_dual(kp, Dq, more ? j0 + 16 : j0, LD, jc, g, Tw, kv, dI, dJ, acc1, out2);
+            sym_step_dual(kp, Dq, more ? j0 + 16 : j0, LD, jc, g, Tw, kv, dI, kt, dJ, acc1, out2);
             *(f64x4s*)(Sw + (q * 16 + jc) * SYM_PLD + 4 * g) = out2;
           }
         } else {

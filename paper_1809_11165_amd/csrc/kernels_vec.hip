@@ -638,7 +638,14 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShap
         double sv = ((pv[u][0] + pv[u][1]) + (pv[u][2] + pv[u][3])) +
                     ((pv[u][4] + pv[u][5]) + (pv[u][6] + pv[u][7]));
         size_t pidx = (size_t)i * ld + pq;
-        for (int sp = 8; sp < ns[u]; ++sp) sv += Vp[(size_t)sp * slot_stride + pidx];
+        // further slots eight at a time, all requested before any is added (the product from the
+        // triangular storage leaves up to one slot per panel)
+        for (int s0 = 8; s0 < ns[u]; s0 += 8) {
+          double t[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) t[e] = (s0 + e < ns[u]) ? Vp[(size_t)(s0 + e) * slot_stride + pidx] : 0.0;
+          sv += ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+        }
         double v = scaleV * sv + addD * dd[u];
         V[(size_t)i * ld + q] = v;
         acc += dd[u] * v;
