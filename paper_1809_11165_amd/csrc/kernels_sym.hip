@@ -18,6 +18,7 @@
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef double f64x4s __attribute__((ext_vector_type(4), aligned(16)));   // as laid out in LDS
+typedef double f64x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
@@ -64,6 +65,17 @@ __device__ __forceinline__ void sym_dma_tile(const float* gbase, unsigned slot_b
                  :: "v"(voff[i]), "s"(gbase), "s"(slot_bytes + 1024u * i) : "memory", "m0");
 }
 
+// The 16 rows of D of one step (2 KB in the quad-swizzled layout: lane (jc, g) owns the 32 bytes
+// D[rows 4g .. 4g+3][rhs jc]) go the same way, 16 bytes per lane and instruction, and every lane
+// reads its own two pieces back.  (Loading them into registers by an asm statement instead would
+// let the compiler copy those registers before the data has arrived.)
+__device__ __forceinline__ void sym_dma_drows(const double* dbase, unsigned dbuf_bytes, const unsigned (&voffd)[2]) {
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(voffd[h]), "s"(dbase), "s"(dbuf_bytes + 1024u * h) : "memory", "m0");
+}
+
 template <int N>
 __device__ __forceinline__ void sym_wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
@@ -72,25 +84,25 @@ __device__ __forceinline__ void sym_wait_vm() {
 __device__ __forceinline__ void sym_wait_lds() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 // One 16-row step that uses every tile twice.  Slot nc of the wave's ring holds tile nc of this
-// step on entry and of the next step on exit (gnext / jnext point at the same step again after
+// step on entry and of the next step on exit (gnext / dnext point at the same step again after
 // the last one, so the loads need no branch).  Lane (jc = lane%16, g = lane/16):
 //   a1[.][r]    K[row 4g+r of the step][columns 4 jc .. +3 of the tile]        (column-side use)
 //   a2[.][s]    K[row jc of the step][columns 16 s + 4 g .. +3 of the tile]    (row-side use)
-//   dn          D[rows 4g .. 4g+3 of the step][rhs jc]     (A operand of the column-side use)
+//   dn          D[rows 4g .. 4g+3 of the step][rhs jc]     (A operand of the column-side use; the next
+//               step's rows are requested during tile 0 and read from their LDS buffer during tile 3)
 //   dJ[nc][s]   D[column 64 nc + 16 s + 4 g + cc of the wave][rhs jc]    (A operand, row-side)
 // a1 / a2 are double-buffered: while tile nc is multiplied, tile nc+1 (tile 0 of the next step
 // after tile 3) is read from its slot; set 0 holds tile 0 on entry and on exit.
 // Loads per step, in issue order: tile 0 (4), D of the next step (2), tiles 1, 2, 3 (4 each).
 // out2: lane holds out[row jc of the step][rhs 4 i + g], i = 0..3, summed over the wave's columns.
-__device__ __forceinline__ void sym_step_dual(const float* gnext, const double* __restrict__ Dq, int jnext,
-                                              int LD, int jc, int g, const float* __restrict__ ring,
-                                              unsigned ring_bytes, const unsigned (&voff)[4],
+__device__ __forceinline__ void sym_step_dual(const float* gnext, const double* dnext, int jc, int g,
+                                              const float* __restrict__ ring, unsigned ring_bytes,
+                                              const f64x2* __restrict__ dbuf, unsigned dbuf_bytes,
+                                              const unsigned (&voff)[4], const unsigned (&voffd)[2],
                                               const int (&rd1)[4], const int (&rd2)[4],
                                               f32x4 (&a1)[2][4], f32x4 (&a2)[2][4], f64x4& dn,
                                               const f64x4 (&dJ)[SYM_NC][4], f64x4 (&acc1)[SYM_NC][4],
                                               f64x4& out2) {
-  // D of this step was requested during tile 0 of the previous step: 12 loads came after it
-  asm volatile("s_waitcnt vmcnt(12)" : "+v"(dn) : : "memory");
   f64x4 dcur = dn;
   f64x4 acc2[4];
 #pragma unroll
@@ -101,19 +113,19 @@ __device__ __forceinline__ void sym_step_dual(const float* gnext, const double* 
     // the reads of this tile (issued one tile ago) are complete: its slot can take the next step's
     sym_wait_lds();
     sym_dma_tile(gnext + nc * 64, ring_bytes + 4096u * nc, voff);
-    if (nc == 0) {
-      const double* dp = Dq + ((size_t)(jnext / 4 + g) * LD + (size_t)jc) * 4;
-      asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
-                   : "=&v"(*(f32x4*)&dn), "=&v"(*((f32x4*)&dn + 1)) : "v"(dp) : "memory");
-    }
+    if (nc == 0) sym_dma_drows(dnext, dbuf_bytes, voffd);   // read into dn (below) during tile 3
     // the tile that follows was requested 14 loads ago (one step back, or during tile 0 for the
-    // next step's tile 0)
-    sym_wait_vm<14>();
+    // next step's tile 0); the D rows came right after that tile 0, 12 loads ago
+    if (nc == SYM_NC - 1) sym_wait_vm<12>(); else sym_wait_vm<14>();
     const float* slot = ring + 1024 * nn;
 #pragma unroll
     for (int r = 0; r < 4; ++r) a1[nxt][r] = *(const f32x4*)(slot + rd1[r]);
 #pragma unroll
     for (int s = 0; s < 4; ++s) a2[nxt][s] = *(const f32x4*)(slot + rd2[s]);
+    if (nc == SYM_NC - 1) {
+      f64x2 lo = dbuf[0], hi = dbuf[64];      // the lane's own two pieces
+      dn = (f64x4){lo[0], lo[1], hi[0], hi[1]};
+    }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -223,15 +235,20 @@ __global__ __launch_bounds__(256, 1) void k_mm_sym_dual(const float* __restrict_
                                                          const DevState* __restrict__ st) {
   if (st->done) return;
   __shared__ __align__(16) float ringmem[4][SYM_NC * 1024];
+  __shared__ __align__(16) double dmem[4][256];
   __shared__ __align__(16) double S[4][16 * SYM_GROUP * SYM_PLD];
   int lane = threadIdx.x & 63;
   int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   int jc = lane & 15, g = lane >> 4;
   const float* ring = ringmem[wave];
   unsigned ring_bytes = (unsigned)(size_t)(lds_float*)ringmem[wave];
+  const f64x2* dbuf = (const f64x2*)dmem[wave] + lane;
+  unsigned dbuf_bytes = (unsigned)(size_t)(lds_float*)(float*)dmem[wave];
   double* Sw = S[wave];
-  unsigned voff[4];
+  unsigned voff[4], voffd[2];
   int rd1[4], rd2[4];
+  voffd[0] = (unsigned)((g * LD + jc) * 4) * 8u;
+  voffd[1] = voffd[0] + 16u;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     int rho = 4 * i + g;                                   // lane's row in load instruction i
@@ -267,11 +284,7 @@ __global__ __launch_bounds__(256, 1) void k_mm_sym_dual(const float* __restrict_
     } else {
       // the first step's tiles and D rows, in the issue order of a step
       sym_dma_tile(gp, ring_bytes, voff);
-      {
-        const double* dp = Dq + ((size_t)(P.row_begin / 4 + g) * LD + (size_t)jc) * 4;
-        asm volatile("global_load_dwordx4 %0, %2, off\n\tglobal_load_dwordx4 %1, %2, off offset:16"
-                     : "=&v"(*(f32x4*)&dn), "=&v"(*((f32x4*)&dn + 1)) : "v"(dp) : "memory");
-      }
+      sym_dma_drows(Dq + (size_t)(P.row_begin / 4) * LD * 4, dbuf_bytes, voffd);
 #pragma unroll
       for (int nc = 1; nc < SYM_NC; ++nc) sym_dma_tile(gp + nc * 64, ring_bytes + 4096u * nc, voff);
 #pragma unroll
@@ -291,6 +304,8 @@ __global__ __launch_bounds__(256, 1) void k_mm_sym_dual(const float* __restrict_
       for (int r = 0; r < 4; ++r) a1[0][r] = *(const f32x4*)(ring + rd1[r]);
 #pragma unroll
       for (int s = 0; s < 4; ++s) a2[0][s] = *(const f32x4*)(ring + rd2[s]);
+      f64x2 lo = dbuf[0], hi = dbuf[64];
+      dn = (f64x4){lo[0], lo[1], hi[0], hi[1]};
     }
     int j0 = P.row_begin;
 #pragma unroll 1
@@ -305,8 +320,8 @@ __global__ __launch_bounds__(256, 1) void k_mm_sym_dual(const float* __restrict_
           bool more = q0 + q + 1 < nsteps;
           if (more) gp += (size_t)16 * SYM_W;
           f64x4 out2;
-          sym_step_dual(gp, Dq, more ? j0 + 16 : j0, LD, jc, g, ring, ring_bytes, voff, rd1, rd2, a1, a2, dn,
-                        dJ, acc1, out2);
+          sym_step_dual(gp, Dq + (size_t)((more ? j0 + 16 : j0) / 4) * LD * 4, jc, g, ring, ring_bytes, dbuf,
+                        dbuf_bytes, voff, voffd, rd1, rd2, a1, a2, dn, dJ, acc1, out2);
           *(f64x4s*)(Sw + (q * 16 + jc) * SYM_PLD + 4 * g) = out2;
         }
       } else {

@@ -172,6 +172,24 @@ def test_config3_full_size(ctx, mode):
     _run_case(ctx, "cfg3_n50000", mode)
 
 
+def test_config3_full_size_triangle_storage(ctx):
+    # the reduced-traffic materialised mode: upper triangle of K_hat only, every tile used twice
+    ctx.bbmm_tune("khat_sym", 1)
+    try:
+        _run_case(ctx, "cfg3_n50000", inputs.MATERIALISED)
+    finally:
+        ctx.bbmm_tune("khat_sym", 0)
+
+
+def test_config2_full_size_triangle_storage(ctx):
+    ctx.bbmm_tune("khat_sym", 1)
+    try:
+        _run_case(ctx, "cfg2_n10000_cap128", inputs.MATERIALISED)
+        _run_case(ctx, "cfg2_n10000", inputs.MATERIALISED)
+    finally:
+        ctx.bbmm_tune("khat_sym", 0)
+
+
 def test_config4_subsample_20000(ctx):
     _run_case(ctx, "cfg4_sub_n20000", inputs.ONTHEFLY)
 
@@ -366,6 +384,14 @@ def _audit(ctx, w, mode, n_rows=256):
 
 def test_config3_full_size_audit_materialised(ctx):
     _audit(ctx, inputs.make(3), inputs.MATERIALISED)
+
+
+def test_config3_full_size_audit_triangle_storage(ctx):
+    ctx.bbmm_tune("khat_sym", 1)
+    try:
+        _audit(ctx, inputs.make(3), inputs.MATERIALISED)
+    finally:
+        ctx.bbmm_tune("khat_sym", 0)
 
 
 def test_config3_full_size_audit_onthefly(ctx):
