@@ -5,9 +5,12 @@ One "step" is one full bbmm_solve_logdet_grad call (preconditioner, probes, mBCG
 log-det, derivative traces) on the n = 50,000, d = 16, t = 10 Matern-5/2 ARD workload
 (rank-20 preconditioner, 50 mBCG iterations), inputs resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode mat|otf|sgpr] [--n N] [--no-cpu]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode sym|mat|otf|sgpr] [--n N] [--no-cpu]
 
---mode sgpr measures the widened path instead (config 5: subset-of-regressors covariance,
+The default mode keeps the fp32 K_hat materialised as its upper triangle (half the HBM bytes per
+product, every tile used for both of its contributions; the product is then bound by the fp64
+matrix rate).  --mode mat keeps the whole matrix (HBM-bound product), --mode otf rebuilds the tiles
+from X in every product.  --mode sgpr measures the widened path instead (config 5: subset-of-regressors covariance,
 n = 500,000, m = 1024 inducing inputs, d = 8, t = 10, rank-10 preconditioner, 50 iterations);
 the default line is the exact-GP workload above.
 """
@@ -33,7 +36,9 @@ MEASURED_TRAFFIC_MAT_N50000 = 10.425e9
 # HBM bytes per SGPR product (both k_mm_mat launches) at n = 500000, m = 1024, measured the same way
 # (profiles/k_mm_mat_cfg5_n500000_sgpr_hbm_counters.txt); only valid for that workload.
 MEASURED_TRAFFIC_SGPR_N500000_M1024 = 4.261e9
-MEASURED_TRAFFIC_SYM_N50000 = None      # not measured yet
+# HBM bytes per product from the upper triangle at n = 50000 (both launches), measured the same way
+# (profiles/k_mm_sym_cfg3_n50000_counters.txt); only valid for that workload.
+MEASURED_TRAFFIC_SYM_N50000 = 5.558e9
 
 
 def cpu_baseline(n_sample: int, n_full: int):
@@ -85,7 +90,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--mode", choices=["mat", "sym", "otf", "sgpr"], default="mat")
+    ap.add_argument("--mode", choices=["sym", "mat", "otf", "sgpr"], default="sym")
     ap.add_argument("--n", type=int, default=None, help="points (default 50000; 500000 for --mode sgpr)")
     ap.add_argument("--m", type=int, default=1024, help="inducing inputs (--mode sgpr)")
     ap.add_argument("--cpu-sample", type=int, default=10000)
@@ -154,16 +159,21 @@ def main():
         metric = "mBCG solve+logdet+grad ms at n=500k,m=1024,t=10 (SGPR)"
         mode_name = "fp32 root A = K_XU G^-T in both layouts"
     elif args.mode == "sym":
-        # the triangle is read once (2 n^2 + 4 n W bytes, W = 1024: the diagonal blocks are whole), but
-        # every 16 x 16 tile still takes its 2 x 4 fp64 MFMAs per 16 columns of the block: the
-        # product is bound by the fp64 matrix rate, 2 n^2 * 16 flop per launch
-        alg_flops = 2.0 * n * n * 16 * ((c + 15) // 16)
+        # The triangle is read once (2 n^2 + 4 n W bytes, W = 1024: the diagonal blocks are whole),
+        # which no longer binds; every stored 16 x 16 tile still takes its 2 x 4 fp64 MFMAs per 16
+        # columns of the block, so the product is bound by the fp64 matrix rate.  Algorithmic flops of
+        # one product: 2 c per pair of points (c = t + 1 columns really used); the MFMAs execute
+        # 2 * 16 per pair (c padded to the 16-wide instruction), reported beside it.
+        alg_flops = 2.0 * c * n * n
         achieved = alg_flops / (mm_ms * 1e-3) / 1e12
+        padded = 2.0 * 16 * ((c + 15) // 16) * n * n / (mm_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F64_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_F64_PEAK_TFLOPS,
                     "traffic": MEASURED_TRAFFIC_SYM_N50000 if n == 50000 else None,
                     "kernel": "k_mm_sym<true> (+ k_mm_sym<false> on the diagonal blocks)",
                     "avg_launch_ms": mm_ms, "launches": mm_launches,
+                    "executed_TFLOPs_with_16_wide_padding": padded,
+                    "executed_frac": padded / MFMA_F64_PEAK_TFLOPS,
                     "effective_GBps_of_full_matrix": (4.0 * n * n + 8.0 * n * c) / (mm_ms * 1e-3) / 1e9}
         mode_name = "materialised fp32 K_hat, upper triangle only (khat_sym)"
     elif mode == inputs.MATERIALISED:

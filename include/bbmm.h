@@ -173,6 +173,13 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *   "khat_panel" layout of the materialised K_hat: column panels of that width (a multiple of
  *                256; default 1024), each panel row-major; 1 = plain row-major.  Takes effect at
  *                the next bbmm_build_khat
+ *   "khat_sym"   1: BBMM_MODE_MATERIALISED keeps only the upper triangle of the symmetric K_hat
+ *                (packed column panels of 1024: about half the memory and half the HBM bytes per
+ *                product) and uses every tile for both of its contributions to K_hat M; the
+ *                entries are the same fp32 values, the fp64 sums are formed in another order.
+ *                0 (default): the whole matrix.  Takes effect at the next bbmm_build_khat (a
+ *                change marks the stored matrix as not built); "khat_panel" is ignored while set;
+ *                "mat_wgs" then counts the workgroups of each of its two launches
  *   "zd_blocks"  workgroups per compute unit of the direction update (default 16, at most 64)
  *   "sgpr_wgs1", "sgpr_wgs2"  workgroups of the two streaming products of an SGPR product
  *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build
