@@ -522,7 +522,7 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     if (c->khat_tri) {
       int rc = ensure_sym_plan(c);
       if (rc) return rc;
-      if (launch_mm_sym(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
+      if (launch_mm_sym(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld, cc,
                         ptr<MmPiece>(c->sym_pieces), ptr<int>(c->sym_first), c->sym_wgs[0],
                         ptr<int>(c->sym_first1), c->sym_wgs[1], ptr<int>(c->sym_base), ptr<DevState>(c->st)))
         return fail(c, BBMM_EINVAL, "unsupported block width");

@@ -168,7 +168,9 @@ int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const 
 // of the launch over the rows above the diagonal blocks / inside them, the range of the list to run
 // (wgs + 1 entries each).  slot_base[s]: first slot of output panel s that takes row-side sums.
 #define BBMM_SYM_PANEL 1024
-int launch_mm_sym(hipStream_t s, const float* Ktri, const double* D4, double* Vp, int np, int ld,
+// cols: columns of the block really in use (a 16-column group with at most 12 of them takes a
+// narrower MFMA on the column-side use).
+int launch_mm_sym(hipStream_t s, const float* Ktri, const double* D4, double* Vp, int np, int ld, int cols,
                   const MmPiece* pieces, const int* first_dual, int wgs_dual, const int* first_single,
                   int wgs_single, const int* slot_base, const DevState* st);
 // Streams the row-major fp32 matrix M (row stride = column count `np`, a multiple of 256) once and

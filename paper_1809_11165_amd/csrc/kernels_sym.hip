@@ -27,6 +27,46 @@ __device__ inline f64x4 mfma16d(double a, double b, f64x4 c) {
   return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
+// The fp64 4x4x4 MFMA (16 cycles, the same flop rate) computes the four diagonal 4 x 4 blocks of what
+// the 16x16x4 instruction would: C[i = lane/16][j = lane%4] of block p = (lane/4)%4
+//   += sum_k A(lane 16 k + 4 p + i) * B(lane 16 k + 4 p + j)      (one register each; measured).
+// With the B operand as above (k <-> rows 4k+r, lane%16 <-> columns 4 (lane%16) + cc) and the A
+// operand D[row 4k+r][rhs 4q + lane%4], three of them (q = 0, 1, 2) give right-hand-side columns
+// 0..11 of the same 64 matrix columns in 48 cycles instead of 64: lane (jc, g) then holds
+// out[column 4jc+cc][rhs 4q+g], which is element q of the 16x16 accumulator's four.
+__device__ inline double mfma4d(double a, double b, double c) {
+  return __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, c, 0, 0, 0);
+}
+
+// Column-side use of one row quad of a tile: 16-wide (all 16 right-hand-side columns of the group)
+// or NARROW (columns 0..11 only, accumulated in accn[cc][q], q = rhs / 4).
+// dcur[q][r]: 16-wide: q = 0 only, D[row 4g+r][rhs jc]; NARROW: D[row 4g+r][rhs 4q + jc%4].
+template <bool NARROW>
+__device__ __forceinline__ void sym_col_mma(const f64x4 (&dcur)[3], int r, const double (&kd)[4], f64x4 (&acc)[4],
+                                            double (&accn)[4][3]) {
+#pragma unroll
+  for (int cc = 0; cc < 4; ++cc) {
+    if (NARROW) {
+#pragma unroll
+      for (int q = 0; q < 3; ++q) accn[cc][q] = mfma4d(dcur[q][r], kd[cc], accn[cc][q]);
+    } else {
+      acc[cc] = mfma16d(dcur[0][r], kd[cc], acc[cc]);
+    }
+  }
+}
+
+template <bool NARROW>
+__device__ __forceinline__ void sym_load_drows(const double* __restrict__ Dq, int j, int LD, int jc, int g,
+                                               f64x4 (&d)[3]) {
+  if (NARROW) {
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+      d[q] = *(const f64x4*)(Dq + ((size_t)(j / 4 + g) * LD + (size_t)(4 * q + (jc & 3))) * 4);
+  } else {
+    d[0] = *(const f64x4*)(Dq + ((size_t)(j / 4 + g) * LD + (size_t)jc) * 4);
+  }
+}
+
 constexpr int SYM_NC = 4;                    // 64-column groups per wave
 constexpr int SYM_W = BBMM_SYM_PANEL;        // columns per workgroup = panel width of the storage
 constexpr int SYM_TLD = 68;                  // floats per row of a wave's transposition area (64 + 4:
@@ -67,13 +107,16 @@ __device__ __forceinline__ void sym_lds_part(int part, float* __restrict__ Tw, i
 //   kt[s][cc]   K[row jc of the step][column 64 nc + 16 s + 4 g + cc]  (from LDS, B operand); on
 //               entry that of tile 0, requested for tile nc+1 during the second use of tile nc
 // out2: lane holds out[row jc of the step][rhs 4 i + g], i = 0..3, summed over the wave's columns.
+template <bool NARROW>
 __device__ __forceinline__ void sym_step_dual(const float* __restrict__ knext, const double* __restrict__ Dq,
                                               int jnext, int LD, int jc, int g, float* __restrict__ Tw,
-                                              f32x4 (&kv)[SYM_NC][4], f64x4& dI, f32x4 (&kt)[4],
+                                              f32x4 (&kv)[SYM_NC][4], f64x4 (&dI)[3], f32x4 (&kt)[4],
                                               const f64x4 (&dJ)[SYM_NC][4], f64x4 (&acc1)[SYM_NC][4],
-                                              f64x4& out2) {
-  f64x4 dcur = dI;
-  dI = *(const f64x4*)(Dq + ((size_t)(jnext / 4 + g) * LD + (size_t)jc) * 4);
+                                              double (&acc1n)[SYM_NC][4][3], f64x4& out2) {
+  f64x4 dcur[3];
+#pragma unroll
+  for (int q = 0; q < (NARROW ? 3 : 1); ++q) dcur[q] = dI[q];
+  sym_load_drows<NARROW>(Dq, jnext, LD, jc, g, dI);
   f64x4 acc2[4];
 #pragma unroll
   for (int cc = 0; cc < 4; ++cc) acc2[cc] = (f64x4){0.0, 0.0, 0.0, 0.0};
@@ -86,8 +129,7 @@ __device__ __forceinline__ void sym_step_dual(const float* __restrict__ knext, c
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) kd[cc] = (double)kv[nc][r][cc];
       kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(knext + (size_t)r * SYM_W + nc * 64));
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) acc1[nc][cc] = mfma16d(dcur[r], kd[cc], acc1[nc][cc]);
+      sym_col_mma<NARROW>(dcur, r, kd, acc1[nc], acc1n[nc]);
       __builtin_amdgcn_sched_barrier(0);
     }
     // the tile that follows: nc + 1 of this step, or tile 0 of the next (already reloaded above)
@@ -109,11 +151,15 @@ __device__ __forceinline__ void sym_step_dual(const float* __restrict__ knext, c
 }
 
 // One 16-row step inside a diagonal block: the first use only.
+template <bool NARROW>
 __device__ __forceinline__ void sym_step_single(const float* __restrict__ knext, const double* __restrict__ Dq,
                                                 int jnext, int LD, int jc, int g, f32x4 (&kv)[SYM_NC][4],
-                                                f64x4& dI, f64x4 (&acc1)[SYM_NC][4]) {
-  f64x4 dcur = dI;
-  dI = *(const f64x4*)(Dq + ((size_t)(jnext / 4 + g) * LD + (size_t)jc) * 4);
+                                                f64x4 (&dI)[3], f64x4 (&acc1)[SYM_NC][4],
+                                                double (&acc1n)[SYM_NC][4][3]) {
+  f64x4 dcur[3];
+#pragma unroll
+  for (int q = 0; q < (NARROW ? 3 : 1); ++q) dcur[q] = dI[q];
+  sym_load_drows<NARROW>(Dq, jnext, LD, jc, g, dI);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int r = 0; r < 4; ++r)
@@ -123,8 +169,7 @@ __device__ __forceinline__ void sym_step_single(const float* __restrict__ knext,
 #pragma unroll
       for (int cc = 0; cc < 4; ++cc) kd[cc] = (double)kv[nc][r][cc];
       kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(knext + (size_t)r * SYM_W + nc * 64));
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) acc1[nc][cc] = mfma16d(dcur[r], kd[cc], acc1[nc][cc]);
+      sym_col_mma<NARROW>(dcur, r, kd, acc1[nc], acc1n[nc]);
       __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -139,7 +184,7 @@ __device__ __forceinline__ void sym_step_single(const float* __restrict__ knext,
 //
 // Dq / Vq point at the 16-column group of the right-hand side / output that this launch handles;
 // LD (16 or 32) is the padded width of both.
-template <bool DUAL>
+template <bool DUAL, bool NARROW>
 __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __restrict__ Kt, const double* __restrict__ Dq,
                                                 double* __restrict__ Vq, int np, int LD,
                                                 const MmPiece* __restrict__ pieces,
@@ -165,14 +210,21 @@ __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __res
     const float* kp = Kt + sym_panel_offset(P.strip) + (size_t)(P.row_begin + g * 4) * SYM_W +
                       (size_t)(wave * (64 * SYM_NC) + 4 * jc);
     f64x4 acc1[SYM_NC][4];
+    double acc1n[SYM_NC][4][3];
 #pragma unroll
     for (int nc = 0; nc < SYM_NC; ++nc)
 #pragma unroll
-      for (int cc = 0; cc < 4; ++cc) acc1[nc][cc] = (f64x4){0.0, 0.0, 0.0, 0.0};
+      for (int cc = 0; cc < 4; ++cc) {
+        acc1[nc][cc] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int q = 0; q < 3; ++q) acc1n[nc][cc][q] = 0.0;
+      }
     f32x4 kv[SYM_NC][4];
-    f64x4 dI = (f64x4){0.0, 0.0, 0.0, 0.0};
+    f64x4 dI[3];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) dI[q] = (f64x4){0.0, 0.0, 0.0, 0.0};
     if (active) {
-      dI = *(const f64x4*)(Dq + ((size_t)(P.row_begin / 4 + g) * LD + (size_t)jc) * 4);
+      sym_load_drows<NARROW>(Dq, P.row_begin, LD, jc, g, dI);
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -186,7 +238,7 @@ __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __res
         for (int q = 0; q < nsteps; ++q, j0 += 16) {
           bool more = q + 1 < nsteps;
           if (more) kp += (size_t)16 * SYM_W;
-          sym_step_single(kp, Dq, more ? j0 + 16 : j0, LD, jc, g, kv, dI, acc1);
+          sym_step_single<NARROW>(kp, Dq, more ? j0 + 16 : j0, LD, jc, g, kv, dI, acc1, acc1n);
         }
       }
     } else {
@@ -219,7 +271,7 @@ __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __res
             bool more = q0 + q + 1 < nsteps;
             if (more) kp += (size_t)16 * SYM_W;
             f64x4 out2;
-            sym_step_dual(kp, Dq, more ? j0 + 16 : j0, LD, jc, g, Tw, kv, dI, kt, dJ, acc1, out2);
+            sym_step_dual<NARROW>(kp, Dq, more ? j0 + 16 : j0, LD, jc, g, Tw, kv, dI, kt, dJ, acc1, acc1n, out2);
             *(f64x4s*)(Sw + (q * 16 + jc) * SYM_PLD + 4 * g) = out2;
           }
         } else {
@@ -253,7 +305,8 @@ __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __res
       for (int nc = 0; nc < SYM_NC; ++nc)
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc)
-          *(f64x4*)(vout + (size_t)(colw + nc * 64 + 4 * jc + cc) * LD + g * 4) = acc1[nc][cc];
+          *(f64x4*)(vout + (size_t)(colw + nc * 64 + 4 * jc + cc) * LD + g * 4) =
+              NARROW ? (f64x4){acc1n[nc][cc][0], acc1n[nc][cc][1], acc1n[nc][cc][2], 0.0} : acc1[nc][cc];
     }
   }
 }
@@ -262,16 +315,25 @@ __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __res
 
 // K_hat D from the triangular storage: per group of 16 right-hand-side columns one launch over
 // the pieces above the diagonal blocks and one over the pieces inside them.
-int launch_mm_sym(hipStream_t s, const float* Ktri, const double* D4, double* Vp, int np, int ld,
+int launch_mm_sym(hipStream_t s, const float* Ktri, const double* D4, double* Vp, int np, int ld, int cols,
                   const MmPiece* pieces, const int* first_dual, int wgs_dual, const int* first_single,
                   int wgs_single, const int* slot_base, const DevState* st) {
   if (ld != 16 && ld != 32) return 1;
   for (int nq = 0; nq < ld / 16; ++nq) {
-    if (wgs_dual > 0)
-      k_mm_sym<true><<<wgs_dual, 256, 0, s>>>(Ktri, D4 + 64 * nq, Vp + 16 * nq, np, ld, pieces, first_dual,
-                                              slot_base, st);
-    k_mm_sym<false><<<wgs_single, 256, 0, s>>>(Ktri, D4 + 64 * nq, Vp + 16 * nq, np, ld, pieces, first_single,
-                                               slot_base, st);
+    // a group of which at most 12 columns are in use takes the narrower column-side instruction
+    bool narrow = cols - 16 * nq <= 12;
+    const double* Dq = D4 + 64 * nq;
+    double* Vq = Vp + 16 * nq;
+    if (wgs_dual > 0) {
+      if (narrow)
+        k_mm_sym<true, true><<<wgs_dual, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_dual, slot_base, st);
+      else
+        k_mm_sym<true, false><<<wgs_dual, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_dual, slot_base, st);
+    }
+    if (narrow)
+      k_mm_sym<false, true><<<wgs_single, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_single, slot_base, st);
+    else
+      k_mm_sym<false, false><<<wgs_single, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_single, slot_base, st);
   }
   return 0;
 }
