@@ -38,7 +38,7 @@ MEASURED_TRAFFIC_MAT_N50000 = 10.425e9
 MEASURED_TRAFFIC_SGPR_N500000_M1024 = 4.261e9
 # HBM bytes per product from the upper triangle at n = 50000 (both launches), measured the same way
 # (profiles/k_mm_sym_cfg3_n50000_counters.txt); only valid for that workload.
-MEASURED_TRAFFIC_SYM_N50000 = 5.558e9
+MEASURED_TRAFFIC_SYM_N50000 = 5.527e9
 
 
 def cpu_baseline(n_sample: int, n_full: int):
@@ -160,20 +160,22 @@ def main():
         mode_name = "fp32 root A = K_XU G^-T in both layouts"
     elif args.mode == "sym":
         # The triangle is read once (2 n^2 + 4 n W bytes, W = 1024: the diagonal blocks are whole),
-        # which no longer binds; every stored 16 x 16 tile still takes its 2 x 4 fp64 MFMAs per 16
-        # columns of the block, so the product is bound by the fp64 matrix rate.  Algorithmic flops of
-        # one product: 2 c per pair of points (c = t + 1 columns really used); the MFMAs execute
-        # 2 * 16 per pair (c padded to the 16-wide instruction), reported beside it.
+        # which no longer binds; every stored 16 x 16 tile still takes its fp64 MFMAs for both of its
+        # uses, so the product is bound by the fp64 matrix rate.  Algorithmic flops of one product:
+        # 2 c per pair of points (c = t + 1 columns really used).  Executed: per pair 16 columns on
+        # the row-side use and 12 or 16 on the column-side use (12 when at most 12 columns of a
+        # 16-column group are in use), each on half the pairs; reported beside it.
         alg_flops = 2.0 * c * n * n
         achieved = alg_flops / (mm_ms * 1e-3) / 1e12
-        padded = 2.0 * 16 * ((c + 15) // 16) * n * n / (mm_ms * 1e-3) / 1e12
+        wide = sum(16 + (12 if min(16, c - 16 * q) <= 12 else 16) for q in range((c + 15) // 16))
+        executed = wide * n * n / (mm_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F64_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_F64_PEAK_TFLOPS,
                     "traffic": MEASURED_TRAFFIC_SYM_N50000 if n == 50000 else None,
                     "kernel": "k_mm_sym<true> (+ k_mm_sym<false> on the diagonal blocks)",
                     "avg_launch_ms": mm_ms, "launches": mm_launches,
-                    "executed_TFLOPs_with_16_wide_padding": padded,
-                    "executed_frac": padded / MFMA_F64_PEAK_TFLOPS,
+                    "executed_TFLOPs_with_padding": executed,
+                    "executed_frac": executed / MFMA_F64_PEAK_TFLOPS,
                     "effective_GBps_of_full_matrix": (4.0 * n * n + 8.0 * n * c) / (mm_ms * 1e-3) / 1e9}
         mode_name = "materialised fp32 K_hat, upper triangle only (khat_sym)"
     elif mode == inputs.MATERIALISED:
