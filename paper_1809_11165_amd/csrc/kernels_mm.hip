@@ -34,6 +34,16 @@ __device__ inline f64x4 mfma16d(double a, double b, f64x4 c) {
   return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
 }
 
+// fp64 MFMA 4x4x4 (16 cycles, the same flop rate as the 16x16x4 one): the four diagonal 4 x 4 blocks
+// of what that instruction would compute, C[i = lane/16][j = lane%4] of block p = (lane/4)%4
+//   += sum_k A(lane 16 k + 4 p + i) * B(lane 16 k + 4 p + j)      (one register each; measured).
+// With the B operand of the product unchanged and D[row][rhs 4q + lane%4] as A operand, three of
+// them (q = 0, 1, 2) give right-hand-side columns 0..11 in 48 cycles instead of 64; the lane then
+// holds out[column lane%16][rhs 4q + lane/16], i.e. element q of the 16x16 accumulator's four.
+__device__ inline double mfma4d(double a, double b, double c) {
+  return __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, c, 0, 0, 0);
+}
+
 // r2 tile: |xs_i - xs_j|^2 for a 16 x 16 tile, clamped at 0.
 template <int KK>
 __device__ inline f32x4 tile_r2(const float (&a)[KK], const float (&b)[KK], f32x4 sqi, float sqj) {
@@ -224,7 +234,9 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
 // way against a whole second MFMA group (4 x 64 cycles) of which 15/16 would be padding.  A lane
 // then holds the sum over its own 4 rows of each tile; the four lane groups are added at the end
 // and stored where the MFMA path would have put them.
-template <int KIND, int KK, int NQ, int NJ, int NX>
+//
+// NARROW (NQ = 1, NX = 0, at most 12 columns in use): the product runs on the 4x4x4 MFMA.
+template <int KIND, int KK, int NQ, int NJ, int NX, bool NARROW = false>
 __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
                                                  const float* __restrict__ Xb,
                                                  const float* __restrict__ sq,
@@ -234,6 +246,7 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
                                                  const DevState* __restrict__ st) {
   if (st->done) return;
   static_assert(NX >= 0 && NX <= 4, "at most 4 columns on the vector unit");
+  static_assert(!NARROW || (NQ == 1 && NX == 0), "the narrow product covers one group of 12 columns");
   constexpr int LD = 16 * (NQ + (NX > 0 ? 1 : 0));
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int nblk = np >> 4;
@@ -245,6 +258,7 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
   float b[NJ][KK];
   float sqj[NJ];
   f64x4 acc[NJ][NQ];
+  double accn[NJ][3];
   double accx[NJ][NX > 0 ? NX : 1];
 #pragma unroll
   for (int jb = 0; jb < NJ; ++jb) {
@@ -253,6 +267,8 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
     sqj[jb] = sq[(jb0 + jb) * 16 + jc];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int q = 0; q < 3; ++q) accn[jb][q] = 0.0;
 #pragma unroll
     for (int x = 0; x < NX; ++x) accx[jb][x] = 0.0;
   }
@@ -263,11 +279,17 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
     f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
-    f64x4 dop[NQ];
+    f64x4 dop[NARROW ? 3 : NQ];
     f64x4 dx[NX > 0 ? NX : 1];
+    if (NARROW) {
 #pragma unroll
-    for (int nq = 0; nq < NQ; ++nq)
-      dop[nq] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+      for (int q = 0; q < 3; ++q)
+        dop[q] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(4 * q + (jc & 3))) * 4);
+    } else {
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq)
+        dop[nq] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+    }
 #pragma unroll
     for (int x = 0; x < NX; ++x)   // rows 4g..4g+3 of column 16 NQ + x (the same for all jc)
       dx[x] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(NQ * 16 + x)) * 4);
@@ -278,8 +300,13 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         double e = (double)unit_kernel<KIND>(r2[r]);
+        if (NARROW) {
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = mfma16d(dop[nq][r], e, acc[jb][nq]);
+          for (int q = 0; q < 3; ++q) accn[jb][q] = mfma4d(dop[q][r], e, accn[jb][q]);
+        } else {
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq) acc[jb][nq] = mfma16d(dop[nq][r], e, acc[jb][nq]);
+        }
 #pragma unroll
         for (int x = 0; x < NX; ++x) accx[jb][x] = fma(e, dx[x][r], accx[jb][x]);
       }
@@ -290,7 +317,8 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
   for (int jb = 0; jb < NJ; ++jb) {
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq)
-      *(f64x4*)(vout + (size_t)((jb0 + jb) * 16 + jc) * LD + nq * 16 + g * 4) = acc[jb][nq];
+      *(f64x4*)(vout + (size_t)((jb0 + jb) * 16 + jc) * LD + nq * 16 + g * 4) =
+          NARROW ? (f64x4){accn[jb][0], accn[jb][1], accn[jb][2], 0.0} : acc[jb][nq];
     if (NX > 0) {
       // column 16 NQ + x belongs at position 4 x of the last group (the order the MFMA path
       // stores its columns in): lane group g writes positions 4g..4g+3, i.e. column g and zeros
@@ -644,6 +672,8 @@ int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const floa
   k_mm_otf<KIND, K, Q, NJ, X><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st)
 #define OTF_KIND(KIND, K)                             \
   if (nq == 2) OTF_LAUNCH(KIND, K, 2, 0);             \
+  else if (nx == 0 && c <= 12)                        \
+    k_mm_otf<KIND, K, 1, NJ, 0, true><<<grid, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, nsplit, blocks_per_split, st); \
   else if (nx == 0) OTF_LAUNCH(KIND, K, 1, 0);        \
   else if (nx == 1) OTF_LAUNCH(KIND, K, 1, 1);        \
   else if (nx == 2) OTF_LAUNCH(KIND, K, 1, 2);        \
