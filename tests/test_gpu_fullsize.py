@@ -394,6 +394,16 @@ def test_config3_full_size_audit_triangle_storage(ctx):
         ctx.bbmm_tune("khat_sym", 0)
 
 
+def test_triangle_storage_audit_at_n_100000(ctx):
+    # twice the benchmark size: 98 panels, i.e. more partial-result slots per row (up to 98) than
+    # the other modes ever use, 20 GB of stored triangle
+    ctx.bbmm_tune("khat_sym", 1)
+    try:
+        _audit(ctx, inputs.make(3, n=100000), inputs.MATERIALISED)
+    finally:
+        ctx.bbmm_tune("khat_sym", 0)
+
+
 def test_config3_full_size_audit_onthefly(ctx):
     _audit(ctx, inputs.make(3), inputs.ONTHEFLY)
 
