@@ -179,7 +179,10 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *                entries are the same fp32 values, the fp64 sums are formed in another order.
  *                0 (default): the whole matrix.  Takes effect at the next bbmm_build_khat (a
  *                change marks the stored matrix as not built); "khat_panel" is ignored while set;
- *                "mat_wgs" then counts the workgroups of each of its two launches
+ *                "mat_wgs" then counts the workgroups of each of its two launches.  A block of
+ *                more than 16 columns takes one pass over the triangle per group of 16 columns
+ *                (the whole-matrix product takes one pass for up to 32), so beyond 16 columns
+ *                the whole matrix is the faster storage
  *   "zd_blocks"  workgroups per compute unit of the direction update (default 16, at most 64)
  *   "sgpr_wgs1", "sgpr_wgs2"  workgroups of the two streaming products of an SGPR product
  *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build

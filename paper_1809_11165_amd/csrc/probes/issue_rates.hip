@@ -10,7 +10,8 @@
 // Findings on MI355X that the kernels in this directory rely on: v_mfma_f64_16x16x4 takes 64
 // cycles, v_mfma_f64_4x4x4 16 (the same flop rate); a VALU instruction between fp64 MFMAs adds its
 // own ~5 cycles (no overlap); LDS reads and global loads add nothing; an LDS write adds ~11 cycles
-// per dword (45 per ds_write_b128), wherever it is placed.
+// per dword (45 per ds_write_b128), wherever it is placed.  At the density of one 8-byte LDS read per
+// 4x4x4 MFMA (16 cycles) the reads are no longer free: ~3 cycles each.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 typedef double f64x4 __attribute__((ext_vector_type(4)));
@@ -141,6 +142,32 @@ __global__ __launch_bounds__(256) void k(double* out, const float* in, int iters
           m3 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m3, 0, 0, 0);
         }
         asm volatile("ds_write_b128 %0, %1\n ds_write_b128 %0, %1 offset:4096\n ds_write_b128 %0, %1 offset:8192\n ds_write_b128 %0, %1 offset:12288" : : "v"(ad), "v"(q0));
+      } else if (MODE == 17) {   // 4 mfma4 + 4 ds_read_b64 (broadcast over lane/4%4, as the row-side A operand would be)
+        unsigned ad = ((lane >> 4) * 4 * 13 + (lane & 3)) * 8;
+        double x0, x1, x2, x3;
+        asm volatile("ds_read_b64 %0, %1" : "=v"(x0) : "v"(ad));
+        acc0 = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc0, 0, 0, 0);
+        asm volatile("ds_read_b64 %0, %1 offset:32" : "=v"(x1) : "v"(ad));
+        acc1 = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc1, 0, 0, 0);
+        asm volatile("ds_read_b64 %0, %1 offset:64" : "=v"(x2) : "v"(ad));
+        acc2 = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc2, 0, 0, 0);
+        asm volatile("ds_read_b64 %0, %1 offset:104" : "=v"(x3) : "v"(ad));
+        acc3 = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc3, 0, 0, 0);
+        asm volatile("" :: "v"(x0), "v"(x1), "v"(x2), "v"(x3));
+      } else if (MODE == 18) {   // as 17 plus 1 ds_read_b128 (the transposed tile reads) per 4 mfma4
+        unsigned ad = ((lane >> 4) * 4 * 13 + (lane & 3)) * 8;
+        unsigned ad2 = 16 * lane;
+        double x0, x1, x2, x3;
+        asm volatile("ds_read_b64 %0, %1" : "=v"(x0) : "v"(ad));
+        acc0 = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc0, 0, 0, 0);
+        asm volatile("ds_read_b64 %0, %1 offset:32" : "=v"(x1) : "v"(ad));
+        acc1 = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc1, 0, 0, 0);
+        asm volatile("ds_read_b64 %0, %1 offset:64" : "=v"(x2) : "v"(ad));
+        acc2 = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc2, 0, 0, 0);
+        asm volatile("ds_read_b64 %0, %1 offset:104" : "=v"(x3) : "v"(ad));
+        acc3 = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc3, 0, 0, 0);
+        asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(q1) : "v"(ad2));
+        asm volatile("" :: "v"(x0), "v"(x1), "v"(x2), "v"(x3));
       } else if (MODE == 11) {   // 4 mfma + 4 global_load_dwordx4 (cached), no waits inside
         m0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m0, 0, 0, 0);
         asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(q0) : "v"(in + 4 * (lane & 63)));
@@ -197,6 +224,9 @@ int main() {
   run<13>("4 cvt + 4 ds_write_b128 + 4 mfma (group of 12)", out, in, 12);
   run<14>("4 mfma + 4 ds_write_b32 interleaved (group of 8)", out, in, 8);
   run<15>("16 mfma + 4 ds_write_b128 bunched (group of 20)", out, in, 20);
+  run<17>("4 mfma4 + 4 ds_read_b64 broadcast (group of 8)", out, in, 8);
+  run<18>("4 mfma4 + 4 ds_read_b64 + 1 ds_read_b128 (group of 9)", out, in, 9);
+  run<4>("mfma_f64_4x4x4 x4 again", out, in, 4);
   run<3>("mfma_f64_16x16x4 x4 again", out, in, 4);
   hipError_t e = hipGetLastError();
   printf("status %s\n", hipGetErrorString(e));
