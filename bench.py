@@ -199,9 +199,11 @@ def main():
         "metric": metric,
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f64", "data": "synthetic",
         "config": {"workload": workload,
                    "mode": mode_name,
+                   "arithmetic": "kernel-matrix entries fp32 (stored or generated), products, sums and all "
+                                 "n x c blocks fp64",
                    "iters_run": res.iters_run, "ms_per_iteration": ms_per_step / max(res.iters_run, 1),
                    "mm_ms_per_iteration": mm_ms,
                    "logdet": res.logdet, "nlml": res.nlml},
