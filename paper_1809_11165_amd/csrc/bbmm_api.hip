@@ -480,21 +480,22 @@ int stage_sgpr_build(bbmm_ctx* c) {
 }
 
 // SGPR product, second half: Vp <- partial sums of A T with T (quad-swizzled, mp rows) in T4.
-int sgpr_second_pass(bbmm_ctx* c, int ld, VpShape* shape) {
+// cols: columns of the block in use (0 = all).
+int sgpr_second_pass(bbmm_ctx* c, int ld, VpShape* shape, int cols = 0) {
   int v = (ld == 32) ? 1 : 0;
   if (launch_mm_mat(c->stream, ptr<float>(c->AT), ptr<double>(c->T4), ptr<double>(c->Vp), c->np, ld,
                     ptr<MmPlan>(c->sgplan[2 + v]), c->sg_wgs[2 + v], ptr<DevState>(c->st), BBMM_SGPR_PANEL,
-                    c->mp))
+                    c->mp, cols))
     return fail(c, BBMM_EINVAL, "unsupported block width");
   *shape = VpShape{0, ptr<int>(c->sgnseg[2 + v]), v ? 512 : 1024};
   return BBMM_OK;
 }
 
 // SGPR product, first half: Tp <- partial sums of A^T D with D (quad-swizzled, np rows) in `D4`.
-int sgpr_first_pass(bbmm_ctx* c, int ld, const double* D4, VpShape* shape) {
+int sgpr_first_pass(bbmm_ctx* c, int ld, const double* D4, VpShape* shape, int cols = 0) {
   int v = (ld == 32) ? 1 : 0;
   if (launch_mm_mat(c->stream, ptr<float>(c->A), D4, ptr<double>(c->Tp), c->mp, ld,
-                    ptr<MmPlan>(c->sgplan[v]), c->sg_wgs[v], ptr<DevState>(c->st), 0, 0))
+                    ptr<MmPlan>(c->sgplan[v]), c->sg_wgs[v], ptr<DevState>(c->st), 0, 0, cols))
     return fail(c, BBMM_EINVAL, "unsupported block width");
   *shape = VpShape{0, ptr<int>(c->sgnseg[v]), v ? 512 : 1024};
   return BBMM_OK;
@@ -509,10 +510,10 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     if (!c->sgpr_built) return fail(c, BBMM_EINVAL, "SGPR product needs bbmm_sgpr_build first");
     if (ld != 16 && ld != 32) return fail(c, BBMM_EINVAL, "unsupported block width");
     VpShape sh1{0, nullptr, 1};
-    int rc = sgpr_first_pass(c, ld, ptr<double>(c->D4), &sh1);
+    int rc = sgpr_first_pass(c, ld, ptr<double>(c->D4), &sh1, cc);
     if (rc) return rc;
     launch_sgpr_mid(c->stream, ptr<double>(c->Tp), sh1, c->mp, ld, ptr<DevState>(c->st), ptr<double>(c->T4));
-    rc = sgpr_second_pass(c, ld, shape);
+    rc = sgpr_second_pass(c, ld, shape, cc);
     if (rc) return rc;
     *scaleV = 1.0;
     *addD = c->prob.noise;
@@ -535,7 +536,7 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     if (rc) return rc;
     int v = (ld == 32) ? 1 : 0;
     if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
-                      ptr<MmPlan>(c->plan[v]), c->plan_wgs[v], ptr<DevState>(c->st), c->khat_pw, c->np))
+                      ptr<MmPlan>(c->plan[v]), c->plan_wgs[v], ptr<DevState>(c->st), c->khat_pw, c->np, cc))
       return fail(c, BBMM_EINVAL, "unsupported block width");
     *shape = VpShape{0, ptr<int>(c->nseg[v]), v ? 512 : 1024};
     *scaleV = 1.0;
@@ -573,7 +574,7 @@ int stage_pivchol(bbmm_ctx* c) {
     for (int m = 0; m < c->k; ++m) {
       launch_sgpr_pick(s, ptr<float>(c->A), c->mp, arg[m & 1], nb, ptr<double>(c->T4), fpiv(m));
       VpShape sh{0, nullptr, 1};
-      int rc = sgpr_second_pass(c, 16, &sh);
+      int rc = sgpr_second_pass(c, 16, &sh, 1);
       if (rc) return rc;
       launch_vreduce(s, ptr<double>(c->Vp), sh, c->n, c->np, 16, 1.0, 0.0, ptr<double>(c->D4), ptr<double>(c->V));
       launch_pc_step(s, c->prob.X, c->n, m, c->kp, c->hyp, ptr<double>(c->delta), ptr<double>(c->L), st,

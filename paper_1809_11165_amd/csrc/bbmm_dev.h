@@ -178,8 +178,11 @@ int launch_mm_sym(hipStream_t s, const float* Ktri, const double* D4, double* Vp
 // K_hat D; the SGPR root uses it on both of its layouts.  plan: one entry per workgroup, laid out
 // by the host (see make_plan).  panel_width > 0: M is stored in column panels of that width
 // (a multiple of 256), each panel row-major with panel_rows rows; 0: plain row-major.
+// cols: columns of the block really in use (0 = all ld of them): with at most 12 of 16 the product
+// runs on the narrower fp64 MFMA and columns 12..15 of the result are written as zero.
 int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
-                  const MmPlan* plan, int wgs, const DevState* st, int panel_width, int panel_rows);
+                  const MmPlan* plan, int wgs, const DevState* st, int panel_width, int panel_rows,
+                  int cols);
 #define BBMM_SGPR_PANEL 512   // column-panel width of the transposed SGPR root
 // c: number of columns really used (<= ld); lets 17..20 columns run one MFMA group plus vector FMAs
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,

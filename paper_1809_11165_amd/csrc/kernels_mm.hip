@@ -121,27 +121,37 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
 // The loads run one 16-row step ahead of the arithmetic: as soon as the MFMAs of one load's
 // registers are issued, the same registers receive the load for the next step, so every wave
 // keeps 16*NC KB in flight while its MFMAs run.
-template <int NQ>
+// NARROW (NQ = 1, at most 12 columns of the block in use): the product runs on the fp64 4x4x4 MFMA
+// (see mfma4d): three right-hand-side operands D[row][4q + lane%4], q = 0..2, per row quad, three
+// scalar accumulators per 4 matrix columns, 48 matrix-pipe cycles per element instead of 64.
+template <int NQ, bool NARROW>
 __device__ __forceinline__ void mm_mat_load_d(const double* __restrict__ D4, int j0, int jc, int g,
-                                              f64x4 (&dop)[NQ]) {
+                                              f64x4 (&dop)[NARROW ? 3 : NQ]) {
   constexpr int LD = 16 * NQ;
+  if (NARROW) {
 #pragma unroll
-  for (int nq = 0; nq < NQ; ++nq)
-    dop[nq] = *(const f64x4*)(D4 + ((size_t)(j0 / 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+    for (int q = 0; q < 3; ++q)
+      dop[q] = *(const f64x4*)(D4 + ((size_t)(j0 / 4 + g) * LD + (size_t)(4 * q + (jc & 3))) * 4);
+  } else {
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+      dop[nq] = *(const f64x4*)(D4 + ((size_t)(j0 / 4 + g) * LD + (size_t)(nq * 16 + jc)) * 4);
+  }
 }
 
 // One 16-row step.  kv / dop hold this step's operands on entry and the next step's on exit
 // (MORE); the right-hand-side operand of the next step is requested first because memory
 // results return in issue order.
-template <int NQ, int NC, bool MORE>
+template <int NQ, int NC, bool MORE, bool NARROW>
 __device__ __forceinline__ void mm_mat_step(const float* __restrict__ knext,
                                             const double* __restrict__ D4, int jnext, int ldk, int jc,
-                                            int g, f32x4 (&kv)[NC][4], f64x4 (&dop)[NQ],
-                                            f64x4 (&acc)[NC][4][NQ]) {
-  f64x4 dcur[NQ];
+                                            int g, f32x4 (&kv)[NC][4], f64x4 (&dop)[NARROW ? 3 : NQ],
+                                            f64x4 (&acc)[NC][4][NQ], double (&accn)[NC][4][3]) {
+  constexpr int ND = NARROW ? 3 : NQ;
+  f64x4 dcur[ND];
 #pragma unroll
-  for (int nq = 0; nq < NQ; ++nq) dcur[nq] = dop[nq];
-  if (MORE) mm_mat_load_d<NQ>(D4, jnext, jc, g, dop);
+  for (int nq = 0; nq < ND; ++nq) dcur[nq] = dop[nq];
+  if (MORE) mm_mat_load_d<NQ, NARROW>(D4, jnext, jc, g, dop);
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int r = 0; r < 4; ++r)
@@ -153,9 +163,15 @@ __device__ __forceinline__ void mm_mat_step(const float* __restrict__ knext,
       // the registers are free once converted: refill them before the MFMAs are issued
       if (MORE) kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(knext + (size_t)r * ldk + nc * 64));
 #pragma unroll
-      for (int cc = 0; cc < 4; ++cc)
+      for (int cc = 0; cc < 4; ++cc) {
+        if (NARROW) {
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = mfma16d(dcur[nq][r], kd[cc], acc[nc][cc][nq]);
+          for (int q = 0; q < 3; ++q) accn[nc][cc][q] = mfma4d(dcur[q][r], kd[cc], accn[nc][cc][q]);
+        } else {
+#pragma unroll
+          for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = mfma16d(dcur[nq][r], kd[cc], acc[nc][cc][nq]);
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -169,13 +185,14 @@ __device__ __forceinline__ void mm_mat_step(const float* __restrict__ knext,
 // panel row-major with ldk = pw: a matrix with few, very long rows (the transposed SGPR root:
 // 1024 x 500,000) then keeps the 16 rows of a step within 16 * pw * 4 bytes instead of one
 // memory page per row.
-template <int NQ, int NC>
+template <int NQ, int NC, bool NARROW>
 __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Khat,
                                                     const double* __restrict__ D4,
                                                     double* __restrict__ Vp, int np, int pw,
                                                     size_t panel_stride, int ldk,
                                                     const MmPlan* __restrict__ plan,
                                                     const DevState* __restrict__ st) {
+  static_assert(!NARROW || NQ == 1, "the narrow product covers one group of 12 columns");
   if (st->done) return;
   constexpr int LD = 16 * NQ;
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -187,18 +204,22 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
     int col0 = (P.strip * 4 + wave) * (64 * NC);
     if (j_begin >= j_end || col0 >= np) continue;
     f64x4 acc[NC][4][NQ];
+    double accn[NC][4][3];
 #pragma unroll
     for (int nc = 0; nc < NC; ++nc)
 #pragma unroll
-      for (int cc = 0; cc < 4; ++cc)
+      for (int cc = 0; cc < 4; ++cc) {
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) acc[nc][cc][nq] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int q = 0; q < 3; ++q) accn[nc][cc][q] = 0.0;
+      }
 
     const float* kp = Khat + (size_t)(col0 / pw) * panel_stride + (size_t)(j_begin + g * 4) * ldk +
                       (size_t)(col0 % pw + 4 * jc);
     f32x4 kv[NC][4];
-    f64x4 dop[NQ];
-    mm_mat_load_d<NQ>(D4, j_begin, jc, g, dop);
+    f64x4 dop[NARROW ? 3 : NQ];
+    mm_mat_load_d<NQ, NARROW>(D4, j_begin, jc, g, dop);
 #pragma unroll
     for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -207,9 +228,9 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
     int j0 = j_begin;
     for (; j0 + 16 < j_end; j0 += 16) {
       kp += (size_t)16 * ldk;
-      mm_mat_step<NQ, NC, true>(kp, D4, j0 + 16, ldk, jc, g, kv, dop, acc);
+      mm_mat_step<NQ, NC, true, NARROW>(kp, D4, j0 + 16, ldk, jc, g, kv, dop, acc, accn);
     }
-    mm_mat_step<NQ, NC, false>(kp, D4, j0, ldk, jc, g, kv, dop, acc);
+    mm_mat_step<NQ, NC, false, NARROW>(kp, D4, j0, ldk, jc, g, kv, dop, acc, accn);
 
     double* vout = Vp + (size_t)P.slot * np * LD;
 #pragma unroll
@@ -219,7 +240,7 @@ __global__ __launch_bounds__(256, 2) void k_mm_mat(const float* __restrict__ Kha
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq)
           *(f64x4*)(vout + (size_t)(col0 + nc * 64 + 4 * jc + cc) * LD + nq * 16 + g * 4) =
-              acc[nc][cc][nq];
+              NARROW ? (f64x4){accn[nc][cc][0], accn[nc][cc][1], accn[nc][cc][2], 0.0} : acc[nc][cc][nq];
   }
 }
 
@@ -639,16 +660,19 @@ int launch_build_khat(hipStream_t s, int kernel, int KK, const float* Xa, const 
 }
 
 int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp, int np, int ld,
-                  const MmPlan* plan, int wgs, const DevState* st, int panel_width, int panel_rows) {
+                  const MmPlan* plan, int wgs, const DevState* st, int panel_width, int panel_rows,
+                  int cols) {
   // panel_width 0: plain row-major with row stride np
   int pw = panel_width > 0 ? panel_width : np;
   int ldk = panel_width > 0 ? panel_width : np;
   size_t panel_stride = panel_width > 0 ? (size_t)panel_rows * panel_width : 0;
   if (pw % 256 != 0) return 1;
-  if (ld == 16)
-    k_mm_mat<1, 4><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, pw, panel_stride, ldk, plan, st);
+  if (ld == 16 && cols > 0 && cols <= 12)
+    k_mm_mat<1, 4, true><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, pw, panel_stride, ldk, plan, st);
+  else if (ld == 16)
+    k_mm_mat<1, 4, false><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, pw, panel_stride, ldk, plan, st);
   else if (ld == 32)
-    k_mm_mat<2, 2><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, pw, panel_stride, ldk, plan, st);
+    k_mm_mat<2, 2, false><<<wgs, 256, 0, s>>>(Khat, D4, Vp, np, pw, panel_stride, ldk, plan, st);
   else
     return 1;
   return 0;
