@@ -6,13 +6,14 @@
 // (rows I, columns J) above the diagonal blocks is then used twice,
 //     out[J] += T^T D[I]      (contraction over the tile's rows, as in k_mm_mat)
 //     out[I] += T   D[J]      (contraction over its columns),
-// both with v_mfma_f64_16x16x4_f64.  The second use needs the tile in the transposed lane layout;
+// both on the fp64 matrix pipe (v_mfma_f64_16x16x4; the first use takes the 4x4x4 form when at most
+// 12 columns of the block are in use).  The second use needs the tile in the transposed lane layout;
 // every wave passes its 16 x 64 tile through a private LDS area for that (no barrier: a wave's LDS
-// operations execute in order), one tile ahead of its use.  The first kind of partial sum stays in registers for a whole piece
-// of work; the second kind is finished after every 16-row step, staged in LDS per wave, and every
-// SYM_GROUP steps the four waves' parts are added in a fixed order and written to a partial-result
-// slot (two barriers per group).  The number of fp64 MFMAs is that of the full-matrix product, which
-// is what bounds this kernel: HBM traffic is halved, arithmetic is not.
+// operations execute in order), one tile ahead of its use.  The first kind of partial sum stays in
+// registers for a whole piece of work; the second kind is finished after every 16-row step, staged
+// in LDS per wave, and every SYM_GROUP steps the four waves' parts are added in a fixed order and
+// written to a partial-result slot (two barriers per group).  The matrix-pipe work is that of the
+// full-matrix product, which is what bounds this kernel: HBM traffic is halved, arithmetic is not.
 #include "bbmm_dev.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -81,7 +82,7 @@ __device__ __forceinline__ size_t sym_panel_offset(int P) {
 
 // Passes one 16 x 64 tile through the wave's LDS area: written as loaded (rows 4g+r, columns 4jc..),
 // read back transposed for the row-side use.  Split in four parts so that a step can place one part
-// after each group of MFMAs.  On this chip LDS reads and memory loads issue for free beside the
+// after each group of MFMAs.  On this chip a few LDS reads and memory loads issue for free beside the
 // fp64 MFMAs, VALU instructions do not (each adds its ~5 cycles), and an LDS *write* holds the matrix
 // pipe up for ~11 cycles per dword (measured: 45 cycles per ds_write_b128 per wave, wherever it is
 // placed), which makes the transposition the largest cost of this kernel after the MFMAs.
@@ -102,7 +103,8 @@ __device__ __forceinline__ void sym_lds_part(int part, float* __restrict__ Tw, i
 // the next step's on exit (knext / jnext point at the same step again after the last one, so the
 // loads need no branch).  Lane (jc = lane%16, g = lane/16):
 //   kv[nc][r]   rows 4g+r, columns 64 nc + 4 jc .. +3 of the wave's 16 x 256 slab
-//   dI[r]       D[row 4g+r of the step][rhs jc]                       (A operand of the first use)
+//   dI[q][r]    A operand of the first use: D[row 4g+r of the step][rhs jc] (q = 0), or, NARROW,
+//               D[row 4g+r of the step][rhs 4q + jc%4], q = 0..2
 //   dJ[nc][s]   D[column 64 nc + 16 s + 4 g + cc of the wave][rhs jc]  (A operand of the second use)
 //   kt[s][cc]   K[row jc of the step][column 64 nc + 16 s + 4 g + cc]  (from LDS, B operand); on
 //               entry that of tile 0, requested for tile nc+1 during the second use of tile nc
