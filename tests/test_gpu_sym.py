@@ -167,3 +167,44 @@ def test_same_call_in_both_storages_agrees(ctx):
     assert _colrel(_host(tri.U), _host(full.U)) < 1e-5
     assert tri.logdet == pytest.approx(full.logdet, rel=1e-8)
     assert np.allclose(tri.trace, full.trace, rtol=1e-6)
+
+
+@pytest.mark.parametrize("ns", [1, 13, 17, 32])
+def test_predict_var_on_the_triangle(ctx, ns):
+    # one more mBCG run with ns right-hand-side columns: 1 and 13 columns take the narrow and the wide
+    # column-side product, 17 and 32 two passes over the triangle
+    w = inputs.tiny(2100, 6, kernel=inputs.MATERN52, ard=True, t=4, k=8, iters=10, noise=0.2, seed=3)
+    ctx.bbmm_tune("khat_sym", 1)
+    ctx.bbmm_setup(_problem(w))
+    ctx.bbmm_build_khat()
+    L, piv, rank = ctx.bbmm_pivoted_cholesky()
+    ctx.bbmm_precond_setup()
+    rng = np.random.default_rng(4)
+    Xs = rng.uniform(w.X.min(0), w.X.max(0), size=(ns, w.d)).astype(np.float32)
+    Xs[:1] = w.X[:1]
+    var, iters, resid = ctx.bbmm_predict_var(inputs.MATERIALISED, torch.from_numpy(Xs).cuda())
+    assert iters == 10
+    P = O.make_preconditioner(_host(L), w.noise)
+    _, var_o, res_o = O.bbmm_predict(w.kernel, w.X, w.lengthscale, w.outputscale, w.noise, Xs,
+                                     np.zeros(w.n), P, 10)
+    assert np.max(np.abs(_host(var) - var_o)) < 1e-3 * w.outputscale
+    assert resid == pytest.approx(res_o.resid[-1].max(), rel=5e-2)
+
+
+def test_warm_start_on_the_triangle(ctx):
+    # Alg. 1/2 with a current solution as input: r_0 = y - K_hat u_init costs one more product
+    w = inputs.tiny(2600, 5, kernel=inputs.RBF, ard=False, t=5, k=8, iters=12, noise=0.3, seed=11)
+    from paper_1809_11165_amd import binding
+    ctx.bbmm_tune("khat_sym", 1)
+    cold = ctx.bbmm_solve_logdet_grad(_problem(w))
+    prob = _problem(w)
+    prob.u0_init = cold.u0.clone()
+    prob.pivots_in = cold.pivots
+    warm = ctx.bbmm_solve_logdet_grad(prob)
+    ref = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
+                           w.k, warm.iters_run, forced_pivots=warm.pivots,
+                           u0_init=_host(cold.u0))
+    assert _colrel(_host(warm.u0)[:, None], ref.u0[:, None]) < 1e-3
+    assert warm.logdet == pytest.approx(ref.logdet, rel=1e-3)
+    # the warm-started solve starts from a smaller residual than the cold one ended with
+    assert warm.resid[0, 0] < cold.resid[0, 0]
