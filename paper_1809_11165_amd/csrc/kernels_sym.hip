@@ -177,12 +177,14 @@ __device__ __forceinline__ void sym_step_single(const float* __restrict__ knext,
 }
 
 // Workgroup = 4 waves on the 1024 columns of one panel; it runs pieces first[b] .. first[b+1]-1 of
-// the work list, each a run of rows of one panel.  DUAL: the rows lie above the panel's diagonal
-// block and every tile is used twice; otherwise they lie inside it and only the column-side use is
-// made (the block is stored whole).  The two kinds run as separate launches because the second
-// needs less than half the registers of the first.  Partial results: the column-side sum of a
-// piece goes to slot `piece.slot` of its panel's rows of the output; the row-side sums of panel P
-// for output rows of panel s < P go to slot slot_base[s] + P - s - 1.
+// the work list, each a run of rows of one panel.  A piece above its panel's diagonal block uses
+// every tile twice; a piece inside the block (stored whole) makes the column-side use only.
+// DUAL = false: a launch over pieces of the second kind only.  DUAL = true: pieces of the first
+// kind and then, in the NARROW form when first_diag is given, the workgroup's share of the second
+// kind too (one launch for the whole product; the 16-wide form has no registers to spare for both
+// loops, and the second kind then runs as its own, lighter launch).  Partial results: the
+// column-side sum of a piece goes to slot `piece.slot` of its panel's rows of the output; the
+// row-side sums of panel P for output rows of panel s < P go to slot slot_base[s] + P - s - 1.
 //
 // Dq / Vq point at the 16-column group of the right-hand side / output that this launch handles;
 // LD (16 or 32) is the padded width of both.
@@ -191,6 +193,7 @@ __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __res
                                                 double* __restrict__ Vq, int np, int LD,
                                                 const MmPiece* __restrict__ pieces,
                                                 const int* __restrict__ first,
+                                                const int* __restrict__ first_diag,
                                                 const int* __restrict__ slot_base,
                                                 const DevState* __restrict__ st) {
   if (st->done) return;
@@ -201,9 +204,19 @@ __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __res
   float* Tw = T[DUAL ? wave : 0];
   double* Sw = S[DUAL ? wave : 0];
 
+  // DUAL: the workgroup's pieces above the diagonal blocks, then (first_diag given) its share of
+  // the pieces inside them
   int pb = first[blockIdx.x], pe = first[blockIdx.x + 1];
+  int db = 0, de = 0;
+  if (DUAL && NARROW && first_diag) {   // (the 16-wide form has no registers to spare for both loops)
+    db = first_diag[blockIdx.x];
+    de = first_diag[blockIdx.x + 1];
+  }
+  int npieces = (pe - pb) + (de - db);
 #pragma unroll 1
-  for (int pc = pb; pc < pe; ++pc) {
+  for (int pi = 0; pi < npieces; ++pi) {
+    const bool dual_piece = DUAL && (!NARROW || pi < pe - pb);
+    int pc = dual_piece || !DUAL ? pb + pi : db + (pi - (pe - pb));
     MmPiece P = pieces[pc];
     int colw = P.strip * SYM_W + wave * (64 * SYM_NC);
     bool active = colw < np;
@@ -234,7 +247,7 @@ __global__ __launch_bounds__(256, DUAL ? 1 : 2) void k_mm_sym(const float* __res
           kv[nc][r] = __builtin_nontemporal_load((const f32x4*)(kp + (size_t)r * SYM_W + nc * 64));
     }
     int j0 = P.row_begin;
-    if (!DUAL) {
+    if (!dual_piece) {
       if (active) {
 #pragma unroll 1
         for (int q = 0; q < nsteps; ++q, j0 += 16) {
@@ -326,16 +339,22 @@ int launch_mm_sym(hipStream_t s, const float* Ktri, const double* D4, double* Vp
     bool narrow = cols - 16 * nq <= 12;
     const double* Dq = D4 + 64 * nq;
     double* Vq = Vp + 16 * nq;
+    // with the same number of workgroups in both lists one launch runs both kinds of piece
+    bool merged = narrow && wgs_dual > 0 && wgs_dual == wgs_single;
+    const int* fd = merged ? first_single : nullptr;
     if (wgs_dual > 0) {
       if (narrow)
-        k_mm_sym<true, true><<<wgs_dual, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_dual, slot_base, st);
+        k_mm_sym<true, true><<<wgs_dual, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_dual, fd, slot_base, st);
       else
-        k_mm_sym<true, false><<<wgs_dual, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_dual, slot_base, st);
+        k_mm_sym<true, false><<<wgs_dual, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_dual, fd, slot_base, st);
     }
+    if (merged) continue;
     if (narrow)
-      k_mm_sym<false, true><<<wgs_single, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_single, slot_base, st);
+      k_mm_sym<false, true><<<wgs_single, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_single, nullptr,
+                                                       slot_base, st);
     else
-      k_mm_sym<false, false><<<wgs_single, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_single, slot_base, st);
+      k_mm_sym<false, false><<<wgs_single, 256, 0, s>>>(Ktri, Dq, Vq, np, ld, pieces, first_single, nullptr,
+                                                        slot_base, st);
   }
   return 0;
 }
