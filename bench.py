@@ -172,7 +172,7 @@ def main():
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F64_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_F64_PEAK_TFLOPS,
                     "traffic": MEASURED_TRAFFIC_SYM_N50000 if n == 50000 else None,
-                    "kernel": "k_mm_sym<true> (+ k_mm_sym<false> on the diagonal blocks)",
+                    "kernel": "k_mm_sym (one launch per product for c <= 12, else a second one for the diagonal blocks)",
                     "avg_launch_ms": mm_ms, "launches": mm_launches,
                     "executed_TFLOPs_with_padding": executed,
                     "executed_frac": executed / MFMA_F64_PEAK_TFLOPS,
