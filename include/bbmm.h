@@ -168,7 +168,12 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
 /* Tuning knobs for experiments (all have sensible defaults):
  *   "mat_wgs"    number of workgroups a materialised product is dealt out to (default: one per
  *                compute unit; clamped to [strips, 60 * strips], strips = column strips of K_hat)
- *   "otf_split"  number of row chunks an on-the-fly product is split into
+ *   "otf_split"  number of row chunks an on-the-fly product is split into (with "otf_sym": number
+ *                of workgroups of each of its two launches, default two per compute unit)
+ *   "otf_sym"    1 (default): an on-the-fly product of at most 16 columns evaluates only the tiles
+ *                on and above the diagonal and uses each for both of its contributions (K is
+ *                symmetric); 0: every tile is evaluated for the one contribution, as it is for
+ *                more than 16 columns.  Same values, fp64 sums in another order
  *   "ur_blocks"  upper limit of the workgroups of the fused U/R update (default 128, at most 512)
  *   "khat_panel" layout of the materialised K_hat: column panels of that width (a multiple of
  *                256; default 1024), each panel row-major; 1 = plain row-major.  Takes effect at
@@ -188,7 +193,8 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build
  *   "time_mm"    1: record HIP events on the context's stream around every K_hat.M launch of
  *                the next mBCG runs (read back with bbmm_mm_timing); 0: off (default)
- * value <= 0 restores the default.  Unknown key: BBMM_EINVAL. */
+ * value <= 0 restores the default (for "khat_sym" and "otf_sym" the value is the setting itself).
+ * Unknown key: BBMM_EINVAL. */
 int bbmm_tune(bbmm_ctx* ctx, const char* key, int64_t value);
 
 /* Duration of the K_hat.M launches of the last mBCG run, measured with HIP events on the

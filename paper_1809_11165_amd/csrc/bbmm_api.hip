@@ -20,6 +20,14 @@ struct Buf {
   size_t cap = 0;
 };
 
+// Work lists of a product that walks only the panels on and above the diagonal (see build_tri_lists).
+struct TriLists {
+  Buf pieces, first0, first1, base, tot;
+  int wgs[2] = {0, 0};
+  int np = 0;
+  int64_t tune = -1;
+};
+
 constexpr int kMaxVecBlocks = 512;   // at most 32 reduction groups of 16 blocks
 constexpr int kMaxSplit = 64;
 constexpr int kDkStride = 2 * (BBMM_MAXD + 2);
@@ -55,8 +63,9 @@ struct bbmm_ctx {
   int64_t khat_sym = 0;                      // 1: keep only the upper triangle of K_hat (packed panels)
   bool khat_tri = false;                     // the K_hat currently in memory is such a triangle
   // work list of the product from the triangle
-  int sym_np = 0, sym_wgs[2] = {0, 0};
-  int64_t sym_tune = -1;
+  TriLists sym;                              // ... from the stored triangle (panels of 1024 columns)
+  TriLists otft;                             // ... on the fly from X (panels of 512 columns)
+  int64_t otf_sym = 1;                       // 1: the on-the-fly product evaluates each tile pair once (<= 16 columns)
   // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
   int plan_np = 0, plan_wgs[2] = {0, 0};
   int64_t plan_tune = -1;
@@ -69,7 +78,7 @@ struct bbmm_ctx {
   int ev_iters = 0;                          // iterations covered by the last timed run
 
   Buf Xa, Xb, Xs, X4, sq, Khat, L, delta, U, R, V, Z0, D4, Vp, partial, gpartial, alpha, beta, resid, st,
-      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[2], nseg[2], sym_pieces, sym_first, sym_first1, sym_base, sym_tot,
+      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[2], nseg[2], 
       KUU, Gm, Ginv, Kux, AT, A, qdiag, Tp, T4, sgplan[4], sgnseg[4],
       Ua, Ub, Us, U4, usq, TU, TW, BU, BW, dkops;
   DevState* h_st = nullptr;   // pinned
@@ -230,15 +239,14 @@ int ensure_mat_plans(bbmm_ctx* c) {
   return BBMM_OK;
 }
 
-// Work lists of the product from the upper triangle (launch_mm_sym).  Panel P offers P * W / 16
-// steps above its diagonal block, in which every tile is used twice, and up to W / 16 steps inside
-// it, used once; each kind is cut into runs of equal length for its own launch.  Output panel s
-// then has cnt[s] column-side partial results (one per piece of panel s) followed by one row-side
-// partial result from every panel right of it.
-int ensure_sym_plan(bbmm_ctx* c) {
-  if (c->sym_np == c->np && c->sym_tune == c->mat_wgs) return BBMM_OK;
+// Work lists of a product that visits only the panels (W columns each) on and above the diagonal.
+// Panel P offers P * W / 16 steps above its diagonal block, in which every tile is used twice, and
+// up to W / 16 steps inside it, used once; each kind is cut into runs of equal length for `want`
+// workgroups of its own list.  Output panel s then has cnt[s] column-side partial results (one per
+// piece of panel s) followed by one row-side partial result from every panel right of it.
+int build_tri_lists(bbmm_ctx* c, int W, int want, int64_t tune, TriLists& L) {
+  if (L.np == c->np && L.tune == tune) return BBMM_OK;
   HIPCHK(c, hipStreamSynchronize(c->stream));   // earlier launches may still read the old lists
-  const int W = BBMM_SYM_PANEL;
   const int S = (c->np + W - 1) / W;
   struct Seg {
     int strip, row_begin, steps;
@@ -254,7 +262,7 @@ int ensure_sym_plan(bbmm_ctx* c) {
       if (g.steps > 0) segs.push_back(g);
       total += g.steps;
     }
-    int nw = (int)std::min<long long>(c->mat_wgs > 0 ? c->mat_wgs : c->num_cus, total);
+    int nw = (int)std::min<long long>(want, total);
     wgs[kind] = nw;
     first[kind].assign((size_t)nw + 1, (int)pieces.size());
     size_t si = 0;
@@ -292,21 +300,31 @@ int ensure_sym_plan(bbmm_ctx* c) {
     Buf* b;
     const void* src;
     size_t bytes;
-  } ups[] = {{&c->sym_pieces, pieces.data(), sizeof(MmPiece) * pieces.size()},
-             {&c->sym_first, first[0].data(), sizeof(int) * first[0].size()},
-             {&c->sym_first1, first[1].data(), sizeof(int) * first[1].size()},
-             {&c->sym_base, cnt.data(), sizeof(int) * cnt.size()},
-             {&c->sym_tot, tot.data(), sizeof(int) * tot.size()}};
+  } ups[] = {{&L.pieces, pieces.data(), sizeof(MmPiece) * pieces.size()},
+             {&L.first0, first[0].data(), sizeof(int) * first[0].size()},
+             {&L.first1, first[1].data(), sizeof(int) * first[1].size()},
+             {&L.base, cnt.data(), sizeof(int) * cnt.size()},
+             {&L.tot, tot.data(), sizeof(int) * tot.size()}};
   for (const Up& u : ups) {
     rc = ensure(c, *u.b, u.bytes);
     if (rc) return rc;
     HIPCHK(c, hipMemcpy(u.b->p, u.src, u.bytes, hipMemcpyHostToDevice));
   }
-  c->sym_wgs[0] = wgs[0];
-  c->sym_wgs[1] = wgs[1];
-  c->sym_np = c->np;
-  c->sym_tune = c->mat_wgs;
+  L.wgs[0] = wgs[0];
+  L.wgs[1] = wgs[1];
+  L.np = c->np;
+  L.tune = tune;
   return BBMM_OK;
+}
+
+int ensure_sym_plan(bbmm_ctx* c) {
+  return build_tri_lists(c, BBMM_SYM_PANEL, c->mat_wgs > 0 ? (int)c->mat_wgs : c->num_cus, c->mat_wgs, c->sym);
+}
+
+// two workgroups of the on-the-fly triangle kernel fit a compute unit
+int ensure_otf_tri_plan(bbmm_ctx* c) {
+  return build_tri_lists(c, BBMM_OTF_PANEL, c->otf_split > 0 ? (int)c->otf_split : 2 * c->num_cus, c->otf_split,
+                         c->otft);
 }
 
 // Workgroups for streaming a rows_p x cols_p matrix.  With at least one column strip per compute
@@ -524,10 +542,10 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
       int rc = ensure_sym_plan(c);
       if (rc) return rc;
       if (launch_mm_sym(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld, cc,
-                        ptr<MmPiece>(c->sym_pieces), ptr<int>(c->sym_first), c->sym_wgs[0],
-                        ptr<int>(c->sym_first1), c->sym_wgs[1], ptr<int>(c->sym_base), ptr<DevState>(c->st)))
+                        ptr<MmPiece>(c->sym.pieces), ptr<int>(c->sym.first0), c->sym.wgs[0],
+                        ptr<int>(c->sym.first1), c->sym.wgs[1], ptr<int>(c->sym.base), ptr<DevState>(c->st)))
         return fail(c, BBMM_EINVAL, "unsupported block width");
-      *shape = VpShape{0, ptr<int>(c->sym_tot), BBMM_SYM_PANEL};
+      *shape = VpShape{0, ptr<int>(c->sym.tot), BBMM_SYM_PANEL};
       *scaleV = 1.0;
       *addD = 0.0;
       return BBMM_OK;
@@ -541,6 +559,18 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     *shape = VpShape{0, ptr<int>(c->nseg[v]), v ? 512 : 1024};
     *scaleV = 1.0;
     *addD = 0.0;
+  } else if (mode == BBMM_MODE_ONTHEFLY && c->otf_sym && ld == 16) {
+    // every pair of tiles (I, J), (J, I) evaluated once and used for both contributions
+    int rc = ensure_otf_tri_plan(c);
+    if (rc) return rc;
+    if (launch_mm_otf_tri(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb), ptr<float>(c->sq),
+                          ptr<double>(c->D4), ptr<double>(c->Vp), c->np, cc, ptr<MmPiece>(c->otft.pieces),
+                          ptr<int>(c->otft.first0), c->otft.wgs[0], ptr<int>(c->otft.first1), c->otft.wgs[1],
+                          ptr<int>(c->otft.base), ptr<DevState>(c->st)))
+      return fail(c, BBMM_EINVAL, "unsupported input dimension");
+    *shape = VpShape{0, ptr<int>(c->otft.tot), BBMM_OTF_PANEL};
+    *scaleV = c->prob.outputscale;
+    *addD = c->prob.noise;
   } else if (mode == BBMM_MODE_ONTHEFLY) {
     int ns = otf_split_of(c);
     if (launch_mm_otf(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb),
@@ -870,7 +900,8 @@ int bbmm_destroy(bbmm_ctx* c) {
   if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
   if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   Buf* bufs[] = {&c->Xa, &c->Xb, &c->Xs, &c->X4, &c->sq, &c->Khat, &c->L, &c->delta, &c->U, &c->R, &c->V,
-                 &c->Z0, &c->D4, &c->Vp, &c->partial, &c->gpartial, &c->alpha, &c->beta, &c->resid, &c->st, &c->sym_pieces, &c->sym_first, &c->sym_first1, &c->sym_base, &c->sym_tot, &c->tmpA,
+                 &c->Z0, &c->D4, &c->Vp, &c->partial, &c->gpartial, &c->alpha, &c->beta, &c->resid, &c->st, &c->sym.pieces, &c->sym.first0, &c->sym.first1, &c->sym.base, &c->sym.tot, &c->otft.pieces, &c->otft.first0,
+                 &c->otft.first1, &c->otft.base, &c->otft.tot, &c->tmpA,
                  &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig, &c->plan[0], &c->plan[1], &c->nseg[0],
                  &c->nseg[1], &c->KUU, &c->Gm, &c->Ginv, &c->Kux, &c->AT, &c->A, &c->qdiag, &c->Tp, &c->T4,
                  &c->sgplan[0], &c->sgplan[1], &c->sgplan[2], &c->sgplan[3], &c->sgnseg[0], &c->sgnseg[1],
@@ -891,6 +922,7 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   if (!c || !key) return BBMM_EINVAL;
   if (!strcmp(key, "mat_wgs")) c->mat_wgs = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
+  else if (!strcmp(key, "otf_sym")) c->otf_sym = value != 0 ? 1 : 0;   // (0 switches it off: no "default" value here)
   else if (!strcmp(key, "ur_blocks")) c->ur_blocks_cap = value > 0 ? value : 0;
   else if (!strcmp(key, "khat_sym")) {
     if (value != 0 && value != 1) return fail(c, BBMM_EINVAL, "khat_sym must be 0 or 1");

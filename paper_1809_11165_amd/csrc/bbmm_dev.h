@@ -187,6 +187,13 @@ int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp
 // c: number of columns really used (<= ld); lets 17..20 columns run one MFMA group plus vector FMAs
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
                   const double* D4, double* Vp, int np, int ld, int c, int nsplit, const DevState* st);
+// The same product with every pair of tiles (I, J), (J, I) evaluated once and used for both of its
+// contributions; ld = 16 only.  Work lists as for launch_mm_sym, with panels of BBMM_OTF_PANEL columns.
+#define BBMM_OTF_PANEL 512
+int launch_mm_otf_tri(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
+                      const double* D4, double* Vp, int np, int cols, const MmPiece* pieces,
+                      const int* first_dual, int wgs_dual, const int* first_single, int wgs_single,
+                      const int* slot_base, const DevState* st);
 // derivative pass: one partial row (pstride doubles) per wave, then a fixed-order fp64 sum into
 // st->dk_out.  Returns non-zero when the configuration is not supported.
 int launch_dk(hipStream_t s, int kernel, int KK, int ard, int TS, const float* Xa, const float* Xb,

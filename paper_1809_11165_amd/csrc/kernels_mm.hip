@@ -357,6 +357,159 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
   }
 }
 
+// ------------------------------------- product on the fly, each tile pair once --
+// K is symmetric, so tile (I, J) is tile (J, I) transposed: only the strips' tiles on and above the
+// diagonal are evaluated, and a tile above it serves both  out[J] += T^T D[I]  (as in k_mm_otf) and
+// out[I] += T D[J].  Work division as for the stored triangle (launch_mm_sym), with panels of
+// BBMM_OTF_PANEL = 512 columns (4 waves x 8 column blocks): a piece is a run of 16-row blocks of one
+// panel, either above its diagonal block (DUAL: both uses) or inside it (the whole square block is
+// evaluated, column-side use only).  The second use needs the tile with rows across lane%16: the
+// wave writes its four values per lane to a private LDS tile [column][row] (one 16-byte write) and
+// reads K[row lane%16][column 4 (lane/16) + s], s = 0..3, back; the A operand D[J] (one f64x4 per
+// column block and lane) is loaded once per piece.  The row-side sums of a row block (16 x 16 per
+// wave, over its 128 columns) are staged in LDS; every OT_GROUP row blocks the four waves' parts are
+// added in a fixed order and written to the slot  slot_base[s] + P - s - 1  of output panel s.
+// NARROW: at most 12 columns in use, column-side use on the 4x4x4 MFMA (see mfma4d).
+constexpr int OT_NJ = 8;
+constexpr int OT_GROUP = 4;
+constexpr int OT_PLD = 18;      // doubles per staged row (16 + 2: conflict-free 32-byte stores)
+constexpr int OT_TLD = 20;      // floats per column of the transposition tile (16 + 4)
+static_assert(BBMM_OTF_PANEL == 4 * OT_NJ * 16, "a workgroup of four waves covers one panel");
+typedef double f64x4s __attribute__((ext_vector_type(4), aligned(16)));   // as laid out in LDS
+
+template <int KIND, int KK, bool NARROW, bool DUAL>
+__global__ __launch_bounds__(256, 2) void k_mm_otf_tri(const float* __restrict__ Xa,
+                                                        const float* __restrict__ Xb,
+                                                        const float* __restrict__ sq,
+                                                        const double* __restrict__ D4,
+                                                        double* __restrict__ Vp, int np,
+                                                        const MmPiece* __restrict__ pieces,
+                                                        const int* __restrict__ first,
+                                                        const int* __restrict__ slot_base,
+                                                        const DevState* __restrict__ st) {
+  if (st->done) return;
+  constexpr int LD = 16;
+  __shared__ __align__(16) float T[DUAL ? 4 : 1][DUAL ? 16 * OT_TLD : 4];
+  __shared__ __align__(16) double S[DUAL ? 4 : 1][DUAL ? 16 * OT_GROUP * OT_PLD : 2];
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int jc = lane & 15, g = lane >> 4;
+  float* Tw = T[DUAL ? wave : 0];
+  double* Sw = S[DUAL ? wave : 0];
+  int pb = first[blockIdx.x], pe = first[blockIdx.x + 1];
+#pragma unroll 1
+  for (int pc = pb; pc < pe; ++pc) {
+    MmPiece P = pieces[pc];
+    int jb0 = (P.strip * 4 + wave) * OT_NJ;
+    bool active = jb0 * 16 < np;
+    int ib_begin = P.row_begin >> 4, ib_end = P.row_end >> 4;
+    if (ib_begin >= ib_end) continue;
+    float b[OT_NJ][KK];
+    float sqj[OT_NJ];
+    f64x4 acc[OT_NJ];
+    double accn[OT_NJ][3];
+    f64x4 dJ[OT_NJ];
+#pragma unroll
+    for (int jb = 0; jb < OT_NJ; ++jb) {
+      acc[jb] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int q = 0; q < 3; ++q) accn[jb][q] = 0.0;
+      if (active) {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) b[jb][kk] = Xb[((size_t)(jb0 + jb) * KK + kk) * 64 + lane];
+        sqj[jb] = sq[(jb0 + jb) * 16 + jc];
+        // columns 16 (jb0+jb) + 4 g + s, s = 0..3, right-hand side jc
+        if (DUAL) dJ[jb] = *(const f64x4*)(D4 + ((size_t)((jb0 + jb) * 4 + g) * LD + (size_t)jc) * 4);
+      }
+    }
+    if (DUAL && !active) {
+      // a wave whose columns lie beyond the matrix stages nothing in this piece: its area must read
+      // as zero in the flushes (the barrier that ended the previous flush has passed)
+      for (int i = lane; i < 16 * OT_GROUP * OT_PLD; i += 64) Sw[i] = 0.0;
+    }
+#pragma unroll 1
+    for (int ig = ib_begin; ig < ib_end; ig += OT_GROUP) {
+      int ng = min(OT_GROUP, ib_end - ig);
+      if (active) {
+#pragma unroll 1
+        for (int qi = 0; qi < ng; ++qi) {
+          int ib = ig + qi;
+          float a[KK];
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
+          f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
+          f64x4 dop[NARROW ? 3 : 1];
+          if (NARROW) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q)
+              dop[q] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)(4 * q + (jc & 3))) * 4);
+          } else {
+            dop[0] = *(const f64x4*)(D4 + ((size_t)(ib * 4 + g) * LD + (size_t)jc) * 4);
+          }
+          f64x4 acc2[2];
+          acc2[0] = (f64x4){0.0, 0.0, 0.0, 0.0};
+          acc2[1] = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+          for (int jb = 0; jb < OT_NJ; ++jb) {
+            f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
+            if (!DUAL && ib == jb0 + jb) r2 = fix_diag(r2, lane);
+            f32x4 e;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) e[r] = unit_kernel<KIND>(r2[r]);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              double ed = (double)e[r];
+              if (NARROW) {
+#pragma unroll
+                for (int q = 0; q < 3; ++q) accn[jb][q] = mfma4d(dop[q][r], ed, accn[jb][q]);
+              } else {
+                acc[jb] = mfma16d(dop[0][r], ed, acc[jb]);
+              }
+            }
+            if (DUAL) {
+              *(f32x4*)(Tw + jc * OT_TLD + 4 * g) = e;          // [column jc][rows 4g .. 4g+3]
+              __builtin_amdgcn_wave_barrier();
+              float kt[4];
+#pragma unroll
+              for (int s = 0; s < 4; ++s) kt[s] = Tw[(4 * g + s) * OT_TLD + jc];   // K[row jc][column 4g+s]
+              __builtin_amdgcn_wave_barrier();
+#pragma unroll
+              for (int s = 0; s < 4; ++s) acc2[s & 1] = mfma16d(dJ[jb][s], (double)kt[s], acc2[s & 1]);
+            }
+          }
+          if (DUAL) *(f64x4s*)(Sw + (qi * 16 + jc) * OT_PLD + 4 * g) = acc2[0] + acc2[1];
+        }
+      }
+      if (DUAL) {
+        __syncthreads();
+        int rl = threadIdx.x >> 1, half = threadIdx.x & 1;
+        if (rl < ng * 16) {
+          int row = ig * 16 + rl;
+          const double* sp = &S[0][0] + rl * OT_PLD + 8 * half;
+          f64x4 lo = *(const f64x4s*)sp, hi = *(const f64x4s*)(sp + 4);
+#pragma unroll
+          for (int w = 1; w < 4; ++w) {
+            lo += *(const f64x4s*)(sp + w * (16 * OT_GROUP * OT_PLD));
+            hi += *(const f64x4s*)(sp + w * (16 * OT_GROUP * OT_PLD) + 4);
+          }
+          int so = row / BBMM_OTF_PANEL;
+          int slot = slot_base[so] + (P.strip - so - 1);
+          double* dst = Vp + ((size_t)slot * np + (size_t)row) * LD + 8 * half;
+          *(f64x4*)dst = lo;
+          *(f64x4*)(dst + 4) = hi;
+        }
+        __syncthreads();
+      }
+    }
+    if (active) {
+      double* vout = Vp + (size_t)P.slot * np * LD;
+#pragma unroll
+      for (int jb = 0; jb < OT_NJ; ++jb)
+        *(f64x4*)(vout + (size_t)((jb0 + jb) * 16 + jc) * LD + g * 4) =
+            NARROW ? (f64x4){accn[jb][0], accn[jb][1], accn[jb][2], 0.0} : acc[jb];
+    }
+  }
+}
+
 // ------------------------------------------------------------ derivative pass --
 // For every pair (i, j):  S_ij = sum_c SA[i][c] SB[j][c]  (the probe outer products, divided by t
 // and symmetrised by the caller) and Q_ij = u0_i u0_j.  Accumulates
@@ -712,6 +865,35 @@ int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const floa
 #undef OTF
 #undef OTF_KIND
 #undef OTF_LAUNCH
+  return 0;
+}
+
+// On-the-fly product with each tile pair evaluated once (ld = 16 only): one launch over the pieces
+// above the diagonal blocks, one over the pieces inside them.
+int launch_mm_otf_tri(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
+                      const double* D4, double* Vp, int np, int cols, const MmPiece* pieces,
+                      const int* first_dual, int wgs_dual, const int* first_single, int wgs_single,
+                      const int* slot_base, const DevState* st) {
+  bool narrow = cols <= 12;
+#define TRI_LAUNCH(KIND, K, NARROW)                                                                       \
+  do {                                                                                                    \
+    if (wgs_dual > 0)                                                                                     \
+      k_mm_otf_tri<KIND, K, NARROW, true><<<wgs_dual, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, pieces,        \
+                                                                   first_dual, slot_base, st);            \
+    k_mm_otf_tri<KIND, K, NARROW, false><<<wgs_single, 256, 0, s>>>(Xa, Xb, sq, D4, Vp, np, pieces,       \
+                                                                    first_single, slot_base, st);         \
+  } while (0)
+#define TRI(K)                                   \
+  if (kernel == 0) {                             \
+    if (narrow) TRI_LAUNCH(0, K, true);          \
+    else TRI_LAUNCH(0, K, false);                \
+  } else {                                       \
+    if (narrow) TRI_LAUNCH(1, K, true);          \
+    else TRI_LAUNCH(1, K, false);                \
+  }
+  FOR_KK(TRI)
+#undef TRI
+#undef TRI_LAUNCH
   return 0;
 }
 

@@ -528,3 +528,43 @@ def test_nan_in_targets_is_reported_not_propagated_silently(ctx):
     with pytest.raises(binding.BbmmError) as ei:
         ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
     assert ei.value.code == binding.ENONFINITE
+
+
+# ------------------------------------- on-the-fly product, tile pairs once -----
+@pytest.mark.parametrize("n", [300, 512, 523, 1030, 1600, 2100, 4200])
+@pytest.mark.parametrize("c", [1, 11, 12, 13, 16])
+def test_onthefly_product_with_each_tile_pair_once(ctx, n, c):
+    # the default for up to 16 columns: tiles on and above the diagonal only, each used for both of
+    # its contributions; against the plain form (every tile evaluated) and the oracle
+    w = _case(inputs.MATERN52, True, n, 5)
+    rng = np.random.default_rng(70 + c)
+    M = _dev(rng.standard_normal((n, c)))
+    ref = _khat(w) @ _host(M)
+    ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+    try:
+        ctx.bbmm_tune("otf_sym", 0)
+        V0 = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))
+        ctx.bbmm_tune("otf_sym", 1)
+        for wgs in (0, 1, 7, 300):
+            ctx.bbmm_tune("otf_split", wgs)
+            V1 = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))
+            assert _colrel(V1, V0) < 2e-7, wgs
+            assert _colrel(V1, ref) < 1e-4, wgs
+    finally:
+        ctx.bbmm_tune("otf_sym", 1)
+        ctx.bbmm_tune("otf_split", 0)
+
+
+def test_onthefly_forms_agree_on_the_whole_call(ctx):
+    w = inputs.make(3, n=2300)
+    try:
+        ctx.bbmm_tune("otf_sym", 0)
+        a = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
+        ctx.bbmm_tune("otf_sym", 1)
+        b = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
+    finally:
+        ctx.bbmm_tune("otf_sym", 1)
+    assert a.pivots.tolist() == b.pivots.tolist()
+    assert _colrel(_host(a.U), _host(b.U)) < 1e-5
+    assert a.logdet == pytest.approx(b.logdet, rel=1e-8)
+    assert np.allclose(a.trace, b.trace, rtol=1e-6)
