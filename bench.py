@@ -192,7 +192,9 @@ def main():
         achieved = alg_flops / (mm_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
-                    "kernel": "k_mm_otf", "avg_launch_ms": mm_ms, "launches": mm_launches,
+                    "kernel": "k_mm_otf_tri (tiles on and above the diagonal, each used twice; two launches per product)"
+                              if c <= 16 else "k_mm_otf",
+                    "avg_launch_ms": mm_ms, "launches": mm_launches,
                     "pairs_per_s": n * n / (mm_ms * 1e-3)}
 
     out = {
