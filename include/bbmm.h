@@ -170,10 +170,11 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *                compute unit; clamped to [strips, 60 * strips], strips = column strips of K_hat)
  *   "otf_split"  number of row chunks an on-the-fly product is split into (with "otf_sym": number
  *                of workgroups of each of its two launches, default two per compute unit)
- *   "otf_sym"    1 (default): an on-the-fly product of at most 16 columns evaluates only the tiles
- *                on and above the diagonal and uses each for both of its contributions (K is
- *                symmetric); 0: every tile is evaluated for the one contribution, as it is for
- *                more than 16 columns.  Same values, fp64 sums in another order
+ *   "otf_sym"    1 (default): an on-the-fly product of at most 16 columns over at most 32 input
+ *                dimensions evaluates only the tiles on and above the diagonal and uses each for
+ *                both of its contributions (K is symmetric); 0: every tile is evaluated for the one
+ *                contribution, as it is for wider blocks and inputs.  Same values, fp64 sums in
+ *                another order
  *   "ur_blocks"  upper limit of the workgroups of the fused U/R update (default 128, at most 512)
  *   "khat_panel" layout of the materialised K_hat: column panels of that width (a multiple of
  *                256; default 1024), each panel row-major; 1 = plain row-major.  Takes effect at

@@ -65,7 +65,7 @@ struct bbmm_ctx {
   // work list of the product from the triangle
   TriLists sym;                              // ... from the stored triangle (panels of 1024 columns)
   TriLists otft;                             // ... on the fly from X (panels of 512 columns)
-  int64_t otf_sym = 1;                       // 1: the on-the-fly product evaluates each tile pair once (<= 16 columns)
+  int64_t otf_sym = 1;                       // 1: the on-the-fly product evaluates each tile pair once (<= 16 columns, d <= 32)
   // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
   int plan_np = 0, plan_wgs[2] = {0, 0};
   int64_t plan_tune = -1;
@@ -559,8 +559,9 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     *shape = VpShape{0, ptr<int>(c->nseg[v]), v ? 512 : 1024};
     *scaleV = 1.0;
     *addD = 0.0;
-  } else if (mode == BBMM_MODE_ONTHEFLY && c->otf_sym && ld == 16) {
-    // every pair of tiles (I, J), (J, I) evaluated once and used for both contributions
+  } else if (mode == BBMM_MODE_ONTHEFLY && c->otf_sym && ld == 16 && c->KK <= 8) {
+    // every pair of tiles (I, J), (J, I) evaluated once and used for both contributions (beyond 32
+    // input dimensions the two-use form runs out of registers and the one-use form is the faster)
     int rc = ensure_otf_tri_plan(c);
     if (rc) return rc;
     if (launch_mm_otf_tri(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb), ptr<float>(c->sq),

@@ -868,8 +868,8 @@ int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const floa
   return 0;
 }
 
-// On-the-fly product with each tile pair evaluated once (ld = 16 only): one launch over the pieces
-// above the diagonal blocks, one over the pieces inside them.
+// On-the-fly product with each tile pair evaluated once (ld = 16 and KK <= 8 only): one launch over
+// the pieces above the diagonal blocks, one over the pieces inside them.
 int launch_mm_otf_tri(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
                       const double* D4, double* Vp, int np, int cols, const MmPiece* pieces,
                       const int* first_dual, int wgs_dual, const int* first_single, int wgs_single,
@@ -891,7 +891,14 @@ int launch_mm_otf_tri(hipStream_t s, int kernel, int KK, const float* Xa, const 
     if (narrow) TRI_LAUNCH(1, K, true);          \
     else TRI_LAUNCH(1, K, false);                \
   }
-  FOR_KK(TRI)
+  // up to 32 input dimensions: beyond that the two-use form does not fit the register file
+  switch (KK) {
+    case 1: TRI(1); break;
+    case 2: TRI(2); break;
+    case 4: TRI(4); break;
+    case 8: TRI(8); break;
+    default: return 1;
+  }
 #undef TRI
 #undef TRI_LAUNCH
   return 0;

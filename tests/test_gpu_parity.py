@@ -555,6 +555,30 @@ def test_onthefly_product_with_each_tile_pair_once(ctx, n, c):
         ctx.bbmm_tune("otf_split", 0)
 
 
+@pytest.mark.parametrize("kernel", [inputs.RBF, inputs.MATERN52])
+@pytest.mark.parametrize("d", [1, 3, 4, 9, 16, 20, 32, 33, 64])
+def test_onthefly_tile_pairs_once_over_input_dimensions(ctx, kernel, d):
+    # d is padded to 4, 8, 16, 32 or 64 coordinates per point; up to 32 the default is the paired
+    # form, beyond it the plain one: either way the product must match the oracle
+    n = 1600
+    w = _case(kernel, True, n, d)
+    rng = np.random.default_rng(170 + d)
+    for c in (11, 16):
+        M = _dev(rng.standard_normal((n, c)))
+        ref = _khat(w) @ _host(M)
+        ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+        try:
+            ctx.bbmm_tune("otf_sym", 0)
+            V0 = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))
+            ctx.bbmm_tune("otf_sym", 1)
+            V1 = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))
+        finally:
+            ctx.bbmm_tune("otf_sym", 1)
+        assert _colrel(V1, V0) < 2e-7, c
+        assert _colrel(V1, ref) < 1e-4, c
+        assert _colrel(V0, ref) < 1e-4, c
+
+
 def test_onthefly_forms_agree_on_the_whole_call(ctx):
     w = inputs.make(3, n=2300)
     try:
