@@ -187,15 +187,20 @@ def main():
                     "traffic": MEASURED_TRAFFIC_MAT_N50000 if n == 50000 else None,
                     "kernel": "k_mm_mat", "avg_launch_ms": mm_ms, "launches": mm_launches}
     else:
-        # algorithmic flops per pair: 2 d (distance contraction) + 2 c (multiply by the block)
+        # algorithmic flops per pair: 2 d (distance contraction) + 2 c (multiply by the block).
+        # `frac` prices all of them at the fp32 matrix rate; the second contraction is carried out in
+        # fp64, at half that rate on the same pipe, so the floor of the two together is
+        # n^2 (2 d / peak32 + 2 c / peak64): `frac_of_mixed_floor` is that floor over the launch time.
         alg_flops = (2.0 * d + 2.0 * c) * n * n
         achieved = alg_flops / (mm_ms * 1e-3) / 1e12
+        mixed_floor_ms = n * n * (2.0 * d / MFMA_F32_PEAK_TFLOPS + 2.0 * c / MFMA_F64_PEAK_TFLOPS) * 1e-9
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
                     "kernel": "k_mm_otf_tri (tiles on and above the diagonal, each used twice; two launches per product)"
                               if c <= 16 else "k_mm_otf",
                     "avg_launch_ms": mm_ms, "launches": mm_launches,
-                    "pairs_per_s": n * n / (mm_ms * 1e-3)}
+                    "pairs_per_s": n * n / (mm_ms * 1e-3),
+                    "mixed_floor_ms": mixed_floor_ms, "frac_of_mixed_floor": mixed_floor_ms / mm_ms}
 
     out = {
         "metric": metric,

@@ -1030,51 +1030,89 @@ __global__ __launch_bounds__(VT) void k_zd(int n, double noise, const double* __
 // Wilkinson shift; each Givens rotation of a sweep is also applied to the row vector
 // w (initially e_1), so w ends up as the first row of the eigenvector matrix.
 // Serial, O(m^2); arrays live in LDS.  b needs m entries (b[m-1] is scratch).
+// One thread runs this, so its cost is its instruction count plus every wait for an LDS value:
+// the top of the unreduced block is therefore not searched for before each sweep but kept from
+// sweep to sweep, and a sweep tests the off-diagonal entries it rewrites as it goes (all of the
+// block's but the last, which the deflation test at the top covers).
 __device__ void tridiag_eig_first_row(double* a, double* b, double* w, int m) {
   for (int i = 0; i < m; ++i) w[i] = (i == 0) ? 1.0 : 0.0;
   if (m <= 1) return;
   b[m - 1] = 0.0;
   const double eps = 2.220446049250313e-16;
   int hi = m - 1;
+  int lo = -1;                          // top of the unreduced block that ends at hi; -1: not known
   int budget = 60 * m;
   while (hi > 0 && budget-- > 0) {
     // deflate converged eigenvalues at the bottom
-    if (fabs(b[hi - 1]) <= eps * (fabs(a[hi - 1]) + fabs(a[hi]))) {
+    double bb = b[hi - 1], ah = a[hi], ahm = a[hi - 1];
+    if (fabs(bb) <= eps * (fabs(ahm) + fabs(ah))) {
       b[hi - 1] = 0.0;
       --hi;
       continue;
     }
-    // find the top of the unreduced block ending at hi
-    int lo = hi - 1;
-    while (lo > 0 && fabs(b[lo - 1]) > eps * (fabs(a[lo - 1]) + fabs(a[lo]))) --lo;
-    if (lo > 0) b[lo - 1] = 0.0;
+    if (lo < 0 || lo >= hi) {
+      // the block above the one just finished: search for its top
+      lo = hi - 1;
+      while (lo > 0 && fabs(b[lo - 1]) > eps * (fabs(a[lo - 1]) + fabs(a[lo]))) --lo;
+      if (lo > 0) b[lo - 1] = 0.0;
+    }
     // Wilkinson shift from the trailing 2 x 2 block
-    double dlt = 0.5 * (a[hi - 1] - a[hi]);
-    double bb = b[hi - 1];
+    double dlt = 0.5 * (ahm - ah);
     double denom = dlt + (dlt >= 0.0 ? 1.0 : -1.0) * sqrt(dlt * dlt + bb * bb);
-    double mu = (denom != 0.0) ? a[hi] - bb * bb / denom : a[hi];
-    // chase the bulge from lo to hi
+    double mu = (denom != 0.0) ? ah - bb * bb / denom : ah;
+    // chase the bulge from lo to hi.  The values that one rotation hands to the next (the entries
+    // a[i], b[i], w[i] that it has just changed, and the bulge x, z) travel in registers; the LDS
+    // arrays are only read at entries no rotation of this sweep has touched yet (one step ahead of
+    // their use) and written with final values, so no step waits for a store of the step before.
     double x = a[lo] - mu;
     double z = b[lo];
+    double ai = a[lo], bi = b[lo], wi = w[lo];
+    double an = a[lo + 1], bn = b[lo + 1], wn = w[lo + 1];
+    double ap = 0.0;                    // a[i - 1] as the rotation before left it
+    int split = -1;
     for (int i = lo; i < hi; ++i) {
-      // rotation (c, s) that zeroes z against x:  [c s; -s c]^T applied to rows/cols i, i+1
-      double r = sqrt(x * x + z * z);
-      double c = (r != 0.0) ? x / r : 1.0;
-      double s = (r != 0.0) ? z / r : 0.0;
-      if (i > lo) b[i - 1] = r;
-      double ai = a[i], aj = a[i + 1], bi = b[i];
-      a[i] = c * c * ai + 2.0 * c * s * bi + s * s * aj;
-      a[i + 1] = s * s * ai - 2.0 * c * s * bi + c * c * aj;
-      b[i] = (c * c - s * s) * bi + c * s * (aj - ai);
-      x = b[i];
-      if (i + 1 < hi) {
-        z = s * b[i + 1];
-        b[i + 1] = c * b[i + 1];
+      double aj = an, bj = bn, wj = wn;
+      if (i + 2 <= hi) {
+        an = a[i + 2];
+        bn = b[i + 2];
+        wn = w[i + 2];
       }
-      double wi = w[i], wj = w[i + 1];
+      // rotation (c, s) that zeroes z against x:  [c s; -s c]^T applied to rows/cols i, i+1
+      // (1 / r from the hardware's reciprocal square root and two Newton steps: a third of the
+      // instructions of sqrt and a division)
+      double h = fma(x, x, z * z);
+      bool nz = h > 1e-290;
+      double y = __builtin_amdgcn_rsq(nz ? h : 1.0);
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        double hy = h * y;
+        y = fma(0.5 * y, fma(-hy, y, 1.0), y);
+      }
+      double rinv = nz ? y : 0.0;
+      double r = h * rinv;
+      double c = nz ? x * rinv : 1.0;
+      double s = z * rinv;
+      double cs2 = 2.0 * c * s * bi;
+      double anew = c * c * ai + cs2 + s * s * aj;
+      a[i] = anew;
+      if (i > lo) {
+        // b[i - 1] = r is final now, and so are its two neighbours on the diagonal
+        bool negligible = r <= eps * (fabs(ap) + fabs(anew));
+        b[i - 1] = negligible ? 0.0 : r;
+        if (negligible) split = i;
+      }
+      ap = anew;
       w[i] = c * wi + s * wj;
-      w[i + 1] = -s * wi + c * wj;
+      x = (c * c - s * s) * bi + c * s * (aj - ai);
+      ai = s * s * ai - cs2 + c * c * aj;
+      wi = -s * wi + c * wj;
+      z = s * bj;                       // (unused after the last rotation: b[hi] is not in the block)
+      bi = c * bj;
     }
+    a[hi] = ai;
+    w[hi] = wi;
+    b[hi - 1] = x;
+    if (split >= 0) lo = split;
   }
 }
 
