@@ -5,14 +5,15 @@ One "step" is one full bbmm_solve_logdet_grad call (preconditioner, probes, mBCG
 log-det, derivative traces) on the n = 50,000, d = 16, t = 10 Matern-5/2 ARD workload
 (rank-20 preconditioner, 50 mBCG iterations), inputs resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode sym|mat|otf|sgpr] [--n N] [--no-cpu]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode sym|mat|otf|sgpr] [--config 3|2] [--n N] [--no-cpu]
 
 The default mode keeps the fp32 K_hat materialised as its upper triangle (half the HBM bytes per
 product, every tile used for both of its contributions; the product is then bound by the fp64
 matrix rate).  --mode mat keeps the whole matrix (HBM-bound product), --mode otf rebuilds the tiles
 from X in every product.  --mode sgpr measures the widened path instead (config 5: subset-of-regressors covariance,
 n = 500,000, m = 1024 inducing inputs, d = 8, t = 10, rank-10 preconditioner, 50 iterations);
-the default line is the exact-GP workload above.
+the default line is the exact-GP workload above.  --config 2 runs the second roofline point instead
+(RBF, n = 10,000, d = 8, rank-10 preconditioner, stop at a relative residual of 1e-2 or 50 iterations).
 """
 import argparse
 import json
@@ -41,15 +42,16 @@ MEASURED_TRAFFIC_SGPR_N500000_M1024 = 4.261e9
 MEASURED_TRAFFIC_SYM_N50000 = 5.527e9
 
 
-def cpu_baseline(n_sample: int, n_full: int):
-    """Times the fp64 oracle (as it stands) on an n_sample-point instance of the same recipe and
-    scales by (n_full / n_sample)^2, the cost ratio of the O(n^2) products that dominate."""
+def cpu_baseline(cfg: int, n_sample: int, n_full: int, iters: int):
+    """Times the fp64 oracle (as it stands) on an n_sample-point instance of the same recipe, for the
+    number of iterations the GPU call ran, and scales by (n_full / n_sample)^2, the cost ratio of the
+    O(n^2) products that dominate."""
     from oracle import bbmm_oracle as O
     from paper_1809_11165_amd import inputs
-    w = inputs.make(3, n=n_sample)
+    w = inputs.make(cfg, n=n_sample)
     t0 = time.perf_counter()
     O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
-                     w.k, w.iters)
+                     w.k, iters)
     dt = time.perf_counter() - t0
     try:
         cores = len(os.sched_getaffinity(0))
@@ -58,9 +60,9 @@ def cpu_baseline(n_sample: int, n_full: int):
     threads = int(os.environ.get("OMP_NUM_THREADS", cores))
     return {"value": dt * 1e3 * (n_full / n_sample) ** 2, "unit": "ms", "cores": min(cores, threads),
             "kind": "oracle",
-            "sample": "fp64 numpy oracle, full call (k=20, t=10, 50 iterations) on n=%d points of the same "
+            "sample": "fp64 numpy oracle, full call (k=%d, t=%d, %d iterations) on n=%d points of the same "
                       "recipe: %.1f s measured, scaled by (n/n_sample)^2 = %.0f"
-                      % (n_sample, dt, (n_full / n_sample) ** 2)}
+                      % (w.k, w.t, iters, n_sample, dt, (n_full / n_sample) ** 2)}
 
 
 def cpu_baseline_sgpr(n_sample: int, n_full: int, m: int):
@@ -91,7 +93,10 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--mode", choices=["sym", "mat", "otf", "sgpr"], default="sym")
-    ap.add_argument("--n", type=int, default=None, help="points (default 50000; 500000 for --mode sgpr)")
+    ap.add_argument("--config", type=int, choices=[2, 3], default=3,
+                    help="exact-GP workload: 3 (default, the headline) or 2 (n = 10000, RBF, tolerance stop)")
+    ap.add_argument("--n", type=int, default=None,
+                    help="points (default 50000; 10000 for --config 2; 500000 for --mode sgpr)")
     ap.add_argument("--m", type=int, default=1024, help="inducing inputs (--mode sgpr)")
     ap.add_argument("--cpu-sample", type=int, default=10000)
     ap.add_argument("--no-cpu", action="store_true")
@@ -109,8 +114,8 @@ def main():
     mode = {"mat": inputs.MATERIALISED, "sym": inputs.MATERIALISED, "otf": inputs.ONTHEFLY,
             "sgpr": inputs.SGPR}[args.mode]
     if args.n is None:
-        args.n = 500000 if mode == inputs.SGPR else 50000
-    w = inputs.make(5, n=args.n, m=args.m) if mode == inputs.SGPR else inputs.make(3, n=args.n)
+        args.n = 500000 if mode == inputs.SGPR else (50000 if args.config == 3 else 10000)
+    w = inputs.make(5, n=args.n, m=args.m) if mode == inputs.SGPR else inputs.make(args.config, n=args.n)
     prob = binding.problem_from_workload(w, mode)
     ctx = binding.Context(0)
     ctx.bbmm_tune("time_mm", 1)
@@ -142,6 +147,10 @@ def main():
     n, c, d = w.n, w.t + 1, w.d
     workload = "config3: exact GP, Matern-5/2 ARD, n=%d, d=16, t=10, k=20, 50 mBCG iterations" % n
     metric = "mBCG solve+logdet+grad ms at n=50k,t=10"
+    if args.config == 2:
+        workload = ("config2: exact GP, RBF, n=%d, d=8, t=10, k=10, mBCG to a relative residual of 1e-2 or "
+                    "50 iterations" % n)
+        metric = "mBCG solve+logdet+grad ms at n=10k,t=10 (config 2)"
     mode_name = "materialised fp32 K_hat" if mode == inputs.MATERIALISED else "on-the-fly tiles"
     if mode == inputs.SGPR:
         # one product = the root A (n x m fp32) streamed once in each layout, the block in and out,
@@ -171,7 +180,7 @@ def main():
         executed = wide * n * n / (mm_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F64_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_F64_PEAK_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_SYM_N50000 if n == 50000 else None,
+                    "traffic": MEASURED_TRAFFIC_SYM_N50000 if (n, args.config) == (50000, 3) else None,
                     "kernel": "k_mm_sym (one launch per product for c <= 12, else a second one for the diagonal blocks)",
                     "avg_launch_ms": mm_ms, "launches": mm_launches,
                     "executed_TFLOPs_with_padding": executed,
@@ -184,7 +193,7 @@ def main():
         achieved = alg_bytes / (mm_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC_MAT_N50000 if n == 50000 else None,
+                    "traffic": MEASURED_TRAFFIC_MAT_N50000 if (n, args.config) == (50000, 3) else None,
                     "kernel": "k_mm_mat", "avg_launch_ms": mm_ms, "launches": mm_launches}
     else:
         # algorithmic flops per pair: 2 d (distance contraction) + 2 c (multiply by the block).
@@ -218,7 +227,8 @@ def main():
     }
     if not args.no_cpu:
         out["cpu_baseline"] = (cpu_baseline_sgpr(min(n, 5 * args.cpu_sample), n, args.m)
-                               if mode == inputs.SGPR else cpu_baseline(args.cpu_sample, n))
+                               if mode == inputs.SGPR
+                               else cpu_baseline(args.config, min(n, args.cpu_sample), n, res.iters_run))
     print(json.dumps(out))
 
 
