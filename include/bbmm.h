@@ -172,8 +172,9 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *   "otf_split"  number of row chunks an on-the-fly product is split into (with "otf_sym": number
  *                of workgroups of each of its two launches, default two per compute unit)
  *   "otf_sym"    1 (default): an on-the-fly product of at most 16 columns over at most 32 input
- *                dimensions evaluates only the tiles on and above the diagonal and uses each for
- *                both of its contributions (K is symmetric); 0: every tile is evaluated for the one
+ *                dimensions and at least 12288 (padded) rows evaluates only the tiles on and above
+ *                the diagonal and uses each for both of its contributions (K is symmetric);
+ *                2: the same for any number of rows; 0: every tile is evaluated for the one
  *                contribution, as it is for wider blocks and inputs.  Same values, fp64 sums in
  *                another order
  *   "ur_blocks"  upper limit of the workgroups of the fused U/R update (default 128, at most 512)

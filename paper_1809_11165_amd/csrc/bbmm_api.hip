@@ -30,6 +30,9 @@ struct TriLists {
 
 constexpr int kMaxVecBlocks = 512;   // at most 32 reduction groups of 16 blocks
 constexpr int kMaxSplit = 64;
+// Measured, product in us (two-use / one-use form): n = 5 000: 88 / 60; 10 000: 125 / 121; 20 000: 312 / 331;
+// 30 000: 630 / 696; 50 000: 1950 / 2630.
+constexpr int kOtfSymMinRows = 12288;
 constexpr int kDkStride = 2 * (BBMM_MAXD + 2);
 
 }  // namespace
@@ -65,7 +68,7 @@ struct bbmm_ctx {
   // work list of the product from the triangle
   TriLists sym;                              // ... from the stored triangle (panels of 1024 columns)
   TriLists otft;                             // ... on the fly from X (panels of 512 columns)
-  int64_t otf_sym = 1;                       // 1: the on-the-fly product evaluates each tile pair once (<= 16 columns, d <= 32)
+  int64_t otf_sym = 1;                       // on-the-fly product with each tile pair evaluated once (<= 16 columns, d <= 32): 0 never, 1 from kOtfSymMinRows rows on, 2 always
   // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
   int plan_np = 0, plan_wgs[2] = {0, 0};
   int64_t plan_tune = -1;
@@ -390,7 +393,8 @@ int ensure_sgpr_plans(bbmm_ctx* c) {
 int otf_split_of(const bbmm_ctx* c) {
   if (c->otf_split > 0) return (int)std::min<int64_t>(c->otf_split, std::min(kMaxSplit, c->np / 16));
   int strips = (c->np / 16 + 31) / 32;          // 4 waves x 8 column blocks per workgroup
-  return split_by_fill(c, strips, 4 * c->num_cus, 0.97);
+  // (at least four 16-row blocks per chunk: n = 1 000 runs 24 us with 16 chunks, 32 us with 64)
+  return std::min(split_by_fill(c, strips, 4 * c->num_cus, 0.97), std::max(1, c->np / 64));
 }
 
 // the derivative pass skips the tiles below the diagonal, so its workgroups differ in length:
@@ -575,9 +579,11 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     *shape = VpShape{0, ptr<int>(c->nseg[v]), v ? 512 : 1024};
     *scaleV = 1.0;
     *addD = 0.0;
-  } else if (mode == BBMM_MODE_ONTHEFLY && c->otf_sym && ld == 16 && c->KK <= 8) {
+  } else if (mode == BBMM_MODE_ONTHEFLY && (c->otf_sym == 2 || (c->otf_sym == 1 && c->np >= kOtfSymMinRows)) &&
+             ld == 16 && c->KK <= 8) {
     // every pair of tiles (I, J), (J, I) evaluated once and used for both contributions (beyond 32
-    // input dimensions the two-use form runs out of registers and the one-use form is the faster)
+    // input dimensions the two-use form runs out of registers and the one-use form is the faster;
+    // so it is for small n, where the pieces of the two-use form are short)
     int rc = ensure_otf_tri_plan(c);
     if (rc) return rc;
     if (launch_mm_otf_tri(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb), ptr<float>(c->sq),
@@ -939,7 +945,7 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   if (!c || !key) return BBMM_EINVAL;
   if (!strcmp(key, "mat_wgs")) c->mat_wgs = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
-  else if (!strcmp(key, "otf_sym")) c->otf_sym = value != 0 ? 1 : 0;   // (0 switches it off: no "default" value here)
+  else if (!strcmp(key, "otf_sym")) c->otf_sym = value <= 0 ? 0 : (value == 1 ? 1 : 2);   // off / by size / always
   else if (!strcmp(key, "ur_blocks")) c->ur_blocks_cap = value > 0 ? value : 0;
   else if (!strcmp(key, "khat_sym")) {
     if (value != 0 && value != 1) return fail(c, BBMM_EINVAL, "khat_sym must be 0 or 1");

@@ -534,8 +534,9 @@ def test_nan_in_targets_is_reported_not_propagated_silently(ctx):
 @pytest.mark.parametrize("n", [300, 512, 523, 1030, 1600, 2100, 4200])
 @pytest.mark.parametrize("c", [1, 11, 12, 13, 16])
 def test_onthefly_product_with_each_tile_pair_once(ctx, n, c):
-    # the default for up to 16 columns: tiles on and above the diagonal only, each used for both of
-    # its contributions; against the plain form (every tile evaluated) and the oracle
+    # tiles on and above the diagonal only, each used for both of its contributions (the default from
+    # 12288 rows on, forced here with the value 2); against the plain form (every tile evaluated) and
+    # the oracle
     w = _case(inputs.MATERN52, True, n, 5)
     rng = np.random.default_rng(70 + c)
     M = _dev(rng.standard_normal((n, c)))
@@ -544,7 +545,7 @@ def test_onthefly_product_with_each_tile_pair_once(ctx, n, c):
     try:
         ctx.bbmm_tune("otf_sym", 0)
         V0 = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))
-        ctx.bbmm_tune("otf_sym", 1)
+        ctx.bbmm_tune("otf_sym", 2)
         for wgs in (0, 1, 7, 300):
             ctx.bbmm_tune("otf_split", wgs)
             V1 = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))
@@ -558,8 +559,8 @@ def test_onthefly_product_with_each_tile_pair_once(ctx, n, c):
 @pytest.mark.parametrize("kernel", [inputs.RBF, inputs.MATERN52])
 @pytest.mark.parametrize("d", [1, 3, 4, 9, 16, 20, 32, 33, 64])
 def test_onthefly_tile_pairs_once_over_input_dimensions(ctx, kernel, d):
-    # d is padded to 4, 8, 16, 32 or 64 coordinates per point; up to 32 the default is the paired
-    # form, beyond it the plain one: either way the product must match the oracle
+    # d is padded to 4, 8, 16, 32 or 64 coordinates per point; up to 32 the paired form is available
+    # (forced here), beyond it the plain one runs: either way the product must match the oracle
     n = 1600
     w = _case(kernel, True, n, d)
     rng = np.random.default_rng(170 + d)
@@ -570,7 +571,7 @@ def test_onthefly_tile_pairs_once_over_input_dimensions(ctx, kernel, d):
         try:
             ctx.bbmm_tune("otf_sym", 0)
             V0 = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))
-            ctx.bbmm_tune("otf_sym", 1)
+            ctx.bbmm_tune("otf_sym", 2)
             V1 = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))
         finally:
             ctx.bbmm_tune("otf_sym", 1)
@@ -579,12 +580,37 @@ def test_onthefly_tile_pairs_once_over_input_dimensions(ctx, kernel, d):
         assert _colrel(V0, ref) < 1e-4, c
 
 
+def test_onthefly_default_form_depends_on_the_size(ctx):
+    # by default the paired form runs from 12288 (padded) rows on: there the default must be the forced
+    # paired product bit for bit, below it the plain one; sampled rows against the oracle's kernel rows
+    for n, paired in ((4000, False), (12500, True)):
+        w = _case(inputs.MATERN52, True, n, 6)
+        rng = np.random.default_rng(n)
+        M = _dev(rng.standard_normal((n, 11)))
+        ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+        try:
+            Vd = ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M)
+            ctx.bbmm_tune("otf_sym", 0)
+            V0 = ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M)
+            ctx.bbmm_tune("otf_sym", 2)
+            V2 = ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M)
+        finally:
+            ctx.bbmm_tune("otf_sym", 1)
+        assert torch.equal(Vd, V2 if paired else V0), n
+        rows = rng.choice(n, size=48, replace=False)
+        Krows = O.kernel_block(w.kernel, w.X[rows], w.X, w.lengthscale, w.outputscale)
+        ref = Krows @ _host(M) + w.noise * _host(M)[rows]
+        for V in (V0, V2):
+            got = _host(V)[rows]
+            assert np.max(np.abs(got - ref)) < 1e-4 * np.max(np.abs(ref)), n
+
+
 def test_onthefly_forms_agree_on_the_whole_call(ctx):
     w = inputs.make(3, n=2300)
     try:
         ctx.bbmm_tune("otf_sym", 0)
         a = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
-        ctx.bbmm_tune("otf_sym", 1)
+        ctx.bbmm_tune("otf_sym", 2)
         b = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
     finally:
         ctx.bbmm_tune("otf_sym", 1)
