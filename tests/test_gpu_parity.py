@@ -530,6 +530,35 @@ def test_nan_in_targets_is_reported_not_propagated_silently(ctx):
     assert ei.value.code == binding.ENONFINITE
 
 
+# ------------------------------ default work plans of the products over sizes -----
+@pytest.mark.parametrize("n", [1000, 2500, 4100, 5000, 10000, 17000, 20000, 30000])
+def test_products_with_their_default_plans_on_sampled_rows(ctx, n):
+    # the default number of workgroups depends on how the column strips divide the compute units
+    # (a whole number per strip, fewer for short matrices): every branch of that choice, in all three
+    # storages, against rows of the oracle's kernel matrix picked at random
+    w = _case(inputs.RBF, True, n, 7)
+    rng = np.random.default_rng(n + 1)
+    rows = np.sort(rng.choice(n, size=40, replace=False))
+    rows[0], rows[-1] = 0, n - 1
+    Krows = O.kernel_block(w.kernel, w.X[rows], w.X, w.lengthscale, w.outputscale)
+    for c in (11, 17):
+        M = _dev(rng.standard_normal((n, c)))
+        ref = Krows @ _host(M) + w.noise * _host(M)[rows]
+        scale = np.max(np.abs(ref))
+        ctx.bbmm_setup(_problem(w, inputs.ONTHEFLY))
+        got = _host(ctx.bbmm_kernel_mm(inputs.ONTHEFLY, M))[rows]
+        assert np.max(np.abs(got - ref)) < 1e-4 * scale, ("on the fly", c)
+        for tri in (0, 1):
+            try:
+                ctx.bbmm_tune("khat_sym", tri)
+                ctx.bbmm_setup(_problem(w, inputs.MATERIALISED))
+                ctx.bbmm_build_khat()
+                got = _host(ctx.bbmm_kernel_mm(inputs.MATERIALISED, M))[rows]
+            finally:
+                ctx.bbmm_tune("khat_sym", 0)
+            assert np.max(np.abs(got - ref)) < 1e-4 * scale, ("triangle" if tri else "whole matrix", c)
+
+
 # ------------------------------------- on-the-fly product, tile pairs once -----
 @pytest.mark.parametrize("n", [300, 512, 523, 1030, 1600, 2100, 4200])
 @pytest.mark.parametrize("c", [1, 11, 12, 13, 16])
