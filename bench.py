@@ -33,7 +33,7 @@ MFMA_F64_PEAK_TFLOPS = 78.6    # MI355X dense fp64 matrix, published
 FP64_VALU_PEAK_TFLOPS = 78.6   # MI355X fp64 vector, published
 # HBM bytes per k_mm_mat launch at n = 50000 from rocprofv3 FETCH_SIZE / WRITE_SIZE, each scaled by a
 # 1 GiB copy (profiles/k_mm_mat_cfg3_n50000_hbm_counters.txt); only valid for that workload.
-MEASURED_TRAFFIC_MAT_N50000 = 10.425e9
+MEASURED_TRAFFIC_MAT_N50000 = 10.141e9
 # HBM bytes per SGPR product (both k_mm_mat launches) at n = 500000, m = 1024, measured the same way
 # (profiles/k_mm_mat_cfg5_n500000_sgpr_hbm_counters.txt); only valid for that workload.
 MEASURED_TRAFFIC_SGPR_N500000_M1024 = 4.261e9
