@@ -66,17 +66,28 @@ __device__ inline f32x4 fix_diag(f32x4 r2, int lane) {
 }
 
 // --------------------------------------------------------- materialise K_hat --
-// One wave: column block jb (16 columns) x 4 row blocks; each tile is written at its
-// transposed position so a wave's stores cover 256 contiguous bytes per K_hat row.
+// One wave: column block jb (16 columns) x 4 row blocks, each tile kept for its transposed position
+// (K is symmetric), so the wave owns 16 rows x 64 adjacent columns of K_hat.  The four tiles pass
+// through a 16 x 64 LDS area of the wave and come back one row per 16 lanes: every store
+// instruction then writes 4 rows x 256 contiguous bytes (straight from the accumulator layout it
+// would write 16 rows x 64 bytes, which the memory system takes at 2.5 TB/s only).
+constexpr int BK_TLD = 68;   // floats per row of the wave's area (64 + 4: both accesses conflict-free)
+
 template <int KIND, int KK>
 __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa,
                                                      const float* __restrict__ Xb,
                                                      const float* __restrict__ sq, int n, int np,
                                                      int pw, int tri, float outputscale,
                                                      float noise, float* __restrict__ Khat) {
+  __shared__ __align__(16) float T[4][16 * BK_TLD];
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int jb = blockIdx.y * 4 + wave;
   int jc = lane & 15, g = lane >> 4;
+  // triangular storage: panel P keeps rows [0, (P+1) pw) only (pw is a multiple of 64, so the four
+  // row blocks of this wave lie in one panel)
+  int col0 = blockIdx.x * 64;
+  if (tri && jb * 16 >= (col0 / pw + 1) * pw) return;
+  float* Tw = T[wave];
   float b[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) b[kk] = Xb[((size_t)jb * KK + kk) * 64 + lane];
@@ -85,8 +96,6 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     int ib = blockIdx.x * 4 + u;
-    // triangular storage: panel P keeps rows [0, (P+1) pw) only
-    if (tri && jb * 16 >= (ib * 16 / pw + 1) * pw) continue;
     float a[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
@@ -102,12 +111,20 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
       if (i >= n || j >= n) v = 0.f;
       out[r] = v;
     }
-    // column panels of width pw, each row-major (pw == np: plain row-major); the panels of the
-    // triangular storage follow each other without the rows they leave out
-    int col = ib * 16 + g * 4;
-    size_t P = (size_t)(col / pw);
-    size_t poff = tri ? (size_t)pw * pw * (P * (P + 1) / 2) : P * np * pw;
-    *(f32x4*)(Khat + poff + (size_t)j * pw + (size_t)(col % pw)) = out;
+    // K_hat[row j][columns 16 u + 4 g .. + 3 of the wave's 64]
+    *(f32x4*)(Tw + jc * BK_TLD + 16 * u + 4 * g) = out;
+  }
+  __builtin_amdgcn_wave_barrier();   // (a wave's LDS operations execute in order)
+  // column panels of width pw, each row-major (pw == np: plain row-major); the panels of the
+  // triangular storage follow each other without the rows they leave out
+  size_t P = (size_t)(col0 / pw);
+  size_t poff = tri ? (size_t)pw * pw * (P * (P + 1) / 2) : P * np * pw;
+  float* dst = Khat + poff + (size_t)(col0 % pw) + (size_t)(4 * jc);
+#pragma unroll
+  for (int s4 = 0; s4 < 4; ++s4) {
+    int row = 4 * s4 + g;
+    f32x4 v = *(const f32x4*)(Tw + row * BK_TLD + 4 * jc);
+    __builtin_nontemporal_store(v, (f32x4*)(dst + (size_t)(jb * 16 + row) * pw));
   }
 }
 
