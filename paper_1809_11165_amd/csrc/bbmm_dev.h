@@ -188,7 +188,8 @@ int launch_mm_mat(hipStream_t s, const float* Khat, const double* D4, double* Vp
 int launch_mm_otf(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
                   const double* D4, double* Vp, int np, int ld, int c, int nsplit, const DevState* st);
 // The same product with every pair of tiles (I, J), (J, I) evaluated once and used for both of its
-// contributions; ld = 16 only.  Work lists as for launch_mm_sym, with panels of BBMM_OTF_PANEL columns.
+// contributions; ld = 16 and KK <= 8 only (returns 1 otherwise).  Work lists as for launch_mm_sym, with
+// panels of BBMM_OTF_PANEL columns.
 #define BBMM_OTF_PANEL 512
 int launch_mm_otf_tri(hipStream_t s, int kernel, int KK, const float* Xa, const float* Xb, const float* sq,
                       const double* D4, double* Vp, int np, int cols, const MmPiece* pieces,
