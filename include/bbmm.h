@@ -166,9 +166,10 @@ int bbmm_destroy(bbmm_ctx* ctx);
 const char* bbmm_last_error(const bbmm_ctx* ctx);
 
 /* Tuning knobs for experiments (all have sensible defaults):
- *   "mat_wgs"    number of workgroups a materialised product is dealt out to (default: a whole
- *                number per column strip of K_hat, close to one per compute unit, else one per
- *                compute unit; clamped to [strips, 60 * strips], strips = column strips of K_hat)
+ *   "mat_wgs"    number of workgroups a materialised product is dealt out to (default: one per
+ *                compute unit; for a block of at most 12 columns a whole number per column strip
+ *                of K_hat close to that; clamped to [strips, 60 * strips], strips = column strips
+ *                of K_hat)
  *   "otf_split"  number of row chunks an on-the-fly product is split into (with "otf_sym": number
  *                of workgroups of each of its two launches, default two per compute unit)
  *   "otf_sym"    1 (default): an on-the-fly product of at most 16 columns over at most 32 input

@@ -69,8 +69,8 @@ struct bbmm_ctx {
   TriLists sym;                              // ... from the stored triangle (panels of 1024 columns)
   TriLists otft;                             // ... on the fly from X (panels of 512 columns)
   int64_t otf_sym = 1;                       // on-the-fly product with each tile pair evaluated once (<= 16 columns, d <= 32): 0 never, 1 from kOtfSymMinRows rows on, 2 always
-  // balanced plans of the materialised product for 16- and 32-wide blocks (index 0 / 1)
-  int plan_np = 0, plan_wgs[2] = {0, 0};
+  // plans of the materialised product: 16- and 32-column blocks (index 0 / 1), 16-column block with at most 12 columns in use (2)
+  int plan_np = 0, plan_wgs[3] = {0, 0, 0};
   int64_t plan_tune = -1;
   // SGPR: plans of the two streaming products per block width: [v] = A (rows np, columns mp),
   // [2 + v] = A^T (rows mp, columns np)
@@ -81,7 +81,7 @@ struct bbmm_ctx {
   int ev_iters = 0;                          // iterations covered by the last timed run
 
   Buf Xa, Xb, Xs, X4, sq, Khat, L, delta, U, R, V, Z0, D4, Vp, partial, gpartial, alpha, beta, resid, st,
-      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[2], nseg[2], 
+      tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[3], nseg[3], 
       KUU, Gm, Ginv, Kux, AT, A, qdiag, Tp, T4, sgplan[4], sgnseg[4],
       Ua, Ub, Us, U4, usq, TU, TW, BU, BW, dkops;
   DevState* h_st = nullptr;   // pinned
@@ -176,13 +176,17 @@ int split_by_fill(const bbmm_ctx* c, int strips, int want_wgs, double min_fill) 
 // (strip, row step) units out evenly, so whole rounds of num_cus workgroups leave no tail.
 // Bounds: at least one workgroup per strip (a run then spans at most two strips), at most
 // kMaxSplit partial slots per strip (checked when the plan is laid out), at most one workgroup per unit.
-int mat_wgs_of(const bbmm_ctx* c, int ld) {
+int mat_wgs_of(const bbmm_ctx* c, int ld, bool narrow) {
   int cols_per_wg = (ld == 16) ? 1024 : 512;
   int strips = (c->np + cols_per_wg - 1) / cols_per_wg;
   long long units = (long long)strips * (c->np / 16);
   long long w = (c->mat_wgs > 0) ? c->mat_wgs
                                  : (long long)c->num_cus * ((strips + c->num_cus - 1) / c->num_cus);
-  if (c->mat_wgs <= 0 && strips <= c->num_cus) {
+  if (c->mat_wgs <= 0 && narrow && strips <= c->num_cus) {
+    // (Blocks of at most 12 columns only, whose product is the most memory-bound.  With 13..16
+    // columns one workgroup per unit is 1-5 % faster again, and the 32-column product is bound by the
+    // fp64 matrix pipe and wants every unit: 2.38 ms on 256 workgroups against 3.07 ms on 196 at
+    // n = 50 000.)
     // Measured (n = 5 000 ... 50 000): a whole number of workgroups per strip (no run crosses a strip
     // boundary and pays two prologues) beats one workgroup per unit by 2 % at n = 50 000 and by
     // 5-11 % below it, where short runs do best on about 0.8 of the units; a matrix of a few
@@ -246,9 +250,10 @@ int make_plan(bbmm_ctx* c, int rows_p, int cols_p, int ld, int wgs, int slot_cap
 int ensure_mat_plans(bbmm_ctx* c) {
   if (c->plan_np == c->np && c->plan_tune == c->mat_wgs) return BBMM_OK;
   HIPCHK(c, hipStreamSynchronize(c->stream));   // earlier launches may still read the old plans
-  for (int v = 0; v < 2; ++v) {
-    int ld = v ? 32 : 16;
-    int wgs = mat_wgs_of(c, ld);
+  // plans: 0 = 16-column block, 1 = 32-column block, 2 = 16-column block with at most 12 columns in use
+  for (int v = 0; v < 3; ++v) {
+    int ld = (v == 1) ? 32 : 16;
+    int wgs = mat_wgs_of(c, ld, v == 2);
     int rc = make_plan(c, c->np, c->np, ld, wgs, kMaxSplit, c->plan[v], c->nseg[v], nullptr);
     if (rc) return rc;
     c->plan_wgs[v] = wgs;
@@ -572,11 +577,11 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     }
     int rc = ensure_mat_plans(c);
     if (rc) return rc;
-    int v = (ld == 32) ? 1 : 0;
+    int v = (ld == 32) ? 1 : (cc <= 12 ? 2 : 0);
     if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
                       ptr<MmPlan>(c->plan[v]), c->plan_wgs[v], ptr<DevState>(c->st), c->khat_pw, c->np, cc))
       return fail(c, BBMM_EINVAL, "unsupported block width");
-    *shape = VpShape{0, ptr<int>(c->nseg[v]), v ? 512 : 1024};
+    *shape = VpShape{0, ptr<int>(c->nseg[v]), v == 1 ? 512 : 1024};
     *scaleV = 1.0;
     *addD = 0.0;
   } else if (mode == BBMM_MODE_ONTHEFLY && (c->otf_sym == 2 || (c->otf_sym == 1 && c->np >= kOtfSymMinRows)) &&
@@ -925,8 +930,8 @@ int bbmm_destroy(bbmm_ctx* c) {
   Buf* bufs[] = {&c->Xa, &c->Xb, &c->Xs, &c->X4, &c->sq, &c->Khat, &c->L, &c->delta, &c->U, &c->R, &c->V,
                  &c->Z0, &c->D4, &c->Vp, &c->partial, &c->gpartial, &c->alpha, &c->beta, &c->resid, &c->st, &c->sym.pieces, &c->sym.first0, &c->sym.first1, &c->sym.base, &c->sym.tot, &c->otft.pieces, &c->otft.first0,
                  &c->otft.first1, &c->otft.base, &c->otft.tot, &c->tmpA,
-                 &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig, &c->plan[0], &c->plan[1], &c->nseg[0],
-                 &c->nseg[1], &c->KUU, &c->Gm, &c->Ginv, &c->Kux, &c->AT, &c->A, &c->qdiag, &c->Tp, &c->T4,
+                 &c->tmpB, &c->SA, &c->SB, &c->u0v, &c->dkpartial, &c->eig, &c->plan[0], &c->plan[1], &c->plan[2], &c->nseg[0],
+                 &c->nseg[1], &c->nseg[2], &c->KUU, &c->Gm, &c->Ginv, &c->Kux, &c->AT, &c->A, &c->qdiag, &c->Tp, &c->T4,
                  &c->sgplan[0], &c->sgplan[1], &c->sgplan[2], &c->sgplan[3], &c->sgnseg[0], &c->sgnseg[1],
                  &c->sgnseg[2], &c->sgnseg[3], &c->Ua, &c->Ub, &c->Us, &c->U4, &c->usq, &c->TU, &c->TW, &c->BU,
                  &c->BW, &c->dkops};
