@@ -387,6 +387,59 @@ def test_tridiag_eig_batched_against_lapack(ctx, m):
         assert got == pytest.approx(ref, rel=1e-9, abs=1e-11)
 
 
+def test_tridiag_eig_on_hard_matrices(ctx):
+    # the cases the QR iteration's bookkeeping has to get right: several exact and near splits (also
+    # adjacent ones and one at the bottom), a graded matrix, and a Lanczos tridiagonal run long enough
+    # without reorthogonalisation to hold near-duplicate ("ghost") eigenvalues
+    import scipy.linalg as sla
+    rng = np.random.default_rng(12)
+    m = 96
+    mats = []
+    d0 = rng.uniform(0.5, 3.0, m)
+    o0 = rng.uniform(0.05, 0.4, m - 1)
+    o1 = o0.copy()
+    o1[[4, 5, 30, 31, 32, 70, m - 2]] = 0.0
+    mats.append((d0, o1))
+    o2 = o0.copy()
+    o2[[10, 11, 50]] = 1e-18                         # below eps * (|a_i| + |a_i+1|): treated as a split
+    o2[[20, 60]] = 1e-9                              # small but not negligible
+    mats.append((d0, o2))
+    g = np.logspace(-8, 4, m)                        # graded: entries over twelve orders of magnitude
+    mats.append((g * rng.uniform(1.0, 2.0, m), 0.3 * np.sqrt(g[:-1] * g[1:])))
+    lam = np.concatenate([np.linspace(0.1, 1.0, 380), [50.0, 80.0, 120.0, 200.0]])
+    q = rng.standard_normal(lam.size)
+    q /= np.linalg.norm(q)
+    qp, beta = np.zeros_like(q), 0.0
+    al, be = [], []
+    for _ in range(m):                               # plain Lanczos on diag(lam)
+        v = lam * q - beta * qp
+        alpha = v @ q
+        v -= alpha * q
+        beta = np.linalg.norm(v)
+        al.append(alpha)
+        be.append(beta)
+        qp, q = q, v / beta
+    mats.append((np.array(al), np.array(be[:-1])))
+    lam_l = sla.eigh_tridiagonal(mats[-1][0], mats[-1][1], eigvals_only=True)
+    assert np.min(np.diff(lam_l)) < 1e-8 * lam_l[-1]    # the case does contain ghosts
+    diag = np.stack([a for a, _ in mats])
+    off = np.stack([b for _, b in mats])
+    vals, first = ctx.bbmm_tridiag_eig_batched(diag, off)
+    for b in range(len(mats)):
+        lam_ref, vec = sla.eigh_tridiagonal(diag[b], off[b])
+        order = np.argsort(vals[b])
+        scale = np.max(np.abs(lam_ref))
+        assert np.max(np.abs(vals[b][order] - lam_ref)) < 1e-12 * scale, b
+        assert np.sum(first[b] ** 2) == pytest.approx(1.0, rel=1e-10)
+        # quadrature functionals, which sum the weights of a cluster: e_1^T f(T) e_1 for f = log, 1/x
+        pos = lam_ref > 0
+        assert np.all(pos)
+        for f in (np.log, lambda x: 1.0 / x):
+            got = np.sum(first[b] ** 2 * f(vals[b]))
+            ref = np.sum(vec[0] ** 2 * f(lam_ref))
+            assert got == pytest.approx(ref, rel=1e-8, abs=1e-10), b
+
+
 # ------------------------------------------------------- derivative pass -------
 @pytest.mark.parametrize("kernel,ard,n,d", CASES)
 def test_dk_traces_match_oracle_formulas(ctx, kernel, ard, n, d):
