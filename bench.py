@@ -5,7 +5,7 @@ One "step" is one full bbmm_solve_logdet_grad call (preconditioner, probes, mBCG
 log-det, derivative traces) on the n = 50,000, d = 16, t = 10 Matern-5/2 ARD workload
 (rank-20 preconditioner, 50 mBCG iterations), inputs resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode sym|mat|otf|sgpr] [--config 3|2] [--n N] [--no-cpu]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--mode sym|mat|otf|sgpr] [--config 3|2|4] [--n N] [--no-cpu]
 
 The default mode keeps the fp32 K_hat materialised as its upper triangle (half the HBM bytes per
 product, every tile used for both of its contributions; the product is then bound by the fp64
@@ -13,7 +13,9 @@ matrix rate).  --mode mat keeps the whole matrix (HBM-bound product), --mode otf
 from X in every product.  --mode sgpr measures the widened path instead (config 5: subset-of-regressors covariance,
 n = 500,000, m = 1024 inducing inputs, d = 8, t = 10, rank-10 preconditioner, 50 iterations);
 the default line is the exact-GP workload above.  --config 2 runs the second roofline point instead
-(RBF, n = 10,000, d = 8, rank-10 preconditioner, stop at a relative residual of 1e-2 or 50 iterations).
+(RBF, n = 10,000, d = 8, rank-10 preconditioner, stop at a relative residual of 1e-2 or 50 iterations),
+--config 4 the largest exact-GP workload (RBF on 20 Gaussian clusters, n = 200,000, d = 8, t = 16, rank-20
+preconditioner, 100 iterations; on the fly unless --mode says otherwise).
 """
 import argparse
 import json
@@ -92,11 +94,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--mode", choices=["sym", "mat", "otf", "sgpr"], default="sym")
-    ap.add_argument("--config", type=int, choices=[2, 3], default=3,
-                    help="exact-GP workload: 3 (default, the headline) or 2 (n = 10000, RBF, tolerance stop)")
+    ap.add_argument("--mode", choices=["sym", "mat", "otf", "sgpr"], default=None,
+                    help="default: sym (otf for --config 4)")
+    ap.add_argument("--config", type=int, choices=[2, 3, 4], default=3,
+                    help="exact-GP workload: 3 (default, the headline), 2 (n = 10000, RBF, tolerance stop) "
+                         "or 4 (n = 200000, RBF, 17 columns, 100 iterations)")
     ap.add_argument("--n", type=int, default=None,
-                    help="points (default 50000; 10000 for --config 2; 500000 for --mode sgpr)")
+                    help="points (default 50000; 10000 for --config 2; 200000 for --config 4; 500000 for --mode sgpr)")
     ap.add_argument("--m", type=int, default=1024, help="inducing inputs (--mode sgpr)")
     ap.add_argument("--cpu-sample", type=int, default=10000)
     ap.add_argument("--no-cpu", action="store_true")
@@ -105,6 +109,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)")
+    if args.mode is None:
+        args.mode = "otf" if args.config == 4 else "sym"
 
     import torch
     from paper_1809_11165_amd import binding, inputs
@@ -114,7 +120,7 @@ def main():
     mode = {"mat": inputs.MATERIALISED, "sym": inputs.MATERIALISED, "otf": inputs.ONTHEFLY,
             "sgpr": inputs.SGPR}[args.mode]
     if args.n is None:
-        args.n = 500000 if mode == inputs.SGPR else (50000 if args.config == 3 else 10000)
+        args.n = 500000 if mode == inputs.SGPR else {3: 50000, 2: 10000, 4: 200000}[args.config]
     w = inputs.make(5, n=args.n, m=args.m) if mode == inputs.SGPR else inputs.make(args.config, n=args.n)
     prob = binding.problem_from_workload(w, mode)
     ctx = binding.Context(0)
@@ -151,6 +157,9 @@ def main():
         workload = ("config2: exact GP, RBF, n=%d, d=8, t=10, k=10, mBCG to a relative residual of 1e-2 or "
                     "50 iterations" % n)
         metric = "mBCG solve+logdet+grad ms at n=10k,t=10 (config 2)"
+    if args.config == 4:
+        workload = ("config4: exact GP, RBF, 20 Gaussian clusters, n=%d, d=8, t=16, k=20, 100 mBCG iterations" % n)
+        metric = "mBCG solve+logdet+grad ms at n=200k,t=16 (config 4)"
     mode_name = "materialised fp32 K_hat" if mode == inputs.MATERIALISED else "on-the-fly tiles"
     if mode == inputs.SGPR:
         # one product = the root A (n x m fp32) streamed once in each layout, the block in and out,
@@ -206,7 +215,7 @@ def main():
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
                     "kernel": "k_mm_otf_tri (tiles on and above the diagonal, each used twice; two launches per product)"
-                              if c <= 16 else "k_mm_otf",
+                              if (c <= 16 and d <= 32 and -(-n // 256) * 256 >= 12288) else "k_mm_otf",
                     "avg_launch_ms": mm_ms, "launches": mm_launches,
                     "pairs_per_s": n * n / (mm_ms * 1e-3),
                     "mixed_floor_ms": mixed_floor_ms, "frac_of_mixed_floor": mixed_floor_ms / mm_ms}

@@ -393,7 +393,9 @@ def e1_logT_e1(dg: np.ndarray, off: np.ndarray) -> float:
     """e_1^T log(T) e_1 = sum_m V[0,m]^2 log(lambda_m)  (App. B, log-det paragraph)."""
     if dg.shape[0] == 0:
         return 0.0
-    lam, vec = sla.eigh_tridiagonal(dg, off)
+    # (LAPACK's QL/QR driver: the default MRRR driver gives up on Lanczos tridiagonals that hold
+    # near-duplicate eigenvalues, which long CG runs produce)
+    lam, vec = sla.eigh_tridiagonal(dg, off, lapack_driver="stev")
     return float(np.sum(vec[0, :] ** 2 * np.log(lam)))
 
 

@@ -414,6 +414,35 @@ def test_e1_logT_e1_diagonal_and_2x2():
 
 
 # ----------------------- estimators: unbiased by exhaustive enumeration ------
+def test_e1_logT_e1_is_gauss_quadrature_also_with_ghost_eigenvalues():
+    # App. B, log-det paragraph: e_1^T log(T_m) e_1 is the m-node Gauss rule for q^T log(A) q.  On
+    # A = diag(lambda) the exact value is sum_i q_i^2 log(lambda_i); plain Lanczos run far past
+    # convergence duplicates the outlying eigenvalues ("ghosts"), which must not change the value
+    # (and is the kind of tridiagonal LAPACK's MRRR driver can fail on)
+    rng = np.random.default_rng(12)
+    lam = np.concatenate([np.linspace(0.1, 1.0, 380), [50.0, 80.0, 120.0, 200.0]])
+    q0 = rng.standard_normal(lam.size)
+    q0 /= np.linalg.norm(q0)
+    exact = np.sum(q0 ** 2 * np.log(lam))
+    for m, tol in ((20, 1e-6), (40, 1e-12), (96, 1e-12), (150, 1e-12)):
+        q, qp, beta = q0.copy(), np.zeros_like(q0), 0.0
+        al, be = [], []
+        for _ in range(m):
+            v = lam * q - beta * qp
+            alpha = v @ q
+            v -= alpha * q
+            beta = np.linalg.norm(v)
+            al.append(alpha)
+            be.append(beta)
+            qp, q = q, v / beta
+        dg, off = np.array(al), np.array(be[:-1])
+        if m >= 96:
+            import scipy.linalg as sla
+            ev = sla.eigh_tridiagonal(dg, off, eigvals_only=True, lapack_driver="stev")
+            assert np.min(np.diff(ev)) < 1e-9 * ev[-1]       # ghosts are present
+        assert abs(O.e1_logT_e1(dg, off) - exact) < tol, m
+
+
 def test_logdet_and_trace_estimators_average_exactly_over_all_rademacher_probes():
     n, k = 7, 3
     w = inputs.tiny(n, 2, kernel=inputs.RBF, ard=True, noise=0.6, t=1, k=k)
