@@ -65,6 +65,17 @@ __device__ inline f32x4 fix_diag(f32x4 r2, int lane) {
   return r2;
 }
 
+// The same on a condition that is uniform over the wave and true for one tile in thousands: kept
+// as a real branch (the empty volatile statement cannot be executed speculatively); turned into
+// selects it costs two vector instructions per value in every tile.
+__device__ __forceinline__ f32x4 fix_diag_if(bool diag_tile, f32x4 r2, int lane) {
+  if (diag_tile) {
+    asm volatile("");
+    r2 = fix_diag(r2, lane);
+  }
+  return r2;
+}
+
 // --------------------------------------------------------- materialise K_hat --
 // One wave: column block jb (16 columns) x 4 row blocks, each tile kept for its transposed position
 // (K is symmetric), so the wave owns 16 rows x 64 adjacent columns of K_hat.  The four tiles pass
@@ -101,7 +112,7 @@ __global__ __launch_bounds__(256) void k_build_khat(const float* __restrict__ Xa
     for (int kk = 0; kk < KK; ++kk) a[kk] = Xa[((size_t)ib * KK + kk) * 64 + lane];
     f32x4 sqi = *(const f32x4*)(sq + ib * 16 + g * 4);
     f32x4 r2 = tile_r2<KK>(a, b, sqi, sqj);
-    if (ib == jb) r2 = fix_diag(r2, lane);
+    r2 = fix_diag_if(ib == jb, r2, lane);
     f32x4 out;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -334,7 +345,7 @@ __global__ __launch_bounds__(256) void k_mm_otf(const float* __restrict__ Xa,
 #pragma unroll
     for (int jb = 0; jb < NJ; ++jb) {
       f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
-      if (ib == jb0 + jb) r2 = fix_diag(r2, lane);
+      r2 = fix_diag_if(ib == jb0 + jb, r2, lane);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         double e = (double)unit_kernel<KIND>(r2[r]);
@@ -468,7 +479,7 @@ __global__ __launch_bounds__(256, 2) void k_mm_otf_tri(const float* __restrict__
 #pragma unroll
           for (int jb = 0; jb < OT_NJ; ++jb) {
             f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
-            if (!DUAL && ib == jb0 + jb) r2 = fix_diag(r2, lane);
+            if (!DUAL) r2 = fix_diag_if(ib == jb0 + jb, r2, lane);
             f32x4 e;
 #pragma unroll
             for (int r = 0; r < 4; ++r) e[r] = unit_kernel<KIND>(r2[r]);
@@ -605,7 +616,7 @@ __device__ __forceinline__ void dk_step(int ib, int jb0, int lane, int TS, const
       wt = (ib < jbg) ? 1.f : ((ib == jbg) ? 0.5f : 0.f);
     }
     f32x4 r2 = tile_r2<KK>(a, b[jb], sqi, sqj[jb]);
-    if (NEAR && ib == jb0 + jb) r2 = fix_diag(r2, lane);
+    if (NEAR) r2 = fix_diag_if(ib == jb0 + jb, r2, lane);
     f32x4 ts, tq;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
