@@ -829,6 +829,15 @@ int stage_dk_sgpr(bbmm_ctx* c, int ld, int t) {
   return BBMM_OK;
 }
 
+// Square of the factor (times 1/l) that the tile kernels' coordinates are scaled by, chosen so that
+// the kernel function needs no constant on the distance: RBF k/s = 2^(-r2) with c0 = log2(e)/2,
+// Matern-5/2 k/s = poly(a) 2^(-a), a = sqrt(r2), with c0 = 5 log2(e)^2.  Squared distances of the
+// derivative pass come out c0 times (Delta/l)^2, which finish_dk divides out.
+double coord_scale_sq(int kernel) {
+  const double log2e = 1.4426950408889634074;
+  return (kernel == BBMM_KERNEL_RBF) ? 0.5 * log2e : 5.0 * log2e * log2e;
+}
+
 // Turns the raw accumulators of the derivative pass into trace[h], quad[h] (host side).
 void finish_dk(const bbmm_ctx* c, double* trace, double* quad) {
   const DevState* st = c->h_st;
@@ -836,8 +845,8 @@ void finish_dk(const bbmm_ctx* c, double* trace, double* quad) {
   int ard = nl > 1;
   int nls_dev = ard ? c->dp : 1;
   double s = c->prob.outputscale;
-  // inputs were scaled by sqrt(c0)/l (RBF, c0 = log2(e)/2) or 1/l (Matern), see HypArgs::xscale
-  double c0 = (c->prob.kernel == BBMM_KERNEL_RBF) ? 0.5 * 1.4426950408889634074 : 1.0;
+  // inputs were scaled by sqrt(c0)/l, see coord_scale_sq and HypArgs::xscale
+  double c0 = coord_scale_sq(c->prob.kernel);
   for (int h = 0; h < nl; ++h) {
     double f = s / (c0 * c->ls[h]);
     trace[h] = f * st->dk_out[2 * h];
@@ -1017,7 +1026,7 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
   c->mp = ((c->m + 255) / 256) * 256;
 
   memset(&c->hyp, 0, sizeof(HypArgs));
-  double c0 = (in->kernel == BBMM_KERNEL_RBF) ? 0.5 * 1.4426950408889634074 : 1.0;
+  double c0 = coord_scale_sq(in->kernel);
   for (int dim = 0; dim < c->d; ++dim) {
     double l = (in->n_lengthscale == 1) ? c->ls[0] : c->ls[dim];
     c->hyp.inv_ls[dim] = 1.0 / l;

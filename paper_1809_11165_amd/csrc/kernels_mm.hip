@@ -44,7 +44,10 @@ __device__ inline double mfma4d(double a, double b, double c) {
   return __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, c, 0, 0, 0);
 }
 
-// r2 tile: |xs_i - xs_j|^2 for a 16 x 16 tile, clamped at 0.
+// r2 tile: |xs_i - xs_j|^2 for a 16 x 16 tile.  The expansion |x|^2 + |x'|^2 - 2 x.x' can come out
+// a rounding error below zero for near-identical points: the absolute value is taken (as good a
+// guess as a clamp at zero for what is rounding noise either way, and free: an operand modifier
+// of the instruction that consumes it).
 template <int KK>
 __device__ inline f32x4 tile_r2(const float (&a)[KK], const float (&b)[KK], f32x4 sqi, float sqj) {
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -52,7 +55,7 @@ __device__ inline f32x4 tile_r2(const float (&a)[KK], const float (&b)[KK], f32x
   for (int kk = 0; kk < KK; ++kk) acc = mfma16(a[kk], b[kk], acc);
   f32x4 r2;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) r2[r] = fmaxf(acc[r] + (sqi[r] + sqj), 0.f);
+  for (int r = 0; r < 4; ++r) r2[r] = __builtin_fabsf(acc[r] + (sqi[r] + sqj));
   return r2;
 }
 
