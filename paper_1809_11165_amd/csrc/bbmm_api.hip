@@ -672,13 +672,14 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld, const float* warm = nullpt
   // wave where n allows it (a trip costs a memory round trip; more waves overlap more of them)
   int nb_zd = std::max(nb, std::min((c->n / 16 + 3) / 4, (c->zd_blocks > 0 ? (int)c->zd_blocks : 16) * c->num_cus));
   size_t blk = (size_t)c->np * ld;
-  launch_fill_f64(s, ptr<double>(c->U), blk, 0.0);
-  launch_fill_f64(s, ptr<double>(c->D4), blk, 0.0);
-  launch_fill_bytes0(s, c->alpha.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
-  launch_fill_bytes0(s, c->beta.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
-  launch_fill_bytes0(s, c->resid.p, sizeof(double) * BBMM_MAXP * BBMM_MAXC);
-  // done / iters_run live next to each other at the end of DevState
-  launch_fill_bytes0(s, &st->done, 2 * sizeof(int));
+  // U, D, the coefficient histories and done / iters_run (next to each other at the end of
+  // DevState), zeroed by one launch
+  {
+    size_t hist = (size_t)2 * BBMM_MAXP * BBMM_MAXC;   // words of one history of doubles
+    ZeroSegs z = {{c->U.p, c->D4.p, c->alpha.p, c->beta.p, c->resid.p, &st->done},
+                  {2 * blk, 2 * blk, hist, hist, hist, 2}, 6};
+    launch_fill_multi0(s, z);
+  }
   double noise = c->prob.noise;
   int nb_ur = ur_blocks(c, c->n, ld);
   double* pdv = ptr<double>(c->gpartial);
@@ -757,8 +758,10 @@ int stage_dk(bbmm_ctx* c, int ld, int t) {
   size_t opsz = (size_t)(c->np / 16) * TS * 64;
   float* SA = ptr<float>(c->SA);
   float* SB = ptr<float>(c->SB);
-  launch_fill_f32(s, SA, opsz, 0.f);
-  launch_fill_f32(s, SB, opsz, 0.f);
+  {
+    ZeroSegs z = {{SA, SB}, {opsz, opsz}, 2};
+    launch_fill_multi0(s, z);
+  }
   const double* U = ptr<double>(c->U);
   const double* Z0 = ptr<double>(c->Z0);
   float h = 0.5f / (float)t;

@@ -72,6 +72,13 @@ struct VpShape {
 void launch_fill_f32(hipStream_t s, float* p, size_t count, float v);
 void launch_fill_f64(hipStream_t s, double* p, size_t count, double v);
 void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes);
+// several buffers zeroed by one launch: pointers and sizes in 4-byte words (all 4-byte aligned)
+struct ZeroSegs {
+  void* p[6];
+  size_t words[6];
+  int n;
+};
+void launch_fill_multi0(hipStream_t s, const ZeroSegs& z);
 void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st, double* partial,
                     double* gpartial);
 void launch_prep_x(hipStream_t s, const float* X, int n, int d, int np, int KK, HypArgs hyp,

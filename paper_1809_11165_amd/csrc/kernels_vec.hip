@@ -120,6 +120,18 @@ __global__ void k_fill_u32(unsigned* p, size_t count) {
   for (; i < count; i += stride) p[i] = 0u;
 }
 
+// Zeroes up to six buffers in one launch (sizes in 4-byte words): a launch costs several
+// microseconds whatever it does, which is what a call on a small problem consists of.
+__global__ void k_fill_multi0(ZeroSegs z) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+#pragma unroll 1
+  for (int k = 0; k < z.n; ++k) {
+    unsigned* p = (unsigned*)z.p[k];
+    for (size_t j = i; j < z.words[k]; j += stride) p[j] = 0u;
+  }
+}
+
 // ------------------------------------------------------- input preparation ---
 // Column means of X (fp64): per-block partial sums, last block finishes.
 __global__ __launch_bounds__(VT) void k_colmean(const float* __restrict__ X, int n, int d,
@@ -1248,6 +1260,15 @@ void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes) {
   int nb = (int)((count + 255) / 256);
   if (nb > 4096) nb = 4096;
   k_fill_u32<<<nb, 256, 0, s>>>((unsigned*)p, count);
+}
+
+void launch_fill_multi0(hipStream_t s, const ZeroSegs& z) {
+  size_t most = 0;
+  for (int k = 0; k < z.n; ++k) most = z.words[k] > most ? z.words[k] : most;
+  if (!most) return;
+  int nb = (int)((most + 255) / 256);
+  if (nb > 4096) nb = 4096;
+  k_fill_multi0<<<nb, 256, 0, s>>>(z);
 }
 
 void launch_colmean(hipStream_t s, const float* X, int n, int d, DevState* st, double* partial,
