@@ -11,7 +11,10 @@
 // cycles, v_mfma_f64_4x4x4 16 (the same flop rate); a VALU instruction between fp64 MFMAs adds its
 // own ~5 cycles (no overlap); LDS reads and global loads add nothing; an LDS write adds ~11 cycles
 // per dword (45 per ds_write_b128), wherever it is placed.  At the density of one 8-byte LDS read per
-// 4x4x4 MFMA (16 cycles) the reads are no longer free: ~3 cycles each.
+// 4x4x4 MFMA (16 cycles) the reads are no longer free: ~3 cycles each.  v_exp_f32 and v_sqrt_f32
+// take 9.3 cycles per wave (other vector instructions 5.6), ~10 between MFMAs; fp64 MFMAs that
+// accumulate onto one register issue back to back at the full rate (no wait for the result of the
+// one before); v_mfma_f32_16x16x4 takes 32 cycles.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 typedef double f64x4 __attribute__((ext_vector_type(4)));
@@ -177,6 +180,38 @@ __global__ __launch_bounds__(256) void k(double* out, const float* in, int iters
         asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(q2) : "v"(in + 4 * (lane & 63)));
         m3 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m3, 0, 0, 0);
         asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(q3) : "v"(in + 4 * (lane & 63)));
+      } else if (MODE == 19) {   // 4 independent v_exp_f32 (the transcendental unit)
+        asm volatile("v_exp_f32 %0, %0\n v_exp_f32 %1, %1\n v_exp_f32 %2, %2\n v_exp_f32 %3, %3"
+                     : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
+      } else if (MODE == 20) {   // 4 independent v_sqrt_f32
+        asm volatile("v_sqrt_f32 %0, %0\n v_sqrt_f32 %1, %1\n v_sqrt_f32 %2, %2\n v_sqrt_f32 %3, %3"
+                     : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]));
+      } else if (MODE == 21) {   // 4 mfma f64 16x16x4 + 4 v_exp_f32 interleaved
+        m0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m0, 0, 0, 0);
+        asm volatile("v_exp_f32 %0, %0" : "+v"(f[0]));
+        m1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m1, 0, 0, 0);
+        asm volatile("v_exp_f32 %0, %0" : "+v"(f[1]));
+        m2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m2, 0, 0, 0);
+        asm volatile("v_exp_f32 %0, %0" : "+v"(f[2]));
+        m3 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m3, 0, 0, 0);
+        asm volatile("v_exp_f32 %0, %0" : "+v"(f[3]));
+      } else if (MODE == 22) {   // 4 mfma f64 16x16x4 on ONE accumulator (each waits for the one before)
+        m0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m0, 0, 0, 0);
+        m0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m0, 0, 0, 0);
+        m0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m0, 0, 0, 0);
+        m0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m0, 0, 0, 0);
+      } else if (MODE == 23) {   // ... on TWO accumulators in turn
+        m0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m0, 0, 0, 0);
+        m1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m1, 0, 0, 0);
+        m0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m0, 0, 0, 0);
+        m1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, m1, 0, 0, 0);
+      } else if (MODE == 24) {   // 4 mfma f32 16x16x4 on independent accumulators
+        typedef float f32x4b __attribute__((ext_vector_type(4)));
+        float af = f[4], bf = f[5];
+        q0 = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf, q0, 0, 0, 0);
+        q1 = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf, q1, 0, 0, 0);
+        q2 = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf, q2, 0, 0, 0);
+        q3 = __builtin_amdgcn_mfma_f32_16x16x4f32(af, bf, q3, 0, 0, 0);
       }
     }
   }
@@ -226,6 +261,12 @@ int main() {
   run<15>("16 mfma + 4 ds_write_b128 bunched (group of 20)", out, in, 20);
   run<17>("4 mfma4 + 4 ds_read_b64 broadcast (group of 8)", out, in, 8);
   run<18>("4 mfma4 + 4 ds_read_b64 + 1 ds_read_b128 (group of 9)", out, in, 9);
+  run<19>("v_exp_f32 x4", out, in, 4);
+  run<20>("v_sqrt_f32 x4", out, in, 4);
+  run<21>("4 mfma16 + 4 v_exp_f32 (per group of 8)", out, in, 8);
+  run<22>("mfma_f64_16x16x4 x4 on one accumulator", out, in, 4);
+  run<23>("mfma_f64_16x16x4 x4 on two accumulators in turn", out, in, 4);
+  run<24>("mfma_f32_16x16x4 x4", out, in, 4);
   run<4>("mfma_f64_4x4x4 x4 again", out, in, 4);
   run<3>("mfma_f64_16x16x4 x4 again", out, in, 4);
   hipError_t e = hipGetLastError();
