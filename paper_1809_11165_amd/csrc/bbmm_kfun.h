@@ -39,7 +39,7 @@ __device__ __forceinline__ void unit_kernel_and_weight(float r2, float& e_out, f
     float a = __builtin_amdgcn_sqrtf(r2);
     float e = __builtin_amdgcn_exp2f(-a);
     e_out = fmaf(a, fmaf(a, kMatK2, kMatK1), 1.f) * e;
-    g_out = (5.f / 3.f) * fmaf(a, kMatK1, 1.f) * e;
+    g_out = fmaf(a, (5.f / 3.f) * kMatK1, 5.f / 3.f) * e;
   }
 }
 
