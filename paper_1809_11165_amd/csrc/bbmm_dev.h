@@ -69,7 +69,6 @@ struct VpShape {
 
 // ---- launchers implemented in kernels_vec.hip ---------------------------------------------
 // n x c blocks (U, R, V, Z0, D4, Vp) and the factor L are fp64; kernel matrix and X copies are fp32.
-void launch_fill_f32(hipStream_t s, float* p, size_t count, float v);
 void launch_fill_f64(hipStream_t s, double* p, size_t count, double v);
 void launch_fill_bytes0(hipStream_t s, void* p, size_t bytes);
 // several buffers zeroed by one launch: pointers and sizes in 4-byte words (all 4-byte aligned)

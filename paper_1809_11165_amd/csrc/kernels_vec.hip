@@ -102,12 +102,6 @@ __device__ inline bool reduce_blocks(const double* __restrict__ partial, double*
 }
 
 // ------------------------------------------------------------------ fills ----
-__global__ void k_fill_f32(float* p, size_t count, float v) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (; i < count; i += stride) p[i] = v;
-}
-
 __global__ void k_fill_f64(double* p, size_t count, double v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -1240,13 +1234,6 @@ inline int blocks_for(size_t count, int threads) { return (int)((count + threads
 }  // namespace
 
 // ------------------------------------------------------------------ launchers
-void launch_fill_f32(hipStream_t s, float* p, size_t count, float v) {
-  if (!count) return;
-  int nb = (int)((count + 255) / 256);
-  if (nb > 4096) nb = 4096;
-  k_fill_f32<<<nb, 256, 0, s>>>(p, count, v);
-}
-
 void launch_fill_f64(hipStream_t s, double* p, size_t count, double v) {
   if (!count) return;
   int nb = (int)((count + 255) / 256);
