@@ -50,7 +50,8 @@ enum {
   BBMM_ENOMEM = 2,     /* device allocation failed (e.g. materialised K_hat does not fit) */
   BBMM_ENOTPD = 3,     /* capacitance matrix (or K_UU + jitter I) not positive definite */
   BBMM_ENONFINITE = 4, /* a non-finite value reached a result */
-  BBMM_EHIP = 5        /* a HIP runtime call failed */
+  BBMM_EHIP = 5,       /* a HIP runtime call failed */
+  BBMM_ENOCONV = 6     /* the tridiagonal eigen-solver did not reduce a matrix within its sweep budget */
 };
 
 enum { BBMM_KERNEL_RBF = 0, BBMM_KERNEL_MATERN52 = 1 };
@@ -195,6 +196,9 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *   "zd_blocks"  workgroups per compute unit of the direction update (default 16, at most 64)
  *   "sgpr_wgs1", "sgpr_wgs2"  workgroups of the two streaming products of an SGPR product
  *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build
+ *   "eig_sweeps" trip budget of the tridiagonal eigen-solver per matrix row (sweeps and deflations;
+ *                default 60, at most 1000; about two sweeps per eigenvalue are needed).  A matrix
+ *                not reduced within it makes the call return BBMM_ENOCONV
  *   "time_mm"    1: record HIP events on the context's stream around every K_hat.M launch of
  *                the next mBCG runs (read back with bbmm_mm_timing); 0: off (default)
  * value <= 0 restores the default (for "khat_sym" and "otf_sym" the value is the setting itself).
@@ -261,7 +265,9 @@ int bbmm_mbcg(bbmm_ctx* ctx, int32_t mode, const float* B, int64_t c, float* U,
 /* Eigen-decomposition of `batch` symmetric tridiagonal matrices of size m <= 256
  * (App. B, log-det paragraph): diag is batch x m, off is batch x (m-1) (host).
  * eigvals: host batch x m (ascending not guaranteed), first_row: host batch x m,
- * first_row[b][i] = first component of the unit eigenvector of eigvals[b][i]. */
+ * first_row[b][i] = first component of the unit eigenvector of eigvals[b][i].
+ * 1 <= batch <= 65535.  BBMM_ENOCONV when a matrix is not reduced within the sweep budget
+ * ("eig_sweeps"); the outputs then hold the unfinished state and must not be used. */
 int bbmm_tridiag_eig_batched(bbmm_ctx* ctx, const double* diag, const double* off, int64_t m,
                              int64_t batch, double* eigvals, double* first_row);
 
@@ -269,6 +275,19 @@ int bbmm_tridiag_eig_batched(bbmm_ctx* ctx, const double* diag, const double* of
  * been [y, z_1..z_t] (columns 1..t are used): log|P| + (1/t) sum_i rho0_i e_1^T log(T_i) e_1.
  * logdet: host; slq_terms: host t (optional). */
 int bbmm_slq_logdet(bbmm_ctx* ctx, double* logdet, double* slq_terms);
+
+/* The same estimate from coefficients the caller hands in (App. A, Observation: Lanczos
+ * tridiagonals from the CG coefficients; App. B, log-det paragraph; Eq. (5),(7)):
+ *   T_i[j][j] = 1/alpha_j + beta_(j-1)/alpha_(j-1),  T_i[j-1][j] = sqrt(beta_(j-1))/alpha_(j-1),
+ *   logdet = logdet_precond + (1/t) sum_i rho0[i] e_1^T log(T_i) e_1.
+ * alpha, beta: host p x t doubles, row j = iteration j, column i = probe i (probe columns only, no
+ * y column); rho0: host t (z_i^T P^{-1} z_i); m_valid: host t, size of T_i (coefficients of
+ * iterations >= m_valid[i] are ignored: a column frozen or stopped early), NULL = p for all;
+ * 1 <= p <= 256, 1 <= t <= 31.  logdet: host; slq_terms: host t (either may be NULL, not both).
+ * Needs no bbmm_setup.  BBMM_ENOCONV / BBMM_ENONFINITE as for bbmm_slq_logdet. */
+int bbmm_slq_from_coeffs(bbmm_ctx* ctx, const double* alpha, const double* beta, const double* rho0,
+                         const int64_t* m_valid, int64_t p, int64_t t, double logdet_precond,
+                         double* logdet, double* slq_terms);
 
 /* Derivative products (Eq. (8), App. B): with U = [u_0 .. u_t] (device n x (t+1)) and
  * W = [w_1 .. w_t] (device n x t, w_i = P^{-1} z_i):

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libbbmm.so")
 
 KERNEL_RBF, KERNEL_MATERN52 = 0, 1
 MODE_MATERIALISED, MODE_ONTHEFLY, MODE_SGPR = 0, 1, 2
-OK, EINVAL, ENOMEM, ENOTPD, ENONFINITE, EHIP = 0, 1, 2, 3, 4, 5
+OK, EINVAL, ENOMEM, ENOTPD, ENONFINITE, EHIP, ENOCONV = 0, 1, 2, 3, 4, 5, 6
 MAX_ITERS = 256
 
 EXPORTS = [
@@ -28,7 +28,7 @@ EXPORTS = [
     "bbmm_setup", "bbmm_build_khat", "bbmm_khat_block", "bbmm_sgpr_build", "bbmm_sgpr_root_rows",
     "bbmm_kernel_mm", "bbmm_pivoted_cholesky",
     "bbmm_precond_setup", "bbmm_precond_solve", "bbmm_make_probes", "bbmm_mbcg",
-    "bbmm_tridiag_eig_batched", "bbmm_slq_logdet", "bbmm_dk_traces",
+    "bbmm_tridiag_eig_batched", "bbmm_slq_logdet", "bbmm_slq_from_coeffs", "bbmm_dk_traces",
     "bbmm_predict_mean", "bbmm_predict_var",
 ]
 
@@ -102,6 +102,9 @@ def load_library() -> C.CDLL:
                                              C.c_int64, C.c_int64, C.POINTER(C.c_double),
                                              C.POINTER(C.c_double)]
     lib.bbmm_slq_logdet.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.bbmm_slq_from_coeffs.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                         C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int64, C.c_int64,
+                                         C.c_double, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.bbmm_dk_traces.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_double),
                                    C.POINTER(C.c_double)]
     lib.bbmm_predict_mean.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
@@ -350,14 +353,14 @@ class Context:
                                     _dbl(resid), C.byref(iters)))
         return U, alpha, beta, resid, int(iters.value)
 
-    def bbmm_tridiag_eig_batched(self, diag: np.ndarray, off: np.ndarray):
+    def bbmm_tridiag_eig_batched(self, diag: np.ndarray, off: np.ndarray, _fn=None):
         diag = np.ascontiguousarray(diag, dtype=np.float64)
         batch, m = diag.shape
         off = np.ascontiguousarray(off, dtype=np.float64).reshape(batch, max(m - 1, 0))
         vals, first = np.zeros((batch, m)), np.zeros((batch, m))
         offp = _dbl(off) if m > 1 else None
-        self._ck(self.lib.bbmm_tridiag_eig_batched(self.h, _dbl(diag), offp, m, batch, _dbl(vals),
-                                                   _dbl(first)))
+        fn = _fn if _fn is not None else self.lib.bbmm_tridiag_eig_batched
+        self._ck(fn(self.h, _dbl(diag), offp, m, batch, _dbl(vals), _dbl(first)))
         return vals, first
 
     def bbmm_slq_logdet(self):
@@ -366,6 +369,28 @@ class Context:
         terms = np.zeros(max(t, 1))
         self._ck(self.lib.bbmm_slq_logdet(self.h, C.byref(out), _dbl(terms)))
         return float(out.value), terms[:t]
+
+    def bbmm_slq_from_coeffs(self, alpha: np.ndarray, beta: np.ndarray, rho0: np.ndarray, m_valid=None,
+                             logdet_precond: float = 0.0):
+        """alpha, beta: (p, t) coefficients of the probe columns; rho0: (t,); m_valid: (t,) or None."""
+        alpha = np.ascontiguousarray(alpha, dtype=np.float64)
+        beta = np.ascontiguousarray(beta, dtype=np.float64)
+        rho0 = np.ascontiguousarray(rho0, dtype=np.float64)
+        p, t = alpha.shape
+        if beta.shape != (p, t) or rho0.shape != (t,):
+            raise ValueError("alpha and beta must be (p, t), rho0 (t,)")
+        mv = None
+        mvp = None
+        if m_valid is not None:
+            mv = np.ascontiguousarray(m_valid, dtype=np.int64)
+            if mv.shape != (t,):
+                raise ValueError("m_valid must have t entries")
+            mvp = mv.ctypes.data_as(C.POINTER(C.c_int64))
+        out = C.c_double(0.0)
+        terms = np.zeros(t)
+        self._ck(self.lib.bbmm_slq_from_coeffs(self.h, _dbl(alpha), _dbl(beta), _dbl(rho0), mvp, p, t,
+                                               float(logdet_precond), C.byref(out), _dbl(terms)))
+        return float(out.value), terms
 
     def bbmm_dk_traces(self, U, W):
         n, _, t, _, _, nl = self._shape

@@ -43,10 +43,6 @@ def build(verbose: bool = False) -> str:
             if verbose and out.strip():
                 print(out)
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs)
-    # the stand-alone issue-rate probe (not part of the library) is built along so that it keeps compiling
-    _run([hipcc, "-O3", "--offload-arch=gfx950", "-Wno-unused-value", "-Xclang", "-target-feature", "-Xclang",
-          "-packed-fp32-ops", os.path.join(CSRC, "probes", "issue_rates.hip"),
-          "-o", os.path.join(OBJ_DIR, "issue_rates")])
     return LIB_PATH
 
 

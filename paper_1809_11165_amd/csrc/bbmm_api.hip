@@ -76,6 +76,8 @@ struct bbmm_ctx {
   // [2 + v] = A^T (rows mp, columns np)
   int sg_np = 0, sg_mp = 0, sg_wgs[4] = {0, 0, 0, 0}, sg_slots[4] = {0, 0, 0, 0};
   int64_t sg_tune[2] = {-1, -1};
+  int64_t eig_sweeps = 0;                    // trip budget of the tridiagonal eigen-solver per row (0 = default)
+  bool side_busy = false;                    // work was forked to `side` and its join has not been queued yet
   bool time_mm = false;                      // record HIP events around every product launch
   std::vector<hipEvent_t> ev;                // 2 per iteration, created on demand
   int ev_iters = 0;                          // iterations covered by the last timed run
@@ -130,6 +132,19 @@ T* ptr(const Buf& b) {
 }
 
 int ld_for(int c) { return c <= 16 ? 16 : 32; }
+
+// about two sweeps per eigenvalue are needed; 60 trips per row is far beyond any convergent case
+int eig_sweeps_of(const bbmm_ctx* c) { return c->eig_sweeps > 0 ? (int)c->eig_sweeps : 60; }
+
+// An error return between a fork to the second stream and the queued join leaves kernels running
+// there that read and write context buffers; the next call that may free or refill those buffers
+// waits for them first.
+int drain_side(bbmm_ctx* c) {
+  if (!c->side_busy) return BBMM_OK;
+  c->side_busy = false;
+  HIPCHK(c, hipStreamSynchronize(c->side));
+  return BBMM_OK;
+}
 
 int vec_blocks(int n, int ld) {
   int rpp = BBMM_VEC_THREADS / ld;
@@ -415,7 +430,7 @@ int check_ready(bbmm_ctx* c) {
   if (!c->is_setup) return fail(c, BBMM_EINVAL, "bbmm_setup has not been called");
   hipError_t e = hipSetDevice(c->device);
   if (e != hipSuccess) return fail(c, BBMM_EHIP, std::string("hipSetDevice: ") + hipGetErrorString(e));
-  return BBMM_OK;
+  return drain_side(c);
 }
 
 // Copies the device state to the pinned mirror and waits for the stream.
@@ -437,6 +452,8 @@ int device_status(bbmm_ctx* c) {
   if (s == BBMM_ENOTPD)
     return fail(c, BBMM_ENOTPD, "capacitance matrix sigma^2 I + L^T L (or K_UU + jitter I) is not positive definite");
   if (s == BBMM_ENONFINITE) return fail(c, BBMM_ENONFINITE, "non-finite value in the log-determinant estimate");
+  if (s == BBMM_ENOCONV)
+    return fail(c, BBMM_ENOCONV, "the eigen-solver did not reduce a Lanczos tridiagonal within its sweep budget");
   if (s != 0) return fail(c, s, "device-side failure");
   return BBMM_OK;
 }
@@ -497,6 +514,7 @@ int stage_sgpr_build(bbmm_ctx* c) {
   // hundred small launches): it runs beside it on the context's second stream
   HIPCHK(c, hipEventRecord(c->ev_fork, s));
   HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+  c->side_busy = true;
   if (c->mp > c->m) launch_fill_f64(c->side, ptr<double>(c->Kux), mp * np, 0.0);   // padding rows of every panel
   if (launch_sgpr_kux(c->side, c->prob.X, c->prob.Uind, c->n, c->np, c->m, c->mp, c->dp, c->hyp,
                       ptr<double>(c->Kux)))
@@ -509,6 +527,7 @@ int stage_sgpr_build(bbmm_ctx* c) {
   launch_sgpr_chol(s, ptr<double>(c->KUU), ptr<double>(c->Gm), c->mp, 1e-13 * c->prob.outputscale, st);
   launch_sgpr_trinv(s, ptr<double>(c->Gm), ptr<double>(c->Ginv), c->mp);
   HIPCHK(c, hipStreamWaitEvent(s, c->ev_join, 0));
+  c->side_busy = false;
   // the Cholesky work matrix is free again: it receives G^{-1} in MFMA operand order
   launch_sgpr_root(s, ptr<double>(c->Ginv), ptr<double>(c->KUU), ptr<double>(c->Kux), c->mp, c->np,
                    ptr<float>(c->AT));
@@ -740,7 +759,7 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld, const float* warm = nullpt
 
 int stage_slq(bbmm_ctx* c, hipStream_t s) {
   if (!c->mbcg_done || c->last_t < 1) return fail(c, BBMM_EINVAL, "bbmm_mbcg with at least one probe column must run first");
-  launch_slq(s, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, ptr<DevState>(c->st));
+  launch_slq(s, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, eig_sweeps_of(c), ptr<DevState>(c->st));
   return BBMM_OK;
 }
 
@@ -975,6 +994,7 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   } else if (!strcmp(key, "zd_blocks")) c->zd_blocks = value > 0 ? std::min<int64_t>(value, 64) : 0;
   else if (!strcmp(key, "sgpr_wgs1")) c->sgpr_wgs[0] = value > 0 ? value : 0;
   else if (!strcmp(key, "sgpr_wgs2")) c->sgpr_wgs[1] = value > 0 ? value : 0;
+  else if (!strcmp(key, "eig_sweeps")) c->eig_sweeps = value > 0 ? std::min<int64_t>(value, 1000) : 0;
   else if (!strcmp(key, "time_mm")) c->time_mm = value > 0;
   else return fail(c, BBMM_EINVAL, std::string("unknown tuning key: ") + key);
   return BBMM_OK;
@@ -1005,6 +1025,8 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
   int rc = validate(c, in);
   if (rc) return rc;
   HIPCHK(c, hipSetDevice(c->device));
+  rc = drain_side(c);
+  if (rc) return rc;
   c->prob = *in;
   c->ls.assign(in->lengthscale, in->lengthscale + in->n_lengthscale);
   c->prob.lengthscale = c->ls.data();
@@ -1302,6 +1324,35 @@ int bbmm_predict_var(bbmm_ctx* c, int32_t mode, const float* Xstar, int64_t ns, 
   return BBMM_OK;
 }
 
+// Copies the batch to `work` (device, room for 3 nd + no doubles and `batch` ints), runs the
+// eigen-solver there and copies values, first rows and the per-matrix status (to `status`, host,
+// `batch` ints) back.
+static int run_tridiag_eig(bbmm_ctx* c, double* work, int* status, const double* diag, const double* off,
+                           int64_t m, int64_t batch, double* eigvals, double* first_row) {
+  size_t nd = (size_t)batch * m, no = (size_t)batch * (m > 1 ? m - 1 : 1);
+  double* d_diag = work;
+  double* d_off = d_diag + nd;
+  double* d_val = d_off + no;
+  double* d_vec = d_val + nd;
+  int* d_status = reinterpret_cast<int*>(d_vec + nd);
+  HIPCHK(c, hipMemcpyAsync(d_diag, diag, sizeof(double) * nd, hipMemcpyHostToDevice, c->stream));
+  if (m > 1) HIPCHK(c, hipMemcpyAsync(d_off, off, sizeof(double) * batch * (m - 1), hipMemcpyHostToDevice, c->stream));
+  launch_tridiag_eig(c->stream, d_diag, d_off, (int)m, (int)batch, eig_sweeps_of(c), d_val, d_vec, d_status);
+  HIPCHK(c, hipMemcpyAsync(eigvals, d_val, sizeof(double) * nd, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipMemcpyAsync(first_row, d_vec, sizeof(double) * nd, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipMemcpyAsync(status, d_status, sizeof(int) * (size_t)batch, hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipGetLastError());
+  for (int64_t b = 0; b < batch; ++b)
+    if (status[b] != 0) {
+      char msg[128];
+      snprintf(msg, sizeof msg, "tridiagonal matrix %lld of the batch was not reduced within the sweep budget",
+               (long long)b);
+      return fail(c, BBMM_ENOCONV, msg);
+    }
+  return BBMM_OK;
+}
+
 int bbmm_tridiag_eig_batched(bbmm_ctx* c, const double* diag, const double* off, int64_t m, int64_t batch,
                              double* eigvals, double* first_row) {
   if (!c) return BBMM_EINVAL;
@@ -1309,19 +1360,55 @@ int bbmm_tridiag_eig_batched(bbmm_ctx* c, const double* diag, const double* off,
     return fail(c, BBMM_EINVAL, "bad tridiagonal batch");
   HIPCHK(c, hipSetDevice(c->device));
   size_t nd = (size_t)batch * m, no = (size_t)batch * (m > 1 ? m - 1 : 1);
-  int rc = ensure(c, c->eig, sizeof(double) * (3 * nd + no));
+  int rc = ensure(c, c->eig, sizeof(double) * (3 * nd + no) + sizeof(int) * (size_t)batch);
   if (rc) return rc;
-  double* d_diag = ptr<double>(c->eig);
-  double* d_off = d_diag + nd;
-  double* d_val = d_off + no;
-  double* d_vec = d_val + nd;
-  HIPCHK(c, hipMemcpyAsync(d_diag, diag, sizeof(double) * nd, hipMemcpyHostToDevice, c->stream));
-  if (m > 1) HIPCHK(c, hipMemcpyAsync(d_off, off, sizeof(double) * batch * (m - 1), hipMemcpyHostToDevice, c->stream));
-  launch_tridiag_eig(c->stream, d_diag, d_off, (int)m, (int)batch, d_val, d_vec);
-  HIPCHK(c, hipMemcpyAsync(eigvals, d_val, sizeof(double) * nd, hipMemcpyDeviceToHost, c->stream));
-  HIPCHK(c, hipMemcpyAsync(first_row, d_vec, sizeof(double) * nd, hipMemcpyDeviceToHost, c->stream));
-  HIPCHK(c, hipStreamSynchronize(c->stream));
+  std::vector<int> status((size_t)batch, 0);
+  return run_tridiag_eig(c, ptr<double>(c->eig), status.data(), diag, off, m, batch, eigvals, first_row);
+}
+
+int bbmm_slq_from_coeffs(bbmm_ctx* c, const double* alpha, const double* beta, const double* rho0,
+                         const int64_t* m_valid, int64_t p, int64_t t, double logdet_precond, double* logdet,
+                         double* slq_terms) {
+  if (!c) return BBMM_EINVAL;
+  if (!alpha || !beta || !rho0 || p < 1 || p > BBMM_MAXP || t < 1 || t > BBMM_MAXC - 1 || (!logdet && !slq_terms))
+    return fail(c, BBMM_EINVAL, "bad coefficient arrays (1 <= p <= 256, 1 <= t <= 31)");
+  std::vector<int> mv((size_t)t, (int)p);
+  if (m_valid)
+    for (int64_t i = 0; i < t; ++i) {
+      if (m_valid[i] < 0 || m_valid[i] > p) return fail(c, BBMM_EINVAL, "m_valid entry outside 0..p");
+      mv[(size_t)i] = (int)m_valid[i];
+    }
+  HIPCHK(c, hipSetDevice(c->device));
+  size_t np_ = (size_t)p * t;
+  int rc = ensure(c, c->eig, sizeof(double) * (2 * np_ + 2 * (size_t)t) + sizeof(int) * 2 * (size_t)t);
+  if (rc) return rc;
+  double* d_alpha = ptr<double>(c->eig);
+  double* d_beta = d_alpha + np_;
+  double* d_rho0 = d_beta + np_;
+  double* d_terms = d_rho0 + t;
+  int* d_mv = reinterpret_cast<int*>(d_terms + t);
+  int* d_status = d_mv + t;
+  std::vector<double> terms((size_t)t, 0.0);
+  std::vector<int> status((size_t)t, 0);
+  hipStream_t s = c->stream;
+  HIPCHK(c, hipMemcpyAsync(d_alpha, alpha, sizeof(double) * np_, hipMemcpyHostToDevice, s));
+  HIPCHK(c, hipMemcpyAsync(d_beta, beta, sizeof(double) * np_, hipMemcpyHostToDevice, s));
+  HIPCHK(c, hipMemcpyAsync(d_rho0, rho0, sizeof(double) * (size_t)t, hipMemcpyHostToDevice, s));
+  HIPCHK(c, hipMemcpyAsync(d_mv, mv.data(), sizeof(int) * (size_t)t, hipMemcpyHostToDevice, s));
+  launch_slq_coeffs(s, d_alpha, d_beta, d_rho0, d_mv, (int)t, eig_sweeps_of(c), d_terms, d_status);
+  HIPCHK(c, hipMemcpyAsync(terms.data(), d_terms, sizeof(double) * (size_t)t, hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipMemcpyAsync(status.data(), d_status, sizeof(int) * (size_t)t, hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipStreamSynchronize(s));
   HIPCHK(c, hipGetLastError());
+  double sum = 0.0;
+  for (int64_t i = 0; i < t; ++i) {
+    if (status[(size_t)i] == BBMM_ENOCONV)
+      return fail(c, BBMM_ENOCONV, "the eigen-solver did not reduce a Lanczos tridiagonal within its sweep budget");
+    if (status[(size_t)i] != 0) return fail(c, BBMM_ENONFINITE, "non-finite value in the log-determinant estimate");
+    sum += terms[(size_t)i];
+    if (slq_terms) slq_terms[i] = terms[(size_t)i];
+  }
+  if (logdet) *logdet = logdet_precond + sum / (double)t;
   return BBMM_OK;
 }
 
@@ -1385,6 +1472,7 @@ int bbmm_solve_logdet_grad(bbmm_ctx* c, const bbmm_problem* in, bbmm_result* out
   // they run side by side, the SLQ kernel on the context's second stream.
   HIPCHK(c, hipEventRecord(c->ev_fork, s));
   HIPCHK(c, hipStreamWaitEvent(c->side, c->ev_fork, 0));
+  c->side_busy = true;
   rc = stage_slq(c, c->side);
   if (rc) return rc;
   HIPCHK(c, hipEventRecord(c->ev_join, c->side));
@@ -1393,6 +1481,7 @@ int bbmm_solve_logdet_grad(bbmm_ctx* c, const bbmm_problem* in, bbmm_result* out
   launch_extract_col(s, ptr<double>(c->U), ld, c->n, c->n, 0, out->u0);
   if (out->U) launch_unpack_rows(s, ptr<double>(c->U), ld, c->n, cc, out->U);
   HIPCHK(c, hipStreamWaitEvent(s, c->ev_join, 0));
+  c->side_busy = false;
   rc = fetch_state(c, true);
   if (rc) return rc;
   rc = device_status(c);

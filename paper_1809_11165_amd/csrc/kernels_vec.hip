@@ -1040,14 +1040,16 @@ __global__ __launch_bounds__(VT) void k_zd(int n, double noise, const double* __
 // the top of the unreduced block is therefore not searched for before each sweep but kept from
 // sweep to sweep, and a sweep tests the off-diagonal entries it rewrites as it goes (all of the
 // block's but the last, which the deflation test at the top covers).
-__device__ void tridiag_eig_first_row(double* a, double* b, double* w, int m) {
+// Returns true when every eigenvalue has deflated within `sweeps_per_row` * m trips (sweeps and
+// deflations); false means a[] still holds an unreduced block and must not be used.
+__device__ bool tridiag_eig_first_row(double* a, double* b, double* w, int m, int sweeps_per_row) {
   for (int i = 0; i < m; ++i) w[i] = (i == 0) ? 1.0 : 0.0;
-  if (m <= 1) return;
+  if (m <= 1) return true;
   b[m - 1] = 0.0;
   const double eps = 2.220446049250313e-16;
   int hi = m - 1;
   int lo = -1;                          // top of the unreduced block that ends at hi; -1: not known
-  int budget = 60 * m;
+  int budget = sweeps_per_row * m;
   while (hi > 0 && budget-- > 0) {
     // deflate converged eigenvalues at the bottom
     double bb = b[hi - 1], ah = a[hi], ahm = a[hi - 1];
@@ -1120,43 +1122,57 @@ __device__ void tridiag_eig_first_row(double* a, double* b, double* w, int m) {
     b[hi - 1] = x;
     if (split >= 0) lo = split;
   }
+  return hi == 0;
+}
+
+// (z^T P^{-1} z) e_1^T log(T) e_1 for one probe column: T of size m from that column's CG
+// coefficients (Observation in App. A; coefficient j of the column at alpha[j * stride]), its
+// eigenvalues and first eigenvector row (App. B, log-det paragraph).  *status receives 0, or the
+// BBMM_* code of what went wrong (eigen-solver out of budget: 6; non-positive eigenvalue with
+// weight, or a non-finite term: 4).  a, b, w: LDS arrays of BBMM_MAXP doubles.
+__device__ double slq_term(const double* __restrict__ alpha, const double* __restrict__ beta, size_t stride,
+                           int m, double rho0, int sweeps_per_row, double* a, double* b, double* w,
+                           int* status) {
+  if (m > BBMM_MAXP) m = BBMM_MAXP;
+  for (int j = 0; j < m; ++j) {
+    double al = alpha[(size_t)j * stride];
+    double dg = 1.0 / al;
+    if (j > 0) {
+      double alp = alpha[(size_t)(j - 1) * stride];
+      double bep = beta[(size_t)(j - 1) * stride];
+      dg += bep / alp;
+      b[j - 1] = sqrt(bep) / alp;
+    }
+    a[j] = dg;
+  }
+  bool conv = tridiag_eig_first_row(a, b, w, m, sweeps_per_row);
+  double g = 0.0;
+  int bad = 0;
+  for (int j = 0; j < m; ++j) {
+    if (!(a[j] > 0.0)) {
+      if (w[j] * w[j] > 1e-20) bad = 1;
+      continue;
+    }
+    g += w[j] * w[j] * log(a[j]);
+  }
+  double term = rho0 * g;
+  if (!finite_d(term)) bad = 1;
+  *status = !conv ? 6 : (bad ? 4 : 0);
+  return term;
 }
 
 // One block per probe column: T from the CG coefficients (Observation in App. A),
 // e_1^T log(T) e_1, times rho0.  Thread 0 of block 0 (last arriving) forms the mean.
 __global__ __launch_bounds__(64) void k_slq(const double* __restrict__ alpha_hist,
                                              const double* __restrict__ beta_hist, int t,
-                                             DevState* st) {
+                                             int sweeps_per_row, DevState* st) {
   __shared__ double a[BBMM_MAXP], b[BBMM_MAXP], w[BBMM_MAXP];
   int col = blockIdx.x + 1;
   if (threadIdx.x == 0) {
-    int m = st->m_valid[col];
-    if (m > BBMM_MAXP) m = BBMM_MAXP;
-    for (int j = 0; j < m; ++j) {
-      double al = alpha_hist[(size_t)j * BBMM_MAXC + col];
-      double dg = 1.0 / al;
-      if (j > 0) {
-        double alp = alpha_hist[(size_t)(j - 1) * BBMM_MAXC + col];
-        double bep = beta_hist[(size_t)(j - 1) * BBMM_MAXC + col];
-        dg += bep / alp;
-        b[j - 1] = sqrt(bep) / alp;
-      }
-      a[j] = dg;
-    }
-    tridiag_eig_first_row(a, b, w, m);
-    double g = 0.0;
     int bad = 0;
-    for (int j = 0; j < m; ++j) {
-      if (!(a[j] > 0.0)) {
-        if (w[j] * w[j] > 1e-20) bad = 1;
-        continue;
-      }
-      g += w[j] * w[j] * log(a[j]);
-    }
-    double term = st->rho0[col] * g;
-    if (!finite_d(term)) bad = 1;
-    st->slq_terms[blockIdx.x] = term;
-    if (bad) st->status = 4;
+    st->slq_terms[blockIdx.x] = slq_term(alpha_hist + col, beta_hist + col, BBMM_MAXC, st->m_valid[col],
+                                         st->rho0[col], sweeps_per_row, a, b, w, &bad);
+    if (bad) st->status = bad;
   }
   if (!last_block_arrives(&st->counter[4][0])) return;
   if (threadIdx.x == 0) {
@@ -1167,21 +1183,41 @@ __global__ __launch_bounds__(64) void k_slq(const double* __restrict__ alpha_his
   }
 }
 
+// The same term from coefficient arrays handed in by the caller: alpha, beta are p x t row-major
+// (row j = iteration j), rho0 and m_valid have t entries; one block per probe column.
+__global__ __launch_bounds__(64) void k_slq_coeffs(const double* __restrict__ alpha,
+                                                    const double* __restrict__ beta,
+                                                    const double* __restrict__ rho0,
+                                                    const int* __restrict__ m_valid, int t,
+                                                    int sweeps_per_row, double* __restrict__ terms,
+                                                    int* __restrict__ status) {
+  __shared__ double a[BBMM_MAXP], b[BBMM_MAXP], w[BBMM_MAXP];
+  if (threadIdx.x != 0) return;
+  int i = blockIdx.x;
+  int bad = 0;
+  terms[i] = slq_term(alpha + i, beta + i, (size_t)t, m_valid[i], rho0[i], sweeps_per_row, a, b, w, &bad);
+  status[i] = bad;
+}
+
 // Stand-alone batched eigen-solve (host arrays copied to the device by the caller).
+// status[b] = 0, or 6 when matrix b did not deflate within the budget.
 __global__ __launch_bounds__(64) void k_tridiag_eig(const double* __restrict__ diag,
                                                      const double* __restrict__ off, int m,
+                                                     int sweeps_per_row,
                                                      double* __restrict__ eigvals,
-                                                     double* __restrict__ first_row) {
+                                                     double* __restrict__ first_row,
+                                                     int* __restrict__ status) {
   __shared__ double a[BBMM_MAXP], b[BBMM_MAXP], w[BBMM_MAXP];
   if (threadIdx.x != 0) return;
   size_t bi = blockIdx.x;
   for (int j = 0; j < m; ++j) a[j] = diag[bi * m + j];
   for (int j = 0; j + 1 < m; ++j) b[j] = off[bi * (m - 1) + j];
-  tridiag_eig_first_row(a, b, w, m);
+  bool conv = tridiag_eig_first_row(a, b, w, m, sweeps_per_row);
   for (int j = 0; j < m; ++j) {
     eigvals[bi * m + j] = a[j];
     first_row[bi * m + j] = w[j];
   }
+  status[bi] = conv ? 0 : 6;
 }
 
 // Noise-derivative terms (dK_hat/dsigma^2 = I): (1/t) sum_i u_i^T w_i and u_0^T u_0, plus y^T u_0.
@@ -1419,13 +1455,19 @@ void launch_cross_dot(hipStream_t s, const float* X, const float* Xs, int n, int
   k_cross_dot<<<ns, VT, 0, s>>>(X, Xs, n, hyp, V, ldv, percol, prior, sign, out);
 }
 
-void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, DevState* st) {
-  k_slq<<<t, 64, 0, s>>>(alpha_hist, beta_hist, t, st);
+void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int sweeps_per_row,
+                DevState* st) {
+  k_slq<<<t, 64, 0, s>>>(alpha_hist, beta_hist, t, sweeps_per_row, st);
+}
+
+void launch_slq_coeffs(hipStream_t s, const double* alpha, const double* beta, const double* rho0,
+                       const int* m_valid, int t, int sweeps_per_row, double* terms, int* status) {
+  k_slq_coeffs<<<t, 64, 0, s>>>(alpha, beta, rho0, m_valid, t, sweeps_per_row, terms, status);
 }
 
 void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,
-                        double* eigvals, double* first_row) {
-  k_tridiag_eig<<<batch, 64, 0, s>>>(diag, off, m, eigvals, first_row);
+                        int sweeps_per_row, double* eigvals, double* first_row, int* status) {
+  k_tridiag_eig<<<batch, 64, 0, s>>>(diag, off, m, sweeps_per_row, eigvals, first_row, status);
 }
 
 void launch_noise_terms(hipStream_t s, const double* U, const double* Z0, const float* y, int n, int ld,

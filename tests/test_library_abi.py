@@ -27,7 +27,8 @@ def test_header_declares_the_documented_entry_points():
     names = _declared_functions()
     for required in ["bbmm_create", "bbmm_destroy", "bbmm_solve_logdet_grad", "bbmm_build_khat",
                      "bbmm_kernel_mm", "bbmm_pivoted_cholesky", "bbmm_precond_solve",
-                     "bbmm_make_probes", "bbmm_mbcg", "bbmm_slq_logdet", "bbmm_tridiag_eig_batched",
+                     "bbmm_make_probes", "bbmm_mbcg", "bbmm_slq_logdet", "bbmm_slq_from_coeffs",
+                     "bbmm_tridiag_eig_batched",
                      "bbmm_dk_traces"]:
         assert required in names
 
