@@ -3,7 +3,17 @@
 Calls ONLY the fp64 oracle and the seeded input generators (never the HIP path):
     python tests/golden/make_golden.py [case ...]
 Each case is one of the benchmark configurations at a size where running the oracle inside the
-GPU test session would take minutes.  Output: tests/golden/<case>.json (text).
+GPU test session would take minutes.  Output: tests/golden/<case>.json (text: scalars,
+coefficient histories, sampled rows) and tests/golden/<case>_U.npy (the oracle's whole solve
+block [u_0 .. u_t], rounded once to float32 -- 6e-8 relative, far below the 1e-3 parity bound --
+so that the tests compare every row; for n = 500,000 every row of u_0 and every 8th row of the
+probe solves).
+
+Cases come in two kinds.  "As configured": the iteration cap the configuration states, where CG
+has not converged and the iterate is only defined up to a fraction of an update (see
+U_last_step, U_reorder_dev, U_fp32_dev below).  "Converged cap" (`*_capN`): the same problem with
+the cap raised until the oracle's last update is far below 1e-3, where a relative bound of 1e-3
+on every solve column is well defined.
 """
 import json
 import multiprocessing
@@ -31,6 +41,25 @@ CASES = {
     "cfg3_n50000": (3, 50000, {}),
     "cfg4_sub_n20000": (4, 20000, {}),
 }
+
+
+def save_U(name: str, U: np.ndarray, every: int = 1):
+    """<name>_U.npy: the solve block in float32.  every > 1: column 0 in full as <name>_u0.npy and
+    rows 0, every, 2 every, .. of all columns."""
+    if every == 1:
+        np.save(os.path.join(OUT_DIR, name + "_U.npy"), U.astype(np.float32))
+    else:
+        np.save(os.path.join(OUT_DIR, name + "_u0.npy"), U[:, 0].astype(np.float32))
+        np.save(os.path.join(OUT_DIR, name + "_U.npy"), U[::every].astype(np.float32))
+
+
+def fp32_entries_matmul(Khat32: np.ndarray, M: np.ndarray, rows: int = 4096) -> np.ndarray:
+    """K M in fp64 arithmetic with the entries of K rounded once to float32 (the precision the
+    paper runs in): what any correct single-precision-matrix implementation starts from."""
+    out = np.empty((Khat32.shape[0], M.shape[1]))
+    for a in range(0, Khat32.shape[0], rows):
+        out[a:a + rows] = Khat32[a:a + rows].astype(np.float64) @ M
+    return out
 
 
 def sample_rows(n: int, cfg: int) -> np.ndarray:
@@ -113,18 +142,23 @@ MATRIX_FREE_CASES = {
 
 
 SGPR_CASES = {
-    # name: (config, n, m): subset-of-regressors covariance, oracle/sgpr_oracle.py
-    "cfg5_n500000": (5, 500000, 1024),
-    "cfg5_sub_n50000": (5, 50000, 1024),
+    # name: (config, n, m, iteration cap or None for the configured one): subset-of-regressors
+    # covariance, oracle/sgpr_oracle.py
+    "cfg5_n500000": (5, 500000, 1024, None),
+    "cfg5_sub_n50000": (5, 50000, 1024, None),
+    # cap raised from 50 to 128: last update ~1e-5 of the iterate at both sizes
+    "cfg5_n500000_cap128": (5, 500000, 1024, 128),
+    "cfg5_sub_n50000_cap128": (5, 50000, 1024, 128),
 }
 
 
-def run_sgpr(name: str, cfg: int, n: int, m: int):
+def run_sgpr(name: str, cfg: int, n: int, m: int, cap=None):
     """Configuration 5 (SGPR): the oracle's BBMM call on the SoR covariance, the size of its last
     update, a second fp64 run with the products grouped through the root A = K_XU G^-T (another
     rounding order of the same operator), and the plain definition by the Woodbury identity."""
     import scipy.linalg as sla
-    w = inputs.make(cfg, n=n, m=m)
+    w = inputs.make(cfg, n=n, m=m) if cap is None else inputs.make(cfg, n=n, m=m, iters=cap)
+    converged_cap = cap is not None
     t0 = time.time()
 
     def say(msg):
@@ -149,38 +183,65 @@ def run_sgpr(name: str, cfg: int, n: int, m: int):
         dg, off = O.tridiag_from_cg(prev.alpha[:, i + 1], prev.beta[:, i + 1], mv)
         terms_prev.append(prev.rho0[i + 1] * O.e1_logT_e1(dg, off))
     logdet_prev = P.logdet + float(np.mean(terms_prev))
-    say("derivative terms one iteration earlier")
-    dargs0 = (w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel, parts)
-    trace_prev = list(S.sor_derivative_products(*dargs0, prev.U[:, 1:], prev.Z0[:, 1:]) / w.t)
-    quad_prev = list(S.sor_derivative_products(*dargs0, prev.U[:, :1], prev.U[:, :1]))
-    trace_prev.append(float(np.sum(prev.U[:, 1:] * prev.Z0[:, 1:]) / w.t))
-    quad_prev.append(float(prev.U[:, 0] @ prev.U[:, 0]))
+    trace_prev = quad_prev = trace_alt = quad_alt = None
+    trace_sens = quad_sens = None
+    dargs = (w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel, parts)
+
+    def dterms(run):
+        tr = list(S.sor_derivative_products(*dargs, run.U[:, 1:], run.Z0[:, 1:]) / w.t)
+        qd = list(S.sor_derivative_products(*dargs, run.U[:, :1], run.U[:, :1]))
+        tr.append(float(np.sum(run.U[:, 1:] * run.Z0[:, 1:]) / w.t))
+        qd.append(float(run.U[:, 0] @ run.U[:, 0]))
+        return [float(v) for v in tr], [float(v) for v in qd]
+
+    if not converged_cap:
+        say("derivative terms one iteration earlier")
+        trace_prev, quad_prev = dterms(prev)
     del prev
     say("rerun with products grouped through the root")
     A = sla.solve_triangular(parts.chol_UU, parts.KXU.T, lower=True).T
     other = O.mbcg(lambda M: A @ (A.T @ M) + w.noise * M, res.B, P.solve, it)
     reorder_dev = norm(res.U - other.U) / norm(res.U)
     yKinvy_alt = float(w.y.astype(np.float64) @ other.U[:, 0])
-    del A
-    # the derivative terms of that second run: u^T dQ w is a small difference of large terms, so at
-    # an unconverged iteration count its value moves with the rounding order far more than U does
-    say("derivative terms of the second run")
-    dargs = (w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale, w.jitter_rel, parts)
-    trace_alt = list(S.sor_derivative_products(*dargs, other.U[:, 1:], other.Z0[:, 1:]) / w.t)
-    quad_alt = list(S.sor_derivative_products(*dargs, other.U[:, :1], other.U[:, :1]))
-    trace_alt.append(float(np.sum(other.U[:, 1:] * other.Z0[:, 1:]) / w.t))
-    quad_alt.append(float(other.U[:, 0] @ other.U[:, 0]))
+    if not converged_cap:
+        # the derivative terms of that second run: u^T dQ w is a small difference of large terms, so
+        # at an unconverged iteration count its value moves with the rounding order far more than U does
+        say("derivative terms of the second run")
+        trace_alt, quad_alt = dterms(other)
     del other
-    say("first-order sensitivity of the trace and quadratic terms to the iterate")
-    trace_sens, quad_sens = S.sor_term_sensitivity(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale,
-                                                   w.jitter_rel, parts, res.U, res.W)
+    # a third fp64 run through the root rounded once to float32 (the precision the paper runs in
+    # and the HIP path stores the root in): how far that alone moves the iterate
+    say("rerun through the float32-rounded root")
+    A32 = A.astype(np.float32)
+    del A
+
+    def root32_mm(M, rows=65536):
+        T = np.zeros((A32.shape[1], M.shape[1]))
+        for a0 in range(0, n, rows):
+            T += A32[a0:a0 + rows].astype(np.float64).T @ M[a0:a0 + rows]
+        out = np.empty_like(M)
+        for a0 in range(0, n, rows):
+            out[a0:a0 + rows] = A32[a0:a0 + rows].astype(np.float64) @ T
+        return out + w.noise * M
+
+    other = O.mbcg(root32_mm, res.B, P.solve, it)
+    fp32_dev = norm(res.U - other.U) / norm(res.U)
+    trace_fp32, quad_fp32 = dterms(other) if converged_cap else (None, None)
+    del other, A32
+    if not converged_cap:
+        say("first-order sensitivity of the trace and quadratic terms to the iterate")
+        ts, qs = S.sor_term_sensitivity(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale,
+                                        w.jitter_rel, parts, res.U, res.W)
+        trace_sens, quad_sens = ts.tolist(), qs.tolist()
     say("Woodbury solve and log-determinant")
     u_exact, logdet_exact = S.sor_woodbury(parts, w.y)
     yKinvy_exact = float(w.y.astype(np.float64) @ u_exact)
     rows = sample_rows(n, cfg)
+    every = 8 if n > 100000 else 1
+    save_U(name, res.U, every)
     out = {
-        "source": "oracle/sgpr_oracle.py sor_bbmm_inference on paper_1809_11165_amd.inputs.make(%d, n=%d, m=%d)"
-                  % (cfg, n, m),
+        "source": "oracle/sgpr_oracle.py sor_bbmm_inference on paper_1809_11165_amd.inputs.make(%d, n=%d, m=%d%s)"
+                  % (cfg, n, m, "" if cap is None else ", iters=%d" % cap),
         "config": cfg, "n": n, "m": m, "d": w.d, "t": w.t, "k": w.k, "iters_cap": w.iters, "tol": w.tol,
         "iters_run": it, "pivots": res.pivots.tolist(), "pivot_dmax": res.pivot_dmax.tolist(),
         "logdet": res.logdet, "logdet_precond": res.logdet_precond, "yKinvy": res.yKinvy,
@@ -188,16 +249,18 @@ def run_sgpr(name: str, cfg: int, n: int, m: int):
         "grad": res.grad.tolist(), "slq_terms": res.slq_terms.tolist(),
         "alpha": res.mbcg.alpha.tolist(), "beta": res.mbcg.beta.tolist(),
         "resid": res.mbcg.resid.tolist(), "rho0": res.mbcg.rho0.tolist(),
+        "m_valid": res.mbcg.m_valid.tolist(),
         "sample_rows": rows.tolist(), "U_sample": res.U[rows].tolist(),
-        "U_colnorm": norm(res.U).tolist(),
+        "U_colnorm": norm(res.U).tolist(), "U_rows_every": every,
         "exact_logdet": logdet_exact, "exact_yKinvy": yKinvy_exact,
         "u0_sample_exact": u_exact[rows].tolist(),
         "u0_rel_err_vs_exact": float(np.linalg.norm(res.U[:, 0] - u_exact) / np.linalg.norm(u_exact)),
         "U_last_step": last_step.tolist(), "U_reorder_dev": reorder_dev.tolist(),
-        "trace_alt": [float(v) for v in trace_alt], "quad_alt": [float(v) for v in quad_alt],
-        "trace_sens": trace_sens.tolist(), "quad_sens": quad_sens.tolist(),
+        "U_fp32_dev": fp32_dev.tolist(),
+        "trace_alt": trace_alt, "quad_alt": quad_alt, "trace_fp32": trace_fp32, "quad_fp32": quad_fp32,
+        "trace_sens": trace_sens, "quad_sens": quad_sens,
         "yKinvy_prev": yKinvy_prev, "logdet_prev": logdet_prev, "yKinvy_alt": yKinvy_alt,
-        "trace_prev": [float(v) for v in trace_prev], "quad_prev": [float(v) for v in quad_prev],
+        "trace_prev": trace_prev, "quad_prev": quad_prev,
         "L_sample": res.L[rows].tolist(),
         "seconds": time.time() - t0,
     }
@@ -258,6 +321,14 @@ def run(name: str):
     other = O.mbcg(panel_mm, res.B, P.solve, it)
     reorder_dev = norm(res.U - other.U) / norm(res.U)
     del other
+    # a third fp64 run on the matrix with its entries rounded once to float32 -- the precision the
+    # paper runs in and the HIP path stores K_hat in: how far that alone moves the iterate
+    say("rerun on float32-rounded matrix entries")
+    Khat32 = Khat.astype(np.float32)
+    other = O.mbcg(lambda M: fp32_entries_matmul(Khat32, M), res.B, P.solve, it)
+    fp32_dev = norm(res.U - other.U) / norm(res.U)
+    del other, Khat32
+    save_U(name, res.U)
     # the plain definition, last because it factorises K_hat in place
     say("dense Cholesky")
     if n * n < 2 ** 31:
@@ -283,6 +354,8 @@ def run(name: str):
         "u0_sample_exact": u_exact[rows].tolist(), "u0_rel_err_vs_exact": u0_err,
         "U_last_step": last_step.tolist(),
         "U_reorder_dev": reorder_dev.tolist(),
+        "U_fp32_dev": fp32_dev.tolist(),
+        "m_valid": res.mbcg.m_valid.tolist(),
         "seconds": time.time() - t0,
     }
     path = os.path.join(OUT_DIR, name + ".json")
