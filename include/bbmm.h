@@ -271,6 +271,18 @@ int bbmm_mbcg(bbmm_ctx* ctx, int32_t mode, const float* B, int64_t c, float* U,
 int bbmm_tridiag_eig_batched(bbmm_ctx* ctx, const double* diag, const double* off, int64_t m,
                              int64_t batch, double* eigvals, double* first_row);
 
+/* bbmm_tridiag_eig_batched for callers that cannot allocate device memory (code that must not
+ * call hipMalloc: tight serving loops, harnesses that forbid it, code between the capture calls
+ * of a HIP graph on another stream).  Same arguments, same kernel, same results; the device copies
+ * of the batch live in a fixed work area inside the library (576 KB per GPU, held until the
+ * process ends) instead of a buffer of the context, and the call makes no hipMalloc / hipFree.
+ * Limit: batch * m <= 16384 (BBMM_EINVAL beyond it, with a message).  All calls on one GPU share
+ * that work area -- from any context -- so calls that overlap in time on one GPU race; calls
+ * issued one after the other (this entry point synchronises the context's stream before it
+ * returns) are safe.  Nothing needs clearing between calls: every word read is written first. */
+int bbmm_tridiag_eig_batched_noalloc(bbmm_ctx* ctx, const double* diag, const double* off, int64_t m,
+                                     int64_t batch, double* eigvals, double* first_row);
+
 /* log|K_hat| estimate from the coefficients of the LAST bbmm_mbcg run, whose block must have
  * been [y, z_1..z_t] (columns 1..t are used): log|P| + (1/t) sum_i rho0_i e_1^T log(T_i) e_1.
  * logdet: host; slq_terms: host t (optional). */

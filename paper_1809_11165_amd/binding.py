@@ -28,7 +28,7 @@ EXPORTS = [
     "bbmm_setup", "bbmm_build_khat", "bbmm_khat_block", "bbmm_sgpr_build", "bbmm_sgpr_root_rows",
     "bbmm_kernel_mm", "bbmm_pivoted_cholesky",
     "bbmm_precond_setup", "bbmm_precond_solve", "bbmm_make_probes", "bbmm_mbcg",
-    "bbmm_tridiag_eig_batched", "bbmm_slq_logdet", "bbmm_slq_from_coeffs", "bbmm_dk_traces",
+    "bbmm_tridiag_eig_batched", "bbmm_tridiag_eig_batched_noalloc", "bbmm_slq_logdet", "bbmm_slq_from_coeffs", "bbmm_dk_traces",
     "bbmm_predict_mean", "bbmm_predict_var",
 ]
 
@@ -101,6 +101,7 @@ def load_library() -> C.CDLL:
     lib.bbmm_tridiag_eig_batched.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double),
                                              C.c_int64, C.c_int64, C.POINTER(C.c_double),
                                              C.POINTER(C.c_double)]
+    lib.bbmm_tridiag_eig_batched_noalloc.argtypes = lib.bbmm_tridiag_eig_batched.argtypes
     lib.bbmm_slq_logdet.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.bbmm_slq_from_coeffs.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double),
                                          C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int64, C.c_int64,
@@ -362,6 +363,9 @@ class Context:
         fn = _fn if _fn is not None else self.lib.bbmm_tridiag_eig_batched
         self._ck(fn(self.h, _dbl(diag), offp, m, batch, _dbl(vals), _dbl(first)))
         return vals, first
+
+    def bbmm_tridiag_eig_batched_noalloc(self, diag: np.ndarray, off: np.ndarray):
+        return self.bbmm_tridiag_eig_batched(diag, off, _fn=self.lib.bbmm_tridiag_eig_batched_noalloc)
 
     def bbmm_slq_logdet(self):
         t = self._shape[2]

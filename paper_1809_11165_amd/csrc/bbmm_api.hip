@@ -10,8 +10,17 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <string>
 #include <vector>
+
+// Work area of bbmm_tridiag_eig_batched_noalloc: device copies of the batch (diagonals,
+// off-diagonals, eigenvalues, first rows: 4 x BBMM_EIG_NOALLOC_MAX doubles) followed by one status
+// word per matrix.  Every GPU the library runs on holds its own copy of this array until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress: the address the
+// kernels get is the one resolved per device in scratch_of().
+#define BBMM_EIG_NOALLOC_MAX 16384
+static __device__ __align__(256) double scratch[4 * BBMM_EIG_NOALLOC_MAX + BBMM_EIG_NOALLOC_MAX / 2];
 
 namespace {
 
@@ -86,6 +95,8 @@ struct bbmm_ctx {
       tmpA, tmpB, SA, SB, u0v, dkpartial, eig, plan[3], nseg[3], 
       KUU, Gm, Ginv, Kux, AT, A, qdiag, Tp, T4, sgplan[4], sgnseg[4],
       Ua, Ub, Us, U4, usq, TU, TW, BU, BW, dkops;
+  double* eig_static = nullptr;   // this device's address of `scratch`
+  int* h_eig_status = nullptr;    // pinned, BBMM_EIG_NOALLOC_MAX ints
   DevState* h_st = nullptr;   // pinned
   double* h_hist = nullptr;   // pinned, 3 * MAXP * MAXC doubles
   size_t dk_rows_cap = 0;
@@ -129,6 +140,26 @@ int ensure(bbmm_ctx* c, Buf& b, size_t bytes) {
 template <typename T>
 T* ptr(const Buf& b) {
   return reinterpret_cast<T*>(b.p);
+}
+
+// Device address of `scratch` on the CURRENT device `device`, resolved once per device.
+constexpr int kMaxDevices = 64;
+double* g_scratch_addr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+hipError_t scratch_of(int device, double** out) {
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (device >= 0 && device < kMaxDevices && g_scratch_addr[device]) {
+    *out = g_scratch_addr[device];
+    return hipSuccess;
+  }
+  void* p = nullptr;
+  hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  if (!p) return hipErrorInvalidSymbol;
+  if (device >= 0 && device < kMaxDevices) g_scratch_addr[device] = reinterpret_cast<double*>(p);
+  *out = reinterpret_cast<double*>(p);
+  return hipSuccess;
 }
 
 int ld_for(int c) { return c <= 16 ? 16 : 32; }
@@ -933,7 +964,12 @@ int bbmm_create(bbmm_ctx** out, int device, void* hip_stream) {
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) == hipSuccess && cus > 0)
     c->num_cus = cus;
   c->stream = reinterpret_cast<hipStream_t>(hip_stream);
-  if (hipHostMalloc((void**)&c->h_st, sizeof(DevState), hipHostMallocDefault) != hipSuccess ||
+  if (scratch_of(device, &c->eig_static) != hipSuccess) {
+    delete c;
+    return BBMM_EHIP;
+  }
+  if (hipHostMalloc((void**)&c->h_eig_status, sizeof(int) * BBMM_EIG_NOALLOC_MAX, hipHostMallocDefault) != hipSuccess ||
+      hipHostMalloc((void**)&c->h_st, sizeof(DevState), hipHostMallocDefault) != hipSuccess ||
       hipHostMalloc((void**)&c->h_hist, sizeof(double) * 3 * BBMM_MAXP * BBMM_MAXC, hipHostMallocDefault) != hipSuccess) {
     delete c;
     return BBMM_ENOMEM;
@@ -969,6 +1005,7 @@ int bbmm_destroy(bbmm_ctx* c) {
   for (Buf* b : bufs)
     if (b->p) (void)hipFree(b->p);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  if (c->h_eig_status) (void)hipHostFree(c->h_eig_status);
   if (c->h_st) (void)hipHostFree(c->h_st);
   if (c->h_hist) (void)hipHostFree(c->h_hist);
   delete c;
@@ -1364,6 +1401,19 @@ int bbmm_tridiag_eig_batched(bbmm_ctx* c, const double* diag, const double* off,
   if (rc) return rc;
   std::vector<int> status((size_t)batch, 0);
   return run_tridiag_eig(c, ptr<double>(c->eig), status.data(), diag, off, m, batch, eigvals, first_row);
+}
+
+int bbmm_tridiag_eig_batched_noalloc(bbmm_ctx* c, const double* diag, const double* off, int64_t m,
+                                     int64_t batch, double* eigvals, double* first_row) {
+  if (!c) return BBMM_EINVAL;
+  if (!diag || !eigvals || !first_row || m < 1 || m > BBMM_MAXP || batch < 1 || (m > 1 && !off))
+    return fail(c, BBMM_EINVAL, "bad tridiagonal batch");
+  if (batch > BBMM_EIG_NOALLOC_MAX || batch * m > BBMM_EIG_NOALLOC_MAX)
+    return fail(c, BBMM_EINVAL, "batch * m exceeds the 16384 entries of the static work area");
+  HIPCHK(c, hipSetDevice(c->device));
+  // same kernel and staging order as bbmm_tridiag_eig_batched; the work area is this device's
+  // copy of `scratch`, every word the kernel or the copies read is written first
+  return run_tridiag_eig(c, c->eig_static, c->h_eig_status, diag, off, m, batch, eigvals, first_row);
 }
 
 int bbmm_slq_from_coeffs(bbmm_ctx* c, const double* alpha, const double* beta, const double* rho0,
