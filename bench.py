@@ -44,6 +44,74 @@ MEASURED_TRAFFIC_SGPR_N500000_M1024 = 4.261e9
 MEASURED_TRAFFIC_SYM_N50000 = 5.527e9
 
 
+def _cores():
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count() or 1
+    return min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+
+
+def cpu_baseline_full_n(cfg: int, n: int, iters: int, rows_build: int = 2048, rows_mm: int = 8192):
+    """The fp64 oracle timed ON the benchmark workload, piece by piece at full width n: every O(n^2)
+    stage of oracle.bbmm_inference is linear in the number of matrix ROWS it handles, so each is timed
+    on a block of rows of the full n-column problem and scaled by n / rows (no scaling in n itself):
+      build      kernel_block(X[rows_build], X)                -> K_hat, once per call
+      product    K_hat[rows_mm] @ D (n x c), fp64              -> one per mBCG iteration
+      derivative kernel_derivative_blocks(X[rows_build], X) and its products with [W, u_0], once per call
+    plus the O(n k^2 + n c) vector work of `iters` iterations measured directly on n x c blocks.
+    Returns (milliseconds for one call of `iters` iterations, description, seconds of CPU time used)."""
+    from oracle import bbmm_oracle as O
+    from paper_1809_11165_amd import inputs
+    w = inputs.make(cfg, n=n)
+    X64 = w.X.astype(np.float64)
+    c, t = w.t + 1, w.t
+    rng = np.random.default_rng(0)
+    t_all = time.perf_counter()
+    rb = min(rows_build, n)
+    t0 = time.perf_counter()
+    Kb = O.kernel_block(w.kernel, X64[:rb], X64, w.lengthscale, w.outputscale)
+    t_build = (time.perf_counter() - t0) * n / rb
+    rm = min(rows_mm, n)
+    slab = np.ascontiguousarray(np.tile(Kb, (-(-rm // rb), 1))[:rm])      # rows_mm x n fp64, values do not matter
+    D = rng.standard_normal((n, c))
+    slab @ D                                                                # warm the BLAS threads
+    t0 = time.perf_counter()
+    for _ in range(3):
+        slab @ D
+    t_mm = (time.perf_counter() - t0) / 3 * n / rm
+    del slab
+    U, W = rng.standard_normal((n, c)), rng.standard_normal((n, t))
+    t0 = time.perf_counter()
+    mats = O.kernel_derivative_blocks(w.kernel, X64[:rb], X64, w.lengthscale, w.outputscale)
+    for M in mats:
+        float(np.sum(U[:rb, 1:] * (M @ W)) / t)
+        float(U[:rb, 0] @ (M @ U[:, 0]))
+    t_dk = (time.perf_counter() - t0) * n / rb
+    del mats, Kb
+    # per-iteration vector work: the preconditioner solve and the updates of Alg. 2 on n x c blocks
+    L = rng.standard_normal((n, w.k))
+    P = O.make_preconditioner(L, w.noise)
+    R = rng.standard_normal((n, c))
+    t0 = time.perf_counter()
+    for _ in range(3):
+        Z = P.solve(R)
+        np.sum(R * Z, axis=0)
+        U2 = U + D * 0.5
+        R2 = R - D * 0.5
+        np.sum(D * R, axis=0)
+        D2 = Z + D * 0.3
+    t_vec = (time.perf_counter() - t0) / 3
+    total = t_build + iters * (t_mm + t_vec) + t_dk
+    used = time.perf_counter() - t_all
+    desc = ("fp64 numpy oracle at full n=%d, timed by stage on blocks of rows of the full-width problem and scaled "
+            "by n/rows only: K_hat build %.1f s (from %d rows), %d x (product %.3f s from %d rows + vector "
+            "updates %.3f s), derivative pass %.1f s (from %d rows); %.0f s of CPU time used"
+            % (n, t_build, rb, iters, t_mm, rm, t_vec, t_dk, rb, used))
+    return total * 1e3, desc, {"build_s": t_build, "product_s_per_iteration": t_mm,
+                               "vector_s_per_iteration": t_vec, "derivative_s": t_dk}
+
+
 def cpu_baseline(cfg: int, n_sample: int, n_full: int, iters: int):
     """Times the fp64 oracle (as it stands) on an n_sample-point instance of the same recipe, for the
     number of iterations the GPU call ran, and scales by (n_full / n_sample)^2, the cost ratio of the
@@ -55,16 +123,18 @@ def cpu_baseline(cfg: int, n_sample: int, n_full: int, iters: int):
     O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
                      w.k, iters)
     dt = time.perf_counter() - t0
-    try:
-        cores = len(os.sched_getaffinity(0))
-    except AttributeError:
-        cores = os.cpu_count() or 1
-    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
-    return {"value": dt * 1e3 * (n_full / n_sample) ** 2, "unit": "ms", "cores": min(cores, threads),
-            "kind": "oracle",
-            "sample": "fp64 numpy oracle, full call (k=%d, t=%d, %d iterations) on n=%d points of the same "
-                      "recipe: %.1f s measured, scaled by (n/n_sample)^2 = %.0f"
-                      % (w.k, w.t, iters, n_sample, dt, (n_full / n_sample) ** 2)}
+    small = {"value": dt * 1e3 * (n_full / n_sample) ** 2, "unit": "ms", "cores": _cores(),
+             "kind": "oracle",
+             "sample": "fp64 numpy oracle, full call (k=%d, t=%d, %d iterations) on n=%d points of the same "
+                       "recipe: %.1f s measured, scaled by (n/n_sample)^2 = %.0f"
+                       % (w.k, w.t, iters, n_sample, dt, (n_full / n_sample) ** 2)}
+    if n_sample >= n_full:
+        return small
+    # the headline figure: the oracle's stages timed at the benchmark's own n; the small-n
+    # extrapolation is kept beside it for comparison
+    ms, desc, parts = cpu_baseline_full_n(cfg, n_full, iters)
+    return {"value": ms, "unit": "ms", "cores": _cores(), "kind": "oracle", "sample": desc, "stages": parts,
+            "extrapolated_from_small_n": {"value": small["value"], "unit": "ms", "sample": small["sample"]}}
 
 
 def cpu_baseline_sgpr(n_sample: int, n_full: int, m: int):
@@ -77,16 +147,84 @@ def cpu_baseline_sgpr(n_sample: int, n_full: int, m: int):
     S.sor_bbmm_inference(w.kernel, w.X, w.Uind, w.y, w.lengthscale, w.outputscale, w.noise, w.jitter_rel,
                          w.E1, w.E2, w.k, w.iters)
     dt = time.perf_counter() - t0
-    try:
-        cores = len(os.sched_getaffinity(0))
-    except AttributeError:
-        cores = os.cpu_count() or 1
-    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
-    return {"value": dt * 1e3 * (n_full / n_sample), "unit": "ms", "cores": min(cores, threads),
+    return {"value": dt * 1e3 * (n_full / n_sample), "unit": "ms", "cores": _cores(),
             "kind": "oracle",
             "sample": "fp64 numpy SGPR oracle, full call (m=%d, k=10, t=10, 50 iterations) on n=%d points of "
                       "the same recipe: %.1f s measured, scaled by n/n_sample = %.0f"
                       % (m, n_sample, dt, n_full / n_sample)}
+
+
+TRAFFIC_NOTE = ("HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this kernel on this "
+                "workload (profiles/%s), not counted in this run")
+
+
+def roofline_sym(n, c, mm_ms, launches, config):
+    """Product from the stored upper triangle.  The triangle is read once (2 n^2 + 4 n W bytes,
+    W = 1024: the diagonal blocks are whole), which no longer binds; every stored 16 x 16 tile still
+    takes its fp64 MFMAs for both of its uses, so the product is bound by the fp64 matrix rate.
+    Algorithmic flops of one product: 2 c per pair of points (c = t + 1 columns really used).
+    Executed: per pair 16 columns on the row-side use and 12 or 16 on the column-side use (12 when at
+    most 12 columns of a 16-column group are in use), each on half the pairs; reported beside it."""
+    alg_flops = 2.0 * c * n * n
+    achieved = alg_flops / (mm_ms * 1e-3) / 1e12
+    wide = sum(16 + (12 if min(16, c - 16 * q) <= 12 else 16) for q in range((c + 15) // 16))
+    executed = wide * n * n / (mm_ms * 1e-3) / 1e12
+    return {"bound": "mfma", "achieved": achieved, "peak": MFMA_F64_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": achieved / MFMA_F64_PEAK_TFLOPS,
+            "traffic": MEASURED_TRAFFIC_SYM_N50000 if (n, config) == (50000, 3) else None,
+            "traffic_source": TRAFFIC_NOTE % "k_mm_sym_cfg3_n50000_counters.txt",
+            "kernel": "k_mm_sym (one launch per product for c <= 12, else a second one for the diagonal blocks)",
+            "avg_launch_ms": mm_ms, "launches": launches,
+            "executed_TFLOPs_with_padding": executed,
+            "executed_frac": executed / MFMA_F64_PEAK_TFLOPS}
+
+
+def roofline_mat(n, c, mm_ms, launches, config):
+    """Whole K_hat streamed once per product: algorithmic bytes 4 n^2 (K_hat) + 8 n c (block in and out)."""
+    alg_bytes = 4.0 * n * n + 8.0 * n * c
+    achieved = alg_bytes / (mm_ms * 1e-3) / 1e9
+    return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_MAT_N50000 if (n, config) == (50000, 3) else None,
+            "traffic_source": TRAFFIC_NOTE % "k_mm_mat_cfg3_n50000_hbm_counters.txt",
+            "kernel": "k_mm_mat", "avg_launch_ms": mm_ms, "launches": launches}
+
+
+def roofline_otf(n, c, d, mm_ms, launches):
+    """Tiles rebuilt from X in every product.  Algorithmic flops per pair: 2 d (distance contraction)
+    + 2 c (multiply by the block).  `frac` prices all of them at the fp32 matrix rate; the second
+    contraction is carried out in fp64, at half that rate on the same pipe, so the floor of the two
+    together is n^2 (2 d / peak32 + 2 c / peak64): `frac_of_mixed_floor` is that floor over the
+    launch time."""
+    alg_flops = (2.0 * d + 2.0 * c) * n * n
+    achieved = alg_flops / (mm_ms * 1e-3) / 1e12
+    mixed_floor_ms = n * n * (2.0 * d / MFMA_F32_PEAK_TFLOPS + 2.0 * c / MFMA_F64_PEAK_TFLOPS) * 1e-9
+    return {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
+            "kernel": "k_mm_otf_tri (tiles on and above the diagonal, each used twice; two launches per product)"
+                      if (c <= 16 and d <= 32 and -(-n // 256) * 256 >= 12288) else "k_mm_otf",
+            "avg_launch_ms": mm_ms, "launches": launches,
+            "pairs_per_s": n * n / (mm_ms * 1e-3),
+            "mixed_floor_ms": mixed_floor_ms, "frac_of_mixed_floor": mixed_floor_ms / mm_ms}
+
+
+def time_calls(ctx, prob, warmup, steps):
+    """(ms per call, mean ms per K_hat.M product from HIP events on the library's stream, launches, last result)"""
+    import torch
+    res = None
+    for _ in range(warmup):
+        res = ctx.bbmm_solve_logdet_grad(prob, want_U=False)
+    torch.cuda.synchronize()
+    mm_avgs, launches = [], 0
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        res = ctx.bbmm_solve_logdet_grad(prob, want_U=False)
+        avg, tot, cnt = ctx.bbmm_mm_timing()
+        mm_avgs.append(avg)
+        launches += cnt
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return dt * 1e3 / steps, float(np.mean(mm_avgs)), launches, res
 
 
 def main():
@@ -104,6 +242,8 @@ def main():
     ap.add_argument("--m", type=int, default=1024, help="inducing inputs (--mode sgpr)")
     ap.add_argument("--cpu-sample", type=int, default=10000)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-other-modes", action="store_true",
+                    help="default run only: skip the whole-matrix and on-the-fly legs (roofline_mat, roofline_otf)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -130,21 +270,7 @@ def main():
     if args.mode == "sym":
         ctx.bbmm_tune("khat_sym", 1)        # keep the upper triangle of K_hat only
 
-    res = None
-    for _ in range(args.warmup):
-        res = ctx.bbmm_solve_logdet_grad(prob, want_U=False)
-    torch.cuda.synchronize()
-    mm_avgs, mm_launches = [], 0
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        res = ctx.bbmm_solve_logdet_grad(prob, want_U=False)
-        avg, tot, cnt = ctx.bbmm_mm_timing()
-        mm_avgs.append(avg)
-        mm_launches += cnt
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
-    mm_ms = float(np.mean(mm_avgs))
+    ms_per_step, mm_ms, mm_launches, res = time_calls(ctx, prob, args.warmup, args.steps)
 
     if args.calib_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB read + 1 GiB written
@@ -172,6 +298,7 @@ def main():
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS,
                     "traffic": MEASURED_TRAFFIC_SGPR_N500000_M1024 if (n, m) == (500000, 1024) else None,
+                    "traffic_source": TRAFFIC_NOTE % "k_mm_mat_cfg5_n500000_sgpr_hbm_counters.txt",
                     "kernel": "k_mm_mat (two launches per product: A^T D, then A T)",
                     "avg_launch_ms": mm_ms / 2.0, "avg_product_ms": mm_ms, "launches": 2 * mm_launches}
         workload = ("config5: SGPR (subset of regressors), RBF, n=%d, m=%d, d=8, t=10, k=10, 50 mBCG "
@@ -179,48 +306,12 @@ def main():
         metric = "mBCG solve+logdet+grad ms at n=500k,m=1024,t=10 (SGPR)"
         mode_name = "fp32 root A = K_XU G^-T in both layouts"
     elif args.mode == "sym":
-        # The triangle is read once (2 n^2 + 4 n W bytes, W = 1024: the diagonal blocks are whole),
-        # which no longer binds; every stored 16 x 16 tile still takes its fp64 MFMAs for both of its
-        # uses, so the product is bound by the fp64 matrix rate.  Algorithmic flops of one product:
-        # 2 c per pair of points (c = t + 1 columns really used).  Executed: per pair 16 columns on
-        # the row-side use and 12 or 16 on the column-side use (12 when at most 12 columns of a
-        # 16-column group are in use), each on half the pairs; reported beside it.
-        alg_flops = 2.0 * c * n * n
-        achieved = alg_flops / (mm_ms * 1e-3) / 1e12
-        wide = sum(16 + (12 if min(16, c - 16 * q) <= 12 else 16) for q in range((c + 15) // 16))
-        executed = wide * n * n / (mm_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F64_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": achieved / MFMA_F64_PEAK_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_SYM_N50000 if (n, args.config) == (50000, 3) else None,
-                    "kernel": "k_mm_sym (one launch per product for c <= 12, else a second one for the diagonal blocks)",
-                    "avg_launch_ms": mm_ms, "launches": mm_launches,
-                    "executed_TFLOPs_with_padding": executed,
-                    "executed_frac": executed / MFMA_F64_PEAK_TFLOPS,
-                    "effective_GBps_of_full_matrix": (4.0 * n * n + 8.0 * n * c) / (mm_ms * 1e-3) / 1e9}
+        roofline = roofline_sym(n, c, mm_ms, mm_launches, args.config)
         mode_name = "materialised fp32 K_hat, upper triangle only (khat_sym)"
     elif mode == inputs.MATERIALISED:
-        # algorithmic bytes of one K_hat.D launch: K_hat once (4 n^2) + block in and out (8 n c)
-        alg_bytes = 4.0 * n * n + 8.0 * n * c
-        achieved = alg_bytes / (mm_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC_MAT_N50000 if (n, args.config) == (50000, 3) else None,
-                    "kernel": "k_mm_mat", "avg_launch_ms": mm_ms, "launches": mm_launches}
+        roofline = roofline_mat(n, c, mm_ms, mm_launches, args.config)
     else:
-        # algorithmic flops per pair: 2 d (distance contraction) + 2 c (multiply by the block).
-        # `frac` prices all of them at the fp32 matrix rate; the second contraction is carried out in
-        # fp64, at half that rate on the same pipe, so the floor of the two together is
-        # n^2 (2 d / peak32 + 2 c / peak64): `frac_of_mixed_floor` is that floor over the launch time.
-        alg_flops = (2.0 * d + 2.0 * c) * n * n
-        achieved = alg_flops / (mm_ms * 1e-3) / 1e12
-        mixed_floor_ms = n * n * (2.0 * d / MFMA_F32_PEAK_TFLOPS + 2.0 * c / MFMA_F64_PEAK_TFLOPS) * 1e-9
-        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_F32_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": achieved / MFMA_F32_PEAK_TFLOPS, "traffic": None,
-                    "kernel": "k_mm_otf_tri (tiles on and above the diagonal, each used twice; two launches per product)"
-                              if (c <= 16 and d <= 32 and -(-n // 256) * 256 >= 12288) else "k_mm_otf",
-                    "avg_launch_ms": mm_ms, "launches": mm_launches,
-                    "pairs_per_s": n * n / (mm_ms * 1e-3),
-                    "mixed_floor_ms": mixed_floor_ms, "frac_of_mixed_floor": mixed_floor_ms / mm_ms}
+        roofline = roofline_otf(n, c, d, mm_ms, mm_launches)
 
     out = {
         "metric": metric,
@@ -236,6 +327,17 @@ def main():
                    "logdet": res.logdet, "nlml": res.nlml},
         "roofline": roofline,
     }
+    if args.config == 3 and args.mode == "sym" and not args.no_other_modes:
+        # the same workload in the other two product modes, in the same run (1 warm-up + 3 timed calls
+        # each): the HBM-bound whole-matrix product and the on-the-fly product
+        ctx.bbmm_tune("khat_sym", 0)
+        ms_mat, mm_mat, l_mat, r_mat = time_calls(ctx, prob, 1, 3)
+        out["roofline_mat"] = dict(roofline_mat(n, c, mm_mat, l_mat, args.config), ms_per_call=ms_mat,
+                                   mode="materialised fp32 K_hat, whole matrix", logdet=r_mat.logdet)
+        prob_otf = binding.problem_from_workload(w, inputs.ONTHEFLY)
+        ms_otf, mm_otf, l_otf, r_otf = time_calls(ctx, prob_otf, 1, 3)
+        out["roofline_otf"] = dict(roofline_otf(n, c, d, mm_otf, l_otf), ms_per_call=ms_otf,
+                                   mode="on-the-fly tiles", logdet=r_otf.logdet)
     if not args.no_cpu:
         out["cpu_baseline"] = (cpu_baseline_sgpr(min(n, 5 * args.cpu_sample), n, args.m)
                                if mode == inputs.SGPR

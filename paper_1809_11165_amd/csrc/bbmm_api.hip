@@ -4,6 +4,7 @@
 // copies the scalar results back with a single stream synchronisation.
 #include "bbmm.h"
 #include "bbmm_dev.h"
+#include "bbmm_plan.h"
 
 #include <math.h>
 #include <stdio.h>
@@ -34,11 +35,12 @@ struct TriLists {
   Buf pieces, first0, first1, base, tot;
   int wgs[2] = {0, 0};
   int np = 0;
+  int max_slots = 0;
   int64_t tune = -1;
 };
 
 constexpr int kMaxVecBlocks = 512;   // at most 32 reduction groups of 16 blocks
-constexpr int kMaxSplit = 64;
+constexpr int kMaxSplit = bbmm_plan::kMaxSplit;
 // Measured, product in us (two-use / one-use form): n = 5 000: 88 / 60; 10 000: 125 / 121; 20 000: 312 / 331;
 // 30 000: 630 / 696; 50 000: 1950 / 2630.
 constexpr int kOtfSymMinRows = 12288;
@@ -79,7 +81,7 @@ struct bbmm_ctx {
   TriLists otft;                             // ... on the fly from X (panels of 512 columns)
   int64_t otf_sym = 1;                       // on-the-fly product with each tile pair evaluated once (<= 16 columns, d <= 32): 0 never, 1 from kOtfSymMinRows rows on, 2 always
   // plans of the materialised product: 16- and 32-column blocks (index 0 / 1), 16-column block with at most 12 columns in use (2)
-  int plan_np = 0, plan_wgs[3] = {0, 0, 0};
+  int plan_np = 0, plan_wgs[3] = {0, 0, 0}, plan_slots[3] = {0, 0, 0};
   int64_t plan_tune = -1;
   // SGPR: plans of the two streaming products per block width: [v] = A (rows np, columns mp),
   // [2 + v] = A^T (rows mp, columns np)
@@ -194,101 +196,37 @@ int ur_blocks(const bbmm_ctx* c, int n, int ld) {
   return std::max(1, std::min(nb, cap));
 }
 
-// Row chunks of a kernel whose workgroups each take one strip of columns and one chunk of rows:
-// the smallest count from `want_wgs` workgroups up for which strips * chunks fills whole rounds of
-// num_cus workgroups to `min_fill` (else the best filling seen).  Fewer chunks mean fewer partial
-// results to add afterwards; a last round in which only some compute units have work is what
-// costs time.
 int split_by_fill(const bbmm_ctx* c, int strips, int want_wgs, double min_fill) {
-  int cap = std::min(kMaxSplit, c->np / 16);
-  int s0 = std::max(1, std::min(cap, (want_wgs + strips - 1) / strips));
-  int best = s0;
-  double best_fill = 0.0;
-  for (int s = s0; s <= cap; ++s) {
-    int wgs = strips * s;
-    int rounds = (wgs + c->num_cus - 1) / c->num_cus;
-    double fill = (double)wgs / ((double)rounds * c->num_cus);
-    if (fill > best_fill + 1e-12) {
-      best_fill = fill;
-      best = s;
-    }
-    if (fill >= min_fill) break;
-  }
-  return best;
+  return bbmm_plan::split_by_fill(c->np, c->num_cus, strips, want_wgs, min_fill);
 }
 
-// Workgroups of the materialised product.  The kernel keeps its own loads in flight, so one
-// workgroup per compute unit already saturates that unit's share of HBM; the plan deals the
-// (strip, row step) units out evenly, so whole rounds of num_cus workgroups leave no tail.
-// Bounds: at least one workgroup per strip (a run then spans at most two strips), at most
-// kMaxSplit partial slots per strip (checked when the plan is laid out), at most one workgroup per unit.
 int mat_wgs_of(const bbmm_ctx* c, int ld, bool narrow) {
-  int cols_per_wg = (ld == 16) ? 1024 : 512;
-  int strips = (c->np + cols_per_wg - 1) / cols_per_wg;
-  long long units = (long long)strips * (c->np / 16);
-  long long w = (c->mat_wgs > 0) ? c->mat_wgs
-                                 : (long long)c->num_cus * ((strips + c->num_cus - 1) / c->num_cus);
-  if (c->mat_wgs <= 0 && narrow && strips <= c->num_cus) {
-    // (Blocks of at most 12 columns only, whose product is the most memory-bound.  With 13..16
-    // columns one workgroup per unit is 1-5 % faster again, and the 32-column product is bound by the
-    // fp64 matrix pipe and wants every unit: 2.38 ms on 256 workgroups against 3.07 ms on 196 at
-    // n = 50 000.)
-    // Measured (n = 5 000 ... 50 000): a whole number of workgroups per strip (no run crosses a strip
-    // boundary and pays two prologues) beats one workgroup per unit by 2 % at n = 50 000 and by
-    // 5-11 % below it, where short runs do best on about 0.8 of the units; a matrix of a few
-    // thousand rows does best with at least six 16-row steps per workgroup (n = 1 000, 2 500).
-    int steps = c->np / 16;
-    int per = std::max(1, (int)(0.8 * c->num_cus / strips + 0.5));
-    if (steps / per >= 512) per = c->num_cus / strips;
-    bool enough = (long long)per * strips * 4 >= (long long)c->num_cus * 3;
-    int cap = std::max(1, steps / 6);
-    if (per > cap) {
-      per = cap;
-      enough = true;
-    }
-    if (enough) w = (long long)per * strips;
-  }
-  w = std::min<long long>(w, (long long)(kMaxSplit - 4) * strips);
-  w = std::min<long long>(w, units);
-  w = std::max<long long>(w, strips);
-  return (int)w;
+  return bbmm_plan::mat_wgs_of(c->np, c->num_cus, c->mat_wgs, ld, narrow);
 }
 
-// Lays out one plan on the host and uploads it: the units (strip of output columns, 16-row step)
-// of a rows_p x cols_p matrix, in strip-major order, are dealt to `wgs` workgroups in equal
-// contiguous runs; a run that crosses strip boundaries becomes several pieces, each with its own
-// partial slot in its strip.  Everything the kernel relies on (rows inside the matrix, slot below
-// slot_cap, at most BBMM_MM_PIECES pieces) is checked here.
+// Partial results of a product: `slots` blocks of np x ld doubles.  Grown on demand, per mode and
+// block width (the largest user is the triangle product: up to one slot per panel).
+int ensure_vp(bbmm_ctx* c, int slots, int ld) {
+  size_t bytes = (size_t)std::max(slots, 1) * c->np * ld * sizeof(double);
+  if (bytes <= c->Vp.cap) return BBMM_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));   // earlier launches may still use the old buffer
+  return ensure(c, c->Vp, bytes);
+}
+
+// Lays out one plan on the host (bbmm_plan::lay_out_plan, which checks everything the kernel
+// relies on) and uploads it.
 int make_plan(bbmm_ctx* c, int rows_p, int cols_p, int ld, int wgs, int slot_cap, Buf& plan_buf,
               Buf& nseg_buf, int* max_slots) {
-  int cols_per_wg = (ld == 32) ? 512 : 1024;
-  int strips = (cols_p + cols_per_wg - 1) / cols_per_wg;
-  int steps = rows_p / 16;
-  long long units = (long long)strips * steps;
-  std::vector<MmPlan> plan((size_t)wgs);
-  std::vector<int> nseg((size_t)strips, 0);
-  for (int w = 0; w < wgs; ++w) {
-    long long b = units * w / wgs, e = units * (w + 1) / wgs;
-    for (int pc = 0; pc < BBMM_MM_PIECES; ++pc) {
-      MmPiece P = {0, 0, 0, 0};
-      if (b < e) {
-        int strip = (int)(b / steps), jb = (int)(b % steps);
-        int je = (int)std::min<long long>(steps, jb + (e - b));
-        P = MmPiece{strip, jb * 16, je * 16, nseg[strip]++};
-        b += je - jb;
-        if (strip >= strips || P.row_end > rows_p || P.slot >= slot_cap)
-          return fail(c, BBMM_EINVAL, "internal: product plan out of range");
-      }
-      plan[w].piece[pc] = P;
-    }
-    if (b < e) return fail(c, BBMM_EINVAL, "internal: product plan needs too many pieces");
-  }
-  int rc = ensure(c, plan_buf, sizeof(MmPlan) * (size_t)wgs);
+  std::vector<MmPlan> plan;
+  std::vector<int> nseg;
+  if (const char* what = bbmm_plan::lay_out_plan(rows_p, cols_p, ld, wgs, slot_cap, plan, nseg))
+    return fail(c, BBMM_EINVAL, what);
+  int rc = ensure(c, plan_buf, sizeof(MmPlan) * plan.size());
   if (rc) return rc;
-  rc = ensure(c, nseg_buf, sizeof(int) * (size_t)strips);
+  rc = ensure(c, nseg_buf, sizeof(int) * nseg.size());
   if (rc) return rc;
-  HIPCHK(c, hipMemcpy(plan_buf.p, plan.data(), sizeof(MmPlan) * (size_t)wgs, hipMemcpyHostToDevice));
-  HIPCHK(c, hipMemcpy(nseg_buf.p, nseg.data(), sizeof(int) * (size_t)strips, hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(plan_buf.p, plan.data(), sizeof(MmPlan) * plan.size(), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(nseg_buf.p, nseg.data(), sizeof(int) * nseg.size(), hipMemcpyHostToDevice));
   if (max_slots) *max_slots = *std::max_element(nseg.begin(), nseg.end());
   return BBMM_OK;
 }
@@ -300,7 +238,7 @@ int ensure_mat_plans(bbmm_ctx* c) {
   for (int v = 0; v < 3; ++v) {
     int ld = (v == 1) ? 32 : 16;
     int wgs = mat_wgs_of(c, ld, v == 2);
-    int rc = make_plan(c, c->np, c->np, ld, wgs, kMaxSplit, c->plan[v], c->nseg[v], nullptr);
+    int rc = make_plan(c, c->np, c->np, ld, wgs, kMaxSplit, c->plan[v], c->nseg[v], &c->plan_slots[v]);
     if (rc) return rc;
     c->plan_wgs[v] = wgs;
   }
@@ -309,79 +247,30 @@ int ensure_mat_plans(bbmm_ctx* c) {
   return BBMM_OK;
 }
 
-// Work lists of a product that visits only the panels (W columns each) on and above the diagonal.
-// Panel P offers P * W / 16 steps above its diagonal block, in which every tile is used twice, and
-// up to W / 16 steps inside it, used once; each kind is cut into runs of equal length for `want`
-// workgroups of its own list.  Output panel s then has cnt[s] column-side partial results (one per
-// piece of panel s) followed by one row-side partial result from every panel right of it.
+// Work lists of a product that visits only the panels (W columns each) on and above the diagonal
+// (bbmm_plan::lay_out_triangle), uploaded.
 int build_tri_lists(bbmm_ctx* c, int W, int want, int64_t tune, TriLists& L) {
   if (L.np == c->np && L.tune == tune) return BBMM_OK;
   HIPCHK(c, hipStreamSynchronize(c->stream));   // earlier launches may still read the old lists
-  const int S = (c->np + W - 1) / W;
-  struct Seg {
-    int strip, row_begin, steps;
-  };
-  std::vector<MmPiece> pieces;
-  std::vector<int> cnt((size_t)S, 0), first[2];
-  int wgs[2] = {0, 0};
-  for (int kind = 0; kind < 2; ++kind) {   // 0: above the diagonal blocks, 1: inside them
-    std::vector<Seg> segs;
-    long long total = 0;
-    for (int P = 0; P < S; ++P) {
-      Seg g = kind == 0 ? Seg{P, 0, P * W / 16} : Seg{P, P * W, (std::min(c->np, (P + 1) * W) - P * W) / 16};
-      if (g.steps > 0) segs.push_back(g);
-      total += g.steps;
-    }
-    int nw = (int)std::min<long long>(want, total);
-    wgs[kind] = nw;
-    first[kind].assign((size_t)nw + 1, (int)pieces.size());
-    size_t si = 0;
-    int off = 0;
-    long long done = 0;
-    for (int w = 0; w < nw; ++w) {
-      first[kind][(size_t)w] = (int)pieces.size();
-      long long target = total * (w + 1) / nw;
-      while (si < segs.size() && done < target) {
-        const Seg& g = segs[si];
-        int take = (int)std::min<long long>(g.steps - off, target - done);
-        pieces.push_back(MmPiece{g.strip, g.row_begin + off * 16, g.row_begin + (off + take) * 16,
-                                 cnt[(size_t)g.strip]++});
-        done += take;
-        off += take;
-        if (off == g.steps) {
-          ++si;
-          off = 0;
-        }
-      }
-    }
-    first[kind][(size_t)nw] = (int)pieces.size();
-    if (si != segs.size() || done != total) return fail(c, BBMM_EINVAL, "internal: triangle work list incomplete");
-  }
-  std::vector<int> tot((size_t)S);
-  int max_slots = 0;
-  for (int s = 0; s < S; ++s) {
-    tot[(size_t)s] = cnt[(size_t)s] + (S - 1 - s);
-    max_slots = std::max(max_slots, tot[(size_t)s]);
-  }
-  // partial-result slots are whole n x 32 blocks; more of them than the other modes ever use
-  int rc = ensure(c, c->Vp, (size_t)max_slots * c->np * BBMM_MAXC * sizeof(double));
-  if (rc) return rc;
+  bbmm_plan::TriHost H;
+  if (const char* what = bbmm_plan::lay_out_triangle(c->np, W, want, H)) return fail(c, BBMM_EINVAL, what);
   struct Up {
     Buf* b;
     const void* src;
     size_t bytes;
-  } ups[] = {{&L.pieces, pieces.data(), sizeof(MmPiece) * pieces.size()},
-             {&L.first0, first[0].data(), sizeof(int) * first[0].size()},
-             {&L.first1, first[1].data(), sizeof(int) * first[1].size()},
-             {&L.base, cnt.data(), sizeof(int) * cnt.size()},
-             {&L.tot, tot.data(), sizeof(int) * tot.size()}};
+  } ups[] = {{&L.pieces, H.pieces.data(), sizeof(MmPiece) * H.pieces.size()},
+             {&L.first0, H.first[0].data(), sizeof(int) * H.first[0].size()},
+             {&L.first1, H.first[1].data(), sizeof(int) * H.first[1].size()},
+             {&L.base, H.cnt.data(), sizeof(int) * H.cnt.size()},
+             {&L.tot, H.tot.data(), sizeof(int) * H.tot.size()}};
   for (const Up& u : ups) {
-    rc = ensure(c, *u.b, u.bytes);
+    int rc = ensure(c, *u.b, std::max<size_t>(u.bytes, 16));
     if (rc) return rc;
-    HIPCHK(c, hipMemcpy(u.b->p, u.src, u.bytes, hipMemcpyHostToDevice));
+    if (u.bytes) HIPCHK(c, hipMemcpy(u.b->p, u.src, u.bytes, hipMemcpyHostToDevice));
   }
-  L.wgs[0] = wgs[0];
-  L.wgs[1] = wgs[1];
+  L.wgs[0] = H.wgs[0];
+  L.wgs[1] = H.wgs[1];
+  L.max_slots = H.max_slots;
   L.np = c->np;
   L.tune = tune;
   return BBMM_OK;
@@ -397,21 +286,8 @@ int ensure_otf_tri_plan(bbmm_ctx* c) {
                          c->otft);
 }
 
-// Workgroups for streaming a rows_p x cols_p matrix.  With at least one column strip per compute
-// unit every workgroup takes one whole strip: a piece that ends inside a strip costs a pipeline
-// drain, a partial result to store and one more to add later (measured at 1024 x 500,224: 373 us
-// with 256 balanced runs of ~3 pieces, 320 us with 489 whole strips).  Otherwise whole rounds of
-// num_cus balanced runs, never more than there are units.
 int rect_wgs_of(const bbmm_ctx* c, int rows_p, int cols_p, int ld, int slot_cap, int64_t tuned) {
-  int cols_per_wg = (ld == 32) ? 512 : 1024;
-  int strips = (cols_p + cols_per_wg - 1) / cols_per_wg;
-  long long units = (long long)strips * (rows_p / 16);
-  long long w = (strips >= c->num_cus) ? strips : c->num_cus;
-  if (tuned > 0) w = tuned;
-  w = std::min<long long>(w, (long long)(slot_cap - 4) * strips);
-  w = std::min<long long>(w, units);
-  w = std::max<long long>(w, std::min<long long>(units, (strips + 1) / 2));
-  return (int)std::max<long long>(w, 1);
+  return bbmm_plan::rect_wgs_of(c->num_cus, rows_p, cols_p, ld, slot_cap, tuned);
 }
 
 constexpr int kSgprSlotCap = 1024;   // partial results of A^T D: one per workgroup when m <= 1024
@@ -576,6 +452,8 @@ int stage_sgpr_build(bbmm_ctx* c) {
 // cols: columns of the block in use (0 = all).
 int sgpr_second_pass(bbmm_ctx* c, int ld, VpShape* shape, int cols = 0) {
   int v = (ld == 32) ? 1 : 0;
+  int rc0 = ensure_vp(c, c->sg_slots[2 + v], ld);
+  if (rc0) return rc0;
   if (launch_mm_mat(c->stream, ptr<float>(c->AT), ptr<double>(c->T4), ptr<double>(c->Vp), c->np, ld,
                     ptr<MmPlan>(c->sgplan[2 + v]), c->sg_wgs[2 + v], ptr<DevState>(c->st), BBMM_SGPR_PANEL,
                     c->mp, cols))
@@ -616,6 +494,8 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     if (c->khat_tri) {
       int rc = ensure_sym_plan(c);
       if (rc) return rc;
+      rc = ensure_vp(c, c->sym.max_slots, ld);
+      if (rc) return rc;
       if (launch_mm_sym(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld, cc,
                         ptr<MmPiece>(c->sym.pieces), ptr<int>(c->sym.first0), c->sym.wgs[0],
                         ptr<int>(c->sym.first1), c->sym.wgs[1], ptr<int>(c->sym.base), ptr<DevState>(c->st)))
@@ -628,6 +508,8 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     int rc = ensure_mat_plans(c);
     if (rc) return rc;
     int v = (ld == 32) ? 1 : (cc <= 12 ? 2 : 0);
+    rc = ensure_vp(c, c->plan_slots[v], ld);
+    if (rc) return rc;
     if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
                       ptr<MmPlan>(c->plan[v]), c->plan_wgs[v], ptr<DevState>(c->st), c->khat_pw, c->np, cc))
       return fail(c, BBMM_EINVAL, "unsupported block width");
@@ -641,6 +523,8 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     // so it is for small n, where the pieces of the two-use form are short)
     int rc = ensure_otf_tri_plan(c);
     if (rc) return rc;
+    rc = ensure_vp(c, c->otft.max_slots, ld);
+    if (rc) return rc;
     if (launch_mm_otf_tri(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb), ptr<float>(c->sq),
                           ptr<double>(c->D4), ptr<double>(c->Vp), c->np, cc, ptr<MmPiece>(c->otft.pieces),
                           ptr<int>(c->otft.first0), c->otft.wgs[0], ptr<int>(c->otft.first1), c->otft.wgs[1],
@@ -651,6 +535,8 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     *addD = c->prob.noise;
   } else if (mode == BBMM_MODE_ONTHEFLY) {
     int ns = otf_split_of(c);
+    int rc = ensure_vp(c, ns, ld);
+    if (rc) return rc;
     if (launch_mm_otf(c->stream, c->prob.kernel, c->KK, ptr<float>(c->Xa), ptr<float>(c->Xb),
                       ptr<float>(c->sq), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld, cc, ns,
                       ptr<DevState>(c->st)))
@@ -1106,7 +992,6 @@ int bbmm_setup(bbmm_ctx* c, const bbmm_problem* in) {
       {&c->Xa, opx}, {&c->Xb, opx}, {&c->Xs, opx}, {&c->X4, opx}, {&c->sq, np * sizeof(float)},
       {&c->L, np * std::max(c->kp, 8) * sizeof(double)}, {&c->delta, np * sizeof(double)},
       {&c->U, blk}, {&c->R, blk}, {&c->V, blk}, {&c->Z0, blk}, {&c->D4, blk},
-      {&c->Vp, (size_t)kMaxSplit * blk},
       {&c->partial, sizeof(double) * (size_t)kMaxVecBlocks * (BBMM_MAXK * BBMM_MAXK + (BBMM_MAXK + 1) * BBMM_MAXC)},
       {&c->gpartial, sizeof(double) * 40 * (BBMM_MAXK * BBMM_MAXK + (BBMM_MAXK + 1) * BBMM_MAXC)},
       {&c->alpha, sizeof(double) * BBMM_MAXP * BBMM_MAXC}, {&c->beta, sizeof(double) * BBMM_MAXP * BBMM_MAXC},

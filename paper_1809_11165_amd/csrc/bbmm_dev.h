@@ -48,16 +48,8 @@ struct HypArgs {
   int d;
 };
 
-// Work of one workgroup of the materialised product: up to BBMM_MM_PIECES pieces, each a run of
-// matrix rows [row_begin, row_end) (multiples of 16) inside one strip of output columns, whose
-// partial result goes to slot `slot` of that strip.  An unused piece has row_begin == row_end.
-#define BBMM_MM_PIECES 4
-struct MmPiece {
-  int strip, row_begin, row_end, slot;
-};
-struct MmPlan {
-  MmPiece piece[BBMM_MM_PIECES];
-};
+// MmPiece / MmPlan (work of one workgroup of a streaming product) come from bbmm_plan.h.
+#include "bbmm_plan.h"
 
 // How the partial products in Vp are to be summed: `nsplit` slots for every row, or, when nseg is
 // set, nseg[row / seg_cols] slots.

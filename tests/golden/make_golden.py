@@ -40,6 +40,12 @@ CASES = {
     "cfg2_n10000_cap128": (2, 10000, {"iters": 128}),
     "cfg3_n50000": (3, 50000, {}),
     "cfg4_sub_n20000": (4, 20000, {}),
+    # converged caps: the same problems run for a fixed number of iterations at which the oracle's
+    # last update is ~1e-5 of the iterate or less (cfg 2: 160, no tolerance stop; cfg 3: 100;
+    # cfg 4 mixture: 200), so that 1e-3 on every solve column is a well-defined bound
+    "cfg2_n10000_cap160": (2, 10000, {"iters": 160, "tol": 0.0}),
+    "cfg3_n50000_cap100": (3, 50000, {"iters": 100}),
+    "cfg4_sub_n20000_cap200": (4, 20000, {"iters": 200}),
 }
 
 

@@ -37,6 +37,20 @@ def test_bench_prints_one_json_line_with_roofline_and_cpu_baseline(mode):
     assert roof["traffic"] is None                     # the measured byte counts belong to n = 50000 only
     cpu = out["cpu_baseline"]
     assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["unit"] == "ms"
+    # the oracle timed by stage at the benchmark's own n, the small-n extrapolation beside it
+    assert set(cpu["stages"]) == {"build_s", "product_s_per_iteration", "vector_s_per_iteration", "derivative_s"}
+    assert cpu["extrapolated_from_small_n"]["value"] > 0
+    if mode == "sym":
+        # the default line also carries the other two product modes, measured in the same run
+        mat, otf = out["roofline_mat"], out["roofline_otf"]
+        assert mat["bound"] == "hbm" and mat["unit"] == "GB/s" and mat["peak"] == 8000.0
+        assert otf["bound"] == "mfma" and otf["unit"] == "TFLOP/s"
+        for leg in (mat, otf):
+            assert leg["frac"] == pytest.approx(leg["achieved"] / leg["peak"]) and leg["ms_per_call"] > 0
+            assert leg["launches"] == 3 * 50
+            assert leg["logdet"] == pytest.approx(out["config"]["logdet"], rel=1e-3)
+    else:
+        assert "roofline_mat" not in out and "roofline_otf" not in out
 
 
 def test_bench_refuses_more_than_one_gpu():
