@@ -196,6 +196,12 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *   "zd_blocks"  workgroups per compute unit of the direction update (default 16, at most 64)
  *   "sgpr_wgs1", "sgpr_wgs2"  workgroups of the two streaming products of an SGPR product
  *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build
+ *   "loop_graph" 1 (default): the iteration loop of an mBCG run whose launch sequence equals that of
+ *                an earlier run of this context (same sizes, mode, tuning values and buffers; the
+ *                hyperparameters and the tolerance may differ, the loop's kernels read them from
+ *                device memory) is replayed as one HIP graph, recorded at the second such run;
+ *                0: every kernel is launched on its own.  Same kernels, same results.  Runs with
+ *                "time_mm" set are never replayed
  *   "eig_sweeps" trip budget of the tridiagonal eigen-solver per matrix row (sweeps and deflations;
  *                default 60, at most 1000; about two sweeps per eigenvalue are needed).  A matrix
  *                not reduced within it makes the call return BBMM_ENOCONV
@@ -209,6 +215,10 @@ int bbmm_tune(bbmm_ctx* ctx, const char* key, int64_t value);
  * context's stream (needs bbmm_tune("time_mm", 1) before the run).  Only launches of iterations
  * that really executed are counted.  avg_ms, total_ms, launches: host (each optional). */
 int bbmm_mm_timing(bbmm_ctx* ctx, double* avg_ms, double* total_ms, int64_t* launches);
+
+/* How often this context has recorded the iteration loop of Alg. 2 as a HIP graph and how often
+ * it has replayed one (see "loop_graph" above).  captures, replays: host, each optional. */
+int bbmm_loop_graph_stats(bbmm_ctx* ctx, int64_t* captures, int64_t* replays);
 
 /* The whole path (Sec. 3 + Sec. 4): preconditioner, probes, mBCG, log-det, traces. */
 int bbmm_solve_logdet_grad(bbmm_ctx* ctx, const bbmm_problem* in, bbmm_result* out);

@@ -23,7 +23,7 @@ OK, EINVAL, ENOMEM, ENOTPD, ENONFINITE, EHIP, ENOCONV = 0, 1, 2, 3, 4, 5, 6
 MAX_ITERS = 256
 
 EXPORTS = [
-    "bbmm_create", "bbmm_destroy", "bbmm_last_error", "bbmm_tune", "bbmm_mm_timing",
+    "bbmm_create", "bbmm_destroy", "bbmm_last_error", "bbmm_tune", "bbmm_mm_timing", "bbmm_loop_graph_stats",
     "bbmm_solve_logdet_grad",
     "bbmm_setup", "bbmm_build_khat", "bbmm_khat_block", "bbmm_sgpr_build", "bbmm_sgpr_root_rows",
     "bbmm_kernel_mm", "bbmm_pivoted_cholesky",
@@ -83,6 +83,7 @@ def load_library() -> C.CDLL:
     lib.bbmm_tune.argtypes = [C.c_void_p, C.c_char_p, C.c_int64]
     lib.bbmm_mm_timing.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double),
                                    C.POINTER(C.c_int64)]
+    lib.bbmm_loop_graph_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.bbmm_solve_logdet_grad.argtypes = [C.c_void_p, C.POINTER(_Problem), C.POINTER(_Result)]
     lib.bbmm_setup.argtypes = [C.c_void_p, C.POINTER(_Problem)]
     lib.bbmm_build_khat.argtypes = [C.c_void_p]
@@ -259,6 +260,12 @@ class Context:
         avg, tot, cnt = C.c_double(0.0), C.c_double(0.0), C.c_int64(0)
         self._ck(self.lib.bbmm_mm_timing(self.h, C.byref(avg), C.byref(tot), C.byref(cnt)))
         return float(avg.value), float(tot.value), int(cnt.value)
+
+    def bbmm_loop_graph_stats(self):
+        """(graphs recorded, graphs replayed) by this context so far."""
+        cap, rep = C.c_int64(0), C.c_int64(0)
+        self._ck(self.lib.bbmm_loop_graph_stats(self.h, C.byref(cap), C.byref(rep)))
+        return int(cap.value), int(rep.value)
 
     def bbmm_solve_logdet_grad(self, prob: Problem, want_U: bool = True) -> Result:
         p = prob.to_c()

@@ -48,6 +48,17 @@ constexpr int kDkStride = 2 * (BBMM_MAXD + 2);
 
 }  // namespace
 
+// Everything the launch sequence of the iteration loop depends on.
+struct LoopKey {
+  uint64_t alloc_epoch, tune_epoch;
+  int mode, kernel, n, d, cc, ld, kp, maxit, m, tri, nls;
+  bool operator==(const LoopKey& o) const {
+    return alloc_epoch == o.alloc_epoch && tune_epoch == o.tune_epoch && mode == o.mode && kernel == o.kernel &&
+           n == o.n && d == o.d && cc == o.cc && ld == o.ld && kp == o.kp && maxit == o.maxit && m == o.m &&
+           tri == o.tri && nls == o.nls;
+  }
+};
+
 struct bbmm_ctx {
   int device = 0;
   int num_cus = 256;          // compute units of the device (hipDeviceProp_t::multiProcessorCount)
@@ -88,6 +99,20 @@ struct bbmm_ctx {
   int sg_np = 0, sg_mp = 0, sg_wgs[4] = {0, 0, 0, 0}, sg_slots[4] = {0, 0, 0, 0};
   int64_t sg_tune[2] = {-1, -1};
   int64_t eig_sweeps = 0;                    // trip budget of the tridiagonal eigen-solver per row (0 = default)
+  // The mBCG iteration loop as a HIP graph: replayed when a run has the same launch sequence as an
+  // earlier one (same sizes, mode, tuning values and buffers; the hyperparameters are read from the
+  // device state, so a training loop replays one graph).
+  int64_t use_graph = 1;                     // "loop_graph": 0 = always launch kernel by kernel
+  uint64_t alloc_epoch = 0, tune_epoch = 0;  // bumped by every (re)allocation / bbmm_tune call
+  hipStream_t cap = nullptr;                 // capture stream (the caller's may be the null stream)
+  struct LoopGraph {
+    LoopKey key;
+    hipGraphExec_t exec = nullptr;           // NULL: key seen once, launched eagerly, not captured yet
+    uint64_t used = 0;
+  };
+  std::vector<LoopGraph> graphs;
+  uint64_t graph_clock = 0;
+  int graph_replays = 0, graph_captures = 0; // statistics (bbmm_tune("loop_graph", -1) reads nothing; tests use timing)
   bool side_busy = false;                    // work was forked to `side` and its join has not been queued yet
   bool time_mm = false;                      // record HIP events around every product launch
   std::vector<hipEvent_t> ev;                // 2 per iteration, created on demand
@@ -136,6 +161,7 @@ int ensure(bbmm_ctx* c, Buf& b, size_t bytes) {
   }
   b.p = p;
   b.cap = bytes;
+  if (c) ++c->alloc_epoch;
   return BBMM_OK;
 }
 
@@ -641,6 +667,17 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld, const float* warm = nullpt
   }
   launch_zd(s, 1, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<double>(c->L), ptr<double>(c->D4),
             ptr<double>(c->Z0), st, nb);
+  // the loop's kernels take noise, tolerance and the (scale, diagonal) pair of the product from the
+  // device state, so their launches are the same for any hyperparameter values
+  {
+    double scaleV = 1.0, addD = 0.0;
+    if (mode == BBMM_MODE_SGPR) addD = noise;
+    else if (mode == BBMM_MODE_ONTHEFLY) {
+      scaleV = c->prob.outputscale;
+      addD = noise;
+    }
+    launch_set_loop_scalars(s, st, noise, c->prob.tol, scaleV, addD);
+  }
   if (c->time_mm) {
     while ((int)c->ev.size() < 2 * c->maxit) {
       hipEvent_t e;
@@ -649,23 +686,99 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld, const float* warm = nullpt
     }
   }
   c->ev_iters = 0;
-  for (int j = 0; j < c->maxit; ++j) {
-    VpShape ns{0, nullptr, 1};
-    double scaleV = 1.0, addD = 0.0;
-    if (c->time_mm) HIPCHK(c, hipEventRecord(c->ev[2 * j], s));
-    int rc = stage_mm(c, mode, cc, ld, &ns, &scaleV, &addD);
-    if (rc) return rc;
-    if (c->time_mm) {
-      HIPCHK(c, hipEventRecord(c->ev[2 * j + 1], s));
-      c->ev_iters = j + 1;
+  // one pass over the maxit iterations on stream `ls`, kernel by kernel
+  auto launch_loop = [&](hipStream_t ls, bool timed) -> int {
+    hipStream_t user = c->stream;
+    c->stream = ls;                       // stage_mm queues on the context's stream
+    int rc = BBMM_OK;
+    for (int j = 0; j < c->maxit && rc == BBMM_OK; ++j) {
+      VpShape ns{0, nullptr, 1};
+      double scaleV = 1.0, addD = 0.0;
+      if (timed && hipEventRecord(c->ev[2 * j], ls) != hipSuccess) rc = fail(c, BBMM_EHIP, "hipEventRecord failed");
+      if (rc == BBMM_OK) rc = stage_mm(c, mode, cc, ld, &ns, &scaleV, &addD);
+      if (rc) break;
+      if (timed) {
+        if (hipEventRecord(c->ev[2 * j + 1], ls) != hipSuccess) {
+          rc = fail(c, BBMM_EHIP, "hipEventRecord failed");
+          break;
+        }
+        c->ev_iters = j + 1;
+      }
+      launch_dv(ls, ptr<double>(c->Vp), ns, c->n, c->np, ld, scaleV, -1.0, ptr<double>(c->D4),
+                ptr<double>(c->V), st, pdv, nb);
+      launch_ur(ls, 0, c->n, ld, cc, c->kp, -1.0, 0.0, ptr<double>(c->D4), ptr<double>(c->V),
+                ptr<double>(c->U), ptr<double>(c->R), ptr<double>(c->L), st, pdv, nb, pur, nb_ur, j,
+                ptr<double>(c->alpha), ptr<double>(c->beta), ptr<double>(c->resid));
+      launch_zd(ls, 0, c->n, ld, c->kp, -1.0, ptr<double>(c->R), ptr<double>(c->L), ptr<double>(c->D4),
+                ptr<double>(c->Z0), st, nb_zd);
     }
-    launch_dv(s, ptr<double>(c->Vp), ns, c->n, c->np, ld, scaleV, addD, ptr<double>(c->D4),
-              ptr<double>(c->V), st, pdv, nb);
-    launch_ur(s, 0, c->n, ld, cc, c->kp, noise, c->prob.tol, ptr<double>(c->D4), ptr<double>(c->V),
-              ptr<double>(c->U), ptr<double>(c->R), ptr<double>(c->L), st, pdv, nb, pur, nb_ur, j,
-              ptr<double>(c->alpha), ptr<double>(c->beta), ptr<double>(c->resid));
-    launch_zd(s, 0, c->n, ld, c->kp, noise, ptr<double>(c->R), ptr<double>(c->L), ptr<double>(c->D4),
-              ptr<double>(c->Z0), st, nb_zd);
+    c->stream = user;
+    return rc;
+  };
+  bool replayed = false;
+  if (c->use_graph && !c->time_mm && c->cap) {
+    LoopKey key{c->alloc_epoch, c->tune_epoch, mode, c->prob.kernel, c->n, c->d, cc, ld, c->kp, c->maxit, c->m,
+                c->khat_tri ? 1 : 0, (int)c->prob.n_lengthscale};
+    // graphs recorded against buffers or tuning values that are gone can never be replayed again
+    for (size_t i = 0; i < c->graphs.size();) {
+      if (c->graphs[i].key.alloc_epoch != c->alloc_epoch || c->graphs[i].key.tune_epoch != c->tune_epoch) {
+        if (c->graphs[i].exec) (void)hipGraphExecDestroy(c->graphs[i].exec);
+        c->graphs.erase(c->graphs.begin() + (long)i);
+      } else {
+        ++i;
+      }
+    }
+    bbmm_ctx::LoopGraph* g = nullptr;
+    for (auto& e : c->graphs)
+      if (e.key == key) g = &e;
+    if (!g) {
+      // first run with this launch sequence: kernel by kernel (it also lays out plans and grows
+      // buffers, which a capture must not do); if nothing was allocated the next run captures it
+      int rc = launch_loop(s, false);
+      if (rc) return rc;
+      replayed = true;
+      if (key.alloc_epoch == c->alloc_epoch) {
+        if (c->graphs.size() >= 8) {
+          size_t old = 0;
+          for (size_t i = 1; i < c->graphs.size(); ++i)
+            if (c->graphs[i].used < c->graphs[old].used) old = i;
+          if (c->graphs[old].exec) (void)hipGraphExecDestroy(c->graphs[old].exec);
+          c->graphs.erase(c->graphs.begin() + (long)old);
+        }
+        c->graphs.push_back(bbmm_ctx::LoopGraph{key, nullptr, ++c->graph_clock});
+      }
+    } else {
+      if (!g->exec) {
+        hipGraph_t graph = nullptr;
+        bool ok = hipStreamBeginCapture(c->cap, hipStreamCaptureModeThreadLocal) == hipSuccess;
+        int rc = BBMM_OK;
+        if (ok) {
+          rc = launch_loop(c->cap, false);
+          ok = hipStreamEndCapture(c->cap, &graph) == hipSuccess && graph != nullptr && rc == BBMM_OK;
+        }
+        if (ok) ok = hipGraphInstantiate(&g->exec, graph, nullptr, nullptr, 0) == hipSuccess;
+        if (graph) (void)hipGraphDestroy(graph);
+        if (!ok) {
+          // no graph on this runtime / for this sequence: stay with kernel-by-kernel launches
+          (void)hipGetLastError();
+          g->exec = nullptr;
+          c->use_graph = 0;
+          if (rc) return rc;
+        } else {
+          ++c->graph_captures;
+        }
+      }
+      if (g->exec) {
+        HIPCHK(c, hipGraphLaunch(g->exec, s));
+        g->used = ++c->graph_clock;
+        ++c->graph_replays;
+        replayed = true;
+      }
+    }
+  }
+  if (!replayed) {
+    int rc = launch_loop(s, c->time_mm);
+    if (rc) return rc;
   }
   c->mbcg_done = true;
   c->last_c = cc;
@@ -860,6 +973,7 @@ int bbmm_create(bbmm_ctx** out, int device, void* hip_stream) {
     delete c;
     return BBMM_ENOMEM;
   }
+  if (hipStreamCreateWithFlags(&c->cap, hipStreamNonBlocking) != hipSuccess) c->cap = nullptr;   // no graphs then
   if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess ||
       hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
@@ -878,6 +992,9 @@ int bbmm_destroy(bbmm_ctx* c) {
     (void)hipStreamSynchronize(c->side);
     (void)hipStreamDestroy(c->side);
   }
+  for (auto& g : c->graphs)
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+  if (c->cap) (void)hipStreamDestroy(c->cap);
   if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
   if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   Buf* bufs[] = {&c->Xa, &c->Xb, &c->Xs, &c->X4, &c->sq, &c->Khat, &c->L, &c->delta, &c->U, &c->R, &c->V,
@@ -902,6 +1019,11 @@ const char* bbmm_last_error(const bbmm_ctx* c) { return c ? c->err.c_str() : "co
 
 int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   if (!c || !key) return BBMM_EINVAL;
+  ++c->tune_epoch;
+  if (!strcmp(key, "loop_graph")) {
+    c->use_graph = value != 0;
+    return BBMM_OK;
+  }
   if (!strcmp(key, "mat_wgs")) c->mat_wgs = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_split")) c->otf_split = value > 0 ? value : 0;
   else if (!strcmp(key, "otf_sym")) c->otf_sym = value <= 0 ? 0 : (value == 1 ? 1 : 2);   // off / by size / always
@@ -920,6 +1042,13 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   else if (!strcmp(key, "eig_sweeps")) c->eig_sweeps = value > 0 ? std::min<int64_t>(value, 1000) : 0;
   else if (!strcmp(key, "time_mm")) c->time_mm = value > 0;
   else return fail(c, BBMM_EINVAL, std::string("unknown tuning key: ") + key);
+  return BBMM_OK;
+}
+
+int bbmm_loop_graph_stats(bbmm_ctx* c, int64_t* captures, int64_t* replays) {
+  if (!c) return BBMM_EINVAL;
+  if (captures) *captures = c->graph_captures;
+  if (replays) *replays = c->graph_replays;
   return BBMM_OK;
 }
 

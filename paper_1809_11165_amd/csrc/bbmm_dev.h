@@ -29,6 +29,10 @@ struct DevState {
   double slq_mean;
   double dk_out[2 * (BBMM_MAXD + 3)];  // raw accumulators of the derivative pass
   double xmean[BBMM_MAXD];
+  // scalars of the iteration loop (set once per mBCG run by launch_set_loop_scalars).  The loop's
+  // kernels read them from here when they are handed a negative noise / diagonal term instead, so
+  // that the launches of the loop do not depend on the hyperparameters and can be replayed as a graph.
+  double loop_noise, loop_tol, loop_scaleV, loop_addD;
   int active[BBMM_MAXC];
   int m_valid[BBMM_MAXC];
   int piv[BBMM_MAXK + 1];
@@ -100,6 +104,8 @@ void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, doub
                       double* partial, double* gpartial, int nblocks);
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const double* L,
                    int n, int t, int kp, int ld, double noise, const DevState* st, double* R);
+void launch_set_loop_scalars(hipStream_t s, DevState* st, double noise, double tol, double scaleV, double addD);
+// launch_dv: addD < 0, launch_ur / launch_zd: noise < 0  =>  the scalars come from st->loop_*
 void launch_dv(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                double addD, const double* D4, double* V, const DevState* st, double* partial_dv,
                int nblocks);

@@ -615,6 +615,10 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShap
                                             double* __restrict__ partial_dv) {
   __shared__ double red[VT];
   if (st->done) return;
+  if (addD < 0.0) {
+    scaleV = st->loop_scaleV;
+    addD = st->loop_addD;
+  }
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
   int pq = perm16(q);
   double acc = 0.0;
@@ -858,6 +862,10 @@ __global__ __launch_bounds__(UT) void k_ur_fin(int init, int ld, int c, double n
   // Everything this block needs from the state is requested first, together with the partial
   // sums, so that the kernel pays one memory round trip instead of one per dependent read.
   int done = st->done;
+  if (noise < 0.0) {
+    noise = st->loop_noise;
+    tol = st->loop_tol;
+  }
   int tq = (int)threadIdx.x < ld ? (int)threadIdx.x : 0;
   double s_rho = st->rho[tq], s_bnorm = st->bnorm[tq], s_dv = st->dvtot[tq];
   int s_active = st->active[tq], s_mvalid = st->m_valid[tq];
@@ -979,6 +987,7 @@ __global__ __launch_bounds__(VT) void k_zd(int n, double noise, const double* __
   constexpr int LD = 16 * NQ;
   constexpr int KS = KP / 4;
   if (MODE != 2 && st->done) return;
+  if (noise < 0.0) noise = st->loop_noise;
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int q = lane & 15, g = lane >> 4;
   double beta[NQ];
@@ -1369,6 +1378,19 @@ void launch_pre_setup(hipStream_t s, const double* L, int n, int k, int kp, doub
 void launch_probes(hipStream_t s, const float* y, const float* E1, const float* E2, const double* L,
                    int n, int t, int kp, int ld, double noise, const DevState* st, double* R) {
   k_probes<<<blocks_for((size_t)n * ld, 256), 256, 0, s>>>(y, E1, E2, L, n, t, kp, ld, sqrt(noise), st, R);
+}
+
+__global__ void k_set_loop_scalars(DevState* st, double noise, double tol, double scaleV, double addD) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    st->loop_noise = noise;
+    st->loop_tol = tol;
+    st->loop_scaleV = scaleV;
+    st->loop_addD = addD;
+  }
+}
+
+void launch_set_loop_scalars(hipStream_t s, DevState* st, double noise, double tol, double scaleV, double addD) {
+  k_set_loop_scalars<<<1, 64, 0, s>>>(st, noise, tol, scaleV, addD);
 }
 
 void launch_dv(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,

@@ -616,6 +616,45 @@ def test_full_path_is_deterministic(ctx):
     assert np.array_equal(a.alpha, b.alpha)
 
 
+@pytest.mark.parametrize("mode,tri", [(inputs.ONTHEFLY, 0), (inputs.MATERIALISED, 0), (inputs.MATERIALISED, 1)])
+def test_loop_graph_replays_equal_kernel_by_kernel_launches(ctx, mode, tri):
+    """The mBCG loop replayed as a HIP graph against the same loop launched kernel by kernel: bit
+    for bit, over several replays with other work and synchronisations of the program in between,
+    with the hyperparameters (which the loop's kernels read from the device state, not from their
+    arguments) changing from call to call, and with a tolerance stop that ends one run early."""
+    w = inputs.make(2, n=2100, iters=40)
+    variants = [(0.05, 1.0, 0.0), (0.2, 1.7, 0.0), (0.05, 1.0, 0.15), (0.4, 0.6, 0.3)]   # (noise, outputscale, tol)
+
+    def run(noise, s, tol):
+        w.noise, w.outputscale, w.tol = noise, s, tol
+        return ctx.bbmm_solve_logdet_grad(_problem(w, mode))
+
+    ctx.bbmm_tune("khat_sym", tri)
+    try:
+        ctx.bbmm_tune("loop_graph", 0)
+        ref = [run(*v) for v in variants]
+        assert ref[2].iters_run < 40 and ref[0].iters_run == 40       # the stop rule does end a run early
+        ctx.bbmm_tune("loop_graph", 1)
+        cap0, rep0 = ctx.bbmm_loop_graph_stats()
+        for rep in range(4):                  # run 1 kernel by kernel, run 2 records, later runs replay
+            for v, r in zip(variants, ref):
+                res = run(*v)
+                # the program's own eager work and a synchronisation between the replays
+                junk = torch.randn(512, 512, device="cuda:0") @ torch.randn(512, 512, device="cuda:0")
+                torch.cuda.synchronize()
+                assert torch.equal(res.U, r.U), (rep, v)
+                assert res.iters_run == r.iters_run and res.logdet == r.logdet
+                assert np.array_equal(res.alpha, r.alpha) and np.array_equal(res.beta, r.beta)
+                assert np.array_equal(res.trace, r.trace) and np.array_equal(res.resid, r.resid)
+                del junk
+        cap1, rep1 = ctx.bbmm_loop_graph_stats()
+        # one launch sequence for all four hyperparameter settings: recorded once, replayed 15 times
+        assert (cap1 - cap0, rep1 - rep0) == (1, 15)
+    finally:
+        ctx.bbmm_tune("loop_graph", 1)
+        ctx.bbmm_tune("khat_sym", 0)
+
+
 # -------------------------------------------------------------- edge cases -----
 def test_edge_small_n_rank0_single_probe(ctx):
     w = inputs.tiny(13, 2, kernel=inputs.RBF, t=1, k=0, iters=13, noise=0.3)
