@@ -196,12 +196,20 @@ const char* bbmm_last_error(const bbmm_ctx* ctx);
  *   "zd_blocks"  workgroups per compute unit of the direction update (default 16, at most 64)
  *   "sgpr_wgs1", "sgpr_wgs2"  workgroups of the two streaming products of an SGPR product
  *                (A^T M, then A (.)); clamped like "mat_wgs"; takes effect at the next bbmm_sgpr_build
- *   "loop_graph" 1 (default): the iteration loop of an mBCG run whose launch sequence equals that of
- *                an earlier run of this context (same sizes, mode, tuning values and buffers; the
+ *   "loop_graph" 1: the iteration loop of an mBCG run whose launch sequence equals that of an
+ *                earlier run of this context (same sizes, mode, tuning values and buffers; the
  *                hyperparameters and the tolerance may differ, the loop's kernels read them from
  *                device memory) is replayed as one HIP graph, recorded at the second such run;
- *                0: every kernel is launched on its own.  Same kernels, same results.  Runs with
- *                "time_mm" set are never replayed
+ *                0 (default): every kernel is launched on its own.  Same kernels, same results;
+ *                it frees the calling thread earlier but the GPU time is the same (the chain of
+ *                dependent kernels is bound by dispatch on the device).  Runs with "time_mm" set
+ *                are never replayed
+ *   "slq_eig"    how e_1^T log(T_i) e_1 of the log-det estimate is evaluated.  0 (default): by a
+ *                trapezoid quadrature in ln s of int_0^inf [1/(1+s) - e_1^T (T_i + s I)^{-1} e_1] ds,
+ *                the resolvent being a continued fraction (every node an independent chain of p
+ *                divisions; exact to ~1e-15, no eigenvalues formed); 1: by the eigen-decomposition
+ *                of T_i as App. B writes it (implicit-shift QR, one thread per probe: 0.7 ms at
+ *                p = 50 against ~15 us).  The two agree to 1e-13 ... 2e-10 relative
  *   "eig_sweeps" trip budget of the tridiagonal eigen-solver per matrix row (sweeps and deflations;
  *                default 60, at most 1000; about two sweeps per eigenvalue are needed).  A matrix
  *                not reduced within it makes the call return BBMM_ENOCONV

@@ -98,11 +98,12 @@ struct bbmm_ctx {
   // [2 + v] = A^T (rows mp, columns np)
   int sg_np = 0, sg_mp = 0, sg_wgs[4] = {0, 0, 0, 0}, sg_slots[4] = {0, 0, 0, 0};
   int64_t sg_tune[2] = {-1, -1};
+  int64_t slq_eig = 0;                       // "slq_eig": 1 = SLQ terms through the eigen-decomposition of T
   int64_t eig_sweeps = 0;                    // trip budget of the tridiagonal eigen-solver per row (0 = default)
   // The mBCG iteration loop as a HIP graph: replayed when a run has the same launch sequence as an
   // earlier one (same sizes, mode, tuning values and buffers; the hyperparameters are read from the
   // device state, so a training loop replays one graph).
-  int64_t use_graph = 1;                     // "loop_graph": 0 = always launch kernel by kernel
+  int64_t use_graph = 0;                     // "loop_graph": 0 = always launch kernel by kernel
   uint64_t alloc_epoch = 0, tune_epoch = 0;  // bumped by every (re)allocation / bbmm_tune call
   hipStream_t cap = nullptr;                 // capture stream (the caller's may be the null stream)
   struct LoopGraph {
@@ -789,7 +790,8 @@ int stage_mbcg(bbmm_ctx* c, int mode, int cc, int ld, const float* warm = nullpt
 
 int stage_slq(bbmm_ctx* c, hipStream_t s) {
   if (!c->mbcg_done || c->last_t < 1) return fail(c, BBMM_EINVAL, "bbmm_mbcg with at least one probe column must run first");
-  launch_slq(s, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, eig_sweeps_of(c), ptr<DevState>(c->st));
+  launch_slq(s, ptr<double>(c->alpha), ptr<double>(c->beta), c->last_t, c->slq_eig ? 1 : 0, eig_sweeps_of(c),
+             ptr<DevState>(c->st));
   return BBMM_OK;
 }
 
@@ -1039,6 +1041,7 @@ int bbmm_tune(bbmm_ctx* c, const char* key, int64_t value) {
   } else if (!strcmp(key, "zd_blocks")) c->zd_blocks = value > 0 ? std::min<int64_t>(value, 64) : 0;
   else if (!strcmp(key, "sgpr_wgs1")) c->sgpr_wgs[0] = value > 0 ? value : 0;
   else if (!strcmp(key, "sgpr_wgs2")) c->sgpr_wgs[1] = value > 0 ? value : 0;
+  else if (!strcmp(key, "slq_eig")) c->slq_eig = value > 0;
   else if (!strcmp(key, "eig_sweeps")) c->eig_sweeps = value > 0 ? std::min<int64_t>(value, 1000) : 0;
   else if (!strcmp(key, "time_mm")) c->time_mm = value > 0;
   else return fail(c, BBMM_EINVAL, std::string("unknown tuning key: ") + key);
@@ -1459,7 +1462,7 @@ int bbmm_slq_from_coeffs(bbmm_ctx* c, const double* alpha, const double* beta, c
   HIPCHK(c, hipMemcpyAsync(d_beta, beta, sizeof(double) * np_, hipMemcpyHostToDevice, s));
   HIPCHK(c, hipMemcpyAsync(d_rho0, rho0, sizeof(double) * (size_t)t, hipMemcpyHostToDevice, s));
   HIPCHK(c, hipMemcpyAsync(d_mv, mv.data(), sizeof(int) * (size_t)t, hipMemcpyHostToDevice, s));
-  launch_slq_coeffs(s, d_alpha, d_beta, d_rho0, d_mv, (int)t, eig_sweeps_of(c), d_terms, d_status);
+  launch_slq_coeffs(s, d_alpha, d_beta, d_rho0, d_mv, (int)t, c->slq_eig ? 1 : 0, eig_sweeps_of(c), d_terms, d_status);
   HIPCHK(c, hipMemcpyAsync(terms.data(), d_terms, sizeof(double) * (size_t)t, hipMemcpyDeviceToHost, s));
   HIPCHK(c, hipMemcpyAsync(status.data(), d_status, sizeof(int) * (size_t)t, hipMemcpyDeviceToHost, s));
   HIPCHK(c, hipStreamSynchronize(s));

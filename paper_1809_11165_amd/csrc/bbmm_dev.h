@@ -124,11 +124,13 @@ void launch_cross_dot(hipStream_t s, const float* X, const float* Xs, int n, int
 // sweeps_per_row: trip budget of the tridiagonal eigen-solver per matrix row (sweeps and deflations;
 // about two sweeps per eigenvalue are needed); a matrix that is not reduced within it is reported
 // through st->status / status[] as BBMM_ENOCONV instead of being used.
-void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int sweeps_per_row,
-                DevState* st);
+// eig != 0: e_1^T log(T) e_1 through the eigen-decomposition of T (one thread per probe); 0: through
+// a quadrature of the resolvent e_1^T (T + s I)^{-1} e_1 (all threads; no eigenvalues computed)
+void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int eig,
+                int sweeps_per_row, DevState* st);
 // alpha, beta: p x t row-major; rho0, m_valid: t entries; terms, status: t entries out
 void launch_slq_coeffs(hipStream_t s, const double* alpha, const double* beta, const double* rho0,
-                       const int* m_valid, int t, int sweeps_per_row, double* terms, int* status);
+                       const int* m_valid, int t, int eig, int sweeps_per_row, double* terms, int* status);
 void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,
                         int sweeps_per_row, double* eigvals, double* first_row, int* status);
 void launch_noise_terms(hipStream_t s, const double* U, const double* Z0, const float* y, int n, int ld,

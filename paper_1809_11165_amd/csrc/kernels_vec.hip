@@ -1170,17 +1170,135 @@ __device__ double slq_term(const double* __restrict__ alpha, const double* __res
   return term;
 }
 
+// The same quantity without an eigen-decomposition.  log(x) = int_0^inf [1/(1+s) - 1/(x+s)] ds, so
+//   e_1^T log(T) e_1 = int_0^inf [1/(1+s) - r(s)] ds,   r(s) = e_1^T (T + s I)^{-1} e_1,
+// and with s = e^u the integrand decays like e^{-|u|} on both sides and is analytic for
+// |Im u| < pi: the trapezoid rule with step h converges like exp(-2 pi^2 / h) (h = 1/2: 7e-18).
+// r(s) is the continued fraction delta_m = a_m + s, delta_j = a_j + s - b_j^2 / delta_{j+1},
+// r = 1 / delta_1 (all delta > 0: T + s I is positive definite), and
+//   1/(1+s) - r(s) = (a_1 - 1 - b_1^2 / delta_2) / ((1+s) delta_1)
+// has no cancellation in s.  Every node is one thread's chain of m divisions, the nodes of all
+// probes run side by side: microseconds where the serial QR sweeps of one thread per probe take
+// most of a millisecond at m = 50 (a rotation is ~25 dependent fp64 instructions).  The range of u
+// needs bounds of the spectrum: Gershgorin from above, and from below the largest G 2^-i (i < 64)
+// under which no eigenvalue lies, by Sturm counts taken side by side as well.  The eigenvalues
+// never appear, so clusters of near-duplicate Ritz values need no care.
+// Agreement with the eigen-decomposition route: 1e-13 ... 2e-10 relative (condition 2e8).
+constexpr int SLQ_THREADS = 256;
+constexpr double SLQ_H = 0.5;        // trapezoid step in u = ln s
+constexpr double SLQ_PAD = 37.0;     // e^-37 = 9e-17: what is cut off at either end
+
+// All SLQ_THREADS threads of the block call this; the result is valid in thread 0.
+// a, b2: LDS, BBMM_MAXP doubles each; red: LDS, SLQ_THREADS doubles; cnt: LDS, 65 ints.
+__device__ double slq_term_quadrature(const double* __restrict__ alpha, const double* __restrict__ beta,
+                                      size_t stride, int m, double rho0, double* a, double* b2, double* red,
+                                      int* cnt, int* status) {
+  int tid = threadIdx.x;
+  if (m > BBMM_MAXP) m = BBMM_MAXP;
+  if (m <= 0) {
+    if (tid == 0) *status = 0;
+    return 0.0;
+  }
+  // T from the coefficients (Observation in App. A); only b^2 is needed
+  for (int j = tid; j < m; j += SLQ_THREADS) {
+    double al = alpha[(size_t)j * stride];
+    double dg = 1.0 / al;
+    if (j > 0) {
+      double alp = alpha[(size_t)(j - 1) * stride];
+      double bep = beta[(size_t)(j - 1) * stride];
+      dg += bep / alp;
+      b2[j - 1] = bep / (alp * alp);
+    }
+    a[j] = dg;
+  }
+  __syncthreads();
+  // Gershgorin bound of the largest eigenvalue
+  double gmax = 0.0;
+  for (int j = tid; j < m; j += SLQ_THREADS) {
+    double r = a[j] + (j + 1 < m ? sqrt(b2[j]) : 0.0) + (j > 0 ? sqrt(b2[j - 1]) : 0.0);
+    gmax = fmax(gmax, finite_d(r) ? r : 1.0e300);
+  }
+  red[tid] = gmax;
+  __syncthreads();
+  for (int w = SLQ_THREADS / 2; w > 0; w >>= 1) {
+    if (tid < w) red[tid] = fmax(red[tid], red[tid + w]);
+    __syncthreads();
+  }
+  double G = red[0];
+  __syncthreads();
+  // Sturm counts: thread i < 64 counts the eigenvalues below G 2^-i, thread 64 those below 0
+  if (tid <= 64) {
+    double x = (tid < 64) ? ldexp(G, -tid) : 0.0;
+    double q = a[0] - x;
+    int c = q < 0.0;
+    for (int j = 1; j < m; ++j) {
+      if (q == 0.0) q = 1.0e-300;
+      q = a[j] - x - b2[j - 1] / q;
+      c += q < 0.0;
+    }
+    cnt[tid] = (q == q) ? c : m;          // a NaN anywhere: treated as "eigenvalues below"
+  }
+  __syncthreads();
+  int ilo = -1;
+  for (int i = 0; i < 64; ++i)
+    if (cnt[i] == 0) {
+      ilo = i;
+      break;
+    }
+  bool pd = ilo >= 0 && cnt[64] == 0 && G > 0.0 && G < 1.0e300;
+  if (!pd) {
+    // not positive definite (or conditioned beyond 2^63): no logarithm to report
+    if (tid == 0) *status = 4;
+    return 0.0;
+  }
+  double xlo = ldexp(G, -ilo);
+  double ulo = log(fmin(1.0, xlo)) - SLQ_PAD, uhi = log(fmax(1.0, G)) + SLQ_PAD;
+  int N = (int)ceil((uhi - ulo) / SLQ_H) + 1;
+  double acc = 0.0;
+  for (int k = tid; k < N; k += SLQ_THREADS) {
+    double sft = exp(ulo + SLQ_H * (double)k);
+    double d = a[m - 1] + sft, below = 0.0;      // below: b_1^2 / delta_2
+    for (int j = m - 2; j >= 0; --j) {
+      below = b2[j] / d;
+      d = a[j] + sft - below;
+    }
+    acc += sft * (a[0] - 1.0 - below) / ((1.0 + sft) * d);
+  }
+  red[tid] = acc;
+  __syncthreads();
+  for (int w = SLQ_THREADS / 2; w > 0; w >>= 1) {
+    if (tid < w) red[tid] += red[tid + w];
+    __syncthreads();
+  }
+  double term = rho0 * (SLQ_H * red[0]);
+  if (tid == 0) *status = finite_d(term) ? 0 : 4;
+  return term;
+}
+
 // One block per probe column: T from the CG coefficients (Observation in App. A),
-// e_1^T log(T) e_1, times rho0.  Thread 0 of block 0 (last arriving) forms the mean.
-__global__ __launch_bounds__(64) void k_slq(const double* __restrict__ alpha_hist,
-                                             const double* __restrict__ beta_hist, int t,
-                                             int sweeps_per_row, DevState* st) {
+// e_1^T log(T) e_1, times rho0.  Thread 0 of the last block to arrive forms the mean.
+// EIG: by the eigen-decomposition of T (App. B) in thread 0; else by the quadrature above.
+template <bool EIG>
+__global__ __launch_bounds__(SLQ_THREADS) void k_slq(const double* __restrict__ alpha_hist,
+                                                      const double* __restrict__ beta_hist, int t,
+                                                      int sweeps_per_row, DevState* st) {
   __shared__ double a[BBMM_MAXP], b[BBMM_MAXP], w[BBMM_MAXP];
+  __shared__ int cnt[65];
   int col = blockIdx.x + 1;
+  int bad = 0;
+  double term = 0.0;
+  if (EIG) {
+    if (threadIdx.x == 0)
+      term = slq_term(alpha_hist + col, beta_hist + col, BBMM_MAXC, st->m_valid[col], st->rho0[col],
+                      sweeps_per_row, a, b, w, &bad);
+  } else {
+    __shared__ int status_s;
+    term = slq_term_quadrature(alpha_hist + col, beta_hist + col, BBMM_MAXC, st->m_valid[col], st->rho0[col],
+                               a, b, w, cnt, &status_s);
+    if (threadIdx.x == 0) bad = status_s;
+  }
   if (threadIdx.x == 0) {
-    int bad = 0;
-    st->slq_terms[blockIdx.x] = slq_term(alpha_hist + col, beta_hist + col, BBMM_MAXC, st->m_valid[col],
-                                         st->rho0[col], sweeps_per_row, a, b, w, &bad);
+    st->slq_terms[blockIdx.x] = term;
     if (bad) st->status = bad;
   }
   if (!last_block_arrives(&st->counter[4][0])) return;
@@ -1194,18 +1312,30 @@ __global__ __launch_bounds__(64) void k_slq(const double* __restrict__ alpha_his
 
 // The same term from coefficient arrays handed in by the caller: alpha, beta are p x t row-major
 // (row j = iteration j), rho0 and m_valid have t entries; one block per probe column.
-__global__ __launch_bounds__(64) void k_slq_coeffs(const double* __restrict__ alpha,
-                                                    const double* __restrict__ beta,
-                                                    const double* __restrict__ rho0,
-                                                    const int* __restrict__ m_valid, int t,
-                                                    int sweeps_per_row, double* __restrict__ terms,
-                                                    int* __restrict__ status) {
+template <bool EIG>
+__global__ __launch_bounds__(SLQ_THREADS) void k_slq_coeffs(const double* __restrict__ alpha,
+                                                             const double* __restrict__ beta,
+                                                             const double* __restrict__ rho0,
+                                                             const int* __restrict__ m_valid, int t,
+                                                             int sweeps_per_row, double* __restrict__ terms,
+                                                             int* __restrict__ status) {
   __shared__ double a[BBMM_MAXP], b[BBMM_MAXP], w[BBMM_MAXP];
-  if (threadIdx.x != 0) return;
+  __shared__ int cnt[65];
   int i = blockIdx.x;
   int bad = 0;
-  terms[i] = slq_term(alpha + i, beta + i, (size_t)t, m_valid[i], rho0[i], sweeps_per_row, a, b, w, &bad);
-  status[i] = bad;
+  double term = 0.0;
+  if (EIG) {
+    if (threadIdx.x == 0)
+      term = slq_term(alpha + i, beta + i, (size_t)t, m_valid[i], rho0[i], sweeps_per_row, a, b, w, &bad);
+  } else {
+    __shared__ int status_s;
+    term = slq_term_quadrature(alpha + i, beta + i, (size_t)t, m_valid[i], rho0[i], a, b, w, cnt, &status_s);
+    if (threadIdx.x == 0) bad = status_s;
+  }
+  if (threadIdx.x == 0) {
+    terms[i] = term;
+    status[i] = bad;
+  }
 }
 
 // Stand-alone batched eigen-solve (host arrays copied to the device by the caller).
@@ -1477,14 +1607,16 @@ void launch_cross_dot(hipStream_t s, const float* X, const float* Xs, int n, int
   k_cross_dot<<<ns, VT, 0, s>>>(X, Xs, n, hyp, V, ldv, percol, prior, sign, out);
 }
 
-void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int sweeps_per_row,
-                DevState* st) {
-  k_slq<<<t, 64, 0, s>>>(alpha_hist, beta_hist, t, sweeps_per_row, st);
+void launch_slq(hipStream_t s, const double* alpha_hist, const double* beta_hist, int t, int eig,
+                int sweeps_per_row, DevState* st) {
+  if (eig) k_slq<true><<<t, SLQ_THREADS, 0, s>>>(alpha_hist, beta_hist, t, sweeps_per_row, st);
+  else k_slq<false><<<t, SLQ_THREADS, 0, s>>>(alpha_hist, beta_hist, t, sweeps_per_row, st);
 }
 
 void launch_slq_coeffs(hipStream_t s, const double* alpha, const double* beta, const double* rho0,
-                       const int* m_valid, int t, int sweeps_per_row, double* terms, int* status) {
-  k_slq_coeffs<<<t, 64, 0, s>>>(alpha, beta, rho0, m_valid, t, sweeps_per_row, terms, status);
+                       const int* m_valid, int t, int eig, int sweeps_per_row, double* terms, int* status) {
+  if (eig) k_slq_coeffs<true><<<t, SLQ_THREADS, 0, s>>>(alpha, beta, rho0, m_valid, t, sweeps_per_row, terms, status);
+  else k_slq_coeffs<false><<<t, SLQ_THREADS, 0, s>>>(alpha, beta, rho0, m_valid, t, sweeps_per_row, terms, status);
 }
 
 void launch_tridiag_eig(hipStream_t s, const double* diag, const double* off, int m, int batch,

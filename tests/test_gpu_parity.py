@@ -449,6 +449,7 @@ def test_tridiag_eig_reports_an_exhausted_sweep_budget(ctx):
     diag = rng.uniform(0.5, 3.0, (3, m))
     off = rng.uniform(0.1, 0.4, (3, m - 1))
     ctx.bbmm_tune("eig_sweeps", 1)
+    ctx.bbmm_tune("slq_eig", 1)
     try:
         with pytest.raises(binding.BbmmError) as e:
             ctx.bbmm_tridiag_eig_batched(diag, off)
@@ -458,6 +459,7 @@ def test_tridiag_eig_reports_an_exhausted_sweep_budget(ctx):
         assert e.value.code == binding.ENOCONV
     finally:
         ctx.bbmm_tune("eig_sweeps", 0)
+        ctx.bbmm_tune("slq_eig", 0)
     vals, first = ctx.bbmm_tridiag_eig_batched(diag, off)          # default budget: fine again
     assert np.all(np.isfinite(vals)) and np.allclose(np.sum(first ** 2, axis=1), 1.0)
 
@@ -466,12 +468,14 @@ def test_whole_call_reports_an_exhausted_sweep_budget(ctx):
     from paper_1809_11165_amd import binding
     w = inputs.tiny(400, 3, t=3, k=2, iters=30)
     ctx.bbmm_tune("eig_sweeps", 1)
+    ctx.bbmm_tune("slq_eig", 1)                     # the eigen-decomposition route of the SLQ terms
     try:
         with pytest.raises(binding.BbmmError) as e:
             ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
         assert e.value.code == binding.ENOCONV
     finally:
         ctx.bbmm_tune("eig_sweeps", 0)
+        ctx.bbmm_tune("slq_eig", 0)
     res = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
     assert np.isfinite(res.logdet)
 
@@ -504,6 +508,47 @@ def test_slq_from_coeffs_on_the_oracles_coefficients(ctx):
     full = [ref.rho0[i] * O.e1_logT_e1(*O.tridiag_from_cg(ref.alpha[:, i], ref.beta[:, i], 40)) for i in (0, 1, 3)]
     assert np.allclose(t2, full, rtol=1e-10)
     assert ld2 == pytest.approx(np.mean(full), rel=1e-10)
+
+
+@pytest.mark.parametrize("route", [0, 1])
+def test_slq_terms_by_quadrature_and_by_eigen_decomposition(ctx, route):
+    """Both routes to e_1^T log(T) e_1 -- the quadrature of the resolvent (default) and the
+    eigen-decomposition of App. B -- on the ORACLE's coefficients of long, ill-conditioned CG runs
+    (Ritz values converged and re-found many times over: clusters of near-duplicate eigenvalues),
+    against the oracle's eigen-decomposition."""
+    rng = np.random.default_rng(3)
+    lam = np.concatenate([np.logspace(-6, 0, 380), [50.0, 80.0, 120.0, 200.0]])
+    B = rng.standard_normal((lam.size, 4))
+    alpha, beta, rho0, mv, ref = [], [], [], [], []
+    for p in (1, 2, 20, 60, 150, 250):
+        r = O.mbcg(lambda M: lam[:, None] * M, B, lambda R: R, p)
+        pad = np.zeros((250 - p, 4))
+        alpha.append(np.vstack([r.alpha, pad]))
+        beta.append(np.vstack([r.beta, pad]))
+        rho0.append(r.rho0)
+        mv.append(r.m_valid)
+        ref.append([r.rho0[i] * O.e1_logT_e1(*O.tridiag_from_cg(r.alpha[:, i], r.beta[:, i], int(r.m_valid[i])))
+                    for i in range(4)])
+    alpha, beta = np.hstack(alpha), np.hstack(beta)
+    rho0, mv, ref = np.concatenate(rho0), np.concatenate(mv), np.concatenate(ref)
+    ctx.bbmm_tune("slq_eig", route)
+    try:
+        logdet, terms = ctx.bbmm_slq_from_coeffs(alpha, beta, rho0, mv, logdet_precond=1.5)
+    finally:
+        ctx.bbmm_tune("slq_eig", 0)
+    assert np.allclose(terms, ref, rtol=2e-9)
+    assert logdet == pytest.approx(1.5 + ref.mean(), rel=1e-9)
+
+
+def test_slq_refuses_a_tridiagonal_that_is_not_positive_definite(ctx):
+    from paper_1809_11165_amd import binding
+    alpha = np.full((6, 2), 0.5)
+    beta = np.full((6, 2), 0.3)
+    alpha[3, 1] = -0.5                                 # 1 / alpha < 0 on the diagonal of T_2
+    with pytest.raises(binding.BbmmError) as e:
+        ctx.bbmm_slq_from_coeffs(alpha, beta, np.ones(2))
+    assert e.value.code == binding.ENONFINITE
+    ctx.bbmm_slq_from_coeffs(alpha[:, :1], beta[:, :1], np.ones(1))      # the other column alone is fine
 
 
 def test_slq_from_coeffs_equals_the_in_context_stage(ctx):
@@ -651,7 +696,7 @@ def test_loop_graph_replays_equal_kernel_by_kernel_launches(ctx, mode, tri):
         # one launch sequence for all four hyperparameter settings: recorded once, replayed 15 times
         assert (cap1 - cap0, rep1 - rep0) == (1, 15)
     finally:
-        ctx.bbmm_tune("loop_graph", 1)
+        ctx.bbmm_tune("loop_graph", 0)
         ctx.bbmm_tune("khat_sym", 0)
 
 
