@@ -1187,6 +1187,7 @@ __device__ double slq_term(const double* __restrict__ alpha, const double* __res
 constexpr int SLQ_THREADS = 256;
 constexpr double SLQ_H = 0.5;        // trapezoid step in u = ln s
 constexpr double SLQ_PAD = 37.0;     // e^-37 = 9e-17: what is cut off at either end
+static_assert(SLQ_THREADS <= BBMM_MAXP, "the reduction buffer of the quadrature is an LDS array of BBMM_MAXP doubles");
 
 // All SLQ_THREADS threads of the block call this; the result is valid in thread 0.
 // a, b2: LDS, BBMM_MAXP doubles each; red: LDS, SLQ_THREADS doubles; cnt: LDS, 65 ints.
