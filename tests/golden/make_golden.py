@@ -234,11 +234,13 @@ def run_sgpr(name: str, cfg: int, n: int, m: int, cap=None):
     fp32_dev = norm(res.U - other.U) / norm(res.U)
     trace_fp32, quad_fp32 = dterms(other) if converged_cap else (None, None)
     del other, A32
-    if not converged_cap:
-        say("first-order sensitivity of the trace and quadratic terms to the iterate")
-        ts, qs = S.sor_term_sensitivity(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale,
-                                        w.jitter_rel, parts, res.U, res.W)
-        trace_sens, quad_sens = ts.tolist(), qs.tolist()
+    # (also at a converged cap: the derivative terms are conditioned ~1e3 with respect to the solves,
+    # so their bound is the parity bound of the term plus this first-order bound times the
+    # distance of the solves)
+    say("first-order sensitivity of the trace and quadratic terms to the iterate")
+    ts, qs = S.sor_term_sensitivity(w.kernel, w.X, w.Uind, w.lengthscale, w.outputscale,
+                                    w.jitter_rel, parts, res.U, res.W)
+    trace_sens, quad_sens = ts.tolist(), qs.tolist()
     say("Woodbury solve and log-determinant")
     u_exact, logdet_exact = S.sor_woodbury(parts, w.y)
     yKinvy_exact = float(w.y.astype(np.float64) @ u_exact)
