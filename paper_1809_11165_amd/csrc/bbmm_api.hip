@@ -485,7 +485,7 @@ int sgpr_second_pass(bbmm_ctx* c, int ld, VpShape* shape, int cols = 0) {
                     ptr<MmPlan>(c->sgplan[2 + v]), c->sg_wgs[2 + v], ptr<DevState>(c->st), BBMM_SGPR_PANEL,
                     c->mp, cols))
     return fail(c, BBMM_EINVAL, "unsupported block width");
-  *shape = VpShape{0, ptr<int>(c->sgnseg[2 + v]), v ? 512 : 1024};
+  *shape = VpShape{0, ptr<int>(c->sgnseg[2 + v]), v ? 512 : 1024, c->sg_slots[2 + v]};
   return BBMM_OK;
 }
 
@@ -540,7 +540,7 @@ int stage_mm(bbmm_ctx* c, int mode, int cc, int ld, VpShape* shape, double* scal
     if (launch_mm_mat(c->stream, ptr<float>(c->Khat), ptr<double>(c->D4), ptr<double>(c->Vp), c->np, ld,
                       ptr<MmPlan>(c->plan[v]), c->plan_wgs[v], ptr<DevState>(c->st), c->khat_pw, c->np, cc))
       return fail(c, BBMM_EINVAL, "unsupported block width");
-    *shape = VpShape{0, ptr<int>(c->nseg[v]), v == 1 ? 512 : 1024};
+    *shape = VpShape{0, ptr<int>(c->nseg[v]), v == 1 ? 512 : 1024, c->plan_slots[v]};
     *scaleV = 1.0;
     *addD = 0.0;
   } else if (mode == BBMM_MODE_ONTHEFLY && (c->otf_sym == 2 || (c->otf_sym == 1 && c->np >= kOtfSymMinRows)) &&

@@ -61,6 +61,7 @@ struct VpShape {
   int nsplit;
   const int* nseg;
   int seg_cols;
+  int max_slots;   // host-side knowledge: the largest slot count of any row (0 = not known)
 };
 
 // ---- launchers implemented in kernels_vec.hip ---------------------------------------------

@@ -608,6 +608,11 @@ __global__ void k_probes(const float* __restrict__ y, const float* __restrict__ 
 // device-wide fence inside a kernel was measured at ~60 us here.
 //
 // (1) after the product: V = scaleV * sum_s Vp[s] + addD * D, and per-block partial d^T v.
+//     RU rows per loop trip and thread; the first NL partial slots of each and its D entry are
+//     requested before anything is added, so a trip costs one memory round trip.  <3, 8> is the
+//     general form; <8, 2> serves products that leave at most two slots per row (the SGPR product:
+//     one), where three rows per trip leave too few loads in flight to cover the latency.
+template <int RU, int NL>
 __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShape shape, int n, int np,
                                             int ld, double scaleV, double addD,
                                             const double* __restrict__ D4, double* __restrict__ V,
@@ -622,13 +627,10 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShap
   int q = threadIdx.x % ld, rl = threadIdx.x / ld, rpp = VT / ld;
   int pq = perm16(q);
   double acc = 0.0;
-  // RU rows per loop trip; the first 8 partial slots of each and its D entry are requested before
-  // anything is added, so a trip costs one memory round trip
-  constexpr int RU = 3;
   int stride = gridDim.x * rpp;
   size_t slot_stride = (size_t)np * ld;
   for (int ib = blockIdx.x * rpp + rl; ib < n; ib += RU * stride) {
-    double pv[RU][8], dd[RU];
+    double pv[RU][NL], dd[RU];
     int ns[RU];
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
@@ -638,19 +640,22 @@ __global__ __launch_bounds__(VT) void k_dv(const double* __restrict__ Vp, VpShap
       ns[u] = ok ? (shape.nseg ? shape.nseg[ic / shape.seg_cols] : shape.nsplit) : 0;
       size_t pidx = (size_t)ic * ld + pq;
 #pragma unroll
-      for (int sp = 0; sp < 8; ++sp) pv[u][sp] = (sp < ns[u]) ? Vp[(size_t)sp * slot_stride + pidx] : 0.0;
+      for (int sp = 0; sp < NL; ++sp) pv[u][sp] = (sp < ns[u]) ? Vp[(size_t)sp * slot_stride + pidx] : 0.0;
       dd[u] = ok ? D4[d4_index(ic, q, ld)] : 0.0;
     }
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
       int i = ib + u * stride;
       if (i < n) {
-        double sv = ((pv[u][0] + pv[u][1]) + (pv[u][2] + pv[u][3])) +
-                    ((pv[u][4] + pv[u][5]) + (pv[u][6] + pv[u][7]));
+        double sv;
+        if (NL == 8)
+          sv = ((pv[u][0] + pv[u][1]) + (pv[u][2] + pv[u][3])) + ((pv[u][4] + pv[u][5]) + (pv[u][6] + pv[u][7]));
+        else
+          sv = (NL > 1) ? pv[u][0] + pv[u][NL > 1 ? 1 : 0] : pv[u][0];
         size_t pidx = (size_t)i * ld + pq;
         // further slots eight at a time, all requested before any is added (the product from the
         // triangular storage leaves up to one slot per panel)
-        for (int s0 = 8; s0 < ns[u]; s0 += 8) {
+        for (int s0 = NL; s0 < ns[u]; s0 += 8) {
           double t[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) t[e] = (s0 + e < ns[u]) ? Vp[(size_t)(s0 + e) * slot_stride + pidx] : 0.0;
@@ -1527,7 +1532,10 @@ void launch_set_loop_scalars(hipStream_t s, DevState* st, double noise, double t
 void launch_dv(hipStream_t s, const double* Vp, VpShape shape, int n, int np, int ld, double scaleV,
                double addD, const double* D4, double* V, const DevState* st, double* partial_dv,
                int nblocks) {
-  k_dv<<<nblocks, VT, 0, s>>>(Vp, shape, n, np, ld, scaleV, addD, D4, V, st, partial_dv);
+  if (shape.max_slots > 0 && shape.max_slots <= 2)
+    k_dv<8, 2><<<nblocks, VT, 0, s>>>(Vp, shape, n, np, ld, scaleV, addD, D4, V, st, partial_dv);
+  else
+    k_dv<3, 8><<<nblocks, VT, 0, s>>>(Vp, shape, n, np, ld, scaleV, addD, D4, V, st, partial_dv);
 }
 
 #define DISPATCH_KP_T(KERNEL, kp, grid, threads, ...)                        \
