@@ -410,9 +410,13 @@ def _run_sgpr_converged_case(ctx, name):
     residual), i.e. conditioned ~1e3-1e4 with respect to the solves: the oracle's own third fp64
     run, through its root rounded once to float32, moves U by 4e-6 and these terms by up to 3e-2 of
     their values ("trace_fp32", "quad_fp32").  Their bound is therefore 1e-3 of the term plus what
-    the measured distance of the GPU's solves explains to first order, by the Cauchy-Schwarz
-    bounds the oracle stores ("trace_sens", "quad_sens": |delta term| <= eps * sens when every
-    column moves by eps of its norm; factor 2 for the second-order part)."""
+    the measured distance eps of the GPU's solves explains: the oracle stores the Cauchy-Schwarz
+    bounds "trace_sens", "quad_sens" (|delta term| <= eps * sens when every column moves by eps of
+    its norm; the terms' condition numbers sens / |term| are 1e4-1e5 here); a perturbation of the
+    solves that is uncorrelated with (dQ) w moves a term by eps * sens / sqrt(n), and a factor 4
+    allows for correlation -- the model the configured-cap test uses with its bound on the
+    iterate.  The oracle's own float32-root run, with its own distance, is held to the same model:
+    if that assertion fails the model is wrong, not the GPU."""
     g = _load(name)
     w = inputs.make(g["config"], n=g["n"], m=g["m"], iters=g["iters_cap"])
     prob = _problem(w, inputs.SGPR)
@@ -445,16 +449,17 @@ def _run_sgpr_converged_case(ctx, name):
     assert res.trace[nl + 1] == pytest.approx(tr[nl + 1], rel=TOL)
     assert res.quad[nl + 1] == pytest.approx(qd[nl + 1], rel=TOL)
     eps_u, eps_0 = float(err[1:].max()), float(err[0])
-    for h in range(len(tr)):
-        btr = TOL * abs(tr[h]) + 2.0 * eps_u * tsens[h]
-        bqd = TOL * abs(qd[h]) + 2.0 * eps_0 * qsens[h]
+    rn = np.sqrt(g["n"])
+    dev = float(np.max(g["U_fp32_dev"]))
+    for h in range(nl + 1):
+        btr = TOL * abs(tr[h]) + 4.0 * eps_u * tsens[h] / rn
+        bqd = TOL * abs(qd[h]) + 4.0 * eps_0 * qsens[h] / rn
         assert abs(res.trace[h] - tr[h]) <= btr, (h, res.trace[h], tr[h], btr)
         assert abs(res.quad[h] - qd[h]) <= bqd, (h, res.quad[h], qd[h], bqd)
         assert abs(res.grad_nlml[h] - g["grad"][h]) <= (btr + bqd) / 2 + 1e-9, h
-        # the oracle's own float32-root run obeys the same first-order bound with its own distance
-        dev = float(np.max(g["U_fp32_dev"]))
-        assert abs(t32[h] - tr[h]) <= 2.0 * dev * tsens[h] + 1e-9 * abs(tr[h])
-        assert abs(q32[h] - qd[h]) <= 2.0 * dev * qsens[h] + 1e-9 * abs(qd[h])
+        assert abs(t32[h] - tr[h]) <= 4.0 * dev * tsens[h] / rn + 1e-9 * abs(tr[h]), h
+        assert abs(q32[h] - qd[h]) <= 4.0 * dev * qsens[h] / rn + 1e-9 * abs(qd[h]), h
+    assert res.grad_nlml[nl + 1] == pytest.approx(g["grad"][nl + 1], rel=TOL)
     # the plain definition (Woodbury identity): log-det within 1e-2, the solve as close as the oracle's
     assert res.logdet == pytest.approx(g["exact_logdet"], rel=1e-2)
     return res, w, g
