@@ -413,10 +413,12 @@ def _run_sgpr_converged_case(ctx, name):
     the measured distance eps of the GPU's solves explains: the oracle stores the Cauchy-Schwarz
     bounds "trace_sens", "quad_sens" (|delta term| <= eps * sens when every column moves by eps of
     its norm; the terms' condition numbers sens / |term| are 1e4-1e5 here); a perturbation of the
-    solves that is uncorrelated with (dQ) w moves a term by eps * sens / sqrt(n), and a factor 4
-    allows for correlation -- the model the configured-cap test uses with its bound on the
-    iterate.  The oracle's own float32-root run, with its own distance, is held to the same model:
-    if that assertion fails the model is wrong, not the GPU."""
+    solves that is uncorrelated with (dQ) w moves a term by eps * sens / sqrt(n), and a factor
+    allows for correlation: 10 here, chosen on oracle-only data -- the oracle's own float32-root
+    run with its own distance needs 5.6 at n = 500,000 (where the terms' condition numbers reach
+    1e6) and 3.2 at n = 50,000, and is asserted to stay inside the same model below: if that
+    assertion fails the model is wrong, not the GPU.  In units of their natural scale sens the
+    GPU's terms are off by 6e-8 at most, i.e. at float32 rounding of the root."""
     g = _load(name)
     w = inputs.make(g["config"], n=g["n"], m=g["m"], iters=g["iters_cap"])
     prob = _problem(w, inputs.SGPR)
@@ -452,13 +454,15 @@ def _run_sgpr_converged_case(ctx, name):
     rn = np.sqrt(g["n"])
     dev = float(np.max(g["U_fp32_dev"]))
     for h in range(nl + 1):
-        btr = TOL * abs(tr[h]) + 4.0 * eps_u * tsens[h] / rn
-        bqd = TOL * abs(qd[h]) + 4.0 * eps_0 * qsens[h] / rn
+        btr = TOL * abs(tr[h]) + 10.0 * eps_u * tsens[h] / rn
+        bqd = TOL * abs(qd[h]) + 10.0 * eps_0 * qsens[h] / rn
         assert abs(res.trace[h] - tr[h]) <= btr, (h, res.trace[h], tr[h], btr)
         assert abs(res.quad[h] - qd[h]) <= bqd, (h, res.quad[h], qd[h], bqd)
         assert abs(res.grad_nlml[h] - g["grad"][h]) <= (btr + bqd) / 2 + 1e-9, h
-        assert abs(t32[h] - tr[h]) <= 4.0 * dev * tsens[h] / rn + 1e-9 * abs(tr[h]), h
-        assert abs(q32[h] - qd[h]) <= 4.0 * dev * qsens[h] / rn + 1e-9 * abs(qd[h]), h
+        assert abs(t32[h] - tr[h]) <= 10.0 * dev * tsens[h] / rn + 1e-9 * abs(tr[h]), h
+        assert abs(q32[h] - qd[h]) <= 10.0 * dev * qsens[h] / rn + 1e-9 * abs(qd[h]), h
+        # and in units of the term's natural scale the GPU is at float32 rounding of the root
+        assert abs(res.trace[h] - tr[h]) <= 5e-7 * tsens[h] and abs(res.quad[h] - qd[h]) <= 5e-7 * qsens[h], h
     assert res.grad_nlml[nl + 1] == pytest.approx(g["grad"][nl + 1], rel=TOL)
     # the plain definition (Woodbury identity): log-det within 1e-2, the solve as close as the oracle's
     assert res.logdet == pytest.approx(g["exact_logdet"], rel=1e-2)
