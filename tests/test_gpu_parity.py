@@ -661,13 +661,16 @@ def test_full_path_is_deterministic(ctx):
     assert np.array_equal(a.alpha, b.alpha)
 
 
-@pytest.mark.parametrize("mode,tri", [(inputs.ONTHEFLY, 0), (inputs.MATERIALISED, 0), (inputs.MATERIALISED, 1)])
+@pytest.mark.parametrize("mode,tri", [(inputs.ONTHEFLY, 0), (inputs.MATERIALISED, 0), (inputs.MATERIALISED, 1),
+                                      (inputs.SGPR, 0)])
 def test_loop_graph_replays_equal_kernel_by_kernel_launches(ctx, mode, tri):
     """The mBCG loop replayed as a HIP graph against the same loop launched kernel by kernel: bit
     for bit, over several replays with other work and synchronisations of the program in between,
     with the hyperparameters (which the loop's kernels read from the device state, not from their
     arguments) changing from call to call, and with a tolerance stop that ends one run early."""
     w = inputs.make(2, n=2100, iters=40)
+    if mode == inputs.SGPR:
+        w = inputs.with_inducing(w, 300, np.random.Generator(np.random.Philox(7)))
     variants = [(0.05, 1.0, 0.0), (0.2, 1.7, 0.0), (0.05, 1.0, 0.15), (0.4, 0.6, 0.3)]   # (noise, outputscale, tol)
 
     def run(noise, s, tol):
