@@ -50,9 +50,11 @@ def _load(name):
 TOL = 1e-3          # the parity bound on solves, log-det and traces
 
 # Every full-size comparison also writes what it measured (one JSON line per case) so that the
-# margin to the bound is on record, not only pass / fail.
-MEASURED = os.environ.get("BBMM_PARITY_LOG", os.path.join(os.path.dirname(GOLDEN), os.pardir, "gpurun_out",
-                                                          "parity_measured.jsonl"))
+# margin to the bound is on record, not only pass / fail: to the file named by BBMM_PARITY_LOG,
+# else to a file in the temporary directory.
+import tempfile  # noqa: E402
+
+MEASURED = os.environ.get("BBMM_PARITY_LOG", os.path.join(tempfile.gettempdir(), "bbmm_parity_measured.jsonl"))
 
 
 def _record(case, **values):
