@@ -652,6 +652,41 @@ def test_full_path_config4_shape(ctx):
     _full_parity(ctx, w, inputs.ONTHEFLY)
 
 
+def test_full_path_at_the_interface_limits(ctx):
+    """Everything at its documented maximum at once: t = 31 probes (32 columns), rank k = 32, d = 64 ARD
+    input dimensions, 256 iterations without a tolerance stop, n ragged (1237 = 77 * 16 + 5).  The
+    iteration converges to rounding level after about 50 steps and runs on for 200 more (recurrence
+    residual 1e-93 at the end): the coefficients of those steps are rounding noise, different on the
+    two sides, and must not disturb the solves or the quadrature of the first row (App. A, B)."""
+    w = inputs.tiny(1237, 64, kernel=O.MATERN52, ard=True, t=31, k=32, iters=256, noise=0.05, seed=3)
+    w.X *= 0.25                               # distances of a few lengthscales, not of dozens
+    runs = {}
+    for name, mode, sym in (("mat", inputs.MATERIALISED, 0), ("sym", inputs.MATERIALISED, 1),
+                            ("otf", inputs.ONTHEFLY, 0)):
+        ctx.bbmm_tune("khat_sym", sym)
+        runs[name] = ctx.bbmm_solve_logdet_grad(_problem(w, mode))
+    ctx.bbmm_tune("khat_sym", 0)
+    first = runs["mat"]
+    ref = O.bbmm_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, w.E1, w.E2,
+                           w.k, 256, forced_pivots=first.pivots)
+    ex = O.exact_inference(w.kernel, w.X, w.y, w.lengthscale, w.outputscale, w.noise, with_traces=False)
+    assert np.linalg.norm(ref.u0 - ex.u0) < 1e-12 * np.linalg.norm(ex.u0)       # the oracle has converged
+    for name, res in runs.items():
+        assert res.iters_run == 256 and res.rank == 32, name
+        assert np.array_equal(res.pivots, first.pivots), name
+        assert _colrel(_host(res.U), ref.U) < 1e-3, name
+        assert _colrel(_host(res.u0), ex.u0) < 1e-3, name
+        assert np.all(np.isfinite(res.alpha)) and np.all(np.isfinite(res.beta)), name
+        assert res.logdet_precond == pytest.approx(ref.logdet_precond, rel=1e-5), name
+        assert np.allclose(res.slq_terms, ref.slq_terms, rtol=1e-3, atol=1e-3 * np.abs(ref.slq_terms).max()), name
+        for key in ("logdet", "yKinvy", "nlml"):
+            assert getattr(res, key) == pytest.approx(getattr(ref, key), rel=1e-3), (name, key)
+        assert res.logdet == pytest.approx(ex.logdet, rel=1e-2), name
+        for h in range(len(ref.trace)):
+            assert res.trace[h] == pytest.approx(ref.trace[h], rel=1e-3, abs=1e-3 * np.max(np.abs(ref.trace))), (name, h)
+            assert res.quad[h] == pytest.approx(ref.quad[h], rel=1e-3, abs=1e-3 * np.max(np.abs(ref.quad))), (name, h)
+
+
 def test_full_path_is_deterministic(ctx):
     w = inputs.make(1, n=777)
     a = ctx.bbmm_solve_logdet_grad(_problem(w, inputs.ONTHEFLY))
