@@ -281,6 +281,22 @@ def test_sgpr_full_path_wide_block_and_warm_start(ctx):
     assert _colrel(_host(warm.u0), u_ref) < 1e-3 + _colrel(ref.u0, u_ref)
 
 
+@pytest.mark.parametrize("n,d,m,scale", [(4203, 6, 4096, 1.0), (2003, 32, 300, 0.3)])
+def test_sgpr_full_path_at_the_interface_limits(ctx, n, d, m, scale):
+    """The documented maxima of the SGPR operator, with t = 31 probes and rank k = 32 in both: the
+    largest inducing set (m = 4096 of n = 4203 ragged points), and the most input dimensions (d = 32,
+    one lengthscale each: 34 derivative terms)."""
+    w = _case(inputs.MATERN52, True, n, d, m, t=31, k=32, iters=128, noise=0.1, seed=2)
+    w.X *= scale
+    w.Uind *= scale
+    res, ref = _full_parity(ctx, w)
+    assert res.iters_run == 128 and ref.mbcg.resid[-1].max() < 1e-4          # plain 1e-3 applied above
+    u_ref, ld_ref = S.sor_woodbury(_parts(w), w.y)
+    assert _colrel(_host(res.u0), u_ref) < 1e-3
+    est_err = abs(ref.logdet - ld_ref)
+    assert abs(res.logdet - ld_ref) <= max(1e-2 * abs(ld_ref), est_err + 1e-3 * abs(ld_ref))
+
+
 def test_sgpr_full_path_config5_shape(ctx):
     w = inputs.make(5, n=20000, m=512)       # the recipe of config 5 at reduced n and m
     res, ref = _full_parity(ctx, w)
