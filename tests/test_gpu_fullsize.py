@@ -591,3 +591,35 @@ def test_config4_full_size_audit(ctx):
     sub = _load("cfg4_sub_n20000")
     # same mixture at 10x the points: log-det per point stays in the same range
     assert 0.3 < (res.logdet / 200000) / (sub["logdet"] / 20000) < 3.0
+
+
+@pytest.mark.parametrize("storage", ["whole matrix", "triangle"])
+def test_materialised_product_at_n_200000_on_sampled_rows(storage):
+    """The largest n of the configurations with K_hat in HBM (Sec. 3, materialised form): 160 GB as a
+    whole matrix, 87 GB as its upper triangle -- element offsets far beyond 2^32.  17 columns as in
+    config 4 (two 16-column passes over the triangle).  Rows of the product picked at random, and
+    the first and last, against the oracle's kernel rows in fp64."""
+    from paper_1809_11165_amd import binding
+    w = inputs.make(4)
+    n, c = w.X.shape[0], w.t + 1
+    assert n == 200000 and c == 17
+    rng = np.random.default_rng(2024)
+    rows = np.sort(rng.choice(n, size=48, replace=False))
+    rows[0], rows[-1] = 0, n - 1
+    M = rng.standard_normal((n, c)).astype(np.float32)
+    Krows = O.kernel_block(w.kernel, w.X[rows], w.X, w.lengthscale, w.outputscale)
+    ref = Krows @ M.astype(np.float64) + w.noise * M[rows].astype(np.float64)
+    own = binding.Context(0)                 # its own context: the matrix is freed with it
+    try:
+        own.bbmm_tune("khat_sym", 1 if storage == "triangle" else 0)
+        own.bbmm_setup(_problem(w, inputs.MATERIALISED))
+        own.bbmm_build_khat()
+        V = own.bbmm_kernel_mm(inputs.MATERIALISED, torch.from_numpy(M).to("cuda:0"))
+        got = V[torch.from_numpy(rows).to("cuda:0")].cpu().numpy().astype(np.float64)
+        finite = bool(torch.isfinite(V).all().item())
+    finally:
+        own.close()
+    assert finite
+    err = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+    _record("materialised_n200000_" + storage.replace(" ", "_"), product_rows_max_err=err)
+    assert err < 1e-5
