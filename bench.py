@@ -172,7 +172,7 @@ def roofline_sym(n, c, mm_ms, launches, config):
     return {"bound": "mfma", "achieved": achieved, "peak": MFMA_F64_PEAK_TFLOPS,
             "unit": "TFLOP/s", "frac": achieved / MFMA_F64_PEAK_TFLOPS,
             "traffic": MEASURED_TRAFFIC_SYM_N50000 if (n, config) == (50000, 3) else None,
-            "traffic_source": TRAFFIC_NOTE % "k_mm_sym_cfg3_n50000_counters.txt",
+            "traffic_source": TRAFFIC_NOTE % "k_mm_sym_cfg3_n50000_counters.txt" if (n, config) == (50000, 3) else None,
             "kernel": "k_mm_sym (one launch per product for c <= 12, else a second one for the diagonal blocks)",
             "avg_launch_ms": mm_ms, "launches": launches,
             "executed_TFLOPs_with_padding": executed,
@@ -186,7 +186,7 @@ def roofline_mat(n, c, mm_ms, launches, config):
     return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_MAT_N50000 if (n, config) == (50000, 3) else None,
-            "traffic_source": TRAFFIC_NOTE % "k_mm_mat_cfg3_n50000_hbm_counters.txt",
+            "traffic_source": TRAFFIC_NOTE % "k_mm_mat_cfg3_n50000_hbm_counters.txt" if (n, config) == (50000, 3) else None,
             "kernel": "k_mm_mat", "avg_launch_ms": mm_ms, "launches": launches}
 
 
@@ -298,7 +298,8 @@ def main():
         roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS,
                     "traffic": MEASURED_TRAFFIC_SGPR_N500000_M1024 if (n, m) == (500000, 1024) else None,
-                    "traffic_source": TRAFFIC_NOTE % "k_mm_mat_cfg5_n500000_sgpr_hbm_counters.txt",
+                    "traffic_source": (TRAFFIC_NOTE % "k_mm_mat_cfg5_n500000_sgpr_hbm_counters.txt"
+                                       if (n, m) == (500000, 1024) else None),
                     "kernel": "k_mm_mat (two launches per product: A^T D, then A T)",
                     "avg_launch_ms": mm_ms / 2.0, "avg_product_ms": mm_ms, "launches": 2 * mm_launches}
         workload = ("config5: SGPR (subset of regressors), RBF, n=%d, m=%d, d=8, t=10, k=10, 50 mBCG "
