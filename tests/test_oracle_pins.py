@@ -490,6 +490,60 @@ def test_preconditioner_rank_trend_univariate_rbf():
     assert its[-1] < its[0]
 
 
+@pytest.mark.parametrize("kernel,d,ls,ranks", [(O.RBF, 1, [0.2], (1, 3, 6, 10)),
+                                                 (O.MATERN52, 3, [0.5, 0.8, 1.1], (1, 4, 10, 25))])
+def test_condition_number_chain_of_the_preconditioner_theorem(kernel, d, ls, ranks):
+    # The proof of Theorem 1's condition-number bound (App. "Proofs of Lemmas") holds step by step
+    # for any kernel: E = K - L_k L_k^T is positive semi-definite, |E|_2 <= tr E = what the pivoted
+    # Cholesky's running diagonal sums to, and kappa(P_k^-1 K_hat) <= (1 + tr(E) / sigma^2)^2;
+    # both sides fall as k grows.
+    rng = np.random.default_rng(5)
+    n, noise = 120, 0.05
+    X = rng.uniform(0, 1, (n, d))
+    K = O.kernel_matrix(kernel, X, ls, 1.3)
+    Kh = K + noise * np.eye(n)
+    kappas, bounds = [], []
+    tiny = 1e-12 * np.trace(K)
+    for k in ranks:
+        L, piv, dmax = _pc(K, k)
+        E = K - L @ L.T
+        ev = np.linalg.eigvalsh(E)
+        assert ev.min() > -tiny
+        assert np.allclose(E[piv], 0.0, atol=1e-10)               # the pivoted rows are reproduced exactly
+        assert ev.max() <= np.trace(E) + tiny
+        # eigenvalues of P^-1 K_hat = those of the symmetric pencil (K_hat, P)
+        P = L @ L.T + noise * np.eye(n)
+        lam = sla.eigh(Kh, P, eigvals_only=True)
+        kappa = lam.max() / lam.min()
+        assert lam.min() >= 1.0 - 1e-9                             # K_hat - P = E >= 0
+        assert kappa <= (1.0 + np.trace(E) / noise) ** 2 * (1 + 1e-9)
+        kappas.append(kappa)
+        bounds.append(np.trace(E))
+    assert all(a > b for a, b in zip(kappas, kappas[1:])) and all(a > b for a, b in zip(bounds, bounds[1:]))
+
+
+def test_cg_error_obeys_the_condition_number_bound_at_every_iteration():
+    # Observation "Convergence of conjugate gradients" (App. A) for the preconditioned iteration:
+    # |u* - u_p|_K <= 2 ((sqrt(kappa) - 1) / (sqrt(kappa) + 1))^p |u* - u_0|_K with
+    # kappa = kappa(P^-1 K_hat), u_0 = 0, for every p and every column; and the K-norm error never grows.
+    w = inputs.tiny(90, 2, kernel=inputs.MATERN52, ard=True, t=4, k=6, iters=1, noise=0.02, seed=4)
+    Kh, L, P = _setup(w, w.k)
+    B = np.column_stack([w.y, O.make_probes(L, w.noise, w.E1, w.E2)])
+    Ustar = np.linalg.solve(Kh, B)
+    lam = sla.eigh(Kh, L @ L.T + w.noise * np.eye(90), eigvals_only=True)
+    rate = (np.sqrt(lam.max() / lam.min()) - 1) / (np.sqrt(lam.max() / lam.min()) + 1)
+    knorm = lambda M: np.sqrt(np.einsum("ij,ij->j", M, Kh @ M))
+    e0 = knorm(Ustar)
+    prev = e0.copy()
+    for p in range(1, 31):
+        res = O.mbcg(lambda M: Kh @ M, B, P.solve, p)
+        err = knorm(Ustar - res.U)
+        assert np.all(err <= 2 * rate ** p * e0 * (1 + 1e-9) + 1e-13 * e0), p
+        assert np.all(err <= prev * (1 + 1e-9) + 1e-13 * e0), p
+        prev = err
+    assert np.all(prev < 1e-3 * e0)                                # and it does converge
+
+
 def test_frozen_column_guard():
     # a zero right-hand side has rho = 0: the column is frozen, others are unaffected
     w = inputs.tiny(12, 2, kernel=inputs.RBF)
