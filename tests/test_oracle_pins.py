@@ -472,6 +472,33 @@ def test_slq_logdet_approaches_cholesky_logdet_as_t_grows():
     assert errs[-1] < errs[0]
 
 
+def test_slq_probe_count_of_the_restated_quadrature_theorem():
+    # Sec. 4, the restated Theorem 4.1 of Ubaru et al.: with Rademacher probes, t >= (24 / eps^2) log(2 / delta)
+    # of them estimate log|P^-1 K_hat| to relative error eps with probability >= 1 - delta (the
+    # quadrature itself made exact here: p = n).  eps = 0.5, delta = 0.1 -> t = 288; 20 independent
+    # probe sets, each also far inside the bound (it is not tight), and the preconditioned
+    # quantity log|K_hat| - log|P| is what the terms estimate.
+    w = inputs.tiny(36, 2, kernel=inputs.RBF, noise=0.05, seed=6)
+    Kh, L, P = _setup(w, 3)
+    truth = np.linalg.slogdet(Kh)[1] - P.logdet
+    assert abs(truth) > 1.0
+    eps, delta = 0.5, 0.1
+    t = int(np.ceil(24 / eps ** 2 * np.log(2 / delta)))
+    assert t == 288
+    rng = np.random.default_rng(77)
+    rel = []
+    for rep in range(20):
+        E1 = rng.integers(0, 2, (3, t)) * 2.0 - 1.0
+        E2 = rng.integers(0, 2, (36, t)) * 2.0 - 1.0
+        Z = O.make_probes(L, w.noise, E1, E2)
+        res = O.mbcg(lambda M: Kh @ M, Z, P.solve, 36)
+        terms = [res.rho0[i] * O.e1_logT_e1(*O.tridiag_from_cg(res.alpha[:, i], res.beta[:, i], int(res.m_valid[i])))
+                 for i in range(t)]
+        rel.append(abs(np.mean(terms) - truth) / abs(truth))
+    assert np.mean(np.array(rel) <= eps) >= 1 - delta
+    assert max(rel) < eps / 2
+
+
 def test_preconditioner_rank_trend_univariate_rbf():
     # Theorem 1: CG converges faster as the pivoted-Cholesky rank grows (1-D RBF).
     rng = np.random.default_rng(0)
